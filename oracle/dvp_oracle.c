@@ -1,0 +1,224 @@
+/*
+ * dvp_oracle.c -- slow, plain fp64 CPU oracle for Dynamic Vocabulary Pruning.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the checker the GPU library is
+ * compared against; it is never part of the product path.  It shares no
+ * code, header, table or helper with the HIP kernels.
+ *
+ * What it computes, per token row with logits z[0..V-1] and sampled id y
+ * (paper Sec. 5 "Dynamic Vocabulary Pruning"):
+ *
+ *   m        = max_k z_k                                  (Def. 5.1, max term)
+ *   tau      = fl32(m + log_rho)                          (App. A, protocol
+ *              item 2 "logit-space thresholding"; one fp32 rounding, so that
+ *              membership is a well defined function of the stored inputs)
+ *   s_k      = [ z_k >= tau ]                             (Def. 5.1; boundary
+ *              is inclusive: the definition uses ">=")
+ *   c        = sum_k s_k                                  (safe-set size)
+ *   lse_safe = log sum_{k: s_k} exp(z_k)                  (Def. 5.2, log of
+ *              the un-normalised mass kept; softmax over the masked logits,
+ *              Prop. 5.6 part 1)
+ *   lse_full = log sum_k exp(z_k)   =>  log Z_theta = lse_safe - lse_full
+ *   logp     = z_y - lse_safe  if s_y, else -inf          (Def. 5.2; a token
+ *              outside the safe set has constrained probability zero,
+ *              Sec. 5.3 closing remark)
+ *   dz_k     = g * (delta_{ky} - exp(z_k - lse_safe)) * s_k   if s_y
+ *            = 0 for every k                                  if not s_y
+ *              (Prop. 5.4 / Prop. 5.6 part 2 with the set held fixed,
+ *              Sec. 5.5; g is the caller's dL/dlogp)
+ *
+ * Everything is done in double on the exactly widened inputs.  Sums use
+ * Neumaier compensation so the oracle's own rounding is far below every
+ * tolerance used against it.  No blocking, fusion or reordering: one loop per
+ * formula above.
+ *
+ * Pins (tests/test_oracle_pins.py): scipy/torch log-softmax with an empty
+ * prune set, scipy logsumexp with an independently built mask, probability
+ * space brute force on V <= 16, torch autograd through a masked log-softmax,
+ * finite differences, sum-to-one, TV = 1 - Z, the mismatch bound of Prop. 4.2.
+ */
+#include <math.h>
+#include <pthread.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { DVP_ORACLE_F32 = 0, DVP_ORACLE_BF16 = 1, DVP_ORACLE_F64 = 2 };
+
+typedef struct {
+    const void *z;
+    int dtype;
+    int64_t n_rows, vocab, ld;
+    const int64_t *ids;
+    float log_rho;
+    double band;
+    const double *grad_out; /* nullable */
+    double *row_max, *tau, *lse_safe, *lse_full, *logp;
+    int64_t *safe_count, *band_count;
+    uint8_t *y_in_safe;
+    uint8_t *safe_flags; /* nullable, [n_rows, vocab] */
+    double *dz;          /* nullable, [n_rows, vocab] */
+} oracle_job;
+
+typedef struct {
+    const oracle_job *job;
+    int64_t row_begin, row_end;
+} oracle_slice;
+
+/* exact widening of one stored element to double */
+static double fetch(const void *base, int dtype, int64_t idx)
+{
+    if (dtype == DVP_ORACLE_F32) {
+        return (double)((const float *)base)[idx];
+    } else if (dtype == DVP_ORACLE_BF16) {
+        uint32_t bits = (uint32_t)((const uint16_t *)base)[idx] << 16;
+        float f;
+        memcpy(&f, &bits, sizeof f);
+        return (double)f;
+    }
+    return ((const double *)base)[idx];
+}
+
+/* Neumaier compensated accumulation */
+typedef struct { double sum, comp; } nsum;
+static void nsum_add(nsum *a, double x)
+{
+    double t = a->sum + x;
+    if (fabs(a->sum) >= fabs(x)) a->comp += (a->sum - t) + x;
+    else                         a->comp += (x - t) + a->sum;
+    a->sum = t;
+}
+static double nsum_value(const nsum *a) { return a->sum + a->comp; }
+
+static void oracle_row(const oracle_job *J, int64_t i, double *zrow)
+{
+    const int64_t V = J->vocab;
+    const int64_t y = J->ids[i];
+    int64_t k;
+
+    for (k = 0; k < V; ++k) zrow[k] = fetch(J->z, J->dtype, i * J->ld + k);
+
+    /* row maximum (Def. 5.1) */
+    double m = zrow[0];
+    for (k = 1; k < V; ++k) if (zrow[k] > m) m = zrow[k];
+
+    /* threshold: ideal value and the single-precision value that decides
+     * membership.  m and log_rho are both fp32-representable for f32/bf16
+     * inputs; rounding their double sum to float equals the fp32 add. */
+    const double tau_ideal = m + (double)J->log_rho;
+    const double tau = (double)(float)tau_ideal;
+
+    /* membership, size, and the count of tokens sitting in the +-band around
+     * the ideal threshold (a relative band in probability is an absolute band
+     * in logit space) */
+    int64_t c = 0, nb = 0;
+    for (k = 0; k < V; ++k) {
+        int s = zrow[k] >= tau;
+        c += s;
+        if (fabs(zrow[k] - tau_ideal) <= J->band) ++nb;
+        if (J->safe_flags) J->safe_flags[i * V + k] = (uint8_t)s;
+    }
+
+    /* masked and full log-sum-exp (Def. 5.2) */
+    nsum S_safe = {0.0, 0.0}, S_full = {0.0, 0.0};
+    for (k = 0; k < V; ++k) {
+        double e = exp(zrow[k] - m);
+        nsum_add(&S_full, e);
+        if (zrow[k] >= tau) nsum_add(&S_safe, e);
+    }
+    const double lse_safe = m + log(nsum_value(&S_safe));
+    const double lse_full = m + log(nsum_value(&S_full));
+
+    /* sampled token's constrained log-probability */
+    const int in_range = (y >= 0 && y < V);
+    const int y_safe = in_range && (zrow[y] >= tau);
+    double logp;
+    if (!in_range)   logp = NAN;
+    else if (y_safe) logp = zrow[y] - lse_safe;
+    else             logp = -INFINITY;
+
+    J->row_max[i] = m;
+    J->tau[i] = tau;
+    J->lse_safe[i] = lse_safe;
+    J->lse_full[i] = lse_full;
+    J->logp[i] = logp;
+    J->safe_count[i] = c;
+    J->band_count[i] = nb;
+    J->y_in_safe[i] = (uint8_t)y_safe;
+
+    /* gradient w.r.t. the row's logits, set held fixed (Prop. 5.4) */
+    if (J->dz) {
+        const double g = J->grad_out ? J->grad_out[i] : 1.0;
+        double *d = J->dz + i * V;
+        for (k = 0; k < V; ++k) {
+            if (y_safe && zrow[k] >= tau) {
+                double p = exp(zrow[k] - lse_safe);
+                d[k] = g * ((k == y ? 1.0 : 0.0) - p);
+            } else {
+                d[k] = 0.0;
+            }
+        }
+    }
+}
+
+static void *oracle_worker(void *arg)
+{
+    const oracle_slice *s = (const oracle_slice *)arg;
+    double *zrow = (double *)malloc(sizeof(double) * (size_t)s->job->vocab);
+    if (!zrow) return (void *)1;
+    for (int64_t i = s->row_begin; i < s->row_end; ++i) oracle_row(s->job, i, zrow);
+    free(zrow);
+    return NULL;
+}
+
+/*
+ * One side (training or inference logits) of the DVP forward, optionally with
+ * the gradient.  All pointers are host pointers owned by the caller.
+ * Returns 0 on success, 1 on bad arguments, 2 on allocation/thread failure.
+ */
+int dvp_oracle_rows(const void *z, int dtype, int64_t n_rows, int64_t vocab, int64_t ld,
+                    const int64_t *ids, float log_rho, double band,
+                    const double *grad_out,
+                    double *row_max, double *tau, double *lse_safe, double *lse_full,
+                    double *logp, int64_t *safe_count, int64_t *band_count,
+                    uint8_t *y_in_safe, uint8_t *safe_flags, double *dz, int n_threads)
+{
+    if (!z || !ids || !row_max || !tau || !lse_safe || !lse_full || !logp ||
+        !safe_count || !band_count || !y_in_safe) return 1;
+    if (n_rows < 0 || vocab < 1 || ld < vocab) return 1;
+    if (dtype < 0 || dtype > 2) return 1;
+    if (log_rho != log_rho || log_rho > 0.0f) return 1;
+    if (n_rows == 0) return 0;
+
+    oracle_job job = { z, dtype, n_rows, vocab, ld, ids, log_rho, band, grad_out,
+                       row_max, tau, lse_safe, lse_full, logp, safe_count, band_count,
+                       y_in_safe, safe_flags, dz };
+
+    if (n_threads < 1) n_threads = 1;
+    if ((int64_t)n_threads > n_rows) n_threads = (int)n_rows;
+
+    if (n_threads == 1) {
+        oracle_slice s = { &job, 0, n_rows };
+        return oracle_worker(&s) ? 2 : 0;
+    }
+
+    pthread_t *th = (pthread_t *)malloc(sizeof(pthread_t) * (size_t)n_threads);
+    oracle_slice *sl = (oracle_slice *)malloc(sizeof(oracle_slice) * (size_t)n_threads);
+    if (!th || !sl) { free(th); free(sl); return 2; }
+    int rc = 0, started = 0;
+    for (int t = 0; t < n_threads; ++t) {
+        sl[t].job = &job;
+        sl[t].row_begin = n_rows * t / n_threads;
+        sl[t].row_end = n_rows * (t + 1) / n_threads;
+        if (pthread_create(&th[t], NULL, oracle_worker, &sl[t]) != 0) { rc = 2; break; }
+        ++started;
+    }
+    for (int t = 0; t < started; ++t) {
+        void *ret = NULL;
+        pthread_join(th[t], &ret);
+        if (ret) rc = 2;
+    }
+    free(th);
+    free(sl);
+    return rc;
+}

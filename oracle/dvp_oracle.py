@@ -1,0 +1,158 @@
+"""Python face of the fp64 CPU oracle for Dynamic Vocabulary Pruning.
+
+TEST INFRASTRUCTURE ONLY: imported by the tests, the smoke check and the
+benchmark's CPU-baseline leg; never by the product package.  The arithmetic
+lives in ``dvp_oracle.c`` (plain C, double precision); this module compiles it
+with gcc, marshals numpy arrays into it and adds the dense LM-head wrapper,
+whose only extra steps are three fp64 matrix products.
+
+Parity status: every function here is pinned by tests/test_oracle_pins.py.
+"""
+from __future__ import annotations
+
+import ctypes
+import math
+import os
+import subprocess
+from pathlib import Path
+
+import numpy as np
+
+_HERE = Path(__file__).resolve().parent
+_SRC = _HERE / "dvp_oracle.c"
+_LIB = _HERE / "libdvp_oracle.so"
+_lib = None
+
+F32, BF16, F64 = 0, 1, 2
+
+
+def build(force: bool = False) -> Path:
+    """Compile the C oracle with gcc (no GPU toolchain involved)."""
+    if force or not _LIB.exists() or _LIB.stat().st_mtime < _SRC.stat().st_mtime:
+        tmp = _LIB.with_suffix(".so.tmp%d" % os.getpid())
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-ffp-contract=off",
+             "-o", str(tmp), str(_SRC), "-lm", "-lpthread"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(str(_LIB))
+        lib.dvp_oracle_rows.restype = ctypes.c_int
+        lib.dvp_oracle_rows.argtypes = [
+            ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+            ctypes.c_void_p, ctypes.c_float, ctypes.c_double, ctypes.c_void_p,
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int]
+        _lib = lib
+    return _lib
+
+
+def log_rho_f32(rho: float) -> np.float32:
+    """The single fp32 constant log(rho) used by the threshold (App. A,
+    protocol item 2).  rho = 0 stands for "no pruning" and maps to -inf."""
+    if rho == 0.0:
+        return np.float32(-np.inf)
+    if not (0.0 < rho <= 1.0):
+        raise ValueError("rho must lie in [0, 1]")
+    return np.float32(math.log(rho))
+
+
+def as_oracle_input(z):
+    """Accepts a numpy float32/float64/uint16(bf16 bits) array or a CPU torch
+    tensor (float32, float64, bfloat16); returns (array, dtype_code) without
+    changing any stored value."""
+    if not isinstance(z, np.ndarray):
+        import torch  # plumbing only: reinterpret bf16 storage as uint16
+        t = z.detach().cpu().contiguous()
+        if t.dtype == torch.bfloat16:
+            z = t.view(torch.int16).numpy().view(np.uint16)
+        else:
+            z = t.numpy()
+    if z.dtype == np.float32:
+        code = F32
+    elif z.dtype == np.uint16:
+        code = BF16
+    elif z.dtype == np.float64:
+        code = F64
+    else:
+        raise TypeError("unsupported logits dtype %s" % z.dtype)
+    if z.ndim != 2:
+        raise ValueError("logits must be [N, V]")
+    return np.ascontiguousarray(z), code
+
+
+def rows(z, ids, log_rho, grad_out=None, want_flags=False, want_dz=False,
+         band=1e-6, threads=1):
+    """One side of the DVP forward (and, with want_dz, the gradient of the
+    sampled token's constrained log-probability) for every row of z.
+
+    Returns a dict of numpy arrays: row_max, tau, lse_safe, lse_full, logp
+    (float64 [N]); safe_count, band_count (int64 [N]); y_in_safe (uint8 [N]);
+    optionally safe_flags (uint8 [N, V]) and dz (float64 [N, V])."""
+    z, code = as_oracle_input(z)
+    n, v = z.shape
+    ids = np.ascontiguousarray(np.asarray(ids, dtype=np.int64))
+    if ids.shape != (n,):
+        raise ValueError("ids must be [N]")
+    g = None
+    if grad_out is not None:
+        g = np.ascontiguousarray(np.asarray(grad_out, dtype=np.float64))
+        if g.shape != (n,):
+            raise ValueError("grad_out must be [N]")
+    out = {
+        "row_max": np.empty(n, np.float64), "tau": np.empty(n, np.float64),
+        "lse_safe": np.empty(n, np.float64), "lse_full": np.empty(n, np.float64),
+        "logp": np.empty(n, np.float64),
+        "safe_count": np.empty(n, np.int64), "band_count": np.empty(n, np.int64),
+        "y_in_safe": np.empty(n, np.uint8),
+    }
+    flags = np.empty((n, v), np.uint8) if want_flags else None
+    dz = np.empty((n, v), np.float64) if want_dz else None
+
+    def p(a):
+        return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+    rc = _load().dvp_oracle_rows(
+        p(z), code, n, v, v, p(ids), ctypes.c_float(float(log_rho)), float(band), p(g),
+        p(out["row_max"]), p(out["tau"]), p(out["lse_safe"]), p(out["lse_full"]),
+        p(out["logp"]), p(out["safe_count"]), p(out["band_count"]), p(out["y_in_safe"]),
+        p(flags), p(dz), int(threads))
+    if rc != 0:
+        raise RuntimeError("dvp_oracle_rows failed with code %d" % rc)
+    if want_flags:
+        out["safe_flags"] = flags
+    if want_dz:
+        out["dz"] = dz
+    return out
+
+
+def _widen(a):
+    """Exact widening of a stored matrix (numpy f32/f64/bf16-bits or torch)."""
+    a, code = as_oracle_input(a)
+    if code == BF16:
+        return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    return a.astype(np.float64)
+
+
+def lmhead(hidden, w, ids, log_rho, grad_out=None, want_flags=False, band=1e-6, threads=1):
+    """Dense LM-head variant: logits z = H W^T formed in fp64 from the stored
+    hidden states H [N, d] and head weights W [V, d], then ``rows`` on them;
+    with grad_out also dH = dz W and dW = dz^T H (chain rule through the
+    linear map).  Returns the ``rows`` dict plus 'z', and 'd_hidden', 'd_w'
+    when grad_out is given."""
+    h64 = _widen(hidden)
+    w64 = _widen(w)
+    z = h64 @ w64.T
+    out = rows(z, ids, log_rho, grad_out=grad_out, want_flags=want_flags,
+               want_dz=grad_out is not None, band=band, threads=threads)
+    out["z"] = z
+    if grad_out is not None:
+        out["d_hidden"] = out["dz"] @ w64
+        out["d_w"] = out["dz"].T @ h64
+    return out

@@ -1,0 +1,354 @@
+"""Pins for the fp64 CPU oracle: each test checks it against something the
+paper or the mathematics fixes, computed here without the oracle's code
+(scipy / torch library routines, probability-space brute force, autograd,
+finite differences, closed-form identities)."""
+import math
+import os
+
+import numpy as np
+import pytest
+import scipy.special
+import torch
+
+from oracle import dvp_oracle as orc
+from paper_2512_23087_amd import workloads
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rand_rows(n, v, seed, scale=3.0, dtype=np.float64):
+    rng = np.random.default_rng(seed)
+    z = (scale * rng.standard_normal((n, v))).astype(dtype)
+    ids = rng.integers(0, v, size=n)
+    return z, ids
+
+
+# --------------------------------------------------------------------------
+# printed constants (Sec. 5.1, Sec. 5.5, App. A)
+# --------------------------------------------------------------------------
+def test_printed_constants():
+    vals = {}
+    with open(os.path.join(GOLDEN, "paper_constants.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            name, val, tol = line.split()
+            vals[name] = (float(val), float(tol))
+    for name in ("exp_minus_13_sec5_1", "exp_minus_13_sec5_5"):
+        v, tol = vals[name]
+        assert abs(math.exp(-13.0) - v) <= tol * v
+        assert abs(float(np.exp(np.float64(orc.log_rho_f32(math.exp(-13.0))))) - v) <= tol * v
+    v, tol = vals["exp_minus_50_appA"]
+    assert abs(math.exp(-50.0) - v) <= tol * v
+    # log_rho helper: single fp32 constant, rho = 0 means no pruning
+    assert orc.log_rho_f32(math.exp(-13.0)) == np.float32(-13.0)
+    assert orc.log_rho_f32(1.0) == np.float32(0.0)
+    assert orc.log_rho_f32(0.0) == np.float32(-np.inf)
+    with pytest.raises(ValueError):
+        orc.log_rho_f32(1.5)
+
+
+# --------------------------------------------------------------------------
+# empty prune set reproduces the full log-softmax exactly (Prop. 5.6 with V_S = V)
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_no_pruning_is_full_log_softmax(dtype):
+    z, ids = _rand_rows(17, 1000, 1, dtype=dtype)
+    out = orc.rows(z, ids, orc.log_rho_f32(0.0), want_flags=True)
+    z64 = z.astype(np.float64)
+    lse = scipy.special.logsumexp(z64, axis=1)
+    lsm = torch.log_softmax(torch.from_numpy(z64), dim=-1).numpy()
+    assert np.all(out["safe_count"] == z.shape[1])
+    assert np.all(out["safe_flags"] == 1)
+    assert np.all(out["y_in_safe"] == 1)
+    np.testing.assert_allclose(out["lse_safe"], lse, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(out["lse_full"], lse, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(out["logp"], lsm[np.arange(len(ids)), ids], rtol=0, atol=1e-12)
+    np.testing.assert_array_equal(out["row_max"], z64.max(axis=1))
+
+
+# --------------------------------------------------------------------------
+# masked case against library routines on an independently built mask
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("rho", [1e-1, 1e-2, 1e-4, math.exp(-13.0), 1.0])
+def test_masked_lse_against_scipy_and_torch(rho):
+    z, ids = _rand_rows(33, 777, 2, dtype=np.float32)
+    lr = orc.log_rho_f32(rho)
+    out = orc.rows(z, ids, lr, want_flags=True)
+    # threshold: one fp32 add of the row max and the fp32 constant (App. A item 2)
+    thr = (z.max(axis=1) + lr).astype(np.float32)
+    mask = z >= thr[:, None]
+    z64 = z.astype(np.float64)
+    np.testing.assert_array_equal(out["safe_flags"].astype(bool), mask)
+    np.testing.assert_array_equal(out["safe_count"], mask.sum(axis=1))
+    np.testing.assert_array_equal(out["tau"], thr.astype(np.float64))
+    lse_m = scipy.special.logsumexp(z64, axis=1, b=mask.astype(np.float64))
+    np.testing.assert_allclose(out["lse_safe"], lse_m, rtol=0, atol=1e-12)
+    # masked-logit form (Sec. 5.5): logits below the threshold go to -inf, then log-softmax
+    zt = torch.from_numpy(z64)
+    masked = torch.where(zt < torch.from_numpy(thr.astype(np.float64))[:, None],
+                         torch.tensor(-math.inf, dtype=torch.float64), zt)
+    lsm = torch.log_softmax(masked, dim=-1).numpy()
+    want = lsm[np.arange(len(ids)), ids]
+    np.testing.assert_allclose(out["logp"], want, rtol=0, atol=1e-12)  # -inf == -inf passes
+    np.testing.assert_array_equal(out["y_in_safe"].astype(bool), mask[np.arange(len(ids)), ids])
+    # coverage mass log Z = lse_safe - lse_full <= 0
+    p = scipy.special.softmax(z64, axis=1)
+    np.testing.assert_allclose(np.exp(out["lse_safe"] - out["lse_full"]),
+                               (p * mask).sum(axis=1), rtol=1e-12)
+
+
+# --------------------------------------------------------------------------
+# brute force in probability space on tiny vocabularies (Def. 5.1 / 5.2 as written)
+# --------------------------------------------------------------------------
+def test_bruteforce_probability_space_tiny_vocab():
+    rng = np.random.default_rng(3)
+    checked = 0
+    for trial in range(400):
+        v = int(rng.integers(1, 17))
+        z = (4.0 * rng.standard_normal(v)).astype(np.float32)
+        rho = float(10.0 ** rng.uniform(-6, 0))
+        y = int(rng.integers(0, v))
+        z64 = z.astype(np.float64)
+        pi = np.exp(z64 - z64.max())
+        pi /= pi.sum()
+        ratio = pi / (rho * pi.max())
+        if np.any(np.abs(ratio - 1.0) < 1e-5):
+            continue  # on the boundary: the two spaces may round differently
+        safe = pi >= rho * pi.max()
+        pmp = np.where(safe, pi, 0.0) / pi[safe].sum()
+        out = orc.rows(z[None, :], [y], orc.log_rho_f32(rho), want_flags=True, want_dz=True,
+                       grad_out=[1.0])
+        np.testing.assert_array_equal(out["safe_flags"][0].astype(bool), safe)
+        assert out["safe_count"][0] == safe.sum()
+        if safe[y]:
+            assert abs(out["logp"][0] - math.log(pmp[y])) < 1e-12
+            onehot = np.zeros(v)
+            onehot[y] = 1.0
+            np.testing.assert_allclose(out["dz"][0], onehot - pmp, rtol=0, atol=1e-12)
+        else:
+            assert out["logp"][0] == -np.inf
+            assert np.all(out["dz"][0] == 0.0)
+        assert abs(math.exp(out["lse_safe"][0] - out["lse_full"][0]) - pi[safe].sum()) < 1e-12
+        checked += 1
+    assert checked > 300
+
+
+# --------------------------------------------------------------------------
+# invariants from the definitions
+# --------------------------------------------------------------------------
+def test_invariants_and_nestedness():
+    wl = workloads.make_rows(0, n=16, v=4000)
+    z = wl.z_train.numpy()
+    ids = wl.ids.numpy()
+    prev_flags = None
+    for rho in [0.0, 1e-6, 1e-4, 1e-2, 1.0]:
+        out = orc.rows(z, ids, orc.log_rho_f32(rho), want_flags=True, want_dz=True,
+                       grad_out=np.ones(len(ids)))
+        f = out["safe_flags"].astype(bool)
+        c = out["safe_count"]
+        assert np.all(c >= 1) and np.all(c <= z.shape[1])
+        assert np.all(f[np.arange(len(ids)), z.argmax(axis=1)])          # arg max is always safe
+        assert np.all(out["row_max"] <= out["lse_safe"] + 1e-15)
+        assert np.all(out["lse_safe"] <= out["row_max"] + np.log(c) + 1e-12)
+        assert np.all(out["lse_safe"] <= out["lse_full"] + 1e-15)
+        # constrained probabilities sum to one and vanish off the safe set (Def. 5.2)
+        pmp = np.where(f, np.exp(z.astype(np.float64) - out["lse_safe"][:, None]), 0.0)
+        np.testing.assert_allclose(pmp.sum(axis=1), 1.0, rtol=0, atol=1e-12)
+        # pruned mass floor: every pruned token has pi < rho * pi_max
+        pmax = np.exp(out["row_max"] - out["lse_full"])
+        one_minus_z = -np.expm1(out["lse_safe"] - out["lse_full"])
+        assert np.all(one_minus_z <= (z.shape[1] - c) * rho * pmax + 1e-15)
+        # gradient: sums to zero, zero off the set, zero row when y is pruned (Prop. 5.4)
+        ys = out["y_in_safe"].astype(bool)
+        np.testing.assert_allclose(out["dz"][ys].sum(axis=1), 0.0, atol=1e-12)
+        assert np.all(out["dz"][~f] == 0.0)
+        assert np.all(out["dz"][~ys] == 0.0)
+        if rho == 1.0:
+            assert np.all(f == (z == z.max(axis=1, keepdims=True)))
+        if prev_flags is not None:
+            assert np.all(prev_flags | ~f)     # larger rho => subset
+        prev_flags = f
+
+
+def test_threshold_boundary_is_inclusive_and_ties():
+    # element exactly at the threshold is safe (Def. 5.1 uses >=); ties at the max are all safe
+    lr = np.float32(-2.0)
+    z = np.array([[4.0, 2.0, 1.9999999, 4.0, -np.inf, 2.0000002]], dtype=np.float32)
+    out = orc.rows(z, [1], lr, want_flags=True)
+    np.testing.assert_array_equal(out["safe_flags"][0], [1, 1, 0, 1, 0, 1])
+    assert out["safe_count"][0] == 4 and out["y_in_safe"][0] == 1
+    want = 2.0 - math.log(2 * math.exp(4.0) + math.exp(2.0) + math.exp(float(np.float32(2.0000002))))
+    assert abs(out["logp"][0] - want) < 1e-12
+    # all-equal row: everything is safe at any rho
+    z = np.full((1, 37), -3.25, dtype=np.float32)
+    out = orc.rows(z, [5], orc.log_rho_f32(1.0))
+    assert out["safe_count"][0] == 37
+    assert abs(out["logp"][0] + math.log(37)) < 1e-12
+    # single element vocabulary
+    out = orc.rows(np.array([[0.7]], dtype=np.float32), [0], orc.log_rho_f32(1e-3))
+    assert out["safe_count"][0] == 1 and out["logp"][0] == 0.0
+    # out-of-range id: NaN log-prob, not in the set
+    out = orc.rows(z, [37], orc.log_rho_f32(1e-3), want_dz=True)
+    assert np.isnan(out["logp"][0]) and out["y_in_safe"][0] == 0 and np.all(out["dz"] == 0)
+
+
+def test_band_count():
+    lr = np.float32(-1.0)
+    z = np.array([[3.0, 2.0, 2.0000005, 1.9999995, 2.00001, 0.0]], dtype=np.float64)
+    out = orc.rows(z, [0], lr, band=1e-6)
+    assert out["band_count"][0] == 3
+
+
+def test_bf16_inputs_are_widened_exactly():
+    t = (3.0 * torch.randn(5, 300, generator=torch.Generator().manual_seed(4))).to(torch.bfloat16)
+    ids = np.arange(5)
+    a = orc.rows(t, ids, orc.log_rho_f32(1e-2), want_flags=True, want_dz=True)
+    b = orc.rows(t.to(torch.float64).numpy(), ids, orc.log_rho_f32(1e-2), want_flags=True,
+                 want_dz=True)
+    for k in a:
+        np.testing.assert_array_equal(a[k], b[k])
+
+
+def test_shift_invariance():
+    z, ids = _rand_rows(8, 500, 5)
+    lr = orc.log_rho_f32(1e-3)
+    a = orc.rows(z, ids, lr, want_flags=True, want_dz=True)
+    # shift by a power of two keeps the fp32 threshold rounding aligned for these magnitudes
+    zf = z.astype(np.float32).astype(np.float64)
+    a = orc.rows(zf, ids, lr, want_flags=True, want_dz=True)
+    b = orc.rows(zf + 64.0, ids, lr, want_flags=True, want_dz=True)
+    agree = np.abs(zf - a["tau"][:, None]).min(axis=1) > 1e-4   # rows with nothing near the threshold
+    assert agree.sum() >= 6
+    np.testing.assert_array_equal(a["safe_flags"][agree], b["safe_flags"][agree])
+    np.testing.assert_allclose(a["logp"][agree], b["logp"][agree], atol=1e-12)
+    np.testing.assert_allclose(a["lse_safe"][agree] + 64.0, b["lse_safe"][agree], atol=1e-11)
+    np.testing.assert_allclose(a["dz"][agree], b["dz"][agree], atol=1e-12)
+
+
+# --------------------------------------------------------------------------
+# gradient: autograd through the masked log-softmax, and finite differences
+# --------------------------------------------------------------------------
+def test_gradient_against_autograd_masked_log_softmax():
+    z, ids = _rand_rows(12, 300, 6, dtype=np.float32)
+    rng = np.random.default_rng(7)
+    g = rng.standard_normal(len(ids))
+    lr = orc.log_rho_f32(1e-2)
+    out = orc.rows(z, ids, lr, grad_out=g, want_dz=True, want_flags=True)
+    zt = torch.from_numpy(z.astype(np.float64)).requires_grad_(True)
+    with torch.no_grad():
+        thr = torch.from_numpy((z.max(axis=1) + lr).astype(np.float32).astype(np.float64))[:, None]
+        pruned = zt < thr
+    masked = torch.where(pruned, torch.tensor(-math.inf, dtype=torch.float64), zt)
+    lp = torch.log_softmax(masked, dim=-1)[torch.arange(len(ids)), torch.from_numpy(ids)]
+    keep = torch.from_numpy(out["y_in_safe"].astype(bool))
+    assert keep.any() and (~keep).any()
+    (lp[keep] * torch.from_numpy(g)[keep]).sum().backward()
+    want = zt.grad.numpy()
+    np.testing.assert_allclose(out["dz"], want, rtol=0, atol=1e-12)   # rows with y pruned: all zero
+
+
+def test_gradient_finite_differences():
+    z, ids = _rand_rows(3, 40, 8)
+    zf = z.astype(np.float32).astype(np.float64)
+    lr = orc.log_rho_f32(1e-1)
+    base = orc.rows(zf, ids, lr, want_dz=True, want_flags=True, grad_out=np.ones(3))
+    h = 1e-6
+    for i in range(3):
+        if not base["y_in_safe"][i]:
+            ids[i] = int(zf[i].argmax())
+    base = orc.rows(zf, ids, lr, want_dz=True, want_flags=True, grad_out=np.ones(3))
+    for i in range(3):
+        gap = np.abs(zf[i] - base["tau"][i]).min()
+        assert gap > 1e-3
+        for k in range(40):
+            if k == int(zf[i].argmax()):
+                continue      # moving the max moves the threshold; the set is held fixed (Sec. 5.5)
+            zp = zf.copy(); zp[i, k] += h
+            zm = zf.copy(); zm[i, k] -= h
+            fp = orc.rows(zp, ids, lr)["logp"][i]
+            fm = orc.rows(zm, ids, lr)["logp"][i]
+            fd = (fp - fm) / (2 * h)
+            assert abs(fd - base["dz"][i, k]) < 1e-8
+            if not base["safe_flags"][i, k]:
+                assert fd == 0.0
+
+
+# --------------------------------------------------------------------------
+# theory checks on generated train / infer pairs
+# --------------------------------------------------------------------------
+def test_mismatch_bound_prop_4_2():
+    """|Delta_a| <= 2 eps_max (1 - p_a(z_c)) for some z_c on the segment; since
+    p_a(z_c) >= p_a exp(-2 eps_max) this gives the checkable bound below, and
+    Delta_a = -eps_a + log sum_j p_j exp(eps_j) exactly (Prop. 4.2's setting)."""
+    for cfg in (0, 1):
+        wl = workloads.make_rows(cfg, n=24, v=3000)
+        zt = wl.z_train.to(torch.float64).numpy()
+        zi = wl.z_infer.to(torch.float64).numpy()
+        ids = wl.ids.numpy()
+        lr = orc.log_rho_f32(0.0)
+        a = orc.rows(wl.z_train, ids, lr)
+        b = orc.rows(wl.z_infer, ids, lr)
+        eps = zi - zt
+        eps_max = np.abs(eps).max(axis=1)
+        delta = a["logp"] - b["logp"]
+        r = np.arange(len(ids))
+        p = scipy.special.softmax(zt, axis=1)
+        exact = -eps[r, ids] + np.log((p * np.exp(eps)).sum(axis=1))
+        np.testing.assert_allclose(delta, exact, rtol=0, atol=1e-11)
+        bound = 2 * eps_max * (1 - p[r, ids] * np.exp(-2 * eps_max))
+        assert np.all(np.abs(delta) <= bound + 1e-12)
+        assert np.all(np.abs(delta) <= 2 * eps_max + 1e-12)
+
+
+def test_bias_bound_prop_5_5_single_step():
+    """TV(pi_mp, pi) = 1 - Z exactly, and |E_mp R - E R| <= R_max (1 - Z) (Prop. 5.5, T = 1)."""
+    wl = workloads.make_rows(0, n=12, v=5000)
+    z = wl.z_train.numpy().astype(np.float64)
+    rng = np.random.default_rng(9)
+    for rho in (1e-2, 1e-4, math.exp(-13.0)):
+        out = orc.rows(wl.z_train, wl.ids.numpy(), orc.log_rho_f32(rho), want_flags=True)
+        f = out["safe_flags"].astype(bool)
+        pi = scipy.special.softmax(z, axis=1)
+        pmp = np.where(f, np.exp(z - out["lse_safe"][:, None]), 0.0)
+        one_minus_z = -np.expm1(out["lse_safe"] - out["lse_full"])
+        tv = 0.5 * np.abs(pmp - pi).sum(axis=1)
+        np.testing.assert_allclose(tv, one_minus_z, rtol=1e-9, atol=1e-14)
+        rmax = 1.0
+        R = rng.uniform(0, rmax, size=z.shape)
+        gap = np.abs((pmp * R).sum(axis=1) - (pi * R).sum(axis=1))
+        assert np.all(gap <= rmax * one_minus_z + 1e-14)
+
+
+# --------------------------------------------------------------------------
+# LM-head wrapper: chain rule through the linear map
+# --------------------------------------------------------------------------
+def test_lmhead_oracle_against_autograd():
+    wl = workloads.make_lmhead(n=10, d=32, v=200)
+    lr = orc.log_rho_f32(1e-2)
+    g = wl.grad_out.numpy().astype(np.float64)
+    out = orc.lmhead(wl.hidden, wl.w_train, wl.ids.numpy(), lr, grad_out=g, want_flags=True)
+    H = wl.hidden.to(torch.float64).requires_grad_(True)
+    W = wl.w_train.to(torch.float64).requires_grad_(True)
+    z = H @ W.T
+    np.testing.assert_allclose(out["z"], z.detach().numpy(), rtol=0, atol=1e-13)
+    with torch.no_grad():
+        m = z.max(dim=-1, keepdim=True).values
+        thr = (m + float(lr)).to(torch.float32).to(torch.float64)
+        pruned = z < thr
+    masked = torch.where(pruned, torch.tensor(-math.inf, dtype=torch.float64), z)
+    lp = torch.log_softmax(masked, dim=-1)[torch.arange(10), wl.ids]
+    keep = torch.from_numpy(out["y_in_safe"].astype(bool))
+    np.testing.assert_allclose(out["logp"][keep.numpy()], lp[keep].detach().numpy(), atol=1e-12)
+    (lp[keep] * torch.from_numpy(g)[keep]).sum().backward()
+    np.testing.assert_allclose(out["d_hidden"], H.grad.numpy(), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(out["d_w"], W.grad.numpy(), rtol=0, atol=1e-12)
+
+
+def test_threads_do_not_change_results():
+    wl = workloads.make_rows(1, n=13, v=2000)
+    g = wl.grad_out.numpy().astype(np.float64)
+    a = orc.rows(wl.z_train, wl.ids.numpy(), orc.log_rho_f32(1e-4), grad_out=g, want_dz=True, threads=1)
+    b = orc.rows(wl.z_train, wl.ids.numpy(), orc.log_rho_f32(1e-4), grad_out=g, want_dz=True, threads=4)
+    for k in a:
+        np.testing.assert_array_equal(a[k], b[k])

@@ -1,0 +1,185 @@
+/*
+ * dvp.h -- C ABI of the MI355X (gfx950) Dynamic Vocabulary Pruning library.
+ *
+ * The library computes, for every token row of vocabulary logits, the min-p
+ * "safe vocabulary" of Def. 5.1, the renormalised (constrained) policy of
+ * Def. 5.2 evaluated at the sampled token under both the training and the
+ * inference logits, and the gradient of that log-probability with the safe
+ * set held fixed (Prop. 5.4, Prop. 5.6 part 2, Sec. 5.5 "Practical
+ * Implementation").
+ *
+ * Conventions for every entry point
+ *   - Pointers named below as DEVICE pointers refer to HBM owned by the
+ *     caller; the library never allocates, frees or retains them.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *     Work is enqueued on it; no entry point synchronises.
+ *   - The return value reports only what the host can see (null pointers,
+ *     shapes, parameters, launch failures).  Conditions only the device can
+ *     see (a sampled id outside [0, V)) are reported per row in `row_flags`.
+ *   - Matrices are row-major with a row stride `ld*` given in ELEMENTS.  When
+ *     base pointers and row strides are 16-byte aligned and the row fits the
+ *     register file (V <= 163840 for bf16, 81920 for fp32) the rows are read
+ *     from HBM exactly once; otherwise a slower re-reading path is used.
+ *   - Outputs are overwritten, never accumulated into.
+ *   - NaN or +inf logits, and rows that are entirely -inf, give unspecified
+ *     values (never a fault).  -inf logits are allowed.
+ */
+#ifndef DVP_H
+#define DVP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DVP_OK = 0,
+    DVP_ERR_NULL = 1,        /* a required pointer is NULL */
+    DVP_ERR_SHAPE = 2,       /* negative sizes, vocab < 1, ld < vocab, vocab > DVP_MAX_VOCAB */
+    DVP_ERR_PARAM = 3,       /* log_rho is NaN or > 0, unknown dtype */
+    DVP_ERR_ALIGN = 4,       /* a pointer is not aligned to its element size */
+    DVP_ERR_UNSUPPORTED = 5, /* shape outside what the fused LM-head kernels handle */
+    DVP_ERR_WORKSPACE = 6,   /* workspace missing or too small */
+    DVP_ERR_HIP = 7          /* the HIP runtime refused a launch */
+} dvp_status;
+
+typedef enum { DVP_F32 = 0, DVP_BF16 = 1 } dvp_dtype;
+
+#define DVP_MAX_VOCAB 2147418112 /* 2^31 - 2^16: column indices stay in 32 bits */
+
+/* bits of row_flags[i] */
+enum {
+    DVP_ROW_Y_IN_TRAIN_SAFE = 1, /* sampled id is in V_S  (training logits)  */
+    DVP_ROW_Y_IN_INFER_SAFE = 2, /* sampled id is in V'_S (inference logits) */
+    DVP_ROW_ID_OUT_OF_RANGE = 4  /* id < 0 or id >= V: log-probs are NaN, gradient row is zero */
+};
+
+typedef struct {
+    int64_t n_rows;   /* N >= 0 token rows */
+    int64_t vocab;    /* V, 1 <= V <= DVP_MAX_VOCAB */
+    int64_t ld_train; /* row stride of z_train, elements, >= vocab */
+    int64_t ld_infer; /* row stride of z_infer (ignored when z_infer is NULL) */
+    int64_t ld_grad;  /* row stride of dz (ignored by dvp_forward) */
+    int32_t dtype;    /* dvp_dtype of z_train, z_infer and dz */
+    float log_rho;    /* log of the pruning ratio rho of Def. 5.1, <= 0.  -INFINITY means
+                         rho = 0: nothing is pruned and the result is the full log-softmax */
+} dvp_params;
+
+/*
+ * Per-row outputs of one side (training or inference logits).  Every member
+ * is a DEVICE pointer to n_rows elements, or NULL when the caller does not
+ * want it.
+ *   row_max     m_i = max_k z_ik                                   (Def. 5.1)
+ *   lse_safe    log sum_{k in V_S} exp(z_ik)   ("logZ" of the masked softmax,
+ *               Prop. 5.6 part 1)
+ *   lse_full    log sum_k exp(z_ik); log of the coverage mass Z_theta of
+ *               Def. 5.2 is lse_safe - lse_full.  Costs one exp per token.
+ *   logp        log pi^mp(y_i) = z_iy - lse_safe if y_i in V_S, else -inf
+ *   safe_count  |V_S|
+ *   safe_bits   membership bitmask, row stride ceil(V/32) words; bit (k % 32)
+ *               of word k / 32 is 1 iff token k is safe; unused high bits of
+ *               the last word are 0.
+ * The safe set is { k : z_ik >= fl32(m_i + log_rho) }: one round-to-nearest
+ * fp32 add, inclusive comparison (App. A, protocol item 2).
+ */
+typedef struct {
+    float *logp;
+    float *row_max;
+    float *lse_safe;
+    float *lse_full;
+    int32_t *safe_count;
+    uint32_t *safe_bits;
+} dvp_side_out;
+
+/*
+ * Forward pass of the row path (Def. 5.1, Def. 5.2).
+ *   z_train   DEVICE [N, ld_train] logits of the training engine.
+ *   z_infer   DEVICE [N, ld_infer] logits of the inference engine, or NULL to
+ *             skip that side (then out_infer is ignored).
+ *   ids       DEVICE int64 [N] sampled tokens y_i.
+ *   out_train / out_infer   host structs of device pointers, see above;
+ *             out_train must not be NULL (its members may be).
+ *   row_flags DEVICE uint8 [N] or NULL.
+ */
+dvp_status dvp_forward(const dvp_params *params, const void *z_train, const void *z_infer,
+                       const int64_t *ids, const dvp_side_out *out_train,
+                       const dvp_side_out *out_infer, uint8_t *row_flags, void *stream);
+
+/*
+ * Backward pass (Prop. 5.4; set held fixed, Sec. 5.5):
+ *   dz_ik = grad_out_i * (delta(k, y_i) - exp(z_ik - lse_safe_i))  for k in V_S
+ *   dz_ik = 0 for k outside V_S, and the whole row is 0 when y_i is not in
+ *   V_S (its constrained probability is 0, Sec. 5.3) or out of range.
+ * grad_out is dL/dlogp_train, DEVICE float [N]; with grad_out = -1 the row is
+ * "pruned softmax minus one-hot".  row_max_train, lse_safe_train and row_flags
+ * are the forward's outputs (all required).  dz is DEVICE [N, ld_grad] of
+ * params->dtype (bf16 is rounded to nearest even) and may not alias z_train.
+ */
+dvp_status dvp_backward(const dvp_params *params, const void *z_train, const int64_t *ids,
+                        const float *grad_out, const float *row_max_train,
+                        const float *lse_safe_train, const uint8_t *row_flags, void *dz,
+                        void *stream);
+
+/*
+ * Forward and backward in one launch: every training row is read from HBM
+ * once, every inference row once, every gradient row written once.
+ * Arguments as in dvp_forward plus grad_out and dz as in dvp_backward.
+ */
+dvp_status dvp_forward_backward(const dvp_params *params, const void *z_train,
+                                const void *z_infer, const int64_t *ids, const float *grad_out,
+                                const dvp_side_out *out_train, const dvp_side_out *out_infer,
+                                uint8_t *row_flags, void *dz, void *stream);
+
+/*
+ * LM-head variant: the logits z = H W^T are produced tile by tile on the
+ * matrix cores and consumed in the tile epilogues; the [N, V] logits are never
+ * stored.  Same per-row definitions as above (Def. 5.1, 5.2, Prop. 5.4); the
+ * gradient is delivered as dH = dz W and dW = dz^T H.
+ */
+typedef struct {
+    int64_t n_rows;    /* N */
+    int64_t hidden;    /* d, a multiple of 64 */
+    int64_t vocab;     /* V */
+    int64_t ld_hidden; /* row stride of hidden and d_hidden, elements, multiple of 8 */
+    int64_t ld_w;      /* row stride of w_train, w_infer and d_w, elements, multiple of 8 */
+    float log_rho;
+} dvp_lmhead_params;
+
+/* Bytes of DEVICE workspace dvp_fused_lmhead needs for these sizes (0 on invalid params). */
+size_t dvp_fused_lmhead_workspace_bytes(const dvp_lmhead_params *params);
+
+/*
+ *   hidden    DEVICE bf16 [N, ld_hidden]
+ *   w_train   DEVICE bf16 [V, ld_w]
+ *   w_infer   DEVICE bf16 [V, ld_w] or NULL (no inference side)
+ *   ids       DEVICE int64 [N]
+ *   grad_out  DEVICE float [N] or NULL (forward only; d_hidden and d_w ignored)
+ *   d_hidden  DEVICE float [N, ld_hidden], overwritten
+ *   d_w       DEVICE float [V, ld_w], overwritten
+ *   workspace DEVICE, 256-byte aligned, at least the size reported above;
+ *             contents on entry are ignored and on exit are unspecified.
+ * safe_bits members of the output structs must be NULL (not produced here).
+ */
+dvp_status dvp_fused_lmhead(const dvp_lmhead_params *params, const void *hidden,
+                            const void *w_train, const void *w_infer, const int64_t *ids,
+                            const float *grad_out, const dvp_side_out *out_train,
+                            const dvp_side_out *out_infer, uint8_t *row_flags, float *d_hidden,
+                            float *d_w, void *workspace, size_t workspace_bytes, void *stream);
+
+/* (float)log(rho) for rho in (0, 1]; -INFINITY for rho == 0; NaN otherwise.  Host only. */
+float dvp_log_rho(double rho);
+
+/* Static, NUL-terminated description of a status code. */
+const char *dvp_status_string(dvp_status status);
+
+/* Which row kernel a call with these params and these alignments would use:
+ * 1 = register-resident single-read path, 0 = re-reading path, -1 = invalid.
+ * `aligned16` says whether all base pointers are 16-byte aligned. */
+int dvp_row_path(const dvp_params *params, int aligned16);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DVP_H */

@@ -1,0 +1,171 @@
+// extern "C" boundary of the DVP library: argument checks and kernel selection.
+// Every entry point only validates, fills an argument block and enqueues work
+// on the caller's stream; nothing here allocates or synchronises.
+#include <math.h>
+
+#include "dvp_internal.h"
+
+namespace {
+
+using dvp::BackwardArgs;
+using dvp::RowArgs;
+using dvp::SideOut;
+
+inline bool aligned_to(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+inline size_t elem_size(int dtype) { return dtype == DVP_BF16 ? 2 : 4; }
+
+dvp_status check_params(const dvp_params *p, bool need_infer, bool need_grad)
+{
+    if (!p) return DVP_ERR_NULL;
+    if (p->dtype != DVP_F32 && p->dtype != DVP_BF16) return DVP_ERR_PARAM;
+    if (p->log_rho != p->log_rho || p->log_rho > 0.0f) return DVP_ERR_PARAM;
+    if (p->n_rows < 0 || p->vocab < 1 || p->vocab > DVP_MAX_VOCAB) return DVP_ERR_SHAPE;
+    if (p->ld_train < p->vocab) return DVP_ERR_SHAPE;
+    if (need_infer && p->ld_infer < p->vocab) return DVP_ERR_SHAPE;
+    if (need_grad && p->ld_grad < p->vocab) return DVP_ERR_SHAPE;
+    return DVP_OK;
+}
+
+SideOut to_side(const dvp_side_out *o)
+{
+    SideOut s = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+    if (o) {
+        s.logp = o->logp; s.row_max = o->row_max; s.lse_safe = o->lse_safe;
+        s.lse_full = o->lse_full; s.safe_count = o->safe_count; s.safe_bits = o->safe_bits;
+    }
+    return s;
+}
+
+bool side_aligned(const dvp_side_out *o)
+{
+    if (!o) return true;
+    return aligned_to(o->logp, 4) && aligned_to(o->row_max, 4) && aligned_to(o->lse_safe, 4) &&
+           aligned_to(o->lse_full, 4) && aligned_to(o->safe_count, 4) && aligned_to(o->safe_bits, 4);
+}
+
+// the single-read kernel needs 16-byte vector access to every row
+bool rows_vector_ok(const dvp_params *p, const void *z_train, const void *z_infer, const void *dz)
+{
+    const size_t es = elem_size(p->dtype);
+    if (!aligned_to(z_train, 16) || (p->ld_train * es) % 16) return false;
+    if (z_infer && (!aligned_to(z_infer, 16) || (p->ld_infer * es) % 16)) return false;
+    if (dz && (!aligned_to(dz, 16) || (p->ld_grad * es) % 16)) return false;
+    return true;
+}
+
+dvp_status run_rows(const dvp_params *p, const void *z_train, const void *z_infer,
+                    const int64_t *ids, const float *grad_out, const dvp_side_out *out_train,
+                    const dvp_side_out *out_infer, uint8_t *row_flags, void *dz, bool backward,
+                    void *stream)
+{
+    dvp_status st = check_params(p, z_infer != nullptr, backward);
+    if (st != DVP_OK) return st;
+    if (!z_train || !ids || !out_train) return DVP_ERR_NULL;
+    if (backward && (!grad_out || !dz)) return DVP_ERR_NULL;
+    const size_t es = elem_size(p->dtype);
+    if (!aligned_to(z_train, es) || !aligned_to(z_infer, es) || !aligned_to(dz, es) ||
+        !aligned_to(ids, 8) || !aligned_to(grad_out, 4) || !side_aligned(out_train) ||
+        (z_infer && !side_aligned(out_infer)))
+        return DVP_ERR_ALIGN;
+    if (p->n_rows == 0) return DVP_OK;
+
+    RowArgs a;
+    a.z[0] = z_train; a.z[1] = z_infer;
+    a.ld[0] = p->ld_train; a.ld[1] = z_infer ? p->ld_infer : 0;
+    a.out[0] = to_side(out_train);
+    a.out[1] = to_side(z_infer ? out_infer : nullptr);
+    a.ids = ids;
+    a.grad_out = backward ? grad_out : nullptr;
+    a.dz = backward ? dz : nullptr;
+    a.ld_grad = backward ? p->ld_grad : 0;
+    a.row_flags = row_flags;
+    a.n_rows = p->n_rows;
+    a.vocab = (int32_t)p->vocab;
+    a.n_sides = z_infer ? 2 : 1;
+    a.log_rho = p->log_rho;
+
+    const bool resident = dvp::row_fits_resident(p->dtype, p->vocab) &&
+                          rows_vector_ok(p, z_train, z_infer, backward ? dz : nullptr);
+    hipError_t e = resident ? dvp::launch_rows_resident(p->dtype, a, (hipStream_t)stream)
+                            : dvp::launch_rows_streaming(p->dtype, a, (hipStream_t)stream);
+    return e == hipSuccess ? DVP_OK : DVP_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+dvp_status dvp_forward(const dvp_params *params, const void *z_train, const void *z_infer,
+                       const int64_t *ids, const dvp_side_out *out_train,
+                       const dvp_side_out *out_infer, uint8_t *row_flags, void *stream)
+{
+    return run_rows(params, z_train, z_infer, ids, nullptr, out_train, out_infer, row_flags,
+                    nullptr, false, stream);
+}
+
+dvp_status dvp_forward_backward(const dvp_params *params, const void *z_train,
+                                const void *z_infer, const int64_t *ids, const float *grad_out,
+                                const dvp_side_out *out_train, const dvp_side_out *out_infer,
+                                uint8_t *row_flags, void *dz, void *stream)
+{
+    return run_rows(params, z_train, z_infer, ids, grad_out, out_train, out_infer, row_flags, dz,
+                    true, stream);
+}
+
+dvp_status dvp_backward(const dvp_params *params, const void *z_train, const int64_t *ids,
+                        const float *grad_out, const float *row_max_train,
+                        const float *lse_safe_train, const uint8_t *row_flags, void *dz,
+                        void *stream)
+{
+    dvp_status st = check_params(params, false, true);
+    if (st != DVP_OK) return st;
+    if (!z_train || !ids || !grad_out || !row_max_train || !lse_safe_train || !row_flags || !dz)
+        return DVP_ERR_NULL;
+    const size_t es = elem_size(params->dtype);
+    if (!aligned_to(z_train, es) || !aligned_to(dz, es) || !aligned_to(ids, 8) ||
+        !aligned_to(grad_out, 4) || !aligned_to(row_max_train, 4) || !aligned_to(lse_safe_train, 4))
+        return DVP_ERR_ALIGN;
+    if (params->n_rows == 0) return DVP_OK;
+
+    BackwardArgs a;
+    a.z = z_train; a.ld = params->ld_train;
+    a.ids = ids; a.grad_out = grad_out;
+    a.row_max = row_max_train; a.lse_safe = lse_safe_train; a.row_flags = row_flags;
+    a.dz = dz; a.ld_grad = params->ld_grad;
+    a.n_rows = params->n_rows; a.vocab = (int32_t)params->vocab; a.log_rho = params->log_rho;
+    const bool vec = rows_vector_ok(params, z_train, nullptr, dz);
+    hipError_t e = dvp::launch_backward(params->dtype, a, vec, (hipStream_t)stream);
+    return e == hipSuccess ? DVP_OK : DVP_ERR_HIP;
+}
+
+int dvp_row_path(const dvp_params *params, int aligned16)
+{
+    if (check_params(params, false, false) != DVP_OK) return -1;
+    const size_t es = elem_size(params->dtype);
+    const bool ld_ok = (params->ld_train * es) % 16 == 0;
+    return (dvp::row_fits_resident(params->dtype, params->vocab) && aligned16 && ld_ok) ? 1 : 0;
+}
+
+float dvp_log_rho(double rho)
+{
+    if (rho == 0.0) return -INFINITY;
+    if (!(rho > 0.0 && rho <= 1.0)) return NAN;
+    return (float)log(rho);
+}
+
+const char *dvp_status_string(dvp_status status)
+{
+    switch (status) {
+    case DVP_OK: return "ok";
+    case DVP_ERR_NULL: return "a required pointer is NULL";
+    case DVP_ERR_SHAPE: return "invalid shape or row stride";
+    case DVP_ERR_PARAM: return "invalid parameter (dtype, or log_rho is NaN or positive)";
+    case DVP_ERR_ALIGN: return "pointer not aligned to its element size";
+    case DVP_ERR_UNSUPPORTED: return "shape not supported by the fused LM-head kernels";
+    case DVP_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case DVP_ERR_HIP: return "HIP runtime error at kernel launch";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

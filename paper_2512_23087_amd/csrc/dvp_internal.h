@@ -1,0 +1,58 @@
+// Host-side declarations shared by the API layer and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/dvp.h"
+
+namespace dvp {
+
+struct SideOut {
+    float *logp;
+    float *row_max;
+    float *lse_safe;
+    float *lse_full;
+    int32_t *safe_count;
+    uint32_t *safe_bits;
+};
+
+// Arguments of the row kernels.  Side 0 = training logits, side 1 = inference.
+struct RowArgs {
+    const void *z[2];
+    int64_t ld[2];
+    SideOut out[2];
+    const int64_t *ids;
+    const float *grad_out;   // null: forward only
+    void *dz;
+    int64_t ld_grad;
+    uint8_t *row_flags;
+    int64_t n_rows;
+    int32_t vocab;
+    int32_t n_sides;         // 1 or 2
+    float log_rho;
+};
+
+struct BackwardArgs {
+    const void *z;
+    int64_t ld;
+    const int64_t *ids;
+    const float *grad_out;
+    const float *row_max;
+    const float *lse_safe;
+    const uint8_t *row_flags;
+    void *dz;
+    int64_t ld_grad;
+    int64_t n_rows;
+    int32_t vocab;
+    float log_rho;
+};
+
+// true when the register-resident kernel can take a row of this many elements
+bool row_fits_resident(int dtype, int64_t vocab);
+
+// Launchers: return hipSuccess or the launch error.
+hipError_t launch_rows_resident(int dtype, const RowArgs &a, hipStream_t stream);
+hipError_t launch_rows_streaming(int dtype, const RowArgs &a, hipStream_t stream);
+hipError_t launch_backward(int dtype, const BackwardArgs &a, bool vector_ok, hipStream_t stream);
+
+}  // namespace dvp

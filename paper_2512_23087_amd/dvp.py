@@ -1,0 +1,265 @@
+"""Thin ctypes binding over the C-ABI library `libdvp_hip.so`.
+
+Argument marshalling only: tensors supply device memory and the current
+stream, every step of the computation runs in the HIP kernels.  There is no
+CPU or PyTorch fallback: a missing or unloadable library raises ImportError
+at first use, and calls on non-GPU tensors raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import math
+from pathlib import Path
+from typing import Optional
+
+import torch
+
+_PKG = Path(__file__).resolve().parent
+LIB_PATH = _PKG / "libdvp_hip.so"
+
+DVP_F32, DVP_BF16 = 0, 1
+ROW_Y_IN_TRAIN_SAFE, ROW_Y_IN_INFER_SAFE, ROW_ID_OUT_OF_RANGE = 1, 2, 4
+
+EXPORTS = ("dvp_forward", "dvp_backward", "dvp_forward_backward", "dvp_fused_lmhead",
+           "dvp_fused_lmhead_workspace_bytes", "dvp_log_rho", "dvp_status_string", "dvp_row_path")
+
+
+class DvpParams(ctypes.Structure):
+    _fields_ = [("n_rows", ctypes.c_int64), ("vocab", ctypes.c_int64),
+                ("ld_train", ctypes.c_int64), ("ld_infer", ctypes.c_int64),
+                ("ld_grad", ctypes.c_int64), ("dtype", ctypes.c_int32),
+                ("log_rho", ctypes.c_float)]
+
+
+class DvpSideOut(ctypes.Structure):
+    _fields_ = [("logp", ctypes.c_void_p), ("row_max", ctypes.c_void_p),
+                ("lse_safe", ctypes.c_void_p), ("lse_full", ctypes.c_void_p),
+                ("safe_count", ctypes.c_void_p), ("safe_bits", ctypes.c_void_p)]
+
+
+class DvpLmHeadParams(ctypes.Structure):
+    _fields_ = [("n_rows", ctypes.c_int64), ("hidden", ctypes.c_int64), ("vocab", ctypes.c_int64),
+                ("ld_hidden", ctypes.c_int64), ("ld_w", ctypes.c_int64),
+                ("log_rho", ctypes.c_float)]
+
+
+class DvpError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (where, status_string(status), status))
+
+
+_lib = None
+
+
+def lib():
+    """Load the shared library (once).  Fails loudly when it has not been built."""
+    global _lib
+    if _lib is None:
+        if not LIB_PATH.exists():
+            raise ImportError("%s not found: run `python -m paper_2512_23087_amd.build` "
+                              "(there is no fallback path)" % LIB_PATH)
+        L = ctypes.CDLL(str(LIB_PATH))
+        vp, i64p = ctypes.c_void_p, ctypes.c_void_p
+        pp, sp = ctypes.POINTER(DvpParams), ctypes.POINTER(DvpSideOut)
+        L.dvp_forward.restype = ctypes.c_int
+        L.dvp_forward.argtypes = [pp, vp, vp, i64p, sp, sp, vp, vp]
+        L.dvp_backward.restype = ctypes.c_int
+        L.dvp_backward.argtypes = [pp, vp, i64p, vp, vp, vp, vp, vp, vp]
+        L.dvp_forward_backward.restype = ctypes.c_int
+        L.dvp_forward_backward.argtypes = [pp, vp, vp, i64p, vp, sp, sp, vp, vp, vp]
+        lp = ctypes.POINTER(DvpLmHeadParams)
+        L.dvp_fused_lmhead_workspace_bytes.restype = ctypes.c_size_t
+        L.dvp_fused_lmhead_workspace_bytes.argtypes = [lp]
+        L.dvp_fused_lmhead.restype = ctypes.c_int
+        L.dvp_fused_lmhead.argtypes = [lp, vp, vp, vp, i64p, vp, sp, sp, vp, vp, vp, vp,
+                                       ctypes.c_size_t, vp]
+        L.dvp_log_rho.restype = ctypes.c_float
+        L.dvp_log_rho.argtypes = [ctypes.c_double]
+        L.dvp_status_string.restype = ctypes.c_char_p
+        L.dvp_status_string.argtypes = [ctypes.c_int]
+        L.dvp_row_path.restype = ctypes.c_int
+        L.dvp_row_path.argtypes = [pp, ctypes.c_int]
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().dvp_status_string(int(status)).decode()
+
+
+def log_rho(rho: float) -> float:
+    """(float)log(rho) as the library computes it; rho = 0 -> -inf (no pruning)."""
+    return float(lib().dvp_log_rho(float(rho)))
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return DVP_F32
+    if t.dtype == torch.bfloat16:
+        return DVP_BF16
+    raise TypeError("logits must be float32 or bfloat16, got %s" % t.dtype)
+
+
+def _check_rows(z: torch.Tensor, name: str):
+    if not z.is_cuda:
+        raise ValueError("%s must live in GPU memory (no CPU path exists)" % name)
+    if z.dim() != 2 or z.stride(1) != 1:
+        raise ValueError("%s must be [N, V] with unit stride along V" % name)
+
+
+class SideOutputs:
+    """Device buffers for one side's per-row outputs."""
+
+    def __init__(self, n, vocab, device, lse_full=False, safe_bits=False):
+        self.logp = torch.empty(n, dtype=torch.float32, device=device)
+        self.row_max = torch.empty(n, dtype=torch.float32, device=device)
+        self.lse_safe = torch.empty(n, dtype=torch.float32, device=device)
+        self.lse_full = torch.empty(n, dtype=torch.float32, device=device) if lse_full else None
+        self.safe_count = torch.empty(n, dtype=torch.int32, device=device)
+        self.safe_bits = (torch.empty(n, (vocab + 31) // 32, dtype=torch.int32, device=device)
+                          if safe_bits else None)
+
+    def struct(self) -> DvpSideOut:
+        return DvpSideOut(*(None if t is None else t.data_ptr() for t in
+                            (self.logp, self.row_max, self.lse_safe, self.lse_full,
+                             self.safe_count, self.safe_bits)))
+
+    def flags_matrix(self, vocab) -> torch.Tensor:
+        """Expand safe_bits to a uint8 [N, V] matrix (test helper; torch ops)."""
+        words = self.safe_bits.to(torch.int64) & 0xFFFFFFFF
+        shifts = torch.arange(32, device=words.device, dtype=torch.int64)
+        bits = ((words.unsqueeze(-1) >> shifts) & 1).to(torch.uint8)
+        return bits.reshape(words.shape[0], -1)[:, :vocab]
+
+
+class RowResult:
+    def __init__(self, train: SideOutputs, infer: Optional[SideOutputs], row_flags, dz):
+        self.train, self.infer, self.row_flags, self.dz = train, infer, row_flags, dz
+
+
+def _params(z_train, z_infer, dz, log_rho_value) -> DvpParams:
+    return DvpParams(z_train.shape[0], z_train.shape[1], z_train.stride(0),
+                     z_infer.stride(0) if z_infer is not None else 0,
+                     dz.stride(0) if dz is not None else 0,
+                     _dtype_code(z_train), float(log_rho_value))
+
+
+def dvp_forward(z_train, z_infer, ids, log_rho_value, *, lse_full=False, safe_bits=False,
+                out_train: Optional[SideOutputs] = None, out_infer: Optional[SideOutputs] = None,
+                row_flags: Optional[torch.Tensor] = None, stream=None) -> RowResult:
+    _check_rows(z_train, "z_train")
+    if z_infer is not None:
+        _check_rows(z_infer, "z_infer")
+        if z_infer.shape != z_train.shape or z_infer.dtype != z_train.dtype:
+            raise ValueError("z_infer must match z_train in shape and dtype")
+    n, v = z_train.shape
+    dev = z_train.device
+    out_train = out_train or SideOutputs(n, v, dev, lse_full, safe_bits)
+    if z_infer is not None:
+        out_infer = out_infer or SideOutputs(n, v, dev, lse_full, safe_bits)
+    if row_flags is None:
+        row_flags = torch.empty(n, dtype=torch.uint8, device=dev)
+    p = _params(z_train, z_infer, None, log_rho_value)
+    st = lib().dvp_forward(ctypes.byref(p), _ptr(z_train), _ptr(z_infer), _ptr(ids),
+                           ctypes.byref(out_train.struct()),
+                           ctypes.byref(out_infer.struct()) if out_infer is not None else None,
+                           _ptr(row_flags), _stream(stream))
+    if st != 0:
+        raise DvpError(st, "dvp_forward")
+    return RowResult(out_train, out_infer, row_flags, None)
+
+
+def dvp_backward(z_train, ids, grad_out, row_max_train, lse_safe_train, row_flags, log_rho_value,
+                 *, dz: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    _check_rows(z_train, "z_train")
+    if dz is None:
+        dz = torch.empty_like(z_train)
+    p = _params(z_train, None, dz, log_rho_value)
+    st = lib().dvp_backward(ctypes.byref(p), _ptr(z_train), _ptr(ids), _ptr(grad_out),
+                            _ptr(row_max_train), _ptr(lse_safe_train), _ptr(row_flags), _ptr(dz),
+                            _stream(stream))
+    if st != 0:
+        raise DvpError(st, "dvp_backward")
+    return dz
+
+
+def dvp_forward_backward(z_train, z_infer, ids, grad_out, log_rho_value, *, lse_full=False,
+                         safe_bits=False, out_train: Optional[SideOutputs] = None,
+                         out_infer: Optional[SideOutputs] = None,
+                         row_flags: Optional[torch.Tensor] = None,
+                         dz: Optional[torch.Tensor] = None, stream=None) -> RowResult:
+    _check_rows(z_train, "z_train")
+    if z_infer is not None:
+        _check_rows(z_infer, "z_infer")
+        if z_infer.shape != z_train.shape or z_infer.dtype != z_train.dtype:
+            raise ValueError("z_infer must match z_train in shape and dtype")
+    n, v = z_train.shape
+    dev = z_train.device
+    out_train = out_train or SideOutputs(n, v, dev, lse_full, safe_bits)
+    if z_infer is not None:
+        out_infer = out_infer or SideOutputs(n, v, dev, lse_full, safe_bits)
+    if row_flags is None:
+        row_flags = torch.empty(n, dtype=torch.uint8, device=dev)
+    if dz is None:
+        dz = torch.empty_like(z_train)
+    p = _params(z_train, z_infer, dz, log_rho_value)
+    st = lib().dvp_forward_backward(ctypes.byref(p), _ptr(z_train), _ptr(z_infer), _ptr(ids),
+                                    _ptr(grad_out), ctypes.byref(out_train.struct()),
+                                    ctypes.byref(out_infer.struct()) if out_infer is not None else None,
+                                    _ptr(row_flags), _ptr(dz), _stream(stream))
+    if st != 0:
+        raise DvpError(st, "dvp_forward_backward")
+    return RowResult(out_train, out_infer, row_flags, dz)
+
+
+class LmHeadResult:
+    def __init__(self, train, infer, row_flags, d_hidden, d_w):
+        self.train, self.infer, self.row_flags = train, infer, row_flags
+        self.d_hidden, self.d_w = d_hidden, d_w
+
+
+def lmhead_workspace_bytes(n, d, v, ld_hidden=None, ld_w=None) -> int:
+    p = DvpLmHeadParams(n, d, v, ld_hidden or d, ld_w or d, -1.0)
+    return int(lib().dvp_fused_lmhead_workspace_bytes(ctypes.byref(p)))
+
+
+def dvp_fused_lmhead(hidden, w_train, w_infer, ids, grad_out, log_rho_value, *, lse_full=False,
+                     workspace: Optional[torch.Tensor] = None, d_hidden=None, d_w=None,
+                     stream=None) -> LmHeadResult:
+    for name, t in (("hidden", hidden), ("w_train", w_train)):
+        if not t.is_cuda or t.dtype != torch.bfloat16 or t.dim() != 2 or t.stride(1) != 1:
+            raise ValueError("%s must be a bf16 [rows, d] GPU tensor with unit inner stride" % name)
+    n, d = hidden.shape
+    v = w_train.shape[0]
+    dev = hidden.device
+    p = DvpLmHeadParams(n, d, v, hidden.stride(0), w_train.stride(0), float(log_rho_value))
+    need = int(lib().dvp_fused_lmhead_workspace_bytes(ctypes.byref(p)))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    out_train = SideOutputs(n, v, dev, lse_full, False)
+    out_infer = SideOutputs(n, v, dev, lse_full, False) if w_infer is not None else None
+    row_flags = torch.empty(n, dtype=torch.uint8, device=dev)
+    if grad_out is not None:
+        if d_hidden is None:
+            d_hidden = torch.empty(n, hidden.stride(0), dtype=torch.float32, device=dev)[:, :d]
+        if d_w is None:
+            d_w = torch.empty(v, w_train.stride(0), dtype=torch.float32, device=dev)[:, :d]
+    st = lib().dvp_fused_lmhead(ctypes.byref(p), _ptr(hidden), _ptr(w_train), _ptr(w_infer),
+                                _ptr(ids), _ptr(grad_out), ctypes.byref(out_train.struct()),
+                                ctypes.byref(out_infer.struct()) if out_infer is not None else None,
+                                _ptr(row_flags), _ptr(d_hidden), _ptr(d_w), _ptr(workspace),
+                                workspace.numel(), _stream(stream))
+    if st != 0:
+        raise DvpError(st, "dvp_fused_lmhead")
+    return LmHeadResult(out_train, out_infer, row_flags, d_hidden, d_w)

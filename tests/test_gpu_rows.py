@@ -1,0 +1,295 @@
+"""GPU parity of the row path (dvp_forward / dvp_backward / dvp_forward_backward)
+against the fp64 oracle, through the C ABI."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2512_23087_amd import workloads
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dvp():
+    from paper_2512_23087_amd import dvp as binding
+    binding.lib()
+    return binding
+
+
+def _run_case(dvp, wl, rho, *, backward, lse_full=True, bits=True, rows=None, threads=8):
+    lr = dvp.log_rho(rho)
+    assert lr == float(parity.orc.log_rho_f32(rho))      # one shared fp32 constant
+    tol = parity.TOL[wl.z_train.dtype]
+    v = wl.z_train.shape[1]
+    if backward:
+        res = dvp.dvp_forward_backward(wl.z_train, wl.z_infer, wl.ids, wl.grad_out, lr,
+                                       lse_full=lse_full, safe_bits=bits)
+    else:
+        res = dvp.dvp_forward(wl.z_train, wl.z_infer, wl.ids, lr, lse_full=lse_full, safe_bits=bits)
+    torch.cuda.synchronize()
+    if rows is None:
+        zt, zi = wl.z_train.cpu(), wl.z_infer.cpu()
+    else:   # bring back only the sampled rows, keep row numbering via a dense copy
+        idx = torch.as_tensor(rows, device=wl.z_train.device)
+        zt, zi = wl.z_train[idx].cpu(), wl.z_infer[idx].cpu()
+    ids = wl.ids.cpu()
+    stats = {}
+    if rows is None:
+        st = parity.check_side("train", res.train, zt, ids, lr, tol, v, threads=threads)
+        si = parity.check_side("infer", res.infer, zi, ids, lr, tol, v, threads=threads)
+        parity.check_flags(res.row_flags, st["y_in_safe"], si["y_in_safe"], ids, v)
+        if backward:
+            stats.update(parity.check_gradient("dz", res.dz, zt, ids, wl.grad_out.cpu(), lr, tol,
+                                               threads=threads))
+    else:
+        sub = _Subset(res, rows)
+        ids_s = ids[torch.as_tensor(rows)]
+        st = parity.check_side("train", sub.train, zt, ids_s, lr, tol, v, threads=threads)
+        si = parity.check_side("infer", sub.infer, zi, ids_s, lr, tol, v, threads=threads)
+        parity.check_flags(sub.row_flags, st["y_in_safe"], si["y_in_safe"], ids_s, v)
+        if backward:
+            stats.update(parity.check_gradient("dz", sub.dz, zt, ids_s,
+                                               wl.grad_out.cpu()[torch.as_tensor(rows)], lr, tol,
+                                               threads=threads))
+    stats.update(train=st, infer=si, result=res)
+    return stats
+
+
+class _Subset:
+    """View of a RowResult restricted to some rows (keeps the oracle's work bounded)."""
+
+    def __init__(self, res, rows):
+        idx = torch.as_tensor(rows, device=res.row_flags.device)
+
+        class Side:
+            pass
+
+        def cut(side):
+            s = Side()
+            for k in ("logp", "row_max", "lse_safe", "lse_full", "safe_count", "safe_bits"):
+                t = getattr(side, k)
+                setattr(s, k, None if t is None else t[idx])
+            s.flags_matrix = lambda vocab, s=s: type(side).flags_matrix(s, vocab)
+            return s
+
+        self.train, self.infer = cut(res.train), cut(res.infer)
+        self.row_flags = res.row_flags[idx]
+        self.dz = None if res.dz is None else res.dz[idx]
+
+
+# ---------------------------------------------------------------------------
+# the five workload recipes at sizes the oracle finishes in seconds
+# ---------------------------------------------------------------------------
+def test_config0_fp32_forward_full_size(dvp):
+    wl = workloads.make_rows(0, device="cuda")
+    st = _run_case(dvp, wl, 1e-4, backward=False)
+    assert st["train"]["safe_count"].min() > 100     # the spike recipe keeps thousands of tokens
+
+
+def test_config1_bf16_forward_backward(dvp):
+    wl = workloads.make_rows(1, device="cuda", n=192)
+    st = _run_case(dvp, wl, 1e-4, backward=True)
+    assert st["err_grad"] <= 2e-3
+
+
+@pytest.mark.parametrize("rho", [1e-4, math.exp(-13.0)])
+def test_config2_heavy_tail_large_vocab(dvp, rho):
+    wl = workloads.make_rows(2, device="cuda", n=80)
+    st = _run_case(dvp, wl, rho, backward=True)
+    # rows with a uniformly drawn token: (nearly) all outside the safe set, gradient row zero
+    forced = wl.forced_rows.cpu().numpy()
+    assert (st["train"]["y_in_safe"][forced] == 0).sum() >= forced.sum() - 1
+    assert (st["train"]["y_in_safe"][~forced] == 1).sum() > 0
+
+
+@pytest.mark.parametrize("rho", [1e-2, 1e-4, 1e-6, 0.0])
+def test_config3_threshold_sweep(dvp, rho):
+    wl = workloads.make_rows(3, device="cuda", n=48)
+    st = _run_case(dvp, wl, rho, backward=True)
+    if rho == 0.0:
+        v = wl.z_train.shape[1]
+        assert np.all(st["train"]["safe_count"] == v)
+        res = st["result"]
+        assert torch.equal(res.train.lse_safe, res.train.lse_full)   # same sum, same order
+
+
+# ---------------------------------------------------------------------------
+# shapes: ragged tails, tiny vocabularies, both kernels, both dtypes
+# ---------------------------------------------------------------------------
+def _random_case(n, v, dtype, seed, device="cuda", ld=None, offset=0):
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    ld = ld or v
+    store_t = torch.full((n, ld + offset), float("nan")).to(dtype)
+    store_i = torch.full((n, ld + offset), float("nan")).to(dtype)
+    zt = (3.0 * torch.randn(n, v, generator=g)).to(dtype)
+    zi = (zt.float() + 0.05 * torch.randn(n, v, generator=g)).to(dtype)
+    store_t[:, offset:offset + v] = zt
+    store_i[:, offset:offset + v] = zi
+    ids = torch.randint(0, v, (n,), generator=g)
+    ids[0] = 0
+    ids[-1] = v - 1
+    gout = torch.randn(n, generator=g)
+    wl = workloads.RowWorkload(
+        name="rand", z_train=store_t.to(device)[:, offset:offset + v],
+        z_infer=store_i.to(device)[:, offset:offset + v], ids=ids.to(device),
+        grad_out=gout.to(device), rhos=[])
+    return wl
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("v", [1, 2, 7, 8, 16, 33, 1000, 2047, 4104, 8200, 20001, 33000, 70003])
+def test_shapes_resident_path(dvp, dtype, v):
+    n = 5 if v > 20000 else 9
+    es = 2 if dtype == torch.bfloat16 else 4
+    ld = (v * es + 15) // 16 * 16 // es          # 16-byte aligned rows -> single-read kernel
+    wl = _random_case(n, v, dtype, seed=v, ld=ld)
+    p = dvp.DvpParams(n, v, ld, ld, ld, 1 if dtype == torch.bfloat16 else 0, -1.0)
+    assert dvp.lib().dvp_row_path(p, 1) == 1
+    for rho in (1e-2, 0.0):
+        _run_case(dvp, wl, rho, backward=True, threads=2)
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("v", [1, 5, 64, 1001, 5000, 40000])
+def test_shapes_streaming_path_misaligned(dvp, dtype, v):
+    # odd leading dimension and an element offset: rows are not 16-byte aligned
+    wl = _random_case(6, v, dtype, seed=1000 + v, ld=v + 3, offset=1)
+    assert wl.z_train.data_ptr() % 16 != 0
+    for rho in (1e-2, 0.0):
+        _run_case(dvp, wl, rho, backward=True, threads=2)
+
+
+def test_vocab_too_large_for_registers_uses_streaming(dvp):
+    v = 8 * 1024 * 20 + 8       # one vector more than the resident kernel holds
+    wl = _random_case(3, v, torch.bfloat16, seed=77)
+    p = dvp.DvpParams(3, v, v, v, v, 1, -1.0)
+    assert dvp.lib().dvp_row_path(p, 1) == 0
+    _run_case(dvp, wl, 1e-3, backward=True, threads=3)
+
+
+# ---------------------------------------------------------------------------
+# degenerate rows
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_adversarial_rows(dvp, dtype):
+    v = 4104
+    rows = []
+    rows.append(torch.full((v,), -3.25))                       # all equal: every token safe
+    r = torch.full((v,), -20.0); r[1234] = 7.5; rows.append(r)  # single spike
+    r = torch.zeros(v); r[[0, v - 1, 77]] = 5.0; rows.append(r)  # ties at the maximum, first/last index
+    r = torch.linspace(-30, 2, v); rows.append(r)               # a ramp crossing the threshold
+    r = torch.randn(v); r[::3] = float("-inf"); rows.append(r)  # -inf entries
+    r = torch.zeros(v); r[5] = 4.0; r[6] = 4.0 - 2.0; rows.append(r)   # token exactly at the threshold (log_rho = -2)
+    r = 300.0 + torch.randn(v); rows.append(r)                  # large magnitudes
+    r = -300.0 + torch.randn(v); rows.append(r)
+    z = torch.stack(rows).to(dtype)
+    n = z.shape[0]
+    ids = torch.tensor([5, 1234, 77, v - 1, 1, 6, 10, 11])
+    gout = torch.tensor([1.0, -1.0, 2.0, 0.5, -0.25, 1.0, 1.0, -3.0])
+    zi = z.clone()
+    zi[:, :16] = (zi[:, :16].float() * 1.01).to(dtype)
+    wl = workloads.RowWorkload("adv", z.cuda(), zi.cuda(), ids.cuda(), gout.cuda(), [])
+    tol = parity.TOL[dtype]
+    for lr in (-2.0, float(parity.orc.log_rho_f32(1e-4)), 0.0, float("-inf")):
+        res = dvp.dvp_forward_backward(wl.z_train, wl.z_infer, wl.ids, wl.grad_out, lr,
+                                       lse_full=True, safe_bits=True)
+        torch.cuda.synchronize()
+        # fp32 outputs carry half an ulp of |lse| (about 1.5e-5 at 300): widen the bound by it
+        st = parity.check_side("train", res.train, z, ids, lr, max(tol, 4e-5), v, threads=2)
+        si = parity.check_side("infer", res.infer, zi, ids, lr, max(tol, 4e-5), v, threads=2)
+        parity.check_flags(res.row_flags, st["y_in_safe"], si["y_in_safe"], ids, v)
+        parity.check_gradient("dz", res.dz, z, ids, gout, lr, tol, threads=2)
+        if lr == -2.0:
+            assert st["safe_count"][0] == v and st["safe_count"][1] == 1 and st["safe_count"][2] == 3
+            assert st["y_in_safe"][5] == 1        # boundary token is inside (Def. 5.1 uses >=)
+
+
+def test_out_of_range_ids_are_flagged_not_faulted(dvp):
+    wl = _random_case(6, 1000, torch.bfloat16, seed=5)
+    ids = wl.ids.clone()
+    ids[1] = -1
+    ids[2] = 1000
+    ids[3] = 2 ** 40
+    wl.ids = ids
+    st = _run_case(dvp, wl, 1e-2, backward=True, threads=1)
+    flags = st["result"].row_flags.cpu().numpy()
+    assert list(flags[1:4] & 4) == [4, 4, 4] and (flags[0] & 4) == 0
+    assert torch.all(st["result"].dz[1:4] == 0)
+
+
+def test_empty_batch_and_no_infer_side(dvp):
+    z = torch.empty(0, 128, dtype=torch.bfloat16, device="cuda")
+    ids = torch.empty(0, dtype=torch.int64, device="cuda")
+    g = torch.empty(0, device="cuda")
+    res = dvp.dvp_forward_backward(z, z, ids, g, -3.0)
+    assert res.dz.shape == (0, 128)
+    wl = _random_case(7, 3000, torch.float32, seed=9)
+    lr = dvp.log_rho(1e-3)
+    res = dvp.dvp_forward(wl.z_train, None, wl.ids, lr, lse_full=True, safe_bits=True)
+    torch.cuda.synchronize()
+    st = parity.check_side("train", res.train, wl.z_train.cpu(), wl.ids.cpu(), lr, 1e-5, 3000)
+    parity.check_flags(res.row_flags, st["y_in_safe"], None, wl.ids.cpu(), 3000)
+
+
+# ---------------------------------------------------------------------------
+# split calls agree with the fused call; repeated runs are bit-identical
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_split_forward_then_backward_matches_oracle_and_fused(dvp, dtype):
+    wl = _random_case(33, 12344, dtype, seed=21)
+    lr = dvp.log_rho(1e-3)
+    fwd = dvp.dvp_forward(wl.z_train, wl.z_infer, wl.ids, lr)
+    dz = dvp.dvp_backward(wl.z_train, wl.ids, wl.grad_out, fwd.train.row_max, fwd.train.lse_safe,
+                          fwd.row_flags, lr)
+    fused = dvp.dvp_forward_backward(wl.z_train, wl.z_infer, wl.ids, wl.grad_out, lr)
+    torch.cuda.synchronize()
+    parity.check_gradient("split dz", dz, wl.z_train.cpu(), wl.ids.cpu(), wl.grad_out.cpu(), lr,
+                          parity.TOL[dtype], threads=4)
+    assert torch.equal(fwd.train.logp, fused.train.logp)
+    assert torch.equal(fwd.infer.logp, fused.infer.logp)
+    assert torch.equal(fwd.row_flags, fused.row_flags)
+    diff = (dz.float() - fused.dz.float()).abs().max().item()
+    assert diff <= (1e-6 if dtype == torch.float32 else 2 ** -8 * 4)
+
+
+def test_repeated_runs_are_bit_identical(dvp):
+    wl = workloads.make_rows(1, device="cuda", n=300)
+    lr = dvp.log_rho(1e-4)
+    a = dvp.dvp_forward_backward(wl.z_train, wl.z_infer, wl.ids, wl.grad_out, lr, lse_full=True)
+    b = dvp.dvp_forward_backward(wl.z_train, wl.z_infer, wl.ids, wl.grad_out, lr, lse_full=True)
+    torch.cuda.synchronize()
+    for k in ("logp", "row_max", "lse_safe", "lse_full", "safe_count"):
+        assert torch.equal(getattr(a.train, k), getattr(b.train, k))
+        assert torch.equal(getattr(a.infer, k), getattr(b.infer, k))
+    assert torch.equal(a.dz.view(torch.int16), b.dz.view(torch.int16))
+
+
+# ---------------------------------------------------------------------------
+# full benchmark size, in the launch configuration the benchmark times:
+# sampled rows against the oracle, plus properties that hold at any size
+# ---------------------------------------------------------------------------
+def test_full_size_large_vocab_sampled_rows(dvp):
+    wl = workloads.make_rows(2, device="cuda")            # 8192 x 151936 bf16
+    n, v = wl.z_train.shape
+    rng = np.random.default_rng(0)
+    forced = torch.nonzero(wl.forced_rows).flatten().cpu().numpy()
+    rows = np.unique(np.concatenate([[0, 1, n - 1], rng.choice(n, 120, replace=False),
+                                     rng.choice(forced, 24, replace=False)]))
+    for rho in (1e-4, 0.0):
+        st = _run_case(dvp, wl, rho, backward=True, bits=False, lse_full=(rho == 0.0), rows=rows)
+        res = st["result"]
+        # any-size properties on every row
+        cnt = res.train.safe_count
+        assert int(cnt.min()) >= 1 and int(cnt.max()) <= v
+        assert torch.all(res.train.lse_safe >= res.train.row_max)
+        ys = (res.row_flags & 1).bool()
+        assert torch.all(res.dz[~ys] == 0)
+        assert torch.all(torch.isneginf(res.train.logp[~ys]))
+        assert torch.all(res.train.logp[ys] <= 0)
+        if rho == 0.0:
+            assert torch.all(cnt == v)
+    del wl
+    torch.cuda.empty_cache()

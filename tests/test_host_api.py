@@ -1,0 +1,100 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the
+header declares, and rejects bad arguments before touching the GPU."""
+import ctypes
+import math
+import re
+from pathlib import Path
+
+import pytest
+
+from paper_2512_23087_amd import dvp
+
+ROOT = Path(__file__).resolve().parents[1]
+FAKE = 0x10000   # never dereferenced: every call below fails validation or has zero rows
+
+
+def test_library_exports_every_declared_symbol():
+    header = (ROOT / "include" / "dvp.h").read_text()
+    declared = set(re.findall(r"\b(dvp_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(dvp.EXPORTS)
+    L = dvp.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_log_rho_and_status_strings():
+    assert dvp.log_rho(math.exp(-13.0)) == -13.0
+    assert dvp.log_rho(1.0) == 0.0
+    assert dvp.log_rho(0.0) == -math.inf
+    assert math.isnan(dvp.log_rho(2.0)) and math.isnan(dvp.log_rho(-1.0))
+    assert dvp.status_string(0) == "ok"
+    texts = {dvp.status_string(i) for i in range(8)}
+    assert len(texts) == 8 and dvp.status_string(99) == "unknown status"
+
+
+def _fwd(p, z_train=FAKE, z_infer=FAKE, ids=FAKE, out_train=True, out_infer=True):
+    so = dvp.DvpSideOut(FAKE, FAKE, FAKE, None, FAKE, None)
+    return dvp.lib().dvp_forward(ctypes.byref(p), z_train, z_infer, ids,
+                                 ctypes.byref(so) if out_train else None,
+                                 ctypes.byref(so) if out_infer else None, FAKE, None)
+
+
+def test_argument_validation_needs_no_gpu():
+    ok = dict(n_rows=0, vocab=100, ld_train=100, ld_infer=100, ld_grad=100, dtype=1, log_rho=-3.0)
+
+    def P(**kw):
+        d = dict(ok); d.update(kw)
+        return dvp.DvpParams(d["n_rows"], d["vocab"], d["ld_train"], d["ld_infer"], d["ld_grad"],
+                             d["dtype"], d["log_rho"])
+
+    assert _fwd(P()) == 0                                   # zero rows: nothing to do
+    assert dvp.lib().dvp_forward(None, FAKE, FAKE, FAKE, None, None, None, None) == 1
+    assert _fwd(P(), z_train=None) == 1
+    assert _fwd(P(), ids=None) == 1
+    assert _fwd(P(), out_train=False) == 1
+    assert _fwd(P(vocab=0)) == 2
+    assert _fwd(P(n_rows=-1)) == 2
+    assert _fwd(P(ld_train=99)) == 2
+    assert _fwd(P(ld_infer=99)) == 2
+    assert _fwd(P(ld_infer=99), z_infer=None) == 0          # ignored without an inference side
+    assert _fwd(P(vocab=2 ** 31 - 2 ** 16 + 1, ld_train=2 ** 31, ld_infer=2 ** 31)) == 2
+    assert _fwd(P(vocab=2 ** 31 - 2 ** 16, ld_train=2 ** 31, ld_infer=2 ** 31)) == 0
+    assert _fwd(P(dtype=7)) == 3
+    assert _fwd(P(log_rho=0.5)) == 3
+    assert _fwd(P(log_rho=float("nan"))) == 3
+    assert _fwd(P(log_rho=-math.inf)) == 0
+    assert _fwd(P(), z_train=FAKE + 1) == 4                 # not aligned to the element size
+    assert _fwd(P(dtype=0), z_infer=FAKE + 2) == 4
+
+    L = dvp.lib()
+    so = dvp.DvpSideOut(FAKE, FAKE, FAKE, None, FAKE, None)
+    p = P()
+    assert L.dvp_forward_backward(ctypes.byref(p), FAKE, FAKE, FAKE, None, ctypes.byref(so),
+                                  ctypes.byref(so), FAKE, FAKE, None) == 1     # grad_out missing
+    assert L.dvp_forward_backward(ctypes.byref(P(ld_grad=5)), FAKE, FAKE, FAKE, FAKE,
+                                  ctypes.byref(so), ctypes.byref(so), FAKE, FAKE, None) == 2
+    assert L.dvp_backward(ctypes.byref(p), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None) == 0
+    assert L.dvp_backward(ctypes.byref(p), FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, None) == 1
+    assert L.dvp_backward(ctypes.byref(p), FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, None) == 1
+
+
+def test_row_path_selection():
+    L = dvp.lib()
+
+    def path(v, dtype, ld=None, aligned=1):
+        p = dvp.DvpParams(4, v, ld or v, ld or v, ld or v, dtype, -1.0)
+        return L.dvp_row_path(ctypes.byref(p), aligned)
+
+    assert path(151936, 1) == 1 and path(32000, 1) == 1 and path(32000, 0) == 1
+    assert path(163840, 1) == 1 and path(163848, 1) == 0       # register file limit, bf16
+    assert path(81920, 0) == 1 and path(81924, 0) == 0         # and fp32
+    assert path(1000, 1, ld=1001) == 0                         # rows not 16-byte aligned
+    assert path(1000, 1, aligned=0) == 0
+    assert path(0, 1) == -1
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    z = torch.zeros(2, 8, dtype=torch.bfloat16)
+    with pytest.raises(ValueError):
+        dvp.dvp_forward(z, None, torch.zeros(2, dtype=torch.int64), -1.0)

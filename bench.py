@@ -1,0 +1,195 @@
+#!/usr/bin/env python3
+"""Benchmark of the DVP row path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3|cfg2] [--rho 1e-4]
+
+One step = one dvp_forward_backward call over the whole batch: both logit
+matrices are read, every per-row output and the full gradient matrix are
+written.  Inputs are generated on the GPU beforehand and are resident in HBM
+when the timed region starts.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by the
+# same counters' reading on a plain copy kernel of known size.  Only valid for the kernel
+# source it was measured on: keyed by the sha256 of the kernel sources.
+MEASURED_TRAFFIC = {
+    # "sha256 of csrc/dvp_rows.hip + csrc/dvp_device.h": {"cfg3": bytes_per_launch, ...}
+}
+
+
+def kernel_source_hash() -> str:
+    import hashlib
+    h = hashlib.sha256()
+    for name in ("dvp_rows.hip", "dvp_device.h"):
+        with open(os.path.join(ROOT, "paper_2512_23087_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def algorithmic_bytes_per_row(vocab: int, elem: int, infer: bool = True) -> int:
+    """What the method must move per row: read the training row, read the
+    inference row, write the gradient row, plus the per-row scalars
+    (id 8, grad_out 4, and per side logp/row_max/lse_safe/safe_count 16; flags 1)."""
+    sides = 2 if infer else 1
+    return (sides + 1) * vocab * elem + 8 + 4 + 16 * sides + 1
+
+
+def cpu_baseline(wl, log_rho, target_seconds=15.0):
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload."""
+    import numpy as np
+    from oracle import dvp_oracle as orc
+    threads = min(os.cpu_count() or 1, 16)
+    n = wl.z_train.shape[0]
+
+    chunk = 512
+    done, spent = 0, 0.0
+    while done < n and spent < target_seconds:
+        r0, r1 = done, min(n, done + chunk)
+        zt = wl.z_train[r0:r1].cpu()
+        zi = wl.z_infer[r0:r1].cpu()
+        ids = wl.ids[r0:r1].cpu().numpy()
+        g = wl.grad_out[r0:r1].cpu().numpy().astype(np.float64)
+        t0 = time.perf_counter()
+        orc.rows(zt, ids, np.float32(log_rho), grad_out=g, want_dz=True, threads=threads)
+        orc.rows(zi, ids, np.float32(log_rho), threads=threads)
+        spent += time.perf_counter() - t0
+        done = r1
+    return {"value": done / spent, "unit": "rows/s", "cores": threads, "kind": "oracle",
+            "sample": "first %d rows of the workload in chunks of %d, forward (both sides) + "
+                      "backward, fp64 C oracle on %d threads, %.1f s of CPU wall time"
+                      % (done, chunk, threads, spent)}
+
+
+def time_launches(fn, steps, warmup):
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    ends = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        starts[i].record()
+        fn()
+        ends[i].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    per_launch_ms = [s.elapsed_time(e) for s, e in zip(starts, ends)]
+    return wall, per_launch_ms
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3"])
+    ap.add_argument("--rho", type=float, default=1e-4)
+    ap.add_argument("--rows", type=int, default=None, help="override N (for quick runs)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sweep", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; rows are independent, so N GPUs would each "
+              "take N_rows/N rows with no communication. Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2512_23087_amd import dvp, workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the DVP library has no CPU path", file=sys.stderr)
+        sys.exit(2)
+    dvp.lib()
+    torch.cuda.set_device(0)
+    cfg = int(args.workload[-1])
+    t_gen = time.perf_counter()
+    wl = workloads.make_rows(cfg, device="cuda:0", n=args.rows)
+    torch.cuda.synchronize()
+    t_gen = time.perf_counter() - t_gen
+    n, v = wl.z_train.shape
+    elem = wl.z_train.element_size()
+    lr = dvp.log_rho(args.rho)
+
+    out_t = dvp.SideOutputs(n, v, wl.z_train.device)
+    out_i = dvp.SideOutputs(n, v, wl.z_train.device)
+    flags = torch.empty(n, dtype=torch.uint8, device="cuda:0")
+    dz = torch.empty_like(wl.z_train)
+
+    def step(log_rho_value=lr):
+        dvp.dvp_forward_backward(wl.z_train, wl.z_infer, wl.ids, wl.grad_out, log_rho_value,
+                                 out_train=out_t, out_infer=out_i, row_flags=flags, dz=dz)
+
+    wall, per_launch = time_launches(step, args.steps, args.warmup)
+    ms_per_step = wall * 1e3 / args.steps
+    kernel_ms = sum(per_launch) / len(per_launch)
+    bytes_per_launch = algorithmic_bytes_per_row(v, elem) * n
+    achieved = bytes_per_launch / (kernel_ms * 1e-3) / 1e9
+
+    traffic = MEASURED_TRAFFIC.get(kernel_source_hash(), {}).get(args.workload) \
+        if args.rows is None and args.rho == 1e-4 else None
+
+    result = {
+        "metric": "DVP fwd+bwd rows/s and achieved HBM GB/s (% of peak), V=151936 bf16",
+        "value": n * args.steps / wall,
+        "unit": "rows/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "configs[%d]: N=%d x V=%d %s logits (train + infer), fused "
+                               "forward+backward, rho=%g" % (cfg, n, v, str(wl.z_train.dtype)[6:], args.rho),
+                   "storage_dtype": str(wl.z_train.dtype)[6:], "n_rows": n, "vocab": v,
+                   "rho": args.rho, "entry_point": "dvp_forward_backward",
+                   "row_kernel": "resident" if dvp.lib().dvp_row_path(
+                       dvp.DvpParams(n, v, v, v, v, 1 if elem == 2 else 0, lr), 1) == 1 else "streaming",
+                   "input_generation_s": round(t_gen, 2)},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "kernel": "rows_resident_kernel", "kernel_ms_avg": kernel_ms,
+                     "kernel_ms_min": min(per_launch),
+                     "algorithmic_bytes_per_launch": bytes_per_launch},
+    }
+
+    # safe-set sizes at the headline threshold, and the threshold sweep of configs[3]
+    cnt = out_t.safe_count.to(torch.float64)
+    result["safe_set"] = {"mean": cnt.mean().item(), "median": cnt.median().item(),
+                          "max": cnt.max().item(),
+                          "y_in_train_safe_frac": (flags & 1).to(torch.float64).mean().item()}
+    if not args.no_sweep:
+        sweep = []
+        for rho in wl.rhos:
+            lr_s = dvp.log_rho(rho)
+            w, pl = time_launches(lambda: step(lr_s), max(3, args.steps // 3), 2)
+            k_ms = sum(pl) / len(pl)
+            c = out_t.safe_count
+            edges = [1, 2, 4, 16, 256, 4096, 65536, v + 1]
+            hist = torch.bucketize(c.to(torch.int64), torch.tensor(edges, device=c.device), right=True)
+            sweep.append({"rho": rho, "kernel_ms_avg": k_ms,
+                          "rows_per_s": n / (k_ms * 1e-3),
+                          "hbm_frac": bytes_per_launch / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                          "safe_size_hist": {"edges": edges,
+                                             "counts": torch.bincount(hist, minlength=len(edges) + 1).tolist()}})
+        result["threshold_sweep"] = sweep
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(wl, lr)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -21,6 +21,8 @@
  *     register file (V <= 163840 for bf16, 81920 for fp32) the rows are read
  *     from HBM exactly once; otherwise a slower re-reading path is used.
  *   - Outputs are overwritten, never accumulated into.
+ *   - With n_rows == 0 (and otherwise valid params) every entry point returns
+ *     DVP_OK without looking at any pointer.
  *   - NaN or +inf logits, and rows that are entirely -inf, give unspecified
  *     values (never a fault).  -inf logits are allowed.
  */

@@ -60,6 +60,7 @@ dvp_status run_rows(const dvp_params *p, const void *z_train, const void *z_infe
 {
     dvp_status st = check_params(p, z_infer != nullptr, backward);
     if (st != DVP_OK) return st;
+    if (p->n_rows == 0) return DVP_OK;   // nothing is read or written; pointers may be NULL
     if (!z_train || !ids || !out_train) return DVP_ERR_NULL;
     if (backward && (!grad_out || !dz)) return DVP_ERR_NULL;
     const size_t es = elem_size(p->dtype);
@@ -67,7 +68,6 @@ dvp_status run_rows(const dvp_params *p, const void *z_train, const void *z_infe
         !aligned_to(ids, 8) || !aligned_to(grad_out, 4) || !side_aligned(out_train) ||
         (z_infer && !side_aligned(out_infer)))
         return DVP_ERR_ALIGN;
-    if (p->n_rows == 0) return DVP_OK;
 
     RowArgs a;
     a.z[0] = z_train; a.z[1] = z_infer;
@@ -119,13 +119,13 @@ dvp_status dvp_backward(const dvp_params *params, const void *z_train, const int
 {
     dvp_status st = check_params(params, false, true);
     if (st != DVP_OK) return st;
+    if (params->n_rows == 0) return DVP_OK;
     if (!z_train || !ids || !grad_out || !row_max_train || !lse_safe_train || !row_flags || !dz)
         return DVP_ERR_NULL;
     const size_t es = elem_size(params->dtype);
     if (!aligned_to(z_train, es) || !aligned_to(dz, es) || !aligned_to(ids, 8) ||
         !aligned_to(grad_out, 4) || !aligned_to(row_max_train, 4) || !aligned_to(lse_safe_train, 4))
         return DVP_ERR_ALIGN;
-    if (params->n_rows == 0) return DVP_OK;
 
     BackwardArgs a;
     a.z = z_train; a.ld = params->ld_train;

@@ -1,10 +1,13 @@
 """Element-by-element comparison of the HIP row path with the fp64 oracle.
 
 Tolerances (absolute): log-probs, lse: 1e-5 for fp32 inputs, 2e-3 for bf16
-inputs; gradients: the same numbers times max(1, |grad_out_i|) (the bf16
-gradient is rounded to nearest even on output, so its half-ulp grows with its
-magnitude).  Row maxima, safe-set sizes and membership must match exactly:
-both sides decide membership by the same fp32 threshold fl32(m + log_rho).
+inputs.  Gradients: fp32 output 1e-5 * max(1, |grad_out_i|); bf16 output
+max(2e-3, half_ulp_bf16(|dz_oracle|) + 1e-5 * max(1, |grad_out_i|)) -- the
+gradient is stored with 8 significant bits, so an element of magnitude >= 1
+cannot be closer than 2^-8 to the exact value whatever the kernel computes;
+below magnitude 1 the bound is the plain 2e-3.  Row maxima, safe-set sizes and
+membership must match exactly: both sides decide membership by the same fp32
+threshold fl32(m + log_rho).
 """
 from __future__ import annotations
 
@@ -91,9 +94,17 @@ def check_gradient(name, dz_gpu, z_host, ids_host, grad_host, log_rho, tol, rows
                  want_flags=True, threads=threads)
     got = f64(dz_gpu[torch.as_tensor(sel).to(dz_gpu.device)])
     scale = np.maximum(1.0, np.abs(g))[:, None]
-    err = np.abs(got - o["dz"]) / scale
+    if dz_gpu.dtype == torch.bfloat16:
+        mag = np.abs(o["dz"])
+        with np.errstate(divide="ignore"):
+            half_ulp = np.where(mag > 0, np.exp2(np.floor(np.log2(np.maximum(mag, 1e-300))) - 8), 0.0)
+        bound = np.maximum(tol, half_ulp + 1e-5 * scale)
+    else:
+        bound = tol * scale
+    err = np.abs(got - o["dz"]) / bound
     worst = err.max() if err.size else 0.0
-    assert worst <= tol, "%s: gradient max scaled abs err %.3e > %.1e" % (name, worst, tol)
+    assert worst <= 1.0, "%s: gradient error is %.3f x its bound (raw max abs %.3e)" % (
+        name, worst, np.abs(got - o["dz"]).max())
     # exact zeros off the safe set and on rows whose sampled token is pruned
     off = o["safe_flags"] == 0
     assert np.all(got[off] == 0.0), name + ": nonzero gradient outside the safe set"

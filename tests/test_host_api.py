@@ -48,10 +48,11 @@ def test_argument_validation_needs_no_gpu():
                              d["dtype"], d["log_rho"])
 
     assert _fwd(P()) == 0                                   # zero rows: nothing to do
+    assert _fwd(P(), z_train=None, ids=None) == 0           # ... and no pointer is looked at
     assert dvp.lib().dvp_forward(None, FAKE, FAKE, FAKE, None, None, None, None) == 1
-    assert _fwd(P(), z_train=None) == 1
-    assert _fwd(P(), ids=None) == 1
-    assert _fwd(P(), out_train=False) == 1
+    assert _fwd(P(n_rows=1), z_train=None) == 1
+    assert _fwd(P(n_rows=1), ids=None) == 1
+    assert _fwd(P(n_rows=1), out_train=False) == 1
     assert _fwd(P(vocab=0)) == 2
     assert _fwd(P(n_rows=-1)) == 2
     assert _fwd(P(ld_train=99)) == 2
@@ -63,19 +64,20 @@ def test_argument_validation_needs_no_gpu():
     assert _fwd(P(log_rho=0.5)) == 3
     assert _fwd(P(log_rho=float("nan"))) == 3
     assert _fwd(P(log_rho=-math.inf)) == 0
-    assert _fwd(P(), z_train=FAKE + 1) == 4                 # not aligned to the element size
-    assert _fwd(P(dtype=0), z_infer=FAKE + 2) == 4
+    assert _fwd(P(n_rows=1), z_train=FAKE + 1) == 4         # not aligned to the element size
+    assert _fwd(P(n_rows=1, dtype=0), z_infer=FAKE + 2) == 4
 
     L = dvp.lib()
     so = dvp.DvpSideOut(FAKE, FAKE, FAKE, None, FAKE, None)
     p = P()
-    assert L.dvp_forward_backward(ctypes.byref(p), FAKE, FAKE, FAKE, None, ctypes.byref(so),
+    p1 = P(n_rows=1)
+    assert L.dvp_forward_backward(ctypes.byref(p1), FAKE, FAKE, FAKE, None, ctypes.byref(so),
                                   ctypes.byref(so), FAKE, FAKE, None) == 1     # grad_out missing
     assert L.dvp_forward_backward(ctypes.byref(P(ld_grad=5)), FAKE, FAKE, FAKE, FAKE,
                                   ctypes.byref(so), ctypes.byref(so), FAKE, FAKE, None) == 2
     assert L.dvp_backward(ctypes.byref(p), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None) == 0
-    assert L.dvp_backward(ctypes.byref(p), FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, None) == 1
-    assert L.dvp_backward(ctypes.byref(p), FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, None) == 1
+    assert L.dvp_backward(ctypes.byref(p1), FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, None) == 1
+    assert L.dvp_backward(ctypes.byref(p1), FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, None) == 1
 
 
 def test_row_path_selection():

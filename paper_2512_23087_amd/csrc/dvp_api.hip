@@ -86,8 +86,20 @@ dvp_status run_rows(const dvp_params *p, const void *z_train, const void *z_infe
 
     const bool resident = dvp::row_fits_resident(p->dtype, p->vocab) &&
                           rows_vector_ok(p, z_train, z_infer, backward ? dz : nullptr);
+    // Split gradient: possible when the per-row flags and safe-set sizes are
+    // produced anyway (the fill kernel reads them back).
+    a.split_grad = (resident && backward && row_flags && a.out[0].safe_count) ? 1 : 0;
+    const int64_t cap = (int64_t)(p->vocab * es / 8) - 2;
+    a.list_cap = (int32_t)(cap < 0 ? 0 : (cap > dvp::kListMax ? dvp::kListMax : cap));
     hipError_t e = resident ? dvp::launch_rows_resident(p->dtype, a, (hipStream_t)stream)
                             : dvp::launch_rows_streaming(p->dtype, a, (hipStream_t)stream);
+    if (e == hipSuccess && a.split_grad) {
+        dvp::FillArgs f;
+        f.dz = dz; f.ld_grad = p->ld_grad;
+        f.row_flags = row_flags; f.safe_count = a.out[0].safe_count;
+        f.n_rows = p->n_rows; f.vocab = (int32_t)p->vocab; f.list_cap = a.list_cap;
+        e = dvp::launch_grad_fill(p->dtype, f, (hipStream_t)stream);
+    }
     return e == hipSuccess ? DVP_OK : DVP_ERR_HIP;
 }
 

@@ -30,7 +30,25 @@ struct RowArgs {
     int32_t vocab;
     int32_t n_sides;         // 1 or 2
     float log_rho;
+    // Split gradient: rows whose sampled token is pruned, or whose safe set has
+    // at most list_cap tokens, are not written by the row kernel; it leaves
+    // their (index, value) pairs at the start of the gradient row and
+    // launch_grad_fill() writes the row.  Needs row_flags and out[0].safe_count.
+    int32_t split_grad;
+    int32_t list_cap;
 };
+
+struct FillArgs {
+    void *dz;
+    int64_t ld_grad;
+    const uint8_t *row_flags;
+    const int32_t *safe_count;
+    int64_t n_rows;
+    int32_t vocab;
+    int32_t list_cap;
+};
+
+constexpr int kListMax = 2048;   // longest (index, value) list a gradient row may carry
 
 struct BackwardArgs {
     const void *z;
@@ -53,6 +71,7 @@ bool row_fits_resident(int dtype, int64_t vocab);
 // Launchers: return hipSuccess or the launch error.
 hipError_t launch_rows_resident(int dtype, const RowArgs &a, hipStream_t stream);
 hipError_t launch_rows_streaming(int dtype, const RowArgs &a, hipStream_t stream);
+hipError_t launch_grad_fill(int dtype, const FillArgs &a, hipStream_t stream);
 hipError_t launch_backward(int dtype, const BackwardArgs &a, bool vector_ok, hipStream_t stream);
 
 }  // namespace dvp

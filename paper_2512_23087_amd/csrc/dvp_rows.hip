@@ -19,35 +19,82 @@ namespace dvp {
 // ---------------------------------------------------------------------------
 // resident kernel: NT threads hold NV 16-byte vectors each
 // ---------------------------------------------------------------------------
-template <typename T>
-__device__ __forceinline__ u32x4 load_tail_vector(const T *p, int n_valid)
-{
-    // fewer than one vector of valid elements at the end of a row: fetch them
-    // one by one and fill the rest with -inf
-    constexpr int EPV = elem_traits<T>::kPerVec;
-    float x[EPV];
-#pragma unroll
-    for (int e = 0; e < EPV; ++e) x[e] = (e < n_valid) ? load_elem(p + e) : -INFINITY;
-    if constexpr (EPV == 4) {
-        return pack(x, float());
-    } else {
-        u32x4 v;   // exact: the values are bf16 already, truncation keeps them
-        v.x = (float_to_bits(x[0]) >> 16) | (float_to_bits(x[1]) & 0xffff0000u);
-        v.y = (float_to_bits(x[2]) >> 16) | (float_to_bits(x[3]) & 0xffff0000u);
-        v.z = (float_to_bits(x[4]) >> 16) | (float_to_bits(x[5]) & 0xffff0000u);
-        v.w = (float_to_bits(x[6]) >> 16) | (float_to_bits(x[7]) & 0xffff0000u);
-        return v;
-    }
-}
-
 // Compiler fences with no run-time cost.  The row lives in registers across
 // three phases; without them the optimiser keeps every phase's unpacked copy
-// of the row (and every per-vector index and predicate) alive from one phase
-// to the next, which overflows the register file.
+// of the row (and every per-slot index and predicate) alive from one phase to
+// the next, which overflows the register file.
 __device__ __forceinline__ void keep_packed(u32x4 &v) { asm volatile("" : "+v"(v)); }
 __device__ __forceinline__ int fresh(int v) { asm volatile("" : "+v"(v)); return v; }
 
-template <typename T, int NV, int NT, int MINW>
+// Register slot j of thread t holds vector (j * NT + t) of the row.  Slots
+// below NVFULL hold a whole vector in every thread of every row the
+// instantiation is launched for; the others may lie past the end of the row
+// and then hold -inf: they never win the max, add exp(-inf) = 0 to the sums,
+// and pass the threshold only when it is -inf itself.
+template <typename T, int NT, int NVFULL>
+__device__ __forceinline__ u32x4 load_slot(const T *zrow, int j, int t, int nvec)
+{
+    using TR = elem_traits<T>;
+    const u32x4 *zvec = (const u32x4 *)zrow;
+    const int idx = j * NT + t;
+    if (j < NVFULL) return __builtin_nontemporal_load(zvec + idx);
+    // the load runs under the lane mask and lands on top of the padding value:
+    // nothing has to wait for it here
+    u32x4 v = (u32x4){TR::kPadWord, TR::kPadWord, TR::kPadWord, TR::kPadWord};
+    if (idx < nvec) v = __builtin_nontemporal_load(zvec + idx);
+    return v;
+}
+
+// Single elements fetched ahead of time stay in their stored form until they
+// are used: converting right after the load would make the wavefront wait for
+// the memory round trip on the spot.
+__device__ __forceinline__ uint32_t load_raw(const float *p) { return __float_as_uint(*p); }
+__device__ __forceinline__ uint32_t load_raw(const bf16_t *p) { return p->bits; }
+__device__ __forceinline__ float from_raw(uint32_t u, float) { return __uint_as_float(u); }
+__device__ __forceinline__ float from_raw(uint32_t u, bf16_t) { return __uint_as_float(u << 16); }
+template <typename T> __device__ __forceinline__ uint32_t raw_neg_inf()
+{
+    return sizeof(T) == 2 ? 0xff80u : 0xff800000u;
+}
+
+// Append the (index, value) pairs of the lanes with `take` set to a row's
+// list; `counter` is a workgroup-wide cursor in LDS.  Wavefront-uniform call.
+__device__ __forceinline__ void list_append(uint2 *list, int *counter, bool take, uint32_t k, float d)
+{
+    const unsigned long long bal = __builtin_amdgcn_ballot_w64(take);
+    if (bal == 0) return;
+    int base = 0;
+    if ((threadIdx.x & (kWave - 1)) == 0) base = atomicAdd(counter, (int)__builtin_popcountll(bal));
+    base = __builtin_amdgcn_readfirstlane(base);
+    if (take) {
+        const int pos = base + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32),
+                                                              __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
+        list[pos] = make_uint2(k, __float_as_uint(d));
+    }
+}
+
+// gradient values of one vector -> storage format
+__device__ __forceinline__ u32x4 pack_grad(const float (&d)[4], float) { return pack(d, float()); }
+__device__ __forceinline__ u32x4 pack_grad(const float (&d)[8], bf16_t)
+{
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    u32x4 v;   // hardware pack-convert, round to nearest even
+    bf16x2 b;
+    b = __builtin_convertvector((f32x2){d[0], d[1]}, bf16x2); v.x = __builtin_bit_cast(uint32_t, b);
+    b = __builtin_convertvector((f32x2){d[2], d[3]}, bf16x2); v.y = __builtin_bit_cast(uint32_t, b);
+    b = __builtin_convertvector((f32x2){d[4], d[5]}, bf16x2); v.z = __builtin_bit_cast(uint32_t, b);
+    b = __builtin_convertvector((f32x2){d[6], d[7]}, bf16x2); v.w = __builtin_bit_cast(uint32_t, b);
+    return v;
+}
+
+// The workgroup walks a list of tasks: for each of its rows, the inference
+// side then the training side.  While the last phase of a task consumes the
+// registers, each freed slot is refilled with the next task's vector, so the
+// CU keeps loads in flight while it computes.  The ragged end of a row (fewer
+// than one vector) is held one element per thread in threads 0..tail-1.
+// EXTRAS builds also produce lse_full and the membership bitmask.
+template <typename T, int NV, int NVFULL, int NT, int MINW, bool EXTRAS>
 __global__ __launch_bounds__(NT, MINW) void rows_resident_kernel(const RowArgs a)
 {
     using TR = elem_traits<T>;
@@ -56,161 +103,220 @@ __global__ __launch_bounds__(NT, MINW) void rows_resident_kernel(const RowArgs a
     __shared__ float lds_max[NW];
     __shared__ float lds_f[2 * NW];
     __shared__ int lds_i[NW];
+    __shared__ int lds_list_count;
 
     const int tid = threadIdx.x;
     const int V = a.vocab;
-    const int nvec = V / EPV;              // whole vectors in a row
-    const int tail = V - nvec * EPV;       // elements in the ragged last vector
-    const int nfull = nvec / NT;           // register slots that hold a whole vector in every thread
+    const int nvec = V / EPV;              // whole vectors in a row (>= 1, checked by the launcher)
+    const int tail = V - nvec * EPV;       // elements in the ragged end
     const float log_rho = a.log_rho;
     const bool want_bwd = a.grad_out != nullptr;
     const int bits_words = (V + 31) / 32;
+    const int first_side = a.n_sides - 1;  // inference row first, training row last
 
-    for (int64_t row = blockIdx.x; row < a.n_rows; row += gridDim.x) {
-        const int64_t y = a.ids[row];
-        const bool y_ok = (y >= 0) && (y < (int64_t)V);
-        uint32_t flags = y_ok ? 0u : (uint32_t)DVP_ROW_ID_OUT_OF_RANGE;
+    int64_t row = blockIdx.x;
+    if (row >= a.n_rows) return;
+    int side = first_side;
 
-        for (int side = a.n_sides - 1; side >= 0; --side) {   // inference row first, training row last
-            const T *zrow = (const T *)a.z[side] + row * a.ld[side];
-            const u32x4 *zvec = (const u32x4 *)zrow;
-            const SideOut &out = a.out[side];
-            const bool want_full = out.lse_full != nullptr;
-            uint8_t *bits_row = out.safe_bits
-                ? (uint8_t *)(out.safe_bits + row * (int64_t)bits_words) : nullptr;
-
-            // ---- the row enters the register file: its only trip from HBM.
-            // Slots past the end of the row hold -inf: they never win the max,
-            // add exp(-inf) = 0 to the sums, and are safe only when tau = -inf.
-            u32x4 r[NV];
-            {
-                const int t = fresh(tid);
+    u32x4 r[NV];
+    uint32_t xt_raw = raw_neg_inf<T>();    // this thread's element of the ragged end (stored form), or -inf
+    uint32_t zy_raw = 0;                   // the sampled token's logit (stored form)
+    int64_t y = a.ids[row];
+    bool y_ok = (y >= 0) && (y < (int64_t)V);
+    float g = want_bwd ? a.grad_out[row] : 0.0f;
+    {
+        const T *zrow = (const T *)a.z[side] + row * a.ld[side];
+        const int t = fresh(tid);
 #pragma unroll
-                for (int j = 0; j < NV; ++j) {
-                    if (j < nfull) {
-                        r[j] = __builtin_nontemporal_load(zvec + (j * NT + t));
-                    } else {
-                        const int idx = j * NT + t;
-                        if (idx < nvec) {
-                            r[j] = __builtin_nontemporal_load(zvec + idx);
-                        } else if (idx == nvec && tail) {
-                            r[j] = load_tail_vector(zrow + (int64_t)nvec * EPV, tail);
-                        } else {
-                            r[j] = (u32x4){TR::kPadWord, TR::kPadWord, TR::kPadWord, TR::kPadWord};
-                        }
-                    }
+        for (int j = 0; j < NV; ++j) r[j] = load_slot<T, NT, NVFULL>(zrow, j, t, nvec);
+        if (t < tail) xt_raw = load_raw(zrow + (int64_t)nvec * EPV + t);
+        if (y_ok) zy_raw = load_raw(zrow + y);
+    }
+    uint32_t flags = y_ok ? 0u : (uint32_t)DVP_ROW_ID_OUT_OF_RANGE;
+
+    for (;;) {
+        // ---- the task after this one (its loads are issued during this task's last phase) ----
+        int64_t nrow = row, ny = y;
+        int nside = side - 1;
+        if (nside < 0) { nrow = row + gridDim.x; nside = first_side; }
+        const bool has_next = nrow < a.n_rows;
+        float ng = g;
+        if (has_next && nrow != row) {
+            ny = a.ids[nrow];
+            if (want_bwd) ng = a.grad_out[nrow];
+        }
+        const bool ny_ok = (ny >= 0) && (ny < (int64_t)V);
+        const T *znext = (const T *)a.z[has_next ? nside : side] + (has_next ? nrow : row) * a.ld[has_next ? nside : side];
+        uint32_t nzy_raw = 0, nxt_raw = raw_neg_inf<T>();
+        const float xt = from_raw(xt_raw, T());
+        const float zy = from_raw(zy_raw, T());
+
+        const SideOut &out = a.out[side];
+        const bool want_full = EXTRAS && out.lse_full != nullptr;
+        uint8_t *bits_row = (EXTRAS && out.safe_bits)
+            ? (uint8_t *)(out.safe_bits + row * (int64_t)bits_words) : nullptr;
+        const bool bwd_here = want_bwd && side == 0;
+        const bool refill_in_sums = has_next && !bwd_here;
+
+        // ---- row maximum (Def. 5.1) ----
+        float m = xt;
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            float x[EPV];
+            unpack(r[j], x, T());
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) m = fmaxf(m, x[e]);
+        }
+        m = block_max<NT>(m, lds_max);
+#pragma unroll
+        for (int j = 0; j < NV; ++j) keep_packed(r[j]);
+        // every wavefront is past the previous row's appends (it reached the barrier
+        // above) and the next appends come after one more barrier
+        if (tid == 0) lds_list_count = 0;
+
+        // ---- threshold, membership, size, masked sum (Def. 5.1 / 5.2) ----
+        const float tau = m + log_rho;   // one fp32 rounding
+        float s_safe = 0.0f, s_full = 0.0f;
+        int wave_count = 0;              // wavefront-uniform: lanes are counted with scalar popcounts
+        uint32_t any_mask = 0;           // bit j: some lane of this wavefront has a safe token in slot j
+        if (has_next) {   // the next task's single elements, fetched early and left in stored form
+            if (ny_ok) nzy_raw = load_raw(znext + ny);
+            if (tid < tail) nxt_raw = load_raw(znext + (int64_t)nvec * EPV + tid);
+        }
+        {   // ragged end: one element per thread
+            wave_count += __builtin_popcountll(__builtin_amdgcn_ballot_w64(xt >= tau));
+            const float ex = __expf(xt - m);
+            s_safe += (xt >= tau) ? ex : 0.0f;
+            if (want_full) s_full += ex;
+        }
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            float x[EPV];
+            unpack(r[j], x, T());
+            const int before = wave_count;
+#pragma unroll
+            for (int e = 0; e < EPV; ++e)
+                wave_count += __builtin_popcountll(__builtin_amdgcn_ballot_w64(x[e] >= tau));
+            const bool any = wave_count != before;
+            if (any) any_mask |= 1u << j;
+            if (want_full) {
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) {
+                    const float ex = __expf(x[e] - m);
+                    s_full += ex;
+                    s_safe += (x[e] >= tau) ? ex : 0.0f;
                 }
+            } else if (any) {   // wavefront-uniform: all-pruned vectors cost no exp
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) s_safe += (x[e] >= tau) ? __expf(x[e] - m) : 0.0f;
             }
-            const float zy = y_ok ? load_elem(zrow + y) : 0.0f;
-
-            // ---- row maximum (Def. 5.1) ----
-            float m = -INFINITY;
+            if (EXTRAS && bits_row) {
+                const int idx = j * NT + fresh(tid);
+                if (idx == nvec && tail) {   // the slot after the last whole vector carries the ragged end's bits
+                    const T *zrow = (const T *)a.z[side] + row * a.ld[side] + (int64_t)nvec * EPV;
 #pragma unroll
-            for (int j = 0; j < NV; ++j) {
-                float x[EPV];
-                unpack(r[j], x, T());
-#pragma unroll
-                for (int e = 0; e < EPV; ++e) m = fmaxf(m, x[e]);
-            }
-            m = block_max<NT>(m, lds_max);
-#pragma unroll
-            for (int j = 0; j < NV; ++j) keep_packed(r[j]);
-
-            // ---- threshold, membership, size, masked sum (Def. 5.1 / 5.2) ----
-            const float tau = m + log_rho;   // one fp32 rounding
-            RowSums acc = {0.0f, 0.0f, 0};
-#pragma unroll
-            for (int j = 0; j < NV; ++j) {
-                float x[EPV];
-                unpack(r[j], x, T());
+                    for (int e = 0; e < EPV; ++e) x[e] = e < tail ? load_elem(zrow + e) : -INFINITY;
+                }
                 uint32_t mask = 0;
 #pragma unroll
                 for (int e = 0; e < EPV; ++e) mask |= (x[e] >= tau ? 1u : 0u) << e;
-                acc.count += __popc(mask);
-                if (want_full) {
+                mask &= idx < nvec ? ((1u << EPV) - 1u) : (idx == nvec ? (1u << tail) - 1u : 0u);
+                if constexpr (EPV == 8) {
+                    if (idx < 4 * bits_words) bits_row[idx] = (uint8_t)mask;
+                } else {
+                    const uint32_t other = __shfl_xor(mask, 1, kWave);
+                    if (!(idx & 1) && (idx >> 1) < 4 * bits_words)
+                        bits_row[idx >> 1] = (uint8_t)(mask | (other << 4));
+                }
+            }
+            if (refill_in_sums) r[j] = load_slot<T, NT, NVFULL>(znext, j, fresh(tid), nvec);
+        }
+        s_safe = wave_sum(s_safe);
+        if (want_full) s_full = wave_sum(s_full);
+        if ((tid & (kWave - 1)) == 0) {
+            const int w = tid / kWave;
+            lds_f[w] = s_safe;
+            lds_f[NW + w] = s_full;
+            lds_i[w] = wave_count;
+        }
+        __syncthreads();
+        RowSums acc = {lds_f[0], lds_f[NW], lds_i[0]};
 #pragma unroll
-                    for (int e = 0; e < EPV; ++e) {
-                        const float ex = __expf(x[e] - m);
-                        acc.s_full += ex;
-                        acc.s_safe += ((mask >> e) & 1u) ? ex : 0.0f;
-                    }
-                } else if (__any(mask != 0u)) {   // wavefront-uniform: skip the exps of all-pruned vectors
+        for (int w = 1; w < NW; ++w) {   // fixed order: results are run-to-run identical
+            acc.s_safe += lds_f[w];
+            acc.s_full += lds_f[NW + w];
+            acc.count += lds_i[w];
+        }
+        if (tau == -INFINITY) acc.count = V;   // nothing pruned; do not count the -inf padding
+
+        const float log_s = logf(acc.s_safe);
+        const bool y_safe = y_ok && (zy >= tau);
+        if (y_safe) flags |= (side == 0 ? DVP_ROW_Y_IN_TRAIN_SAFE : DVP_ROW_Y_IN_INFER_SAFE);
+        if (tid == 0) {
+            if (out.row_max) out.row_max[row] = m;
+            if (out.lse_safe) out.lse_safe[row] = m + log_s;
+            if (want_full) out.lse_full[row] = m + logf(acc.s_full);
+            if (out.safe_count) out.safe_count[row] = acc.count;
+            if (out.logp)
+                out.logp[row] = !y_ok ? __uint_as_float(0x7fc00000u)
+                                      : (y_safe ? (zy - m) - log_s : -INFINITY);
+            if (side == 0 && a.row_flags) a.row_flags[row] = (uint8_t)flags;
+        }
+
+        // ---- gradient of the training row (Prop. 5.4), straight from the registers.
+        // Dense rows are written here.  In split mode a row with a short safe set
+        // (or a pruned sampled token: all zero) only leaves its (index, value)
+        // pairs at the start of the gradient row; the fill kernel writes the row
+        // afterwards, so this kernel's memory traffic stays (almost) read-only.
+        if (bwd_here) {
+            T *dzrow = (T *)a.dz + row * a.ld_grad;
+            u32x4 *dzvec = (u32x4 *)dzrow;
+            uint2 *list = (uint2 *)dzrow;
+            const bool listed = a.split_grad && !(y_safe && acc.count > a.list_cap);
+            const float neg_g = -g;
+            const int t = fresh(tid);
+            const int64_t y_slot = y_safe ? (y / EPV) : -1;
+            {   // ragged end
+                const int64_t k = (int64_t)nvec * EPV + t;
+                const bool safe = y_safe && t < tail && xt >= tau;
+                float d = 0.0f;
+                if (safe) d = neg_g * __expf((xt - m) - log_s) - (k == y ? neg_g : 0.0f);
+                if (listed) list_append(list, &lds_list_count, safe, (uint32_t)k, d);
+                else if (t < tail) store_elem(dzrow + k, d);
+            }
+#pragma unroll
+            for (int j = 0; j < NV; ++j) {
+                const int idx = j * NT + t;
+                u32x4 o = {0u, 0u, 0u, 0u};
+                if (y_safe && ((any_mask >> j) & 1u)) {   // wavefront-uniform
+                    float x[EPV], d[EPV];
+                    keep_packed(r[j]);
+                    unpack(r[j], x, T());
 #pragma unroll
                     for (int e = 0; e < EPV; ++e)
-                        acc.s_safe += ((mask >> e) & 1u) ? __expf(x[e] - m) : 0.0f;
-                }
-                if (bits_row) {
-                    const int idx = j * NT + fresh(tid);
-                    const uint32_t valid = idx < nvec ? ((1u << EPV) - 1u)
-                                                      : (idx == nvec ? (1u << tail) - 1u : 0u);
-                    mask &= valid;
-                    if constexpr (EPV == 8) {
-                        if (idx < 4 * bits_words) bits_row[idx] = (uint8_t)mask;
+                        d[e] = (x[e] >= tau) ? neg_g * __expf((x[e] - m) - log_s) : 0.0f;
+                    if ((int64_t)idx == y_slot) {          // the sampled token: g * (1 - p)
+                        const int ey = (int)(y - (int64_t)idx * EPV);
+#pragma unroll
+                        for (int e = 0; e < EPV; ++e)
+                            if (e == ey) d[e] -= neg_g;
+                    }
+                    if (listed) {
+#pragma unroll
+                        for (int e = 0; e < EPV; ++e)
+                            list_append(list, &lds_list_count, x[e] >= tau, (uint32_t)(idx * EPV + e), d[e]);
                     } else {
-                        const uint32_t other = __shfl_xor(mask, 1, kWave);
-                        if (!(idx & 1) && (idx >> 1) < 4 * bits_words)
-                            bits_row[idx >> 1] = (uint8_t)(mask | (other << 4));
+                        o = pack_grad(d, T());
                     }
                 }
-            }
-            acc = block_sums<NT>(acc, lds_f, lds_i);
-            if (tau == -INFINITY) acc.count = V;   // nothing pruned; do not count the -inf padding
-
-            const float log_s = logf(acc.s_safe);
-            const bool y_safe = y_ok && (zy >= tau);
-            if (y_safe) flags |= (side == 0 ? DVP_ROW_Y_IN_TRAIN_SAFE : DVP_ROW_Y_IN_INFER_SAFE);
-            if (tid == 0) {
-                if (out.row_max) out.row_max[row] = m;
-                if (out.lse_safe) out.lse_safe[row] = m + log_s;
-                if (out.lse_full) out.lse_full[row] = m + logf(acc.s_full);
-                if (out.safe_count) out.safe_count[row] = acc.count;
-                if (out.logp)
-                    out.logp[row] = !y_ok ? __uint_as_float(0x7fc00000u)
-                                          : (y_safe ? (zy - m) - log_s : -INFINITY);
-            }
-
-            // ---- gradient of the training row (Prop. 5.4), straight from the registers ----
-            if (side == 0 && want_bwd) {
-                T *dzrow = (T *)a.dz + row * a.ld_grad;
-                u32x4 *dzvec = (u32x4 *)dzrow;
-                const float g = a.grad_out[row];
-                const int t = fresh(tid);
-#pragma unroll
-                for (int j = 0; j < NV; ++j) {
-                    keep_packed(r[j]);
-                    const int idx = j * NT + t;
-                    u32x4 o = {0u, 0u, 0u, 0u};
-                    if (y_safe) {
-                        float x[EPV];
-                        unpack(r[j], x, T());
-                        bool any_safe = false;
-#pragma unroll
-                        for (int e = 0; e < EPV; ++e) any_safe |= (x[e] >= tau);
-                        if (__any(any_safe)) {
-                            float d[EPV];
-                            const int64_t k0 = (int64_t)idx * EPV;
-#pragma unroll
-                            for (int e = 0; e < EPV; ++e) {
-                                const float p = __expf((x[e] - m) - log_s);
-                                const float onehot = (k0 + e == y) ? 1.0f : 0.0f;
-                                d[e] = (x[e] >= tau) ? g * (onehot - p) : 0.0f;
-                            }
-                            o = pack(d, T());
-                        }
-                    }
-                    if (j < nfull) {
-                        __builtin_nontemporal_store(o, dzvec + idx);
-                    } else if (idx < nvec) {
-                        __builtin_nontemporal_store(o, dzvec + idx);
-                    } else if (idx == nvec && tail) {   // ragged last vector: element stores
-                        float d[EPV];
-                        unpack(o, d, T());
-                        for (int e = 0; e < tail; ++e) store_elem(dzrow + (int64_t)nvec * EPV + e, d[e]);
-                    }
-                }
+                if (!listed && (j < NVFULL || idx < nvec)) __builtin_nontemporal_store(o, dzvec + idx);
+                if (has_next) r[j] = load_slot<T, NT, NVFULL>(znext, j, t, nvec);
             }
         }
-        if (tid == 0 && a.row_flags) a.row_flags[row] = (uint8_t)flags;
+
+        if (!has_next) break;
+        if (nrow != row) flags = ny_ok ? 0u : (uint32_t)DVP_ROW_ID_OUT_OF_RANGE;
+        row = nrow; side = nside; y = ny; y_ok = ny_ok; g = ng; zy_raw = nzy_raw; xt_raw = nxt_raw;
     }
 }
 
@@ -374,6 +480,48 @@ __global__ __launch_bounds__(NT) void backward_kernel(const BackwardArgs a)
 }
 
 // ---------------------------------------------------------------------------
+// gradient fill: finishes the rows the resident kernel left as lists.  Reads a
+// row's (index, value) pairs, writes the whole row as zeros, then drops the
+// values in place.  Apart from the few list bytes this kernel only writes, so
+// HBM sees one long burst of stores instead of stores mixed into the reads.
+// ---------------------------------------------------------------------------
+template <typename T, int NT>
+__global__ __launch_bounds__(NT) void grad_fill_kernel(const FillArgs a)
+{
+    using TR = elem_traits<T>;
+    constexpr int EPV = TR::kPerVec;
+    __shared__ uint2 lds_list[kListMax];
+    const int tid = threadIdx.x;
+    const int V = a.vocab;
+    const int nvec = V / EPV;
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+
+    for (int64_t row = blockIdx.x; row < a.n_rows; row += gridDim.x) {
+        const bool y_safe = (a.row_flags[row] & DVP_ROW_Y_IN_TRAIN_SAFE) != 0;
+        const int count = a.safe_count[row];
+        if (y_safe && count > a.list_cap) continue;      // dense row: the row kernel wrote it
+        const int len = y_safe ? count : 0;
+        T *dzrow = (T *)a.dz + row * a.ld_grad;
+        const uint2 *list = (const uint2 *)dzrow;
+        for (int i = tid; i < len; i += NT) lds_list[i] = list[i];
+        __syncthreads();                                  // the list is in LDS before the row is overwritten
+        u32x4 *dzvec = (u32x4 *)dzrow;
+        for (int idx = tid; idx < nvec; idx += NT) __builtin_nontemporal_store(zero, dzvec + idx);
+        for (int k = nvec * EPV + tid; k < V; k += NT) store_elem(dzrow + k, 0.0f);
+        if (len > 0) {
+            // the zeros must have reached the L2 before another thread writes a value on top
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            for (int i = tid; i < len; i += NT) {
+                const uint2 e = lds_list[i];
+                store_elem(dzrow + e.x, __uint_as_float(e.y));
+            }
+        }
+        __syncthreads();                                  // LDS is reused by the next row
+    }
+}
+
+// ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
 static int device_cu_count()
@@ -398,46 +546,65 @@ static int blocks_per_cu(Kernel k, int threads)
     return nb;
 }
 
-template <typename T, int NV, int NT, int MINW>
+template <typename T, int NV, int NVFULL, int NT, int MINW, bool EXTRAS>
 static hipError_t launch_resident_inst(const RowArgs &a, hipStream_t stream)
 {
     static int per_cu = 0;
-    if (per_cu == 0) per_cu = blocks_per_cu(rows_resident_kernel<T, NV, NT, MINW>, NT);
+    if (per_cu == 0) per_cu = blocks_per_cu(rows_resident_kernel<T, NV, NVFULL, NT, MINW, EXTRAS>, NT);
     int64_t grid = (int64_t)device_cu_count() * per_cu;
     if (grid > a.n_rows) grid = a.n_rows;
-    hipLaunchKernelGGL((rows_resident_kernel<T, NV, NT, MINW>), dim3((unsigned)grid), dim3(NT), 0, stream, a);
+    hipLaunchKernelGGL((rows_resident_kernel<T, NV, NVFULL, NT, MINW, EXTRAS>), dim3((unsigned)grid),
+                       dim3(NT), 0, stream, a);
     return hipGetLastError();
 }
 
-// vectors per thread the resident kernel is built for: 256-thread groups for
-// short rows (several groups share a CU), 1024-thread groups for long rows
-// (one group owns the CU's register file)
-template <typename T>
+// Register slots per thread the resident kernel is built for: 256-thread
+// groups for short rows (several groups share a CU), 1024-thread groups for
+// long rows (one group owns the CU's register file).  Each build covers row
+// lengths from its NVFULL (exclusive) to its NV (inclusive) slots per thread.
+template <typename T, bool EXTRAS>
 static hipError_t launch_resident_t(const RowArgs &a, hipStream_t stream)
 {
     const int epv = elem_traits<T>::kPerVec;
-    const int64_t slots = ((int64_t)a.vocab + epv - 1) / epv;
-    if (slots <= 256 * 4)   return launch_resident_inst<T, 4, 256, 8>(a, stream);
-    if (slots <= 256 * 8)   return launch_resident_inst<T, 8, 256, 6>(a, stream);
-    if (slots <= 256 * 16)  return launch_resident_inst<T, 16, 256, 4>(a, stream);
-    if (slots <= 1024 * 8)  return launch_resident_inst<T, 8, 1024, 4>(a, stream);
-    if (slots <= 1024 * 12) return launch_resident_inst<T, 12, 1024, 4>(a, stream);
-    if (slots <= 1024 * 16) return launch_resident_inst<T, 16, 1024, 4>(a, stream);
-    if (slots <= 1024 * 19) return launch_resident_inst<T, 19, 1024, 4>(a, stream);
-    if (slots <= 1024 * 20) return launch_resident_inst<T, 20, 1024, 4>(a, stream);
+    const int64_t slots = (int64_t)a.vocab / epv;   // whole vectors; the ragged end lives outside the slots
+    if (slots <= 256 * 4)   return launch_resident_inst<T, 4, 0, 256, 6, EXTRAS>(a, stream);
+    if (slots <= 256 * 8)   return launch_resident_inst<T, 8, 4, 256, 6, EXTRAS>(a, stream);
+    if (slots <= 256 * 16)  return launch_resident_inst<T, 16, 8, 256, 4, EXTRAS>(a, stream);
+    if (slots <= 1024 * 8)  return launch_resident_inst<T, 8, 4, 1024, 5, EXTRAS>(a, stream);
+    if (slots <= 1024 * 12) return launch_resident_inst<T, 12, 8, 1024, 4, EXTRAS>(a, stream);
+    if (slots <= 1024 * 16) return launch_resident_inst<T, 16, 12, 1024, 4, EXTRAS>(a, stream);
+    if (slots <= 1024 * 19) return launch_resident_inst<T, 19, 16, 1024, 4, EXTRAS>(a, stream);
+    if (slots <= 1024 * 20) return launch_resident_inst<T, 20, 19, 1024, 4, EXTRAS>(a, stream);
     return hipErrorInvalidValue;
 }
 
 bool row_fits_resident(int dtype, int64_t vocab)
 {
     const int epv = dtype == DVP_BF16 ? 8 : 4;
-    return (vocab + epv - 1) / epv <= 1024 * 20;
+    return vocab >= epv && vocab / epv <= 1024 * 20;
 }
 
 hipError_t launch_rows_resident(int dtype, const RowArgs &a, hipStream_t stream)
 {
     if (a.n_rows == 0) return hipSuccess;
-    return dtype == DVP_BF16 ? launch_resident_t<bf16_t>(a, stream) : launch_resident_t<float>(a, stream);
+    const bool extras = a.out[0].lse_full || a.out[0].safe_bits ||
+                        (a.n_sides == 2 && (a.out[1].lse_full || a.out[1].safe_bits));
+    if (dtype == DVP_BF16)
+        return extras ? launch_resident_t<bf16_t, true>(a, stream) : launch_resident_t<bf16_t, false>(a, stream);
+    return extras ? launch_resident_t<float, true>(a, stream) : launch_resident_t<float, false>(a, stream);
+}
+
+hipError_t launch_grad_fill(int dtype, const FillArgs &a, hipStream_t stream)
+{
+    if (a.n_rows == 0) return hipSuccess;
+    constexpr int NT = 256;
+    int64_t grid = (int64_t)device_cu_count() * 8;
+    if (grid > a.n_rows) grid = a.n_rows;
+    if (dtype == DVP_BF16)
+        hipLaunchKernelGGL((grad_fill_kernel<bf16_t, NT>), dim3((unsigned)grid), dim3(NT), 0, stream, a);
+    else
+        hipLaunchKernelGGL((grad_fill_kernel<float, NT>), dim3((unsigned)grid), dim3(NT), 0, stream, a);
+    return hipGetLastError();
 }
 
 hipError_t launch_rows_streaming(int dtype, const RowArgs &a, hipStream_t stream)

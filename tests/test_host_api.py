@@ -92,6 +92,8 @@ def test_row_path_selection():
     assert path(81920, 0) == 1 and path(81924, 0) == 0         # and fp32
     assert path(1000, 1, ld=1001) == 0                         # rows not 16-byte aligned
     assert path(1000, 1, aligned=0) == 0
+    assert path(7, 1) == 0 and path(8, 1, ld=8) == 1               # shorter than one vector
+    assert path(3, 0) == 0 and path(4, 0) == 1
     assert path(0, 1) == -1
 
 

@@ -480,44 +480,73 @@ __global__ __launch_bounds__(NT) void backward_kernel(const BackwardArgs a)
 }
 
 // ---------------------------------------------------------------------------
-// gradient fill: finishes the rows the resident kernel left as lists.  Reads a
-// row's (index, value) pairs, writes the whole row as zeros, then drops the
-// values in place.  Apart from the few list bytes this kernel only writes, so
-// HBM sees one long burst of stores instead of stores mixed into the reads.
+// gradient fill: finishes the rows the resident kernel left as lists.
+//   zero kernel     one workgroup per 16 KB chunk of a row, in memory order:
+//                   writes zeros everywhere except over the row's list.  Apart
+//                   from two words per chunk it only writes, so HBM sees one
+//                   long burst of stores instead of stores mixed into reads.
+//   scatter kernel  one workgroup per row: reads the list, zeroes the bytes it
+//                   occupied, drops the values in place.
 // ---------------------------------------------------------------------------
-template <typename T, int NT>
-__global__ __launch_bounds__(NT) void grad_fill_kernel(const FillArgs a)
+constexpr int kFillThreads = 256;
+constexpr int kFillVecPerThread = 4;
+constexpr int kFillChunk = kFillThreads * kFillVecPerThread;   // vectors per workgroup
+
+__device__ __forceinline__ bool row_is_listed(const FillArgs &a, int64_t row, int &len)
+{
+    const bool y_safe = (a.row_flags[row] & DVP_ROW_Y_IN_TRAIN_SAFE) != 0;
+    const int count = a.safe_count[row];
+    len = y_safe ? count : 0;
+    return !(y_safe && count > a.list_cap);     // same test as in the row kernel
+}
+
+template <typename T>
+__global__ __launch_bounds__(kFillThreads) void grad_zero_kernel(const FillArgs a, int chunks_per_row)
 {
     using TR = elem_traits<T>;
     constexpr int EPV = TR::kPerVec;
-    __shared__ uint2 lds_list[kListMax];
-    const int tid = threadIdx.x;
+    const int64_t row = blockIdx.x / chunks_per_row;
+    const int chunk = blockIdx.x - (int)(row * chunks_per_row);
+    int len;
+    if (!row_is_listed(a, row, len)) return;    // dense row: the row kernel wrote it
     const int V = a.vocab;
     const int nvec = V / EPV;
+    const int first = (len * 8 + 15) / 16;      // vectors covered by the list: left to the scatter kernel
+    T *dzrow = (T *)a.dz + row * a.ld_grad;
+    u32x4 *dzvec = (u32x4 *)dzrow;
     const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int u = 0; u < kFillVecPerThread; ++u) {
+        const int idx = chunk * kFillChunk + u * kFillThreads + threadIdx.x;
+        if (idx >= first && idx < nvec) dzvec[idx] = zero;
+    }
+    if (chunk == chunks_per_row - 1) {          // ragged end of the row (a list never reaches the last 16 bytes)
+        const int k = nvec * EPV + threadIdx.x;
+        if (k < V) store_elem(dzrow + k, 0.0f);
+    }
+}
 
-    for (int64_t row = blockIdx.x; row < a.n_rows; row += gridDim.x) {
-        const bool y_safe = (a.row_flags[row] & DVP_ROW_Y_IN_TRAIN_SAFE) != 0;
-        const int count = a.safe_count[row];
-        if (y_safe && count > a.list_cap) continue;      // dense row: the row kernel wrote it
-        const int len = y_safe ? count : 0;
-        T *dzrow = (T *)a.dz + row * a.ld_grad;
-        const uint2 *list = (const uint2 *)dzrow;
-        for (int i = tid; i < len; i += NT) lds_list[i] = list[i];
-        __syncthreads();                                  // the list is in LDS before the row is overwritten
-        u32x4 *dzvec = (u32x4 *)dzrow;
-        for (int idx = tid; idx < nvec; idx += NT) __builtin_nontemporal_store(zero, dzvec + idx);
-        for (int k = nvec * EPV + tid; k < V; k += NT) store_elem(dzrow + k, 0.0f);
-        if (len > 0) {
-            // the zeros must have reached the L2 before another thread writes a value on top
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
-            for (int i = tid; i < len; i += NT) {
-                const uint2 e = lds_list[i];
-                store_elem(dzrow + e.x, __uint_as_float(e.y));
-            }
-        }
-        __syncthreads();                                  // LDS is reused by the next row
+template <typename T>
+__global__ __launch_bounds__(kFillThreads) void grad_scatter_kernel(const FillArgs a)
+{
+    __shared__ uint2 lds_list[kListMax];
+    const int tid = threadIdx.x;
+    const int64_t row = blockIdx.x;
+    int len;
+    if (!row_is_listed(a, row, len) || len == 0) return;
+    T *dzrow = (T *)a.dz + row * a.ld_grad;
+    const uint2 *list = (const uint2 *)dzrow;
+    for (int i = tid; i < len; i += kFillThreads) lds_list[i] = list[i];
+    __syncthreads();                            // the list is in LDS before its bytes are cleared
+    // the whole vectors the list touched (the zero kernel skipped exactly these)
+    const int stop = (len * 8 + 15) / 16 * elem_traits<T>::kPerVec;
+    for (int k = tid; k < stop; k += kFillThreads) store_elem(dzrow + k, 0.0f);
+    // the zeros must have reached the L2 before another thread writes a value on top
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    for (int i = tid; i < len; i += kFillThreads) {
+        const uint2 e = lds_list[i];
+        store_elem(dzrow + e.x, __uint_as_float(e.y));
     }
 }
 
@@ -597,14 +626,28 @@ hipError_t launch_rows_resident(int dtype, const RowArgs &a, hipStream_t stream)
 hipError_t launch_grad_fill(int dtype, const FillArgs &a, hipStream_t stream)
 {
     if (a.n_rows == 0) return hipSuccess;
-    constexpr int NT = 256;
-    int64_t grid = (int64_t)device_cu_count() * 8;
-    if (grid > a.n_rows) grid = a.n_rows;
-    if (dtype == DVP_BF16)
-        hipLaunchKernelGGL((grad_fill_kernel<bf16_t, NT>), dim3((unsigned)grid), dim3(NT), 0, stream, a);
-    else
-        hipLaunchKernelGGL((grad_fill_kernel<float, NT>), dim3((unsigned)grid), dim3(NT), 0, stream, a);
-    return hipGetLastError();
+    const int epv = dtype == DVP_BF16 ? 8 : 4;
+    const int64_t nvec = a.vocab / epv;
+    const int chunks = (int)((nvec + kFillChunk - 1) / kFillChunk > 0 ? (nvec + kFillChunk - 1) / kFillChunk : 1);
+    const int64_t max_rows = 0x7fffffff / chunks;        // one launch covers this many rows
+    for (int64_t r0 = 0; r0 < a.n_rows; r0 += max_rows) {
+        FillArgs b = a;
+        b.n_rows = a.n_rows - r0 < max_rows ? a.n_rows - r0 : max_rows;
+        b.dz = (char *)a.dz + r0 * a.ld_grad * (dtype == DVP_BF16 ? 2 : 4);
+        b.row_flags = a.row_flags + r0;
+        b.safe_count = a.safe_count + r0;
+        const dim3 gz((unsigned)(b.n_rows * chunks)), gs((unsigned)b.n_rows), blk(kFillThreads);
+        if (dtype == DVP_BF16) {
+            hipLaunchKernelGGL((grad_zero_kernel<bf16_t>), gz, blk, 0, stream, b, chunks);
+            hipLaunchKernelGGL((grad_scatter_kernel<bf16_t>), gs, blk, 0, stream, b);
+        } else {
+            hipLaunchKernelGGL((grad_zero_kernel<float>), gz, blk, 0, stream, b, chunks);
+            hipLaunchKernelGGL((grad_scatter_kernel<float>), gs, blk, 0, stream, b);
+        }
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 hipError_t launch_rows_streaming(int dtype, const RowArgs &a, hipStream_t stream)

@@ -156,7 +156,6 @@ __global__ __launch_bounds__(NT, MINW) void rows_resident_kernel(const RowArgs a
         uint8_t *bits_row = (EXTRAS && out.safe_bits)
             ? (uint8_t *)(out.safe_bits + row * (int64_t)bits_words) : nullptr;
         const bool bwd_here = want_bwd && side == 0;
-        const bool refill_in_sums = has_next && !bwd_here;
 
         // ---- row maximum (Def. 5.1) ----
         float m = xt;
@@ -229,7 +228,9 @@ __global__ __launch_bounds__(NT, MINW) void rows_resident_kernel(const RowArgs a
                         bits_row[idx >> 1] = (uint8_t)(mask | (other << 4));
                 }
             }
-            if (refill_in_sums) r[j] = load_slot<T, NT, NVFULL>(znext, j, fresh(tid), nvec);
+            // a slot the gradient phase will not read again (no safe token in this
+            // wavefront's part of it) is refilled right away
+            if (has_next && (!bwd_here || !any)) r[j] = load_slot<T, NT, NVFULL>(znext, j, fresh(tid), nvec);
         }
         s_safe = wave_sum(s_safe);
         if (want_full) s_full = wave_sum(s_full);
@@ -310,7 +311,7 @@ __global__ __launch_bounds__(NT, MINW) void rows_resident_kernel(const RowArgs a
                     }
                 }
                 if (!listed && (j < NVFULL || idx < nvec)) __builtin_nontemporal_store(o, dzvec + idx);
-                if (has_next) r[j] = load_slot<T, NT, NVFULL>(znext, j, t, nvec);
+                if (has_next && ((any_mask >> j) & 1u)) r[j] = load_slot<T, NT, NVFULL>(znext, j, t, nvec);
             }
         }
 
@@ -489,7 +490,7 @@ __global__ __launch_bounds__(NT) void backward_kernel(const BackwardArgs a)
 //                   occupied, drops the values in place.
 // ---------------------------------------------------------------------------
 constexpr int kFillThreads = 256;
-constexpr int kFillVecPerThread = 4;
+constexpr int kFillVecPerThread = 4;   // 16 KB per workgroup amortises the row-info lookup
 constexpr int kFillChunk = kFillThreads * kFillVecPerThread;   // vectors per workgroup
 
 __device__ __forceinline__ bool row_is_listed(const FillArgs &a, int64_t row, int &len)

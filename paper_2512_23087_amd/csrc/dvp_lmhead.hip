@@ -1,15 +1,575 @@
-// Fused LM-head variant (placeholder until the MFMA kernels land).
+// LM-head variant of the DVP hot path for gfx950: the logits z = H W^T are
+// produced tile by tile on the matrix cores (MFMA, bf16 in, fp32 accumulate)
+// and consumed in the tile epilogues; the [N, V] logits are never stored.
+//
+// Membership needs the final row maximum (Def. 5.1), so the logits are
+// produced three times:
+//   pass A  z tiles -> running row max, and z_y where a tile holds column y
+//   pass B  z tiles -> safe-set size and masked sum at tau = fl32(m + log_rho)
+//           (Def. 5.1 / 5.2), per 128-column partials, reduced in fixed order
+//   pass C  (training side, when a gradient is asked for) z tiles -> dz tile
+//           (Prop. 5.4), written per vocabulary chunk as bf16 in both
+//           orientations, then dH += dz W and dW = dz^T H on the same GEMM kernel
+// Every GEMM is C = A B^T with both operands K-major; H and W are transposed
+// once per call so that the two gradient products have that form too.
+#include <math.h>
+
+#include "dvp_device.h"
 #include "dvp_internal.h"
+
+namespace dvp {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int BM = 128, BN = 128, BK = 64;
+constexpr int kGemmThreads = 256;
+constexpr int kLdsStride = BK;                  // bf16 elements per LDS row (128 B); 16-byte chunks are XOR-swizzled by row
+constexpr int kVocabChunk = 8192;               // columns of dz held at a time (pass C)
+
+__device__ __forceinline__ int float_to_ordered(float f)
+{
+    const int b = __float_as_int(f);
+    return b >= 0 ? b : b ^ 0x7fffffff;
+}
+__device__ __forceinline__ float ordered_to_float(int k)
+{
+    return __int_as_float(k >= 0 ? k : k ^ 0x7fffffff);
+}
+
+// per-row quantities of one side, device arrays in the workspace
+struct RowStats {
+    int *max_key;        // [n] ordered-int row maximum (pass A, atomicMax)
+    float *zy;           // [n] logit of the sampled token (pass A)
+    float *m;            // [n] row maximum (after pass A)
+    float *tau;          // [n] threshold
+    float *part_s;       // [col_tiles][n] masked exp sums per 128-column tile (pass B)
+    float *part_f;       // [col_tiles][n] full exp sums, or null
+    int *part_c;         // [col_tiles][n] safe counts per tile
+    float *lse;          // [n] masked log-sum-exp (after pass B)
+    float *coef;         // [n] grad_out where the sampled token is safe, else 0 (pass C)
+};
+
+struct GemmArgs {
+    const uint16_t *A;   // [M, lda] bf16, K-major
+    const uint16_t *B;   // [N, ldb] bf16, K-major
+    int64_t lda, ldb;
+    int M, N, K;         // K a multiple of BK; rows beyond M / N are clamped on load and masked in the epilogue
+    int col_offset;      // global column of this launch's column 0 (vocabulary chunking)
+};
+
+// ---------------------------------------------------------------------------
+// epilogues: called once per wavefront with its 64x64 accumulator block.
+// Element (mi, ni, i) of lane l is row r0 + mi*32 + (i/4)*8 + (l/32)*4 + i%4,
+// column c0 + ni*32 + l%32 of the launch's output.
+// ---------------------------------------------------------------------------
+struct EpiMax {
+    RowStats st;
+    const int64_t *ids;
+    __device__ void operator()(const GemmArgs &g, f32x16 (&acc)[2][2], int r0, int c0, int lane, float *, int) const
+    {
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int row = r0 + mi * 32 + (i / 4) * 8 + (lane / 32) * 4 + (i % 4);
+                const bool row_ok = row < g.M;
+                const int64_t y = row_ok ? ids[row] : -1;
+                float v = -INFINITY;
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni) {
+                    const int col = c0 + ni * 32 + (lane % 32);
+                    const float z = acc[mi][ni][i];
+                    if (col < g.N) {
+                        v = fmaxf(v, z);
+                        if (row_ok && (int64_t)(col + g.col_offset) == y) st.zy[row] = z;
+                    }
+                }
+#pragma unroll
+                for (int off = 16; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+                if ((lane % 32) == 0 && row_ok) atomicMax(st.max_key + row, float_to_ordered(v));
+            }
+        }
+    }
+};
+
+struct EpiSum {
+    RowStats st;
+    int n_rows;
+    // `lds` is the workgroup's scratch (>= 3 * 2 * 128 floats), wn the wavefront's column half
+    __device__ void operator()(const GemmArgs &g, f32x16 (&acc)[2][2], int r0, int c0, int lane, float *lds, int wn) const
+    {
+        const bool want_full = st.part_f != nullptr;
+        float *ls = lds, *lf = lds + 2 * BM;
+        int *lc = (int *)(lds + 4 * BM);
+        const int tile_row0 = r0 - (r0 % BM);
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int row = r0 + mi * 32 + (i / 4) * 8 + (lane / 32) * 4 + (i % 4);
+                const bool row_ok = row < g.M;
+                const float m = row_ok ? st.m[row] : 0.0f;
+                const float tau = row_ok ? st.tau[row] : INFINITY;
+                float s = 0.0f, f = 0.0f;
+                int c = 0;
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni) {
+                    const int col = c0 + ni * 32 + (lane % 32);
+                    const float z = acc[mi][ni][i];
+                    if (col < g.N && row_ok) {
+                        const bool safe = z >= tau;
+                        c += safe ? 1 : 0;
+                        if (want_full) {
+                            const float e = __expf(z - m);
+                            f += e;
+                            s += safe ? e : 0.0f;
+                        } else if (safe) {
+                            s += __expf(z - m);
+                        }
+                    }
+                }
+#pragma unroll
+                for (int off = 16; off > 0; off >>= 1) {
+                    s += __shfl_xor(s, off, kWave);
+                    f += __shfl_xor(f, off, kWave);
+                    c += __shfl_xor(c, off, kWave);
+                }
+                if ((lane % 32) == 0) {
+                    const int lr = row - tile_row0;           // 0..127
+                    ls[wn * BM + lr] = s;
+                    lf[wn * BM + lr] = f;
+                    lc[wn * BM + lr] = c;
+                }
+            }
+        }
+    }
+    // after a barrier: 128 threads combine the two column halves in fixed order
+    __device__ void finish(const GemmArgs &g, int tile_row0, int tile_col, float *lds, int tid) const
+    {
+        if (tid >= BM) return;
+        const int row = tile_row0 + tid;
+        if (row >= g.M) return;
+        const float *ls = lds, *lf = lds + 2 * BM;
+        const int *lc = (const int *)(lds + 4 * BM);
+        const int64_t o = (int64_t)tile_col * n_rows + row;
+        st.part_s[o] = ls[tid] + ls[BM + tid];
+        st.part_c[o] = lc[tid] + lc[BM + tid];
+        if (st.part_f) st.part_f[o] = lf[tid] + lf[BM + tid];
+    }
+};
+
+struct EpiGrad {
+    RowStats st;
+    const int64_t *ids;
+    uint16_t *dz;        // [Mpad, ld_dz] bf16: rows = token rows, columns = chunk columns
+    uint16_t *dzt;       // [chunk columns (padded), ld_dzt] bf16: the transpose
+    int64_t ld_dz, ld_dzt;
+    __device__ void operator()(const GemmArgs &g, f32x16 (&acc)[2][2], int r0, int c0, int lane, float *, int) const
+    {
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi) {
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni) {
+                const int col = c0 + ni * 32 + (lane % 32);          // column inside the chunk
+                const bool col_ok = col < g.N;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    uint32_t packed[2] = {0u, 0u};
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int i = q * 4 + r;
+                        const int row = r0 + mi * 32 + q * 8 + (lane / 32) * 4 + r;
+                        float d = 0.0f;
+                        if (row < g.M && col_ok) {
+                            const float coef = st.coef[row];
+                            const float z = acc[mi][ni][i];
+                            if (coef != 0.0f && z >= st.tau[row]) {
+                                const float p = __expf((z - st.m[row]) - (st.lse[row] - st.m[row]));
+                                const float onehot = ((int64_t)(col + g.col_offset) == ids[row]) ? 1.0f : 0.0f;
+                                d = coef * (onehot - p);
+                            }
+                        }
+                        const uint32_t b = f32_to_bf16_rne(d);
+                        // rows beyond M and columns beyond N are written as zeros: they pad
+                        // the K dimension of the two gradient products
+                        dz[(int64_t)row * ld_dz + col] = (uint16_t)b;
+                        packed[r >> 1] |= b << (16 * (r & 1));
+                    }
+                    const int row4 = r0 + mi * 32 + q * 8 + (lane / 32) * 4;
+                    *(uint2 *)(dzt + (int64_t)col * ld_dzt + row4) = make_uint2(packed[0], packed[1]);
+                }
+            }
+        }
+    }
+};
+
+struct EpiStore {
+    float *C;            // [M, ldc] fp32
+    int64_t ldc;
+    int accumulate;      // 0: C = acc, 1: C += acc
+    __device__ void operator()(const GemmArgs &g, f32x16 (&acc)[2][2], int r0, int c0, int lane, float *, int) const
+    {
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int row = r0 + mi * 32 + (i / 4) * 8 + (lane / 32) * 4 + (i % 4);
+                if (row >= g.M) continue;
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni) {
+                    const int col = c0 + ni * 32 + (lane % 32);
+                    if (col >= g.N) continue;
+                    float *p = C + (int64_t)row * ldc + col;
+                    *p = accumulate ? *p + acc[mi][ni][i] : acc[mi][ni][i];
+                }
+            }
+        }
+    }
+};
+
+// ---------------------------------------------------------------------------
+// C = A B^T on MFMA: 128x128 tile per workgroup, 4 wavefronts as 2x2, each a
+// 64x64 block of four 32x32 accumulators; K in steps of 64 through a double
+// buffered LDS tile (global -> registers -> LDS, one barrier per step).
+// ---------------------------------------------------------------------------
+template <class Epi, bool NEEDS_FINISH>
+__global__ __launch_bounds__(kGemmThreads, 2) void gemm_nt_kernel(const GemmArgs g, const Epi epi, int tiles_m, int tiles_n)
+{
+    __shared__ __attribute__((aligned(16))) uint16_t lds[2][2][BM * kLdsStride];
+
+    // tile order: groups of 8 row tiles sweep the column tiles together so that
+    // concurrently resident workgroups reuse the same B tiles from the L2
+    constexpr int GROUP = 8;
+    const int pid = blockIdx.x;
+    const int per_group = GROUP * tiles_n;
+    const int group = pid / per_group;
+    const int first_m = group * GROUP;
+    const int group_rows = (tiles_m - first_m) < GROUP ? (tiles_m - first_m) : GROUP;
+    const int in_group = pid - group * per_group;
+    const int tile_m = first_m + in_group % group_rows;
+    const int tile_n = in_group / group_rows;
+
+    const int tid = threadIdx.x;
+    const int wave = tid / kWave, lane = tid % kWave;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    // global -> LDS mapping: a 128x64 bf16 tile is 1024 chunks of 16 B; thread t moves chunks t, t+256, ...
+    const u32x4 *gA[4], *gB[4];
+    int lds_off[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int c = tid + i * kGemmThreads;
+        const int row = c >> 3, kc = c & 7;
+        int ra = tile_m * BM + row; if (ra >= g.M) ra = g.M - 1;
+        int rb = tile_n * BN + row; if (rb >= g.N) rb = g.N - 1;
+        gA[i] = (const u32x4 *)(g.A + (int64_t)ra * g.lda + kc * 8);
+        gB[i] = (const u32x4 *)(g.B + (int64_t)rb * g.ldb + kc * 8);
+        lds_off[i] = row * kLdsStride + ((kc ^ (row & 7)) * 8);
+    }
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.0f;
+
+    u32x4 ra[4], rb[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { ra[i] = gA[i][0]; rb[i] = gB[i][0]; }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        *(u32x4 *)(&lds[0][0][lds_off[i]]) = ra[i];
+        *(u32x4 *)(&lds[0][1][lds_off[i]]) = rb[i];
+    }
+    __syncthreads();
+
+    const int nk = g.K / BK;
+    // operand fetch: lane l reads row (l % 32), the 8 consecutive k of chunk 2 * ks + l / 32.
+    // Rows 32 apart share (row & 7), so one swizzle key serves both row blocks.
+    const int a_row = (wm * 64 + (lane % 32)) * kLdsStride;
+    const int b_row = (wn * 64 + (lane % 32)) * kLdsStride;
+    const int key = lane & 7, half = lane / 32;
+
+    for (int kt = 0; kt < nk; ++kt) {
+        const int s = kt & 1;
+        if (kt + 1 < nk) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {   // 16-byte vectors: (kt + 1) * 64 bf16 = (kt + 1) * 8 vectors
+                ra[i] = gA[i][(kt + 1) * (BK / 8)];
+                rb[i] = gB[i][(kt + 1) * (BK / 8)];
+            }
+        }
+        const uint16_t *la = lds[s][0], *lb = lds[s][1];
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            bf16x8 a[2], b[2];
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+                a[mi] = *(const bf16x8 *)(la + a_row + mi * 32 * kLdsStride + (((ks * 2 + half) ^ key) * 8));
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+                b[ni] = *(const bf16x8 *)(lb + b_row + ni * 32 * kLdsStride + (((ks * 2 + half) ^ key) * 8));
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
+        }
+        if (kt + 1 < nk) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                *(u32x4 *)(&lds[s ^ 1][0][lds_off[i]]) = ra[i];
+                *(u32x4 *)(&lds[s ^ 1][1][lds_off[i]]) = rb[i];
+            }
+        }
+        __syncthreads();
+    }
+
+    float *scratch = (float *)&lds[0][0][0];     // the operand tiles are dead: reuse as epilogue scratch
+    epi(g, acc, tile_m * BM + wm * 64, tile_n * BN + wn * 64, lane, scratch, wn);
+    if constexpr (NEEDS_FINISH) {
+        __syncthreads();
+        epi.finish(g, tile_m * BM, tile_n + g.col_offset / BN, scratch, tid);
+    }
+}
+
+template <class Epi, bool NEEDS_FINISH>
+static hipError_t launch_gemm(const GemmArgs &g, const Epi &epi, hipStream_t stream)
+{
+    const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+    hipLaunchKernelGGL((gemm_nt_kernel<Epi, NEEDS_FINISH>), dim3((unsigned)(tiles_m * tiles_n)),
+                       dim3(kGemmThreads), 0, stream, g, epi, tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// small helper kernels
+// ---------------------------------------------------------------------------
+__global__ void init_stats_kernel(RowStats st, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) { st.max_key[i] = (int)0x80000000; st.zy[i] = 0.0f; }
+}
+
+__global__ void after_max_kernel(RowStats st, int n, float log_rho)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) {
+        const float m = ordered_to_float(st.max_key[i]);
+        st.m[i] = m;
+        st.tau[i] = m + log_rho;                  // one fp32 rounding
+    }
+}
+
+// reduce the per-tile partials in tile order and write the side's outputs
+__global__ void after_sum_kernel(RowStats st, SideOut out, const int64_t *ids, const float *grad_out,
+                                 uint8_t *row_flags, int n, int vocab, int col_tiles, int side)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    float s = 0.0f, f = 0.0f;
+    int c = 0;
+    for (int t = 0; t < col_tiles; ++t) {
+        const int64_t o = (int64_t)t * n + i;
+        s += st.part_s[o];
+        c += st.part_c[o];
+        if (st.part_f) f += st.part_f[o];
+    }
+    const float m = st.m[i], tau = st.tau[i];
+    const float log_s = logf(s);
+    const int64_t y = ids[i];
+    const bool y_ok = y >= 0 && y < (int64_t)vocab;
+    const float zy = st.zy[i];
+    const bool y_safe = y_ok && zy >= tau;
+    st.lse[i] = m + log_s;
+    if (side == 0) st.coef[i] = (grad_out && y_safe) ? grad_out[i] : 0.0f;
+    if (out.row_max) out.row_max[i] = m;
+    if (out.lse_safe) out.lse_safe[i] = m + log_s;
+    if (out.lse_full) out.lse_full[i] = m + logf(f);
+    if (out.safe_count) out.safe_count[i] = c;
+    if (out.logp)
+        out.logp[i] = !y_ok ? __uint_as_float(0x7fc00000u) : (y_safe ? (zy - m) - log_s : -INFINITY);
+    if (row_flags) {
+        uint32_t fl = side == 0 ? (y_ok ? 0u : (uint32_t)DVP_ROW_ID_OUT_OF_RANGE) : row_flags[i];
+        if (y_safe) fl |= side == 0 ? DVP_ROW_Y_IN_TRAIN_SAFE : DVP_ROW_Y_IN_INFER_SAFE;
+        row_flags[i] = (uint8_t)fl;
+    }
+}
+
+// out[c, r] = in[r, c] for r < rows, c < cols; out rows are ld_out long and zero padded up to rows_pad
+__global__ void transpose_bf16_kernel(const uint16_t *in, int64_t ld_in, uint16_t *out, int64_t ld_out,
+                                      int rows, int cols, int rows_pad)
+{
+    __shared__ uint16_t tile[32][33];
+    const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
+    const int tx = threadIdx.x, ty = threadIdx.y;     // 32 x 8
+    for (int k = ty; k < 32; k += 8) {
+        const int r = r0 + k, c = c0 + tx;
+        tile[k][tx] = (r < rows && c < cols) ? in[(int64_t)r * ld_in + c] : (uint16_t)0;
+    }
+    __syncthreads();
+    for (int k = ty; k < 32; k += 8) {
+        const int c = c0 + k, r = r0 + tx;
+        if (c < cols && r < rows_pad) out[(int64_t)c * ld_out + r] = tile[tx][k];
+    }
+}
+
+// ---------------------------------------------------------------------------
+// workspace layout
+// ---------------------------------------------------------------------------
+static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct LmLayout {
+    size_t total;
+    size_t off_i32[2], off_zy[2], off_m[2], off_tau[2], off_lse[2], off_coef;
+    size_t off_ps[2], off_pf[2], off_pc[2];
+    size_t off_ht, off_wt, off_dz, off_dzt;
+    int n_pad, v_pad, col_tiles;
+};
+
+static LmLayout lm_layout(int64_t n, int64_t d, int64_t v)
+{
+    LmLayout L;
+    L.n_pad = (int)((n + BM - 1) / BM * BM);
+    L.v_pad = (int)((v + BN - 1) / BN * BN);
+    L.col_tiles = L.v_pad / BN;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o += align256(bytes); return at; };
+    for (int s = 0; s < 2; ++s) {
+        L.off_i32[s] = take(n * 4); L.off_zy[s] = take(n * 4); L.off_m[s] = take(n * 4);
+        L.off_tau[s] = take(n * 4); L.off_lse[s] = take(n * 4);
+        L.off_ps[s] = take((size_t)L.col_tiles * n * 4);
+        L.off_pf[s] = take((size_t)L.col_tiles * n * 4);
+        L.off_pc[s] = take((size_t)L.col_tiles * n * 4);
+    }
+    L.off_coef = take(n * 4);
+    L.off_ht = take((size_t)d * L.n_pad * 2);
+    L.off_wt = take((size_t)d * L.v_pad * 2);
+    L.off_dz = take((size_t)L.n_pad * kVocabChunk * 2);
+    L.off_dzt = take((size_t)kVocabChunk * L.n_pad * 2);
+    L.total = o;
+    return L;
+}
+
+static bool lm_params_ok(const dvp_lmhead_params *p)
+{
+    if (!p) return false;
+    if (p->n_rows < 0 || p->vocab < 1 || p->hidden < BK) return false;
+    if (p->hidden % BK || p->ld_hidden < p->hidden || p->ld_w < p->hidden) return false;
+    if (p->ld_hidden % 8 || p->ld_w % 8) return false;
+    if (p->n_rows > (1 << 30) || p->vocab > (1 << 30) || p->hidden > (1 << 20)) return false;
+    if (p->log_rho != p->log_rho || p->log_rho > 0.0f) return false;
+    return true;
+}
+
+}  // namespace dvp
 
 extern "C" {
 
-size_t dvp_fused_lmhead_workspace_bytes(const dvp_lmhead_params *) { return 0; }
-
-dvp_status dvp_fused_lmhead(const dvp_lmhead_params *, const void *, const void *, const void *,
-                            const int64_t *, const float *, const dvp_side_out *,
-                            const dvp_side_out *, uint8_t *, float *, float *, void *, size_t, void *)
+size_t dvp_fused_lmhead_workspace_bytes(const dvp_lmhead_params *p)
 {
-    return DVP_ERR_UNSUPPORTED;
+    if (!dvp::lm_params_ok(p)) return 0;
+    return dvp::lm_layout(p->n_rows, p->hidden, p->vocab).total;
 }
 
+dvp_status dvp_fused_lmhead(const dvp_lmhead_params *p, const void *hidden, const void *w_train,
+                            const void *w_infer, const int64_t *ids, const float *grad_out,
+                            const dvp_side_out *out_train, const dvp_side_out *out_infer,
+                            uint8_t *row_flags, float *d_hidden, float *d_w, void *workspace,
+                            size_t workspace_bytes, void *stream_)
+{
+    using namespace dvp;
+    if (!p) return DVP_ERR_NULL;
+    if (p->log_rho != p->log_rho || p->log_rho > 0.0f) return DVP_ERR_PARAM;
+    if (p->n_rows < 0 || p->vocab < 1 || p->hidden < 1 || p->ld_hidden < p->hidden || p->ld_w < p->hidden)
+        return DVP_ERR_SHAPE;
+    if (!lm_params_ok(p)) return DVP_ERR_UNSUPPORTED;
+    if (p->n_rows == 0) return DVP_OK;
+    if (!hidden || !w_train || !ids || !out_train) return DVP_ERR_NULL;
+    if (grad_out && (!d_hidden || !d_w)) return DVP_ERR_NULL;
+    if ((out_train && out_train->safe_bits) || (w_infer && out_infer && out_infer->safe_bits))
+        return DVP_ERR_UNSUPPORTED;
+    if (((uintptr_t)hidden | (uintptr_t)w_train | (uintptr_t)w_infer) % 16) return DVP_ERR_ALIGN;
+    const LmLayout L = lm_layout(p->n_rows, p->hidden, p->vocab);
+    if (!workspace || ((uintptr_t)workspace % 256) || workspace_bytes < L.total) return DVP_ERR_WORKSPACE;
+
+    hipStream_t stream = (hipStream_t)stream_;
+    const int n = (int)p->n_rows, d = (int)p->hidden, v = (int)p->vocab;
+    char *ws = (char *)workspace;
+    const void *w_side[2] = {w_train, w_infer};
+    const int n_sides = w_infer ? 2 : 1;
+    SideOut outs[2];
+    for (int s = 0; s < 2; ++s) {
+        const dvp_side_out *o = s == 0 ? out_train : (w_infer ? out_infer : nullptr);
+        outs[s] = SideOut{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+        if (o) outs[s] = SideOut{o->logp, o->row_max, o->lse_safe, o->lse_full, o->safe_count, nullptr};
+    }
+    RowStats st[2];
+    for (int s = 0; s < 2; ++s) {
+        st[s].max_key = (int *)(ws + L.off_i32[s]); st[s].zy = (float *)(ws + L.off_zy[s]);
+        st[s].m = (float *)(ws + L.off_m[s]); st[s].tau = (float *)(ws + L.off_tau[s]);
+        st[s].lse = (float *)(ws + L.off_lse[s]); st[s].coef = (float *)(ws + L.off_coef);
+        st[s].part_s = (float *)(ws + L.off_ps[s]); st[s].part_c = (int *)(ws + L.off_pc[s]);
+        st[s].part_f = outs[s].lse_full ? (float *)(ws + L.off_pf[s]) : nullptr;
+    }
+    const int tb = 256, nb = (n + tb - 1) / tb;
+    hipError_t e = hipSuccess;
+#define DVP_CHECK_LAUNCH() do { e = hipGetLastError(); if (e != hipSuccess) return DVP_ERR_HIP; } while (0)
+
+    // pass A and pass B for each side
+    for (int s = 0; s < n_sides; ++s) {
+        GemmArgs g;
+        g.A = (const uint16_t *)hidden; g.lda = p->ld_hidden;
+        g.B = (const uint16_t *)w_side[s]; g.ldb = p->ld_w;
+        g.M = n; g.N = v; g.K = d; g.col_offset = 0;
+        hipLaunchKernelGGL(init_stats_kernel, dim3(nb), dim3(tb), 0, stream, st[s], n);
+        DVP_CHECK_LAUNCH();
+        if (launch_gemm<EpiMax, false>(g, EpiMax{st[s], ids}, stream) != hipSuccess) return DVP_ERR_HIP;
+        hipLaunchKernelGGL(after_max_kernel, dim3(nb), dim3(tb), 0, stream, st[s], n, p->log_rho);
+        DVP_CHECK_LAUNCH();
+        if (launch_gemm<EpiSum, true>(g, EpiSum{st[s], n}, stream) != hipSuccess) return DVP_ERR_HIP;
+        hipLaunchKernelGGL(after_sum_kernel, dim3(nb), dim3(tb), 0, stream, st[s], outs[s], ids, grad_out,
+                           row_flags, n, v, L.col_tiles, s);
+        DVP_CHECK_LAUNCH();
+    }
+    if (!grad_out) return DVP_OK;
+
+    // pass C: gradient through the training head
+    uint16_t *ht = (uint16_t *)(ws + L.off_ht), *wt = (uint16_t *)(ws + L.off_wt);
+    uint16_t *dz = (uint16_t *)(ws + L.off_dz), *dzt = (uint16_t *)(ws + L.off_dzt);
+    hipLaunchKernelGGL(transpose_bf16_kernel, dim3((d + 31) / 32, (L.n_pad + 31) / 32), dim3(32, 8), 0, stream,
+                       (const uint16_t *)hidden, p->ld_hidden, ht, (int64_t)L.n_pad, n, d, L.n_pad);
+    DVP_CHECK_LAUNCH();
+    hipLaunchKernelGGL(transpose_bf16_kernel, dim3((d + 31) / 32, (L.v_pad + 31) / 32), dim3(32, 8), 0, stream,
+                       (const uint16_t *)w_train, p->ld_w, wt, (int64_t)L.v_pad, v, d, L.v_pad);
+    DVP_CHECK_LAUNCH();
+    for (int c0 = 0, chunk = 0; c0 < v; c0 += kVocabChunk, ++chunk) {
+        const int vc = (v - c0) < kVocabChunk ? (v - c0) : kVocabChunk;
+        const int vc_pad = (vc + BN - 1) / BN * BN;
+        GemmArgs g;
+        g.A = (const uint16_t *)hidden; g.lda = p->ld_hidden;
+        g.B = (const uint16_t *)w_train + (int64_t)c0 * p->ld_w; g.ldb = p->ld_w;
+        g.M = n; g.N = vc; g.K = d; g.col_offset = c0;
+        EpiGrad eg{st[0], ids, dz, dzt, (int64_t)kVocabChunk, (int64_t)L.n_pad};
+        if (launch_gemm<EpiGrad, false>(g, eg, stream) != hipSuccess) return DVP_ERR_HIP;
+        // dH (+)= dz_chunk [n, vc_pad] . (W^T[:, c0 : c0 + vc_pad])^T
+        GemmArgs gh;
+        gh.A = dz; gh.lda = kVocabChunk; gh.B = wt + c0; gh.ldb = L.v_pad;
+        gh.M = n; gh.N = d; gh.K = vc_pad; gh.col_offset = 0;
+        if (launch_gemm<EpiStore, false>(gh, EpiStore{d_hidden, p->ld_hidden, chunk > 0}, stream) != hipSuccess)
+            return DVP_ERR_HIP;
+        // dW[c0 : c0 + vc, :] = dz_chunk^T [vc, n_pad] . (H^T)^T
+        GemmArgs gw;
+        gw.A = dzt; gw.lda = L.n_pad; gw.B = ht; gw.ldb = L.n_pad;
+        gw.M = vc; gw.N = d; gw.K = L.n_pad; gw.col_offset = 0;
+        if (launch_gemm<EpiStore, false>(gw, EpiStore{d_w + (int64_t)c0 * p->ld_w, p->ld_w, 0}, stream) != hipSuccess)
+            return DVP_ERR_HIP;
+    }
+#undef DVP_CHECK_LAUNCH
+    return DVP_OK;
 }
+
+}  // extern "C"

@@ -92,12 +92,56 @@ def time_launches(fn, steps, warmup):
     return wall, per_launch_ms
 
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 matrix peak
+
+
+def bench_lmhead(args):
+    """configs[4]: the LM-head variant (logits never stored).  One step = one
+    dvp_fused_lmhead call: both sides' forward and the training side's dH, dW."""
+    import torch
+    from paper_2512_23087_amd import dvp, workloads
+    wl = workloads.make_lmhead(device="cuda:0", n=args.rows)
+    n, d = wl.hidden.shape
+    v = wl.w_train.shape[0]
+    lr = dvp.log_rho(args.rho)
+    ws = torch.empty(dvp.lmhead_workspace_bytes(n, d, v), dtype=torch.uint8, device="cuda:0")
+    dh = torch.empty(n, d, dtype=torch.float32, device="cuda:0")
+    dw = torch.empty(v, d, dtype=torch.float32, device="cuda:0")
+
+    def step():
+        dvp.dvp_fused_lmhead(wl.hidden, wl.w_train, wl.w_infer, wl.ids, wl.grad_out, lr,
+                             workspace=ws, d_hidden=dh, d_w=dw)
+
+    steps = min(args.steps, 5)
+    wall, per_launch = time_launches(step, steps, min(args.warmup, 2))
+    ms = sum(per_launch) / len(per_launch)
+    gemm = 2.0 * n * v * d
+    useful, executed = 4 * gemm, 7 * gemm          # train fwd, infer fwd, dH, dW; vs the passes actually run
+    result = {
+        "metric": "DVP fused LM-head fwd+bwd rows/s and MFMA TFLOP/s, V=%d bf16" % v,
+        "value": n * steps / wall, "unit": "rows/s", "n_gpus": 1, "steps": steps,
+        "warmup": min(args.warmup, 2), "ms_per_step": wall * 1e3 / steps, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "configs[4]: hidden [%d, %d] bf16 x W [%d, %d] bf16 (train) and its "
+                               "fp8-e4m3-rounded copy (infer), rho=%g" % (n, d, v, d, args.rho),
+                   "entry_point": "dvp_fused_lmhead", "workspace_bytes": ws.numel()},
+        "roofline": {"bound": "mfma", "achieved": executed / (ms * 1e-3) / 1e12,
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": executed / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "kernel": "gemm_nt_kernel (7 GEMM passes of 2*N*V*d flop each per call)",
+                     "kernel_ms_avg": ms, "executed_tflop": executed / 1e12,
+                     "useful_tflop": useful / 1e12,
+                     "useful_tflops": useful / (ms * 1e-3) / 1e12},
+    }
+    print(json.dumps(result))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3"])
+    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "lmhead"])
     ap.add_argument("--rho", type=float, default=1e-4)
     ap.add_argument("--rows", type=int, default=None, help="override N (for quick runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -119,6 +163,8 @@ def main():
         sys.exit(2)
     dvp.lib()
     torch.cuda.set_device(0)
+    if args.workload == "lmhead":
+        return bench_lmhead(args)
     cfg = int(args.workload[-1])
     t_gen = time.perf_counter()
     wl = workloads.make_rows(cfg, device="cuda:0", n=args.rows)

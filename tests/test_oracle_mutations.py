@@ -1,0 +1,39 @@
+"""The pins must be able to see a mistake: plant plausible errors in a copy of
+the oracle's C source (CPU only) and check that the pin suite fails on each."""
+import os
+import subprocess
+import sys
+from pathlib import Path
+
+import pytest
+
+ROOT = Path(__file__).resolve().parents[1]
+SRC = ROOT / "oracle" / "dvp_oracle.c"
+
+MUTATIONS = {
+    "exclusive_boundary": ("int s = zrow[k] >= tau;", "int s = zrow[k] > tau;"),
+    "gradient_sign": ("(k == y ? 1.0 : 0.0) - p", "p - (k == y ? 1.0 : 0.0)"),
+    "unmasked_sum": ("if (zrow[k] >= tau) nsum_add(&S_safe, e);", "nsum_add(&S_safe, e);"),
+    "unrounded_threshold": ("const double tau = (double)(float)tau_ideal;", "const double tau = tau_ideal;"),
+    "full_normaliser": ("logp = zrow[y] - lse_safe;", "logp = zrow[y] - lse_full;"),
+    "gradient_on_pruned_token_rows": ("if (y_safe && zrow[k] >= tau) {", "if (zrow[k] >= tau) {"),
+    "gradient_scale_dropped": ("d[k] = g * (", "d[k] = ("),
+    "threshold_sign": ("const double tau_ideal = m + (double)J->log_rho;",
+                       "const double tau_ideal = m - (double)J->log_rho;"),
+    "onehot_index": ("(k == y ? 1.0 : 0.0)", "(k == y + 1 ? 1.0 : 0.0)"),
+}
+
+
+@pytest.mark.parametrize("name", sorted(MUTATIONS))
+def test_planted_mistake_is_caught(name, tmp_path):
+    old, new = MUTATIONS[name]
+    text = SRC.read_text()
+    assert text.count(old) >= 1, "mutation site not found: " + name
+    mutated = tmp_path / ("oracle_%s.c" % name)
+    mutated.write_text(text.replace(old, new, 1))
+    env = dict(os.environ, DVP_ORACLE_SRC=str(mutated))
+    r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
+                        str(ROOT / "tests" / "test_oracle_pins.py")],
+                       cwd=str(ROOT), env=env, capture_output=True, text=True, timeout=300)
+    assert r.returncode != 0, "the pins did not notice: " + name
+    assert "failed" in r.stdout

@@ -489,9 +489,10 @@ __global__ __launch_bounds__(NT) void backward_kernel(const BackwardArgs a)
 //   scatter kernel  one workgroup per row: reads the list, zeroes the bytes it
 //                   occupied, drops the values in place.
 // ---------------------------------------------------------------------------
-constexpr int kFillThreads = 256;
-constexpr int kFillVecPerThread = 4;   // 16 KB per workgroup amortises the row-info lookup
-constexpr int kFillChunk = kFillThreads * kFillVecPerThread;   // vectors per workgroup
+constexpr int kZeroThreads = 1024;     // measured best among 64..1024 threads x 1..16 stores per thread
+constexpr int kFillVecPerThread = 2;   // 32 KB per workgroup amortises the row-info lookup
+constexpr int kFillChunk = kZeroThreads * kFillVecPerThread;   // vectors per workgroup
+constexpr int kFillThreads = 256;      // scatter kernel
 
 __device__ __forceinline__ bool row_is_listed(const FillArgs &a, int64_t row, int &len)
 {
@@ -502,7 +503,7 @@ __device__ __forceinline__ bool row_is_listed(const FillArgs &a, int64_t row, in
 }
 
 template <typename T>
-__global__ __launch_bounds__(kFillThreads) void grad_zero_kernel(const FillArgs a, int chunks_per_row)
+__global__ __launch_bounds__(kZeroThreads) void grad_zero_kernel(const FillArgs a, int chunks_per_row)
 {
     using TR = elem_traits<T>;
     constexpr int EPV = TR::kPerVec;
@@ -518,7 +519,7 @@ __global__ __launch_bounds__(kFillThreads) void grad_zero_kernel(const FillArgs 
     const u32x4 zero = {0u, 0u, 0u, 0u};
 #pragma unroll
     for (int u = 0; u < kFillVecPerThread; ++u) {
-        const int idx = chunk * kFillChunk + u * kFillThreads + threadIdx.x;
+        const int idx = chunk * kFillChunk + u * kZeroThreads + threadIdx.x;
         if (idx >= first && idx < nvec) dzvec[idx] = zero;
     }
     if (chunk == chunks_per_row - 1) {          // ragged end of the row (a list never reaches the last 16 bytes)
@@ -637,12 +638,13 @@ hipError_t launch_grad_fill(int dtype, const FillArgs &a, hipStream_t stream)
         b.dz = (char *)a.dz + r0 * a.ld_grad * (dtype == DVP_BF16 ? 2 : 4);
         b.row_flags = a.row_flags + r0;
         b.safe_count = a.safe_count + r0;
-        const dim3 gz((unsigned)(b.n_rows * chunks)), gs((unsigned)b.n_rows), blk(kFillThreads);
+        const dim3 gz((unsigned)(b.n_rows * chunks)), gs((unsigned)b.n_rows);
+        const dim3 bz(kZeroThreads), blk(kFillThreads);
         if (dtype == DVP_BF16) {
-            hipLaunchKernelGGL((grad_zero_kernel<bf16_t>), gz, blk, 0, stream, b, chunks);
+            hipLaunchKernelGGL((grad_zero_kernel<bf16_t>), gz, bz, 0, stream, b, chunks);
             hipLaunchKernelGGL((grad_scatter_kernel<bf16_t>), gs, blk, 0, stream, b);
         } else {
-            hipLaunchKernelGGL((grad_zero_kernel<float>), gz, blk, 0, stream, b, chunks);
+            hipLaunchKernelGGL((grad_zero_kernel<float>), gz, bz, 0, stream, b, chunks);
             hipLaunchKernelGGL((grad_scatter_kernel<float>), gs, blk, 0, stream, b);
         }
         hipError_t e = hipGetLastError();

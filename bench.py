@@ -26,7 +26,9 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # same counters' reading on a plain copy kernel of known size.  Only valid for the kernel
 # source it was measured on: keyed by the sha256 of the kernel sources.
 MEASURED_TRAFFIC = {
-    # "sha256 of csrc/dvp_rows.hip + csrc/dvp_device.h": {"cfg3": bytes_per_launch, ...}
+    # sha256 of csrc/dvp_rows.hip + csrc/dvp_device.h -> HBM bytes per launch; see
+    # profiles/rows_cfg3_hbm_traffic.md for the counter values and scale factors
+    "5c3b50e3962b52639f35e9e93ac26edeed27aaa32da3387f6bf6874150c3990f": {"cfg3": 29896408000},
 }
 
 

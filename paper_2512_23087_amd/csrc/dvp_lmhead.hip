@@ -22,9 +22,12 @@ namespace dvp {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int BM = 128, BN = 128, BK = 64;
-constexpr int kGemmThreads = 256;
+constexpr int BM = 256, BN = 256, BK = 64;      // workgroup tile
+constexpr int MI = 4, NI = 4;                   // 32x32 accumulator blocks per wavefront: a 128x128 block
+constexpr int kGemmThreads = 256;               // 4 wavefronts as 2 x 2
 constexpr int kLdsStride = BK;                  // bf16 elements per LDS row (128 B); 16-byte chunks are XOR-swizzled by row
+constexpr int kTileElems = BM * BK;             // one operand tile in LDS: 32 KB
+constexpr int kGemmLdsBytes = 2 * 2 * kTileElems * 2;   // two stages x (A, B): 128 KB of the CU's 160 KB
 constexpr int kVocabChunk = 8192;               // columns of dz held at a time (pass C)
 
 __device__ __forceinline__ int float_to_ordered(float f)
@@ -43,7 +46,7 @@ struct RowStats {
     float *zy;           // [n] logit of the sampled token (pass A)
     float *m;            // [n] row maximum (after pass A)
     float *tau;          // [n] threshold
-    float *part_s;       // [col_tiles][n] masked exp sums per 128-column tile (pass B)
+    float *part_s;       // [col_tiles][n] masked exp sums per 256-column tile (pass B)
     float *part_f;       // [col_tiles][n] full exp sums, or null
     int *part_c;         // [col_tiles][n] safe counts per tile
     float *lse;          // [n] masked log-sum-exp (after pass B)
@@ -59,17 +62,17 @@ struct GemmArgs {
 };
 
 // ---------------------------------------------------------------------------
-// epilogues: called once per wavefront with its 64x64 accumulator block.
+// epilogues: called once per wavefront with its 128x128 accumulator block.
 // Element (mi, ni, i) of lane l is row r0 + mi*32 + (i/4)*8 + (l/32)*4 + i%4,
 // column c0 + ni*32 + l%32 of the launch's output.
 // ---------------------------------------------------------------------------
 struct EpiMax {
     RowStats st;
     const int64_t *ids;
-    __device__ void operator()(const GemmArgs &g, f32x16 (&acc)[2][2], int r0, int c0, int lane, float *, int) const
+    __device__ __forceinline__ void operator()(const GemmArgs &g, f32x16 (&acc)[MI][NI], int r0, int c0, int lane, float *, int) const
     {
 #pragma unroll
-        for (int mi = 0; mi < 2; ++mi) {
+        for (int mi = 0; mi < MI; ++mi) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int row = r0 + mi * 32 + (i / 4) * 8 + (lane / 32) * 4 + (i % 4);
@@ -77,7 +80,7 @@ struct EpiMax {
                 const int64_t y = row_ok ? ids[row] : -1;
                 float v = -INFINITY;
 #pragma unroll
-                for (int ni = 0; ni < 2; ++ni) {
+                for (int ni = 0; ni < NI; ++ni) {
                     const int col = c0 + ni * 32 + (lane % 32);
                     const float z = acc[mi][ni][i];
                     if (col < g.N) {
@@ -96,15 +99,15 @@ struct EpiMax {
 struct EpiSum {
     RowStats st;
     int n_rows;
-    // `lds` is the workgroup's scratch (>= 3 * 2 * 128 floats), wn the wavefront's column half
-    __device__ void operator()(const GemmArgs &g, f32x16 (&acc)[2][2], int r0, int c0, int lane, float *lds, int wn) const
+    // `lds` is the workgroup's scratch (>= 3 * 2 * BM floats), wn the wavefront's column half
+    __device__ __forceinline__ void operator()(const GemmArgs &g, f32x16 (&acc)[MI][NI], int r0, int c0, int lane, float *lds, int wn) const
     {
         const bool want_full = st.part_f != nullptr;
         float *ls = lds, *lf = lds + 2 * BM;
         int *lc = (int *)(lds + 4 * BM);
         const int tile_row0 = r0 - (r0 % BM);
 #pragma unroll
-        for (int mi = 0; mi < 2; ++mi) {
+        for (int mi = 0; mi < MI; ++mi) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int row = r0 + mi * 32 + (i / 4) * 8 + (lane / 32) * 4 + (i % 4);
@@ -114,7 +117,7 @@ struct EpiSum {
                 float s = 0.0f, f = 0.0f;
                 int c = 0;
 #pragma unroll
-                for (int ni = 0; ni < 2; ++ni) {
+                for (int ni = 0; ni < NI; ++ni) {
                     const int col = c0 + ni * 32 + (lane % 32);
                     const float z = acc[mi][ni][i];
                     if (col < g.N && row_ok) {
@@ -136,7 +139,7 @@ struct EpiSum {
                     c += __shfl_xor(c, off, kWave);
                 }
                 if ((lane % 32) == 0) {
-                    const int lr = row - tile_row0;           // 0..127
+                    const int lr = row - tile_row0;           // 0..BM-1
                     ls[wn * BM + lr] = s;
                     lf[wn * BM + lr] = f;
                     lc[wn * BM + lr] = c;
@@ -144,8 +147,8 @@ struct EpiSum {
             }
         }
     }
-    // after a barrier: 128 threads combine the two column halves in fixed order
-    __device__ void finish(const GemmArgs &g, int tile_row0, int tile_col, float *lds, int tid) const
+    // after a barrier: one thread per tile row combines the two column halves in fixed order
+    __device__ __forceinline__ void finish(const GemmArgs &g, int tile_row0, int tile_col, float *lds, int tid) const
     {
         if (tid >= BM) return;
         const int row = tile_row0 + tid;
@@ -165,12 +168,12 @@ struct EpiGrad {
     uint16_t *dz;        // [Mpad, ld_dz] bf16: rows = token rows, columns = chunk columns
     uint16_t *dzt;       // [chunk columns (padded), ld_dzt] bf16: the transpose
     int64_t ld_dz, ld_dzt;
-    __device__ void operator()(const GemmArgs &g, f32x16 (&acc)[2][2], int r0, int c0, int lane, float *, int) const
+    __device__ __forceinline__ void operator()(const GemmArgs &g, f32x16 (&acc)[MI][NI], int r0, int c0, int lane, float *, int) const
     {
 #pragma unroll
-        for (int mi = 0; mi < 2; ++mi) {
+        for (int mi = 0; mi < MI; ++mi) {
 #pragma unroll
-            for (int ni = 0; ni < 2; ++ni) {
+            for (int ni = 0; ni < NI; ++ni) {
                 const int col = c0 + ni * 32 + (lane % 32);          // column inside the chunk
                 const bool col_ok = col < g.N;
 #pragma unroll
@@ -208,16 +211,16 @@ struct EpiStore {
     float *C;            // [M, ldc] fp32
     int64_t ldc;
     int accumulate;      // 0: C = acc, 1: C += acc
-    __device__ void operator()(const GemmArgs &g, f32x16 (&acc)[2][2], int r0, int c0, int lane, float *, int) const
+    __device__ __forceinline__ void operator()(const GemmArgs &g, f32x16 (&acc)[MI][NI], int r0, int c0, int lane, float *, int) const
     {
 #pragma unroll
-        for (int mi = 0; mi < 2; ++mi) {
+        for (int mi = 0; mi < MI; ++mi) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int row = r0 + mi * 32 + (i / 4) * 8 + (lane / 32) * 4 + (i % 4);
                 if (row >= g.M) continue;
 #pragma unroll
-                for (int ni = 0; ni < 2; ++ni) {
+                for (int ni = 0; ni < NI; ++ni) {
                     const int col = c0 + ni * 32 + (lane % 32);
                     if (col >= g.N) continue;
                     float *p = C + (int64_t)row * ldc + col;
@@ -229,19 +232,26 @@ struct EpiStore {
 };
 
 // ---------------------------------------------------------------------------
-// C = A B^T on MFMA: 128x128 tile per workgroup, 4 wavefronts as 2x2, each a
-// 64x64 block of four 32x32 accumulators; K in steps of 64 through a double
-// buffered LDS tile (global -> registers -> LDS, one barrier per step).
+// C = A B^T on MFMA.  256x256 tile per workgroup; 4 wavefronts as 2x2, each a
+// 128x128 block of sixteen 32x32 accumulators (256 accumulator registers: one
+// wavefront per SIMD, so the whole register file is its own).  K advances in
+// steps of 64 through a double buffered LDS tile (global -> registers -> LDS,
+// one barrier per step).  Per step a wavefront issues 64 MFMAs against 32
+// 16-byte LDS reads, which keeps the LDS pipe at about half the MFMA time.
 // ---------------------------------------------------------------------------
 template <class Epi, bool NEEDS_FINISH>
-__global__ __launch_bounds__(kGemmThreads, 2) void gemm_nt_kernel(const GemmArgs g, const Epi epi, int tiles_m, int tiles_n)
+__global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs g, const Epi epi, int tiles_m, int tiles_n)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t lds[2][2][BM * kLdsStride];
+    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];   // [stage][A | B][BM * BK]
 
-    // tile order: groups of 8 row tiles sweep the column tiles together so that
-    // concurrently resident workgroups reuse the same B tiles from the L2
-    constexpr int GROUP = 8;
-    const int pid = blockIdx.x;
+    // Tile order.  Hardware deals workgroups round-robin to the 8 XCDs; give each
+    // XCD a contiguous range of the walk below so that the ~32 workgroups resident
+    // on it cover 4 row tiles x 8 column tiles and share operand tiles in its L2.
+    const int total = tiles_m * tiles_n;
+    const int per_xcd = total / 8;
+    int pid = blockIdx.x;
+    if (pid < per_xcd * 8) pid = (pid % 8) * per_xcd + pid / 8;
+    constexpr int GROUP = 4;
     const int per_group = GROUP * tiles_n;
     const int group = pid / per_group;
     const int first_m = group * GROUP;
@@ -254,82 +264,89 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_nt_kernel(const GemmArgs
     const int wave = tid / kWave, lane = tid % kWave;
     const int wm = wave >> 1, wn = wave & 1;
 
-    // global -> LDS mapping: a 128x64 bf16 tile is 1024 chunks of 16 B; thread t moves chunks t, t+256, ...
-    const u32x4 *gA[4], *gB[4];
-    int lds_off[4];
+    // global -> LDS mapping: a 256x64 bf16 tile is 2048 chunks of 16 B; thread t moves chunks t, t+256, ...
+    const char *baseA = (const char *)(g.A + (int64_t)tile_m * BM * g.lda);
+    const char *baseB = (const char *)(g.B + (int64_t)tile_n * BN * g.ldb);
+    const int rows_a = g.M - tile_m * BM, rows_b = g.N - tile_n * BN;   // >= 1; rows past the end repeat the last one
+    uint32_t off_a[8], off_b[8];
+    int lds_off[8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 8; ++i) {
         const int c = tid + i * kGemmThreads;
         const int row = c >> 3, kc = c & 7;
-        int ra = tile_m * BM + row; if (ra >= g.M) ra = g.M - 1;
-        int rb = tile_n * BN + row; if (rb >= g.N) rb = g.N - 1;
-        gA[i] = (const u32x4 *)(g.A + (int64_t)ra * g.lda + kc * 8);
-        gB[i] = (const u32x4 *)(g.B + (int64_t)rb * g.ldb + kc * 8);
+        const int ra = row < rows_a ? row : rows_a - 1;
+        const int rb = row < rows_b ? row : rows_b - 1;
+        off_a[i] = (uint32_t)(((int64_t)ra * g.lda + kc * 8) * 2);
+        off_b[i] = (uint32_t)(((int64_t)rb * g.ldb + kc * 8) * 2);
         lds_off[i] = row * kLdsStride + ((kc ^ (row & 7)) * 8);
     }
 
-    f32x16 acc[2][2];
+    f32x16 acc[MI][NI];
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
+    for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
+        for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.0f;
 
-    u32x4 ra[4], rb[4];
+    u32x4 ra[8], rb[8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) { ra[i] = gA[i][0]; rb[i] = gB[i][0]; }
+    for (int i = 0; i < 8; ++i) {
+        ra[i] = *(const u32x4 *)(baseA + off_a[i]);
+        rb[i] = *(const u32x4 *)(baseB + off_b[i]);
+    }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        *(u32x4 *)(&lds[0][0][lds_off[i]]) = ra[i];
-        *(u32x4 *)(&lds[0][1][lds_off[i]]) = rb[i];
+    for (int i = 0; i < 8; ++i) {
+        *(u32x4 *)(lds + lds_off[i]) = ra[i];
+        *(u32x4 *)(lds + kTileElems + lds_off[i]) = rb[i];
     }
     __syncthreads();
 
     const int nk = g.K / BK;
     // operand fetch: lane l reads row (l % 32), the 8 consecutive k of chunk 2 * ks + l / 32.
-    // Rows 32 apart share (row & 7), so one swizzle key serves both row blocks.
-    const int a_row = (wm * 64 + (lane % 32)) * kLdsStride;
-    const int b_row = (wn * 64 + (lane % 32)) * kLdsStride;
+    // Rows 32 apart share (row & 7), so one swizzle key serves all row blocks.
+    const int a_row = (wm * (MI * 32) + (lane % 32)) * kLdsStride;
+    const int b_row = (wn * (NI * 32) + (lane % 32)) * kLdsStride;
     const int key = lane & 7, half = lane / 32;
 
     for (int kt = 0; kt < nk; ++kt) {
         const int s = kt & 1;
         if (kt + 1 < nk) {
+            const size_t koff = (size_t)(kt + 1) * (BK * 2);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {   // 16-byte vectors: (kt + 1) * 64 bf16 = (kt + 1) * 8 vectors
-                ra[i] = gA[i][(kt + 1) * (BK / 8)];
-                rb[i] = gB[i][(kt + 1) * (BK / 8)];
+            for (int i = 0; i < 8; ++i) {
+                ra[i] = *(const u32x4 *)(baseA + off_a[i] + koff);
+                rb[i] = *(const u32x4 *)(baseB + off_b[i] + koff);
             }
         }
-        const uint16_t *la = lds[s][0], *lb = lds[s][1];
+        const uint16_t *la = lds + s * 2 * kTileElems, *lb = la + kTileElems;
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 a[2], b[2];
+            bf16x8 a[MI], b[NI];
+            const int chunk = ((ks * 2 + half) ^ key) * 8;
 #pragma unroll
-            for (int mi = 0; mi < 2; ++mi)
-                a[mi] = *(const bf16x8 *)(la + a_row + mi * 32 * kLdsStride + (((ks * 2 + half) ^ key) * 8));
+            for (int mi = 0; mi < MI; ++mi) a[mi] = *(const bf16x8 *)(la + a_row + mi * 32 * kLdsStride + chunk);
 #pragma unroll
-            for (int ni = 0; ni < 2; ++ni)
-                b[ni] = *(const bf16x8 *)(lb + b_row + ni * 32 * kLdsStride + (((ks * 2 + half) ^ key) * 8));
+            for (int ni = 0; ni < NI; ++ni) b[ni] = *(const bf16x8 *)(lb + b_row + ni * 32 * kLdsStride + chunk);
 #pragma unroll
-            for (int mi = 0; mi < 2; ++mi)
+            for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-                for (int ni = 0; ni < 2; ++ni)
+                for (int ni = 0; ni < NI; ++ni)
                     acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
         }
         if (kt + 1 < nk) {
+            uint16_t *wa = lds + (s ^ 1) * 2 * kTileElems, *wb = wa + kTileElems;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                *(u32x4 *)(&lds[s ^ 1][0][lds_off[i]]) = ra[i];
-                *(u32x4 *)(&lds[s ^ 1][1][lds_off[i]]) = rb[i];
+            for (int i = 0; i < 8; ++i) {
+                *(u32x4 *)(wa + lds_off[i]) = ra[i];
+                *(u32x4 *)(wb + lds_off[i]) = rb[i];
             }
         }
         __syncthreads();
     }
 
-    float *scratch = (float *)&lds[0][0][0];     // the operand tiles are dead: reuse as epilogue scratch
-    epi(g, acc, tile_m * BM + wm * 64, tile_n * BN + wn * 64, lane, scratch, wn);
+    float *scratch = (float *)lds;               // the operand tiles are dead: reuse as epilogue scratch
+    epi(g, acc, tile_m * BM + wm * (MI * 32), tile_n * BN + wn * (NI * 32), lane, scratch, wn);
     if constexpr (NEEDS_FINISH) {
         __syncthreads();
         epi.finish(g, tile_m * BM, tile_n + g.col_offset / BN, scratch, tid);
@@ -339,9 +356,16 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_nt_kernel(const GemmArgs
 template <class Epi, bool NEEDS_FINISH>
 static hipError_t launch_gemm(const GemmArgs &g, const Epi &epi, hipStream_t stream)
 {
+    static bool configured = false;
+    if (!configured) {   // more than 64 KB of LDS per workgroup has to be asked for
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_nt_kernel<Epi, NEEDS_FINISH>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
     const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
     hipLaunchKernelGGL((gemm_nt_kernel<Epi, NEEDS_FINISH>), dim3((unsigned)(tiles_m * tiles_n)),
-                       dim3(kGemmThreads), 0, stream, g, epi, tiles_m, tiles_n);
+                       dim3(kGemmThreads), kGemmLdsBytes, stream, g, epi, tiles_m, tiles_n);
     return hipGetLastError();
 }
 
@@ -461,6 +485,7 @@ static bool lm_params_ok(const dvp_lmhead_params *p)
     if (p->hidden % BK || p->ld_hidden < p->hidden || p->ld_w < p->hidden) return false;
     if (p->ld_hidden % 8 || p->ld_w % 8) return false;
     if (p->n_rows > (1 << 30) || p->vocab > (1 << 30) || p->hidden > (1 << 20)) return false;
+    if (p->ld_hidden > (1 << 22) || p->ld_w > (1 << 22)) return false;   // tile-relative byte offsets stay in 32 bits
     if (p->log_rho != p->log_rho || p->log_rho > 0.0f) return false;
     return true;
 }

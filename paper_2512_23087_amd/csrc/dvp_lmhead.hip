@@ -23,11 +23,16 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int BM = 256, BN = 256, BK = 64;      // workgroup tile
-constexpr int MI = 4, NI = 4;                   // 32x32 accumulator blocks per wavefront: a 128x128 block
-constexpr int kGemmThreads = 256;               // 4 wavefronts as 2 x 2
-constexpr int kLdsStride = BK;                  // bf16 elements per LDS row (128 B); 16-byte chunks are XOR-swizzled by row
-constexpr int kTileElems = BM * BK;             // one operand tile in LDS: 32 KB
-constexpr int kGemmLdsBytes = 2 * 2 * kTileElems * 2;   // two stages x (A, B): 128 KB of the CU's 160 KB
+constexpr int WM = 4, WN = 2;                   // 8 wavefronts as 4 x 2, two per SIMD
+constexpr int MI = BM / WM / 32, NI = BN / WN / 32;   // 32x32 accumulator blocks per wavefront: a 64x128 block
+constexpr int kGemmWaves = WM * WN;
+constexpr int kGemmThreads = kGemmWaves * kWave;
+constexpr int kRowBytes = BK * 2;               // one tile row in LDS: 128 B, its eight 16-byte chunks XOR-swizzled by row
+constexpr int kTileBytes = BM * kRowBytes;      // one operand tile in LDS: 32 KB
+constexpr int kStageBytes = 2 * kTileBytes;     // A tile, then B tile
+constexpr int kGemmLdsBytes = 2 * kStageBytes;  // two stages: 128 KB of the CU's 160 KB
+constexpr int kCopiesPerWave = BM * (BK / 8) / kWave / kGemmWaves;   // 1 KB wavefront copies per operand tile and wavefront
+static_assert(BM == BN, "the operand tiles share one copy schedule");
 constexpr int kVocabChunk = 8192;               // columns of dz held at a time (pass C)
 
 __device__ __forceinline__ int float_to_ordered(float f)
@@ -232,20 +237,38 @@ struct EpiStore {
 };
 
 // ---------------------------------------------------------------------------
-// C = A B^T on MFMA.  256x256 tile per workgroup; 4 wavefronts as 2x2, each a
-// 128x128 block of sixteen 32x32 accumulators (256 accumulator registers: one
-// wavefront per SIMD, so the whole register file is its own).  K advances in
-// steps of 64 through a double buffered LDS tile (global -> registers -> LDS,
-// one barrier per step).  Per step a wavefront issues 64 MFMAs against 32
-// 16-byte LDS reads, which keeps the LDS pipe at about half the MFMA time.
+// C = A B^T on MFMA.  256x256 tile per workgroup, K in steps of 64.
+//
+// Operand tiles go from global memory straight into LDS (16 bytes per lane,
+// no register staging): a wavefront copy lands as 1 KB of consecutive LDS, so
+// the lane -> global address map carries the row swizzle.  The copies are
+// invisible to the compiler's wait-count bookkeeping; the loop waits for them
+// explicitly, always together with the workgroup barrier.
+//
+// Two LDS stages.  The barrier of a K step sits between the LDS reads of the
+// step's last 16-wide slice and that slice's MFMAs: past it, tile j+1 has
+// landed and tile j is dead in every wavefront, so the copy of tile j+2 is
+// issued into tile j's buffer and the first fragments of tile j+1 are fetched
+// while the matrix cores still have the last slice of tile j to do.
 // ---------------------------------------------------------------------------
+__device__ __forceinline__ void copy16_to_lds(const void *gbase, uint32_t voff, uint32_t lds_addr)
+{
+    // lane l: 16 bytes from gbase + voff (per lane) to LDS byte lds_addr + 16 l (lds_addr wavefront-uniform)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_addr), "v"(voff), "s"(gbase) : "memory");
+}
+__device__ __forceinline__ void wait_copies_and_barrier()
+{
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 template <class Epi, bool NEEDS_FINISH>
 __global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs g, const Epi epi, int tiles_m, int tiles_n)
 {
-    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];   // [stage][A | B][BM * BK]
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];   // [stage][A | B][256 rows][128 B]
 
     // Tile order.  Hardware deals workgroups round-robin to the 8 XCDs; give each
-    // XCD a contiguous range of the walk below so that the ~32 workgroups resident
+    // XCD a contiguous range of the walk below so that the 32 workgroups resident
     // on it cover 4 row tiles x 8 column tiles and share operand tiles in its L2.
     const int total = tiles_m * tiles_n;
     const int per_xcd = total / 8;
@@ -261,25 +284,34 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs
     const int tile_n = in_group / group_rows;
 
     const int tid = threadIdx.x;
-    const int wave = tid / kWave, lane = tid % kWave;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave), lane = tid % kWave;
+    const int wm = wave / WN, wn = wave % WN;
 
-    // global -> LDS mapping: a 256x64 bf16 tile is 2048 chunks of 16 B; thread t moves chunks t, t+256, ...
-    const char *baseA = (const char *)(g.A + (int64_t)tile_m * BM * g.lda);
-    const char *baseB = (const char *)(g.B + (int64_t)tile_n * BN * g.ldb);
+    // global -> LDS: copy c of a tile (c = i * 8 + wave) fills LDS chunks 64 c .. 64 c + 63, i.e. tile
+    // rows 8 c .. 8 c + 7; the chunk at physical position p of row r holds logical chunk p ^ (r & 7).
+    const uint8_t *baseA = (const uint8_t *)(g.A + (int64_t)tile_m * BM * g.lda);
+    const uint8_t *baseB = (const uint8_t *)(g.B + (int64_t)tile_n * BN * g.ldb);
     const int rows_a = g.M - tile_m * BM, rows_b = g.N - tile_n * BN;   // >= 1; rows past the end repeat the last one
-    uint32_t off_a[8], off_b[8];
-    int lds_off[8];
+    uint32_t off_a[kCopiesPerWave], off_b[kCopiesPerWave];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int c = tid + i * kGemmThreads;
-        const int row = c >> 3, kc = c & 7;
+    for (int i = 0; i < kCopiesPerWave; ++i) {
+        const int p = (i * kGemmWaves + wave) * kWave + lane;
+        const int row = p >> 3, kc = (p & 7) ^ (row & 7);
         const int ra = row < rows_a ? row : rows_a - 1;
         const int rb = row < rows_b ? row : rows_b - 1;
         off_a[i] = (uint32_t)(((int64_t)ra * g.lda + kc * 8) * 2);
         off_b[i] = (uint32_t)(((int64_t)rb * g.ldb + kc * 8) * 2);
-        lds_off[i] = row * kLdsStride + ((kc ^ (row & 7)) * 8);
     }
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)lds;
+    auto issue_copies = [&](int kt, int stage) {
+        const uint8_t *pa = baseA + (size_t)kt * kRowBytes;
+        const uint8_t *pb = baseB + (size_t)kt * kRowBytes;
+        const uint32_t sa = lds_base + stage * kStageBytes;
+#pragma unroll
+        for (int i = 0; i < kCopiesPerWave; ++i) copy16_to_lds(pa, off_a[i], sa + (i * kGemmWaves + wave) * 1024);
+#pragma unroll
+        for (int i = 0; i < kCopiesPerWave; ++i) copy16_to_lds(pb, off_b[i], sa + kTileBytes + (i * kGemmWaves + wave) * 1024);
+    };
 
     f32x16 acc[MI][NI];
 #pragma unroll
@@ -289,63 +321,56 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.0f;
 
-    u32x4 ra[8], rb[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        ra[i] = *(const u32x4 *)(baseA + off_a[i]);
-        rb[i] = *(const u32x4 *)(baseB + off_b[i]);
-    }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        *(u32x4 *)(lds + lds_off[i]) = ra[i];
-        *(u32x4 *)(lds + kTileElems + lds_off[i]) = rb[i];
-    }
-    __syncthreads();
-
-    const int nk = g.K / BK;
     // operand fetch: lane l reads row (l % 32), the 8 consecutive k of chunk 2 * ks + l / 32.
     // Rows 32 apart share (row & 7), so one swizzle key serves all row blocks.
-    const int a_row = (wm * (MI * 32) + (lane % 32)) * kLdsStride;
-    const int b_row = (wn * (NI * 32) + (lane % 32)) * kLdsStride;
-    const int key = lane & 7, half = lane / 32;
+    const int frow = lane % 32, half = lane / 32, key = lane & 7;
+    const int a_off = (wm * MI * 32 + frow) * kRowBytes;
+    const int b_off = kTileBytes + (wn * NI * 32 + frow) * kRowBytes;
+    bf16x8 fa[2][MI], fb[2][NI];
+    auto fetch = [&](int buf, int stage, int ks) {
+        const uint8_t *sb = lds + stage * kStageBytes;
+        const int chunk = ((ks * 2 + half) ^ key) * 16;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) fa[buf][mi] = *(const bf16x8 *)(sb + a_off + mi * 32 * kRowBytes + chunk);
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) fb[buf][ni] = *(const bf16x8 *)(sb + b_off + ni * 32 * kRowBytes + chunk);
+    };
+    auto multiply = [&](int buf) {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][mi], fb[buf][ni], acc[mi][ni], 0, 0, 0);
+        // scheduling hint: spread the LDS reads of the next slice between this slice's MFMAs
+        constexpr int NM = MI * NI, NR = MI + NI, PER = NM / NR;
+#pragma unroll
+        for (int i = 0; i < NR; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, PER, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        if constexpr (NM - PER * NR > 0) __builtin_amdgcn_sched_group_barrier(0x008, NM - PER * NR, 0);
+    };
 
-    for (int kt = 0; kt < nk; ++kt) {
-        const int s = kt & 1;
-        if (kt + 1 < nk) {
-            const size_t koff = (size_t)(kt + 1) * (BK * 2);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                ra[i] = *(const u32x4 *)(baseA + off_a[i] + koff);
-                rb[i] = *(const u32x4 *)(baseB + off_b[i] + koff);
-            }
-        }
-        const uint16_t *la = lds + s * 2 * kTileElems, *lb = la + kTileElems;
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 a[MI], b[NI];
-            const int chunk = ((ks * 2 + half) ^ key) * 8;
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi) a[mi] = *(const bf16x8 *)(la + a_row + mi * 32 * kLdsStride + chunk);
-#pragma unroll
-            for (int ni = 0; ni < NI; ++ni) b[ni] = *(const bf16x8 *)(lb + b_row + ni * 32 * kLdsStride + chunk);
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < NI; ++ni)
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
-        }
-        if (kt + 1 < nk) {
-            uint16_t *wa = lds + (s ^ 1) * 2 * kTileElems, *wb = wa + kTileElems;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                *(u32x4 *)(wa + lds_off[i]) = ra[i];
-                *(u32x4 *)(wb + lds_off[i]) = rb[i];
-            }
-        }
-        __syncthreads();
+    const int nk = g.K / BK;
+    issue_copies(0, 0);
+    wait_copies_and_barrier();
+    if (nk > 1) issue_copies(1, 1);
+    fetch(0, 0, 0);
+    for (int j = 0; j < nk; ++j) {
+        const int stage = j & 1;
+        fetch(1, stage, 1); multiply(0);
+        fetch(0, stage, 2); multiply(1);
+        fetch(1, stage, 3); multiply(0);
+        // own reads of tile j are home, own copies of tile j+1 have landed; past the
+        // barrier that holds for every wavefront
+        wait_copies_and_barrier();
+        if (j + 2 < nk) issue_copies(j + 2, stage);
+        fetch(0, stage ^ 1, 0);             // after the last tile: reads a dead buffer, unused
+        multiply(1);
     }
 
-    float *scratch = (float *)lds;               // the operand tiles are dead: reuse as epilogue scratch
+    // every wavefront is past the last barrier: the operand tiles are dead, reuse them as epilogue scratch
+    float *scratch = (float *)lds;
     epi(g, acc, tile_m * BM + wm * (MI * 32), tile_n * BN + wn * (NI * 32), lane, scratch, wn);
     if constexpr (NEEDS_FINISH) {
         __syncthreads();

@@ -2,16 +2,24 @@
 // produced tile by tile on the matrix cores (MFMA, bf16 in, fp32 accumulate)
 // and consumed in the tile epilogues; the [N, V] logits are never stored.
 //
-// Membership needs the final row maximum (Def. 5.1), so the logits are
-// produced three times:
+// Membership needs the final row maximum (Def. 5.1), so the logits of a side
+// are produced twice:
 //   pass A  z tiles -> running row max, and z_y where a tile holds column y
 //   pass B  z tiles -> safe-set size and masked sum at tau = fl32(m + log_rho)
-//           (Def. 5.1 / 5.2), per 128-column partials, reduced in fixed order
-//   pass C  (training side, when a gradient is asked for) z tiles -> dz tile
-//           (Prop. 5.4), written per vocabulary chunk as bf16 in both
-//           orientations, then dH += dz W and dW = dz^T H on the same GEMM kernel
-// Every GEMM is C = A B^T with both operands K-major; H and W are transposed
-// once per call so that the two gradient products have that form too.
+//           (Def. 5.1 / 5.2), per 256-column partials, reduced in fixed order
+// When a gradient is asked for, the training side runs in blocks of 4096 token
+// rows and pass B also leaves the block's masked exponentials
+//   E_ik = [z_ik >= tau_i] exp(z_ik - m_i)          (bf16, both orientations)
+// behind.  With S_i their row sum and c_i = grad_out_i (0 when y_i is pruned),
+// Prop. 5.4 reads dz_ik = c_i delta(k, y_i) - (c_i / S_i) E_ik, so
+//   dH_i = c_i W_y + s_i (E W)_i,   dW = onehot^T diag(c) H + E^T (diag(s) H),   s_i = -c_i / S_i.
+// The two E products run on the matrix cores (the row factor s is applied in
+// fp32 when dH is written and folded into H for dW, which is accumulated over
+// the row blocks); the one-hot terms, the only O(1) entries of dz, are added in
+// fp32 and never rounded to bf16.
+// Every GEMM is C = A B^T with both operands K-major; W is transposed once per
+// call and the scaled H once per row block so that the two E products have
+// that form too.
 #include <math.h>
 
 #include "dvp_device.h"
@@ -30,10 +38,14 @@ constexpr int kGemmThreads = kGemmWaves * kWave;
 constexpr int kRowBytes = BK * 2;               // one tile row in LDS: 128 B, its eight 16-byte chunks XOR-swizzled by row
 constexpr int kTileBytes = BM * kRowBytes;      // one operand tile in LDS: 32 KB
 constexpr int kStageBytes = 2 * kTileBytes;     // A tile, then B tile
-constexpr int kGemmLdsBytes = 2 * kStageBytes;  // two stages: 128 KB of the CU's 160 KB
+constexpr int kPipeLdsBytes = 2 * kStageBytes;  // two stages: 128 KB of the CU's 160 KB
+constexpr int kSumScratchBytes = 6 * BM * 4;    // pass B's per-row partials of the two column halves
+constexpr int kGemmLdsBytes = kPipeLdsBytes + kSumScratchBytes;
+constexpr int kWaveStageBytes = kPipeLdsBytes / kGemmWaves;   // 16 KB: a wavefront's 64x128 block as bf16
+static_assert(kWaveStageBytes == MI * 32 * NI * 32 * 2, "epilogue staging assumes one bf16 block per wavefront");
 constexpr int kCopiesPerWave = BM * (BK / 8) / kWave / kGemmWaves;   // 1 KB wavefront copies per operand tile and wavefront
 static_assert(BM == BN, "the operand tiles share one copy schedule");
-constexpr int kVocabChunk = 8192;               // columns of dz held at a time (pass C)
+constexpr int kRowBlock = 4096;                 // token rows whose masked exponentials are held at a time
 
 __device__ __forceinline__ int float_to_ordered(float f)
 {
@@ -54,8 +66,8 @@ struct RowStats {
     float *part_s;       // [col_tiles][n] masked exp sums per 256-column tile (pass B)
     float *part_f;       // [col_tiles][n] full exp sums, or null
     int *part_c;         // [col_tiles][n] safe counts per tile
-    float *lse;          // [n] masked log-sum-exp (after pass B)
-    float *coef;         // [n] grad_out where the sampled token is safe, else 0 (pass C)
+    float *coef;         // [n] c: grad_out where the sampled token is safe, else 0 (after pass B)
+    float *scale;        // [n] s = -c / S (after pass B)
 };
 
 struct GemmArgs {
@@ -63,18 +75,19 @@ struct GemmArgs {
     const uint16_t *B;   // [N, ldb] bf16, K-major
     int64_t lda, ldb;
     int M, N, K;         // K a multiple of BK; rows beyond M / N are clamped on load and masked in the epilogue
-    int col_offset;      // global column of this launch's column 0 (vocabulary chunking)
 };
 
 // ---------------------------------------------------------------------------
-// epilogues: called once per wavefront with its 128x128 accumulator block.
+// epilogues: called once per wavefront with its 64x128 accumulator block.
 // Element (mi, ni, i) of lane l is row r0 + mi*32 + (i/4)*8 + (l/32)*4 + i%4,
-// column c0 + ni*32 + l%32 of the launch's output.
+// column c0 + ni*32 + l%32 of the launch's output.  `lds` is the workgroup's
+// dynamic LDS: the operand tiles (dead by now) and, behind them, the scratch of
+// pass B's sums.
 // ---------------------------------------------------------------------------
 struct EpiMax {
     RowStats st;
     const int64_t *ids;
-    __device__ __forceinline__ void operator()(const GemmArgs &g, f32x16 (&acc)[MI][NI], int r0, int c0, int lane, float *, int) const
+    __device__ __forceinline__ void operator()(const GemmArgs &g, f32x16 (&acc)[MI][NI], int r0, int c0, int lane, uint8_t *, int, int) const
     {
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
@@ -90,7 +103,7 @@ struct EpiMax {
                     const float z = acc[mi][ni][i];
                     if (col < g.N) {
                         v = fmaxf(v, z);
-                        if (row_ok && (int64_t)(col + g.col_offset) == y) st.zy[row] = z;
+                        if (row_ok && (int64_t)col == y) st.zy[row] = z;
                     }
                 }
 #pragma unroll
@@ -101,15 +114,28 @@ struct EpiMax {
     }
 };
 
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)   // hardware pack-convert, round to nearest even
+{
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){lo, hi}, bf16x2));
+}
+
+// WRITE_E: also store the masked exponentials of the tile, as bf16, row-major in
+// E [rows (padded to 256), ld_e] and transposed in Et [columns (padded), ld_et];
+// rows beyond M and columns beyond N are stored as zeros (they pad the K
+// dimension of the two gradient products).
+template <bool WRITE_E>
 struct EpiSum {
     RowStats st;
     int n_rows;
-    // `lds` is the workgroup's scratch (>= 3 * 2 * BM floats), wn the wavefront's column half
-    __device__ __forceinline__ void operator()(const GemmArgs &g, f32x16 (&acc)[MI][NI], int r0, int c0, int lane, float *lds, int wn) const
+    uint16_t *E, *Et;
+    int64_t ld_e, ld_et;
+    __device__ __forceinline__ void operator()(const GemmArgs &g, f32x16 (&acc)[MI][NI], int r0, int c0, int lane, uint8_t *lds, int wave, int wn) const
     {
         const bool want_full = st.part_f != nullptr;
-        float *ls = lds, *lf = lds + 2 * BM;
-        int *lc = (int *)(lds + 4 * BM);
+        float *ls = (float *)(lds + kPipeLdsBytes), *lf = ls + 2 * BM;
+        int *lc = (int *)(ls + 4 * BM);
         const int tile_row0 = r0 - (r0 % BM);
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
@@ -125,17 +151,20 @@ struct EpiSum {
                 for (int ni = 0; ni < NI; ++ni) {
                     const int col = c0 + ni * 32 + (lane % 32);
                     const float z = acc[mi][ni][i];
+                    float kept = 0.0f;
                     if (col < g.N && row_ok) {
                         const bool safe = z >= tau;
                         c += safe ? 1 : 0;
                         if (want_full) {
                             const float e = __expf(z - m);
                             f += e;
-                            s += safe ? e : 0.0f;
+                            kept = safe ? e : 0.0f;
                         } else if (safe) {
-                            s += __expf(z - m);
+                            kept = __expf(z - m);
                         }
+                        s += kept;
                     }
+                    if constexpr (WRITE_E) acc[mi][ni][i] = kept;   // the accumulators now hold E
                 }
 #pragma unroll
                 for (int off = 16; off > 0; off >>= 1) {
@@ -151,15 +180,61 @@ struct EpiSum {
                 }
             }
         }
+        if constexpr (WRITE_E) {
+            // Each wavefront turns its block into 16-byte stores through its own 16 KB of the dead
+            // operand tiles: LDS operations of one wavefront complete in order, no barrier is needed.
+            uint8_t *stage = lds + wave * kWaveStageBytes;
+            const int l32 = lane % 32, up = lane / 32;
+            // row-major: [64 rows][128 columns] bf16.  Neighbouring lanes hold neighbouring columns of
+            // the same row; they trade one value so that each writes a whole 32-bit word.
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                    for (int i = 0; i < 16; i += 2) {
+                        const float a = acc[mi][ni][i], b = acc[mi][ni][i + 1];
+                        const bool odd = lane & 1;
+                        const float got = __shfl_xor(odd ? a : b, 1, kWave);
+                        const uint32_t word = odd ? pack_bf16x2(got, b) : pack_bf16x2(a, got);
+                        const int lrow = mi * 32 + (i / 4) * 8 + up * 4 + (i % 4) + (odd ? 1 : 0);
+                        const int lcol = ni * 32 + (l32 & ~1);
+                        *(uint32_t *)(stage + lrow * (NI * 32 * 2) + lcol * 2) = word;
+                    }
+#pragma unroll
+            for (int t = 0; t < MI * 32 / 4; ++t) {
+                const int lrow = t * 4 + lane / 16, chunk = lane % 16;
+                const u32x4 v = *(const u32x4 *)(stage + lrow * (NI * 32 * 2) + chunk * 16);
+                *(u32x4 *)(E + (int64_t)(r0 + lrow) * ld_e + c0 + chunk * 8) = v;
+            }
+            // transposed: [128 columns][64 rows] bf16; a lane holds 4 consecutive rows of a column
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const uint32_t w0 = pack_bf16x2(acc[mi][ni][q * 4], acc[mi][ni][q * 4 + 1]);
+                        const uint32_t w1 = pack_bf16x2(acc[mi][ni][q * 4 + 2], acc[mi][ni][q * 4 + 3]);
+                        const int lcol = ni * 32 + l32, lrow = mi * 32 + q * 8 + up * 4;
+                        *(uint2 *)(stage + lcol * (MI * 32 * 2) + lrow * 2) = make_uint2(w0, w1);
+                    }
+#pragma unroll
+            for (int t = 0; t < NI * 32 / 8; ++t) {
+                const int lcol = t * 8 + lane / 8, chunk = lane % 8;
+                const u32x4 v = *(const u32x4 *)(stage + lcol * (MI * 32 * 2) + chunk * 16);
+                *(u32x4 *)(Et + (int64_t)(c0 + lcol) * ld_et + r0 + chunk * 8) = v;
+            }
+        }
     }
     // after a barrier: one thread per tile row combines the two column halves in fixed order
-    __device__ __forceinline__ void finish(const GemmArgs &g, int tile_row0, int tile_col, float *lds, int tid) const
+    __device__ __forceinline__ void finish(const GemmArgs &g, int tile_row0, int tile_col, uint8_t *lds, int tid) const
     {
         if (tid >= BM) return;
         const int row = tile_row0 + tid;
         if (row >= g.M) return;
-        const float *ls = lds, *lf = lds + 2 * BM;
-        const int *lc = (const int *)(lds + 4 * BM);
+        const float *ls = (const float *)(lds + kPipeLdsBytes), *lf = ls + 2 * BM;
+        const int *lc = (const int *)(ls + 4 * BM);
         const int64_t o = (int64_t)tile_col * n_rows + row;
         st.part_s[o] = ls[tid] + ls[BM + tid];
         st.part_c[o] = lc[tid] + lc[BM + tid];
@@ -167,56 +242,16 @@ struct EpiSum {
     }
 };
 
-struct EpiGrad {
-    RowStats st;
-    const int64_t *ids;
-    uint16_t *dz;        // [Mpad, ld_dz] bf16: rows = token rows, columns = chunk columns
-    uint16_t *dzt;       // [chunk columns (padded), ld_dzt] bf16: the transpose
-    int64_t ld_dz, ld_dzt;
-    __device__ __forceinline__ void operator()(const GemmArgs &g, f32x16 (&acc)[MI][NI], int r0, int c0, int lane, float *, int) const
-    {
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi) {
-#pragma unroll
-            for (int ni = 0; ni < NI; ++ni) {
-                const int col = c0 + ni * 32 + (lane % 32);          // column inside the chunk
-                const bool col_ok = col < g.N;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    uint32_t packed[2] = {0u, 0u};
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int i = q * 4 + r;
-                        const int row = r0 + mi * 32 + q * 8 + (lane / 32) * 4 + r;
-                        float d = 0.0f;
-                        if (row < g.M && col_ok) {
-                            const float coef = st.coef[row];
-                            const float z = acc[mi][ni][i];
-                            if (coef != 0.0f && z >= st.tau[row]) {
-                                const float p = __expf((z - st.m[row]) - (st.lse[row] - st.m[row]));
-                                const float onehot = ((int64_t)(col + g.col_offset) == ids[row]) ? 1.0f : 0.0f;
-                                d = coef * (onehot - p);
-                            }
-                        }
-                        const uint32_t b = f32_to_bf16_rne(d);
-                        // rows beyond M and columns beyond N are written as zeros: they pad
-                        // the K dimension of the two gradient products
-                        dz[(int64_t)row * ld_dz + col] = (uint16_t)b;
-                        packed[r >> 1] |= b << (16 * (r & 1));
-                    }
-                    const int row4 = r0 + mi * 32 + q * 8 + (lane / 32) * 4;
-                    *(uint2 *)(dzt + (int64_t)col * ld_dzt + row4) = make_uint2(packed[0], packed[1]);
-                }
-            }
-        }
-    }
-};
-
 struct EpiStore {
-    float *C;            // [M, ldc] fp32
+    float *C;                // [M, ldc] fp32
     int64_t ldc;
-    int accumulate;      // 0: C = acc, 1: C += acc
-    __device__ __forceinline__ void operator()(const GemmArgs &g, f32x16 (&acc)[MI][NI], int r0, int c0, int lane, float *, int) const
+    int accumulate;          // 0: C = v, 1: C += v
+    const float *row_scale;  // v = row_scale[row] * acc (null: v = acc) ...
+    const float *row_coef;   // ... + row_coef[row] * src[ids[row], col] where row_coef[row] != 0 (null: no such term)
+    const int64_t *ids;
+    const uint16_t *src;     // bf16 [*, ld_src]
+    int64_t ld_src;
+    __device__ __forceinline__ void operator()(const GemmArgs &g, f32x16 (&acc)[MI][NI], int r0, int c0, int lane, uint8_t *, int, int) const
     {
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
@@ -224,12 +259,17 @@ struct EpiStore {
             for (int i = 0; i < 16; ++i) {
                 const int row = r0 + mi * 32 + (i / 4) * 8 + (lane / 32) * 4 + (i % 4);
                 if (row >= g.M) continue;
+                const float sc = row_scale ? row_scale[row] : 1.0f;
+                const float co = row_coef ? row_coef[row] : 0.0f;
+                const uint16_t *srow = co != 0.0f ? src + ids[row] * ld_src : nullptr;
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni) {
                     const int col = c0 + ni * 32 + (lane % 32);
                     if (col >= g.N) continue;
                     float *p = C + (int64_t)row * ldc + col;
-                    *p = accumulate ? *p + acc[mi][ni][i] : acc[mi][ni][i];
+                    float v = sc * acc[mi][ni][i];
+                    if (srow) v += co * __uint_as_float((uint32_t)srow[col] << 16);
+                    *p = accumulate ? *p + v : v;
                 }
             }
         }
@@ -369,12 +409,11 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs
         multiply(1);
     }
 
-    // every wavefront is past the last barrier: the operand tiles are dead, reuse them as epilogue scratch
-    float *scratch = (float *)lds;
-    epi(g, acc, tile_m * BM + wm * (MI * 32), tile_n * BN + wn * (NI * 32), lane, scratch, wn);
+    // every wavefront is past the last barrier: the operand tiles are dead, the epilogue may reuse them
+    epi(g, acc, tile_m * BM + wm * (MI * 32), tile_n * BN + wn * (NI * 32), lane, lds, wave, wn);
     if constexpr (NEEDS_FINISH) {
         __syncthreads();
-        epi.finish(g, tile_m * BM, tile_n + g.col_offset / BN, scratch, tid);
+        epi.finish(g, tile_m * BM, tile_n, lds, tid);
     }
 }
 
@@ -433,8 +472,11 @@ __global__ void after_sum_kernel(RowStats st, SideOut out, const int64_t *ids, c
     const bool y_ok = y >= 0 && y < (int64_t)vocab;
     const float zy = st.zy[i];
     const bool y_safe = y_ok && zy >= tau;
-    st.lse[i] = m + log_s;
-    if (side == 0) st.coef[i] = (grad_out && y_safe) ? grad_out[i] : 0.0f;
+    if (side == 0) {
+        const float c_i = (grad_out && y_safe) ? grad_out[i] : 0.0f;
+        st.coef[i] = c_i;
+        st.scale[i] = -c_i / s;
+    }
     if (out.row_max) out.row_max[i] = m;
     if (out.lse_safe) out.lse_safe[i] = m + log_s;
     if (out.lse_full) out.lse_full[i] = m + logf(f);
@@ -448,16 +490,64 @@ __global__ void after_sum_kernel(RowStats st, SideOut out, const int64_t *ids, c
     }
 }
 
-// out[c, r] = in[r, c] for r < rows, c < cols; out rows are ld_out long and zero padded up to rows_pad
+// One-hot part of dW (Prop. 5.4): dW[y_i, :] += c_i H_i for the `rows` token rows of a block, in
+// fp32 and in row order whatever the launch order (run-to-run identical).  One workgroup per token
+// row; the first row of the block that sampled a token adds the contributions of every row that
+// sampled it.  Runs after the block's E^T product has been written to dW.
+constexpr int kOnehotThreads = 256;
+__global__ __launch_bounds__(kOnehotThreads) void onehot_dw_kernel(const int64_t *ids, const float *coef, const uint16_t *H,
+                                                                   int64_t ld_h, float *dW, int64_t ld_w, int rows, int d)
+{
+    __shared__ int tok[kRowBlock];      // sampled token per row, -1 where the row contributes nothing
+    __shared__ int match[kRowBlock];    // rows that sampled this workgroup's token, ascending
+    __shared__ int n_match;
+    const int i = blockIdx.x, tid = threadIdx.x;
+    for (int r = tid; r < rows; r += kOnehotThreads) tok[r] = coef[r] != 0.0f ? (int)ids[r] : -1;
+    __syncthreads();
+    const int y = tok[i];
+    if (y < 0) return;
+    int earlier = 0;
+    for (int r = tid; r < i; r += kOnehotThreads) earlier |= tok[r] == y;
+    if (__syncthreads_or(earlier)) return;
+    if (tid < kWave) {                  // first wavefront: ordered list of the matching rows
+        int count = 0;
+        for (int base = i; base < rows; base += kWave) {
+            const int r = base + tid;
+            const bool hit = r < rows && tok[r] == y;
+            const unsigned long long bal = __builtin_amdgcn_ballot_w64(hit);
+            if (hit) match[count + (int)__builtin_popcountll(bal & ((1ull << tid) - 1ull))] = r;
+            count += (int)__builtin_popcountll(bal);
+        }
+        if (tid == 0) n_match = count;
+    }
+    __syncthreads();
+    const int nm = n_match;
+    for (int j = tid; j < d; j += kOnehotThreads) {
+        float a = 0.0f;
+        for (int q = 0; q < nm; ++q) {
+            const int r = match[q];
+            a += coef[r] * __uint_as_float((uint32_t)H[(int64_t)r * ld_h + j] << 16);
+        }
+        dW[(int64_t)y * ld_w + j] += a;
+    }
+}
+
+// out[c, r] = bf16(scale[r] * in[r, c]) (scale null: a plain copy) for r < rows, c < cols;
+// out rows are ld_out long and zero padded up to rows_pad
 __global__ void transpose_bf16_kernel(const uint16_t *in, int64_t ld_in, uint16_t *out, int64_t ld_out,
-                                      int rows, int cols, int rows_pad)
+                                      int rows, int cols, int rows_pad, const float *scale)
 {
     __shared__ uint16_t tile[32][33];
     const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
     const int tx = threadIdx.x, ty = threadIdx.y;     // 32 x 8
     for (int k = ty; k < 32; k += 8) {
         const int r = r0 + k, c = c0 + tx;
-        tile[k][tx] = (r < rows && c < cols) ? in[(int64_t)r * ld_in + c] : (uint16_t)0;
+        uint16_t v = 0;
+        if (r < rows && c < cols) {
+            v = in[(int64_t)r * ld_in + c];
+            if (scale) v = (uint16_t)f32_to_bf16_rne(scale[r] * __uint_as_float((uint32_t)v << 16));
+        }
+        tile[k][tx] = v;
     }
     __syncthreads();
     for (int k = ty; k < 32; k += 8) {
@@ -473,32 +563,34 @@ static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct LmLayout {
     size_t total;
-    size_t off_i32[2], off_zy[2], off_m[2], off_tau[2], off_lse[2], off_coef;
+    size_t off_i32[2], off_zy[2], off_m[2], off_tau[2], off_coef, off_scale;
     size_t off_ps[2], off_pf[2], off_pc[2];
-    size_t off_ht, off_wt, off_dz, off_dzt;
-    int n_pad, v_pad, col_tiles;
+    size_t off_ht, off_wt, off_e, off_et;
+    int block_pad, v_pad, col_tiles;
 };
 
 static LmLayout lm_layout(int64_t n, int64_t d, int64_t v)
 {
     LmLayout L;
-    L.n_pad = (int)((n + BM - 1) / BM * BM);
+    const int64_t block = n < kRowBlock ? n : kRowBlock;
+    L.block_pad = (int)((block + BM - 1) / BM * BM);
     L.v_pad = (int)((v + BN - 1) / BN * BN);
     L.col_tiles = L.v_pad / BN;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o += align256(bytes); return at; };
     for (int s = 0; s < 2; ++s) {
         L.off_i32[s] = take(n * 4); L.off_zy[s] = take(n * 4); L.off_m[s] = take(n * 4);
-        L.off_tau[s] = take(n * 4); L.off_lse[s] = take(n * 4);
+        L.off_tau[s] = take(n * 4);
         L.off_ps[s] = take((size_t)L.col_tiles * n * 4);
         L.off_pf[s] = take((size_t)L.col_tiles * n * 4);
         L.off_pc[s] = take((size_t)L.col_tiles * n * 4);
     }
     L.off_coef = take(n * 4);
-    L.off_ht = take((size_t)d * L.n_pad * 2);
+    L.off_scale = take(n * 4);
+    L.off_ht = take((size_t)d * L.block_pad * 2);
     L.off_wt = take((size_t)d * L.v_pad * 2);
-    L.off_dz = take((size_t)L.n_pad * kVocabChunk * 2);
-    L.off_dzt = take((size_t)kVocabChunk * L.n_pad * 2);
+    L.off_e = take((size_t)L.block_pad * L.v_pad * 2);
+    L.off_et = take((size_t)L.v_pad * L.block_pad * 2);
     L.total = o;
     return L;
 }
@@ -509,7 +601,7 @@ static bool lm_params_ok(const dvp_lmhead_params *p)
     if (p->n_rows < 0 || p->vocab < 1 || p->hidden < BK) return false;
     if (p->hidden % BK || p->ld_hidden < p->hidden || p->ld_w < p->hidden) return false;
     if (p->ld_hidden % 8 || p->ld_w % 8) return false;
-    if (p->n_rows > (1 << 30) || p->vocab > (1 << 30) || p->hidden > (1 << 20)) return false;
+    if (p->n_rows > (1 << 30) || p->vocab > (1 << 22) || p->hidden > (1 << 20)) return false;
     if (p->ld_hidden > (1 << 22) || p->ld_w > (1 << 22)) return false;   // tile-relative byte offsets stay in 32 bits
     if (p->log_rho != p->log_rho || p->log_rho > 0.0f) return false;
     return true;
@@ -550,73 +642,92 @@ dvp_status dvp_fused_lmhead(const dvp_lmhead_params *p, const void *hidden, cons
     const int n = (int)p->n_rows, d = (int)p->hidden, v = (int)p->vocab;
     char *ws = (char *)workspace;
     const void *w_side[2] = {w_train, w_infer};
-    const int n_sides = w_infer ? 2 : 1;
     SideOut outs[2];
     for (int s = 0; s < 2; ++s) {
         const dvp_side_out *o = s == 0 ? out_train : (w_infer ? out_infer : nullptr);
         outs[s] = SideOut{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
         if (o) outs[s] = SideOut{o->logp, o->row_max, o->lse_safe, o->lse_full, o->safe_count, nullptr};
     }
-    RowStats st[2];
-    for (int s = 0; s < 2; ++s) {
-        st[s].max_key = (int *)(ws + L.off_i32[s]); st[s].zy = (float *)(ws + L.off_zy[s]);
-        st[s].m = (float *)(ws + L.off_m[s]); st[s].tau = (float *)(ws + L.off_tau[s]);
-        st[s].lse = (float *)(ws + L.off_lse[s]); st[s].coef = (float *)(ws + L.off_coef);
-        st[s].part_s = (float *)(ws + L.off_ps[s]); st[s].part_c = (int *)(ws + L.off_pc[s]);
-        st[s].part_f = outs[s].lse_full ? (float *)(ws + L.off_pf[s]) : nullptr;
-    }
-    const int tb = 256, nb = (n + tb - 1) / tb;
-    hipError_t e = hipSuccess;
-#define DVP_CHECK_LAUNCH() do { e = hipGetLastError(); if (e != hipSuccess) return DVP_ERR_HIP; } while (0)
-
-    // pass A and pass B for each side
-    for (int s = 0; s < n_sides; ++s) {
-        GemmArgs g;
-        g.A = (const uint16_t *)hidden; g.lda = p->ld_hidden;
-        g.B = (const uint16_t *)w_side[s]; g.ldb = p->ld_w;
-        g.M = n; g.N = v; g.K = d; g.col_offset = 0;
-        hipLaunchKernelGGL(init_stats_kernel, dim3(nb), dim3(tb), 0, stream, st[s], n);
-        DVP_CHECK_LAUNCH();
-        if (launch_gemm<EpiMax, false>(g, EpiMax{st[s], ids}, stream) != hipSuccess) return DVP_ERR_HIP;
-        hipLaunchKernelGGL(after_max_kernel, dim3(nb), dim3(tb), 0, stream, st[s], n, p->log_rho);
-        DVP_CHECK_LAUNCH();
-        if (launch_gemm<EpiSum, true>(g, EpiSum{st[s], n}, stream) != hipSuccess) return DVP_ERR_HIP;
-        hipLaunchKernelGGL(after_sum_kernel, dim3(nb), dim3(tb), 0, stream, st[s], outs[s], ids, grad_out,
-                           row_flags, n, v, L.col_tiles, s);
-        DVP_CHECK_LAUNCH();
-    }
-    if (!grad_out) return DVP_OK;
-
-    // pass C: gradient through the training head
     uint16_t *ht = (uint16_t *)(ws + L.off_ht), *wt = (uint16_t *)(ws + L.off_wt);
-    uint16_t *dz = (uint16_t *)(ws + L.off_dz), *dzt = (uint16_t *)(ws + L.off_dzt);
-    hipLaunchKernelGGL(transpose_bf16_kernel, dim3((d + 31) / 32, (L.n_pad + 31) / 32), dim3(32, 8), 0, stream,
-                       (const uint16_t *)hidden, p->ld_hidden, ht, (int64_t)L.n_pad, n, d, L.n_pad);
-    DVP_CHECK_LAUNCH();
-    hipLaunchKernelGGL(transpose_bf16_kernel, dim3((d + 31) / 32, (L.v_pad + 31) / 32), dim3(32, 8), 0, stream,
-                       (const uint16_t *)w_train, p->ld_w, wt, (int64_t)L.v_pad, v, d, L.v_pad);
-    DVP_CHECK_LAUNCH();
-    for (int c0 = 0, chunk = 0; c0 < v; c0 += kVocabChunk, ++chunk) {
-        const int vc = (v - c0) < kVocabChunk ? (v - c0) : kVocabChunk;
-        const int vc_pad = (vc + BN - 1) / BN * BN;
+    uint16_t *E = (uint16_t *)(ws + L.off_e), *Et = (uint16_t *)(ws + L.off_et);
+    const int tb = 256;
+#define DVP_CHECK_LAUNCH() do { if (hipGetLastError() != hipSuccess) return DVP_ERR_HIP; } while (0)
+
+    // Forward of `rows` token rows starting at r0 on side s: pass A, pass B, outputs.  The per-row
+    // statistics and the partials are indexed from 0 within the call.
+    auto forward = [&](int s, int r0, int rows, bool write_e, RowStats &st) -> dvp_status {
+        st.max_key = (int *)(ws + L.off_i32[s]); st.zy = (float *)(ws + L.off_zy[s]);
+        st.m = (float *)(ws + L.off_m[s]); st.tau = (float *)(ws + L.off_tau[s]);
+        st.coef = (float *)(ws + L.off_coef); st.scale = (float *)(ws + L.off_scale);
+        st.part_s = (float *)(ws + L.off_ps[s]); st.part_c = (int *)(ws + L.off_pc[s]);
+        st.part_f = outs[s].lse_full ? (float *)(ws + L.off_pf[s]) : nullptr;
+        SideOut o = outs[s];
+        if (o.logp) o.logp += r0;
+        if (o.row_max) o.row_max += r0;
+        if (o.lse_safe) o.lse_safe += r0;
+        if (o.lse_full) o.lse_full += r0;
+        if (o.safe_count) o.safe_count += r0;
+        const int nb = (rows + tb - 1) / tb;
         GemmArgs g;
-        g.A = (const uint16_t *)hidden; g.lda = p->ld_hidden;
-        g.B = (const uint16_t *)w_train + (int64_t)c0 * p->ld_w; g.ldb = p->ld_w;
-        g.M = n; g.N = vc; g.K = d; g.col_offset = c0;
-        EpiGrad eg{st[0], ids, dz, dzt, (int64_t)kVocabChunk, (int64_t)L.n_pad};
-        if (launch_gemm<EpiGrad, false>(g, eg, stream) != hipSuccess) return DVP_ERR_HIP;
-        // dH (+)= dz_chunk [n, vc_pad] . (W^T[:, c0 : c0 + vc_pad])^T
-        GemmArgs gh;
-        gh.A = dz; gh.lda = kVocabChunk; gh.B = wt + c0; gh.ldb = L.v_pad;
-        gh.M = n; gh.N = d; gh.K = vc_pad; gh.col_offset = 0;
-        if (launch_gemm<EpiStore, false>(gh, EpiStore{d_hidden, p->ld_hidden, chunk > 0}, stream) != hipSuccess)
-            return DVP_ERR_HIP;
-        // dW[c0 : c0 + vc, :] = dz_chunk^T [vc, n_pad] . (H^T)^T
-        GemmArgs gw;
-        gw.A = dzt; gw.lda = L.n_pad; gw.B = ht; gw.ldb = L.n_pad;
-        gw.M = vc; gw.N = d; gw.K = L.n_pad; gw.col_offset = 0;
-        if (launch_gemm<EpiStore, false>(gw, EpiStore{d_w + (int64_t)c0 * p->ld_w, p->ld_w, 0}, stream) != hipSuccess)
-            return DVP_ERR_HIP;
+        g.A = (const uint16_t *)hidden + (int64_t)r0 * p->ld_hidden; g.lda = p->ld_hidden;
+        g.B = (const uint16_t *)w_side[s]; g.ldb = p->ld_w;
+        g.M = rows; g.N = v; g.K = d;
+        hipLaunchKernelGGL(init_stats_kernel, dim3(nb), dim3(tb), 0, stream, st, rows);
+        DVP_CHECK_LAUNCH();
+        if (launch_gemm<EpiMax, false>(g, EpiMax{st, ids + r0}, stream) != hipSuccess) return DVP_ERR_HIP;
+        hipLaunchKernelGGL(after_max_kernel, dim3(nb), dim3(tb), 0, stream, st, rows, p->log_rho);
+        DVP_CHECK_LAUNCH();
+        if (write_e) {
+            if (launch_gemm<EpiSum<true>, true>(g, EpiSum<true>{st, rows, E, Et, (int64_t)L.v_pad, (int64_t)L.block_pad},
+                                                stream) != hipSuccess) return DVP_ERR_HIP;
+        } else {
+            if (launch_gemm<EpiSum<false>, true>(g, EpiSum<false>{st, rows, nullptr, nullptr, 0, 0}, stream) != hipSuccess)
+                return DVP_ERR_HIP;
+        }
+        hipLaunchKernelGGL(after_sum_kernel, dim3(nb), dim3(tb), 0, stream, st, o, ids + r0,
+                           grad_out ? grad_out + r0 : nullptr, row_flags ? row_flags + r0 : nullptr, rows, v,
+                           L.col_tiles, s);
+        DVP_CHECK_LAUNCH();
+        return DVP_OK;
+    };
+
+    RowStats st;
+    dvp_status rc;
+    if (!grad_out) {
+        if ((rc = forward(0, 0, n, false, st)) != DVP_OK) return rc;
+    } else {
+        // training side with gradient, in blocks of kRowBlock token rows
+        hipLaunchKernelGGL(transpose_bf16_kernel, dim3((d + 31) / 32, (L.v_pad + 31) / 32), dim3(32, 8), 0, stream,
+                           (const uint16_t *)w_train, p->ld_w, wt, (int64_t)L.v_pad, v, d, L.v_pad, (const float *)nullptr);
+        DVP_CHECK_LAUNCH();
+        for (int r0 = 0; r0 < n; r0 += kRowBlock) {
+            const int rows = (n - r0) < kRowBlock ? (n - r0) : kRowBlock;
+            const int rows_pad = (rows + BM - 1) / BM * BM;
+            if ((rc = forward(0, r0, rows, true, st)) != DVP_OK) return rc;
+            const uint16_t *hblock = (const uint16_t *)hidden + (int64_t)r0 * p->ld_hidden;
+            hipLaunchKernelGGL(transpose_bf16_kernel, dim3((d + 31) / 32, (rows_pad + 31) / 32), dim3(32, 8), 0, stream,
+                               hblock, p->ld_hidden, ht, (int64_t)L.block_pad, rows, d, rows_pad, (const float *)st.scale);
+            DVP_CHECK_LAUNCH();
+            // dH[r0 : r0 + rows, :] = diag(s) . E [rows, v_pad] . (W^T [d, v_pad])^T + diag(c) . W[y, :]
+            GemmArgs gh;
+            gh.A = E; gh.lda = L.v_pad; gh.B = wt; gh.ldb = L.v_pad;
+            gh.M = rows; gh.N = d; gh.K = L.v_pad;
+            const EpiStore eh{d_hidden + (int64_t)r0 * p->ld_hidden, p->ld_hidden, 0, st.scale, st.coef, ids + r0,
+                              (const uint16_t *)w_train, p->ld_w};
+            if (launch_gemm<EpiStore, false>(gh, eh, stream) != hipSuccess) return DVP_ERR_HIP;
+            // dW (+)= E^T [v, rows_pad] . ((diag(s) H)^T [d, rows_pad])^T, then its one-hot rows
+            GemmArgs gw;
+            gw.A = Et; gw.lda = L.block_pad; gw.B = ht; gw.ldb = L.block_pad;
+            gw.M = v; gw.N = d; gw.K = rows_pad;
+            const EpiStore ew{d_w, p->ld_w, r0 > 0, nullptr, nullptr, nullptr, nullptr, 0};
+            if (launch_gemm<EpiStore, false>(gw, ew, stream) != hipSuccess) return DVP_ERR_HIP;
+            hipLaunchKernelGGL(onehot_dw_kernel, dim3(rows), dim3(kOnehotThreads), 0, stream, ids + r0,
+                               (const float *)st.coef, hblock, p->ld_hidden, d_w, p->ld_w, rows, d);
+            DVP_CHECK_LAUNCH();
+        }
+    }
+    if (w_infer) {
+        if ((rc = forward(1, 0, n, false, st)) != DVP_OK) return rc;
     }
 #undef DVP_CHECK_LAUNCH
     return DVP_OK;

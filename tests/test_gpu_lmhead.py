@@ -7,9 +7,15 @@ d <= 4096).  Consequences, all stated here and checked below:
   * row maxima and lse agree to 2e-3 (the bf16-input tolerance);
   * membership is compared outside a band: |count_gpu - count_oracle| is at
     most the number of oracle logits within BAND of the ideal threshold;
-  * dz is rounded to bf16 before the two gradient products, so
-    |dH_gpu - dH| <= 2^-8 * (|dz| |W|) + ATOL and likewise for dW (first-order
-    bound from the 8 significant bits, doubled for the product's own rounding).
+  * the gradient is split as dz = c onehot - (c/S) E (Prop. 5.4).  The one-hot
+    terms, the only O(1) entries, are added in fp32.  The masked exponentials E
+    are rounded to bf16 (8 significant bits: relative error <= 2^-8) before the
+    two matrix products.  dH = c W_y + diag(-c/S) E W applies the row factor in
+    fp32, so to first order |dH_gpu - dH| <= 2^-8 (|c| p |W|) with p the pruned
+    softmax.  dW = onehot^T diag(c) H + E^T (diag(-c/S) H) rounds the scaled H
+    to bf16 as well: two roundings per term, |dW_gpu - dW| <= 2^-7 (|c| p)^T |H|.
+    Both are asserted per element with ATOL = 1e-5 + 2^-20 |reference| for the
+    fp32 accumulation.  On the workloads here that is far inside 2e-3 absolute.
 """
 import math
 
@@ -72,9 +78,11 @@ def _run(dvp, wl, rho, lse_full=False, grad=True):
     if grad:
         H64 = H.double().numpy()
         W64 = Wt.double().numpy()
-        adz = np.abs(ot["dz"])
-        bound_h = 2.0 ** -8 * (adz @ np.abs(W64)) + 1e-5
-        bound_w = 2.0 ** -8 * (adz.T @ np.abs(H64)) + 1e-5
+        soft = np.abs(ot["dz"])                       # |c| p: the part of dz that goes through bf16
+        safe_rows = np.nonzero(ot["y_in_safe"])[0]
+        soft[safe_rows, ids[safe_rows]] = np.abs(g[safe_rows]) * np.exp(ot["logp"][safe_rows])
+        bound_h = 2.0 ** -8 * (soft @ np.abs(W64)) + 1e-5 + 2.0 ** -20 * np.abs(ot["d_hidden"])
+        bound_w = 2.0 ** -7 * (soft.T @ np.abs(H64)) + 1e-5 + 2.0 ** -20 * np.abs(ot["d_w"])
         dh = res.d_hidden.cpu().double().numpy()
         dw = res.d_w.cpu().double().numpy()
         rows = same_t                                  # rows whose sampled token flipped sides are excluded
@@ -83,8 +91,11 @@ def _run(dvp, wl, rho, lse_full=False, grad=True):
         if rows.all():
             err_w = np.abs(dw - ot["d_w"]) / bound_w
             assert err_w.max() <= 1.0, "dW error is %.2f x its bound" % err_w.max()
+            print("dH at %.3f, dW at %.3f of their bounds; max abs error dH %.2e dW %.2e" %
+                  (err_h.max(), err_w.max(), np.abs(dh - ot["d_hidden"])[rows].max(), np.abs(dw - ot["d_w"]).max()))
+            assert np.abs(dw - ot["d_w"]).max() <= 2e-3 and np.abs(dh - ot["d_hidden"])[rows].max() <= 2e-3
         # and the bound is not vacuous: the gradients are far above it
-        assert np.abs(ot["d_hidden"]).max() > 20 * np.median(bound_h)
+        assert np.abs(ot["d_hidden"]).max() > 100 * np.median(bound_h)
     return res, ot, oi
 
 
@@ -94,8 +105,16 @@ def test_small_ragged_shapes(dvp):
         _run(dvp, wl, rho, lse_full=True)
 
 
-def test_multiple_vocab_chunks(dvp):
-    # V > 8192: the gradient pass walks several vocabulary chunks, the last one ragged
+def test_multiple_row_blocks(dvp):
+    # N > 4096: the gradient runs over several blocks of token rows, the last one ragged,
+    # and dW is accumulated across them
+    wl = workloads.make_lmhead(device="cuda", n=2 * 4096 + 300, d=64, v=700)
+    _run(dvp, wl, 1e-2)
+    _run(dvp, wl, 0.0)
+
+
+def test_many_column_tiles(dvp):
+    # V spans many 256-column tiles, the last one ragged
     wl = workloads.make_lmhead(device="cuda", n=300, d=256, v=20000)
     res, ot, oi = _run(dvp, wl, 1e-4)
     assert ot["safe_count"].min() > 1000            # dense-safe regime, as in the full-size case
@@ -182,10 +201,14 @@ def test_full_size_sampled_rows(dvp):
     same_t = _check_side("train", cut(res.train), ot, ot)
     _check_side("infer", cut(res.infer), oi, oi)
     W64 = Wt.double().numpy()
-    bound_h = 2.0 ** -8 * (np.abs(ot["dz"]) @ np.abs(W64)) + 1e-5
+    soft = np.abs(ot["dz"])
+    safe_rows = np.nonzero(ot["y_in_safe"])[0]
+    soft[safe_rows, ids[safe_rows]] = np.abs(g[safe_rows]) * np.exp(ot["logp"][safe_rows])
+    bound_h = 2.0 ** -8 * (soft @ np.abs(W64)) + 1e-5 + 2.0 ** -20 * np.abs(ot["d_hidden"])
     dh = res.d_hidden[ridx].cpu().double().numpy()
     err = (np.abs(dh - ot["d_hidden"]) / bound_h)[same_t]
     assert err.max() <= 1.0, "dH error is %.2f x its bound" % err.max()
+    assert np.abs(dh - ot["d_hidden"])[same_t].max() <= 2e-3
     # any-size properties on every row
     assert torch.all(res.train.safe_count >= 1) and torch.all(res.train.safe_count <= v)
     assert torch.all(res.train.lse_safe >= res.train.row_max)

@@ -255,6 +255,19 @@ struct EpiStore {
     {
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
+            // accumulate: fetch the block's old values first, all loads in flight together
+            float old[16][NI];
+            if (accumulate) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int row = r0 + mi * 32 + (i / 4) * 8 + (lane / 32) * 4 + (i % 4);
+#pragma unroll
+                    for (int ni = 0; ni < NI; ++ni) {
+                        const int col = c0 + ni * 32 + (lane % 32);
+                        old[i][ni] = (row < g.M && col < g.N) ? C[(int64_t)row * ldc + col] : 0.0f;
+                    }
+                }
+            }
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int row = r0 + mi * 32 + (i / 4) * 8 + (lane / 32) * 4 + (i % 4);
@@ -266,10 +279,9 @@ struct EpiStore {
                 for (int ni = 0; ni < NI; ++ni) {
                     const int col = c0 + ni * 32 + (lane % 32);
                     if (col >= g.N) continue;
-                    float *p = C + (int64_t)row * ldc + col;
                     float v = sc * acc[mi][ni][i];
                     if (srow) v += co * __uint_as_float((uint32_t)srow[col] << 16);
-                    *p = accumulate ? *p + v : v;
+                    C[(int64_t)row * ldc + col] = accumulate ? old[i][ni] + v : v;
                 }
             }
         }
@@ -452,20 +464,35 @@ __global__ void after_max_kernel(RowStats st, int n, float log_rho)
     }
 }
 
-// reduce the per-tile partials in tile order and write the side's outputs
-__global__ void after_sum_kernel(RowStats st, SideOut out, const int64_t *ids, const float *grad_out,
-                                 uint8_t *row_flags, int n, int vocab, int col_tiles, int side)
+// Reduce the per-tile partials and write the side's outputs.  A workgroup takes 32 rows; the
+// column tiles are cut into 8 contiguous segments, each summed in tile order by one thread per
+// row, and the 8 segment sums are combined in segment order: a fixed order, run-to-run identical.
+constexpr int kAfterRows = 32, kAfterSegs = 8;
+__global__ __launch_bounds__(kAfterRows * kAfterSegs) void after_sum_kernel(RowStats st, SideOut out, const int64_t *ids,
+                                                                            const float *grad_out, uint8_t *row_flags,
+                                                                            int n, int vocab, int col_tiles, int side)
 {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
+    __shared__ float seg_s[kAfterSegs][kAfterRows], seg_f[kAfterSegs][kAfterRows];
+    __shared__ int seg_c[kAfterSegs][kAfterRows];
+    const int r = threadIdx.x % kAfterRows, seg = threadIdx.x / kAfterRows;
+    const int i = blockIdx.x * kAfterRows + r;
+    const int per = (col_tiles + kAfterSegs - 1) / kAfterSegs;
+    const int t0 = seg * per, t1 = (t0 + per) < col_tiles ? (t0 + per) : col_tiles;
     float s = 0.0f, f = 0.0f;
     int c = 0;
-    for (int t = 0; t < col_tiles; ++t) {
-        const int64_t o = (int64_t)t * n + i;
-        s += st.part_s[o];
-        c += st.part_c[o];
-        if (st.part_f) f += st.part_f[o];
+    if (i < n) {
+        for (int t = t0; t < t1; ++t) {
+            const int64_t o = (int64_t)t * n + i;
+            s += st.part_s[o];
+            c += st.part_c[o];
+            if (st.part_f) f += st.part_f[o];
+        }
     }
+    seg_s[seg][r] = s; seg_f[seg][r] = f; seg_c[seg][r] = c;
+    __syncthreads();
+    if (seg != 0 || i >= n) return;
+#pragma unroll
+    for (int q = 1; q < kAfterSegs; ++q) { s += seg_s[q][r]; f += seg_f[q][r]; c += seg_c[q][r]; }
     const float m = st.m[i], tau = st.tau[i];
     const float log_s = logf(s);
     const int64_t y = ids[i];
@@ -684,7 +711,8 @@ dvp_status dvp_fused_lmhead(const dvp_lmhead_params *p, const void *hidden, cons
             if (launch_gemm<EpiSum<false>, true>(g, EpiSum<false>{st, rows, nullptr, nullptr, 0, 0}, stream) != hipSuccess)
                 return DVP_ERR_HIP;
         }
-        hipLaunchKernelGGL(after_sum_kernel, dim3(nb), dim3(tb), 0, stream, st, o, ids + r0,
+        hipLaunchKernelGGL(after_sum_kernel, dim3((rows + kAfterRows - 1) / kAfterRows),
+                           dim3(kAfterRows * kAfterSegs), 0, stream, st, o, ids + r0,
                            grad_out ? grad_out + r0 : nullptr, row_flags ? row_flags + r0 : nullptr, rows, v,
                            L.col_tiles, s);
         DVP_CHECK_LAUNCH();

@@ -138,12 +138,16 @@ dvp_status dvp_forward_backward(const dvp_params *params, const void *z_train,
  * LM-head variant: the logits z = H W^T are produced tile by tile on the
  * matrix cores and consumed in the tile epilogues; the [N, V] logits are never
  * stored.  Same per-row definitions as above (Def. 5.1, 5.2, Prop. 5.4); the
- * gradient is delivered as dH = dz W and dW = dz^T H.
+ * gradient is delivered as dH = dz W and dW = dz^T H.  The softmax part of dz
+ * passes through bf16 on its way into the two products; its one-hot part is
+ * added in fp32.  Results are run-to-run identical.
+ * Limits (DVP_ERR_UNSUPPORTED otherwise): hidden a multiple of 64, row strides
+ * multiples of 8 and at most 2^22 elements, vocab at most 2^22.
  */
 typedef struct {
     int64_t n_rows;    /* N */
     int64_t hidden;    /* d, a multiple of 64 */
-    int64_t vocab;     /* V */
+    int64_t vocab;     /* V, at most 2^22 */
     int64_t ld_hidden; /* row stride of hidden and d_hidden, elements, multiple of 8 */
     int64_t ld_w;      /* row stride of w_train, w_infer and d_w, elements, multiple of 8 */
     float log_rho;

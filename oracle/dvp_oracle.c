@@ -32,6 +32,22 @@
  * tolerance used against it.  No blocking, fusion or reordering: one loop per
  * formula above.
  *
+ * Sequence level (dvp_oracle_sequences, Thm. 4.1 and App. A protocol items 4
+ * and 5), per token t of a sampled sequence with constrained log-probabilities
+ * lt (training) and li (inference):
+ *
+ *   l_t   = lt - li;  -inf when lt = -inf (the constrained training
+ *           probability of the token is zero, Sec. 5.3: "the ratio is zero")
+ *   w_t   = exp(l_t)                     importance weight, item 4: the two
+ *           log-probabilities are computed independently and their
+ *           difference is exponentiated
+ *   Delta = sum_t l_t                    cumulative sequence-level mismatch
+ *           (Thm. 4.1)
+ *   veto  = some token has w_t < threshold   (item 5, threshold 1e-4),
+ *           decided as fl32(lt - li) < log_threshold in single precision so
+ *           that the decision is a well defined function of the stored
+ *           inputs; a token whose weight is NaN or +inf also vetoes.
+ *
  * Pins (tests/test_oracle_pins.py): scipy/torch log-softmax with an empty
  * prune set, scipy logsumexp with an independently built mask, probability
  * space brute force on V <= 16, torch autograd through a masked log-softmax,
@@ -221,4 +237,50 @@ int dvp_oracle_rows(const void *z, int dtype, int64_t n_rows, int64_t vocab, int
     free(th);
     free(sl);
     return rc;
+}
+
+
+/*
+ * Sequence-level importance weights and token veto (Thm. 4.1; App. A items 4, 5).
+ * Sequence s owns tokens offsets[s] .. offsets[s+1]-1.  Host pointers.
+ *   weight[t]        w_t (tokens outside every sequence are left untouched)
+ *   seq_log_ratio[s] Delta_s = sum_t l_t
+ *   seq_min_weight[s] min_t w_t (+inf for an empty sequence, NaN when a weight is NaN)
+ *   seq_veto[s]      1 when the sequence is discarded
+ * Returns 0 on success, 1 on bad arguments.
+ */
+int dvp_oracle_sequences(int64_t n_tokens, int64_t n_seq, const float *logp_train,
+                         const float *logp_infer, const int64_t *offsets, float log_threshold,
+                         double *weight, double *seq_log_ratio, double *seq_min_weight,
+                         uint8_t *seq_veto)
+{
+    if (n_tokens < 0 || n_seq < 0) return 1;
+    if (n_seq == 0) return 0;
+    if (!logp_train || !logp_infer || !offsets || !weight || !seq_log_ratio || !seq_min_weight || !seq_veto)
+        return 1;
+    for (int64_t s = 0; s < n_seq; ++s) {
+        if (offsets[s] < 0 || offsets[s + 1] < offsets[s] || offsets[s + 1] > n_tokens) return 1;
+        nsum delta = {0.0, 0.0};
+        double extreme = 0.0;      /* +-inf or NaN terms are summed outside the compensated sum */
+        double wmin = INFINITY;
+        int veto = 0, saw_nan = 0;
+        for (int64_t t = offsets[s]; t < offsets[s + 1]; ++t) {
+            const double lt = (double)logp_train[t], li = (double)logp_infer[t];
+            double l;
+            if (lt == -INFINITY) l = -INFINITY;          /* weight zero whatever li is */
+            else                 l = lt - li;
+            const double w = exp(l);
+            weight[t] = w;
+            if (isfinite(l)) nsum_add(&delta, l); else extreme += l;
+            if (w != w) saw_nan = 1;
+            else if (w < wmin) wmin = w;
+            /* the veto decision, in single precision */
+            const float l32 = (lt == -INFINITY) ? -INFINITY : (float)l;
+            if (l32 < log_threshold || l32 != l32 || l32 == INFINITY) veto = 1;
+        }
+        seq_log_ratio[s] = nsum_value(&delta) + extreme;
+        seq_min_weight[s] = saw_nan ? NAN : wmin;
+        seq_veto[s] = (uint8_t)veto;
+    }
+    return 0;
 }

@@ -57,6 +57,10 @@ def _load():
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int]
+        lib.dvp_oracle_sequences.restype = ctypes.c_int
+        lib.dvp_oracle_sequences.argtypes = [
+            ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         _lib = lib
     return _lib
 
@@ -163,4 +167,38 @@ def lmhead(hidden, w, ids, log_rho, grad_out=None, want_flags=False, band=1e-6, 
     if grad_out is not None:
         out["d_hidden"] = out["dz"] @ w64
         out["d_w"] = out["dz"].T @ h64
+    return out
+
+
+def log_threshold_f32(threshold: float) -> np.float32:
+    """The single fp32 constant log(threshold) the token veto compares with
+    (App. A, protocol item 5; threshold 1e-4 in the paper)."""
+    if not (threshold > 0.0):
+        raise ValueError("threshold must be positive")
+    return np.float32(math.log(threshold))
+
+
+def sequences(logp_train, logp_infer, offsets, log_threshold):
+    """Sequence-level importance weights and token veto (Thm. 4.1; App. A
+    protocol items 4 and 5) from the two sides' fp32 constrained log-probs.
+    offsets: int64 [n_seq + 1]; sequence s owns tokens offsets[s] .. offsets[s+1]-1.
+    Returns weight (float64 [N], NaN where no sequence owns the token),
+    seq_log_ratio, seq_min_weight (float64 [n_seq]), seq_veto (uint8 [n_seq])."""
+    lt = np.ascontiguousarray(np.asarray(logp_train, dtype=np.float32))
+    li = np.ascontiguousarray(np.asarray(logp_infer, dtype=np.float32))
+    off = np.ascontiguousarray(np.asarray(offsets, dtype=np.int64))
+    n, n_seq = lt.shape[0], off.shape[0] - 1
+    if li.shape != (n,) or n_seq < 0:
+        raise ValueError("shape mismatch")
+    out = {"weight": np.full(n, np.nan, np.float64), "seq_log_ratio": np.empty(n_seq, np.float64),
+           "seq_min_weight": np.empty(n_seq, np.float64), "seq_veto": np.empty(n_seq, np.uint8)}
+
+    def p(a):
+        return a.ctypes.data_as(ctypes.c_void_p)
+
+    rc = _load().dvp_oracle_sequences(n, n_seq, p(lt), p(li), p(off), ctypes.c_float(float(log_threshold)),
+                                      p(out["weight"]), p(out["seq_log_ratio"]), p(out["seq_min_weight"]),
+                                      p(out["seq_veto"]))
+    if rc != 0:
+        raise RuntimeError("dvp_oracle_sequences failed with code %d" % rc)
     return out

@@ -21,6 +21,11 @@ MUTATIONS = {
     "threshold_sign": ("const double tau_ideal = m + (double)J->log_rho;",
                        "const double tau_ideal = m - (double)J->log_rho;"),
     "onehot_index": ("(k == y ? 1.0 : 0.0)", "(k == y + 1 ? 1.0 : 0.0)"),
+    "weight_ratio_direction": ("else                 l = lt - li;", "else                 l = li - lt;"),
+    "veto_inclusive": ("if (l32 < log_threshold ||", "if (l32 <= log_threshold ||"),
+    "pruned_token_weight_not_zero": ("if (lt == -INFINITY) l = -INFINITY;", "if (0) l = -INFINITY;"),
+    "sequence_min_never_updated": ("else if (w < wmin) wmin = w;", "else if (w > wmin) wmin = w;"),
+    "infinite_weight_not_vetoed": ("|| l32 == INFINITY) veto = 1;", ") veto = 1;"),
 }
 
 

@@ -352,3 +352,100 @@ def test_threads_do_not_change_results():
     b = orc.rows(wl.z_train, wl.ids.numpy(), orc.log_rho_f32(1e-4), grad_out=g, want_dz=True, threads=4)
     for k in a:
         np.testing.assert_array_equal(a[k], b[k])
+
+
+# --------------------------------------------------------------------------
+# sequence level: importance weights, cumulative mismatch, token veto
+# (Thm. 4.1; App. A protocol items 4 and 5)
+# --------------------------------------------------------------------------
+def _veto_constant():
+    with open(os.path.join(GOLDEN, "paper_constants.txt")) as f:
+        for line in f:
+            if line.startswith("veto_threshold_appA"):
+                return float(line.split()[1])
+    raise AssertionError("fixture line missing")
+
+
+def test_sequence_hand_example():
+    """Two short sequences worked by hand: weights are e^(lt - li), the
+    sequence mismatch is their log-product, and 1e-4 (App. A item 5) vetoes."""
+    thr = _veto_constant()
+    assert thr == 1e-4
+    lt = np.log(np.array([0.5, 0.25, 0.2, 0.5, 1e-6], np.float64)).astype(np.float32)
+    li = np.log(np.array([0.25, 0.5, 0.2, 0.5, 0.5], np.float64)).astype(np.float32)
+    out = orc.sequences(lt, li, [0, 3, 5], orc.log_threshold_f32(thr))
+    np.testing.assert_allclose(out["weight"], [2.0, 0.5, 1.0, 1.0, 2e-6], rtol=2e-6)
+    np.testing.assert_allclose(out["seq_log_ratio"], [0.0, math.log(2e-6)], atol=1e-6)
+    np.testing.assert_allclose(out["seq_min_weight"], [0.5, 2e-6], rtol=2e-6)
+    assert out["seq_veto"].tolist() == [0, 1]
+
+
+def test_sequence_weights_against_numpy_and_identities():
+    rng = np.random.default_rng(5)
+    n, n_seq = 5000, 37
+    lt = (-3.0 * rng.random(n)).astype(np.float32)
+    li = (lt + 0.05 * rng.standard_normal(n)).astype(np.float32)
+    cuts = np.sort(rng.choice(np.arange(1, n), n_seq - 1, replace=False))
+    off = np.concatenate([[0], cuts, [n]])
+    out = orc.sequences(lt, li, off, orc.log_threshold_f32(1e-4))
+    l = lt.astype(np.float64) - li.astype(np.float64)
+    np.testing.assert_allclose(out["weight"], np.exp(l), rtol=1e-14)
+    for s in range(n_seq):
+        seg = slice(off[s], off[s + 1])
+        assert abs(out["seq_log_ratio"][s] - math.fsum(l[seg])) <= 1e-12
+        # the sequence weight is the product of the token weights (Thm. 4.1's e^{Delta_y})
+        assert abs(math.exp(out["seq_log_ratio"][s]) - np.prod(out["weight"][seg])) <= 1e-9 * np.prod(out["weight"][seg])
+        assert out["seq_min_weight"][s] == out["weight"][seg].min()
+    assert not out["seq_veto"].any()
+    # identical engines: every weight 1, no mismatch
+    same = orc.sequences(lt, lt, off, orc.log_threshold_f32(1e-4))
+    assert np.all(same["weight"] == 1.0) and np.all(same["seq_log_ratio"] == 0.0)
+
+
+def test_sequence_veto_boundary_and_conventions():
+    lthr = orc.log_threshold_f32(1e-4)
+    base = np.float32(-1.0)
+    # a token exactly at the threshold is kept (item 5 says "<"), one fp32 step below is vetoed
+    at = np.float32(base + lthr)
+    assert np.float32(at - base) == lthr
+    below = np.nextafter(at, np.float32(-np.inf))
+    out = orc.sequences([at, below], [base, base], [0, 1, 2], lthr)
+    assert out["seq_veto"].tolist() == [0, 1]
+    # a pruned sampled token under the training policy: weight zero (Sec. 5.3), sequence discarded
+    out = orc.sequences([-np.inf, -0.5, -np.inf], [-0.7, -0.5, -np.inf], [0, 2, 3], lthr)
+    assert out["weight"].tolist() == [0.0, 1.0, 0.0]
+    assert out["seq_log_ratio"].tolist() == [-np.inf, -np.inf] and out["seq_veto"].tolist() == [1, 1]
+    # undefined or infinite weights discard the sequence too; an empty sequence is kept
+    out = orc.sequences([np.nan, -0.5, -0.1], [-0.5, -np.inf, -0.1], [0, 1, 2, 2, 3], lthr)
+    assert np.isnan(out["weight"][0]) and out["weight"][1] == np.inf
+    assert out["seq_veto"].tolist() == [1, 1, 0, 0]
+    assert out["seq_min_weight"][2] == np.inf and out["seq_log_ratio"][2] == 0.0
+    # tokens owned by no sequence are not written
+    out = orc.sequences([-1.0, -1.0, -1.0], [-1.0, -1.0, -1.0], [1, 2], lthr)
+    assert np.isnan(out["weight"][0]) and out["weight"][1] == 1.0 and np.isnan(out["weight"][2])
+
+
+def test_sequence_weight_is_the_change_of_measure_of_thm_4_1():
+    """Thm. 4.1's step: an expectation under the inference policy equals the
+    expectation under the training policy of e^{-Delta_y} f(y).  Enumerate every
+    two-token sequence of a 5-token vocabulary; Delta_y comes from the oracle."""
+    rng = np.random.default_rng(9)
+    v = 5
+    zt = rng.standard_normal((1 + v, v))          # step-1 logits, then step-2 logits per first token
+    zi = zt + 0.3 * rng.standard_normal(zt.shape)
+    lpt = torch.log_softmax(torch.from_numpy(zt), -1).numpy()
+    lpi = torch.log_softmax(torch.from_numpy(zi), -1).numpy()
+    f = rng.standard_normal((v, v))
+    lt, li, off = [], [], [0]
+    for a in range(v):
+        for b in range(v):
+            lt += [lpt[0, a], lpt[1 + a, b]]
+            li += [lpi[0, a], lpi[1 + a, b]]
+            off.append(len(lt))
+    out = orc.sequences(np.array(lt, np.float32), np.array(li, np.float32), off, orc.log_threshold_f32(1e-4))
+    p_train = np.exp(np.array(lt).reshape(-1, 2).sum(1))
+    p_infer = np.exp(np.array(li).reshape(-1, 2).sum(1))
+    lhs = float((p_infer * f.ravel()).sum())
+    rhs = float((p_train * np.exp(-out["seq_log_ratio"]) * f.ravel()).sum())
+    assert abs(lhs - rhs) <= 1e-6
+    assert abs(p_train.sum() - 1.0) <= 1e-12 and abs(p_infer.sum() - 1.0) <= 1e-12

@@ -139,12 +139,60 @@ def bench_lmhead(args):
     print(json.dumps(result))
 
 
+def bench_sequences(args):
+    """Sequence-level step (importance weights, cumulative mismatch, token veto) on the paper's batch
+    shape (Sec. 6): 32 sampled sequences of up to 16384 tokens.  One step = one dvp_sequence_weights call."""
+    import numpy as np
+    import torch
+    from paper_2512_23087_amd import dvp
+    g = torch.Generator(device="cuda:0"); g.manual_seed(0xD5B0 + 5)
+    lens = torch.randint(8192, 16385, (32,), generator=g, device="cuda:0")
+    off = torch.cat([torch.zeros(1, dtype=torch.int64, device="cuda:0"), torch.cumsum(lens, 0)])
+    n = int(off[-1].item())
+    lt = -3.0 * torch.rand(n, generator=g, device="cuda:0")
+    li = lt + 0.02 * torch.randn(n, generator=g, device="cuda:0")
+    lthr = dvp.log_threshold(1e-4)
+    w = torch.empty(n, dtype=torch.float32, device="cuda:0")
+    r = torch.empty(32, dtype=torch.float32, device="cuda:0")
+    mn = torch.empty(32, dtype=torch.float32, device="cuda:0")
+    veto = torch.empty(32, dtype=torch.uint8, device="cuda:0")
+
+    def step():
+        dvp.dvp_sequence_weights(lt, li, off, lthr, weight=w, seq_log_ratio=r, seq_min_weight=mn, seq_veto=veto)
+
+    wall, per_launch = time_launches(step, args.steps, args.warmup)
+    ms = sum(per_launch) / len(per_launch)
+    nbytes = 12 * n + 33 * 8 + 32 * 9          # two fp32 log-probs in, one weight out per token; offsets; per-sequence outputs
+    result = {
+        "metric": "DVP sequence weights tokens/s and achieved HBM GB/s", "value": n * args.steps / wall,
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "32 sequences of 8192..16384 tokens (%d tokens), veto threshold 1e-4" % n,
+                   "entry_point": "dvp_sequence_weights"},
+        "roofline": {"bound": "hbm", "achieved": nbytes / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "sequence_kernel (32 workgroups: launch-latency bound at this size)",
+                     "kernel_ms_avg": ms, "algorithmic_bytes_per_launch": nbytes},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import dvp_oracle as orc
+        a, b, o = lt.cpu().numpy(), li.cpu().numpy(), off.cpu().numpy()
+        t0 = time.perf_counter(); reps = 0
+        while time.perf_counter() - t0 < 10.0:
+            orc.sequences(a, b, o, np.float32(lthr)); reps += 1
+        spent = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": n * reps / spent, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+                                  "sample": "%d passes of the fp64 C oracle over the same %d tokens, %.1f s" % (reps, n, spent)}
+    print(json.dumps(result))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "lmhead"])
+    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "lmhead", "seq"])
     ap.add_argument("--rho", type=float, default=1e-4)
     ap.add_argument("--rows", type=int, default=None, help="override N (for quick runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -168,6 +216,8 @@ def main():
     torch.cuda.set_device(0)
     if args.workload == "lmhead":
         return bench_lmhead(args)
+    if args.workload == "seq":
+        return bench_sequences(args)
     cfg = int(args.workload[-1])
     t_gen = time.perf_counter()
     wl = workloads.make_rows(cfg, device="cuda:0", n=args.rows)

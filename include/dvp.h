@@ -174,6 +174,37 @@ dvp_status dvp_fused_lmhead(const dvp_lmhead_params *params, const void *hidden,
                             const dvp_side_out *out_infer, uint8_t *row_flags, float *d_hidden,
                             float *d_w, void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Sequence-level importance weights and token veto, from the per-token
+ * outputs of the calls above (Thm. 4.1; App. A, protocol items 4 and 5).
+ * Sequence s owns the token rows seq_offsets[s] .. seq_offsets[s+1] - 1.
+ *   logp_train, logp_infer   DEVICE float [n_tokens]: log pi^mp of the sampled
+ *                  token under the training and the inference logits.
+ *   seq_offsets    DEVICE int64 [n_seq + 1], non-decreasing.  The host cannot
+ *                  see them: token indices outside [0, n_tokens) are ignored.
+ *   log_threshold  log of the veto threshold (1e-4 in the paper), see
+ *                  dvp_log_threshold; -INFINITY disables the veto rule
+ *                  (undefined and infinite weights still veto).
+ *   weight         DEVICE float [n_tokens] or NULL: w_t = exp(l_t) with
+ *                  l_t = logp_train - logp_infer (one fp32 rounding), and
+ *                  l_t = -inf, w_t = 0 when logp_train = -inf (the sampled token is
+ *                  outside the training safe set, Sec. 5.3).  Tokens owned by
+ *                  no sequence are not written.
+ *   seq_log_ratio  DEVICE float [n_seq]: Delta_s = sum_t l_t (summed in double).
+ *   seq_min_weight DEVICE float [n_seq] or NULL: min_t w_t; +inf for an empty
+ *                  sequence, NaN when some weight is NaN.
+ *   seq_veto       DEVICE uint8 [n_seq]: 1 when some token has w_t < threshold,
+ *                  decided as l_t < log_threshold on the fp32 difference, or an
+ *                  undefined (NaN) or infinite weight; else 0.
+ */
+dvp_status dvp_sequence_weights(int64_t n_tokens, int64_t n_seq, const float *logp_train,
+                                const float *logp_infer, const int64_t *seq_offsets, float log_threshold,
+                                float *weight, float *seq_log_ratio, float *seq_min_weight,
+                                uint8_t *seq_veto, void *stream);
+
+/* (float)log(threshold) for threshold > 0; NaN otherwise.  Host only. */
+float dvp_log_threshold(double threshold);
+
 /* (float)log(rho) for rho in (0, 1]; -INFINITY for rho == 0; NaN otherwise.  Host only. */
 float dvp_log_rho(double rho);
 

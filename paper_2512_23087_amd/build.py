@@ -14,7 +14,7 @@ PKG = Path(__file__).resolve().parent
 CSRC = PKG / "csrc"
 OBJ = PKG / "_build"
 LIB = PKG / "libdvp_hip.so"
-SOURCES = ["dvp_api.hip", "dvp_rows.hip", "dvp_lmhead.hip"]
+SOURCES = ["dvp_api.hip", "dvp_rows.hip", "dvp_lmhead.hip", "dvp_sequences.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

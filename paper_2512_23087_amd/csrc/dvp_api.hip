@@ -150,6 +150,31 @@ dvp_status dvp_backward(const dvp_params *params, const void *z_train, const int
     return e == hipSuccess ? DVP_OK : DVP_ERR_HIP;
 }
 
+dvp_status dvp_sequence_weights(int64_t n_tokens, int64_t n_seq, const float *logp_train,
+                                const float *logp_infer, const int64_t *seq_offsets, float log_threshold,
+                                float *weight, float *seq_log_ratio, float *seq_min_weight,
+                                uint8_t *seq_veto, void *stream)
+{
+    if (log_threshold != log_threshold) return DVP_ERR_PARAM;
+    if (n_tokens < 0 || n_seq < 0) return DVP_ERR_SHAPE;
+    if (n_seq == 0) return DVP_OK;
+    if (!logp_train || !logp_infer || !seq_offsets || !seq_log_ratio || !seq_veto) return DVP_ERR_NULL;
+    if (!aligned_to(logp_train, 4) || !aligned_to(logp_infer, 4) || !aligned_to(seq_offsets, 8) ||
+        !aligned_to(weight, 4) || !aligned_to(seq_log_ratio, 4) || !aligned_to(seq_min_weight, 4))
+        return DVP_ERR_ALIGN;
+    dvp::SequenceArgs a;
+    a.logp_train = logp_train; a.logp_infer = logp_infer; a.offsets = seq_offsets;
+    a.weight = weight; a.seq_log_ratio = seq_log_ratio; a.seq_min_weight = seq_min_weight;
+    a.seq_veto = seq_veto; a.n_tokens = n_tokens; a.n_seq = n_seq; a.log_threshold = log_threshold;
+    return dvp::launch_sequences(a, (hipStream_t)stream) == hipSuccess ? DVP_OK : DVP_ERR_HIP;
+}
+
+float dvp_log_threshold(double threshold)
+{
+    if (!(threshold > 0.0)) return NAN;
+    return (float)log(threshold);
+}
+
 int dvp_row_path(const dvp_params *params, int aligned16)
 {
     if (check_params(params, false, false) != DVP_OK) return -1;

@@ -65,6 +65,18 @@ struct BackwardArgs {
     float log_rho;
 };
 
+struct SequenceArgs {
+    const float *logp_train;
+    const float *logp_infer;
+    const int64_t *offsets;   // [n_seq + 1]
+    float *weight;            // [n_tokens] or null
+    float *seq_log_ratio;     // [n_seq]
+    float *seq_min_weight;    // [n_seq] or null
+    uint8_t *seq_veto;        // [n_seq]
+    int64_t n_tokens, n_seq;
+    float log_threshold;
+};
+
 // true when the register-resident kernel can take a row of this many elements
 bool row_fits_resident(int dtype, int64_t vocab);
 
@@ -73,5 +85,6 @@ hipError_t launch_rows_resident(int dtype, const RowArgs &a, hipStream_t stream)
 hipError_t launch_rows_streaming(int dtype, const RowArgs &a, hipStream_t stream);
 hipError_t launch_grad_fill(int dtype, const FillArgs &a, hipStream_t stream);
 hipError_t launch_backward(int dtype, const BackwardArgs &a, bool vector_ok, hipStream_t stream);
+hipError_t launch_sequences(const SequenceArgs &a, hipStream_t stream);
 
 }  // namespace dvp

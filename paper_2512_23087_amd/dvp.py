@@ -21,7 +21,8 @@ DVP_F32, DVP_BF16 = 0, 1
 ROW_Y_IN_TRAIN_SAFE, ROW_Y_IN_INFER_SAFE, ROW_ID_OUT_OF_RANGE = 1, 2, 4
 
 EXPORTS = ("dvp_forward", "dvp_backward", "dvp_forward_backward", "dvp_fused_lmhead",
-           "dvp_fused_lmhead_workspace_bytes", "dvp_log_rho", "dvp_status_string", "dvp_row_path")
+           "dvp_fused_lmhead_workspace_bytes", "dvp_log_rho", "dvp_status_string", "dvp_row_path",
+           "dvp_sequence_weights", "dvp_log_threshold")
 
 
 class DvpParams(ctypes.Structure):
@@ -80,6 +81,11 @@ def lib():
         L.dvp_status_string.argtypes = [ctypes.c_int]
         L.dvp_row_path.restype = ctypes.c_int
         L.dvp_row_path.argtypes = [pp, ctypes.c_int]
+        L.dvp_sequence_weights.restype = ctypes.c_int
+        L.dvp_sequence_weights.argtypes = [ctypes.c_int64, ctypes.c_int64, vp, vp, i64p, ctypes.c_float,
+                                           vp, vp, vp, vp, vp]
+        L.dvp_log_threshold.restype = ctypes.c_float
+        L.dvp_log_threshold.argtypes = [ctypes.c_double]
         _lib = L
     return _lib
 
@@ -263,3 +269,40 @@ def dvp_fused_lmhead(hidden, w_train, w_infer, ids, grad_out, log_rho_value, *, 
     if st != 0:
         raise DvpError(st, "dvp_fused_lmhead")
     return LmHeadResult(out_train, out_infer, row_flags, d_hidden, d_w)
+
+
+class SequenceResult:
+    def __init__(self, weight, seq_log_ratio, seq_min_weight, seq_veto):
+        self.weight, self.seq_log_ratio = weight, seq_log_ratio
+        self.seq_min_weight, self.seq_veto = seq_min_weight, seq_veto
+
+
+def log_threshold(threshold: float) -> float:
+    """(float)log(threshold) as the library computes it (token veto, 1e-4 in the paper)."""
+    return float(lib().dvp_log_threshold(float(threshold)))
+
+
+def dvp_sequence_weights(logp_train, logp_infer, seq_offsets, log_threshold_value, *, weight=None,
+                         seq_log_ratio=None, seq_min_weight=None, seq_veto=None,
+                         stream=None) -> SequenceResult:
+    for name, t in (("logp_train", logp_train), ("logp_infer", logp_infer)):
+        if not t.is_cuda or t.dtype != torch.float32 or t.dim() != 1 or not t.is_contiguous():
+            raise ValueError("%s must be a contiguous float32 [N] GPU tensor" % name)
+    if not seq_offsets.is_cuda or seq_offsets.dtype != torch.int64 or seq_offsets.dim() != 1:
+        raise ValueError("seq_offsets must be an int64 [n_seq + 1] GPU tensor")
+    n, n_seq = logp_train.shape[0], seq_offsets.shape[0] - 1
+    dev = logp_train.device
+    if weight is None:
+        weight = torch.empty(n, dtype=torch.float32, device=dev)
+    if seq_log_ratio is None:
+        seq_log_ratio = torch.empty(n_seq, dtype=torch.float32, device=dev)
+    if seq_min_weight is None:
+        seq_min_weight = torch.empty(n_seq, dtype=torch.float32, device=dev)
+    if seq_veto is None:
+        seq_veto = torch.empty(n_seq, dtype=torch.uint8, device=dev)
+    st = lib().dvp_sequence_weights(n, n_seq, _ptr(logp_train), _ptr(logp_infer), _ptr(seq_offsets),
+                                    float(log_threshold_value), _ptr(weight), _ptr(seq_log_ratio),
+                                    _ptr(seq_min_weight), _ptr(seq_veto), _stream(stream))
+    if st != 0:
+        raise DvpError(st, "dvp_sequence_weights")
+    return SequenceResult(weight, seq_log_ratio, seq_min_weight, seq_veto)

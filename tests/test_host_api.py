@@ -102,3 +102,19 @@ def test_binding_refuses_cpu_tensors():
     z = torch.zeros(2, 8, dtype=torch.bfloat16)
     with pytest.raises(ValueError):
         dvp.dvp_forward(z, None, torch.zeros(2, dtype=torch.int64), -1.0)
+
+
+def test_sequence_weights_validation_needs_no_gpu():
+    L = dvp.lib()
+
+    def call(n_tokens=8, n_seq=0, lt=FAKE, li=FAKE, off=FAKE, lthr=-9.0, w=FAKE, r=FAKE, mn=FAKE, v=FAKE):
+        return L.dvp_sequence_weights(n_tokens, n_seq, lt, li, off, lthr, w, r, mn, v, None)
+
+    assert call() == 0 and call(lt=None, off=None) == 0       # zero sequences: nothing to do
+    assert call(n_seq=-1) == 2 and call(n_tokens=-1) == 2
+    assert call(lthr=float("nan")) == 3
+    assert call(n_seq=1, lt=None) == 1 and call(n_seq=1, off=None) == 1 and call(n_seq=1, v=None) == 1
+    assert call(n_seq=1, r=None) == 1
+    assert call(n_seq=1, off=FAKE + 4) == 4 and call(n_seq=1, w=FAKE + 2) == 4
+    assert dvp.log_threshold(1e-4) == pytest.approx(math.log(1e-4), rel=1e-7)
+    assert math.isnan(dvp.log_threshold(0.0)) and math.isnan(dvp.log_threshold(-1.0))

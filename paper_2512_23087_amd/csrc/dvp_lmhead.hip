@@ -85,6 +85,7 @@ struct GemmArgs {
 // pass B's sums.
 // ---------------------------------------------------------------------------
 struct EpiMax {
+    static constexpr bool kUsesTileLds = false;
     RowStats st;
     const int64_t *ids;
     __device__ __forceinline__ void operator()(const GemmArgs &g, f32x16 (&acc)[MI][NI], int r0, int c0, int lane, uint8_t *, int, int) const
@@ -127,6 +128,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)   // hardwar
 // dimension of the two gradient products).
 template <bool WRITE_E>
 struct EpiSum {
+    static constexpr bool kUsesTileLds = WRITE_E;   // the bf16 staging lives in the operand tiles
     RowStats st;
     int n_rows;
     uint16_t *E, *Et;
@@ -243,6 +245,7 @@ struct EpiSum {
 };
 
 struct EpiStore {
+    static constexpr bool kUsesTileLds = false;
     float *C;                // [M, ldc] fp32
     int64_t ldc;
     int accumulate;          // 0: C = v, 1: C += v
@@ -314,70 +317,74 @@ __device__ __forceinline__ void wait_copies_and_barrier()
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+// where a workgroup's tile sits and how its lanes address the operand rows
+struct TilePlace {
+    const uint8_t *baseA, *baseB;                        // first row of the A tile / B tile
+    uint32_t off_a[kCopiesPerWave], off_b[kCopiesPerWave];   // per-lane byte offsets of the wavefront copies
+    int tile_m, tile_n;
+};
+
+// Persistent: the grid has one workgroup per CU and each walks its share of the tiles.  Unless the
+// epilogue needs the tile buffers, the first two K steps of the next tile are copied under the last
+// two K steps of the current one, so only the epilogue itself separates the MFMA streams of two tiles.
 template <class Epi, bool NEEDS_FINISH>
 __global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs g, const Epi epi, int tiles_m, int tiles_n)
 {
-    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];   // [stage][A | B][256 rows][128 B]
-
-    // Tile order.  Hardware deals workgroups round-robin to the 8 XCDs; give each
-    // XCD a contiguous range of the walk below so that the 32 workgroups resident
-    // on it cover 4 row tiles x 8 column tiles and share operand tiles in its L2.
-    const int total = tiles_m * tiles_n;
-    const int per_xcd = total / 8;
-    int pid = blockIdx.x;
-    if (pid < per_xcd * 8) pid = (pid % 8) * per_xcd + pid / 8;
-    constexpr int GROUP = 4;
-    const int per_group = GROUP * tiles_n;
-    const int group = pid / per_group;
-    const int first_m = group * GROUP;
-    const int group_rows = (tiles_m - first_m) < GROUP ? (tiles_m - first_m) : GROUP;
-    const int in_group = pid - group * per_group;
-    const int tile_m = first_m + in_group % group_rows;
-    const int tile_n = in_group / group_rows;
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];   // [stage][A | B][256 rows][128 B], then sums scratch
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave), lane = tid % kWave;
     const int wm = wave / WN, wn = wave % WN;
+    const int total = tiles_m * tiles_n;
 
+    // Tile order.  Hardware deals workgroups round-robin to the 8 XCDs and the grid is a multiple of
+    // 8 (or smaller than the tile count is not: then it equals it), so launch position t always runs
+    // on XCD t % 8.  Each XCD gets a contiguous range of the walk below, so that the 32 workgroups
+    // resident on it cover 4 row tiles x 8 column tiles and share operand tiles in its L2.
     // global -> LDS: copy c of a tile (c = i * 8 + wave) fills LDS chunks 64 c .. 64 c + 63, i.e. tile
     // rows 8 c .. 8 c + 7; the chunk at physical position p of row r holds logical chunk p ^ (r & 7).
-    const uint8_t *baseA = (const uint8_t *)(g.A + (int64_t)tile_m * BM * g.lda);
-    const uint8_t *baseB = (const uint8_t *)(g.B + (int64_t)tile_n * BN * g.ldb);
-    const int rows_a = g.M - tile_m * BM, rows_b = g.N - tile_n * BN;   // >= 1; rows past the end repeat the last one
-    uint32_t off_a[kCopiesPerWave], off_b[kCopiesPerWave];
+    auto place = [&](int t, TilePlace &tp) {
+        const int per_xcd = total / 8;
+        int pid = t;
+        if (pid < per_xcd * 8) pid = (pid % 8) * per_xcd + pid / 8;
+        constexpr int GROUP = 4;
+        const int per_group = GROUP * tiles_n;
+        const int group = pid / per_group;
+        const int first_m = group * GROUP;
+        const int group_rows = (tiles_m - first_m) < GROUP ? (tiles_m - first_m) : GROUP;
+        const int in_group = pid - group * per_group;
+        tp.tile_m = first_m + in_group % group_rows;
+        tp.tile_n = in_group / group_rows;
+        tp.baseA = (const uint8_t *)(g.A + (int64_t)tp.tile_m * BM * g.lda);
+        tp.baseB = (const uint8_t *)(g.B + (int64_t)tp.tile_n * BN * g.ldb);
+        const int rows_a = g.M - tp.tile_m * BM, rows_b = g.N - tp.tile_n * BN;   // >= 1; rows past the end repeat the last one
 #pragma unroll
-    for (int i = 0; i < kCopiesPerWave; ++i) {
-        const int p = (i * kGemmWaves + wave) * kWave + lane;
-        const int row = p >> 3, kc = (p & 7) ^ (row & 7);
-        const int ra = row < rows_a ? row : rows_a - 1;
-        const int rb = row < rows_b ? row : rows_b - 1;
-        off_a[i] = (uint32_t)(((int64_t)ra * g.lda + kc * 8) * 2);
-        off_b[i] = (uint32_t)(((int64_t)rb * g.ldb + kc * 8) * 2);
-    }
+        for (int i = 0; i < kCopiesPerWave; ++i) {
+            const int p = (i * kGemmWaves + wave) * kWave + lane;
+            const int row = p >> 3, kc = (p & 7) ^ (row & 7);
+            const int ra = row < rows_a ? row : rows_a - 1;
+            const int rb = row < rows_b ? row : rows_b - 1;
+            tp.off_a[i] = (uint32_t)(((int64_t)ra * g.lda + kc * 8) * 2);
+            tp.off_b[i] = (uint32_t)(((int64_t)rb * g.ldb + kc * 8) * 2);
+        }
+    };
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)lds;
-    auto issue_copies = [&](int kt, int stage) {
-        const uint8_t *pa = baseA + (size_t)kt * kRowBytes;
-        const uint8_t *pb = baseB + (size_t)kt * kRowBytes;
+    auto issue_copies = [&](const TilePlace &tp, int kt, int stage) {
+        const uint8_t *pa = tp.baseA + (size_t)kt * kRowBytes;
+        const uint8_t *pb = tp.baseB + (size_t)kt * kRowBytes;
         const uint32_t sa = lds_base + stage * kStageBytes;
 #pragma unroll
-        for (int i = 0; i < kCopiesPerWave; ++i) copy16_to_lds(pa, off_a[i], sa + (i * kGemmWaves + wave) * 1024);
+        for (int i = 0; i < kCopiesPerWave; ++i) copy16_to_lds(pa, tp.off_a[i], sa + (i * kGemmWaves + wave) * 1024);
 #pragma unroll
-        for (int i = 0; i < kCopiesPerWave; ++i) copy16_to_lds(pb, off_b[i], sa + kTileBytes + (i * kGemmWaves + wave) * 1024);
+        for (int i = 0; i < kCopiesPerWave; ++i) copy16_to_lds(pb, tp.off_b[i], sa + kTileBytes + (i * kGemmWaves + wave) * 1024);
     };
-
-    f32x16 acc[MI][NI];
-#pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.0f;
 
     // operand fetch: lane l reads row (l % 32), the 8 consecutive k of chunk 2 * ks + l / 32.
     // Rows 32 apart share (row & 7), so one swizzle key serves all row blocks.
     const int frow = lane % 32, half = lane / 32, key = lane & 7;
     const int a_off = (wm * MI * 32 + frow) * kRowBytes;
     const int b_off = kTileBytes + (wn * NI * 32 + frow) * kRowBytes;
+    f32x16 acc[MI][NI];
     bf16x8 fa[2][MI], fb[2][NI];
     auto fetch = [&](int buf, int stage, int ks) {
         const uint8_t *sb = lds + stage * kStageBytes;
@@ -404,29 +411,72 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs
     };
 
     const int nk = g.K / BK;
-    issue_copies(0, 0);
+    const bool chain = !Epi::kUsesTileLds && nk >= 2;
+    int t = blockIdx.x;                 // < total: the launcher never starts more workgroups than tiles
+    int sp = 0;                         // LDS stage that holds K step 0 of the current tile
+    TilePlace cur, nxt;
+    place(t, cur);
+    issue_copies(cur, 0, 0);
     wait_copies_and_barrier();
-    if (nk > 1) issue_copies(1, 1);
+    if (nk > 1) issue_copies(cur, 1, 1);
     fetch(0, 0, 0);
-    for (int j = 0; j < nk; ++j) {
-        const int stage = j & 1;
-        fetch(1, stage, 1); multiply(0);
-        fetch(0, stage, 2); multiply(1);
-        fetch(1, stage, 3); multiply(0);
-        // own reads of tile j are home, own copies of tile j+1 have landed; past the
-        // barrier that holds for every wavefront
-        wait_copies_and_barrier();
-        if (j + 2 < nk) issue_copies(j + 2, stage);
-        fetch(0, stage ^ 1, 0);             // after the last tile: reads a dead buffer, unused
-        multiply(1);
-    }
+    for (;;) {
+        const int t_next = t + (int)gridDim.x;
+        const bool has_next = t_next < total;
+        if (has_next) place(t_next, nxt);
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.0f;
 
-    // every wavefront is past the last barrier: the operand tiles are dead, the epilogue may reuse them
-    epi(g, acc, tile_m * BM + wm * (MI * 32), tile_n * BN + wn * (NI * 32), lane, lds, wave, wn);
-    if constexpr (NEEDS_FINISH) {
-        __syncthreads();
-        epi.finish(g, tile_m * BM, tile_n, lds, tid);
+        for (int j = 0; j < nk; ++j) {
+            const int stage = (sp + j) & 1;
+            fetch(1, stage, 1); multiply(0);
+            fetch(0, stage, 2); multiply(1);
+            fetch(1, stage, 3); multiply(0);
+            // own reads of K step j are home, own copies of step j+1 have landed; past the
+            // barrier that holds for every wavefront
+            wait_copies_and_barrier();
+            if (j + 2 < nk) issue_copies(cur, j + 2, stage);
+            else if (chain && has_next) issue_copies(nxt, j + 2 - nk, stage);
+            fetch(0, stage ^ 1, 0);         // step j+1, or step 0 of the next tile; unused (dead buffer) otherwise
+            multiply(1);
+        }
+
+        // every wavefront is past the tile's last barrier and its last useful fetch
+        epi(g, acc, cur.tile_m * BM + wm * (MI * 32), cur.tile_n * BN + wn * (NI * 32), lane, lds, wave, wn);
+        if constexpr (NEEDS_FINISH) {
+            __syncthreads();
+            epi.finish(g, cur.tile_m * BM, cur.tile_n, lds, tid);
+        }
+        if (!has_next) break;
+        sp = (sp + nk) & 1;
+        if (!chain) {
+            __syncthreads();                // the tile buffers are free again in every wavefront
+            issue_copies(nxt, 0, sp);
+            wait_copies_and_barrier();
+            if (nk > 1) issue_copies(nxt, 1, sp ^ 1);
+            fetch(0, sp, 0);
+        }
+        cur = nxt;
+        t = t_next;
     }
+}
+
+static int gemm_cu_count()
+{
+    static int cached = 0;
+    if (cached == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            cached = n;
+        else
+            return 256;
+    }
+    return cached;
 }
 
 template <class Epi, bool NEEDS_FINISH>
@@ -440,8 +490,12 @@ static hipError_t launch_gemm(const GemmArgs &g, const Epi &epi, hipStream_t str
         configured = true;
     }
     const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
-    hipLaunchKernelGGL((gemm_nt_kernel<Epi, NEEDS_FINISH>), dim3((unsigned)(tiles_m * tiles_n)),
-                       dim3(kGemmThreads), kGemmLdsBytes, stream, g, epi, tiles_m, tiles_n);
+    const int total = tiles_m * tiles_n;
+    int grid = gemm_cu_count() / 8 * 8;     // one workgroup per CU; a multiple of the XCD count
+    if (grid < 8) grid = 8;
+    if (grid > total) grid = total;
+    hipLaunchKernelGGL((gemm_nt_kernel<Epi, NEEDS_FINISH>), dim3((unsigned)grid), dim3(kGemmThreads),
+                       kGemmLdsBytes, stream, g, epi, tiles_m, tiles_n);
     return hipGetLastError();
 }
 

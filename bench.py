@@ -195,6 +195,9 @@ def main():
     ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "lmhead", "seq"])
     ap.add_argument("--rho", type=float, default=1e-4)
     ap.add_argument("--rows", type=int, default=None, help="override N (for quick runs)")
+    ap.add_argument("--sparse-grad", type=int, default=0, metavar="CAP",
+                    help="deliver the gradient as per-row (index, value) lists of at most CAP entries "
+                         "(dvp_forward_backward_sparse) instead of the dense matrix")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
@@ -232,9 +235,19 @@ def main():
     flags = torch.empty(n, dtype=torch.uint8, device="cuda:0")
     dz = torch.empty_like(wl.z_train)
 
-    def step(log_rho_value=lr):
-        dvp.dvp_forward_backward(wl.z_train, wl.z_infer, wl.ids, wl.grad_out, log_rho_value,
-                                 out_train=out_t, out_infer=out_i, row_flags=flags, dz=dz)
+    if args.sparse_grad:
+        del dz
+        entries = torch.empty(n, args.sparse_grad, 2, dtype=torch.int32, device="cuda:0")
+        glen = torch.empty(n, dtype=torch.int32, device="cuda:0")
+
+        def step(log_rho_value=lr):
+            dvp.dvp_forward_backward_sparse(wl.z_train, wl.z_infer, wl.ids, wl.grad_out, log_rho_value,
+                                            args.sparse_grad, out_train=out_t, out_infer=out_i,
+                                            row_flags=flags, entries=entries, grad_len=glen)
+    else:
+        def step(log_rho_value=lr):
+            dvp.dvp_forward_backward(wl.z_train, wl.z_infer, wl.ids, wl.grad_out, log_rho_value,
+                                     out_train=out_t, out_infer=out_i, row_flags=flags, dz=dz)
 
     if args.copy_probe:
         for _ in range(3):
@@ -244,10 +257,14 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
     kernel_ms = sum(per_launch) / len(per_launch)
     bytes_per_launch = algorithmic_bytes_per_row(v, elem) * n
+    if args.sparse_grad:
+        # no dense gradient row; the lists that were written (8 bytes per entry) and their lengths instead
+        listed = glen[(flags & 8) == 0].to(torch.int64).sum().item()
+        bytes_per_launch += -v * elem * n + 8 * listed + 4 * n
     achieved = bytes_per_launch / (kernel_ms * 1e-3) / 1e9
 
     traffic = MEASURED_TRAFFIC.get(kernel_source_hash(), {}).get(args.workload) \
-        if args.rows is None and args.rho == 1e-4 else None
+        if args.rows is None and args.rho == 1e-4 and not args.sparse_grad else None
 
     result = {
         "metric": "DVP fwd+bwd rows/s and achieved HBM GB/s (% of peak), V=151936 bf16",
@@ -260,13 +277,16 @@ def main():
         "config": {"workload": "configs[%d]: N=%d x V=%d %s logits (train + infer), fused "
                                "forward+backward, rho=%g" % (cfg, n, v, str(wl.z_train.dtype)[6:], args.rho),
                    "storage_dtype": str(wl.z_train.dtype)[6:], "n_rows": n, "vocab": v,
-                   "rho": args.rho, "entry_point": "dvp_forward_backward",
+                   "rho": args.rho,
+                   "entry_point": "dvp_forward_backward_sparse (list capacity %d)" % args.sparse_grad
+                   if args.sparse_grad else "dvp_forward_backward",
                    "row_kernel": "resident" if dvp.lib().dvp_row_path(
                        dvp.DvpParams(n, v, v, v, v, 1 if elem == 2 else 0, lr), 1) == 1 else "streaming",
                    "input_generation_s": round(t_gen, 2)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": "rows_resident_kernel + grad_zero_kernel + grad_scatter_kernel "
+                     "kernel": "rows_resident_kernel (gradient as lists)" if args.sparse_grad else
+                               "rows_resident_kernel + grad_zero_kernel + grad_scatter_kernel "
                                "(one dvp_forward_backward call; durations summed)",
                      "kernel_ms_avg": kernel_ms, "kernel_ms_min": min(per_launch),
                      "algorithmic_bytes_per_launch": bytes_per_launch},
@@ -277,7 +297,9 @@ def main():
     result["safe_set"] = {"mean": cnt.mean().item(), "median": cnt.median().item(),
                           "max": cnt.max().item(),
                           "y_in_train_safe_frac": (flags & 1).to(torch.float64).mean().item()}
-    if not args.no_sweep:
+    if args.sparse_grad:
+        result["overflow_rows"] = int(((flags & 8) != 0).sum().item())
+    if not args.no_sweep and not args.sparse_grad:
         sweep = []
         for rho in wl.rhos:
             lr_s = dvp.log_rho(rho)

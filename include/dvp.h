@@ -42,7 +42,7 @@ typedef enum {
     DVP_ERR_SHAPE = 2,       /* negative sizes, vocab < 1, ld < vocab, vocab > DVP_MAX_VOCAB */
     DVP_ERR_PARAM = 3,       /* log_rho is NaN or > 0, unknown dtype */
     DVP_ERR_ALIGN = 4,       /* a pointer is not aligned to its element size */
-    DVP_ERR_UNSUPPORTED = 5, /* shape outside what the fused LM-head kernels handle */
+    DVP_ERR_UNSUPPORTED = 5, /* shape or alignment outside what the entry point handles */
     DVP_ERR_WORKSPACE = 6,   /* workspace missing or too small */
     DVP_ERR_HIP = 7          /* the HIP runtime refused a launch */
 } dvp_status;
@@ -55,7 +55,9 @@ typedef enum { DVP_F32 = 0, DVP_BF16 = 1 } dvp_dtype;
 enum {
     DVP_ROW_Y_IN_TRAIN_SAFE = 1, /* sampled id is in V_S  (training logits)  */
     DVP_ROW_Y_IN_INFER_SAFE = 2, /* sampled id is in V'_S (inference logits) */
-    DVP_ROW_ID_OUT_OF_RANGE = 4  /* id < 0 or id >= V: log-probs are NaN, gradient row is zero */
+    DVP_ROW_ID_OUT_OF_RANGE = 4, /* id < 0 or id >= V: log-probs are NaN, gradient row is zero */
+    DVP_ROW_GRAD_OVERFLOW = 8    /* dvp_forward_backward_sparse only: the safe set has more than
+                                    list_cap tokens, no gradient entry was written for this row */
 };
 
 typedef struct {
@@ -133,6 +135,37 @@ dvp_status dvp_forward_backward(const dvp_params *params, const void *z_train,
                                 const void *z_infer, const int64_t *ids, const float *grad_out,
                                 const dvp_side_out *out_train, const dvp_side_out *out_infer,
                                 uint8_t *row_flags, void *dz, void *stream);
+
+/*
+ * Forward and backward with the gradient delivered as per-row lists instead of
+ * a dense [N, V] matrix: Prop. 5.4's gradient is zero outside the safe set, so
+ * a row has at most |V_S| non-zero entries.  HBM then sees both logit rows
+ * once and only the lists are written.
+ *   entries   DEVICE [N, list_cap] of (index, value): row i's first grad_len[i]
+ *             entries hold every token k of its safe set (in no particular
+ *             order) with value = dz_ik in fp32, exactly as defined for
+ *             dvp_backward; entries beyond grad_len[i] are not written.
+ *   grad_len  DEVICE int32 [N] or NULL: |V_S| when y_i is in V_S, else 0 (the
+ *             whole gradient row is zero).
+ *   list_cap  1 .. DVP_MAX_LIST_CAP.  A row with |V_S| > list_cap gets
+ *             DVP_ROW_GRAD_OVERFLOW in row_flags and no entries (grad_len still
+ *             reports |V_S|); the caller can run dvp_backward on those rows.
+ *   row_flags is required.  params->ld_grad is ignored.
+ * Only the single-read path takes this call: 16-byte aligned rows that fit the
+ * register file (see the conventions above), else DVP_ERR_UNSUPPORTED.
+ */
+typedef struct {
+    uint32_t index;
+    float value;
+} dvp_grad_entry;
+
+#define DVP_MAX_LIST_CAP 65536
+
+dvp_status dvp_forward_backward_sparse(const dvp_params *params, const void *z_train,
+                                       const void *z_infer, const int64_t *ids, const float *grad_out,
+                                       const dvp_side_out *out_train, const dvp_side_out *out_infer,
+                                       uint8_t *row_flags, dvp_grad_entry *entries, int32_t *grad_len,
+                                       int32_t list_cap, void *stream);
 
 /*
  * LM-head variant: the logits z = H W^T are produced tile by tile on the

@@ -84,6 +84,8 @@ dvp_status run_rows(const dvp_params *p, const void *z_train, const void *z_infe
     a.n_sides = z_infer ? 2 : 1;
     a.log_rho = p->log_rho;
 
+    a.sparse_only = 0;
+    a.grad_len = nullptr;
     const bool resident = dvp::row_fits_resident(p->dtype, p->vocab) &&
                           rows_vector_ok(p, z_train, z_infer, backward ? dz : nullptr);
     // Split gradient: possible when the per-row flags and safe-set sizes are
@@ -122,6 +124,41 @@ dvp_status dvp_forward_backward(const dvp_params *params, const void *z_train,
 {
     return run_rows(params, z_train, z_infer, ids, grad_out, out_train, out_infer, row_flags, dz,
                     true, stream);
+}
+
+dvp_status dvp_forward_backward_sparse(const dvp_params *params, const void *z_train,
+                                       const void *z_infer, const int64_t *ids, const float *grad_out,
+                                       const dvp_side_out *out_train, const dvp_side_out *out_infer,
+                                       uint8_t *row_flags, dvp_grad_entry *entries, int32_t *grad_len,
+                                       int32_t list_cap, void *stream)
+{
+    dvp_status st = check_params(params, z_infer != nullptr, false);
+    if (st != DVP_OK) return st;
+    if (list_cap < 1 || list_cap > DVP_MAX_LIST_CAP) return DVP_ERR_PARAM;
+    if (params->n_rows == 0) return DVP_OK;
+    if (!z_train || !ids || !out_train || !grad_out || !row_flags || !entries) return DVP_ERR_NULL;
+    const size_t es = elem_size(params->dtype);
+    if (!aligned_to(z_train, es) || !aligned_to(z_infer, es) || !aligned_to(ids, 8) ||
+        !aligned_to(grad_out, 4) || !aligned_to(entries, 8) || !aligned_to(grad_len, 4) ||
+        !side_aligned(out_train) || (z_infer && !side_aligned(out_infer)))
+        return DVP_ERR_ALIGN;
+    // the lists are formed from rows held in registers: single-read path only
+    if (!dvp::row_fits_resident(params->dtype, params->vocab) || !rows_vector_ok(params, z_train, z_infer, nullptr))
+        return DVP_ERR_UNSUPPORTED;
+
+    RowArgs a;
+    a.z[0] = z_train; a.z[1] = z_infer;
+    a.ld[0] = params->ld_train; a.ld[1] = z_infer ? params->ld_infer : 0;
+    a.out[0] = to_side(out_train);
+    a.out[1] = to_side(z_infer ? out_infer : nullptr);
+    a.ids = ids; a.grad_out = grad_out;
+    a.dz = entries; a.ld_grad = 0;
+    a.row_flags = row_flags;
+    a.n_rows = params->n_rows; a.vocab = (int32_t)params->vocab;
+    a.n_sides = z_infer ? 2 : 1;
+    a.log_rho = params->log_rho;
+    a.split_grad = 1; a.list_cap = list_cap; a.sparse_only = 1; a.grad_len = grad_len;
+    return dvp::launch_rows_resident(params->dtype, a, (hipStream_t)stream) == hipSuccess ? DVP_OK : DVP_ERR_HIP;
 }
 
 dvp_status dvp_backward(const dvp_params *params, const void *z_train, const int64_t *ids,
@@ -198,7 +235,7 @@ const char *dvp_status_string(dvp_status status)
     case DVP_ERR_SHAPE: return "invalid shape or row stride";
     case DVP_ERR_PARAM: return "invalid parameter (dtype, or log_rho is NaN or positive)";
     case DVP_ERR_ALIGN: return "pointer not aligned to its element size";
-    case DVP_ERR_UNSUPPORTED: return "shape not supported by the fused LM-head kernels";
+    case DVP_ERR_UNSUPPORTED: return "shape or alignment not supported by this entry point";
     case DVP_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case DVP_ERR_HIP: return "HIP runtime error at kernel launch";
     }

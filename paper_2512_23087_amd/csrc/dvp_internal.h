@@ -36,6 +36,10 @@ struct RowArgs {
     // launch_grad_fill() writes the row.  Needs row_flags and out[0].safe_count.
     int32_t split_grad;
     int32_t list_cap;
+    // List-only output: dz is a [n_rows, list_cap] array of (index, value) pairs and no dense row is
+    // ever written; rows whose safe set exceeds list_cap get DVP_ROW_GRAD_OVERFLOW.  Needs split_grad.
+    int32_t sparse_only;
+    int32_t *grad_len;       // [n_rows] or null: entries per row (the safe-set size, 0 when y is pruned)
 };
 
 struct FillArgs {

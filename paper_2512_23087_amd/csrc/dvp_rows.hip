@@ -253,7 +253,11 @@ __global__ __launch_bounds__(NT, MINW) void rows_resident_kernel(const RowArgs a
         const float log_s = logf(acc.s_safe);
         const bool y_safe = y_ok && (zy >= tau);
         if (y_safe) flags |= (side == 0 ? DVP_ROW_Y_IN_TRAIN_SAFE : DVP_ROW_Y_IN_INFER_SAFE);
+        // list-only output: a safe set longer than the list's capacity is reported, not written
+        const bool overflow = a.sparse_only && bwd_here && y_safe && acc.count > a.list_cap;
+        if (overflow) flags |= DVP_ROW_GRAD_OVERFLOW;
         if (tid == 0) {
+            if (bwd_here && a.grad_len) a.grad_len[row] = y_safe ? acc.count : 0;
             if (out.row_max) out.row_max[row] = m;
             if (out.lse_safe) out.lse_safe[row] = m + log_s;
             if (want_full) out.lse_full[row] = m + logf(acc.s_full);
@@ -270,26 +274,28 @@ __global__ __launch_bounds__(NT, MINW) void rows_resident_kernel(const RowArgs a
         // pairs at the start of the gradient row; the fill kernel writes the row
         // afterwards, so this kernel's memory traffic stays (almost) read-only.
         if (bwd_here) {
-            T *dzrow = (T *)a.dz + row * a.ld_grad;
+            const bool dense_out = !a.sparse_only;
+            T *dzrow = (T *)a.dz + (dense_out ? row * a.ld_grad : 0);
             u32x4 *dzvec = (u32x4 *)dzrow;
-            uint2 *list = (uint2 *)dzrow;
+            uint2 *list = dense_out ? (uint2 *)dzrow : (uint2 *)a.dz + row * (int64_t)a.list_cap;
             const bool listed = a.split_grad && !(y_safe && acc.count > a.list_cap);
+            const bool grad_row = y_safe && !overflow;     // an overflowing row is only walked to refill its slots
             const float neg_g = -g;
             const int t = fresh(tid);
-            const int64_t y_slot = y_safe ? (y / EPV) : -1;
+            const int64_t y_slot = grad_row ? (y / EPV) : -1;
             {   // ragged end
                 const int64_t k = (int64_t)nvec * EPV + t;
-                const bool safe = y_safe && t < tail && xt >= tau;
+                const bool safe = grad_row && t < tail && xt >= tau;
                 float d = 0.0f;
                 if (safe) d = neg_g * __expf((xt - m) - log_s) - (k == y ? neg_g : 0.0f);
                 if (listed) list_append(list, &lds_list_count, safe, (uint32_t)k, d);
-                else if (t < tail) store_elem(dzrow + k, d);
+                else if (t < tail && dense_out) store_elem(dzrow + k, d);
             }
 #pragma unroll
             for (int j = 0; j < NV; ++j) {
                 const int idx = j * NT + t;
                 u32x4 o = {0u, 0u, 0u, 0u};
-                if (y_safe && ((any_mask >> j) & 1u)) {   // wavefront-uniform
+                if (grad_row && ((any_mask >> j) & 1u)) {   // wavefront-uniform
                     float x[EPV], d[EPV];
                     keep_packed(r[j]);
                     unpack(r[j], x, T());
@@ -303,14 +309,15 @@ __global__ __launch_bounds__(NT, MINW) void rows_resident_kernel(const RowArgs a
                             if (e == ey) d[e] -= neg_g;
                     }
                     if (listed) {
+                        const bool real = j < NVFULL || idx < nvec;   // padding slots pass a -inf threshold
 #pragma unroll
                         for (int e = 0; e < EPV; ++e)
-                            list_append(list, &lds_list_count, x[e] >= tau, (uint32_t)(idx * EPV + e), d[e]);
+                            list_append(list, &lds_list_count, real && x[e] >= tau, (uint32_t)(idx * EPV + e), d[e]);
                     } else {
                         o = pack_grad(d, T());
                     }
                 }
-                if (!listed && (j < NVFULL || idx < nvec)) __builtin_nontemporal_store(o, dzvec + idx);
+                if (!listed && dense_out && (j < NVFULL || idx < nvec)) __builtin_nontemporal_store(o, dzvec + idx);
                 if (has_next && ((any_mask >> j) & 1u)) r[j] = load_slot<T, NT, NVFULL>(znext, j, t, nvec);
             }
         }
@@ -598,7 +605,7 @@ static hipError_t launch_resident_t(const RowArgs &a, hipStream_t stream)
 {
     const int epv = elem_traits<T>::kPerVec;
     const int64_t slots = (int64_t)a.vocab / epv;   // whole vectors; the ragged end lives outside the slots
-    if (slots <= 256 * 4)   return launch_resident_inst<T, 4, 0, 256, 6, EXTRAS>(a, stream);
+    if (slots <= 256 * 4)   return launch_resident_inst<T, 4, 0, 256, 4, EXTRAS>(a, stream);
     if (slots <= 256 * 8)   return launch_resident_inst<T, 8, 4, 256, 6, EXTRAS>(a, stream);
     if (slots <= 256 * 16)  return launch_resident_inst<T, 16, 8, 256, 4, EXTRAS>(a, stream);
     if (slots <= 1024 * 8)  return launch_resident_inst<T, 8, 4, 1024, 5, EXTRAS>(a, stream);

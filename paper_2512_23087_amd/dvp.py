@@ -18,11 +18,11 @@ _PKG = Path(__file__).resolve().parent
 LIB_PATH = _PKG / "libdvp_hip.so"
 
 DVP_F32, DVP_BF16 = 0, 1
-ROW_Y_IN_TRAIN_SAFE, ROW_Y_IN_INFER_SAFE, ROW_ID_OUT_OF_RANGE = 1, 2, 4
+ROW_Y_IN_TRAIN_SAFE, ROW_Y_IN_INFER_SAFE, ROW_ID_OUT_OF_RANGE, ROW_GRAD_OVERFLOW = 1, 2, 4, 8
 
 EXPORTS = ("dvp_forward", "dvp_backward", "dvp_forward_backward", "dvp_fused_lmhead",
            "dvp_fused_lmhead_workspace_bytes", "dvp_log_rho", "dvp_status_string", "dvp_row_path",
-           "dvp_sequence_weights", "dvp_log_threshold")
+           "dvp_sequence_weights", "dvp_log_threshold", "dvp_forward_backward_sparse")
 
 
 class DvpParams(ctypes.Structure):
@@ -81,6 +81,8 @@ def lib():
         L.dvp_status_string.argtypes = [ctypes.c_int]
         L.dvp_row_path.restype = ctypes.c_int
         L.dvp_row_path.argtypes = [pp, ctypes.c_int]
+        L.dvp_forward_backward_sparse.restype = ctypes.c_int
+        L.dvp_forward_backward_sparse.argtypes = [pp, vp, vp, i64p, vp, sp, sp, vp, vp, vp, ctypes.c_int32, vp]
         L.dvp_sequence_weights.restype = ctypes.c_int
         L.dvp_sequence_weights.argtypes = [ctypes.c_int64, ctypes.c_int64, vp, vp, i64p, ctypes.c_float,
                                            vp, vp, vp, vp, vp]
@@ -227,6 +229,54 @@ def dvp_forward_backward(z_train, z_infer, ids, grad_out, log_rho_value, *, lse_
     if st != 0:
         raise DvpError(st, "dvp_forward_backward")
     return RowResult(out_train, out_infer, row_flags, dz)
+
+
+class SparseResult:
+    def __init__(self, train, infer, row_flags, entries, grad_len):
+        self.train, self.infer, self.row_flags = train, infer, row_flags
+        self.entries, self.grad_len = entries, grad_len      # entries: int32 [N, cap, 2] = (index, fp32 bits)
+
+    def row(self, i):
+        """(indices int64, values float32) of row i, sorted by index (host-side test helper)."""
+        n = int(self.grad_len[i].item())
+        if int(self.row_flags[i].item()) & ROW_GRAD_OVERFLOW:
+            return None
+        e = self.entries[i, :n].cpu()
+        idx = e[:, 0].to(torch.int64) & 0xFFFFFFFF
+        val = e[:, 1].contiguous().view(torch.float32)
+        order = torch.argsort(idx)
+        return idx[order], val[order]
+
+
+def dvp_forward_backward_sparse(z_train, z_infer, ids, grad_out, log_rho_value, list_cap, *,
+                                out_train: Optional[SideOutputs] = None,
+                                out_infer: Optional[SideOutputs] = None, row_flags=None, entries=None,
+                                grad_len=None, stream=None) -> SparseResult:
+    _check_rows(z_train, "z_train")
+    if z_infer is not None:
+        _check_rows(z_infer, "z_infer")
+        if z_infer.shape != z_train.shape or z_infer.dtype != z_train.dtype:
+            raise ValueError("z_infer must match z_train in shape and dtype")
+    n, v = z_train.shape
+    dev = z_train.device
+    out_train = out_train or SideOutputs(n, v, dev)
+    if z_infer is not None:
+        out_infer = out_infer or SideOutputs(n, v, dev)
+    if row_flags is None:
+        row_flags = torch.empty(n, dtype=torch.uint8, device=dev)
+    if entries is None:
+        entries = torch.empty(n, list_cap, 2, dtype=torch.int32, device=dev)
+    if grad_len is None:
+        grad_len = torch.empty(n, dtype=torch.int32, device=dev)
+    p = _params(z_train, z_infer, None, log_rho_value)
+    st = lib().dvp_forward_backward_sparse(ctypes.byref(p), _ptr(z_train), _ptr(z_infer), _ptr(ids),
+                                           _ptr(grad_out), ctypes.byref(out_train.struct()),
+                                           ctypes.byref(out_infer.struct()) if out_infer is not None else None,
+                                           _ptr(row_flags), _ptr(entries), _ptr(grad_len), int(list_cap),
+                                           _stream(stream))
+    if st != 0:
+        raise DvpError(st, "dvp_forward_backward_sparse")
+    return SparseResult(out_train, out_infer, row_flags, entries, grad_len)
 
 
 class LmHeadResult:

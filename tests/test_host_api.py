@@ -118,3 +118,21 @@ def test_sequence_weights_validation_needs_no_gpu():
     assert call(n_seq=1, off=FAKE + 4) == 4 and call(n_seq=1, w=FAKE + 2) == 4
     assert dvp.log_threshold(1e-4) == pytest.approx(math.log(1e-4), rel=1e-7)
     assert math.isnan(dvp.log_threshold(0.0)) and math.isnan(dvp.log_threshold(-1.0))
+
+
+def test_sparse_gradient_validation_needs_no_gpu():
+    L = dvp.lib()
+    so = dvp.DvpSideOut(FAKE, FAKE, FAKE, None, FAKE, None)
+
+    def call(n_rows=1, vocab=32000, cap=64, z=FAKE, flags=FAKE, entries=FAKE, dtype=1, ld=None):
+        p = dvp.DvpParams(n_rows, vocab, ld or vocab, ld or vocab, 0, dtype, -3.0)
+        return L.dvp_forward_backward_sparse(ctypes.byref(p), z, FAKE, FAKE, FAKE, ctypes.byref(so),
+                                             ctypes.byref(so), flags, entries, FAKE, cap, None)
+
+    assert call(n_rows=0) == 0
+    assert call(cap=0) == 3 and call(cap=65537) == 3
+    assert call(flags=None) == 1 and call(entries=None) == 1 and call(z=None) == 1
+    assert call(entries=FAKE + 4) == 4
+    assert call(vocab=32001) == 5            # rows not 16-byte aligned: no single-read path
+    assert call(vocab=200000) == 5           # does not fit the register file
+    assert call(z=FAKE + 2) == 5             # base pointer not 16-byte aligned

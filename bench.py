@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MEASURED_TRAFFIC = {
     # sha256 of csrc/dvp_rows.hip + csrc/dvp_device.h -> HBM bytes per launch; see
     # profiles/rows_cfg3_hbm_traffic.md for the counter values and scale factors
-    "5c3b50e3962b52639f35e9e93ac26edeed27aaa32da3387f6bf6874150c3990f": {"cfg3": 29896408000},
+    "b6bfb4d8929e60a3d002c2286fe4de2d39e2db02aa64f54e7116a26ac2af4ef2": {"cfg3": 29894934000},
 }
 
 

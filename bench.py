@@ -49,7 +49,7 @@ def algorithmic_bytes_per_row(vocab: int, elem: int, infer: bool = True) -> int:
     return (sides + 1) * vocab * elem + 8 + 4 + 16 * sides + 1
 
 
-def cpu_baseline(wl, log_rho, target_seconds=15.0):
+def cpu_baseline(wl, log_rho, target_seconds=12.0):
     """The fp64 oracle, as it stands, on a bounded sample of the same workload."""
     import numpy as np
     from oracle import dvp_oracle as orc
@@ -57,9 +57,9 @@ def cpu_baseline(wl, log_rho, target_seconds=15.0):
     n = wl.z_train.shape[0]
 
     chunk = 512
-    done, spent = 0, 0.0
-    while done < n and spent < target_seconds:
-        r0, r1 = done, min(n, done + chunk)
+    done, spent, r0 = 0, 0.0, 0
+    while spent < target_seconds:            # walks the workload's rows, wrapping around if it is short
+        r1 = min(n, r0 + chunk)
         zt = wl.z_train[r0:r1].cpu()
         zi = wl.z_infer[r0:r1].cpu()
         ids = wl.ids[r0:r1].cpu().numpy()
@@ -68,11 +68,12 @@ def cpu_baseline(wl, log_rho, target_seconds=15.0):
         orc.rows(zt, ids, np.float32(log_rho), grad_out=g, want_dz=True, threads=threads)
         orc.rows(zi, ids, np.float32(log_rho), threads=threads)
         spent += time.perf_counter() - t0
-        done = r1
+        done += r1 - r0
+        r0 = r1 if r1 < n else 0
     return {"value": done / spent, "unit": "rows/s", "cores": threads, "kind": "oracle",
-            "sample": "first %d rows of the workload in chunks of %d, forward (both sides) + "
-                      "backward, fp64 C oracle on %d threads, %.1f s of CPU wall time"
-                      % (done, chunk, threads, spent)}
+            "sample": "%d rows of the workload in chunks of %d (wrapping around after its %d rows), forward "
+                      "(both sides) + backward, fp64 C oracle on %d threads, %.1f s of CPU wall time"
+                      % (done, chunk, n, threads, spent)}
 
 
 def time_launches(fn, steps, warmup):

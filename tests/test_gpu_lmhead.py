@@ -219,3 +219,38 @@ def test_full_size_sampled_rows(dvp):
     assert col <= 2.0 ** -8 * scale
     del wl, res
     torch.cuda.empty_cache()
+
+
+def test_padded_strides_and_out_of_range_ids(dvp):
+    """Row strides larger than the hidden size, and sampled ids outside [0, V): flagged per row,
+    NaN log-probs, zero gradient contribution, nothing else disturbed."""
+    n, d, v, pad = 150, 128, 900, 8
+    wl = workloads.make_lmhead(device="cuda", n=n, d=d, v=v)
+    H = torch.full((n, d + pad), float("nan"), dtype=torch.bfloat16, device="cuda")
+    W = torch.full((v, d + pad), float("nan"), dtype=torch.bfloat16, device="cuda")
+    H[:, :d] = wl.hidden
+    W[:, :d] = wl.w_train
+    ids = wl.ids.clone()
+    ids[3] = -1
+    ids[77] = v
+    lr = dvp.log_rho(1e-3)
+    a = dvp.dvp_fused_lmhead(H[:, :d], W[:, :d], None, ids, wl.grad_out, lr)
+    torch.cuda.synchronize()
+    flags = a.row_flags.cpu().numpy()
+    assert flags[3] == 4 and flags[77] == 4 and (np.delete(flags, [3, 77]) & 4).sum() == 0
+    assert torch.isnan(a.train.logp[3]) and torch.isnan(a.train.logp[77])
+    assert torch.all(a.d_hidden[3] == 0) and torch.all(a.d_hidden[77] == 0)
+    assert torch.isfinite(a.d_w).all() and torch.isfinite(a.d_hidden).all()
+    # the other rows equal a contiguous run with those two rows' upstream gradient set to zero
+    g2 = wl.grad_out.clone()
+    g2[3] = 0
+    g2[77] = 0
+    ids2 = ids.clone()
+    ids2[3] = 0
+    ids2[77] = 0
+    b = dvp.dvp_fused_lmhead(wl.hidden, wl.w_train, None, ids2, g2, lr)
+    torch.cuda.synchronize()
+    keep = torch.ones(n, dtype=torch.bool, device="cuda")
+    keep[3] = keep[77] = False
+    assert torch.equal(a.train.logp[keep], b.train.logp[keep])
+    assert torch.equal(a.d_hidden[keep], b.d_hidden[keep]) and torch.equal(a.d_w, b.d_w)

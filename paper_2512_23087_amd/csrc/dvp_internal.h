@@ -52,7 +52,7 @@ struct FillArgs {
     int32_t list_cap;
 };
 
-constexpr int kListMax = 2048;   // longest (index, value) list a gradient row may carry
+constexpr int kListMax = 64;     // longest (index, value) list a gradient row may carry before it is written densely
 
 struct BackwardArgs {
     const void *z;

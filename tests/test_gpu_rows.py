@@ -294,3 +294,22 @@ def test_full_size_large_vocab_sampled_rows(dvp):
             assert torch.all(cnt == v)
     del wl
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_rows_on_both_sides_of_the_list_capacity(dvp, dtype):
+    """Gaussian logits whose safe sets straddle the 64-token list capacity: some rows leave a list
+    for the fill kernels, the others are written densely by the row kernel, in one call."""
+    n, v = 48, 40000
+    g = torch.Generator(device="cpu").manual_seed(4242)
+    zt = (12.0 * torch.randn(n, v, generator=g)).to(dtype)
+    zi = (zt.float() + 0.01 * torch.randn(n, v, generator=g)).to(dtype)
+    ids = torch.argmax(zi.float(), dim=1)
+    ids[5] = int(torch.argmin(zt[5].float()))            # a pruned sampled token among them
+    wl = workloads.RowWorkload(name="gauss", z_train=zt.cuda(), z_infer=zi.cuda(), ids=ids.cuda(),
+                               grad_out=torch.randn(n, generator=g).cuda(), rhos=[])
+    res = dvp.dvp_forward(wl.z_train, wl.z_infer, wl.ids, dvp.log_rho(1e-6))
+    torch.cuda.synchronize()
+    counts = res.train.safe_count.cpu().numpy()
+    assert (counts <= 64).sum() >= 5 and (counts > 64).sum() >= 5 and counts.max() < 2000
+    _run_case(dvp, wl, 1e-6, backward=True, threads=4)

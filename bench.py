@@ -26,16 +26,16 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # same counters' reading on a plain copy kernel of known size.  Only valid for the kernel
 # source it was measured on: keyed by the sha256 of the kernel sources.
 MEASURED_TRAFFIC = {
-    # sha256 of csrc/dvp_rows.hip + csrc/dvp_device.h -> HBM bytes per launch; see
+    # sha256 of csrc/dvp_rows.hip + dvp_device.h + dvp_internal.h -> HBM bytes per launch; see
     # profiles/rows_cfg3_hbm_traffic.md for the counter values and scale factors
-    "b6bfb4d8929e60a3d002c2286fe4de2d39e2db02aa64f54e7116a26ac2af4ef2": {"cfg3": 29894934000},
+    "971de22430770d032872b564e95a27059ae58ea232fe8bfb5b269fb538caa37f": {"cfg3": 29894940000},
 }
 
 
 def kernel_source_hash() -> str:
     import hashlib
     h = hashlib.sha256()
-    for name in ("dvp_rows.hip", "dvp_device.h"):
+    for name in ("dvp_rows.hip", "dvp_device.h", "dvp_internal.h"):
         with open(os.path.join(ROOT, "paper_2512_23087_amd", "csrc", name), "rb") as f:
             h.update(f.read())
     return h.hexdigest()

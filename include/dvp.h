@@ -171,9 +171,11 @@ dvp_status dvp_forward_backward_sparse(const dvp_params *params, const void *z_t
  * LM-head variant: the logits z = H W^T are produced tile by tile on the
  * matrix cores and consumed in the tile epilogues; the [N, V] logits are never
  * stored.  Same per-row definitions as above (Def. 5.1, 5.2, Prop. 5.4); the
- * gradient is delivered as dH = dz W and dW = dz^T H.  The softmax part of dz
- * passes through bf16 on its way into the two products; its one-hot part is
- * added in fp32.  Results are run-to-run identical.
+ * gradient is delivered as dH = dz W and dW = dz^T H.  Every entry of dz but
+ * the sampled token's passes through bf16 on its way into the two products;
+ * the sampled token's entry g (1 - p_y) is formed and added in fp32, so a row
+ * that puts all its mass on its sampled token yields an exactly zero gradient.
+ * Results are run-to-run identical.
  * Limits (DVP_ERR_UNSUPPORTED otherwise): hidden a multiple of 64, row strides
  * multiples of 8 and at most 2^22 elements, vocab at most 2^22.
  */

@@ -10,13 +10,15 @@
 // When a gradient is asked for, the training side runs in blocks of 4096 token
 // rows and pass B also leaves the block's masked exponentials
 //   E_ik = [z_ik >= tau_i] exp(z_ik - m_i)          (bf16, both orientations)
-// behind.  With S_i their row sum and c_i = grad_out_i (0 when y_i is pruned),
-// Prop. 5.4 reads dz_ik = c_i delta(k, y_i) - (c_i / S_i) E_ik, so
-//   dH_i = c_i W_y + s_i (E W)_i,   dW = onehot^T diag(c) H + E^T (diag(s) H),   s_i = -c_i / S_i.
+// behind, with the sampled token's own entry E_iy set to zero.  With S_i the
+// row sum (sampled token included), c_i = grad_out_i (0 when y_i is pruned),
+// s_i = -c_i / S_i and q_i = c_i (1 - p_iy) the sampled token's gradient entry,
+// Prop. 5.4 reads dz_ik = q_i delta(k, y_i) + s_i E_ik, so
+//   dH_i = q_i W_y + s_i (E W)_i,   dW = onehot^T diag(q) H + E^T (diag(s) H).
 // The two E products run on the matrix cores (the row factor s is applied in
 // fp32 when dH is written and folded into H for dW, which is accumulated over
-// the row blocks); the one-hot terms, the only O(1) entries of dz, are added in
-// fp32 and never rounded to bf16.
+// the row blocks); the sampled token's entry, the one that cancels when the
+// distribution is peaked, is formed and added in fp32 and never rounded to bf16.
 // Every GEMM is C = A B^T with both operands K-major; W is transposed once per
 // call and the scaled H once per row block so that the two E products have
 // that form too.
@@ -66,7 +68,7 @@ struct RowStats {
     float *part_s;       // [col_tiles][n] masked exp sums per 256-column tile (pass B)
     float *part_f;       // [col_tiles][n] full exp sums, or null
     int *part_c;         // [col_tiles][n] safe counts per tile
-    float *coef;         // [n] c: grad_out where the sampled token is safe, else 0 (after pass B)
+    float *coef;         // [n] q = c (1 - p_y), c = grad_out where the sampled token is safe, else 0 (after pass B)
     float *scale;        // [n] s = -c / S (after pass B)
 };
 
@@ -131,6 +133,7 @@ struct EpiSum {
     static constexpr bool kUsesTileLds = WRITE_E;   // the bf16 staging lives in the operand tiles
     RowStats st;
     int n_rows;
+    const int64_t *ids;      // WRITE_E: the sampled token's own entry of E is stored as zero
     uint16_t *E, *Et;
     int64_t ld_e, ld_et;
     __device__ __forceinline__ void operator()(const GemmArgs &g, f32x16 (&acc)[MI][NI], int r0, int c0, int lane, uint8_t *lds, int wave, int wn) const
@@ -147,6 +150,8 @@ struct EpiSum {
                 const bool row_ok = row < g.M;
                 const float m = row_ok ? st.m[row] : 0.0f;
                 const float tau = row_ok ? st.tau[row] : INFINITY;
+                int64_t y = -1;
+                if constexpr (WRITE_E) y = row_ok ? ids[row] : -1;
                 float s = 0.0f, f = 0.0f;
                 int c = 0;
 #pragma unroll
@@ -166,7 +171,7 @@ struct EpiSum {
                         }
                         s += kept;
                     }
-                    if constexpr (WRITE_E) acc[mi][ni][i] = kept;   // the accumulators now hold E
+                    if constexpr (WRITE_E) acc[mi][ni][i] = (int64_t)col == y ? 0.0f : kept;   // the accumulators now hold E
                 }
 #pragma unroll
                 for (int off = 16; off > 0; off >>= 1) {
@@ -555,7 +560,7 @@ __global__ __launch_bounds__(kAfterRows * kAfterSegs) void after_sum_kernel(RowS
     const bool y_safe = y_ok && zy >= tau;
     if (side == 0) {
         const float c_i = (grad_out && y_safe) ? grad_out[i] : 0.0f;
-        st.coef[i] = c_i;
+        st.coef[i] = c_i != 0.0f ? c_i * (1.0f - __expf(zy - m) / s) : 0.0f;
         st.scale[i] = -c_i / s;
     }
     if (out.row_max) out.row_max[i] = m;
@@ -571,7 +576,7 @@ __global__ __launch_bounds__(kAfterRows * kAfterSegs) void after_sum_kernel(RowS
     }
 }
 
-// One-hot part of dW (Prop. 5.4): dW[y_i, :] += c_i H_i for the `rows` token rows of a block, in
+// Sampled-token part of dW (Prop. 5.4): dW[y_i, :] += q_i H_i for the `rows` token rows of a block, in
 // fp32 and in row order whatever the launch order (run-to-run identical).  One workgroup per token
 // row; the first row of the block that sampled a token adds the contributions of every row that
 // sampled it.  Runs after the block's E^T product has been written to dW.
@@ -759,10 +764,10 @@ dvp_status dvp_fused_lmhead(const dvp_lmhead_params *p, const void *hidden, cons
         hipLaunchKernelGGL(after_max_kernel, dim3(nb), dim3(tb), 0, stream, st, rows, p->log_rho);
         DVP_CHECK_LAUNCH();
         if (write_e) {
-            if (launch_gemm<EpiSum<true>, true>(g, EpiSum<true>{st, rows, E, Et, (int64_t)L.v_pad, (int64_t)L.block_pad},
+            if (launch_gemm<EpiSum<true>, true>(g, EpiSum<true>{st, rows, ids + r0, E, Et, (int64_t)L.v_pad, (int64_t)L.block_pad},
                                                 stream) != hipSuccess) return DVP_ERR_HIP;
         } else {
-            if (launch_gemm<EpiSum<false>, true>(g, EpiSum<false>{st, rows, nullptr, nullptr, 0, 0}, stream) != hipSuccess)
+            if (launch_gemm<EpiSum<false>, true>(g, EpiSum<false>{st, rows, nullptr, nullptr, nullptr, 0, 0}, stream) != hipSuccess)
                 return DVP_ERR_HIP;
         }
         hipLaunchKernelGGL(after_sum_kernel, dim3((rows + kAfterRows - 1) / kAfterRows),
@@ -790,14 +795,14 @@ dvp_status dvp_fused_lmhead(const dvp_lmhead_params *p, const void *hidden, cons
             hipLaunchKernelGGL(transpose_bf16_kernel, dim3((d + 31) / 32, (rows_pad + 31) / 32), dim3(32, 8), 0, stream,
                                hblock, p->ld_hidden, ht, (int64_t)L.block_pad, rows, d, rows_pad, (const float *)st.scale);
             DVP_CHECK_LAUNCH();
-            // dH[r0 : r0 + rows, :] = diag(s) . E [rows, v_pad] . (W^T [d, v_pad])^T + diag(c) . W[y, :]
+            // dH[r0 : r0 + rows, :] = diag(s) . E [rows, v_pad] . (W^T [d, v_pad])^T + diag(q) . W[y, :]
             GemmArgs gh;
             gh.A = E; gh.lda = L.v_pad; gh.B = wt; gh.ldb = L.v_pad;
             gh.M = rows; gh.N = d; gh.K = L.v_pad;
             const EpiStore eh{d_hidden + (int64_t)r0 * p->ld_hidden, p->ld_hidden, 0, st.scale, st.coef, ids + r0,
                               (const uint16_t *)w_train, p->ld_w};
             if (launch_gemm<EpiStore, false>(gh, eh, stream) != hipSuccess) return DVP_ERR_HIP;
-            // dW (+)= E^T [v, rows_pad] . ((diag(s) H)^T [d, rows_pad])^T, then its one-hot rows
+            // dW (+)= E^T [v, rows_pad] . ((diag(s) H)^T [d, rows_pad])^T, then the sampled tokens' rows
             GemmArgs gw;
             gw.A = Et; gw.lda = L.block_pad; gw.B = ht; gw.ldb = L.block_pad;
             gw.M = v; gw.N = d; gw.K = rows_pad;

@@ -7,15 +7,23 @@ d <= 4096).  Consequences, all stated here and checked below:
   * row maxima and lse agree to 2e-3 (the bf16-input tolerance);
   * membership is compared outside a band: |count_gpu - count_oracle| is at
     most the number of oracle logits within BAND of the ideal threshold;
-  * the gradient is split as dz = c onehot - (c/S) E (Prop. 5.4).  The one-hot
-    terms, the only O(1) entries, are added in fp32.  The masked exponentials E
-    are rounded to bf16 (8 significant bits: relative error <= 2^-8) before the
-    two matrix products.  dH = c W_y + diag(-c/S) E W applies the row factor in
-    fp32, so to first order |dH_gpu - dH| <= 2^-8 (|c| p |W|) with p the pruned
-    softmax.  dW = onehot^T diag(c) H + E^T (diag(-c/S) H) rounds the scaled H
-    to bf16 as well: two roundings per term, |dW_gpu - dW| <= 2^-7 (|c| p)^T |H|.
-    Both are asserted per element with ATOL = 1e-5 + 2^-20 |reference| for the
-    fp32 accumulation.  On the workloads here that is far inside 2e-3 absolute.
+  * the gradient is split as dz = q onehot - (c/S) E with E the masked
+    exponentials of every token but the sampled one and q = c (1 - p_y) the
+    sampled token's own entry, formed and added in fp32 (it is the entry that
+    cancels when the distribution is peaked).  E is rounded to bf16 (8
+    significant bits: relative error <= 2^-8) before the two matrix products.
+    dH = q W_y + diag(-c/S) E W applies the row factor in fp32, so to first
+    order |dH_gpu - dH| <= 2^-8 (|c| p' |W|) with p' the pruned softmax without
+    the sampled token.  dW = onehot^T diag(q) H + E^T (diag(-c/S) H) rounds the
+    scaled H to bf16 as well: two roundings per term, |dW_gpu - dW| <=
+    2^-7 (|c| p')^T |H|.  Both are asserted per element with
+    ATOL = 1e-5 + 2^-20 |reference| for the fp32 accumulation.  On the workloads
+    here that is far inside 2e-3 absolute, which is asserted as well;
+  * the fp32 logits themselves carry a rounding dz <= 2^-21 max|z| (four units
+    in the last place of the largest logit), which moves every probability by
+    |dp_k| <= 2 p_k dz to first order, the sampled token's included.  That adds
+    2 dz (|c| p) |W| and 2 dz (|c| p)^T |H| to the two bounds, with the full p.
+    It is invisible while |z| is O(1) and matters once logits reach ~100.
 """
 import math
 
@@ -60,7 +68,7 @@ def _check_side(name, side, o, band_o):
     return same
 
 
-def _run(dvp, wl, rho, lse_full=False, grad=True):
+def _run(dvp, wl, rho, lse_full=False, grad=True, abs_check=True):
     lr = dvp.log_rho(rho)
     res = dvp.dvp_fused_lmhead(wl.hidden, wl.w_train, wl.w_infer, wl.ids,
                                wl.grad_out if grad else None, lr, lse_full=lse_full)
@@ -80,9 +88,14 @@ def _run(dvp, wl, rho, lse_full=False, grad=True):
         W64 = Wt.double().numpy()
         soft = np.abs(ot["dz"])                       # |c| p: the part of dz that goes through bf16
         safe_rows = np.nonzero(ot["y_in_safe"])[0]
-        soft[safe_rows, ids[safe_rows]] = np.abs(g[safe_rows]) * np.exp(ot["logp"][safe_rows])
-        bound_h = 2.0 ** -8 * (soft @ np.abs(W64)) + 1e-5 + 2.0 ** -20 * np.abs(ot["d_hidden"])
-        bound_w = 2.0 ** -7 * (soft.T @ np.abs(H64)) + 1e-5 + 2.0 ** -20 * np.abs(ot["d_w"])
+        soft[safe_rows, ids[safe_rows]] = 0.0         # the sampled token's entry never passes through bf16
+        full = soft.copy()                            # |c| p with the sampled token's p_y put back
+        full[safe_rows, ids[safe_rows]] = np.abs(g[safe_rows]) * np.exp(ot["logp"][safe_rows])
+        dz_round = 2.0 ** -21 * (np.abs(ot["row_max"]).max() + 10.0)
+        bound_h = (2.0 ** -8 * (soft @ np.abs(W64)) + 2 * dz_round * (full @ np.abs(W64))
+                   + 1e-5 + 2.0 ** -20 * np.abs(ot["d_hidden"]))
+        bound_w = (2.0 ** -7 * (soft.T @ np.abs(H64)) + 2 * dz_round * (full.T @ np.abs(H64))
+                   + 1e-5 + 2.0 ** -20 * np.abs(ot["d_w"]))
         dh = res.d_hidden.cpu().double().numpy()
         dw = res.d_w.cpu().double().numpy()
         rows = same_t                                  # rows whose sampled token flipped sides are excluded
@@ -93,9 +106,11 @@ def _run(dvp, wl, rho, lse_full=False, grad=True):
             assert err_w.max() <= 1.0, "dW error is %.2f x its bound" % err_w.max()
             print("dH at %.3f, dW at %.3f of their bounds; max abs error dH %.2e dW %.2e" %
                   (err_h.max(), err_w.max(), np.abs(dh - ot["d_hidden"])[rows].max(), np.abs(dw - ot["d_w"]).max()))
-            assert np.abs(dw - ot["d_w"]).max() <= 2e-3 and np.abs(dh - ot["d_hidden"])[rows].max() <= 2e-3
-        # and the bound is not vacuous: the gradients are far above it
-        assert np.abs(ot["d_hidden"]).max() > 100 * np.median(bound_h)
+            if abs_check:
+                assert np.abs(dw - ot["d_w"]).max() <= 2e-3 and np.abs(dh - ot["d_hidden"])[rows].max() <= 2e-3
+        # and the bound is not vacuous: the gradients are far above it (a one-token vocabulary has none)
+        if W64.shape[0] > 1:
+            assert np.abs(ot["d_hidden"]).max() > 100 * np.median(bound_h)
     return res, ot, oi
 
 
@@ -103,6 +118,33 @@ def test_small_ragged_shapes(dvp):
     wl = workloads.make_lmhead(device="cuda", n=200, d=128, v=1000)
     for rho in (1e-2, 1e-4, 0.0):
         _run(dvp, wl, rho, lse_full=True)
+
+
+@pytest.mark.parametrize("n,d,v", [(1, 64, 3), (2, 64, 1), (257, 192, 257), (33, 64, 513)])
+def test_degenerate_shapes(dvp, n, d, v):
+    # a single row, a single token (probability one, zero gradient), odd K step counts, tiles one past a boundary
+    wl = workloads.make_lmhead(device="cuda", n=n, d=d, v=v)
+    _run(dvp, wl, 1e-2)
+    _run(dvp, wl, 0.0, lse_full=True)
+
+
+def test_peaked_distributions(dvp):
+    """Hidden states scaled up until most rows put nearly all mass on one token, usually the sampled
+    one: the sampled token's gradient entry c (1 - p_y) cancels and must not inherit a bf16 rounding of
+    c.  Rows that sampled a rare token keep an O(1) entry -c p_k at the peak, which is rounded to bf16
+    like any other: covered by the per-element bound, not by the 2e-3 absolute figure."""
+    wl = workloads.make_lmhead(device="cuda", n=192, d=128, v=1500)
+    wl.hidden = (wl.hidden.float() * 120.0).to(torch.bfloat16)
+    z = wl.hidden.float() @ wl.w_train.float().T
+    p = torch.softmax(z, dim=-1)
+    assert (p.max(dim=1).values > 0.9).float().mean().item() > 0.5
+    wl.ids = torch.multinomial(p, 1, generator=torch.Generator(device="cuda").manual_seed(5)).squeeze(1)
+    res, ot, oi = _run(dvp, wl, 1e-4, abs_check=False)
+    # rows that sampled their peak token: the whole gradient row is tiny and so is its error
+    peak = (np.exp(ot["logp"]) > 0.99)
+    assert peak.sum() > 20
+    dh = res.d_hidden.cpu().double().numpy()
+    assert np.abs(dh - ot["d_hidden"])[peak].max() <= 2e-5
 
 
 def test_multiple_row_blocks(dvp):
@@ -203,7 +245,7 @@ def test_full_size_sampled_rows(dvp):
     W64 = Wt.double().numpy()
     soft = np.abs(ot["dz"])
     safe_rows = np.nonzero(ot["y_in_safe"])[0]
-    soft[safe_rows, ids[safe_rows]] = np.abs(g[safe_rows]) * np.exp(ot["logp"][safe_rows])
+    soft[safe_rows, ids[safe_rows]] = 0.0
     bound_h = 2.0 ** -8 * (soft @ np.abs(W64)) + 1e-5 + 2.0 ** -20 * np.abs(ot["d_hidden"])
     dh = res.d_hidden[ridx].cpu().double().numpy()
     err = (np.abs(dh - ot["d_hidden"]) / bound_h)[same_t]

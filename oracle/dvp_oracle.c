@@ -48,6 +48,9 @@
  *           that the decision is a well defined function of the stored
  *           inputs; a token whose weight is NaN or +inf also vetoes.
  *
+ * Inference logits may be stored as 8-bit E4M3 codes (dvp_oracle_e4m3_value);
+ * they are widened exactly and everything above applies unchanged.
+ *
  * Pins (tests/test_oracle_pins.py): scipy/torch log-softmax with an empty
  * prune set, scipy logsumexp with an independently built mask, probability
  * space brute force on V <= 16, torch autograd through a masked log-softmax,
@@ -59,7 +62,27 @@
 #include <stdlib.h>
 #include <string.h>
 
-enum { DVP_ORACLE_F32 = 0, DVP_ORACLE_BF16 = 1, DVP_ORACLE_F64 = 2 };
+enum { DVP_ORACLE_F32 = 0, DVP_ORACLE_BF16 = 1, DVP_ORACLE_F64 = 2, DVP_ORACLE_F8E4M3 = 3 };
+
+/*
+ * Value of one 8-bit E4M3 code (the OCP 8-bit floating point format the paper's
+ * FP8 inference engines store, Sec. 4.2 "low-precision inference"): 1 sign
+ * bit, 4 exponent bits with bias 7, 3 mantissa bits; no infinities; the one
+ * NaN per sign is exponent 15 with mantissa 7; exponent 0 holds the
+ * subnormals mantissa * 2^-9 (and the two zeros).  Largest finite value
+ * 1.75 * 2^8 = 448.
+ */
+double dvp_oracle_e4m3_value(uint8_t code)
+{
+    const int sign = code >> 7;
+    const int expo = (code >> 3) & 15;
+    const int mant = code & 7;
+    double v;
+    if (expo == 15 && mant == 7) return NAN;
+    if (expo == 0) v = ldexp((double)mant, -9);
+    else           v = ldexp(1.0 + (double)mant / 8.0, expo - 7);
+    return sign ? -v : v;
+}
 
 typedef struct {
     const void *z;
@@ -91,6 +114,8 @@ static double fetch(const void *base, int dtype, int64_t idx)
         float f;
         memcpy(&f, &bits, sizeof f);
         return (double)f;
+    } else if (dtype == DVP_ORACLE_F8E4M3) {
+        return dvp_oracle_e4m3_value(((const uint8_t *)base)[idx]);
     }
     return ((const double *)base)[idx];
 }
@@ -119,7 +144,7 @@ static void oracle_row(const oracle_job *J, int64_t i, double *zrow)
     for (k = 1; k < V; ++k) if (zrow[k] > m) m = zrow[k];
 
     /* threshold: ideal value and the single-precision value that decides
-     * membership.  m and log_rho are both fp32-representable for f32/bf16
+     * membership.  m and log_rho are both fp32-representable for f32/bf16/e4m3
      * inputs; rounding their double sum to float equals the fp32 add. */
     const double tau_ideal = m + (double)J->log_rho;
     const double tau = (double)(float)tau_ideal;
@@ -202,7 +227,7 @@ int dvp_oracle_rows(const void *z, int dtype, int64_t n_rows, int64_t vocab, int
     if (!z || !ids || !row_max || !tau || !lse_safe || !lse_full || !logp ||
         !safe_count || !band_count || !y_in_safe) return 1;
     if (n_rows < 0 || vocab < 1 || ld < vocab) return 1;
-    if (dtype < 0 || dtype > 2) return 1;
+    if (dtype < 0 || dtype > 3) return 1;
     if (log_rho != log_rho || log_rho > 0.0f) return 1;
     if (n_rows == 0) return 0;
 

@@ -23,7 +23,7 @@ _SRC = _HERE / "dvp_oracle.c"
 _LIB = _HERE / "libdvp_oracle.so"
 _lib = None
 
-F32, BF16, F64 = 0, 1, 2
+F32, BF16, F64, F8E4M3 = 0, 1, 2, 3
 
 
 def build(force: bool = False) -> Path:
@@ -57,6 +57,8 @@ def _load():
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int]
+        lib.dvp_oracle_e4m3_value.restype = ctypes.c_double
+        lib.dvp_oracle_e4m3_value.argtypes = [ctypes.c_uint8]
         lib.dvp_oracle_sequences.restype = ctypes.c_int
         lib.dvp_oracle_sequences.argtypes = [
             ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
@@ -76,14 +78,16 @@ def log_rho_f32(rho: float) -> np.float32:
 
 
 def as_oracle_input(z):
-    """Accepts a numpy float32/float64/uint16(bf16 bits) array or a CPU torch
-    tensor (float32, float64, bfloat16); returns (array, dtype_code) without
-    changing any stored value."""
+    """Accepts a numpy float32/float64/uint16(bf16 bits)/uint8(E4M3 codes) array
+    or a CPU torch tensor (float32, float64, bfloat16, float8_e4m3fn); returns
+    (array, dtype_code) without changing any stored value."""
     if not isinstance(z, np.ndarray):
-        import torch  # plumbing only: reinterpret bf16 storage as uint16
+        import torch  # plumbing only: reinterpret bf16 / fp8 storage as integers
         t = z.detach().cpu().contiguous()
         if t.dtype == torch.bfloat16:
             z = t.view(torch.int16).numpy().view(np.uint16)
+        elif t.dtype == torch.float8_e4m3fn:
+            z = t.view(torch.uint8).numpy()
         else:
             z = t.numpy()
     if z.dtype == np.float32:
@@ -92,11 +96,18 @@ def as_oracle_input(z):
         code = BF16
     elif z.dtype == np.float64:
         code = F64
+    elif z.dtype == np.uint8:
+        code = F8E4M3
     else:
         raise TypeError("unsupported logits dtype %s" % z.dtype)
     if z.ndim != 2:
         raise ValueError("logits must be [N, V]")
     return np.ascontiguousarray(z), code
+
+
+def e4m3_value(code: int) -> float:
+    """Value of one 8-bit E4M3 code (NaN for the two NaN codes)."""
+    return float(_load().dvp_oracle_e4m3_value(int(code) & 0xFF))
 
 
 def rows(z, ids, log_rho, grad_out=None, want_flags=False, want_dz=False,
@@ -149,6 +160,9 @@ def _widen(a):
     a, code = as_oracle_input(a)
     if code == BF16:
         return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    if code == F8E4M3:
+        table = np.array([e4m3_value(c) for c in range(256)], dtype=np.float64)
+        return table[a]
     return a.astype(np.float64)
 
 

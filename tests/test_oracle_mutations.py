@@ -25,6 +25,11 @@ MUTATIONS = {
     "veto_inclusive": ("if (l32 < log_threshold ||", "if (l32 <= log_threshold ||"),
     "pruned_token_weight_not_zero": ("if (lt == -INFINITY) l = -INFINITY;", "if (0) l = -INFINITY;"),
     "sequence_min_never_updated": ("else if (w < wmin) wmin = w;", "else if (w > wmin) wmin = w;"),
+    "e4m3_bias": ("ldexp(1.0 + (double)mant / 8.0, expo - 7)", "ldexp(1.0 + (double)mant / 8.0, expo - 8)"),
+    "e4m3_subnormals_flushed": ("if (expo == 0) v = ldexp((double)mant, -9);", "if (expo == 0) v = 0.0;"),
+    "e4m3_has_infinity": ("if (expo == 15 && mant == 7) return NAN;",
+                          "if (expo == 15) return mant ? NAN : (sign ? -INFINITY : INFINITY);"),
+    "e4m3_mantissa_width": ("(double)mant / 8.0, expo", "(double)mant / 16.0, expo"),
     "infinite_weight_not_vetoed": ("|| l32 == INFINITY) veto = 1;", ") veto = 1;"),
 }
 

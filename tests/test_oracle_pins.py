@@ -210,6 +210,46 @@ def test_bf16_inputs_are_widened_exactly():
         np.testing.assert_array_equal(a[k], b[k])
 
 
+def test_e4m3_codes_against_the_format_definition_and_torch():
+    """The 8-bit E4M3 decode (inference logits of an FP8 engine, Sec. 4.2) against facts the OCP
+    format fixes and against torch's own float8_e4m3fn widening of all 256 codes."""
+    val = np.array([orc.e4m3_value(c) for c in range(256)])
+    # facts of the format: 1.0, the largest finite value 448, the smallest normal 2^-6, the
+    # smallest subnormal 2^-9, one NaN per sign and no infinity, two zeros
+    assert val[0x38] == 1.0 and val[0x7E] == 448.0 and val[0x08] == 2.0 ** -6 and val[0x01] == 2.0 ** -9
+    assert val[0x00] == 0.0 and val[0x80] == 0.0 and np.signbit(val[0x80])
+    assert np.isnan(val[0x7F]) and np.isnan(val[0xFF]) and np.isnan(val).sum() == 2
+    assert not np.isinf(val).any()
+    pos = val[:0x7F]
+    assert np.all(np.diff(pos) > 0)                       # codes order like their values
+    np.testing.assert_array_equal(val[0x80:0xFF], -pos)   # the sign bit only flips the sign
+    # subnormals are evenly spaced, and each binade holds 8 evenly spaced values
+    np.testing.assert_array_equal(val[0:8], np.arange(8) * 2.0 ** -9)
+    for e in range(1, 16):
+        top = 8 if e < 15 else 7
+        np.testing.assert_array_equal(val[8 * e:8 * e + top], 2.0 ** (e - 7) * (1 + np.arange(top) / 8))
+    # torch's conversion of the same bit patterns
+    t = torch.arange(256, dtype=torch.int32).to(torch.uint8).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    np.testing.assert_array_equal(np.isnan(t), np.isnan(val))
+    ok = ~np.isnan(val)
+    np.testing.assert_array_equal(t[ok], val[ok])
+    assert np.array_equal(np.signbit(t[ok]), np.signbit(val[ok]))
+
+
+def test_e4m3_inputs_are_widened_exactly():
+    g = torch.Generator().manual_seed(9)
+    t = (3.0 * torch.randn(6, 333, generator=g)).to(torch.float8_e4m3fn)
+    ids = np.arange(6)
+    a = orc.rows(t, ids, orc.log_rho_f32(1e-2), want_flags=True)
+    b = orc.rows(t.to(torch.float64).numpy(), ids, orc.log_rho_f32(1e-2), want_flags=True)
+    for k in a:
+        np.testing.assert_array_equal(a[k], b[k])
+    # and as raw codes in a numpy array
+    c = orc.rows(t.view(torch.uint8).numpy(), ids, orc.log_rho_f32(1e-2), want_flags=True)
+    for k in a:
+        np.testing.assert_array_equal(a[k], c[k])
+
+
 def test_shift_invariance():
     z, ids = _rand_rows(8, 500, 5)
     lr = orc.log_rho_f32(1e-3)

@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MEASURED_TRAFFIC = {
     # sha256 of csrc/dvp_rows.hip + dvp_device.h + dvp_internal.h -> HBM bytes per launch; see
     # profiles/rows_cfg3_hbm_traffic.md for the counter values and scale factors
-    "971de22430770d032872b564e95a27059ae58ea232fe8bfb5b269fb538caa37f": {"cfg3": 29894940000},
+    "16f033a935c62574e50de82fb1fc3a55990deacdf1133025b15e103b94c719ea": {"cfg3": 29894916000},
 }
 
 
@@ -41,12 +41,11 @@ def kernel_source_hash() -> str:
     return h.hexdigest()
 
 
-def algorithmic_bytes_per_row(vocab: int, elem: int, infer: bool = True) -> int:
+def algorithmic_bytes_per_row(vocab: int, elem: int, infer_elem: int) -> int:
     """What the method must move per row: read the training row, read the
     inference row, write the gradient row, plus the per-row scalars
     (id 8, grad_out 4, and per side logp/row_max/lse_safe/safe_count 16; flags 1)."""
-    sides = 2 if infer else 1
-    return (sides + 1) * vocab * elem + 8 + 4 + 16 * sides + 1
+    return 2 * vocab * elem + vocab * infer_elem + 8 + 4 + 16 * 2 + 1
 
 
 def cpu_baseline(wl, log_rho, target_seconds=12.0):
@@ -199,6 +198,9 @@ def main():
     ap.add_argument("--sparse-grad", type=int, default=0, metavar="CAP",
                     help="deliver the gradient as per-row (index, value) lists of at most CAP entries "
                          "(dvp_forward_backward_sparse) instead of the dense matrix")
+    ap.add_argument("--infer-dtype", default="same", choices=["same", "f8"],
+                    help="f8: the inference logits are rounded through E4M3 (saturating) and handed over as "
+                         "one byte per token")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
@@ -230,6 +232,13 @@ def main():
     n, v = wl.z_train.shape
     elem = wl.z_train.element_size()
     lr = dvp.log_rho(args.rho)
+    if args.infer_dtype == "f8":
+        zi8 = torch.empty(n, v, dtype=torch.float8_e4m3fn, device="cuda:0")
+        for r0 in range(0, n, 1024):
+            zi8[r0:r0 + 1024] = workloads.through_e4m3(wl.z_infer[r0:r0 + 1024].float()).to(torch.float8_e4m3fn)
+        wl.z_infer = zi8
+        torch.cuda.synchronize()
+    infer_elem = wl.z_infer.element_size()
 
     out_t = dvp.SideOutputs(n, v, wl.z_train.device)
     out_i = dvp.SideOutputs(n, v, wl.z_train.device)
@@ -257,7 +266,7 @@ def main():
     wall, per_launch = time_launches(step, args.steps, args.warmup)
     ms_per_step = wall * 1e3 / args.steps
     kernel_ms = sum(per_launch) / len(per_launch)
-    bytes_per_launch = algorithmic_bytes_per_row(v, elem) * n
+    bytes_per_launch = algorithmic_bytes_per_row(v, elem, infer_elem) * n
     if args.sparse_grad:
         # no dense gradient row; the lists that were written (8 bytes per entry) and their lengths instead
         listed = glen[(flags & 8) == 0].to(torch.int64).sum().item()
@@ -265,7 +274,7 @@ def main():
     achieved = bytes_per_launch / (kernel_ms * 1e-3) / 1e9
 
     traffic = MEASURED_TRAFFIC.get(kernel_source_hash(), {}).get(args.workload) \
-        if args.rows is None and args.rho == 1e-4 and not args.sparse_grad else None
+        if args.rows is None and args.rho == 1e-4 and not args.sparse_grad and args.infer_dtype == "same" else None
 
     result = {
         "metric": "DVP fwd+bwd rows/s and achieved HBM GB/s (% of peak), V=151936 bf16",
@@ -275,14 +284,18 @@ def main():
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "configs[%d]: N=%d x V=%d %s logits (train + infer), fused "
-                               "forward+backward, rho=%g" % (cfg, n, v, str(wl.z_train.dtype)[6:], args.rho),
-                   "storage_dtype": str(wl.z_train.dtype)[6:], "n_rows": n, "vocab": v,
+        "config": {"workload": "configs[%d]: N=%d x V=%d %s logits (train + infer%s), fused "
+                               "forward+backward, rho=%g" % (cfg, n, v, str(wl.z_train.dtype)[6:],
+                                                             ", inference logits as E4M3 bytes" if infer_elem == 1 else "",
+                                                             args.rho),
+                   "storage_dtype": str(wl.z_train.dtype)[6:], "infer_storage_dtype": str(wl.z_infer.dtype)[6:],
+                   "n_rows": n, "vocab": v,
                    "rho": args.rho,
                    "entry_point": "dvp_forward_backward_sparse (list capacity %d)" % args.sparse_grad
                    if args.sparse_grad else "dvp_forward_backward",
                    "row_kernel": "resident" if dvp.lib().dvp_row_path(
-                       dvp.DvpParams(n, v, v, v, v, 1 if elem == 2 else 0, lr), 1) == 1 else "streaming",
+                       dvp.DvpParams(n, v, v, v, v, 1 if elem == 2 else 0, lr,
+                                     2 if infer_elem == 1 else (1 if elem == 2 else 0)), 1) == 1 else "streaming",
                    "input_generation_s": round(t_gen, 2)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,

@@ -17,14 +17,15 @@
  *     shapes, parameters, launch failures).  Conditions only the device can
  *     see (a sampled id outside [0, V)) are reported per row in `row_flags`.
  *   - Matrices are row-major with a row stride `ld*` given in ELEMENTS.  When
- *     base pointers and row strides are 16-byte aligned and the row fits the
- *     register file (V <= 163840 for bf16, 81920 for fp32) the rows are read
- *     from HBM exactly once; otherwise a slower re-reading path is used.
+ *     base pointers and row strides (in bytes) are 16-byte aligned and the row
+ *     fits the register file (V <= 163840 for bf16, 81920 for fp32) the rows are
+ *     read from HBM exactly once; otherwise a slower re-reading path is used.
  *   - Outputs are overwritten, never accumulated into.
  *   - With n_rows == 0 (and otherwise valid params) every entry point returns
  *     DVP_OK without looking at any pointer.
- *   - NaN or +inf logits, and rows that are entirely -inf, give unspecified
- *     values (never a fault).  -inf logits are allowed.
+ *   - NaN or +inf logits (the two NaN codes of E4M3 included), and rows that
+ *     are entirely -inf, give unspecified values (never a fault).  -inf logits
+ *     are allowed.
  */
 #ifndef DVP_H
 #define DVP_H
@@ -40,14 +41,18 @@ typedef enum {
     DVP_OK = 0,
     DVP_ERR_NULL = 1,        /* a required pointer is NULL */
     DVP_ERR_SHAPE = 2,       /* negative sizes, vocab < 1, ld < vocab, vocab > DVP_MAX_VOCAB */
-    DVP_ERR_PARAM = 3,       /* log_rho is NaN or > 0, unknown dtype */
+    DVP_ERR_PARAM = 3,       /* log_rho is NaN or > 0, unknown dtype or dtype combination */
     DVP_ERR_ALIGN = 4,       /* a pointer is not aligned to its element size */
     DVP_ERR_UNSUPPORTED = 5, /* shape or alignment outside what the entry point handles */
     DVP_ERR_WORKSPACE = 6,   /* workspace missing or too small */
     DVP_ERR_HIP = 7          /* the HIP runtime refused a launch */
 } dvp_status;
 
-typedef enum { DVP_F32 = 0, DVP_BF16 = 1 } dvp_dtype;
+typedef enum {
+    DVP_F32 = 0,
+    DVP_BF16 = 1,
+    DVP_F8E4M3 = 2 /* OCP 8-bit E4M3 (bias 7, no infinity, largest value 448): inference logits only */
+} dvp_dtype;
 
 #define DVP_MAX_VOCAB 2147418112 /* 2^31 - 2^16: column indices stay in 32 bits */
 
@@ -66,9 +71,14 @@ typedef struct {
     int64_t ld_train; /* row stride of z_train, elements, >= vocab */
     int64_t ld_infer; /* row stride of z_infer (ignored when z_infer is NULL) */
     int64_t ld_grad;  /* row stride of dz (ignored by dvp_forward) */
-    int32_t dtype;    /* dvp_dtype of z_train, z_infer and dz */
+    int32_t dtype;    /* dvp_dtype of z_train and dz: DVP_F32 or DVP_BF16 */
     float log_rho;    /* log of the pruning ratio rho of Def. 5.1, <= 0.  -INFINITY means
                          rho = 0: nothing is pruned and the result is the full log-softmax */
+    int32_t dtype_infer; /* dvp_dtype of z_infer (ignored when z_infer is NULL): the same as `dtype`,
+                            or DVP_F8E4M3 when the inference engine hands over 8-bit logits (the
+                            low-precision rollout engines of Sec. 4.2): one byte per token, widened
+                            exactly.  The single-read path takes 8-bit inference rows next to
+                            bf16 training rows with V >= 16; other combinations are re-read. */
 } dvp_params;
 
 /*

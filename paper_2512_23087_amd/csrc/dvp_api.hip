@@ -12,12 +12,13 @@ using dvp::RowArgs;
 using dvp::SideOut;
 
 inline bool aligned_to(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
-inline size_t elem_size(int dtype) { return dtype == DVP_BF16 ? 2 : 4; }
+inline size_t elem_size(int dtype) { return dtype == DVP_BF16 ? 2 : (dtype == DVP_F8E4M3 ? 1 : 4); }
 
 dvp_status check_params(const dvp_params *p, bool need_infer, bool need_grad)
 {
     if (!p) return DVP_ERR_NULL;
     if (p->dtype != DVP_F32 && p->dtype != DVP_BF16) return DVP_ERR_PARAM;
+    if (need_infer && p->dtype_infer != p->dtype && p->dtype_infer != DVP_F8E4M3) return DVP_ERR_PARAM;
     if (p->log_rho != p->log_rho || p->log_rho > 0.0f) return DVP_ERR_PARAM;
     if (p->n_rows < 0 || p->vocab < 1 || p->vocab > DVP_MAX_VOCAB) return DVP_ERR_SHAPE;
     if (p->ld_train < p->vocab) return DVP_ERR_SHAPE;
@@ -48,7 +49,7 @@ bool rows_vector_ok(const dvp_params *p, const void *z_train, const void *z_infe
 {
     const size_t es = elem_size(p->dtype);
     if (!aligned_to(z_train, 16) || (p->ld_train * es) % 16) return false;
-    if (z_infer && (!aligned_to(z_infer, 16) || (p->ld_infer * es) % 16)) return false;
+    if (z_infer && (!aligned_to(z_infer, 16) || (p->ld_infer * elem_size(p->dtype_infer)) % 16)) return false;
     if (dz && (!aligned_to(dz, 16) || (p->ld_grad * es) % 16)) return false;
     return true;
 }
@@ -64,7 +65,8 @@ dvp_status run_rows(const dvp_params *p, const void *z_train, const void *z_infe
     if (!z_train || !ids || !out_train) return DVP_ERR_NULL;
     if (backward && (!grad_out || !dz)) return DVP_ERR_NULL;
     const size_t es = elem_size(p->dtype);
-    if (!aligned_to(z_train, es) || !aligned_to(z_infer, es) || !aligned_to(dz, es) ||
+    const int dtype_infer = z_infer ? p->dtype_infer : p->dtype;
+    if (!aligned_to(z_train, es) || !aligned_to(z_infer, elem_size(dtype_infer)) || !aligned_to(dz, es) ||
         !aligned_to(ids, 8) || !aligned_to(grad_out, 4) || !side_aligned(out_train) ||
         (z_infer && !side_aligned(out_infer)))
         return DVP_ERR_ALIGN;
@@ -86,15 +88,15 @@ dvp_status run_rows(const dvp_params *p, const void *z_train, const void *z_infe
 
     a.sparse_only = 0;
     a.grad_len = nullptr;
-    const bool resident = dvp::row_fits_resident(p->dtype, p->vocab) &&
+    const bool resident = dvp::row_fits_resident(p->dtype, dtype_infer, p->vocab) &&
                           rows_vector_ok(p, z_train, z_infer, backward ? dz : nullptr);
     // Split gradient: possible when the per-row flags and safe-set sizes are
     // produced anyway (the fill kernel reads them back).
     a.split_grad = (resident && backward && row_flags && a.out[0].safe_count) ? 1 : 0;
     const int64_t cap = (int64_t)(p->vocab * es / 8) - 2;
     a.list_cap = (int32_t)(cap < 0 ? 0 : (cap > dvp::kListMax ? dvp::kListMax : cap));
-    hipError_t e = resident ? dvp::launch_rows_resident(p->dtype, a, (hipStream_t)stream)
-                            : dvp::launch_rows_streaming(p->dtype, a, (hipStream_t)stream);
+    hipError_t e = resident ? dvp::launch_rows_resident(p->dtype, dtype_infer, a, (hipStream_t)stream)
+                            : dvp::launch_rows_streaming(p->dtype, dtype_infer, a, (hipStream_t)stream);
     if (e == hipSuccess && a.split_grad) {
         dvp::FillArgs f;
         f.dz = dz; f.ld_grad = p->ld_grad;
@@ -138,12 +140,14 @@ dvp_status dvp_forward_backward_sparse(const dvp_params *params, const void *z_t
     if (params->n_rows == 0) return DVP_OK;
     if (!z_train || !ids || !out_train || !grad_out || !row_flags || !entries) return DVP_ERR_NULL;
     const size_t es = elem_size(params->dtype);
-    if (!aligned_to(z_train, es) || !aligned_to(z_infer, es) || !aligned_to(ids, 8) ||
+    const int dtype_infer = z_infer ? params->dtype_infer : params->dtype;
+    if (!aligned_to(z_train, es) || !aligned_to(z_infer, elem_size(dtype_infer)) || !aligned_to(ids, 8) ||
         !aligned_to(grad_out, 4) || !aligned_to(entries, 8) || !aligned_to(grad_len, 4) ||
         !side_aligned(out_train) || (z_infer && !side_aligned(out_infer)))
         return DVP_ERR_ALIGN;
     // the lists are formed from rows held in registers: single-read path only
-    if (!dvp::row_fits_resident(params->dtype, params->vocab) || !rows_vector_ok(params, z_train, z_infer, nullptr))
+    if (!dvp::row_fits_resident(params->dtype, dtype_infer, params->vocab) ||
+        !rows_vector_ok(params, z_train, z_infer, nullptr))
         return DVP_ERR_UNSUPPORTED;
 
     RowArgs a;
@@ -158,7 +162,8 @@ dvp_status dvp_forward_backward_sparse(const dvp_params *params, const void *z_t
     a.n_sides = z_infer ? 2 : 1;
     a.log_rho = params->log_rho;
     a.split_grad = 1; a.list_cap = list_cap; a.sparse_only = 1; a.grad_len = grad_len;
-    return dvp::launch_rows_resident(params->dtype, a, (hipStream_t)stream) == hipSuccess ? DVP_OK : DVP_ERR_HIP;
+    return dvp::launch_rows_resident(params->dtype, dtype_infer, a, (hipStream_t)stream) == hipSuccess ? DVP_OK
+                                                                                                     : DVP_ERR_HIP;
 }
 
 dvp_status dvp_backward(const dvp_params *params, const void *z_train, const int64_t *ids,
@@ -216,8 +221,10 @@ int dvp_row_path(const dvp_params *params, int aligned16)
 {
     if (check_params(params, false, false) != DVP_OK) return -1;
     const size_t es = elem_size(params->dtype);
-    const bool ld_ok = (params->ld_train * es) % 16 == 0;
-    return (dvp::row_fits_resident(params->dtype, params->vocab) && aligned16 && ld_ok) ? 1 : 0;
+    const int dtype_infer = params->dtype_infer == DVP_F8E4M3 ? DVP_F8E4M3 : params->dtype;
+    const bool ld_ok = (params->ld_train * es) % 16 == 0 &&
+                       (dtype_infer != DVP_F8E4M3 || params->ld_infer % 16 == 0);
+    return (dvp::row_fits_resident(params->dtype, dtype_infer, params->vocab) && aligned16 && ld_ok) ? 1 : 0;
 }
 
 float dvp_log_rho(double rho)

@@ -11,15 +11,26 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kWave = 64;
 
 struct bf16_t { uint16_t bits; };   // storage-only tag type for bf16 rows
+struct f8_t { uint8_t bits; };      // storage-only tag type for 8-bit E4M3 rows (OCP: bias 7, no infinity, max 448)
 
 template <typename T> struct elem_traits;
 template <> struct elem_traits<float> {
     static constexpr int kPerVec = 4;
+    static constexpr int kPerPart = 4;
     static constexpr uint32_t kPadWord = 0xff800000u;   // -inf
+    static constexpr bool kHasNegInf = true;
 };
 template <> struct elem_traits<bf16_t> {
     static constexpr int kPerVec = 8;
+    static constexpr int kPerPart = 8;
     static constexpr uint32_t kPadWord = 0xff80ff80u;   // two bf16 -inf
+    static constexpr bool kHasNegInf = true;
+};
+template <> struct elem_traits<f8_t> {
+    static constexpr int kPerVec = 16;
+    static constexpr int kPerPart = 8;                  // widened half a vector at a time
+    static constexpr uint32_t kPadWord = 0u;            // the format has no -inf: readers mask by index
+    static constexpr bool kHasNegInf = false;
 };
 
 __device__ __forceinline__ float bits_to_float(uint32_t u) { return __uint_as_float(u); }
@@ -47,6 +58,22 @@ __device__ __forceinline__ void unpack(const u32x4 v, float (&x)[8], bf16_t)
     x[6] = bits_to_float(v.w << 16); x[7] = bits_to_float(v.w & 0xffff0000u);
 }
 
+// 8-bit E4M3 -> fp32 with the hardware converter (exact: every code is an fp32 value)
+__device__ __forceinline__ float e4m3_to_float(uint32_t byte) { return __builtin_amdgcn_cvt_f32_fp8((int)byte, 0); }
+__device__ __forceinline__ void unpack(const u32x4 v, float (&x)[8], int part, f8_t)   // bytes 8*part .. 8*part+7
+{
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    const uint32_t w[2] = {part == 0 ? v.x : v.z, part == 0 ? v.y : v.w};
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], false);
+        const f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], true);
+        x[4 * i + 0] = lo.x; x[4 * i + 1] = lo.y; x[4 * i + 2] = hi.x; x[4 * i + 3] = hi.y;
+    }
+}
+__device__ __forceinline__ void unpack(const u32x4 v, float (&x)[4], int, float) { unpack(v, x, float()); }
+__device__ __forceinline__ void unpack(const u32x4 v, float (&x)[8], int, bf16_t) { unpack(v, x, bf16_t()); }
+
 __device__ __forceinline__ u32x4 pack(const float (&d)[4], float)
 {
     u32x4 v;
@@ -69,6 +96,7 @@ __device__ __forceinline__ float load_elem(const bf16_t *p)
 {
     return bits_to_float((uint32_t)p->bits << 16);
 }
+__device__ __forceinline__ float load_elem(const f8_t *p) { return e4m3_to_float(p->bits); }
 __device__ __forceinline__ void store_elem(float *p, float v) { *p = v; }
 __device__ __forceinline__ void store_elem(bf16_t *p, float v)
 {

@@ -81,12 +81,13 @@ struct SequenceArgs {
     float log_threshold;
 };
 
-// true when the register-resident kernel can take a row of this many elements
-bool row_fits_resident(int dtype, int64_t vocab);
+// true when the register-resident kernel can take rows of this many elements
+// (dtype: training rows and gradient; dtype_infer: inference rows)
+bool row_fits_resident(int dtype, int dtype_infer, int64_t vocab);
 
 // Launchers: return hipSuccess or the launch error.
-hipError_t launch_rows_resident(int dtype, const RowArgs &a, hipStream_t stream);
-hipError_t launch_rows_streaming(int dtype, const RowArgs &a, hipStream_t stream);
+hipError_t launch_rows_resident(int dtype, int dtype_infer, const RowArgs &a, hipStream_t stream);
+hipError_t launch_rows_streaming(int dtype, int dtype_infer, const RowArgs &a, hipStream_t stream);
 hipError_t launch_grad_fill(int dtype, const FillArgs &a, hipStream_t stream);
 hipError_t launch_backward(int dtype, const BackwardArgs &a, bool vector_ok, hipStream_t stream);
 hipError_t launch_sequences(const SequenceArgs &a, hipStream_t stream);

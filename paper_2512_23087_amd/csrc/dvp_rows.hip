@@ -45,16 +45,39 @@ __device__ __forceinline__ u32x4 load_slot(const T *zrow, int j, int t, int nvec
     return v;
 }
 
+// Unpack part `part` of a slot (a slot is read in kParts pieces so that no
+// more than 8 widened elements are live at a time).  Formats with a -inf
+// encoding pad the slots past the end of the row with it at load time; 8-bit
+// E4M3 has none, so those elements are replaced here (only the slots that can
+// lie past the end pay for the test).
+template <typename T, int NT, int NVFULL>
+__device__ __forceinline__ void unpack_part(const u32x4 v, float (&x)[elem_traits<T>::kPerPart], int part, int j,
+                                            int tid, int nvec)
+{
+    unpack(v, x, part, T());
+    if constexpr (!elem_traits<T>::kHasNegInf) {
+        if (j >= NVFULL && j * NT + tid >= nvec) {
+#pragma unroll
+            for (int e = 0; e < elem_traits<T>::kPerPart; ++e) x[e] = -INFINITY;
+        }
+    }
+}
+
 // Single elements fetched ahead of time stay in their stored form until they
 // are used: converting right after the load would make the wavefront wait for
 // the memory round trip on the spot.
 __device__ __forceinline__ uint32_t load_raw(const float *p) { return __float_as_uint(*p); }
 __device__ __forceinline__ uint32_t load_raw(const bf16_t *p) { return p->bits; }
+__device__ __forceinline__ uint32_t load_raw(const f8_t *p) { return p->bits; }
 __device__ __forceinline__ float from_raw(uint32_t u, float) { return __uint_as_float(u); }
 __device__ __forceinline__ float from_raw(uint32_t u, bf16_t) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float from_raw(uint32_t u, f8_t)    // bit 8 set: no element here
+{
+    return (u & 0x100u) ? -INFINITY : e4m3_to_float(u);
+}
 template <typename T> __device__ __forceinline__ uint32_t raw_neg_inf()
 {
-    return sizeof(T) == 2 ? 0xff80u : 0xff800000u;
+    return sizeof(T) == 1 ? 0x100u : (sizeof(T) == 2 ? 0xff80u : 0xff800000u);
 }
 
 // Append the (index, value) pairs of the lanes with `take` set to a row's
@@ -88,6 +111,274 @@ __device__ __forceinline__ u32x4 pack_grad(const float (&d)[8], bf16_t)
     return v;
 }
 
+// What a workgroup carries from one task (one side of one row) to the next.
+struct TaskState {
+    int64_t row;
+    int side;            // 1 = inference row, 0 = training row
+    int64_t y;
+    bool y_ok;
+    float g;
+    uint32_t zy_raw;     // the sampled token's logit (stored form)
+    uint32_t xt_raw;     // this thread's element of the ragged end (stored form), or -inf
+    uint32_t flags;
+};
+
+// One task: everything one side of one row needs, from the registers.
+//   TS / NVS / NVFULL_S   element type of this task's row, the register slots it
+//                         occupies and how many of them are full in every thread
+//   TN / NVN / NVFULL_N   the same for the task after it, whose vectors are
+//                         loaded into the slots as this task lets go of them
+// Returns false after the workgroup's last task.
+template <typename TS, int NVS, int NVFULL_S, typename TN, int NVN, int NVFULL_N, int NV, int NT, bool EXTRAS,
+          bool CAN_BWD>
+__device__ __forceinline__ bool row_task(const RowArgs &a, TaskState &s, u32x4 (&r)[NV], float *lds_max,
+                                         float *lds_f, int *lds_i, int *lds_list_count)
+{
+    using TR = elem_traits<TS>;
+    constexpr int EPV = TR::kPerVec;
+    constexpr int EPP = TR::kPerPart;      // elements widened at a time
+    constexpr int PARTS = EPV / EPP;
+    constexpr int EPV_N = elem_traits<TN>::kPerVec;
+    constexpr int NW = NT / kWave;
+    static_assert(NVS <= NV && NVN <= NV, "slots");
+    static_assert(!CAN_BWD || PARTS == 1, "gradient rows are widened whole");
+
+    const int tid = threadIdx.x;
+    const int V = a.vocab;
+    const int nvec = V / EPV;              // whole vectors in this task's row
+    const int tail = V - nvec * EPV;       // elements in its ragged end
+    const int nvec_n = V / EPV_N;          // the same for the next task's row
+    const int tail_n = V - nvec_n * EPV_N;
+    const float log_rho = a.log_rho;
+    const bool want_bwd = CAN_BWD && a.grad_out != nullptr;
+    const int bits_words = (V + 31) / 32;
+    const int first_side = a.n_sides - 1;  // inference row first, training row last
+
+    const int64_t row = s.row;
+    const int side = s.side;
+    const int64_t y = s.y;
+    const bool y_ok = s.y_ok;
+    const float g = s.g;
+    uint32_t flags = s.flags;
+
+    // ---- the task after this one (its loads are issued during this task's last phase) ----
+    int64_t nrow = row, ny = y;
+    int nside = side - 1;
+    if (nside < 0) { nrow = row + gridDim.x; nside = first_side; }
+    const bool has_next = nrow < a.n_rows;
+    float ng = g;
+    if (has_next && nrow != row) {
+        ny = a.ids[nrow];
+        if (a.grad_out != nullptr) ng = a.grad_out[nrow];
+    }
+    const bool ny_ok = (ny >= 0) && (ny < (int64_t)V);
+    const TN *znext = (const TN *)a.z[has_next ? nside : side] + (has_next ? nrow : row) * a.ld[has_next ? nside : side];
+    uint32_t nzy_raw = 0, nxt_raw = raw_neg_inf<TN>();
+    const float xt = from_raw(s.xt_raw, TS());
+    const float zy = from_raw(s.zy_raw, TS());
+
+    // slots this task's row does not reach are free for the next row from the start
+    if constexpr (NVN > NVS) {
+        if (has_next) {
+#pragma unroll
+            for (int j = NVS; j < NVN; ++j) r[j] = load_slot<TN, NT, NVFULL_N>(znext, j, fresh(tid), nvec_n);
+        }
+    }
+
+    const SideOut &out = a.out[side];
+    const bool want_full = EXTRAS && out.lse_full != nullptr;
+    uint8_t *bits_row = (EXTRAS && out.safe_bits)
+        ? (uint8_t *)(out.safe_bits + row * (int64_t)bits_words) : nullptr;
+    const bool bwd_here = want_bwd && side == 0;
+
+    // ---- row maximum (Def. 5.1) ----
+    float m = xt;
+#pragma unroll
+    for (int j = 0; j < NVS; ++j) {
+#pragma unroll
+        for (int part = 0; part < PARTS; ++part) {
+            float x[EPP];
+            unpack_part<TS, NT, NVFULL_S>(r[j], x, part, j, tid, nvec);
+#pragma unroll
+            for (int e = 0; e < EPP; ++e) m = fmaxf(m, x[e]);
+        }
+    }
+    m = block_max<NT>(m, lds_max);
+#pragma unroll
+    for (int j = 0; j < NVS; ++j) keep_packed(r[j]);
+    // every wavefront is past the previous row's appends (it reached the barrier
+    // above) and the next appends come after one more barrier
+    if (tid == 0) *lds_list_count = 0;
+
+    // ---- threshold, membership, size, masked sum (Def. 5.1 / 5.2) ----
+    const float tau = m + log_rho;   // one fp32 rounding
+    float s_safe = 0.0f, s_full = 0.0f;
+    int wave_count = 0;              // wavefront-uniform: lanes are counted with scalar popcounts
+    uint32_t any_mask = 0;           // bit j: some lane of this wavefront has a safe token in slot j
+    if (has_next) {   // the next task's single elements, fetched early and left in stored form
+        if (ny_ok) nzy_raw = load_raw(znext + ny);
+        if (tid < tail_n) nxt_raw = load_raw(znext + (int64_t)nvec_n * EPV_N + tid);
+    }
+    {   // ragged end: one element per thread
+        wave_count += __builtin_popcountll(__builtin_amdgcn_ballot_w64(xt >= tau));
+        const float ex = __expf(xt - m);
+        s_safe += (xt >= tau) ? ex : 0.0f;
+        if (want_full) s_full += ex;
+    }
+#pragma unroll
+    for (int j = 0; j < NVS; ++j) {
+        bool any = false;
+        uint32_t mask = 0;
+#pragma unroll
+        for (int part = 0; part < PARTS; ++part) {
+            float x[EPP];
+            unpack_part<TS, NT, NVFULL_S>(r[j], x, part, j, tid, nvec);
+            const int before = wave_count;
+#pragma unroll
+            for (int e = 0; e < EPP; ++e)
+                wave_count += __builtin_popcountll(__builtin_amdgcn_ballot_w64(x[e] >= tau));
+            const bool any_part = wave_count != before;
+            any |= any_part;
+            if (want_full) {
+#pragma unroll
+                for (int e = 0; e < EPP; ++e) {
+                    const float ex = __expf(x[e] - m);
+                    s_full += ex;
+                    s_safe += (x[e] >= tau) ? ex : 0.0f;
+                }
+            } else if (any_part) {   // wavefront-uniform: all-pruned vectors cost no exp
+#pragma unroll
+                for (int e = 0; e < EPP; ++e) s_safe += (x[e] >= tau) ? __expf(x[e] - m) : 0.0f;
+            }
+            if (EXTRAS && bits_row) {
+                const int idx = j * NT + fresh(tid);
+                if (idx == nvec && tail) {   // the slot after the last whole vector carries the ragged end's bits
+                    const TS *zrow = (const TS *)a.z[side] + row * a.ld[side] + (int64_t)nvec * EPV;
+#pragma unroll
+                    for (int e = 0; e < EPP; ++e)
+                        x[e] = part * EPP + e < tail ? load_elem(zrow + part * EPP + e) : -INFINITY;
+                }
+#pragma unroll
+                for (int e = 0; e < EPP; ++e) mask |= (x[e] >= tau ? 1u : 0u) << (part * EPP + e);
+            }
+        }
+        if (any) any_mask |= 1u << j;
+        if (EXTRAS && bits_row) {
+            const int idx = j * NT + fresh(tid);
+            mask &= idx < nvec ? ((1u << EPV) - 1u) : (idx == nvec ? (1u << tail) - 1u : 0u);
+            if constexpr (EPV == 16) {
+                if (idx < 2 * bits_words) ((uint16_t *)bits_row)[idx] = (uint16_t)mask;
+            } else if constexpr (EPV == 8) {
+                if (idx < 4 * bits_words) bits_row[idx] = (uint8_t)mask;
+            } else {
+                const uint32_t other = __shfl_xor(mask, 1, kWave);
+                if (!(idx & 1) && (idx >> 1) < 4 * bits_words)
+                    bits_row[idx >> 1] = (uint8_t)(mask | (other << 4));
+            }
+        }
+        // a slot the gradient phase will not read again (no safe token in this
+        // wavefront's part of it) is refilled right away
+        if (j < NVN && has_next && (!bwd_here || !any)) r[j] = load_slot<TN, NT, NVFULL_N>(znext, j, fresh(tid), nvec_n);
+    }
+    s_safe = wave_sum(s_safe);
+    if (want_full) s_full = wave_sum(s_full);
+    if ((tid & (kWave - 1)) == 0) {
+        const int w = tid / kWave;
+        lds_f[w] = s_safe;
+        lds_f[NW + w] = s_full;
+        lds_i[w] = wave_count;
+    }
+    __syncthreads();
+    RowSums acc = {lds_f[0], lds_f[NW], lds_i[0]};
+#pragma unroll
+    for (int w = 1; w < NW; ++w) {   // fixed order: results are run-to-run identical
+        acc.s_safe += lds_f[w];
+        acc.s_full += lds_f[NW + w];
+        acc.count += lds_i[w];
+    }
+    if (tau == -INFINITY) acc.count = V;   // nothing pruned; do not count the -inf padding
+
+    const float log_s = logf(acc.s_safe);
+    const bool y_safe = y_ok && (zy >= tau);
+    if (y_safe) flags |= (side == 0 ? DVP_ROW_Y_IN_TRAIN_SAFE : DVP_ROW_Y_IN_INFER_SAFE);
+    // list-only output: a safe set longer than the list's capacity is reported, not written
+    const bool overflow = a.sparse_only && bwd_here && y_safe && acc.count > a.list_cap;
+    if (overflow) flags |= DVP_ROW_GRAD_OVERFLOW;
+    if (tid == 0) {
+        if (bwd_here && a.grad_len) a.grad_len[row] = y_safe ? acc.count : 0;
+        if (out.row_max) out.row_max[row] = m;
+        if (out.lse_safe) out.lse_safe[row] = m + log_s;
+        if (want_full) out.lse_full[row] = m + logf(acc.s_full);
+        if (out.safe_count) out.safe_count[row] = acc.count;
+        if (out.logp)
+            out.logp[row] = !y_ok ? __uint_as_float(0x7fc00000u)
+                                  : (y_safe ? (zy - m) - log_s : -INFINITY);
+        if (side == 0 && a.row_flags) a.row_flags[row] = (uint8_t)flags;
+    }
+
+    // ---- gradient of the training row (Prop. 5.4), straight from the registers.
+    // Dense rows are written here.  In split mode a row with a short safe set
+    // (or a pruned sampled token: all zero) only leaves its (index, value)
+    // pairs at the start of the gradient row; the fill kernel writes the row
+    // afterwards, so this kernel's memory traffic stays (almost) read-only.
+    if constexpr (CAN_BWD) {
+    if (bwd_here) {
+        const bool dense_out = !a.sparse_only;
+        TS *dzrow = (TS *)a.dz + (dense_out ? row * a.ld_grad : 0);
+        u32x4 *dzvec = (u32x4 *)dzrow;
+        uint2 *list = dense_out ? (uint2 *)dzrow : (uint2 *)a.dz + row * (int64_t)a.list_cap;
+        const bool listed = a.split_grad && !(y_safe && acc.count > a.list_cap);
+        const bool grad_row = y_safe && !overflow;     // an overflowing row is only walked to refill its slots
+        const float neg_g = -g;
+        const int t = fresh(tid);
+        const int64_t y_slot = grad_row ? (y / EPV) : -1;
+        {   // ragged end
+            const int64_t k = (int64_t)nvec * EPV + t;
+            const bool safe = grad_row && t < tail && xt >= tau;
+            float d = 0.0f;
+            if (safe) d = neg_g * __expf((xt - m) - log_s) - (k == y ? neg_g : 0.0f);
+            if (listed) list_append(list, lds_list_count, safe, (uint32_t)k, d);
+            else if (t < tail && dense_out) store_elem(dzrow + k, d);
+        }
+#pragma unroll
+        for (int j = 0; j < NVS; ++j) {
+            const int idx = j * NT + t;
+            u32x4 o = {0u, 0u, 0u, 0u};
+            if (grad_row && ((any_mask >> j) & 1u)) {   // wavefront-uniform
+                float x[EPV], d[EPV];
+                keep_packed(r[j]);
+                unpack(r[j], x, TS());
+#pragma unroll
+                for (int e = 0; e < EPV; ++e)
+                    d[e] = (x[e] >= tau) ? neg_g * __expf((x[e] - m) - log_s) : 0.0f;
+                if ((int64_t)idx == y_slot) {          // the sampled token: g * (1 - p)
+                    const int ey = (int)(y - (int64_t)idx * EPV);
+#pragma unroll
+                    for (int e = 0; e < EPV; ++e)
+                        if (e == ey) d[e] -= neg_g;
+                }
+                if (listed) {
+                    const bool real = j < NVFULL_S || idx < nvec;   // padding slots pass a -inf threshold
+#pragma unroll
+                    for (int e = 0; e < EPV; ++e)
+                        list_append(list, lds_list_count, real && x[e] >= tau, (uint32_t)(idx * EPV + e), d[e]);
+                } else {
+                    o = pack_grad(d, TS());
+                }
+            }
+            if (!listed && dense_out && (j < NVFULL_S || idx < nvec)) __builtin_nontemporal_store(o, dzvec + idx);
+            if (j < NVN && has_next && ((any_mask >> j) & 1u)) r[j] = load_slot<TN, NT, NVFULL_N>(znext, j, t, nvec_n);
+        }
+    }
+    }
+
+    if (!has_next) return false;
+    if (nrow != row) flags = ny_ok ? 0u : (uint32_t)DVP_ROW_ID_OUT_OF_RANGE;
+    s.row = nrow; s.side = nside; s.y = ny; s.y_ok = ny_ok; s.g = ng; s.zy_raw = nzy_raw; s.xt_raw = nxt_raw;
+    s.flags = flags;
+    return true;
+}
+
 // The workgroup walks a list of tasks: for each of its rows, the inference
 // side then the training side.  While the last phase of a task consumes the
 // registers, each freed slot is refilled with the next task's vector, so the
@@ -109,229 +400,79 @@ __global__ __launch_bounds__(NT, MINW) void rows_resident_kernel(const RowArgs a
     const int V = a.vocab;
     const int nvec = V / EPV;              // whole vectors in a row (>= 1, checked by the launcher)
     const int tail = V - nvec * EPV;       // elements in the ragged end
-    const float log_rho = a.log_rho;
-    const bool want_bwd = a.grad_out != nullptr;
-    const int bits_words = (V + 31) / 32;
-    const int first_side = a.n_sides - 1;  // inference row first, training row last
+    if ((int64_t)blockIdx.x >= a.n_rows) return;
 
-    int64_t row = blockIdx.x;
-    if (row >= a.n_rows) return;
-    int side = first_side;
-
+    TaskState s;
+    s.row = blockIdx.x;
+    s.side = a.n_sides - 1;                // inference row first, training row last
+    s.y = a.ids[s.row];
+    s.y_ok = (s.y >= 0) && (s.y < (int64_t)V);
+    s.g = a.grad_out ? a.grad_out[s.row] : 0.0f;
+    s.xt_raw = raw_neg_inf<T>();
+    s.zy_raw = 0;
+    s.flags = s.y_ok ? 0u : (uint32_t)DVP_ROW_ID_OUT_OF_RANGE;
     u32x4 r[NV];
-    uint32_t xt_raw = raw_neg_inf<T>();    // this thread's element of the ragged end (stored form), or -inf
-    uint32_t zy_raw = 0;                   // the sampled token's logit (stored form)
-    int64_t y = a.ids[row];
-    bool y_ok = (y >= 0) && (y < (int64_t)V);
-    float g = want_bwd ? a.grad_out[row] : 0.0f;
     {
-        const T *zrow = (const T *)a.z[side] + row * a.ld[side];
+        const T *zrow = (const T *)a.z[s.side] + s.row * a.ld[s.side];
         const int t = fresh(tid);
 #pragma unroll
         for (int j = 0; j < NV; ++j) r[j] = load_slot<T, NT, NVFULL>(zrow, j, t, nvec);
-        if (t < tail) xt_raw = load_raw(zrow + (int64_t)nvec * EPV + t);
-        if (y_ok) zy_raw = load_raw(zrow + y);
+        if (t < tail) s.xt_raw = load_raw(zrow + (int64_t)nvec * EPV + t);
+        if (s.y_ok) s.zy_raw = load_raw(zrow + s.y);
     }
-    uint32_t flags = y_ok ? 0u : (uint32_t)DVP_ROW_ID_OUT_OF_RANGE;
+    while (row_task<T, NV, NVFULL, T, NV, NVFULL, NV, NT, EXTRAS, true>(a, s, r, lds_max, lds_f, lds_i, &lds_list_count)) {}
+}
 
+// The same walk when the inference logits are stored as 8-bit E4M3 codes: an
+// inference row then takes half the register slots of a training row and half
+// the HBM bytes.  Always two sides; tasks alternate between the two types.
+template <typename T, int NV, int NVFULL, int NT, int MINW, bool EXTRAS>
+__global__ __launch_bounds__(NT, MINW) void rows_resident_f8infer_kernel(const RowArgs a)
+{
+    constexpr int NVI = (NV + 1) / 2, NVFULL_I = NVFULL / 2;
+    constexpr int EPV_I = elem_traits<f8_t>::kPerVec;
+    constexpr int NW = NT / kWave;
+    __shared__ float lds_max[NW];
+    __shared__ float lds_f[2 * NW];
+    __shared__ int lds_i[NW];
+    __shared__ int lds_list_count;
+
+    const int tid = threadIdx.x;
+    const int V = a.vocab;
+    const int nvec_i = V / EPV_I;
+    const int tail_i = V - nvec_i * EPV_I;
+    if ((int64_t)blockIdx.x >= a.n_rows) return;
+
+    TaskState s;
+    s.row = blockIdx.x;
+    s.side = 1;
+    s.y = a.ids[s.row];
+    s.y_ok = (s.y >= 0) && (s.y < (int64_t)V);
+    s.g = a.grad_out ? a.grad_out[s.row] : 0.0f;
+    s.xt_raw = raw_neg_inf<f8_t>();
+    s.zy_raw = 0;
+    s.flags = s.y_ok ? 0u : (uint32_t)DVP_ROW_ID_OUT_OF_RANGE;
+    u32x4 r[NV];
+    {
+        const f8_t *zrow = (const f8_t *)a.z[1] + s.row * a.ld[1];
+        const int t = fresh(tid);
+#pragma unroll
+        for (int j = 0; j < NVI; ++j) r[j] = load_slot<f8_t, NT, NVFULL_I>(zrow, j, t, nvec_i);
+        if (t < tail_i) s.xt_raw = load_raw(zrow + (int64_t)nvec_i * EPV_I + t);
+        if (s.y_ok) s.zy_raw = load_raw(zrow + s.y);
+    }
     for (;;) {
-        // ---- the task after this one (its loads are issued during this task's last phase) ----
-        int64_t nrow = row, ny = y;
-        int nside = side - 1;
-        if (nside < 0) { nrow = row + gridDim.x; nside = first_side; }
-        const bool has_next = nrow < a.n_rows;
-        float ng = g;
-        if (has_next && nrow != row) {
-            ny = a.ids[nrow];
-            if (want_bwd) ng = a.grad_out[nrow];
-        }
-        const bool ny_ok = (ny >= 0) && (ny < (int64_t)V);
-        const T *znext = (const T *)a.z[has_next ? nside : side] + (has_next ? nrow : row) * a.ld[has_next ? nside : side];
-        uint32_t nzy_raw = 0, nxt_raw = raw_neg_inf<T>();
-        const float xt = from_raw(xt_raw, T());
-        const float zy = from_raw(zy_raw, T());
-
-        const SideOut &out = a.out[side];
-        const bool want_full = EXTRAS && out.lse_full != nullptr;
-        uint8_t *bits_row = (EXTRAS && out.safe_bits)
-            ? (uint8_t *)(out.safe_bits + row * (int64_t)bits_words) : nullptr;
-        const bool bwd_here = want_bwd && side == 0;
-
-        // ---- row maximum (Def. 5.1) ----
-        float m = xt;
-#pragma unroll
-        for (int j = 0; j < NV; ++j) {
-            float x[EPV];
-            unpack(r[j], x, T());
-#pragma unroll
-            for (int e = 0; e < EPV; ++e) m = fmaxf(m, x[e]);
-        }
-        m = block_max<NT>(m, lds_max);
-#pragma unroll
-        for (int j = 0; j < NV; ++j) keep_packed(r[j]);
-        // every wavefront is past the previous row's appends (it reached the barrier
-        // above) and the next appends come after one more barrier
-        if (tid == 0) lds_list_count = 0;
-
-        // ---- threshold, membership, size, masked sum (Def. 5.1 / 5.2) ----
-        const float tau = m + log_rho;   // one fp32 rounding
-        float s_safe = 0.0f, s_full = 0.0f;
-        int wave_count = 0;              // wavefront-uniform: lanes are counted with scalar popcounts
-        uint32_t any_mask = 0;           // bit j: some lane of this wavefront has a safe token in slot j
-        if (has_next) {   // the next task's single elements, fetched early and left in stored form
-            if (ny_ok) nzy_raw = load_raw(znext + ny);
-            if (tid < tail) nxt_raw = load_raw(znext + (int64_t)nvec * EPV + tid);
-        }
-        {   // ragged end: one element per thread
-            wave_count += __builtin_popcountll(__builtin_amdgcn_ballot_w64(xt >= tau));
-            const float ex = __expf(xt - m);
-            s_safe += (xt >= tau) ? ex : 0.0f;
-            if (want_full) s_full += ex;
-        }
-#pragma unroll
-        for (int j = 0; j < NV; ++j) {
-            float x[EPV];
-            unpack(r[j], x, T());
-            const int before = wave_count;
-#pragma unroll
-            for (int e = 0; e < EPV; ++e)
-                wave_count += __builtin_popcountll(__builtin_amdgcn_ballot_w64(x[e] >= tau));
-            const bool any = wave_count != before;
-            if (any) any_mask |= 1u << j;
-            if (want_full) {
-#pragma unroll
-                for (int e = 0; e < EPV; ++e) {
-                    const float ex = __expf(x[e] - m);
-                    s_full += ex;
-                    s_safe += (x[e] >= tau) ? ex : 0.0f;
-                }
-            } else if (any) {   // wavefront-uniform: all-pruned vectors cost no exp
-#pragma unroll
-                for (int e = 0; e < EPV; ++e) s_safe += (x[e] >= tau) ? __expf(x[e] - m) : 0.0f;
-            }
-            if (EXTRAS && bits_row) {
-                const int idx = j * NT + fresh(tid);
-                if (idx == nvec && tail) {   // the slot after the last whole vector carries the ragged end's bits
-                    const T *zrow = (const T *)a.z[side] + row * a.ld[side] + (int64_t)nvec * EPV;
-#pragma unroll
-                    for (int e = 0; e < EPV; ++e) x[e] = e < tail ? load_elem(zrow + e) : -INFINITY;
-                }
-                uint32_t mask = 0;
-#pragma unroll
-                for (int e = 0; e < EPV; ++e) mask |= (x[e] >= tau ? 1u : 0u) << e;
-                mask &= idx < nvec ? ((1u << EPV) - 1u) : (idx == nvec ? (1u << tail) - 1u : 0u);
-                if constexpr (EPV == 8) {
-                    if (idx < 4 * bits_words) bits_row[idx] = (uint8_t)mask;
-                } else {
-                    const uint32_t other = __shfl_xor(mask, 1, kWave);
-                    if (!(idx & 1) && (idx >> 1) < 4 * bits_words)
-                        bits_row[idx >> 1] = (uint8_t)(mask | (other << 4));
-                }
-            }
-            // a slot the gradient phase will not read again (no safe token in this
-            // wavefront's part of it) is refilled right away
-            if (has_next && (!bwd_here || !any)) r[j] = load_slot<T, NT, NVFULL>(znext, j, fresh(tid), nvec);
-        }
-        s_safe = wave_sum(s_safe);
-        if (want_full) s_full = wave_sum(s_full);
-        if ((tid & (kWave - 1)) == 0) {
-            const int w = tid / kWave;
-            lds_f[w] = s_safe;
-            lds_f[NW + w] = s_full;
-            lds_i[w] = wave_count;
-        }
-        __syncthreads();
-        RowSums acc = {lds_f[0], lds_f[NW], lds_i[0]};
-#pragma unroll
-        for (int w = 1; w < NW; ++w) {   // fixed order: results are run-to-run identical
-            acc.s_safe += lds_f[w];
-            acc.s_full += lds_f[NW + w];
-            acc.count += lds_i[w];
-        }
-        if (tau == -INFINITY) acc.count = V;   // nothing pruned; do not count the -inf padding
-
-        const float log_s = logf(acc.s_safe);
-        const bool y_safe = y_ok && (zy >= tau);
-        if (y_safe) flags |= (side == 0 ? DVP_ROW_Y_IN_TRAIN_SAFE : DVP_ROW_Y_IN_INFER_SAFE);
-        // list-only output: a safe set longer than the list's capacity is reported, not written
-        const bool overflow = a.sparse_only && bwd_here && y_safe && acc.count > a.list_cap;
-        if (overflow) flags |= DVP_ROW_GRAD_OVERFLOW;
-        if (tid == 0) {
-            if (bwd_here && a.grad_len) a.grad_len[row] = y_safe ? acc.count : 0;
-            if (out.row_max) out.row_max[row] = m;
-            if (out.lse_safe) out.lse_safe[row] = m + log_s;
-            if (want_full) out.lse_full[row] = m + logf(acc.s_full);
-            if (out.safe_count) out.safe_count[row] = acc.count;
-            if (out.logp)
-                out.logp[row] = !y_ok ? __uint_as_float(0x7fc00000u)
-                                      : (y_safe ? (zy - m) - log_s : -INFINITY);
-            if (side == 0 && a.row_flags) a.row_flags[row] = (uint8_t)flags;
-        }
-
-        // ---- gradient of the training row (Prop. 5.4), straight from the registers.
-        // Dense rows are written here.  In split mode a row with a short safe set
-        // (or a pruned sampled token: all zero) only leaves its (index, value)
-        // pairs at the start of the gradient row; the fill kernel writes the row
-        // afterwards, so this kernel's memory traffic stays (almost) read-only.
-        if (bwd_here) {
-            const bool dense_out = !a.sparse_only;
-            T *dzrow = (T *)a.dz + (dense_out ? row * a.ld_grad : 0);
-            u32x4 *dzvec = (u32x4 *)dzrow;
-            uint2 *list = dense_out ? (uint2 *)dzrow : (uint2 *)a.dz + row * (int64_t)a.list_cap;
-            const bool listed = a.split_grad && !(y_safe && acc.count > a.list_cap);
-            const bool grad_row = y_safe && !overflow;     // an overflowing row is only walked to refill its slots
-            const float neg_g = -g;
-            const int t = fresh(tid);
-            const int64_t y_slot = grad_row ? (y / EPV) : -1;
-            {   // ragged end
-                const int64_t k = (int64_t)nvec * EPV + t;
-                const bool safe = grad_row && t < tail && xt >= tau;
-                float d = 0.0f;
-                if (safe) d = neg_g * __expf((xt - m) - log_s) - (k == y ? neg_g : 0.0f);
-                if (listed) list_append(list, &lds_list_count, safe, (uint32_t)k, d);
-                else if (t < tail && dense_out) store_elem(dzrow + k, d);
-            }
-#pragma unroll
-            for (int j = 0; j < NV; ++j) {
-                const int idx = j * NT + t;
-                u32x4 o = {0u, 0u, 0u, 0u};
-                if (grad_row && ((any_mask >> j) & 1u)) {   // wavefront-uniform
-                    float x[EPV], d[EPV];
-                    keep_packed(r[j]);
-                    unpack(r[j], x, T());
-#pragma unroll
-                    for (int e = 0; e < EPV; ++e)
-                        d[e] = (x[e] >= tau) ? neg_g * __expf((x[e] - m) - log_s) : 0.0f;
-                    if ((int64_t)idx == y_slot) {          // the sampled token: g * (1 - p)
-                        const int ey = (int)(y - (int64_t)idx * EPV);
-#pragma unroll
-                        for (int e = 0; e < EPV; ++e)
-                            if (e == ey) d[e] -= neg_g;
-                    }
-                    if (listed) {
-                        const bool real = j < NVFULL || idx < nvec;   // padding slots pass a -inf threshold
-#pragma unroll
-                        for (int e = 0; e < EPV; ++e)
-                            list_append(list, &lds_list_count, real && x[e] >= tau, (uint32_t)(idx * EPV + e), d[e]);
-                    } else {
-                        o = pack_grad(d, T());
-                    }
-                }
-                if (!listed && dense_out && (j < NVFULL || idx < nvec)) __builtin_nontemporal_store(o, dzvec + idx);
-                if (has_next && ((any_mask >> j) & 1u)) r[j] = load_slot<T, NT, NVFULL>(znext, j, t, nvec);
-            }
-        }
-
-        if (!has_next) break;
-        if (nrow != row) flags = ny_ok ? 0u : (uint32_t)DVP_ROW_ID_OUT_OF_RANGE;
-        row = nrow; side = nside; y = ny; y_ok = ny_ok; g = ng; zy_raw = nzy_raw; xt_raw = nxt_raw;
+        row_task<f8_t, NVI, NVFULL_I, T, NV, NVFULL, NV, NT, EXTRAS, false>(a, s, r, lds_max, lds_f, lds_i, &lds_list_count);
+        if (!row_task<T, NV, NVFULL, f8_t, NVI, NVFULL_I, NV, NT, EXTRAS, true>(a, s, r, lds_max, lds_f, lds_i, &lds_list_count))
+            break;
     }
 }
 
 // ---------------------------------------------------------------------------
 // streaming kernel: any V, any stride, any alignment; re-reads the row per phase
 // ---------------------------------------------------------------------------
-template <typename T, int NT>
+// TI is the element type of the inference rows (T, or 8-bit E4M3 codes).
+template <typename T, typename TI, int NT>
 __global__ __launch_bounds__(NT) void rows_streaming_kernel(const RowArgs a)
 {
     constexpr int NW = NT / kWave;
@@ -352,21 +493,23 @@ __global__ __launch_bounds__(NT) void rows_streaming_kernel(const RowArgs a)
         uint32_t flags = y_ok ? 0u : (uint32_t)DVP_ROW_ID_OUT_OF_RANGE;
 
         for (int side = a.n_sides - 1; side >= 0; --side) {
-            const T *zrow = (const T *)a.z[side] + row * a.ld[side];
+            const T *zrow = (const T *)a.z[0] + row * a.ld[0];
+            const TI *zrow_i = (const TI *)a.z[1] + (side == 1 ? row * a.ld[1] : 0);
+            auto logit = [&](int64_t k) { return side == 1 ? load_elem(zrow_i + k) : load_elem(zrow + k); };
             const SideOut &out = a.out[side];
             const bool want_full = out.lse_full != nullptr;
             uint32_t *bits_row = out.safe_bits ? out.safe_bits + row * (int64_t)bits_words : nullptr;
-            const float zy = y_ok ? load_elem(zrow + y) : 0.0f;
+            const float zy = y_ok ? logit(y) : 0.0f;
 
             float m = -INFINITY;
-            for (int k = tid; k < V; k += NT) m = fmaxf(m, load_elem(zrow + k));
+            for (int k = tid; k < V; k += NT) m = fmaxf(m, logit(k));
             m = block_max<NT>(m, lds_max);
 
             const float tau = m + log_rho;
             RowSums acc = {0.0f, 0.0f, 0};
             for (int k = tid; k < v_round; k += NT) {   // uniform trip count: ballot below needs every lane
                 const bool in = k < V;
-                const float x = in ? load_elem(zrow + k) : -INFINITY;
+                const float x = in ? logit(k) : -INFINITY;
                 const bool safe = in && (x >= tau);
                 acc.count += safe ? 1 : 0;
                 if (want_full) {
@@ -584,15 +727,17 @@ static int blocks_per_cu(Kernel k, int threads)
     return nb;
 }
 
-template <typename T, int NV, int NVFULL, int NT, int MINW, bool EXTRAS>
+template <typename T, bool F8_INFER, int NV, int NVFULL, int NT, int MINW, bool EXTRAS>
 static hipError_t launch_resident_inst(const RowArgs &a, hipStream_t stream)
 {
+    void (*kernel)(const RowArgs);
+    if constexpr (F8_INFER) kernel = rows_resident_f8infer_kernel<T, NV, NVFULL, NT, MINW, EXTRAS>;
+    else                    kernel = rows_resident_kernel<T, NV, NVFULL, NT, MINW, EXTRAS>;
     static int per_cu = 0;
-    if (per_cu == 0) per_cu = blocks_per_cu(rows_resident_kernel<T, NV, NVFULL, NT, MINW, EXTRAS>, NT);
+    if (per_cu == 0) per_cu = blocks_per_cu(kernel, NT);
     int64_t grid = (int64_t)device_cu_count() * per_cu;
     if (grid > a.n_rows) grid = a.n_rows;
-    hipLaunchKernelGGL((rows_resident_kernel<T, NV, NVFULL, NT, MINW, EXTRAS>), dim3((unsigned)grid),
-                       dim3(NT), 0, stream, a);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(NT), 0, stream, a);
     return hipGetLastError();
 }
 
@@ -600,36 +745,41 @@ static hipError_t launch_resident_inst(const RowArgs &a, hipStream_t stream)
 // groups for short rows (several groups share a CU), 1024-thread groups for
 // long rows (one group owns the CU's register file).  Each build covers row
 // lengths from its NVFULL (exclusive) to its NV (inclusive) slots per thread.
-template <typename T, bool EXTRAS>
+template <typename T, bool F8_INFER, bool EXTRAS>
 static hipError_t launch_resident_t(const RowArgs &a, hipStream_t stream)
 {
     const int epv = elem_traits<T>::kPerVec;
     const int64_t slots = (int64_t)a.vocab / epv;   // whole vectors; the ragged end lives outside the slots
-    if (slots <= 256 * 4)   return launch_resident_inst<T, 4, 0, 256, 4, EXTRAS>(a, stream);
-    if (slots <= 256 * 8)   return launch_resident_inst<T, 8, 4, 256, 6, EXTRAS>(a, stream);
-    if (slots <= 256 * 16)  return launch_resident_inst<T, 16, 8, 256, 4, EXTRAS>(a, stream);
-    if (slots <= 1024 * 8)  return launch_resident_inst<T, 8, 4, 1024, 5, EXTRAS>(a, stream);
-    if (slots <= 1024 * 12) return launch_resident_inst<T, 12, 8, 1024, 4, EXTRAS>(a, stream);
-    if (slots <= 1024 * 16) return launch_resident_inst<T, 16, 12, 1024, 4, EXTRAS>(a, stream);
-    if (slots <= 1024 * 19) return launch_resident_inst<T, 19, 16, 1024, 4, EXTRAS>(a, stream);
-    if (slots <= 1024 * 20) return launch_resident_inst<T, 20, 19, 1024, 4, EXTRAS>(a, stream);
+    if (slots <= 256 * 4)   return launch_resident_inst<T, F8_INFER, 4, 0, 256, 4, EXTRAS>(a, stream);
+    if (slots <= 256 * 8)   return launch_resident_inst<T, F8_INFER, 8, 4, 256, 6, EXTRAS>(a, stream);
+    if (slots <= 256 * 16)  return launch_resident_inst<T, F8_INFER, 16, 8, 256, 4, EXTRAS>(a, stream);
+    if (slots <= 1024 * 8)  return launch_resident_inst<T, F8_INFER, 8, 4, 1024, 5, EXTRAS>(a, stream);
+    if (slots <= 1024 * 12) return launch_resident_inst<T, F8_INFER, 12, 8, 1024, 4, EXTRAS>(a, stream);
+    if (slots <= 1024 * 16) return launch_resident_inst<T, F8_INFER, 16, 12, 1024, 4, EXTRAS>(a, stream);
+    if (slots <= 1024 * 19) return launch_resident_inst<T, F8_INFER, 19, 16, 1024, 4, EXTRAS>(a, stream);
+    if (slots <= 1024 * 20) return launch_resident_inst<T, F8_INFER, 20, 19, 1024, 4, EXTRAS>(a, stream);
     return hipErrorInvalidValue;
 }
 
-bool row_fits_resident(int dtype, int64_t vocab)
+bool row_fits_resident(int dtype, int dtype_infer, int64_t vocab)
 {
     const int epv = dtype == DVP_BF16 ? 8 : 4;
+    if (dtype_infer == DVP_F8E4M3 && (dtype != DVP_BF16 || vocab < 16)) return false;   // bf16 training rows only
     return vocab >= epv && vocab / epv <= 1024 * 20;
 }
 
-hipError_t launch_rows_resident(int dtype, const RowArgs &a, hipStream_t stream)
+hipError_t launch_rows_resident(int dtype, int dtype_infer, const RowArgs &a, hipStream_t stream)
 {
     if (a.n_rows == 0) return hipSuccess;
     const bool extras = a.out[0].lse_full || a.out[0].safe_bits ||
                         (a.n_sides == 2 && (a.out[1].lse_full || a.out[1].safe_bits));
+    if (a.n_sides == 2 && dtype_infer == DVP_F8E4M3) {
+        if (dtype != DVP_BF16) return hipErrorInvalidValue;
+        return extras ? launch_resident_t<bf16_t, true, true>(a, stream) : launch_resident_t<bf16_t, true, false>(a, stream);
+    }
     if (dtype == DVP_BF16)
-        return extras ? launch_resident_t<bf16_t, true>(a, stream) : launch_resident_t<bf16_t, false>(a, stream);
-    return extras ? launch_resident_t<float, true>(a, stream) : launch_resident_t<float, false>(a, stream);
+        return extras ? launch_resident_t<bf16_t, false, true>(a, stream) : launch_resident_t<bf16_t, false, false>(a, stream);
+    return extras ? launch_resident_t<float, false, true>(a, stream) : launch_resident_t<float, false, false>(a, stream);
 }
 
 hipError_t launch_grad_fill(int dtype, const FillArgs &a, hipStream_t stream)
@@ -660,16 +810,21 @@ hipError_t launch_grad_fill(int dtype, const FillArgs &a, hipStream_t stream)
     return hipSuccess;
 }
 
-hipError_t launch_rows_streaming(int dtype, const RowArgs &a, hipStream_t stream)
+hipError_t launch_rows_streaming(int dtype, int dtype_infer, const RowArgs &a, hipStream_t stream)
 {
     if (a.n_rows == 0) return hipSuccess;
     constexpr int NT = 512;
     int64_t grid = (int64_t)device_cu_count() * 4;
     if (grid > a.n_rows) grid = a.n_rows;
-    if (dtype == DVP_BF16)
-        hipLaunchKernelGGL((rows_streaming_kernel<bf16_t, NT>), dim3((unsigned)grid), dim3(NT), 0, stream, a);
-    else
-        hipLaunchKernelGGL((rows_streaming_kernel<float, NT>), dim3((unsigned)grid), dim3(NT), 0, stream, a);
+    const dim3 g((unsigned)grid), b(NT);
+    const bool f8 = a.n_sides == 2 && dtype_infer == DVP_F8E4M3;
+    if (dtype == DVP_BF16) {
+        if (f8) hipLaunchKernelGGL((rows_streaming_kernel<bf16_t, f8_t, NT>), g, b, 0, stream, a);
+        else    hipLaunchKernelGGL((rows_streaming_kernel<bf16_t, bf16_t, NT>), g, b, 0, stream, a);
+    } else {
+        if (f8) hipLaunchKernelGGL((rows_streaming_kernel<float, f8_t, NT>), g, b, 0, stream, a);
+        else    hipLaunchKernelGGL((rows_streaming_kernel<float, float, NT>), g, b, 0, stream, a);
+    }
     return hipGetLastError();
 }
 

@@ -17,7 +17,7 @@ import torch
 _PKG = Path(__file__).resolve().parent
 LIB_PATH = _PKG / "libdvp_hip.so"
 
-DVP_F32, DVP_BF16 = 0, 1
+DVP_F32, DVP_BF16, DVP_F8E4M3 = 0, 1, 2
 ROW_Y_IN_TRAIN_SAFE, ROW_Y_IN_INFER_SAFE, ROW_ID_OUT_OF_RANGE, ROW_GRAD_OVERFLOW = 1, 2, 4, 8
 
 EXPORTS = ("dvp_forward", "dvp_backward", "dvp_forward_backward", "dvp_fused_lmhead",
@@ -29,7 +29,7 @@ class DvpParams(ctypes.Structure):
     _fields_ = [("n_rows", ctypes.c_int64), ("vocab", ctypes.c_int64),
                 ("ld_train", ctypes.c_int64), ("ld_infer", ctypes.c_int64),
                 ("ld_grad", ctypes.c_int64), ("dtype", ctypes.c_int32),
-                ("log_rho", ctypes.c_float)]
+                ("log_rho", ctypes.c_float), ("dtype_infer", ctypes.c_int32)]
 
 
 class DvpSideOut(ctypes.Structure):
@@ -119,6 +119,24 @@ def _dtype_code(t: torch.Tensor) -> int:
     raise TypeError("logits must be float32 or bfloat16, got %s" % t.dtype)
 
 
+def _infer_dtype_code(z_train: torch.Tensor, z_infer: Optional[torch.Tensor]) -> int:
+    """Inference logits share the training logits' dtype or are 8-bit E4M3 (torch.float8_e4m3fn)."""
+    if z_infer is None or z_infer.dtype == z_train.dtype:
+        return _dtype_code(z_train)
+    if z_infer.dtype == torch.float8_e4m3fn:
+        return DVP_F8E4M3
+    raise ValueError("z_infer must have z_train's dtype or be float8_e4m3fn, got %s" % z_infer.dtype)
+
+
+def _check_pair(z_train, z_infer):
+    _check_rows(z_train, "z_train")
+    if z_infer is not None:
+        _check_rows(z_infer, "z_infer")
+        if z_infer.shape != z_train.shape:
+            raise ValueError("z_infer must match z_train in shape")
+        _infer_dtype_code(z_train, z_infer)
+
+
 def _check_rows(z: torch.Tensor, name: str):
     if not z.is_cuda:
         raise ValueError("%s must live in GPU memory (no CPU path exists)" % name)
@@ -160,17 +178,13 @@ def _params(z_train, z_infer, dz, log_rho_value) -> DvpParams:
     return DvpParams(z_train.shape[0], z_train.shape[1], z_train.stride(0),
                      z_infer.stride(0) if z_infer is not None else 0,
                      dz.stride(0) if dz is not None else 0,
-                     _dtype_code(z_train), float(log_rho_value))
+                     _dtype_code(z_train), float(log_rho_value), _infer_dtype_code(z_train, z_infer))
 
 
 def dvp_forward(z_train, z_infer, ids, log_rho_value, *, lse_full=False, safe_bits=False,
                 out_train: Optional[SideOutputs] = None, out_infer: Optional[SideOutputs] = None,
                 row_flags: Optional[torch.Tensor] = None, stream=None) -> RowResult:
-    _check_rows(z_train, "z_train")
-    if z_infer is not None:
-        _check_rows(z_infer, "z_infer")
-        if z_infer.shape != z_train.shape or z_infer.dtype != z_train.dtype:
-            raise ValueError("z_infer must match z_train in shape and dtype")
+    _check_pair(z_train, z_infer)
     n, v = z_train.shape
     dev = z_train.device
     out_train = out_train or SideOutputs(n, v, dev, lse_full, safe_bits)
@@ -207,11 +221,7 @@ def dvp_forward_backward(z_train, z_infer, ids, grad_out, log_rho_value, *, lse_
                          out_infer: Optional[SideOutputs] = None,
                          row_flags: Optional[torch.Tensor] = None,
                          dz: Optional[torch.Tensor] = None, stream=None) -> RowResult:
-    _check_rows(z_train, "z_train")
-    if z_infer is not None:
-        _check_rows(z_infer, "z_infer")
-        if z_infer.shape != z_train.shape or z_infer.dtype != z_train.dtype:
-            raise ValueError("z_infer must match z_train in shape and dtype")
+    _check_pair(z_train, z_infer)
     n, v = z_train.shape
     dev = z_train.device
     out_train = out_train or SideOutputs(n, v, dev, lse_full, safe_bits)
@@ -252,11 +262,7 @@ def dvp_forward_backward_sparse(z_train, z_infer, ids, grad_out, log_rho_value, 
                                 out_train: Optional[SideOutputs] = None,
                                 out_infer: Optional[SideOutputs] = None, row_flags=None, entries=None,
                                 grad_len=None, stream=None) -> SparseResult:
-    _check_rows(z_train, "z_train")
-    if z_infer is not None:
-        _check_rows(z_infer, "z_infer")
-        if z_infer.shape != z_train.shape or z_infer.dtype != z_train.dtype:
-            raise ValueError("z_infer must match z_train in shape and dtype")
+    _check_pair(z_train, z_infer)
     n, v = z_train.shape
     dev = z_train.device
     out_train = out_train or SideOutputs(n, v, dev)

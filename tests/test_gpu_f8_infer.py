@@ -1,0 +1,186 @@
+"""GPU parity of the row path when the inference logits are stored as 8-bit E4M3
+codes (one byte per token, widened exactly), against the fp64 oracle, through
+the C ABI.
+
+Bars: row maxima, safe-set sizes, membership bits and flags are exact (every
+E4M3 code is an fp32 value, so the kernel's fp32 threshold test and the
+oracle's see the same numbers); lse / logp of the inference side are fp32 sums
+of exactly widened inputs and are held to the fp32 tolerance 1e-5 (plus half a
+unit in the last place of |lse| where the logits are large); the training side
+and the gradient keep their bf16 / fp32 bars.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import dvp_oracle as orc
+from paper_2512_23087_amd import workloads
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+F8 = torch.float8_e4m3fn
+
+
+@pytest.fixture(scope="module")
+def dvp():
+    from paper_2512_23087_amd import dvp as binding
+    binding.lib()
+    return binding
+
+
+def _codes(t):
+    """uint8 view of an fp8 tensor on the host (what the oracle takes)."""
+    return t.view(torch.uint8).cpu().contiguous()
+
+
+def _case(n, v, seed, train_dtype=torch.bfloat16, ld_t=None, ld_i=None, offset_i=0, scale=3.0):
+    """Random training rows and the same rows plus noise rounded to E4M3, each in a NaN-filled
+    (0x7f for the bytes) allocation with the given row strides."""
+    g = torch.Generator().manual_seed(seed)
+    ld_t, ld_i = ld_t or v, ld_i or v
+    zt = (scale * torch.randn(n, v, generator=g)).to(train_dtype)
+    zi = workloads.through_e4m3(zt.float() + 0.05 * torch.randn(n, v, generator=g)).to(F8)
+    store_t = torch.full((n, ld_t), float("nan")).to(train_dtype)
+    store_t[:, :v] = zt
+    store_i = torch.full((n * ld_i + offset_i,), 0x7f, dtype=torch.uint8)
+    store_i[offset_i:].view(n, ld_i)[:, :v] = zi.view(torch.uint8)
+    ids = torch.randint(0, v, (n,), generator=g)
+    ids[0], ids[-1] = 0, v - 1
+    gout = torch.randn(n, generator=g)
+    zi_dev = store_i.cuda()[offset_i:].view(n, ld_i)[:, :v].view(F8)
+    return workloads.RowWorkload(name="f8", z_train=store_t.cuda()[:, :v], z_infer=zi_dev, ids=ids.cuda(),
+                                 grad_out=gout.cuda(), rhos=[])
+
+
+def _run(dvp, wl, rho, *, backward=True, extras=True, tol_i=1e-5, threads=8):
+    lr = dvp.log_rho(rho)
+    v = wl.z_train.shape[1]
+    tol_t = parity.TOL[wl.z_train.dtype]
+    if backward:
+        res = dvp.dvp_forward_backward(wl.z_train, wl.z_infer, wl.ids, wl.grad_out, lr, lse_full=extras,
+                                       safe_bits=extras)
+    else:
+        res = dvp.dvp_forward(wl.z_train, wl.z_infer, wl.ids, lr, lse_full=extras, safe_bits=extras)
+    torch.cuda.synchronize()
+    zt, zi, ids = wl.z_train.cpu(), _codes(wl.z_infer), wl.ids.cpu()
+    st = parity.check_side("train", res.train, zt, ids, lr, tol_t, v, threads=threads)
+    si = parity.check_side("infer", res.infer, zi, ids, lr, tol_i, v, threads=threads)
+    parity.check_flags(res.row_flags, st["y_in_safe"], si["y_in_safe"], ids, v)
+    out = dict(train=st, infer=si, result=res)
+    if backward:
+        out.update(parity.check_gradient("dz", res.dz, zt, ids, wl.grad_out.cpu(), lr, tol_t, threads=threads))
+    return out
+
+
+def test_every_code_is_widened_exactly(dvp):
+    """Row c holds code c in every position: its maximum is that code's value.  The last row holds
+    all 254 numbers in code order: its membership bits check the position of every byte."""
+    good = [c for c in range(256) if c not in (0x7F, 0xFF)]
+    v = 256
+    rows = torch.empty(len(good) + 1, v, dtype=torch.uint8)
+    for r, c in enumerate(good):
+        rows[r].fill_(c)
+    ramp = torch.tensor(good + [0x00, 0x80], dtype=torch.uint8)
+    rows[-1] = ramp
+    n = rows.shape[0]
+    zi = rows.cuda().view(F8)
+    zt = torch.zeros(n, v, dtype=torch.bfloat16, device="cuda")
+    ids = torch.zeros(n, dtype=torch.int64, device="cuda")
+    want = np.array([orc.e4m3_value(c) for c in good])
+    for rho in (1e-2, 0.0):
+        res = dvp.dvp_forward(zt, zi, ids, dvp.log_rho(rho), lse_full=True, safe_bits=True)
+        torch.cuda.synchronize()
+        got = res.infer.row_max.cpu().double().numpy()
+        np.testing.assert_array_equal(got[:-1], want)
+        assert got[-1] == 448.0
+        parity.check_side("infer", res.infer, rows, ids.cpu(), dvp.log_rho(rho), 1e-4, v, threads=2)
+    # the same bytes through the re-reading kernel (rows not 16-byte aligned)
+    store = torch.empty(n * v + 1, dtype=torch.uint8)
+    store[1:] = rows.reshape(-1)
+    zi2 = store.cuda()[1:].view(n, v).view(F8)
+    res = dvp.dvp_forward(zt, zi2, ids, dvp.log_rho(1e-2), lse_full=True, safe_bits=True)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(res.infer.row_max.cpu().double().numpy()[:-1], want)
+    parity.check_side("infer", res.infer, rows, ids.cpu(), dvp.log_rho(1e-2), 1e-4, v, threads=2)
+
+
+@pytest.mark.parametrize("v,ld_t,ld_i", [
+    (16, 16, 16), (33, 40, 48), (1001, 1008, 1008), (4096, 4096, 4096), (5000, 5000, 5008),
+    (12345, 12352, 12352), (32000, 32000, 32000), (40000, 40000, 40000), (70001, 70008, 70016),
+    (100000, 100000, 100000), (131072, 131072, 131072), (151936, 151936, 151936), (163840, 163840, 163840)])
+def test_shapes_single_read_path(dvp, v, ld_t, ld_i):
+    n = 5 if v > 20000 else 9
+    wl = _case(n, v, seed=v, ld_t=ld_t, ld_i=ld_i)
+    p = dvp.DvpParams(n, v, ld_t, ld_i, ld_t, 1, -1.0, 2)
+    assert dvp.lib().dvp_row_path(p, 1) == 1
+    for rho in (1e-2, 0.0):
+        _run(dvp, wl, rho, threads=3)
+    _run(dvp, wl, 1e-3, backward=False, extras=False, threads=3)
+
+
+@pytest.mark.parametrize("train_dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("v", [1, 5, 15, 1001, 40000])
+def test_shapes_rereading_path(dvp, train_dtype, v):
+    # byte rows at an odd offset and an odd stride; fp32 training rows always take this path
+    wl = _case(6, v, seed=500 + v, train_dtype=train_dtype, ld_i=v + 3, offset_i=1)
+    for rho in (1e-2, 0.0):
+        _run(dvp, wl, rho, threads=3)
+
+
+def test_config1_recipe_with_byte_inference_logits(dvp):
+    """configs[1]: the inference logits of that recipe are E4M3 values already; stored as bytes they
+    give the same numbers as stored as bf16."""
+    wl = workloads.make_rows(1, device="cuda", n=192)
+    zi8 = wl.z_infer.float().to(F8)
+    assert torch.equal(zi8.float(), wl.z_infer.float())        # nothing is lost
+    wl8 = workloads.RowWorkload(name="c1f8", z_train=wl.z_train, z_infer=zi8, ids=wl.ids, grad_out=wl.grad_out,
+                                rhos=wl.rhos)
+    st = _run(dvp, wl8, 1e-4, tol_i=2e-5)
+    ref = dvp.dvp_forward_backward(wl.z_train, wl.z_infer, wl.ids, wl.grad_out, dvp.log_rho(1e-4))
+    torch.cuda.synchronize()
+    res = st["result"]
+    assert torch.equal(res.infer.row_max, ref.infer.row_max)
+    assert torch.equal(res.infer.safe_count, ref.infer.safe_count)
+    assert torch.equal(res.row_flags, ref.row_flags)
+    fin = torch.isfinite(ref.infer.logp)
+    assert torch.equal(res.infer.logp[~fin], ref.infer.logp[~fin])
+    assert (res.infer.logp[fin] - ref.infer.logp[fin]).abs().max().item() <= 2e-5
+    assert torch.equal(res.dz, ref.dz)                          # the training side does not change
+
+
+def test_heavy_tail_saturates_at_448(dvp):
+    """configs[3]'s heavy-tailed rows pushed through E4M3: values beyond 448 saturate, several tokens
+    can tie at the maximum, and the spacing near the top is 32."""
+    wl = workloads.make_rows(3, device="cuda", n=40)
+    zi8 = workloads.through_e4m3(wl.z_infer.float()).to(F8)
+    wl8 = workloads.RowWorkload(name="c3f8", z_train=wl.z_train, z_infer=zi8, ids=wl.ids, grad_out=wl.grad_out,
+                                rhos=wl.rhos)
+    for rho in (1e-4, 0.0):
+        st = _run(dvp, wl8, rho, tol_i=4e-5)
+    assert st["infer"]["safe_count"].min() >= 1
+
+
+def test_sparse_gradient_with_byte_inference_logits(dvp):
+    wl = _case(40, 32000, seed=11, scale=4.0)
+    lr = dvp.log_rho(1e-2)
+    res = dvp.dvp_forward_backward_sparse(wl.z_train, wl.z_infer, wl.ids, wl.grad_out, lr, 4096)
+    ref = dvp.dvp_forward_backward(wl.z_train, wl.z_infer, wl.ids, wl.grad_out, lr)
+    torch.cuda.synchronize()
+    assert torch.equal(res.infer.logp, ref.infer.logp) and torch.equal(res.train.logp, ref.train.logp)
+    assert torch.equal(res.row_flags & 7, ref.row_flags & 7)
+    dense = ref.dz.float().cpu()
+    for i in range(40):
+        idx, val = res.row(i)
+        want = torch.nonzero(dense[i]).squeeze(1)
+        # every non-zero dense entry is listed, with the value before its rounding to bf16
+        assert set(want.tolist()) <= set(idx.tolist())
+        assert torch.equal(val.to(torch.bfloat16).float()[torch.isin(idx, want)], dense[i][want])
+
+
+def test_binding_refuses_other_dtype_pairs(dvp):
+    zt = torch.zeros(2, 32, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(ValueError):
+        dvp.dvp_forward(zt, torch.zeros(2, 32, dtype=torch.float32, device="cuda"),
+                        torch.zeros(2, dtype=torch.int64, device="cuda"), -1.0)

@@ -146,7 +146,8 @@ def test_shapes_resident_path(dvp, dtype, v):
     es = 2 if dtype == torch.bfloat16 else 4
     ld = (v * es + 15) // 16 * 16 // es          # 16-byte aligned rows -> single-read kernel
     wl = _random_case(n, v, dtype, seed=v, ld=ld)
-    p = dvp.DvpParams(n, v, ld, ld, ld, 1 if dtype == torch.bfloat16 else 0, -1.0)
+    code = 1 if dtype == torch.bfloat16 else 0
+    p = dvp.DvpParams(n, v, ld, ld, ld, code, -1.0, code)
     # rows shorter than one 16-byte vector go to the streaming kernel
     assert dvp.lib().dvp_row_path(p, 1) == (1 if v * es >= 16 else 0)
     for rho in (1e-2, 0.0):
@@ -166,7 +167,7 @@ def test_shapes_streaming_path_misaligned(dvp, dtype, v):
 def test_vocab_too_large_for_registers_uses_streaming(dvp):
     v = 8 * 1024 * 20 + 8       # one vector more than the resident kernel holds
     wl = _random_case(3, v, torch.bfloat16, seed=77)
-    p = dvp.DvpParams(3, v, v, v, v, 1, -1.0)
+    p = dvp.DvpParams(3, v, v, v, v, 1, -1.0, 1)
     assert dvp.lib().dvp_row_path(p, 1) == 0
     _run_case(dvp, wl, 1e-3, backward=True, threads=3)
 

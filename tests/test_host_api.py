@@ -45,7 +45,7 @@ def test_argument_validation_needs_no_gpu():
     def P(**kw):
         d = dict(ok); d.update(kw)
         return dvp.DvpParams(d["n_rows"], d["vocab"], d["ld_train"], d["ld_infer"], d["ld_grad"],
-                             d["dtype"], d["log_rho"])
+                             d["dtype"], d["log_rho"], d.get("dtype_infer", d["dtype"]))
 
     assert _fwd(P()) == 0                                   # zero rows: nothing to do
     assert _fwd(P(), z_train=None, ids=None) == 0           # ... and no pointer is looked at
@@ -61,6 +61,11 @@ def test_argument_validation_needs_no_gpu():
     assert _fwd(P(vocab=2 ** 31 - 2 ** 16 + 1, ld_train=2 ** 31, ld_infer=2 ** 31)) == 2
     assert _fwd(P(vocab=2 ** 31 - 2 ** 16, ld_train=2 ** 31, ld_infer=2 ** 31)) == 0
     assert _fwd(P(dtype=7)) == 3
+    assert _fwd(P(dtype=2)) == 3                            # 8-bit logits are an inference-side format only
+    assert _fwd(P(dtype=1, dtype_infer=0)) == 3             # the two sides differ only by the 8-bit case
+    assert _fwd(P(dtype=1, dtype_infer=2)) == 0 and _fwd(P(dtype=0, dtype_infer=2)) == 0
+    assert _fwd(P(dtype=1, dtype_infer=9), z_infer=None) == 0   # ignored without an inference side
+    assert _fwd(P(n_rows=1, dtype=1, dtype_infer=2), z_infer=FAKE + 1) != 4   # bytes need no alignment
     assert _fwd(P(log_rho=0.5)) == 3
     assert _fwd(P(log_rho=float("nan"))) == 3
     assert _fwd(P(log_rho=-math.inf)) == 0
@@ -83,8 +88,8 @@ def test_argument_validation_needs_no_gpu():
 def test_row_path_selection():
     L = dvp.lib()
 
-    def path(v, dtype, ld=None, aligned=1):
-        p = dvp.DvpParams(4, v, ld or v, ld or v, ld or v, dtype, -1.0)
+    def path(v, dtype, ld=None, aligned=1, dtype_infer=None):
+        p = dvp.DvpParams(4, v, ld or v, ld or v, ld or v, dtype, -1.0, dtype if dtype_infer is None else dtype_infer)
         return L.dvp_row_path(ctypes.byref(p), aligned)
 
     assert path(151936, 1) == 1 and path(32000, 1) == 1 and path(32000, 0) == 1
@@ -95,6 +100,11 @@ def test_row_path_selection():
     assert path(7, 1) == 0 and path(8, 1, ld=8) == 1               # shorter than one vector
     assert path(3, 0) == 0 and path(4, 0) == 1
     assert path(0, 1) == -1
+    # 8-bit inference rows: single-read next to bf16 training rows of at least one 16-token vector
+    assert path(151936, 1, dtype_infer=2) == 1 and path(32000, 1, dtype_infer=2) == 1
+    assert path(32008, 1, dtype_infer=2) == 0                  # 32008 bytes per inference row: not 16-byte aligned
+    assert path(8, 1, dtype_infer=2) == 0 and path(16, 1, dtype_infer=2) == 1
+    assert path(32000, 0, dtype_infer=2) == 0                  # fp32 training rows take the re-reading path
 
 
 def test_binding_refuses_cpu_tensors():
@@ -125,7 +135,7 @@ def test_sparse_gradient_validation_needs_no_gpu():
     so = dvp.DvpSideOut(FAKE, FAKE, FAKE, None, FAKE, None)
 
     def call(n_rows=1, vocab=32000, cap=64, z=FAKE, flags=FAKE, entries=FAKE, dtype=1, ld=None):
-        p = dvp.DvpParams(n_rows, vocab, ld or vocab, ld or vocab, 0, dtype, -3.0)
+        p = dvp.DvpParams(n_rows, vocab, ld or vocab, ld or vocab, 0, dtype, -3.0, dtype)
         return L.dvp_forward_backward_sparse(ctypes.byref(p), z, FAKE, FAKE, FAKE, ctypes.byref(so),
                                              ctypes.byref(so), flags, entries, FAKE, cap, None)
 

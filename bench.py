@@ -95,6 +95,7 @@ def time_launches(fn, steps, warmup):
 
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 matrix peak
+MFMA_FP8_PEAK_TFLOPS = 5000.0    # and dense fp8
 
 
 def bench_lmhead(args):
@@ -102,7 +103,8 @@ def bench_lmhead(args):
     dvp_fused_lmhead call: both sides' forward and the training side's dH, dW."""
     import torch
     from paper_2512_23087_amd import dvp, workloads
-    wl = workloads.make_lmhead(device="cuda:0", n=args.rows)
+    f8 = args.infer_dtype == "f8"
+    wl = workloads.make_lmhead(device="cuda:0", n=args.rows, f8_engine=f8)
     n, d = wl.hidden.shape
     v = wl.w_train.shape[0]
     lr = dvp.log_rho(args.rho)
@@ -111,8 +113,12 @@ def bench_lmhead(args):
     dw = torch.empty(v, d, dtype=torch.float32, device="cuda:0")
 
     def step():
-        dvp.dvp_fused_lmhead(wl.hidden, wl.w_train, wl.w_infer, wl.ids, wl.grad_out, lr,
-                             workspace=ws, d_hidden=dh, d_w=dw)
+        if f8:
+            dvp.dvp_fused_lmhead(wl.hidden, wl.w_train, None, wl.ids, wl.grad_out, lr, workspace=ws, d_hidden=dh,
+                                 d_w=dw, infer_f8=(wl.hidden8, wl.w8, wl.scale_infer))
+        else:
+            dvp.dvp_fused_lmhead(wl.hidden, wl.w_train, wl.w_infer, wl.ids, wl.grad_out, lr,
+                                 workspace=ws, d_hidden=dh, d_w=dw)
 
     steps = min(args.steps, 5)
     wall, per_launch = time_launches(step, steps, min(args.warmup, 2))
@@ -120,18 +126,27 @@ def bench_lmhead(args):
     gemm = 2.0 * n * v * d
     useful, executed = 4 * gemm, 6 * gemm          # train fwd, infer fwd, dH, dW; vs the passes actually run
     # (each side's forward produces the logits twice: row max first, then sums at the threshold)
+    # Peak for the mix of passes: each contraction is priced at the peak of its own operand type, so the
+    # call's floor is sum(flop_i / peak_i) and the peak quoted is executed flop over that floor.
+    n_f8 = 2 if f8 else 0
+    floor_s = ((6 - n_f8) * gemm / MFMA_BF16_PEAK_TFLOPS + n_f8 * gemm / MFMA_FP8_PEAK_TFLOPS) / 1e12
+    peak = executed / floor_s / 1e12
     result = {
         "metric": "DVP fused LM-head fwd+bwd rows/s and MFMA TFLOP/s, V=%d bf16" % v,
         "value": n * steps / wall, "unit": "rows/s", "n_gpus": 1, "steps": steps,
         "warmup": min(args.warmup, 2), "ms_per_step": wall * 1e3 / steps, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "configs[4]: hidden [%d, %d] bf16 x W [%d, %d] bf16 (train) and its "
-                               "fp8-e4m3-rounded copy (infer), rho=%g" % (n, d, v, d, args.rho),
-                   "entry_point": "dvp_fused_lmhead", "workspace_bytes": ws.numel()},
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16+f8" if f8 else "bf16", "data": "synthetic",
+        "config": {"workload": ("configs[4]: hidden [%d, %d] bf16 x W [%d, %d] bf16 (train); inference side an 8-bit "
+                                "engine: E4M3 activations and head with per-tensor factors, rho=%g" if f8 else
+                                "configs[4]: hidden [%d, %d] bf16 x W [%d, %d] bf16 (train) and its "
+                                "fp8-e4m3-rounded copy (infer), rho=%g") % (n, d, v, d, args.rho),
+                   "entry_point": "dvp_fused_lmhead_f8infer" if f8 else "dvp_fused_lmhead",
+                   "workspace_bytes": ws.numel()},
         "roofline": {"bound": "mfma", "achieved": executed / (ms * 1e-3) / 1e12,
-                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": executed / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
-                     "kernel": "gemm_nt_kernel (6 GEMM passes of 2*N*V*d flop each per call)",
+                     "peak": peak, "unit": "TFLOP/s",
+                     "frac": executed / (ms * 1e-3) / 1e12 / peak, "traffic": None,
+                     "kernel": "gemm_nt_kernel (6 GEMM passes of 2*N*V*d flop each per call%s)"
+                               % (": 4 bf16 at 2.5 PFLOP/s peak, 2 fp8 at 5.0" if f8 else ""),
                      "kernel_ms_avg": ms, "executed_tflop": executed / 1e12,
                      "useful_tflop": useful / 1e12,
                      "useful_tflops": useful / (ms * 1e-3) / 1e12},

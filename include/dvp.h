@@ -220,6 +220,36 @@ dvp_status dvp_fused_lmhead(const dvp_lmhead_params *params, const void *hidden,
                             float *d_w, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The same call when the inference engine is an 8-bit (W8A8) engine (the FP8
+ * rollout engines of Sec. 4.2): its logits are
+ *     z' = scale * (hidden8 . w8^T)
+ * with hidden8 its own E4M3 activations, w8 its E4M3 head and scale the product
+ * of the two per-tensor dequantisation factors; the dot products are
+ * accumulated in fp32 on the 8-bit matrix instructions and multiplied by scale
+ * in fp32 (one rounding).  Everything else (training side, gradient, outputs,
+ * workspace, limits) is as in dvp_fused_lmhead.
+ *   infer->hidden  DEVICE E4M3 bytes [N, ld_hidden]
+ *   infer->w       DEVICE E4M3 bytes [V, ld_w]
+ *   ld_hidden, ld_w  row strides in bytes, multiples of 16, at most 2^23
+ *   scale          finite, > 0
+ * Further limit: hidden a multiple of 128 (DVP_ERR_UNSUPPORTED otherwise).
+ */
+typedef struct {
+    const void *hidden;
+    const void *w;
+    int64_t ld_hidden;
+    int64_t ld_w;
+    float scale;
+} dvp_lmhead_f8_side;
+
+dvp_status dvp_fused_lmhead_f8infer(const dvp_lmhead_params *params, const void *hidden,
+                                    const void *w_train, const dvp_lmhead_f8_side *infer,
+                                    const int64_t *ids, const float *grad_out,
+                                    const dvp_side_out *out_train, const dvp_side_out *out_infer,
+                                    uint8_t *row_flags, float *d_hidden, float *d_w, void *workspace,
+                                    size_t workspace_bytes, void *stream);
+
+/*
  * Sequence-level importance weights and token veto, from the per-token
  * outputs of the calls above (Thm. 4.1; App. A, protocol items 4 and 5).
  * Sequence s owns the token rows seq_offsets[s] .. seq_offsets[s+1] - 1.

@@ -166,15 +166,19 @@ def _widen(a):
     return a.astype(np.float64)
 
 
-def lmhead(hidden, w, ids, log_rho, grad_out=None, want_flags=False, band=1e-6, threads=1):
-    """Dense LM-head variant: logits z = H W^T formed in fp64 from the stored
-    hidden states H [N, d] and head weights W [V, d], then ``rows`` on them;
-    with grad_out also dH = dz W and dW = dz^T H (chain rule through the
-    linear map).  Returns the ``rows`` dict plus 'z', and 'd_hidden', 'd_w'
-    when grad_out is given."""
+def lmhead(hidden, w, ids, log_rho, grad_out=None, want_flags=False, band=1e-6, threads=1, scale=1.0):
+    """Dense LM-head variant: logits z = scale * H W^T formed in fp64 from the
+    stored hidden states H [N, d] and head weights W [V, d] (bf16, fp32 or, for
+    an 8-bit inference engine as in Sec. 4.2, E4M3 codes with `scale` the
+    product of its two dequantisation factors), then ``rows`` on them; with
+    grad_out also dH = dz W and dW = dz^T H (chain rule through the linear map;
+    scale must be 1 there).  Returns the ``rows`` dict plus 'z', and
+    'd_hidden', 'd_w' when grad_out is given."""
     h64 = _widen(hidden)
     w64 = _widen(w)
-    z = h64 @ w64.T
+    if grad_out is not None and scale != 1.0:
+        raise ValueError("the gradient is defined for the training side only (scale = 1)")
+    z = float(scale) * (h64 @ w64.T)
     out = rows(z, ids, log_rho, grad_out=grad_out, want_flags=want_flags,
                want_dz=grad_out is not None, band=band, threads=threads)
     out["z"] = z

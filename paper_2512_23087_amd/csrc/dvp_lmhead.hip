@@ -31,6 +31,8 @@ namespace dvp {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x8 __attribute__((ext_vector_type(8)));
 
 constexpr int BM = 256, BN = 256, BK = 64;      // workgroup tile
 constexpr int WM = 4, WN = 2;                   // 8 wavefronts as 4 x 2, two per SIMD
@@ -77,6 +79,9 @@ struct GemmArgs {
     const uint16_t *B;   // [N, ldb] bf16, K-major
     int64_t lda, ldb;
     int M, N, K;         // K a multiple of BK; rows beyond M / N are clamped on load and masked in the epilogue
+    float scale;         // 8-bit operands only: the accumulators are multiplied by it before the epilogue
+    // 8-bit (E4M3) operands are described in the same units: two bytes count as one element, so a K
+    // step is still 128 bytes of every row and the copy schedule does not change.
 };
 
 // ---------------------------------------------------------------------------
@@ -332,7 +337,12 @@ struct TilePlace {
 // Persistent: the grid has one workgroup per CU and each walks its share of the tiles.  Unless the
 // epilogue needs the tile buffers, the first two K steps of the next tile are copied under the last
 // two K steps of the current one, so only the epilogue itself separates the MFMA streams of two tiles.
-template <class Epi, bool NEEDS_FINISH>
+//
+// F8: both operands are E4M3 bytes and the products run on the 64-deep 8-bit matrix instruction, whose
+// operands are 32 bytes per lane: a K step (128 bytes of every row) is two instructions deep instead of
+// four.  Lane l takes the 32 bytes (two swizzled 16-byte chunks) 4 * pair + 2 * (l / 32) of its row, of A
+// and of B alike, so both operands present the same k to the same position of the instruction.
+template <class Epi, bool NEEDS_FINISH, bool F8>
 __global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs g, const Epi epi, int tiles_m, int tiles_n)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];   // [stage][A | B][256 rows][128 B], then sums scratch
@@ -391,15 +401,52 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs
     const int b_off = kTileBytes + (wn * NI * 32 + frow) * kRowBytes;
     f32x16 acc[MI][NI];
     bf16x8 fa[2][MI], fb[2][NI];
+    i32x8 fa8[2][MI], fb8[2][NI];       // F8 only
     auto fetch = [&](int buf, int stage, int ks) {
         const uint8_t *sb = lds + stage * kStageBytes;
-        const int chunk = ((ks * 2 + half) ^ key) * 16;
+        if constexpr (F8) {             // ks counts 64-deep pairs here: 0 or 1
+            const int c0 = ((ks * 4 + half * 2) ^ key) * 16, c1 = ((ks * 4 + half * 2 + 1) ^ key) * 16;
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi) fa[buf][mi] = *(const bf16x8 *)(sb + a_off + mi * 32 * kRowBytes + chunk);
+            for (int mi = 0; mi < MI; ++mi) {
+                const i32x4 lo = *(const i32x4 *)(sb + a_off + mi * 32 * kRowBytes + c0);
+                const i32x4 hi = *(const i32x4 *)(sb + a_off + mi * 32 * kRowBytes + c1);
+                fa8[buf][mi] = (i32x8){lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+            }
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni) fb[buf][ni] = *(const bf16x8 *)(sb + b_off + ni * 32 * kRowBytes + chunk);
+            for (int ni = 0; ni < NI; ++ni) {
+                const i32x4 lo = *(const i32x4 *)(sb + b_off + ni * 32 * kRowBytes + c0);
+                const i32x4 hi = *(const i32x4 *)(sb + b_off + ni * 32 * kRowBytes + c1);
+                fb8[buf][ni] = (i32x8){lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+            }
+        } else {
+            const int chunk = ((ks * 2 + half) ^ key) * 16;
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) fa[buf][mi] = *(const bf16x8 *)(sb + a_off + mi * 32 * kRowBytes + chunk);
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni) fb[buf][ni] = *(const bf16x8 *)(sb + b_off + ni * 32 * kRowBytes + chunk);
+        }
     };
     auto multiply = [&](int buf) {
+        if constexpr (F8) {
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)   // formats 0, 0: E4M3 x E4M3; zero scale operands: the unscaled instruction
+                    acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fa8[buf][mi], fb8[buf][ni], acc[mi][ni],
+                                                                                 0, 0, 0, 0, 0, 0);
+            // twelve 16-byte LDS reads of the next pair between these eight MFMAs
+#pragma unroll
+            for (int i = 0; i < MI * NI / 2; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            }
+#pragma unroll
+            for (int i = 0; i < MI * NI / 2; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            return;
+        }
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
@@ -438,9 +485,13 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs
 
         for (int j = 0; j < nk; ++j) {
             const int stage = (sp + j) & 1;
-            fetch(1, stage, 1); multiply(0);
-            fetch(0, stage, 2); multiply(1);
-            fetch(1, stage, 3); multiply(0);
+            if constexpr (F8) {
+                fetch(1, stage, 1); multiply(0);
+            } else {
+                fetch(1, stage, 1); multiply(0);
+                fetch(0, stage, 2); multiply(1);
+                fetch(1, stage, 3); multiply(0);
+            }
             // own reads of K step j are home, own copies of step j+1 have landed; past the
             // barrier that holds for every wavefront
             wait_copies_and_barrier();
@@ -450,6 +501,14 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs
             multiply(1);
         }
 
+        if constexpr (F8) {
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc[mi][ni][i] *= g.scale;
+        }
         // every wavefront is past the tile's last barrier and its last useful fetch
         epi(g, acc, cur.tile_m * BM + wm * (MI * 32), cur.tile_n * BN + wn * (NI * 32), lane, lds, wave, wn);
         if constexpr (NEEDS_FINISH) {
@@ -484,12 +543,12 @@ static int gemm_cu_count()
     return cached;
 }
 
-template <class Epi, bool NEEDS_FINISH>
+template <class Epi, bool NEEDS_FINISH, bool F8 = false>
 static hipError_t launch_gemm(const GemmArgs &g, const Epi &epi, hipStream_t stream)
 {
     static bool configured = false;
     if (!configured) {   // more than 64 KB of LDS per workgroup has to be asked for
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_nt_kernel<Epi, NEEDS_FINISH>,
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_nt_kernel<Epi, NEEDS_FINISH, F8>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
         if (e != hipSuccess) return e;
         configured = true;
@@ -499,7 +558,7 @@ static hipError_t launch_gemm(const GemmArgs &g, const Epi &epi, hipStream_t str
     int grid = gemm_cu_count() / 8 * 8;     // one workgroup per CU; a multiple of the XCD count
     if (grid < 8) grid = 8;
     if (grid > total) grid = total;
-    hipLaunchKernelGGL((gemm_nt_kernel<Epi, NEEDS_FINISH>), dim3((unsigned)grid), dim3(kGemmThreads),
+    hipLaunchKernelGGL((gemm_nt_kernel<Epi, NEEDS_FINISH, F8>), dim3((unsigned)grid), dim3(kGemmThreads),
                        kGemmLdsBytes, stream, g, epi, tiles_m, tiles_n);
     return hipGetLastError();
 }
@@ -693,23 +752,14 @@ static bool lm_params_ok(const dvp_lmhead_params *p)
     return true;
 }
 
-}  // namespace dvp
-
-extern "C" {
-
-size_t dvp_fused_lmhead_workspace_bytes(const dvp_lmhead_params *p)
+// Both entry points.  The inference side is either a bf16 head applied to the same hidden states
+// (w_infer) or an 8-bit engine with its own activations and head (f8), or absent (both null).
+static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, const void *w_train,
+                             const void *w_infer, const dvp_lmhead_f8_side *f8, const int64_t *ids,
+                             const float *grad_out, const dvp_side_out *out_train, const dvp_side_out *out_infer,
+                             uint8_t *row_flags, float *d_hidden, float *d_w, void *workspace,
+                             size_t workspace_bytes, void *stream_)
 {
-    if (!dvp::lm_params_ok(p)) return 0;
-    return dvp::lm_layout(p->n_rows, p->hidden, p->vocab).total;
-}
-
-dvp_status dvp_fused_lmhead(const dvp_lmhead_params *p, const void *hidden, const void *w_train,
-                            const void *w_infer, const int64_t *ids, const float *grad_out,
-                            const dvp_side_out *out_train, const dvp_side_out *out_infer,
-                            uint8_t *row_flags, float *d_hidden, float *d_w, void *workspace,
-                            size_t workspace_bytes, void *stream_)
-{
-    using namespace dvp;
     if (!p) return DVP_ERR_NULL;
     if (p->log_rho != p->log_rho || p->log_rho > 0.0f) return DVP_ERR_PARAM;
     if (p->n_rows < 0 || p->vocab < 1 || p->hidden < 1 || p->ld_hidden < p->hidden || p->ld_w < p->hidden)
@@ -718,9 +768,20 @@ dvp_status dvp_fused_lmhead(const dvp_lmhead_params *p, const void *hidden, cons
     if (p->n_rows == 0) return DVP_OK;
     if (!hidden || !w_train || !ids || !out_train) return DVP_ERR_NULL;
     if (grad_out && (!d_hidden || !d_w)) return DVP_ERR_NULL;
-    if ((out_train && out_train->safe_bits) || (w_infer && out_infer && out_infer->safe_bits))
+    if ((out_train && out_train->safe_bits) || ((w_infer || f8) && out_infer && out_infer->safe_bits))
         return DVP_ERR_UNSUPPORTED;
     if (((uintptr_t)hidden | (uintptr_t)w_train | (uintptr_t)w_infer) % 16) return DVP_ERR_ALIGN;
+    if (f8) {
+        if (!f8->hidden || !f8->w) return DVP_ERR_NULL;
+        if (f8->ld_hidden < p->hidden || f8->ld_w < p->hidden) return DVP_ERR_SHAPE;
+        if (!(f8->scale == f8->scale) || f8->scale <= 0.0f || isinf(f8->scale)) return DVP_ERR_PARAM;
+        // a K step is 128 bytes of every row; tile-relative byte offsets stay in 32 bits
+        if (p->hidden % (2 * BK) || f8->ld_hidden % 16 || f8->ld_w % 16 || f8->ld_hidden > (1 << 23) ||
+            f8->ld_w > (1 << 23))
+            return DVP_ERR_UNSUPPORTED;
+        if (((uintptr_t)f8->hidden | (uintptr_t)f8->w) % 16) return DVP_ERR_ALIGN;
+    }
+    const bool infer_side = w_infer != nullptr || f8 != nullptr;
     const LmLayout L = lm_layout(p->n_rows, p->hidden, p->vocab);
     if (!workspace || ((uintptr_t)workspace % 256) || workspace_bytes < L.total) return DVP_ERR_WORKSPACE;
 
@@ -730,7 +791,7 @@ dvp_status dvp_fused_lmhead(const dvp_lmhead_params *p, const void *hidden, cons
     const void *w_side[2] = {w_train, w_infer};
     SideOut outs[2];
     for (int s = 0; s < 2; ++s) {
-        const dvp_side_out *o = s == 0 ? out_train : (w_infer ? out_infer : nullptr);
+        const dvp_side_out *o = s == 0 ? out_train : (infer_side ? out_infer : nullptr);
         outs[s] = SideOut{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
         if (o) outs[s] = SideOut{o->logp, o->row_max, o->lse_safe, o->lse_full, o->safe_count, nullptr};
     }
@@ -754,16 +815,30 @@ dvp_status dvp_fused_lmhead(const dvp_lmhead_params *p, const void *hidden, cons
         if (o.lse_full) o.lse_full += r0;
         if (o.safe_count) o.safe_count += r0;
         const int nb = (rows + tb - 1) / tb;
+        const bool bytes = s == 1 && f8 != nullptr;
         GemmArgs g;
         g.A = (const uint16_t *)hidden + (int64_t)r0 * p->ld_hidden; g.lda = p->ld_hidden;
         g.B = (const uint16_t *)w_side[s]; g.ldb = p->ld_w;
-        g.M = rows; g.N = v; g.K = d;
+        g.M = rows; g.N = v; g.K = d; g.scale = 1.0f;
+        if (bytes) {   // two bytes count as one element
+            g.A = (const uint16_t *)((const uint8_t *)f8->hidden + (int64_t)r0 * f8->ld_hidden); g.lda = f8->ld_hidden / 2;
+            g.B = (const uint16_t *)f8->w; g.ldb = f8->ld_w / 2;
+            g.K = d / 2; g.scale = f8->scale;
+        }
         hipLaunchKernelGGL(init_stats_kernel, dim3(nb), dim3(tb), 0, stream, st, rows);
         DVP_CHECK_LAUNCH();
-        if (launch_gemm<EpiMax, false>(g, EpiMax{st, ids + r0}, stream) != hipSuccess) return DVP_ERR_HIP;
+        if (bytes) {
+            if (launch_gemm<EpiMax, false, true>(g, EpiMax{st, ids + r0}, stream) != hipSuccess) return DVP_ERR_HIP;
+        } else {
+            if (launch_gemm<EpiMax, false>(g, EpiMax{st, ids + r0}, stream) != hipSuccess) return DVP_ERR_HIP;
+        }
         hipLaunchKernelGGL(after_max_kernel, dim3(nb), dim3(tb), 0, stream, st, rows, p->log_rho);
         DVP_CHECK_LAUNCH();
-        if (write_e) {
+        if (bytes) {
+            if (launch_gemm<EpiSum<false>, true, true>(g, EpiSum<false>{st, rows, nullptr, nullptr, nullptr, 0, 0}, stream) !=
+                hipSuccess)
+                return DVP_ERR_HIP;
+        } else if (write_e) {
             if (launch_gemm<EpiSum<true>, true>(g, EpiSum<true>{st, rows, ids + r0, E, Et, (int64_t)L.v_pad, (int64_t)L.block_pad},
                                                 stream) != hipSuccess) return DVP_ERR_HIP;
         } else {
@@ -813,11 +888,42 @@ dvp_status dvp_fused_lmhead(const dvp_lmhead_params *p, const void *hidden, cons
             DVP_CHECK_LAUNCH();
         }
     }
-    if (w_infer) {
+    if (infer_side) {
         if ((rc = forward(1, 0, n, false, st)) != DVP_OK) return rc;
     }
 #undef DVP_CHECK_LAUNCH
     return DVP_OK;
+}
+
+}  // namespace dvp
+
+extern "C" {
+
+size_t dvp_fused_lmhead_workspace_bytes(const dvp_lmhead_params *p)
+{
+    if (!dvp::lm_params_ok(p)) return 0;
+    return dvp::lm_layout(p->n_rows, p->hidden, p->vocab).total;
+}
+
+dvp_status dvp_fused_lmhead(const dvp_lmhead_params *p, const void *hidden, const void *w_train,
+                            const void *w_infer, const int64_t *ids, const float *grad_out,
+                            const dvp_side_out *out_train, const dvp_side_out *out_infer,
+                            uint8_t *row_flags, float *d_hidden, float *d_w, void *workspace,
+                            size_t workspace_bytes, void *stream)
+{
+    return dvp::run_lmhead(p, hidden, w_train, w_infer, nullptr, ids, grad_out, out_train, out_infer, row_flags,
+                           d_hidden, d_w, workspace, workspace_bytes, stream);
+}
+
+dvp_status dvp_fused_lmhead_f8infer(const dvp_lmhead_params *p, const void *hidden, const void *w_train,
+                                    const dvp_lmhead_f8_side *infer, const int64_t *ids, const float *grad_out,
+                                    const dvp_side_out *out_train, const dvp_side_out *out_infer,
+                                    uint8_t *row_flags, float *d_hidden, float *d_w, void *workspace,
+                                    size_t workspace_bytes, void *stream)
+{
+    if (!infer) return DVP_ERR_NULL;
+    return dvp::run_lmhead(p, hidden, w_train, nullptr, infer, ids, grad_out, out_train, out_infer, row_flags,
+                           d_hidden, d_w, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

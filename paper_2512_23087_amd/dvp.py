@@ -22,7 +22,8 @@ ROW_Y_IN_TRAIN_SAFE, ROW_Y_IN_INFER_SAFE, ROW_ID_OUT_OF_RANGE, ROW_GRAD_OVERFLOW
 
 EXPORTS = ("dvp_forward", "dvp_backward", "dvp_forward_backward", "dvp_fused_lmhead",
            "dvp_fused_lmhead_workspace_bytes", "dvp_log_rho", "dvp_status_string", "dvp_row_path",
-           "dvp_sequence_weights", "dvp_log_threshold", "dvp_forward_backward_sparse")
+           "dvp_sequence_weights", "dvp_log_threshold", "dvp_forward_backward_sparse",
+           "dvp_fused_lmhead_f8infer")
 
 
 class DvpParams(ctypes.Structure):
@@ -42,6 +43,11 @@ class DvpLmHeadParams(ctypes.Structure):
     _fields_ = [("n_rows", ctypes.c_int64), ("hidden", ctypes.c_int64), ("vocab", ctypes.c_int64),
                 ("ld_hidden", ctypes.c_int64), ("ld_w", ctypes.c_int64),
                 ("log_rho", ctypes.c_float)]
+
+
+class DvpLmHeadF8Side(ctypes.Structure):
+    _fields_ = [("hidden", ctypes.c_void_p), ("w", ctypes.c_void_p), ("ld_hidden", ctypes.c_int64),
+                ("ld_w", ctypes.c_int64), ("scale", ctypes.c_float)]
 
 
 class DvpError(RuntimeError):
@@ -75,6 +81,9 @@ def lib():
         L.dvp_fused_lmhead.restype = ctypes.c_int
         L.dvp_fused_lmhead.argtypes = [lp, vp, vp, vp, i64p, vp, sp, sp, vp, vp, vp, vp,
                                        ctypes.c_size_t, vp]
+        L.dvp_fused_lmhead_f8infer.restype = ctypes.c_int
+        L.dvp_fused_lmhead_f8infer.argtypes = [lp, vp, vp, ctypes.POINTER(DvpLmHeadF8Side), i64p, vp, sp, sp, vp, vp,
+                                               vp, vp, ctypes.c_size_t, vp]
         L.dvp_log_rho.restype = ctypes.c_float
         L.dvp_log_rho.argtypes = [ctypes.c_double]
         L.dvp_status_string.restype = ctypes.c_char_p
@@ -298,10 +307,18 @@ def lmhead_workspace_bytes(n, d, v, ld_hidden=None, ld_w=None) -> int:
 
 def dvp_fused_lmhead(hidden, w_train, w_infer, ids, grad_out, log_rho_value, *, lse_full=False,
                      workspace: Optional[torch.Tensor] = None, d_hidden=None, d_w=None,
-                     stream=None) -> LmHeadResult:
+                     stream=None, infer_f8=None) -> LmHeadResult:
+    """infer_f8 = (hidden8, w8, scale): the inference side is an 8-bit engine with float8_e4m3fn
+    activations [N, d] and head [V, d], logits scale * hidden8 w8^T (then w_infer must be None)."""
     for name, t in (("hidden", hidden), ("w_train", w_train)):
         if not t.is_cuda or t.dtype != torch.bfloat16 or t.dim() != 2 or t.stride(1) != 1:
             raise ValueError("%s must be a bf16 [rows, d] GPU tensor with unit inner stride" % name)
+    if infer_f8 is not None:
+        if w_infer is not None:
+            raise ValueError("give either w_infer or infer_f8")
+        for name, t in (("infer_f8 hidden", infer_f8[0]), ("infer_f8 w", infer_f8[1])):
+            if not t.is_cuda or t.dtype != torch.float8_e4m3fn or t.dim() != 2 or t.stride(1) != 1:
+                raise ValueError("%s must be a float8_e4m3fn [rows, d] GPU tensor with unit inner stride" % name)
     n, d = hidden.shape
     v = w_train.shape[0]
     dev = hidden.device
@@ -310,13 +327,23 @@ def dvp_fused_lmhead(hidden, w_train, w_infer, ids, grad_out, log_rho_value, *, 
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
     out_train = SideOutputs(n, v, dev, lse_full, False)
-    out_infer = SideOutputs(n, v, dev, lse_full, False) if w_infer is not None else None
+    out_infer = SideOutputs(n, v, dev, lse_full, False) if (w_infer is not None or infer_f8 is not None) else None
     row_flags = torch.empty(n, dtype=torch.uint8, device=dev)
     if grad_out is not None:
         if d_hidden is None:
             d_hidden = torch.empty(n, hidden.stride(0), dtype=torch.float32, device=dev)[:, :d]
         if d_w is None:
             d_w = torch.empty(v, w_train.stride(0), dtype=torch.float32, device=dev)[:, :d]
+    if infer_f8 is not None:
+        h8, w8, scale = infer_f8
+        side = DvpLmHeadF8Side(h8.data_ptr(), w8.data_ptr(), h8.stride(0), w8.stride(0), float(scale))
+        st = lib().dvp_fused_lmhead_f8infer(ctypes.byref(p), _ptr(hidden), _ptr(w_train), ctypes.byref(side),
+                                            _ptr(ids), _ptr(grad_out), ctypes.byref(out_train.struct()),
+                                            ctypes.byref(out_infer.struct()), _ptr(row_flags), _ptr(d_hidden),
+                                            _ptr(d_w), _ptr(workspace), workspace.numel(), _stream(stream))
+        if st != 0:
+            raise DvpError(st, "dvp_fused_lmhead_f8infer")
+        return LmHeadResult(out_train, out_infer, row_flags, d_hidden, d_w)
     st = lib().dvp_fused_lmhead(ctypes.byref(p), _ptr(hidden), _ptr(w_train), _ptr(w_infer),
                                 _ptr(ids), _ptr(grad_out), ctypes.byref(out_train.struct()),
                                 ctypes.byref(out_infer.struct()) if out_infer is not None else None,

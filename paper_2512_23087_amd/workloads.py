@@ -45,6 +45,11 @@ class LmHeadWorkload:
     grad_out: torch.Tensor  # [N] fp32
     rhos: List[float]
     meta: dict = field(default_factory=dict)
+    # an 8-bit inference engine for the same model (make_lmhead(f8_engine=True)): activations and head
+    # as float8_e4m3fn with per-tensor factors; its logits are scale_infer * hidden8 w8^T
+    hidden8: Optional[torch.Tensor] = None
+    w8: Optional[torch.Tensor] = None
+    scale_infer: float = 1.0
 
 
 # (N, V, dtype, kind) of the five cases; kind selects the logit recipe below.
@@ -145,10 +150,15 @@ def make_rows(config: int, device="cpu", n: Optional[int] = None, v: Optional[in
 
 
 def make_lmhead(device="cpu", n: Optional[int] = None, d: Optional[int] = None,
-                v: Optional[int] = None, chunk: int = 1024) -> LmHeadWorkload:
+                v: Optional[int] = None, chunk: int = 1024, f8_engine: bool = False) -> LmHeadWorkload:
     """Hidden states ~ N(0,1), head weights ~ N(0, 0.02^2), both bf16; the
     inference head is the same matrix rounded through fp8-e4m3.  Tokens are
-    sampled from the softmax of the inference logits H W_infer^T."""
+    sampled from the softmax of the inference logits H W_infer^T.
+
+    f8_engine: the inference side is instead an 8-bit engine: activations
+    e4m3(H / s_h) and head e4m3(W / s_w) with per-tensor factors s = max|.| / 448
+    (the usual per-tensor FP8 recipe), logits (s_h s_w) * hidden8 w8^T, and the
+    tokens are sampled from those."""
     c = LMHEAD_CONFIG
     n = c["n"] if n is None else n
     d = c["d"] if d is None else d
@@ -162,14 +172,27 @@ def make_lmhead(device="cpu", n: Optional[int] = None, d: Optional[int] = None,
     del w32
     ids = torch.empty(n, dtype=torch.int64, device=dev)
     mm_dtype = torch.float32
-    wi = w_infer.to(mm_dtype)
+    hidden8 = w8 = None
+    scale_infer = 1.0
+    if f8_engine:
+        s_h = float(hidden.float().abs().max().item()) / E4M3_MAX
+        s_w = float(w_train.float().abs().max().item()) / E4M3_MAX
+        hidden8 = (hidden.float() / s_h).clamp(-E4M3_MAX, E4M3_MAX).to(torch.float8_e4m3fn)
+        w8 = torch.empty(v, d, dtype=torch.float8_e4m3fn, device=dev)
+        for r0 in range(0, v, 16384):
+            w8[r0:r0 + 16384] = (w_train[r0:r0 + 16384].float() / s_w).clamp(-E4M3_MAX, E4M3_MAX).to(torch.float8_e4m3fn)
+        scale_infer = float(torch.tensor(s_h * s_w, dtype=torch.float32).item())   # the fp32 value both sides use
+        lhs, wi = hidden8, w8.to(mm_dtype)
+    else:
+        lhs, wi = hidden, w_infer.to(mm_dtype)
     for r0 in range(0, n, chunk):
         r1 = min(n, r0 + chunk)
-        logits = hidden[r0:r1].to(mm_dtype) @ wi.T
+        logits = scale_infer * (lhs[r0:r1].to(mm_dtype) @ wi.T)
         ids[r0:r1] = _sample_ids(logits, g)
         del logits
     del wi
     grad_out = torch.randn(n, generator=g, device=dev)
     return LmHeadWorkload(name="lmhead_N%d_d%d_V%d" % (n, d, v), hidden=hidden,
                           w_train=w_train, w_infer=w_infer, ids=ids, grad_out=grad_out,
-                          rhos=list(c["rhos"]), meta=dict(n=n, d=d, v=v))
+                          rhos=list(c["rhos"]), meta=dict(n=n, d=d, v=v), hidden8=hidden8, w8=w8,
+                          scale_infer=scale_infer)

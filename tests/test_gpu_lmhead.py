@@ -296,3 +296,82 @@ def test_padded_strides_and_out_of_range_ids(dvp):
     keep[3] = keep[77] = False
     assert torch.equal(a.train.logp[keep], b.train.logp[keep])
     assert torch.equal(a.d_hidden[keep], b.d_hidden[keep]) and torch.equal(a.d_w, b.d_w)
+
+
+# ---------------------------------------------------------------------------
+# the inference side as an 8-bit (W8A8) engine: z' = scale * hidden8 w8^T on the 8-bit matrix instructions
+# ---------------------------------------------------------------------------
+def _run_f8(dvp, wl, rho, grad=True, lse_full=False):
+    lr = dvp.log_rho(rho)
+    res = dvp.dvp_fused_lmhead(wl.hidden, wl.w_train, None, wl.ids, wl.grad_out if grad else None, lr,
+                               lse_full=lse_full, infer_f8=(wl.hidden8, wl.w8, wl.scale_infer))
+    torch.cuda.synchronize()
+    ids = wl.ids.cpu().numpy()
+    h8 = wl.hidden8.view(torch.uint8).cpu().numpy()
+    w8 = wl.w8.view(torch.uint8).cpu().numpy()
+    oi = orc.lmhead(h8, w8, ids, np.float32(lr), band=BAND, threads=8, scale=wl.scale_infer)
+    same_i = _check_side("infer", res.infer, oi, oi)
+    flags = res.row_flags.cpu().numpy()
+    np.testing.assert_array_equal(((flags >> 1) & 1)[same_i], oi["y_in_safe"][same_i])
+    # the training side and the gradient do not depend on how the inference logits were made
+    ref = dvp.dvp_fused_lmhead(wl.hidden, wl.w_train, None, wl.ids, wl.grad_out if grad else None, lr,
+                               lse_full=lse_full)
+    torch.cuda.synchronize()
+    for k in ("logp", "row_max", "lse_safe", "safe_count"):
+        assert torch.equal(getattr(res.train, k), getattr(ref.train, k)), k
+    assert torch.equal(res.row_flags & 5, ref.row_flags & 5)
+    if grad:
+        assert torch.equal(res.d_hidden, ref.d_hidden) and torch.equal(res.d_w, ref.d_w)
+    return res, oi
+
+
+def test_f8_engine_small_ragged_shapes(dvp):
+    wl = workloads.make_lmhead(device="cuda", n=200, d=128, v=1000, f8_engine=True)
+    for rho in (1e-2, 1e-4, 0.0):
+        res, oi = _run_f8(dvp, wl, rho, lse_full=True)
+    # the 8-bit engine's logits differ visibly from the bf16 ones: this is a different engine, not a copy
+    zt = wl.hidden.float() @ wl.w_train.float().T
+    assert (torch.as_tensor(oi["z"], device="cuda").float() - zt).abs().max().item() > 1e-2
+
+
+def test_f8_engine_several_tiles_and_k_steps(dvp):
+    wl = workloads.make_lmhead(device="cuda", n=700, d=1024, v=3001, f8_engine=True)
+    _run_f8(dvp, wl, 1e-4, grad=False)
+    wl = workloads.make_lmhead(device="cuda", n=513, d=384, v=777, f8_engine=True)
+    _run_f8(dvp, wl, 1e-3)
+
+
+def test_f8_engine_padded_strides(dvp):
+    wl = workloads.make_lmhead(device="cuda", n=130, d=256, v=600, f8_engine=True)
+    h8 = torch.zeros(130, 256 + 48, dtype=torch.uint8, device="cuda").fill_(0x7f)
+    w8 = torch.zeros(600, 256 + 16, dtype=torch.uint8, device="cuda").fill_(0x7f)
+    h8[:, :256] = wl.hidden8.view(torch.uint8)
+    w8[:, :256] = wl.w8.view(torch.uint8)
+    wl.hidden8 = h8.view(torch.float8_e4m3fn)[:, :256]
+    wl.w8 = w8.view(torch.float8_e4m3fn)[:, :256]
+    wl2 = wl
+    lr = dvp.log_rho(1e-4)
+    res = dvp.dvp_fused_lmhead(wl2.hidden, wl2.w_train, None, wl2.ids, None, lr,
+                               infer_f8=(wl2.hidden8, wl2.w8, wl2.scale_infer))
+    torch.cuda.synchronize()
+    oi = orc.lmhead(wl2.hidden8.contiguous().view(torch.uint8).cpu().numpy(),
+                    wl2.w8.contiguous().view(torch.uint8).cpu().numpy(), wl2.ids.cpu().numpy(), np.float32(lr),
+                    band=BAND, threads=4, scale=wl2.scale_infer)
+    _check_side("infer", res.infer, oi, oi)
+
+
+def test_f8_engine_rejects_bad_arguments(dvp):
+    wl = workloads.make_lmhead(device="cuda", n=16, d=128, v=64, f8_engine=True)
+    lr = dvp.log_rho(1e-4)
+    with pytest.raises(dvp.DvpError) as e:      # hidden size not a multiple of 128
+        wl64 = workloads.make_lmhead(device="cuda", n=16, d=64, v=64, f8_engine=True)
+        dvp.dvp_fused_lmhead(wl64.hidden, wl64.w_train, None, wl64.ids, None, lr,
+                             infer_f8=(wl64.hidden8, wl64.w8, wl64.scale_infer))
+    assert e.value.status == 5
+    for bad in (0.0, -1.0, float("nan"), float("inf")):
+        with pytest.raises(dvp.DvpError) as e:
+            dvp.dvp_fused_lmhead(wl.hidden, wl.w_train, None, wl.ids, None, lr, infer_f8=(wl.hidden8, wl.w8, bad))
+        assert e.value.status == 3
+    with pytest.raises(ValueError):
+        dvp.dvp_fused_lmhead(wl.hidden, wl.w_train, wl.w_infer, wl.ids, None, lr,
+                             infer_f8=(wl.hidden8, wl.w8, wl.scale_infer))

@@ -146,3 +146,44 @@ def test_sparse_gradient_validation_needs_no_gpu():
     assert call(vocab=32001) == 5            # rows not 16-byte aligned: no single-read path
     assert call(vocab=200000) == 5           # does not fit the register file
     assert call(z=FAKE + 2) == 5             # base pointer not 16-byte aligned
+
+
+def test_lmhead_argument_validation_needs_no_gpu():
+    L = dvp.lib()
+    so = dvp.DvpSideOut(FAKE, FAKE, FAKE, None, FAKE, None)
+    ws = FAKE * 256
+
+    def P(n=1, d=128, v=64, ld_h=None, ld_w=None, lr=-3.0):
+        return dvp.DvpLmHeadParams(n, d, v, ld_h or d, ld_w or d, lr)
+
+    def call(p, hidden=FAKE, w=FAKE, w_infer=FAKE, ids=FAKE, grad=None, bytes_=1 << 40, workspace=ws):
+        return L.dvp_fused_lmhead(ctypes.byref(p), hidden, w, w_infer, ids, grad, ctypes.byref(so), ctypes.byref(so),
+                                  FAKE, None, None, workspace, bytes_, None)
+
+    assert L.dvp_fused_lmhead_workspace_bytes(ctypes.byref(P())) > 0
+    assert L.dvp_fused_lmhead_workspace_bytes(ctypes.byref(P(d=100))) == 0
+    assert call(P(n=0)) == 0
+    assert call(P(), hidden=None) == 1
+    assert call(P(lr=0.5)) == 3
+    assert call(P(v=0)) == 2
+    assert call(P(d=96)) == 5                       # hidden size not a multiple of 64
+    assert call(P(v=(1 << 22) + 1)) == 5
+    assert call(P(), grad=FAKE) == 1                # gradient outputs missing
+    assert call(P(), hidden=FAKE + 8) == 4
+    assert call(P(), bytes_=16) == 6 and call(P(), workspace=None) == 6
+
+    def call8(p, side, hidden=FAKE):
+        return L.dvp_fused_lmhead_f8infer(ctypes.byref(p), hidden, FAKE, side, FAKE, None, ctypes.byref(so),
+                                          ctypes.byref(so), FAKE, None, None, ws, 1 << 40, None)
+
+    def S(hidden=FAKE, w=FAKE, ld_h=128, ld_w=128, scale=0.5):
+        return ctypes.byref(dvp.DvpLmHeadF8Side(hidden, w, ld_h, ld_w, scale))
+
+    assert call8(P(), None) == 1
+    assert call8(P(), S(hidden=None)) == 1
+    assert call8(P(), S(ld_h=64)) == 2              # row stride shorter than the hidden size
+    assert call8(P(), S(scale=0.0)) == 3 and call8(P(), S(scale=float("nan"))) == 3
+    assert call8(P(d=192, ld_h=192, ld_w=192), S(ld_h=192, ld_w=192)) == 5     # hidden size not a multiple of 128
+    assert call8(P(), S(ld_h=136)) == 5             # byte rows not 16-byte aligned
+    assert call8(P(), S(w=FAKE + 8)) == 4
+    assert call8(P(n=0), S()) == 0

@@ -250,6 +250,27 @@ def test_e4m3_inputs_are_widened_exactly():
         np.testing.assert_array_equal(a[k], c[k])
 
 
+def test_lmhead_oracle_with_an_8bit_inference_engine():
+    """Logits of an 8-bit engine, scale * hidden8 w8^T on E4M3 codes, equal the logits of the dequantised
+    matrices (s_h hidden8)(s_w w8)^T; torch's own float8 widening supplies the dequantised values."""
+    g = torch.Generator().manual_seed(21)
+    h = torch.randn(7, 64, generator=g)
+    w = 0.02 * torch.randn(50, 64, generator=g)
+    s_h, s_w = float(h.abs().max()) / 448.0, float(w.abs().max()) / 448.0
+    h8 = (h / s_h).to(torch.float8_e4m3fn)
+    w8 = (w / s_w).to(torch.float8_e4m3fn)
+    ids = np.arange(7)
+    lr = orc.log_rho_f32(1e-3)
+    a = orc.lmhead(h8, w8, ids, lr, scale=s_h * s_w)
+    b = orc.lmhead((h8.to(torch.float64) * s_h).numpy(), (w8.to(torch.float64) * s_w).numpy(), ids, lr)
+    np.testing.assert_allclose(a["z"], b["z"], rtol=1e-13, atol=1e-15)
+    np.testing.assert_array_equal(a["safe_count"], b["safe_count"])
+    np.testing.assert_allclose(a["logp"], b["logp"], rtol=0, atol=1e-12)
+    assert np.abs(a["z"]).max() > 0.1        # not a comparison of zeros
+    with pytest.raises(ValueError):
+        orc.lmhead(h8, w8, ids, lr, grad_out=np.ones(7), scale=2.0)
+
+
 def test_shift_invariance():
     z, ids = _rand_rows(8, 500, 5)
     lr = orc.log_rho_f32(1e-3)

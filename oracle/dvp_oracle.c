@@ -19,6 +19,9 @@
  *              the un-normalised mass kept; softmax over the masked logits,
  *              Prop. 5.6 part 1)
  *   lse_full = log sum_k exp(z_k)   =>  log Z_theta = lse_safe - lse_full
+ *   entropy  = -sum_{k: s_k} pi_mp(k) log pi_mp(k), pi_mp(k) = exp(z_k - lse_safe)
+ *              (entropy of the constrained policy of Def. 5.2; Sec. 7 names
+ *              it as the signal an adaptive rho would follow)
  *   logp     = z_y - lse_safe  if s_y, else -inf          (Def. 5.2; a token
  *              outside the safe set has constrained probability zero,
  *              Sec. 5.3 closing remark)
@@ -97,6 +100,7 @@ typedef struct {
     uint8_t *y_in_safe;
     uint8_t *safe_flags; /* nullable, [n_rows, vocab] */
     double *dz;          /* nullable, [n_rows, vocab] */
+    double *entropy;     /* nullable, [n_rows] */
 } oracle_job;
 
 typedef struct {
@@ -187,6 +191,19 @@ static void oracle_row(const oracle_job *J, int64_t i, double *zrow)
     J->band_count[i] = nb;
     J->y_in_safe[i] = (uint8_t)y_safe;
 
+    /* entropy of the constrained policy, H = -sum_{k in V_S} pi_mp(k) log pi_mp(k) (Def. 5.2; the
+     * quantity Sec. 7 proposes to steer rho with) */
+    if (J->entropy) {
+        nsum H = {0.0, 0.0};
+        for (k = 0; k < V; ++k) {
+            if (zrow[k] >= tau) {
+                double lp = zrow[k] - lse_safe;
+                nsum_add(&H, -exp(lp) * lp);
+            }
+        }
+        J->entropy[i] = nsum_value(&H);
+    }
+
     /* gradient w.r.t. the row's logits, set held fixed (Prop. 5.4) */
     if (J->dz) {
         const double g = J->grad_out ? J->grad_out[i] : 1.0;
@@ -222,7 +239,7 @@ int dvp_oracle_rows(const void *z, int dtype, int64_t n_rows, int64_t vocab, int
                     const double *grad_out,
                     double *row_max, double *tau, double *lse_safe, double *lse_full,
                     double *logp, int64_t *safe_count, int64_t *band_count,
-                    uint8_t *y_in_safe, uint8_t *safe_flags, double *dz, int n_threads)
+                    uint8_t *y_in_safe, uint8_t *safe_flags, double *dz, int n_threads, double *entropy)
 {
     if (!z || !ids || !row_max || !tau || !lse_safe || !lse_full || !logp ||
         !safe_count || !band_count || !y_in_safe) return 1;
@@ -233,7 +250,7 @@ int dvp_oracle_rows(const void *z, int dtype, int64_t n_rows, int64_t vocab, int
 
     oracle_job job = { z, dtype, n_rows, vocab, ld, ids, log_rho, band, grad_out,
                        row_max, tau, lse_safe, lse_full, logp, safe_count, band_count,
-                       y_in_safe, safe_flags, dz };
+                       y_in_safe, safe_flags, dz, entropy };
 
     if (n_threads < 1) n_threads = 1;
     if ((int64_t)n_threads > n_rows) n_threads = (int)n_rows;
@@ -307,5 +324,96 @@ int dvp_oracle_sequences(int64_t n_tokens, int64_t n_seq, const float *logp_trai
         seq_min_weight[s] = saw_nan ? NAN : wmin;
         seq_veto[s] = (uint8_t)veto;
     }
+    return 0;
+}
+
+
+/*
+ * The finite-mask variant the paper describes for low-precision training (Sec. 5.5 "Logit Masking
+ * Strategy", App. A protocol item 3 and the appendix's masking function), followed by the log-softmax
+ * of the masked logits and its gradient as automatic differentiation would deliver it:
+ *
+ *   m        = max_k z_k
+ *   tau_c    = m + log_rho evaluated in the arithmetic of the logits' storage type: an fp32 add,
+ *              then, for bf16 logits, a rounding of the sum to bf16 (round to nearest even); the
+ *              plain double sum for fp64 inputs
+ *   pruned_k = [ z_k < tau_c ]
+ *   z'_k     = mask_value if pruned_k else z_k          (pruned logits become a finite constant,
+ *              -50 in the paper, instead of -inf)
+ *   lse      = log sum_k exp(z'_k)                      (over ALL k: each pruned token keeps the
+ *              mass exp(mask_value - lse))
+ *   logp     = z'_y - lse                               (finite also when y is pruned)
+ *   dz_k     = 0 if pruned_k (the mask constant carries no gradient to the logit it replaced),
+ *              else g * ([k = y and not pruned_y] - exp(z_k - lse))
+ *
+ * Outputs as in dvp_oracle_rows; y_in_safe = !pruned_y.  Returns 0 / 1 like it.
+ */
+static float bf16_round_nearest_even(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    if ((u & 0x7f800000u) != 0x7f800000u) {            /* finite: round the low 16 bits away */
+        uint32_t keep_odd = (u >> 16) & 1u;
+        u += 0x7fffu + keep_odd;
+    }
+    u &= 0xffff0000u;
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+int dvp_oracle_rows_finite_mask(const void *z, int dtype, int64_t n_rows, int64_t vocab, int64_t ld,
+                                const int64_t *ids, double log_rho, double mask_value,
+                                const double *grad_out, double *row_max, double *tau_out,
+                                double *lse_out, double *logp_out, int64_t *safe_count,
+                                uint8_t *y_in_safe, uint8_t *safe_flags, double *dz)
+{
+    if (!z || !ids || !row_max || !tau_out || !lse_out || !logp_out || !safe_count || !y_in_safe) return 1;
+    if (n_rows < 0 || vocab < 1 || ld < vocab) return 1;
+    if (dtype < 0 || dtype > 2) return 1;
+    if (log_rho != log_rho || log_rho > 0.0 || !isfinite(mask_value)) return 1;
+    double *zrow = (double *)malloc(sizeof(double) * (size_t)vocab);
+    if (!zrow) return 2;
+    for (int64_t i = 0; i < n_rows; ++i) {
+        const int64_t V = vocab, y = ids[i];
+        int64_t k;
+        for (k = 0; k < V; ++k) zrow[k] = fetch(z, dtype, i * ld + k);
+        double m = zrow[0];
+        for (k = 1; k < V; ++k) if (zrow[k] > m) m = zrow[k];
+        double tau;
+        if (dtype == DVP_ORACLE_F64) {
+            tau = m + log_rho;
+        } else {
+            float t32 = (float)m + (float)log_rho;         /* fp32 add of two fp32 values */
+            if (dtype == DVP_ORACLE_BF16) t32 = bf16_round_nearest_even(t32);
+            tau = (double)t32;
+        }
+        int64_t c = 0;
+        nsum S = {0.0, 0.0};
+        /* exponentials are taken relative to the larger of m and the mask so that nothing overflows */
+        const double ref = m > mask_value ? m : mask_value;
+        for (k = 0; k < V; ++k) {
+            const int pruned = zrow[k] < tau;
+            c += !pruned;
+            if (safe_flags) safe_flags[i * V + k] = (uint8_t)!pruned;
+            nsum_add(&S, exp((pruned ? mask_value : zrow[k]) - ref));
+        }
+        const double lse = ref + log(nsum_value(&S));
+        const int in_range = (y >= 0 && y < V);
+        const int y_pruned = in_range && (zrow[y] < tau);
+        row_max[i] = m;
+        tau_out[i] = tau;
+        lse_out[i] = lse;
+        safe_count[i] = c;
+        y_in_safe[i] = (uint8_t)(in_range && !y_pruned);
+        logp_out[i] = !in_range ? NAN : ((y_pruned ? mask_value : zrow[y]) - lse);
+        if (dz) {
+            const double g = grad_out ? grad_out[i] : 1.0;
+            for (k = 0; k < V; ++k) {
+                if (!in_range || zrow[k] < tau) dz[i * V + k] = 0.0;
+                else dz[i * V + k] = g * ((k == y ? 1.0 : 0.0) - exp(zrow[k] - lse));
+            }
+        }
+    }
+    free(zrow);
     return 0;
 }

@@ -56,7 +56,12 @@ def _load():
             ctypes.c_void_p, ctypes.c_float, ctypes.c_double, ctypes.c_void_p,
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
-            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int]
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
+        lib.dvp_oracle_rows_finite_mask.restype = ctypes.c_int
+        lib.dvp_oracle_rows_finite_mask.argtypes = [
+            ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
+            ctypes.c_double, ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         lib.dvp_oracle_e4m3_value.restype = ctypes.c_double
         lib.dvp_oracle_e4m3_value.argtypes = [ctypes.c_uint8]
         lib.dvp_oracle_sequences.restype = ctypes.c_int
@@ -111,13 +116,14 @@ def e4m3_value(code: int) -> float:
 
 
 def rows(z, ids, log_rho, grad_out=None, want_flags=False, want_dz=False,
-         band=1e-6, threads=1):
+         band=1e-6, threads=1, want_entropy=False):
     """One side of the DVP forward (and, with want_dz, the gradient of the
     sampled token's constrained log-probability) for every row of z.
 
     Returns a dict of numpy arrays: row_max, tau, lse_safe, lse_full, logp
     (float64 [N]); safe_count, band_count (int64 [N]); y_in_safe (uint8 [N]);
-    optionally safe_flags (uint8 [N, V]) and dz (float64 [N, V])."""
+    optionally safe_flags (uint8 [N, V]), dz (float64 [N, V]) and entropy (float64 [N]: entropy of
+    the constrained policy)."""
     z, code = as_oracle_input(z)
     n, v = z.shape
     ids = np.ascontiguousarray(np.asarray(ids, dtype=np.int64))
@@ -137,6 +143,7 @@ def rows(z, ids, log_rho, grad_out=None, want_flags=False, want_dz=False,
     }
     flags = np.empty((n, v), np.uint8) if want_flags else None
     dz = np.empty((n, v), np.float64) if want_dz else None
+    ent = np.empty(n, np.float64) if want_entropy else None
 
     def p(a):
         return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
@@ -145,9 +152,42 @@ def rows(z, ids, log_rho, grad_out=None, want_flags=False, want_dz=False,
         p(z), code, n, v, v, p(ids), ctypes.c_float(float(log_rho)), float(band), p(g),
         p(out["row_max"]), p(out["tau"]), p(out["lse_safe"]), p(out["lse_full"]),
         p(out["logp"]), p(out["safe_count"]), p(out["band_count"]), p(out["y_in_safe"]),
-        p(flags), p(dz), int(threads))
+        p(flags), p(dz), int(threads), p(ent))
     if rc != 0:
         raise RuntimeError("dvp_oracle_rows failed with code %d" % rc)
+    if want_flags:
+        out["safe_flags"] = flags
+    if want_dz:
+        out["dz"] = dz
+    if want_entropy:
+        out["entropy"] = ent
+    return out
+
+
+def rows_finite_mask(z, ids, log_rho, mask_value=-50.0, grad_out=None, want_flags=False, want_dz=False):
+    """The finite-mask variant (Sec. 5.5 "Logit Masking Strategy", App. A item 3): pruned logits
+    become `mask_value`, the threshold is evaluated in the logits' storage arithmetic, and log-softmax
+    runs over the whole masked row.  `log_rho` is the double log(rho).  Returns row_max, tau, lse, logp
+    (float64 [N]), safe_count (int64 [N]), y_in_safe (uint8 [N]), optionally safe_flags and dz."""
+    z, code = as_oracle_input(z)
+    if code == F8E4M3:
+        raise TypeError("8-bit logits are an inference-side format of the exact path only")
+    n, v = z.shape
+    ids = np.ascontiguousarray(np.asarray(ids, dtype=np.int64))
+    g = None if grad_out is None else np.ascontiguousarray(np.asarray(grad_out, dtype=np.float64))
+    out = {"row_max": np.empty(n, np.float64), "tau": np.empty(n, np.float64), "lse": np.empty(n, np.float64),
+           "logp": np.empty(n, np.float64), "safe_count": np.empty(n, np.int64), "y_in_safe": np.empty(n, np.uint8)}
+    flags = np.empty((n, v), np.uint8) if want_flags else None
+    dz = np.empty((n, v), np.float64) if want_dz else None
+
+    def p(a):
+        return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+    rc = _load().dvp_oracle_rows_finite_mask(p(z), code, n, v, v, p(ids), float(log_rho), float(mask_value), p(g),
+                                             p(out["row_max"]), p(out["tau"]), p(out["lse"]), p(out["logp"]),
+                                             p(out["safe_count"]), p(out["y_in_safe"]), p(flags), p(dz))
+    if rc != 0:
+        raise RuntimeError("dvp_oracle_rows_finite_mask failed with code %d" % rc)
     if want_flags:
         out["safe_flags"] = flags
     if want_dz:

@@ -30,6 +30,18 @@ MUTATIONS = {
     "e4m3_has_infinity": ("if (expo == 15 && mant == 7) return NAN;",
                           "if (expo == 15) return mant ? NAN : (sign ? -INFINITY : INFINITY);"),
     "e4m3_mantissa_width": ("(double)mant / 8.0, expo", "(double)mant / 16.0, expo"),
+    "entropy_sign": ("nsum_add(&H, -exp(lp) * lp);", "nsum_add(&H, exp(lp) * lp);"),
+    "entropy_over_all_tokens": ("""            if (zrow[k] >= tau) {
+                double lp = zrow[k] - lse_safe;""", """            if (1) {
+                double lp = zrow[k] - lse_safe;"""),
+    "finite_mask_threshold_not_rounded": ("if (dtype == DVP_ORACLE_BF16) t32 = bf16_round_nearest_even(t32);", ""),
+    "finite_mask_pruned_mass_dropped": ("nsum_add(&S, exp((pruned ? mask_value : zrow[k]) - ref));",
+                                        "if (!pruned) nsum_add(&S, exp(zrow[k] - ref));"),
+    "finite_mask_pruned_token_minus_inf": ("((y_pruned ? mask_value : zrow[y]) - lse)",
+                                           "(y_pruned ? -INFINITY : zrow[y] - lse)"),
+    "finite_mask_gradient_reaches_pruned": ("if (!in_range || zrow[k] < tau) dz[i * V + k] = 0.0;",
+                                            "if (!in_range) dz[i * V + k] = 0.0;"),
+    "finite_mask_inclusive_pruning": ("const int pruned = zrow[k] < tau;", "const int pruned = zrow[k] <= tau;"),
     "infinite_weight_not_vetoed": ("|| l32 == INFINITY) veto = 1;", ") veto = 1;"),
 }
 

@@ -510,3 +510,122 @@ def test_sequence_weight_is_the_change_of_measure_of_thm_4_1():
     rhs = float((p_train * np.exp(-out["seq_log_ratio"]) * f.ravel()).sum())
     assert abs(lhs - rhs) <= 1e-6
     assert abs(p_train.sum() - 1.0) <= 1e-12 and abs(p_infer.sum() - 1.0) <= 1e-12
+
+
+# ---------------------------------------------------------------------------
+# entropy of the constrained policy
+# ---------------------------------------------------------------------------
+def test_entropy_against_scipy_and_closed_forms():
+    import scipy.stats
+    z, ids = _rand_rows(12, 700, 31)
+    lr = orc.log_rho_f32(1e-2)
+    out = orc.rows(z, ids, lr, want_entropy=True, want_flags=True)
+    for i in range(z.shape[0]):
+        keep = z[i] >= np.float64(np.float32(z[i].max() + np.float64(lr)))       # mask rebuilt here
+        np.testing.assert_array_equal(keep, out["safe_flags"][i] == 1)
+        p = np.exp(z[i][keep] - z[i].max())
+        want = scipy.stats.entropy(p / p.sum())
+        assert abs(out["entropy"][i] - want) <= 1e-12
+        assert -1e-15 <= out["entropy"][i] <= math.log(keep.sum()) + 1e-12
+        # H = lse_safe - E_pi[z]
+        pi = p / p.sum()
+        assert abs(out["entropy"][i] - (out["lse_safe"][i] - (pi * z[i][keep]).sum())) <= 1e-10
+    # closed forms: c equal logits above the threshold -> log c; a lone maximum -> 0
+    zz = np.full((1, 50), -100.0); zz[0, :7] = 3.25
+    assert abs(orc.rows(zz, [0], lr, want_entropy=True)["entropy"][0] - math.log(7)) <= 1e-14
+    zz[0, 1:] = -100.0
+    assert orc.rows(zz, [0], lr, want_entropy=True)["entropy"][0] == 0.0
+    # no pruning: the entropy of the plain softmax
+    full = orc.rows(z, ids, orc.log_rho_f32(0.0), want_entropy=True)["entropy"]
+    np.testing.assert_allclose(full, [scipy.stats.entropy(scipy.special.softmax(r)) for r in z], rtol=0, atol=1e-12)
+
+
+# ---------------------------------------------------------------------------
+# the finite-mask variant (Sec. 5.5 "Logit Masking Strategy", App. A item 3)
+# ---------------------------------------------------------------------------
+def _torch_finite_mask(z, ids, rho, mask_value, g):
+    """The variant written with torch operators: threshold and comparison in the tensor's own dtype,
+    a constant in place of the pruned logits, log-softmax over the whole row (in float64), autograd."""
+    zz = z.clone().requires_grad_(True)
+    with torch.no_grad():
+        m = zz.max(dim=-1, keepdim=True).values
+        if zz.dtype == torch.bfloat16:
+            # On the GPU, where the method runs, torch adds a Python scalar to a bf16 tensor in fp32 and
+            # rounds the sum; its CPU kernel rounds the scalar to bf16 first (observed: 8.375 + log(0.01)
+            # gives 3.78125 instead of 3.765625).  The GPU behaviour is the one followed, written out
+            # here; tests/test_gpu_finite_mask.py checks it against torch's own GPU add.
+            thr = (m.float() + torch.tensor(math.log(rho), dtype=torch.float32)).to(torch.bfloat16)
+        else:
+            thr = m + math.log(rho)
+        pruned = zz < thr
+    masked = torch.where(pruned, torch.tensor(mask_value, dtype=zz.dtype), zz)
+    lp = torch.log_softmax(masked.to(torch.float64), dim=-1)
+    picked = lp.gather(1, torch.as_tensor(ids).view(-1, 1)).squeeze(1)
+    (picked * torch.as_tensor(g, dtype=torch.float64)).sum().backward()
+    return pruned.numpy(), thr.to(torch.float64).squeeze(1).numpy(), picked.detach().numpy(), \
+        zz.grad.to(torch.float64).numpy()
+
+
+@pytest.mark.parametrize("dtype", [torch.float64, torch.float32, torch.bfloat16])
+def test_finite_mask_against_torch(dtype):
+    gen = torch.Generator().manual_seed(77)
+    z = (3.0 * torch.randn(16, 900, generator=gen, dtype=torch.float64)).to(dtype)
+    ids = torch.randint(0, 900, (16,), generator=gen).numpy()
+    ids[0] = int(z[0].argmin())                     # a pruned sampled token
+    ids[1] = int(z[1].argmax())
+    g = torch.randn(16, generator=gen, dtype=torch.float64).numpy()
+    for rho, mask_value in ((1e-2, -50.0), (math.exp(-13.0), -50.0), (1e-1, -7.5)):
+        pruned, thr, lp, grad = _torch_finite_mask(z, ids, rho, mask_value, g)
+        out = orc.rows_finite_mask(z, ids, math.log(rho), mask_value, grad_out=g, want_flags=True, want_dz=True)
+        np.testing.assert_array_equal(out["safe_flags"] == 0, pruned)
+        np.testing.assert_array_equal(out["tau"], thr)
+        np.testing.assert_allclose(out["logp"], lp, rtol=0, atol=1e-11)
+        # autograd hands the gradient back in the leaf's dtype: one rounding to that type
+        eps = {torch.float64: 0.0, torch.float32: 2.0 ** -24, torch.bfloat16: 2.0 ** -8}[dtype]
+        assert np.all(np.abs(out["dz"] - grad) <= eps * np.abs(out["dz"]) + 1e-12)
+        np.testing.assert_array_equal((out["dz"] == 0), (grad == 0))
+        np.testing.assert_array_equal(out["safe_count"], (~pruned).sum(1))
+        np.testing.assert_array_equal(out["y_in_safe"], ~pruned[np.arange(16), ids])
+    assert out["y_in_safe"][0] == 0 and np.isfinite(out["logp"][0])
+    assert np.abs(out["dz"][0]).max() > 0           # a pruned sampled token still pulls the safe logits down
+
+
+def test_finite_mask_threshold_is_rounded_to_the_logits_dtype():
+    """bf16 logits: the threshold 10 + log(1e-4) = 0.78966 is rounded to the bf16 grid point 0.7890625,
+    which then counts as safe; the exact rule (one fp32 threshold, Def. 5.1) prunes it.  The variant
+    reproduces that artefact, the main oracle does not."""
+    row = torch.tensor([[10.0, 0.7890625, 0.79296875, 0.78515625, -3.0]], dtype=torch.bfloat16)
+    lit = orc.rows_finite_mask(row, [0], math.log(1e-4), want_flags=True)
+    np.testing.assert_array_equal(lit["safe_flags"][0], [1, 1, 1, 0, 0])
+    assert lit["tau"][0] == 0.7890625
+    exact = orc.rows(row, [0], orc.log_rho_f32(1e-4), want_flags=True)
+    np.testing.assert_array_equal(exact["safe_flags"][0], [1, 0, 1, 0, 0])
+    pruned, thr, _, _ = _torch_finite_mask(row, [0], 1e-4, -50.0, [1.0])
+    np.testing.assert_array_equal(pruned[0], [False, False, False, True, True])
+    # fp32 logits: both rules agree
+    row32 = row.to(torch.float32)
+    np.testing.assert_array_equal(orc.rows_finite_mask(row32, [0], math.log(1e-4), want_flags=True)["safe_flags"],
+                                  orc.rows(row32, [0], orc.log_rho_f32(1e-4), want_flags=True)["safe_flags"])
+
+
+def test_finite_mask_converges_to_the_exact_rule():
+    """With the mask far below the row the pruned tokens' mass vanishes: log-probs and gradients of rows
+    whose sampled token is safe equal the exact -inf semantics (Prop. 5.6)."""
+    z, ids = _rand_rows(10, 400, 5)
+    ids = z.argmax(1)
+    g = np.linspace(-1, 1, 10)
+    lit = orc.rows_finite_mask(z, ids, math.log(1e-2), -745.0, grad_out=g, want_dz=True)
+    # fp64 logits: the exact oracle rounds its threshold to fp32, so compare away from the boundary
+    ex = orc.rows(z, ids, orc.log_rho_f32(1e-2), grad_out=g, want_dz=True, band=1e-5)
+    ok = ex["band_count"] == 0
+    assert ok.sum() >= 8
+    np.testing.assert_allclose(lit["logp"][ok], ex["logp"][ok], rtol=0, atol=1e-12)
+    np.testing.assert_allclose(lit["dz"][ok], ex["dz"][ok], rtol=0, atol=1e-12)
+    # a mask within reach shows the pruned tokens' mass: logp drops by log(1 + (V - c) e^{mask - lse});
+    # with the paper's -50 that is ~1e-24, below what a double can show next to an O(1) log-prob
+    lit5 = orc.rows_finite_mask(z, ids, math.log(1e-2), -5.0)
+    extra = (400 - ex["safe_count"]) * np.exp(-5.0 - ex["lse_safe"])
+    assert extra[ok].min() > 1e-5
+    np.testing.assert_allclose((ex["logp"] - lit5["logp"])[ok], np.log1p(extra)[ok], rtol=1e-9, atol=1e-13)
+    lit50 = orc.rows_finite_mask(z, ids, math.log(1e-2), -50.0)
+    np.testing.assert_allclose(lit50["logp"][ok], ex["logp"][ok], rtol=0, atol=1e-15)

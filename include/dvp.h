@@ -65,6 +65,25 @@ enum {
                                     list_cap tokens, no gradient entry was written for this row */
 };
 
+/*
+ * dvp_params.mode
+ *   DVP_MODE_EXACT        the definitions as written: pruned tokens have probability zero (Def. 5.2),
+ *                         one fp32 threshold (see dvp_side_out).  The default, and the fast path.
+ *   DVP_MODE_FINITE_MASK  the low-precision recipe of Sec. 5.5 ("Logit Masking Strategy") and App. A
+ *                         item 3, for callers that have to reproduce a run made with it: a pruned
+ *                         logit counts as the finite constant mask_value (-50 in the paper) instead
+ *                         of -inf, and the threshold m + log_rho is rounded to the logits' storage
+ *                         type (a no-op for fp32).  Then
+ *                           lse_safe = log( sum_{k safe} exp(z_k) + (V - |V_S|) exp(mask_value) ),
+ *                           logp     = (z_y if y is safe else mask_value) - lse_safe   (always finite),
+ *                           dz_k     = grad_out * ([k = y and y safe] - exp(z_k - lse_safe)) for safe k,
+ *                                      0 for pruned k: also when y itself is pruned.
+ *                         row_flags, safe_count, safe_bits report the set as before.  Runs on the
+ *                         re-reading kernels; not available for 8-bit inference logits, for the
+ *                         list output, for entropy, or in the LM-head variant.
+ */
+enum { DVP_MODE_EXACT = 0, DVP_MODE_FINITE_MASK = 1 };
+
 typedef struct {
     int64_t n_rows;   /* N >= 0 token rows */
     int64_t vocab;    /* V, 1 <= V <= DVP_MAX_VOCAB */
@@ -79,6 +98,8 @@ typedef struct {
                             low-precision rollout engines of Sec. 4.2): one byte per token, widened
                             exactly.  The single-read path takes 8-bit inference rows next to
                             bf16 training rows with V >= 16; other combinations are re-read. */
+    int32_t mode;        /* DVP_MODE_EXACT (0) or DVP_MODE_FINITE_MASK */
+    float mask_value;    /* DVP_MODE_FINITE_MASK only: finite; give a value the logits' type represents */
 } dvp_params;
 
 /*
@@ -95,6 +116,9 @@ typedef struct {
  *   safe_bits   membership bitmask, row stride ceil(V/32) words; bit (k % 32)
  *               of word k / 32 is 1 iff token k is safe; unused high bits of
  *               the last word are 0.
+ *   entropy     -sum_{k in V_S} pi^mp(k) log pi^mp(k), the entropy of the
+ *               constrained policy of Def. 5.2 (the signal Sec. 7 proposes for an
+ *               adaptive rho).  Costs one exp per token, like lse_full.
  * The safe set is { k : z_ik >= fl32(m_i + log_rho) }: one round-to-nearest
  * fp32 add, inclusive comparison (App. A, protocol item 2).
  */
@@ -105,6 +129,7 @@ typedef struct {
     float *lse_full;
     int32_t *safe_count;
     uint32_t *safe_bits;
+    float *entropy;
 } dvp_side_out;
 
 /*
@@ -211,7 +236,7 @@ size_t dvp_fused_lmhead_workspace_bytes(const dvp_lmhead_params *params);
  *   d_w       DEVICE float [V, ld_w], overwritten
  *   workspace DEVICE, 256-byte aligned, at least the size reported above;
  *             contents on entry are ignored and on exit are unspecified.
- * safe_bits members of the output structs must be NULL (not produced here).
+ * safe_bits and entropy members of the output structs must be NULL (not produced here).
  */
 dvp_status dvp_fused_lmhead(const dvp_lmhead_params *params, const void *hidden,
                             const void *w_train, const void *w_infer, const int64_t *ids,

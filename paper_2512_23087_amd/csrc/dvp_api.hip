@@ -19,6 +19,11 @@ dvp_status check_params(const dvp_params *p, bool need_infer, bool need_grad)
     if (!p) return DVP_ERR_NULL;
     if (p->dtype != DVP_F32 && p->dtype != DVP_BF16) return DVP_ERR_PARAM;
     if (need_infer && p->dtype_infer != p->dtype && p->dtype_infer != DVP_F8E4M3) return DVP_ERR_PARAM;
+    if (p->mode != DVP_MODE_EXACT && p->mode != DVP_MODE_FINITE_MASK) return DVP_ERR_PARAM;
+    if (p->mode == DVP_MODE_FINITE_MASK) {
+        if (!(p->mask_value == p->mask_value) || isinf(p->mask_value)) return DVP_ERR_PARAM;
+        if (need_infer && p->dtype_infer != p->dtype) return DVP_ERR_PARAM;   // the variant is defined per storage type
+    }
     if (p->log_rho != p->log_rho || p->log_rho > 0.0f) return DVP_ERR_PARAM;
     if (p->n_rows < 0 || p->vocab < 1 || p->vocab > DVP_MAX_VOCAB) return DVP_ERR_SHAPE;
     if (p->ld_train < p->vocab) return DVP_ERR_SHAPE;
@@ -29,10 +34,11 @@ dvp_status check_params(const dvp_params *p, bool need_infer, bool need_grad)
 
 SideOut to_side(const dvp_side_out *o)
 {
-    SideOut s = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+    SideOut s = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
     if (o) {
         s.logp = o->logp; s.row_max = o->row_max; s.lse_safe = o->lse_safe;
         s.lse_full = o->lse_full; s.safe_count = o->safe_count; s.safe_bits = o->safe_bits;
+        s.entropy = o->entropy;
     }
     return s;
 }
@@ -41,7 +47,8 @@ bool side_aligned(const dvp_side_out *o)
 {
     if (!o) return true;
     return aligned_to(o->logp, 4) && aligned_to(o->row_max, 4) && aligned_to(o->lse_safe, 4) &&
-           aligned_to(o->lse_full, 4) && aligned_to(o->safe_count, 4) && aligned_to(o->safe_bits, 4);
+           aligned_to(o->lse_full, 4) && aligned_to(o->safe_count, 4) && aligned_to(o->safe_bits, 4) &&
+           aligned_to(o->entropy, 4);
 }
 
 // the single-read kernel needs 16-byte vector access to every row
@@ -88,7 +95,10 @@ dvp_status run_rows(const dvp_params *p, const void *z_train, const void *z_infe
 
     a.sparse_only = 0;
     a.grad_len = nullptr;
-    const bool resident = dvp::row_fits_resident(p->dtype, dtype_infer, p->vocab) &&
+    a.finite_mask = p->mode == DVP_MODE_FINITE_MASK;
+    a.mask_value = p->mask_value;
+    if (a.finite_mask && (a.out[0].entropy || a.out[1].entropy)) return DVP_ERR_UNSUPPORTED;   // defined for the exact rule only
+    const bool resident = !a.finite_mask && dvp::row_fits_resident(p->dtype, dtype_infer, p->vocab) &&
                           rows_vector_ok(p, z_train, z_infer, backward ? dz : nullptr);
     // Split gradient: possible when the per-row flags and safe-set sizes are
     // produced anyway (the fill kernel reads them back).
@@ -137,6 +147,7 @@ dvp_status dvp_forward_backward_sparse(const dvp_params *params, const void *z_t
     dvp_status st = check_params(params, z_infer != nullptr, false);
     if (st != DVP_OK) return st;
     if (list_cap < 1 || list_cap > DVP_MAX_LIST_CAP) return DVP_ERR_PARAM;
+    if (params->mode != DVP_MODE_EXACT) return DVP_ERR_UNSUPPORTED;
     if (params->n_rows == 0) return DVP_OK;
     if (!z_train || !ids || !out_train || !grad_out || !row_flags || !entries) return DVP_ERR_NULL;
     const size_t es = elem_size(params->dtype);
@@ -162,6 +173,7 @@ dvp_status dvp_forward_backward_sparse(const dvp_params *params, const void *z_t
     a.n_sides = z_infer ? 2 : 1;
     a.log_rho = params->log_rho;
     a.split_grad = 1; a.list_cap = list_cap; a.sparse_only = 1; a.grad_len = grad_len;
+    a.finite_mask = 0; a.mask_value = 0.0f;
     return dvp::launch_rows_resident(params->dtype, dtype_infer, a, (hipStream_t)stream) == hipSuccess ? DVP_OK
                                                                                                      : DVP_ERR_HIP;
 }
@@ -187,6 +199,7 @@ dvp_status dvp_backward(const dvp_params *params, const void *z_train, const int
     a.row_max = row_max_train; a.lse_safe = lse_safe_train; a.row_flags = row_flags;
     a.dz = dz; a.ld_grad = params->ld_grad;
     a.n_rows = params->n_rows; a.vocab = (int32_t)params->vocab; a.log_rho = params->log_rho;
+    a.finite_mask = params->mode == DVP_MODE_FINITE_MASK;
     const bool vec = rows_vector_ok(params, z_train, nullptr, dz);
     hipError_t e = dvp::launch_backward(params->dtype, a, vec, (hipStream_t)stream);
     return e == hipSuccess ? DVP_OK : DVP_ERR_HIP;
@@ -224,6 +237,7 @@ int dvp_row_path(const dvp_params *params, int aligned16)
     const int dtype_infer = params->dtype_infer == DVP_F8E4M3 ? DVP_F8E4M3 : params->dtype;
     const bool ld_ok = (params->ld_train * es) % 16 == 0 &&
                        (dtype_infer != DVP_F8E4M3 || params->ld_infer % 16 == 0);
+    if (params->mode == DVP_MODE_FINITE_MASK) return 0;
     return (dvp::row_fits_resident(params->dtype, dtype_infer, params->vocab) && aligned16 && ld_ok) ? 1 : 0;
 }
 
@@ -240,7 +254,7 @@ const char *dvp_status_string(dvp_status status)
     case DVP_OK: return "ok";
     case DVP_ERR_NULL: return "a required pointer is NULL";
     case DVP_ERR_SHAPE: return "invalid shape or row stride";
-    case DVP_ERR_PARAM: return "invalid parameter (dtype, or log_rho is NaN or positive)";
+    case DVP_ERR_PARAM: return "invalid parameter (dtype or mode, log_rho NaN or positive, mask_value not finite)";
     case DVP_ERR_ALIGN: return "pointer not aligned to its element size";
     case DVP_ERR_UNSUPPORTED: return "shape or alignment not supported by this entry point";
     case DVP_ERR_WORKSPACE: return "workspace missing, misaligned or too small";

@@ -103,6 +103,11 @@ __device__ __forceinline__ void store_elem(bf16_t *p, float v)
     p->bits = (uint16_t)f32_to_bf16_rne(v);
 }
 
+// Threshold of the finite-mask variant: the fp32 sum rounded to the logits' storage type, as a
+// tensor-plus-scalar add in that type delivers it on a GPU (Sec. 5.5, App. A).
+__device__ __forceinline__ float storage_rounded(float t, float) { return t; }
+__device__ __forceinline__ float storage_rounded(float t, bf16_t) { return bits_to_float(f32_to_bf16_rne(t) << 16); }
+
 // ---- wavefront reductions (all 64 lanes end with the result) ----
 __device__ __forceinline__ float wave_max(float v)
 {

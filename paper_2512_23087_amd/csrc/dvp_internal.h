@@ -14,6 +14,7 @@ struct SideOut {
     float *lse_full;
     int32_t *safe_count;
     uint32_t *safe_bits;
+    float *entropy;
 };
 
 // Arguments of the row kernels.  Side 0 = training logits, side 1 = inference.
@@ -40,6 +41,10 @@ struct RowArgs {
     // ever written; rows whose safe set exceeds list_cap get DVP_ROW_GRAD_OVERFLOW.  Needs split_grad.
     int32_t sparse_only;
     int32_t *grad_len;       // [n_rows] or null: entries per row (the safe-set size, 0 when y is pruned)
+    // Finite-mask variant (re-reading kernel only): pruned logits count as mask_value instead of -inf
+    // and the threshold is rounded to the logits' storage type.
+    int32_t finite_mask;
+    float mask_value;
 };
 
 struct FillArgs {
@@ -67,6 +72,7 @@ struct BackwardArgs {
     int64_t n_rows;
     int32_t vocab;
     float log_rho;
+    int32_t finite_mask;     // see RowArgs
 };
 
 struct SequenceArgs {

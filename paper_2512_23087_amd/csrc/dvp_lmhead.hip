@@ -768,7 +768,8 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
     if (p->n_rows == 0) return DVP_OK;
     if (!hidden || !w_train || !ids || !out_train) return DVP_ERR_NULL;
     if (grad_out && (!d_hidden || !d_w)) return DVP_ERR_NULL;
-    if ((out_train && out_train->safe_bits) || ((w_infer || f8) && out_infer && out_infer->safe_bits))
+    if ((out_train && (out_train->safe_bits || out_train->entropy)) ||
+        ((w_infer || f8) && out_infer && (out_infer->safe_bits || out_infer->entropy)))
         return DVP_ERR_UNSUPPORTED;
     if (((uintptr_t)hidden | (uintptr_t)w_train | (uintptr_t)w_infer) % 16) return DVP_ERR_ALIGN;
     if (f8) {

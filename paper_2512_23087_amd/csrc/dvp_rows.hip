@@ -129,7 +129,7 @@ struct TaskState {
 //   TN / NVN / NVFULL_N   the same for the task after it, whose vectors are
 //                         loaded into the slots as this task lets go of them
 // Returns false after the workgroup's last task.
-template <typename TS, int NVS, int NVFULL_S, typename TN, int NVN, int NVFULL_N, int NV, int NT, bool EXTRAS,
+template <typename TS, int NVS, int NVFULL_S, typename TN, int NVN, int NVFULL_N, int NV, int NT, int EXTRAS,
           bool CAN_BWD>
 __device__ __forceinline__ bool row_task(const RowArgs &a, TaskState &s, u32x4 (&r)[NV], float *lds_max,
                                          float *lds_f, int *lds_i, int *lds_list_count)
@@ -186,7 +186,8 @@ __device__ __forceinline__ bool row_task(const RowArgs &a, TaskState &s, u32x4 (
     }
 
     const SideOut &out = a.out[side];
-    const bool want_full = EXTRAS && out.lse_full != nullptr;
+    const bool want_ent = EXTRAS == 2 && out.entropy != nullptr;
+    const bool want_full = EXTRAS && (out.lse_full != nullptr || want_ent);   // every exponential is taken
     uint8_t *bits_row = (EXTRAS && out.safe_bits)
         ? (uint8_t *)(out.safe_bits + row * (int64_t)bits_words) : nullptr;
     const bool bwd_here = want_bwd && side == 0;
@@ -213,6 +214,7 @@ __device__ __forceinline__ bool row_task(const RowArgs &a, TaskState &s, u32x4 (
     // ---- threshold, membership, size, masked sum (Def. 5.1 / 5.2) ----
     const float tau = m + log_rho;   // one fp32 rounding
     float s_safe = 0.0f, s_full = 0.0f;
+    float s_ent = 0.0f;              // sum over the safe set of exp(z - m) (z - m): entropy (EXTRAS builds)
     int wave_count = 0;              // wavefront-uniform: lanes are counted with scalar popcounts
     uint32_t any_mask = 0;           // bit j: some lane of this wavefront has a safe token in slot j
     if (has_next) {   // the next task's single elements, fetched early and left in stored form
@@ -224,6 +226,7 @@ __device__ __forceinline__ bool row_task(const RowArgs &a, TaskState &s, u32x4 (
         const float ex = __expf(xt - m);
         s_safe += (xt >= tau) ? ex : 0.0f;
         if (want_full) s_full += ex;
+        if (want_ent && xt >= tau && ex > 0.0f) s_ent += ex * (xt - m);   // 0 log 0 = 0 (also the -inf padding when tau = -inf)
     }
 #pragma unroll
     for (int j = 0; j < NVS; ++j) {
@@ -245,6 +248,7 @@ __device__ __forceinline__ bool row_task(const RowArgs &a, TaskState &s, u32x4 (
                     const float ex = __expf(x[e] - m);
                     s_full += ex;
                     s_safe += (x[e] >= tau) ? ex : 0.0f;
+                    if (want_ent) s_ent += (x[e] >= tau && ex > 0.0f) ? ex * (x[e] - m) : 0.0f;
                 }
             } else if (any_part) {   // wavefront-uniform: all-pruned vectors cost no exp
 #pragma unroll
@@ -282,18 +286,22 @@ __device__ __forceinline__ bool row_task(const RowArgs &a, TaskState &s, u32x4 (
     }
     s_safe = wave_sum(s_safe);
     if (want_full) s_full = wave_sum(s_full);
+    if (want_ent) s_ent = wave_sum(s_ent);
     if ((tid & (kWave - 1)) == 0) {
         const int w = tid / kWave;
         lds_f[w] = s_safe;
         lds_f[NW + w] = s_full;
+        if (EXTRAS == 2) lds_f[2 * NW + w] = s_ent;
         lds_i[w] = wave_count;
     }
     __syncthreads();
     RowSums acc = {lds_f[0], lds_f[NW], lds_i[0]};
+    float ent_sum = EXTRAS == 2 ? lds_f[2 * NW] : 0.0f;
 #pragma unroll
     for (int w = 1; w < NW; ++w) {   // fixed order: results are run-to-run identical
         acc.s_safe += lds_f[w];
         acc.s_full += lds_f[NW + w];
+        if (EXTRAS == 2) ent_sum += lds_f[2 * NW + w];
         acc.count += lds_i[w];
     }
     if (tau == -INFINITY) acc.count = V;   // nothing pruned; do not count the -inf padding
@@ -308,7 +316,9 @@ __device__ __forceinline__ bool row_task(const RowArgs &a, TaskState &s, u32x4 (
         if (bwd_here && a.grad_len) a.grad_len[row] = y_safe ? acc.count : 0;
         if (out.row_max) out.row_max[row] = m;
         if (out.lse_safe) out.lse_safe[row] = m + log_s;
-        if (want_full) out.lse_full[row] = m + logf(acc.s_full);
+        if (EXTRAS && out.lse_full) out.lse_full[row] = m + logf(acc.s_full);
+        // H = -sum pi log pi with log pi = (z - m) - log S  =>  H = log S - (sum e^{z-m} (z-m)) / S
+        if (want_ent) out.entropy[row] = log_s - ent_sum / acc.s_safe;
         if (out.safe_count) out.safe_count[row] = acc.count;
         if (out.logp)
             out.logp[row] = !y_ok ? __uint_as_float(0x7fc00000u)
@@ -384,15 +394,15 @@ __device__ __forceinline__ bool row_task(const RowArgs &a, TaskState &s, u32x4 (
 // registers, each freed slot is refilled with the next task's vector, so the
 // CU keeps loads in flight while it computes.  The ragged end of a row (fewer
 // than one vector) is held one element per thread in threads 0..tail-1.
-// EXTRAS builds also produce lse_full and the membership bitmask.
-template <typename T, int NV, int NVFULL, int NT, int MINW, bool EXTRAS>
+// EXTRAS builds also produce lse_full and the membership bitmask (1), and the entropy on top (2).
+template <typename T, int NV, int NVFULL, int NT, int MINW, int EXTRAS>
 __global__ __launch_bounds__(NT, MINW) void rows_resident_kernel(const RowArgs a)
 {
     using TR = elem_traits<T>;
     constexpr int EPV = TR::kPerVec;
     constexpr int NW = NT / kWave;
     __shared__ float lds_max[NW];
-    __shared__ float lds_f[2 * NW];
+    __shared__ float lds_f[3 * NW];
     __shared__ int lds_i[NW];
     __shared__ int lds_list_count;
 
@@ -426,14 +436,14 @@ __global__ __launch_bounds__(NT, MINW) void rows_resident_kernel(const RowArgs a
 // The same walk when the inference logits are stored as 8-bit E4M3 codes: an
 // inference row then takes half the register slots of a training row and half
 // the HBM bytes.  Always two sides; tasks alternate between the two types.
-template <typename T, int NV, int NVFULL, int NT, int MINW, bool EXTRAS>
+template <typename T, int NV, int NVFULL, int NT, int MINW, int EXTRAS>
 __global__ __launch_bounds__(NT, MINW) void rows_resident_f8infer_kernel(const RowArgs a)
 {
     constexpr int NVI = (NV + 1) / 2, NVFULL_I = NVFULL / 2;
     constexpr int EPV_I = elem_traits<f8_t>::kPerVec;
     constexpr int NW = NT / kWave;
     __shared__ float lds_max[NW];
-    __shared__ float lds_f[2 * NW];
+    __shared__ float lds_f[3 * NW];
     __shared__ int lds_i[NW];
     __shared__ int lds_list_count;
 
@@ -497,7 +507,8 @@ __global__ __launch_bounds__(NT) void rows_streaming_kernel(const RowArgs a)
             const TI *zrow_i = (const TI *)a.z[1] + (side == 1 ? row * a.ld[1] : 0);
             auto logit = [&](int64_t k) { return side == 1 ? load_elem(zrow_i + k) : load_elem(zrow + k); };
             const SideOut &out = a.out[side];
-            const bool want_full = out.lse_full != nullptr;
+            const bool want_ent = out.entropy != nullptr;
+            const bool want_full = out.lse_full != nullptr || want_ent;
             uint32_t *bits_row = out.safe_bits ? out.safe_bits + row * (int64_t)bits_words : nullptr;
             const float zy = y_ok ? logit(y) : 0.0f;
 
@@ -505,8 +516,10 @@ __global__ __launch_bounds__(NT) void rows_streaming_kernel(const RowArgs a)
             for (int k = tid; k < V; k += NT) m = fmaxf(m, logit(k));
             m = block_max<NT>(m, lds_max);
 
-            const float tau = m + log_rho;
+            float tau = m + log_rho;
+            if (a.finite_mask) tau = storage_rounded(tau, T());   // both sides share T in that variant
             RowSums acc = {0.0f, 0.0f, 0};
+            float s_ent = 0.0f;
             for (int k = tid; k < v_round; k += NT) {   // uniform trip count: ballot below needs every lane
                 const bool in = k < V;
                 const float x = in ? logit(k) : -INFINITY;
@@ -516,6 +529,7 @@ __global__ __launch_bounds__(NT) void rows_streaming_kernel(const RowArgs a)
                     const float ex = in ? __expf(x - m) : 0.0f;
                     acc.s_full += ex;
                     acc.s_safe += safe ? ex : 0.0f;
+                    if (want_ent && safe && ex > 0.0f) s_ent += ex * (x - m);   // 0 log 0 = 0
                 } else if (safe) {
                     acc.s_safe += __expf(x - m);
                 }
@@ -529,28 +543,48 @@ __global__ __launch_bounds__(NT) void rows_streaming_kernel(const RowArgs a)
                 }
             }
             acc = block_sums<NT>(acc, lds_f, lds_i);
+            float ent_sum = 0.0f;
+            if (want_ent) {      // workgroup-uniform; lds_max is free again (a barrier has passed since its reads)
+                s_ent = wave_sum(s_ent);
+                if ((tid & (kWave - 1)) == 0) lds_max[tid / kWave] = s_ent;
+                __syncthreads();
+#pragma unroll
+                for (int w = 0; w < NW; ++w) ent_sum += lds_max[w];
+                __syncthreads();
+            }
 
-            const float log_s = logf(acc.s_safe);
+            // Exact rule: log S over the safe set.  Finite-mask variant (Sec. 5.5): every pruned token
+            // also counts, with the logit mask_value; sums are rebased to ref = max(m, mask_value).
+            float ref = m, log_s = logf(acc.s_safe);
+            if (a.finite_mask) {
+                ref = fmaxf(m, a.mask_value);
+                log_s = logf(acc.s_safe * __expf(m - ref) + (float)(V - acc.count) * __expf(a.mask_value - ref));
+            }
             const bool y_safe = y_ok && (zy >= tau);
             if (y_safe) flags |= (side == 0 ? DVP_ROW_Y_IN_TRAIN_SAFE : DVP_ROW_Y_IN_INFER_SAFE);
             if (tid == 0) {
                 if (out.row_max) out.row_max[row] = m;
-                if (out.lse_safe) out.lse_safe[row] = m + log_s;
+                if (out.lse_safe) out.lse_safe[row] = ref + log_s;
                 if (out.lse_full) out.lse_full[row] = m + logf(acc.s_full);
+                if (want_ent) out.entropy[row] = log_s - ent_sum / acc.s_safe;
                 if (out.safe_count) out.safe_count[row] = acc.count;
-                if (out.logp)
-                    out.logp[row] = !y_ok ? __uint_as_float(0x7fc00000u)
-                                          : (y_safe ? (zy - m) - log_s : -INFINITY);
+                if (out.logp) {
+                    float lp = y_safe ? (zy - ref) - log_s : -INFINITY;
+                    if (a.finite_mask && !y_safe) lp = (a.mask_value - ref) - log_s;   // finite: the mask's own log-prob
+                    out.logp[row] = !y_ok ? __uint_as_float(0x7fc00000u) : lp;
+                }
             }
 
             if (side == 0 && want_bwd) {
                 T *dzrow = (T *)a.dz + row * a.ld_grad;
                 const float g = a.grad_out[row];
+                // finite-mask variant: a pruned sampled token still pushes the safe logits down
+                const bool grad_row = a.finite_mask ? y_ok : y_safe;
                 for (int k = tid; k < V; k += NT) {
                     const float x = load_elem(zrow + k);
                     float d = 0.0f;
-                    if (y_safe && x >= tau) {
-                        const float p = __expf((x - m) - log_s);
+                    if (grad_row && x >= tau) {
+                        const float p = __expf((x - ref) - log_s);
                         d = g * (((int64_t)k == y ? 1.0f : 0.0f) - p);
                     }
                     store_elem(dzrow + k, d);
@@ -578,10 +612,13 @@ __global__ __launch_bounds__(NT) void backward_kernel(const BackwardArgs a)
         T *dzrow = (T *)a.dz + row * a.ld_grad;
         const float m = a.row_max[row];
         const float log_s = a.lse_safe[row] - m;
-        const float tau = m + a.log_rho;      // same fp32 add as the forward
+        float tau = m + a.log_rho;            // same fp32 add as the forward
+        if (a.finite_mask) tau = storage_rounded(tau, T());
         const float g = a.grad_out[row];
         const int64_t y = a.ids[row];
-        const bool y_safe = (a.row_flags[row] & DVP_ROW_Y_IN_TRAIN_SAFE) != 0;
+        // "gradient row": the sampled token is safe; in the finite-mask variant, any id in range
+        const bool y_safe = a.finite_mask ? (a.row_flags[row] & DVP_ROW_ID_OUT_OF_RANGE) == 0
+                                          : (a.row_flags[row] & DVP_ROW_Y_IN_TRAIN_SAFE) != 0;
         int k_scalar = 0;
         if constexpr (VEC) {
             const int nvec = V / EPV;
@@ -727,7 +764,7 @@ static int blocks_per_cu(Kernel k, int threads)
     return nb;
 }
 
-template <typename T, bool F8_INFER, int NV, int NVFULL, int NT, int MINW, bool EXTRAS>
+template <typename T, bool F8_INFER, int NV, int NVFULL, int NT, int MINW, int EXTRAS>
 static hipError_t launch_resident_inst(const RowArgs &a, hipStream_t stream)
 {
     void (*kernel)(const RowArgs);
@@ -745,7 +782,7 @@ static hipError_t launch_resident_inst(const RowArgs &a, hipStream_t stream)
 // groups for short rows (several groups share a CU), 1024-thread groups for
 // long rows (one group owns the CU's register file).  Each build covers row
 // lengths from its NVFULL (exclusive) to its NV (inclusive) slots per thread.
-template <typename T, bool F8_INFER, bool EXTRAS>
+template <typename T, bool F8_INFER, int EXTRAS>
 static hipError_t launch_resident_t(const RowArgs &a, hipStream_t stream)
 {
     const int epv = elem_traits<T>::kPerVec;
@@ -771,15 +808,20 @@ bool row_fits_resident(int dtype, int dtype_infer, int64_t vocab)
 hipError_t launch_rows_resident(int dtype, int dtype_infer, const RowArgs &a, hipStream_t stream)
 {
     if (a.n_rows == 0) return hipSuccess;
-    const bool extras = a.out[0].lse_full || a.out[0].safe_bits ||
-                        (a.n_sides == 2 && (a.out[1].lse_full || a.out[1].safe_bits));
-    if (a.n_sides == 2 && dtype_infer == DVP_F8E4M3) {
+    const bool two = a.n_sides == 2;
+    const bool ent = a.out[0].entropy || (two && a.out[1].entropy);
+    const bool extras = a.out[0].lse_full || a.out[0].safe_bits || (two && (a.out[1].lse_full || a.out[1].safe_bits));
+    const int level = ent ? 2 : (extras ? 1 : 0);
+    if (two && dtype_infer == DVP_F8E4M3) {
         if (dtype != DVP_BF16) return hipErrorInvalidValue;
-        return extras ? launch_resident_t<bf16_t, true, true>(a, stream) : launch_resident_t<bf16_t, true, false>(a, stream);
+        return level == 2 ? launch_resident_t<bf16_t, true, 2>(a, stream)
+             : level == 1 ? launch_resident_t<bf16_t, true, 1>(a, stream) : launch_resident_t<bf16_t, true, 0>(a, stream);
     }
     if (dtype == DVP_BF16)
-        return extras ? launch_resident_t<bf16_t, false, true>(a, stream) : launch_resident_t<bf16_t, false, false>(a, stream);
-    return extras ? launch_resident_t<float, false, true>(a, stream) : launch_resident_t<float, false, false>(a, stream);
+        return level == 2 ? launch_resident_t<bf16_t, false, 2>(a, stream)
+             : level == 1 ? launch_resident_t<bf16_t, false, 1>(a, stream) : launch_resident_t<bf16_t, false, 0>(a, stream);
+    return level == 2 ? launch_resident_t<float, false, 2>(a, stream)
+         : level == 1 ? launch_resident_t<float, false, 1>(a, stream) : launch_resident_t<float, false, 0>(a, stream);
 }
 
 hipError_t launch_grad_fill(int dtype, const FillArgs &a, hipStream_t stream)

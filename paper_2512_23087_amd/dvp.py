@@ -30,13 +30,15 @@ class DvpParams(ctypes.Structure):
     _fields_ = [("n_rows", ctypes.c_int64), ("vocab", ctypes.c_int64),
                 ("ld_train", ctypes.c_int64), ("ld_infer", ctypes.c_int64),
                 ("ld_grad", ctypes.c_int64), ("dtype", ctypes.c_int32),
-                ("log_rho", ctypes.c_float), ("dtype_infer", ctypes.c_int32)]
+                ("log_rho", ctypes.c_float), ("dtype_infer", ctypes.c_int32),
+                ("mode", ctypes.c_int32), ("mask_value", ctypes.c_float)]
 
 
 class DvpSideOut(ctypes.Structure):
     _fields_ = [("logp", ctypes.c_void_p), ("row_max", ctypes.c_void_p),
                 ("lse_safe", ctypes.c_void_p), ("lse_full", ctypes.c_void_p),
-                ("safe_count", ctypes.c_void_p), ("safe_bits", ctypes.c_void_p)]
+                ("safe_count", ctypes.c_void_p), ("safe_bits", ctypes.c_void_p),
+                ("entropy", ctypes.c_void_p)]
 
 
 class DvpLmHeadParams(ctypes.Structure):
@@ -156,7 +158,7 @@ def _check_rows(z: torch.Tensor, name: str):
 class SideOutputs:
     """Device buffers for one side's per-row outputs."""
 
-    def __init__(self, n, vocab, device, lse_full=False, safe_bits=False):
+    def __init__(self, n, vocab, device, lse_full=False, safe_bits=False, entropy=False):
         self.logp = torch.empty(n, dtype=torch.float32, device=device)
         self.row_max = torch.empty(n, dtype=torch.float32, device=device)
         self.lse_safe = torch.empty(n, dtype=torch.float32, device=device)
@@ -164,11 +166,12 @@ class SideOutputs:
         self.safe_count = torch.empty(n, dtype=torch.int32, device=device)
         self.safe_bits = (torch.empty(n, (vocab + 31) // 32, dtype=torch.int32, device=device)
                           if safe_bits else None)
+        self.entropy = torch.empty(n, dtype=torch.float32, device=device) if entropy else None
 
     def struct(self) -> DvpSideOut:
         return DvpSideOut(*(None if t is None else t.data_ptr() for t in
                             (self.logp, self.row_max, self.lse_safe, self.lse_full,
-                             self.safe_count, self.safe_bits)))
+                             self.safe_count, self.safe_bits, self.entropy)))
 
     def flags_matrix(self, vocab) -> torch.Tensor:
         """Expand safe_bits to a uint8 [N, V] matrix (test helper; torch ops)."""
@@ -183,25 +186,31 @@ class RowResult:
         self.train, self.infer, self.row_flags, self.dz = train, infer, row_flags, dz
 
 
-def _params(z_train, z_infer, dz, log_rho_value) -> DvpParams:
+DVP_MODE_EXACT, DVP_MODE_FINITE_MASK = 0, 1
+
+
+def _params(z_train, z_infer, dz, log_rho_value, mask_value=None) -> DvpParams:
+    """mask_value not None selects the finite-mask variant (pruned logits count as that constant)."""
     return DvpParams(z_train.shape[0], z_train.shape[1], z_train.stride(0),
                      z_infer.stride(0) if z_infer is not None else 0,
                      dz.stride(0) if dz is not None else 0,
-                     _dtype_code(z_train), float(log_rho_value), _infer_dtype_code(z_train, z_infer))
+                     _dtype_code(z_train), float(log_rho_value), _infer_dtype_code(z_train, z_infer),
+                     DVP_MODE_EXACT if mask_value is None else DVP_MODE_FINITE_MASK,
+                     0.0 if mask_value is None else float(mask_value))
 
 
-def dvp_forward(z_train, z_infer, ids, log_rho_value, *, lse_full=False, safe_bits=False,
+def dvp_forward(z_train, z_infer, ids, log_rho_value, *, lse_full=False, safe_bits=False, entropy=False,
                 out_train: Optional[SideOutputs] = None, out_infer: Optional[SideOutputs] = None,
-                row_flags: Optional[torch.Tensor] = None, stream=None) -> RowResult:
+                row_flags: Optional[torch.Tensor] = None, stream=None, mask_value=None) -> RowResult:
     _check_pair(z_train, z_infer)
     n, v = z_train.shape
     dev = z_train.device
-    out_train = out_train or SideOutputs(n, v, dev, lse_full, safe_bits)
+    out_train = out_train or SideOutputs(n, v, dev, lse_full, safe_bits, entropy)
     if z_infer is not None:
-        out_infer = out_infer or SideOutputs(n, v, dev, lse_full, safe_bits)
+        out_infer = out_infer or SideOutputs(n, v, dev, lse_full, safe_bits, entropy)
     if row_flags is None:
         row_flags = torch.empty(n, dtype=torch.uint8, device=dev)
-    p = _params(z_train, z_infer, None, log_rho_value)
+    p = _params(z_train, z_infer, None, log_rho_value, mask_value)
     st = lib().dvp_forward(ctypes.byref(p), _ptr(z_train), _ptr(z_infer), _ptr(ids),
                            ctypes.byref(out_train.struct()),
                            ctypes.byref(out_infer.struct()) if out_infer is not None else None,
@@ -212,11 +221,11 @@ def dvp_forward(z_train, z_infer, ids, log_rho_value, *, lse_full=False, safe_bi
 
 
 def dvp_backward(z_train, ids, grad_out, row_max_train, lse_safe_train, row_flags, log_rho_value,
-                 *, dz: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+                 *, dz: Optional[torch.Tensor] = None, stream=None, mask_value=None) -> torch.Tensor:
     _check_rows(z_train, "z_train")
     if dz is None:
         dz = torch.empty_like(z_train)
-    p = _params(z_train, None, dz, log_rho_value)
+    p = _params(z_train, None, dz, log_rho_value, mask_value)
     st = lib().dvp_backward(ctypes.byref(p), _ptr(z_train), _ptr(ids), _ptr(grad_out),
                             _ptr(row_max_train), _ptr(lse_safe_train), _ptr(row_flags), _ptr(dz),
                             _stream(stream))
@@ -226,21 +235,21 @@ def dvp_backward(z_train, ids, grad_out, row_max_train, lse_safe_train, row_flag
 
 
 def dvp_forward_backward(z_train, z_infer, ids, grad_out, log_rho_value, *, lse_full=False,
-                         safe_bits=False, out_train: Optional[SideOutputs] = None,
+                         safe_bits=False, entropy=False, out_train: Optional[SideOutputs] = None,
                          out_infer: Optional[SideOutputs] = None,
                          row_flags: Optional[torch.Tensor] = None,
-                         dz: Optional[torch.Tensor] = None, stream=None) -> RowResult:
+                         dz: Optional[torch.Tensor] = None, stream=None, mask_value=None) -> RowResult:
     _check_pair(z_train, z_infer)
     n, v = z_train.shape
     dev = z_train.device
-    out_train = out_train or SideOutputs(n, v, dev, lse_full, safe_bits)
+    out_train = out_train or SideOutputs(n, v, dev, lse_full, safe_bits, entropy)
     if z_infer is not None:
-        out_infer = out_infer or SideOutputs(n, v, dev, lse_full, safe_bits)
+        out_infer = out_infer or SideOutputs(n, v, dev, lse_full, safe_bits, entropy)
     if row_flags is None:
         row_flags = torch.empty(n, dtype=torch.uint8, device=dev)
     if dz is None:
         dz = torch.empty_like(z_train)
-    p = _params(z_train, z_infer, dz, log_rho_value)
+    p = _params(z_train, z_infer, dz, log_rho_value, mask_value)
     st = lib().dvp_forward_backward(ctypes.byref(p), _ptr(z_train), _ptr(z_infer), _ptr(ids),
                                     _ptr(grad_out), ctypes.byref(out_train.struct()),
                                     ctypes.byref(out_infer.struct()) if out_infer is not None else None,

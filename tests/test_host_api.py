@@ -45,7 +45,8 @@ def test_argument_validation_needs_no_gpu():
     def P(**kw):
         d = dict(ok); d.update(kw)
         return dvp.DvpParams(d["n_rows"], d["vocab"], d["ld_train"], d["ld_infer"], d["ld_grad"],
-                             d["dtype"], d["log_rho"], d.get("dtype_infer", d["dtype"]))
+                             d["dtype"], d["log_rho"], d.get("dtype_infer", d["dtype"]), d.get("mode", 0),
+                             d.get("mask_value", 0.0))
 
     assert _fwd(P()) == 0                                   # zero rows: nothing to do
     assert _fwd(P(), z_train=None, ids=None) == 0           # ... and no pointer is looked at
@@ -61,6 +62,10 @@ def test_argument_validation_needs_no_gpu():
     assert _fwd(P(vocab=2 ** 31 - 2 ** 16 + 1, ld_train=2 ** 31, ld_infer=2 ** 31)) == 2
     assert _fwd(P(vocab=2 ** 31 - 2 ** 16, ld_train=2 ** 31, ld_infer=2 ** 31)) == 0
     assert _fwd(P(dtype=7)) == 3
+    assert _fwd(P(mode=1, mask_value=-50.0)) == 0 and _fwd(P(mode=2)) == 3
+    assert _fwd(P(mode=1, mask_value=float("nan"))) == 3 and _fwd(P(mode=1, mask_value=-math.inf)) == 3
+    assert _fwd(P(mode=1, mask_value=-50.0, dtype_infer=2)) == 3   # no storage arithmetic to round the threshold in
+    assert _fwd(P(mode=0, mask_value=float("nan"))) == 0          # ignored by the exact rule
     assert _fwd(P(dtype=2)) == 3                            # 8-bit logits are an inference-side format only
     assert _fwd(P(dtype=1, dtype_infer=0)) == 3             # the two sides differ only by the 8-bit case
     assert _fwd(P(dtype=1, dtype_infer=2)) == 0 and _fwd(P(dtype=0, dtype_infer=2)) == 0
@@ -100,6 +105,8 @@ def test_row_path_selection():
     assert path(7, 1) == 0 and path(8, 1, ld=8) == 1               # shorter than one vector
     assert path(3, 0) == 0 and path(4, 0) == 1
     assert path(0, 1) == -1
+    p = dvp.DvpParams(4, 32000, 32000, 32000, 32000, 1, -1.0, 1, 1, -50.0)
+    assert L.dvp_row_path(ctypes.byref(p), 1) == 0                # the finite-mask variant is re-read
     # 8-bit inference rows: single-read next to bf16 training rows of at least one 16-token vector
     assert path(151936, 1, dtype_infer=2) == 1 and path(32000, 1, dtype_infer=2) == 1
     assert path(32008, 1, dtype_infer=2) == 0                  # 32008 bytes per inference row: not 16-byte aligned

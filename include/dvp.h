@@ -17,9 +17,12 @@
  *     shapes, parameters, launch failures).  Conditions only the device can
  *     see (a sampled id outside [0, V)) are reported per row in `row_flags`.
  *   - Matrices are row-major with a row stride `ld*` given in ELEMENTS.  When
- *     base pointers and row strides (in bytes) are 16-byte aligned and the row
- *     fits the register file (V <= 163840 for bf16, 81920 for fp32) the rows are
- *     read from HBM exactly once; otherwise a slower re-reading path is used.
+ *     base pointers and row strides (in bytes) are 16-byte aligned the rows are
+ *     held in the register file while they are worked on and HBM sees every
+ *     logit exactly once (V <= 163840 for bf16, 81920 for fp32); of a longer
+ *     row the first 131072 bf16 / 65536 fp32 logits are held and the rest is
+ *     read again per phase (max, sums, gradient), normally from the last-level
+ *     cache.  Unaligned rows take a slower path that re-reads whole rows.
  *   - Outputs are overwritten, never accumulated into.
  *   - With n_rows == 0 (and otherwise valid params) every entry point returns
  *     DVP_OK without looking at any pointer.
@@ -96,8 +99,9 @@ typedef struct {
     int32_t dtype_infer; /* dvp_dtype of z_infer (ignored when z_infer is NULL): the same as `dtype`,
                             or DVP_F8E4M3 when the inference engine hands over 8-bit logits (the
                             low-precision rollout engines of Sec. 4.2): one byte per token, widened
-                            exactly.  The single-read path takes 8-bit inference rows next to
-                            bf16 training rows with V >= 16; other combinations are re-read. */
+                            exactly.  The register-resident path takes 8-bit inference rows next
+                            to bf16 training rows with 16 <= V <= 163840; other combinations are
+                            re-read. */
     int32_t mode;        /* DVP_MODE_EXACT (0) or DVP_MODE_FINITE_MASK */
     float mask_value;    /* DVP_MODE_FINITE_MASK only: finite; give a value the logits' type represents */
 } dvp_params;
@@ -186,8 +190,8 @@ dvp_status dvp_forward_backward(const dvp_params *params, const void *z_train,
  *             DVP_ROW_GRAD_OVERFLOW in row_flags and no entries (grad_len still
  *             reports |V_S|); the caller can run dvp_backward on those rows.
  *   row_flags is required.  params->ld_grad is ignored.
- * Only the single-read path takes this call: 16-byte aligned rows that fit the
- * register file (see the conventions above), else DVP_ERR_UNSUPPORTED.
+ * Only the register-resident path takes this call: 16-byte aligned rows (see
+ * the conventions above), else DVP_ERR_UNSUPPORTED.
  */
 typedef struct {
     uint32_t index;
@@ -312,7 +316,7 @@ float dvp_log_rho(double rho);
 const char *dvp_status_string(dvp_status status);
 
 /* Which row kernel a call with these params and these alignments would use:
- * 1 = register-resident single-read path, 0 = re-reading path, -1 = invalid.
+ * 1 = register-resident path, 0 = re-reading path, -1 = invalid.
  * `aligned16` says whether all base pointers are 16-byte aligned. */
 int dvp_row_path(const dvp_params *params, int aligned16);
 

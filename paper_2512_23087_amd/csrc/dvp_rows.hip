@@ -129,8 +129,11 @@ struct TaskState {
 //   TN / NVN / NVFULL_N   the same for the task after it, whose vectors are
 //                         loaded into the slots as this task lets go of them
 // Returns false after the workgroup's last task.
+//   OVF                   the row is longer than the slots hold: vectors from NT * NVS on are
+//                         re-read from memory in every phase (all slots are then full, and both
+//                         tasks have the same type)
 template <typename TS, int NVS, int NVFULL_S, typename TN, int NVN, int NVFULL_N, int NV, int NT, int EXTRAS,
-          bool CAN_BWD>
+          bool CAN_BWD, bool OVF = false>
 __device__ __forceinline__ bool row_task(const RowArgs &a, TaskState &s, u32x4 (&r)[NV], float *lds_max,
                                          float *lds_f, int *lds_i, int *lds_list_count)
 {
@@ -142,6 +145,9 @@ __device__ __forceinline__ bool row_task(const RowArgs &a, TaskState &s, u32x4 (
     constexpr int NW = NT / kWave;
     static_assert(NVS <= NV && NVN <= NV, "slots");
     static_assert(!CAN_BWD || PARTS == 1, "gradient rows are widened whole");
+    static_assert(!OVF || (PARTS == 1 && NVFULL_S == NVS && NVS == NVN), "overflow builds: full slots, one type");
+    constexpr int FIRST_OVF = NT * NVS;    // first vector that lives outside the registers (OVF)
+    constexpr int OVF_BATCH = 4;           // vectors a thread has in flight while it walks that part
 
     const int tid = threadIdx.x;
     const int V = a.vocab;
@@ -191,6 +197,12 @@ __device__ __forceinline__ bool row_task(const RowArgs &a, TaskState &s, u32x4 (
     uint8_t *bits_row = (EXTRAS && out.safe_bits)
         ? (uint8_t *)(out.safe_bits + row * (int64_t)bits_words) : nullptr;
     const bool bwd_here = want_bwd && side == 0;
+    // OVF: the part of the row beyond the slots; the vector after the last whole one takes part in the
+    // uniform loops when it has to carry the ragged end's membership bits
+    const u32x4 *zovf = (const u32x4 *)((const TS *)a.z[side] + row * a.ld[side]) + FIRST_OVF;
+    const int novf = OVF ? nvec - FIRST_OVF : 0;
+    const int novf_round = (novf + (tail ? 1 : 0) + NT * OVF_BATCH - 1) / (NT * OVF_BATCH) * (NT * OVF_BATCH);
+    const u32x4 pad_vec = {TR::kPadWord, TR::kPadWord, TR::kPadWord, TR::kPadWord};
 
     // ---- row maximum (Def. 5.1) ----
     float m = xt;
@@ -202,6 +214,21 @@ __device__ __forceinline__ bool row_task(const RowArgs &a, TaskState &s, u32x4 (
             unpack_part<TS, NT, NVFULL_S>(r[j], x, part, j, tid, nvec);
 #pragma unroll
             for (int e = 0; e < EPP; ++e) m = fmaxf(m, x[e]);
+        }
+    }
+    if constexpr (OVF) {
+        for (int q0 = tid; q0 < novf_round; q0 += NT * OVF_BATCH) {
+            u32x4 v[OVF_BATCH];
+#pragma unroll
+            for (int u = 0; u < OVF_BATCH; ++u)    // plain loads: these lines are read again in the next phase
+                v[u] = q0 + u * NT < novf ? zovf[q0 + u * NT] : pad_vec;
+#pragma unroll
+            for (int u = 0; u < OVF_BATCH; ++u) {
+                float x[EPV];
+                unpack(v[u], x, TS());
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) m = fmaxf(m, x[e]);
+            }
         }
     }
     m = block_max<NT>(m, lds_max);
@@ -283,6 +310,53 @@ __device__ __forceinline__ bool row_task(const RowArgs &a, TaskState &s, u32x4 (
         // a slot the gradient phase will not read again (no safe token in this
         // wavefront's part of it) is refilled right away
         if (j < NVN && has_next && (!bwd_here || !any)) r[j] = load_slot<TN, NT, NVFULL_N>(znext, j, fresh(tid), nvec_n);
+    }
+    if constexpr (OVF) {
+        for (int q0 = tid; q0 < novf_round; q0 += NT * OVF_BATCH) {   // uniform trip count: the ballots need every lane
+            u32x4 v[OVF_BATCH];
+#pragma unroll
+            for (int u = 0; u < OVF_BATCH; ++u) v[u] = q0 + u * NT < novf ? zovf[q0 + u * NT] : pad_vec;
+#pragma unroll
+            for (int u = 0; u < OVF_BATCH; ++u) {
+                const int idx = FIRST_OVF + q0 + u * NT;
+                float x[EPV];
+                unpack(v[u], x, TS());
+                const int before = wave_count;
+#pragma unroll
+                for (int e = 0; e < EPV; ++e)
+                    wave_count += __builtin_popcountll(__builtin_amdgcn_ballot_w64(x[e] >= tau));
+                if (want_full) {
+#pragma unroll
+                    for (int e = 0; e < EPV; ++e) {
+                        const float ex = __expf(x[e] - m);
+                        s_full += ex;
+                        s_safe += (x[e] >= tau) ? ex : 0.0f;
+                        if (want_ent) s_ent += (x[e] >= tau && ex > 0.0f) ? ex * (x[e] - m) : 0.0f;
+                    }
+                } else if (wave_count != before) {
+#pragma unroll
+                    for (int e = 0; e < EPV; ++e) s_safe += (x[e] >= tau) ? __expf(x[e] - m) : 0.0f;
+                }
+                if (EXTRAS && bits_row) {
+                    if (idx == nvec && tail) {
+                        const TS *zrow = (const TS *)a.z[side] + row * a.ld[side] + (int64_t)nvec * EPV;
+#pragma unroll
+                        for (int e = 0; e < EPV; ++e) x[e] = e < tail ? load_elem(zrow + e) : -INFINITY;
+                    }
+                    uint32_t mask = 0;
+#pragma unroll
+                    for (int e = 0; e < EPV; ++e) mask |= (x[e] >= tau ? 1u : 0u) << e;
+                    mask &= idx < nvec ? ((1u << EPV) - 1u) : (idx == nvec ? (1u << tail) - 1u : 0u);
+                    if constexpr (EPV == 8) {
+                        if (idx < 4 * bits_words) bits_row[idx] = (uint8_t)mask;
+                    } else {
+                        const uint32_t other = __shfl_xor(mask, 1, kWave);
+                        if (!(idx & 1) && (idx >> 1) < 4 * bits_words)
+                            bits_row[idx >> 1] = (uint8_t)(mask | (other << 4));
+                    }
+                }
+            }
+        }
     }
     s_safe = wave_sum(s_safe);
     if (want_full) s_full = wave_sum(s_full);
@@ -379,6 +453,48 @@ __device__ __forceinline__ bool row_task(const RowArgs &a, TaskState &s, u32x4 (
             if (!listed && dense_out && (j < NVFULL_S || idx < nvec)) __builtin_nontemporal_store(o, dzvec + idx);
             if (j < NVN && has_next && ((any_mask >> j) & 1u)) r[j] = load_slot<TN, NT, NVFULL_N>(znext, j, t, nvec_n);
         }
+        if constexpr (OVF) {
+            // the part beyond the slots, read once more; a listed row without gradient has nothing to add
+            if (!listed || grad_row) {
+                for (int q0 = t; q0 < novf_round; q0 += NT * OVF_BATCH) {
+                    u32x4 v[OVF_BATCH];
+#pragma unroll
+                    for (int u = 0; u < OVF_BATCH; ++u)
+                        v[u] = (grad_row && q0 + u * NT < novf) ? zovf[q0 + u * NT] : pad_vec;
+#pragma unroll
+                    for (int u = 0; u < OVF_BATCH; ++u) {
+                        const int idx = FIRST_OVF + q0 + u * NT;
+                        const bool in = q0 + u * NT < novf;
+                        u32x4 o = {0u, 0u, 0u, 0u};
+                        float x[EPV], d[EPV];
+                        unpack(v[u], x, TS());
+                        bool mine = false;
+#pragma unroll
+                        for (int e = 0; e < EPV; ++e) mine |= x[e] >= tau;
+                        mine &= in && grad_row;                 // (padding passes a -inf threshold)
+                        if (__builtin_amdgcn_ballot_w64(mine) != 0) {
+#pragma unroll
+                            for (int e = 0; e < EPV; ++e)
+                                d[e] = (mine && x[e] >= tau) ? neg_g * __expf((x[e] - m) - log_s) : 0.0f;
+                            if ((int64_t)idx == y_slot) {
+                                const int ey = (int)(y - (int64_t)idx * EPV);
+#pragma unroll
+                                for (int e = 0; e < EPV; ++e)
+                                    if (e == ey) d[e] -= neg_g;
+                            }
+                            if (listed) {
+#pragma unroll
+                                for (int e = 0; e < EPV; ++e)
+                                    list_append(list, lds_list_count, mine && x[e] >= tau, (uint32_t)(idx * EPV + e), d[e]);
+                            } else {
+                                o = pack_grad(d, TS());
+                            }
+                        }
+                        if (!listed && dense_out && in) __builtin_nontemporal_store(o, dzvec + idx);
+                    }
+                }
+            }
+        }
     }
     }
 
@@ -395,7 +511,9 @@ __device__ __forceinline__ bool row_task(const RowArgs &a, TaskState &s, u32x4 (
 // CU keeps loads in flight while it computes.  The ragged end of a row (fewer
 // than one vector) is held one element per thread in threads 0..tail-1.
 // EXTRAS builds also produce lse_full and the membership bitmask (1), and the entropy on top (2).
-template <typename T, int NV, int NVFULL, int NT, int MINW, int EXTRAS>
+// OVF builds take rows longer than the registers hold: the first NT * NV vectors are resident, the rest
+// is re-read in every phase (from the last-level cache when the workgroups' rows fit it).
+template <typename T, int NV, int NVFULL, int NT, int MINW, int EXTRAS, bool OVF = false>
 __global__ __launch_bounds__(NT, MINW) void rows_resident_kernel(const RowArgs a)
 {
     using TR = elem_traits<T>;
@@ -430,7 +548,7 @@ __global__ __launch_bounds__(NT, MINW) void rows_resident_kernel(const RowArgs a
         if (t < tail) s.xt_raw = load_raw(zrow + (int64_t)nvec * EPV + t);
         if (s.y_ok) s.zy_raw = load_raw(zrow + s.y);
     }
-    while (row_task<T, NV, NVFULL, T, NV, NVFULL, NV, NT, EXTRAS, true>(a, s, r, lds_max, lds_f, lds_i, &lds_list_count)) {}
+    while (row_task<T, NV, NVFULL, T, NV, NVFULL, NV, NT, EXTRAS, true, OVF>(a, s, r, lds_max, lds_f, lds_i, &lds_list_count)) {}
 }
 
 // The same walk when the inference logits are stored as 8-bit E4M3 codes: an
@@ -764,12 +882,12 @@ static int blocks_per_cu(Kernel k, int threads)
     return nb;
 }
 
-template <typename T, bool F8_INFER, int NV, int NVFULL, int NT, int MINW, int EXTRAS>
+template <typename T, bool F8_INFER, int NV, int NVFULL, int NT, int MINW, int EXTRAS, bool OVF = false>
 static hipError_t launch_resident_inst(const RowArgs &a, hipStream_t stream)
 {
     void (*kernel)(const RowArgs);
     if constexpr (F8_INFER) kernel = rows_resident_f8infer_kernel<T, NV, NVFULL, NT, MINW, EXTRAS>;
-    else                    kernel = rows_resident_kernel<T, NV, NVFULL, NT, MINW, EXTRAS>;
+    else                    kernel = rows_resident_kernel<T, NV, NVFULL, NT, MINW, EXTRAS, OVF>;
     static int per_cu = 0;
     if (per_cu == 0) per_cu = blocks_per_cu(kernel, NT);
     int64_t grid = (int64_t)device_cu_count() * per_cu;
@@ -795,14 +913,16 @@ static hipError_t launch_resident_t(const RowArgs &a, hipStream_t stream)
     if (slots <= 1024 * 16) return launch_resident_inst<T, F8_INFER, 16, 12, 1024, 4, EXTRAS>(a, stream);
     if (slots <= 1024 * 19) return launch_resident_inst<T, F8_INFER, 19, 16, 1024, 4, EXTRAS>(a, stream);
     if (slots <= 1024 * 20) return launch_resident_inst<T, F8_INFER, 20, 19, 1024, 4, EXTRAS>(a, stream);
+    if constexpr (!F8_INFER) return launch_resident_inst<T, false, 16, 16, 1024, 4, EXTRAS, true>(a, stream);
     return hipErrorInvalidValue;
 }
 
 bool row_fits_resident(int dtype, int dtype_infer, int64_t vocab)
 {
     const int epv = dtype == DVP_BF16 ? 8 : 4;
-    if (dtype_infer == DVP_F8E4M3 && (dtype != DVP_BF16 || vocab < 16)) return false;   // bf16 training rows only
-    return vocab >= epv && vocab / epv <= 1024 * 20;
+    if (dtype_infer == DVP_F8E4M3)    // bf16 training rows that fit the registers only
+        return dtype == DVP_BF16 && vocab >= 16 && vocab / epv <= 1024 * 20;
+    return vocab >= epv;              // longer rows: resident up to 1024 * 20 vectors, the rest re-read
 }
 
 hipError_t launch_rows_resident(int dtype, int dtype_infer, const RowArgs &a, hipStream_t stream)

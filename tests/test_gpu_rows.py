@@ -164,12 +164,30 @@ def test_shapes_streaming_path_misaligned(dvp, dtype, v):
         _run_case(dvp, wl, rho, backward=True, threads=2)
 
 
-def test_vocab_too_large_for_registers_uses_streaming(dvp):
-    v = 8 * 1024 * 20 + 8       # one vector more than the resident kernel holds
-    wl = _random_case(3, v, torch.bfloat16, seed=77)
-    p = dvp.DvpParams(3, v, v, v, v, 1, -1.0, 1)
-    assert dvp.lib().dvp_row_path(p, 1) == 0
-    _run_case(dvp, wl, 1e-3, backward=True, threads=3)
+@pytest.mark.parametrize("dtype,v,ld", [
+    (torch.bfloat16, 8 * 1024 * 20 + 8, None),        # one vector more than the registers hold
+    (torch.bfloat16, 8 * 1024 * 20 + 8 * 1024 + 3, 8 * 1024 * 21 + 8),   # one more per thread, ragged end
+    (torch.bfloat16, 262144, None),                   # a 256k vocabulary: 192 KB of every row outside the registers
+    (torch.float32, 4 * 1024 * 20 + 4, None),
+    (torch.float32, 151936, None),                    # fp32 logits at the 152k vocabulary
+    (torch.float32, 100003, 100004)])
+def test_rows_longer_than_the_register_file(dvp, dtype, v, ld):
+    """The first 1024 x 20 vectors of a row stay in registers, the rest is re-read in every phase by the
+    same kernel: every output and both gradient forms (lists for short safe sets, dense rows) to the
+    usual bars, membership bits included."""
+    wl = _random_case(5, v, dtype, seed=v % 1000, ld=ld)
+    code = 1 if dtype == torch.bfloat16 else 0
+    p = dvp.DvpParams(5, v, ld or v, ld or v, ld or v, code, -1.0, code)
+    assert dvp.lib().dvp_row_path(p, 1) == 1
+    # put the sampled token of one row, and the row maximum of another, into the re-read part
+    with torch.no_grad():
+        wl.ids[1] = v - 5
+        wl.z_train[2, v - 9] = 40.0
+        wl.z_infer[2, v - 9] = 40.0
+        wl.ids[2] = v - 9
+    for rho in (1e-3, 1e-1, 0.0):       # dense rows, rows with a handful of safe tokens (lists), no pruning
+        _run_case(dvp, wl, rho, backward=True, threads=4)
+    _run_case(dvp, wl, 1e-2, backward=False, lse_full=False, bits=False, threads=4)
 
 
 # ---------------------------------------------------------------------------

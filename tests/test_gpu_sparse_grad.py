@@ -93,7 +93,7 @@ def test_thousands_of_safe_tokens_and_overflow(dvp, dtype):
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
-@pytest.mark.parametrize("v", [9, 1000, 20011, 70003])
+@pytest.mark.parametrize("v", [9, 1000, 20011, 70003, 170003])
 def test_ragged_vocab(dvp, dtype, v):
     # padded 16-byte aligned rows with a ragged end, sampled ids at both ends of the row
     from tests.test_gpu_rows import _random_case
@@ -102,7 +102,8 @@ def test_ragged_vocab(dvp, dtype, v):
     wl = _random_case(7, v, dtype, seed=77 + v, ld=ld)
     cap = min(v, 65536)
     _check_lists(dvp, wl, 1e-2, cap)
-    _check_lists(dvp, wl, 0.0, cap)            # at v = 70003 every row overflows the largest list
+    _check_lists(dvp, wl, 0.0, cap)            # from v = 70003 on every row overflows the largest list
+    # (v = 170003: longer than the register file holds, the end of the row is re-read)
     _check_lists(dvp, wl, 1e-2, 3)
 
 

@@ -98,8 +98,9 @@ def test_row_path_selection():
         return L.dvp_row_path(ctypes.byref(p), aligned)
 
     assert path(151936, 1) == 1 and path(32000, 1) == 1 and path(32000, 0) == 1
-    assert path(163840, 1) == 1 and path(163848, 1) == 0       # register file limit, bf16
-    assert path(81920, 0) == 1 and path(81924, 0) == 0         # and fp32
+    assert path(163840, 1) == 1 and path(163848, 1) == 1       # beyond the register file: partly re-read, same kernel
+    assert path(81920, 0) == 1 and path(81924, 0) == 1 and path(151936, 0) == 1
+    assert path(163848, 1, dtype_infer=2) == 0                 # byte inference rows: only while the bf16 row fits
     assert path(1000, 1, ld=1001) == 0                         # rows not 16-byte aligned
     assert path(1000, 1, aligned=0) == 0
     assert path(7, 1) == 0 and path(8, 1, ld=8) == 1               # shorter than one vector
@@ -151,7 +152,6 @@ def test_sparse_gradient_validation_needs_no_gpu():
     assert call(flags=None) == 1 and call(entries=None) == 1 and call(z=None) == 1
     assert call(entries=FAKE + 4) == 4
     assert call(vocab=32001) == 5            # rows not 16-byte aligned: no single-read path
-    assert call(vocab=200000) == 5           # does not fit the register file
     assert call(z=FAKE + 2) == 5             # base pointer not 16-byte aligned
 
 

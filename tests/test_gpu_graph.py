@@ -1,0 +1,98 @@
+"""The library only enqueues kernels on the caller's stream (no allocation, no synchronisation, no
+memset nodes), so a call sequence can be captured in a HIP graph and replayed.  Each replay is compared
+bit for bit with the same calls made eagerly on the same inputs, with the inputs changed and eager work
+done between the replays."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2512_23087_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dvp():
+    from paper_2512_23087_amd import dvp as binding
+    binding.lib()
+    return binding
+
+
+def _row_buffers(dvp, n, v, like):
+    return dict(out_train=dvp.SideOutputs(n, v, "cuda"), out_infer=dvp.SideOutputs(n, v, "cuda"),
+                row_flags=torch.empty(n, dtype=torch.uint8, device="cuda"), dz=torch.empty_like(like))
+
+
+def test_rows_and_sequence_step_replayed_from_a_graph(dvp):
+    n, v = 96, 40000
+    wl = workloads.make_rows(2, device="cuda", n=n, v=v)
+    other = workloads.make_rows(3, device="cuda", n=n, v=v)
+    lr, lthr = dvp.log_rho(1e-4), dvp.log_threshold(1e-4)
+    off = torch.tensor([0, 10, 10, 57, 96], dtype=torch.int64, device="cuda")
+    zt, zi = wl.z_train.clone(), wl.z_infer.clone()
+    ids, go = wl.ids.clone(), wl.grad_out.clone()
+
+    def run(bufs, seq):
+        dvp.dvp_forward_backward(zt, zi, ids, go, lr, **bufs)
+        dvp.dvp_sequence_weights(bufs["out_train"].logp, bufs["out_infer"].logp, off, lthr, **seq)
+
+    def seq_buffers():
+        return dict(weight=torch.empty(n, device="cuda"), seq_log_ratio=torch.empty(4, device="cuda"),
+                    seq_min_weight=torch.empty(4, device="cuda"), seq_veto=torch.empty(4, dtype=torch.uint8, device="cuda"))
+
+    eager, eager_seq = _row_buffers(dvp, n, v, zt), seq_buffers()
+    graph_b, graph_seq = _row_buffers(dvp, n, v, zt), seq_buffers()
+    run(eager, eager_seq)                       # warm-up: one-time occupancy queries happen outside the capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run(graph_b, graph_seq)
+    for rep in range(4):
+        if rep == 1:                            # new logits, ids and upstream gradients in the captured buffers
+            zt.copy_(other.z_train); zi.copy_(other.z_infer); ids.copy_(other.ids); go.copy_(other.grad_out)
+        if rep == 2:
+            zt.copy_(wl.z_train); ids.copy_(wl.ids)
+        if rep == 3:
+            graph_b["dz"].fill_(7.0)            # stale output contents must not matter
+        run(eager, eager_seq)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(graph_b["dz"], eager["dz"]), rep
+        assert torch.equal(graph_b["row_flags"], eager["row_flags"])
+        for side in ("out_train", "out_infer"):
+            for k in ("logp", "row_max", "lse_safe", "safe_count"):
+                a, b = getattr(graph_b[side], k), getattr(eager[side], k)
+                assert torch.equal(torch.nan_to_num(a.float(), nan=-1.0), torch.nan_to_num(b.float(), nan=-1.0)), (rep, side, k)
+        for k in graph_seq:
+            assert torch.equal(torch.nan_to_num(graph_seq[k].float(), nan=-1.0),
+                               torch.nan_to_num(eager_seq[k].float(), nan=-1.0)), (rep, k)
+    assert graph_b["dz"].float().abs().max().item() > 0
+
+
+def test_lmhead_replayed_from_a_graph(dvp):
+    wl = workloads.make_lmhead(device="cuda", n=300, d=128, v=1500)
+    wl2 = workloads.make_lmhead(device="cuda", n=300, d=128, v=1500)
+    lr = dvp.log_rho(1e-4)
+    hidden = wl.hidden.clone()
+    ws = torch.empty(dvp.lmhead_workspace_bytes(300, 128, 1500), dtype=torch.uint8, device="cuda")
+    ws2 = torch.empty_like(ws)
+    dh, dw = torch.empty(300, 128, device="cuda"), torch.empty(1500, 128, device="cuda")
+    dh2, dw2 = torch.empty_like(dh), torch.empty_like(dw)
+    # the binding allocates the per-row output arrays itself: keep the first call's and capture that call
+    first = dvp.dvp_fused_lmhead(hidden, wl.w_train, wl.w_infer, wl.ids, wl.grad_out, lr, workspace=ws2, d_hidden=dh2, d_w=dw2)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        res = dvp.dvp_fused_lmhead(hidden, wl.w_train, wl.w_infer, wl.ids, wl.grad_out, lr, workspace=ws, d_hidden=dh, d_w=dw)
+    for rep in range(3):
+        if rep == 1:
+            hidden.copy_((wl2.hidden.float() * 1.5).to(torch.bfloat16))
+        ref = dvp.dvp_fused_lmhead(hidden, wl.w_train, wl.w_infer, wl.ids, wl.grad_out, lr, workspace=ws2, d_hidden=dh2, d_w=dw2)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(dh, dh2) and torch.equal(dw, dw2), rep
+        assert torch.equal(res.train.logp, ref.train.logp) and torch.equal(res.infer.logp, ref.infer.logp)
+        assert torch.equal(res.row_flags, ref.row_flags)
+    assert first.train.logp.shape == res.train.logp.shape

@@ -7,7 +7,7 @@
 //   pass A  z tiles -> running row max, and z_y where a tile holds column y
 //   pass B  z tiles -> safe-set size and masked sum at tau = fl32(m + log_rho)
 //           (Def. 5.1 / 5.2), per 256-column partials, reduced in fixed order
-// When a gradient is asked for, the training side runs in blocks of 4096 token
+// When a gradient is asked for, the training side runs in blocks of 8192 token
 // rows and pass B also leaves the block's masked exponentials
 //   E_ik = [z_ik >= tau_i] exp(z_ik - m_i)          (bf16, both orientations)
 // behind, with the sampled token's own entry E_iy set to zero.  With S_i the
@@ -49,7 +49,7 @@ constexpr int kWaveStageBytes = kPipeLdsBytes / kGemmWaves;   // 16 KB: a wavefr
 static_assert(kWaveStageBytes == MI * 32 * NI * 32 * 2, "epilogue staging assumes one bf16 block per wavefront");
 constexpr int kCopiesPerWave = BM * (BK / 8) / kWave / kGemmWaves;   // 1 KB wavefront copies per operand tile and wavefront
 static_assert(BM == BN, "the operand tiles share one copy schedule");
-constexpr int kRowBlock = 4096;                 // token rows whose masked exponentials are held at a time
+constexpr int kRowBlock = 8192;                 // token rows whose masked exponentials are held at a time
 
 __device__ __forceinline__ int float_to_ordered(float f)
 {
@@ -637,14 +637,16 @@ __global__ __launch_bounds__(kAfterRows * kAfterSegs) void after_sum_kernel(RowS
 
 // Sampled-token part of dW (Prop. 5.4): dW[y_i, :] += q_i H_i for the `rows` token rows of a block, in
 // fp32 and in row order whatever the launch order (run-to-run identical).  One workgroup per token
-// row; the first row of the block that sampled a token adds the contributions of every row that
-// sampled it.  Runs after the block's E^T product has been written to dW.
+// row; the first row of the launch that sampled a token adds the contributions of every row of the
+// launch that sampled it; a block of rows is covered by successive launches of kOnehotRows rows.  Runs
+// after the block's E^T product has been written to dW.
 constexpr int kOnehotThreads = 256;
+constexpr int kOnehotRows = 4096;       // rows per launch: every workgroup scans its launch's sampled tokens
 __global__ __launch_bounds__(kOnehotThreads) void onehot_dw_kernel(const int64_t *ids, const float *coef, const uint16_t *H,
                                                                    int64_t ld_h, float *dW, int64_t ld_w, int rows, int d)
 {
-    __shared__ int tok[kRowBlock];      // sampled token per row, -1 where the row contributes nothing
-    __shared__ int match[kRowBlock];    // rows that sampled this workgroup's token, ascending
+    __shared__ int tok[kOnehotRows];    // sampled token per row, -1 where the row contributes nothing
+    __shared__ uint16_t match[kOnehotRows];   // rows that sampled this workgroup's token, ascending
     __shared__ int n_match;
     const int i = blockIdx.x, tid = threadIdx.x;
     for (int r = tid; r < rows; r += kOnehotThreads) tok[r] = coef[r] != 0.0f ? (int)ids[r] : -1;
@@ -660,7 +662,7 @@ __global__ __launch_bounds__(kOnehotThreads) void onehot_dw_kernel(const int64_t
             const int r = base + tid;
             const bool hit = r < rows && tok[r] == y;
             const unsigned long long bal = __builtin_amdgcn_ballot_w64(hit);
-            if (hit) match[count + (int)__builtin_popcountll(bal & ((1ull << tid) - 1ull))] = r;
+            if (hit) match[count + (int)__builtin_popcountll(bal & ((1ull << tid) - 1ull))] = (uint16_t)r;
             count += (int)__builtin_popcountll(bal);
         }
         if (tid == 0) n_match = count;
@@ -884,9 +886,13 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
             gw.M = v; gw.N = d; gw.K = rows_pad;
             const EpiStore ew{d_w, p->ld_w, r0 > 0, nullptr, nullptr, nullptr, nullptr, 0};
             if (launch_gemm<EpiStore, false>(gw, ew, stream) != hipSuccess) return DVP_ERR_HIP;
-            hipLaunchKernelGGL(onehot_dw_kernel, dim3(rows), dim3(kOnehotThreads), 0, stream, ids + r0,
-                               (const float *)st.coef, hblock, p->ld_hidden, d_w, p->ld_w, rows, d);
-            DVP_CHECK_LAUNCH();
+            for (int q0 = 0; q0 < rows; q0 += kOnehotRows) {   // in row order: launches on one stream run in order
+                const int qrows = (rows - q0) < kOnehotRows ? (rows - q0) : kOnehotRows;
+                hipLaunchKernelGGL(onehot_dw_kernel, dim3(qrows), dim3(kOnehotThreads), 0, stream, ids + r0 + q0,
+                                   (const float *)st.coef + q0, hblock + (int64_t)q0 * p->ld_hidden, p->ld_hidden,
+                                   d_w, p->ld_w, qrows, d);
+                DVP_CHECK_LAUNCH();
+            }
         }
     }
     if (infer_side) {

@@ -213,6 +213,10 @@ def main():
     ap.add_argument("--sparse-grad", type=int, default=0, metavar="CAP",
                     help="deliver the gradient as per-row (index, value) lists of at most CAP entries "
                          "(dvp_forward_backward_sparse) instead of the dense matrix")
+    ap.add_argument("--split-lists", type=int, default=0, metavar="CAP",
+                    help="the flow of a caller that learns grad_out only after the forward: one step = "
+                         "dvp_forward_backward_sparse with grad_out = 1 (lists of at most CAP entries) followed by "
+                         "dvp_lists_to_dense with the real grad_out (dense gradient, logits not read again)")
     ap.add_argument("--infer-dtype", default="same", choices=["same", "f8"],
                     help="f8: the inference logits are rounded through E4M3 (saturating) and handed over as "
                          "one byte per token")
@@ -260,7 +264,19 @@ def main():
     flags = torch.empty(n, dtype=torch.uint8, device="cuda:0")
     dz = torch.empty_like(wl.z_train)
 
-    if args.sparse_grad:
+    if args.split_lists:
+        cap = args.split_lists
+        entries = torch.empty(n, cap, 2, dtype=torch.int32, device="cuda:0")
+        glen = torch.empty(n, dtype=torch.int32, device="cuda:0")
+        ones = torch.ones(n, dtype=torch.float32, device="cuda:0")
+
+        def step(log_rho_value=lr):
+            sp = dvp.dvp_forward_backward_sparse(wl.z_train, wl.z_infer, wl.ids, ones, log_rho_value, cap,
+                                                 out_train=out_t, out_infer=out_i, row_flags=flags,
+                                                 entries=entries, grad_len=glen)
+            dvp.dvp_lists_to_dense(sp, v, wl.z_train.dtype, wl.grad_out, log_rho_value, z_train=wl.z_train,
+                                   ids=wl.ids, dz=dz)
+    elif args.sparse_grad:
         del dz
         entries = torch.empty(n, args.sparse_grad, 2, dtype=torch.int32, device="cuda:0")
         glen = torch.empty(n, dtype=torch.int32, device="cuda:0")
@@ -289,7 +305,8 @@ def main():
     achieved = bytes_per_launch / (kernel_ms * 1e-3) / 1e9
 
     traffic = MEASURED_TRAFFIC.get(kernel_source_hash(), {}).get(args.workload) \
-        if args.rows is None and args.rho == 1e-4 and not args.sparse_grad and args.infer_dtype == "same" else None
+        if args.rows is None and args.rho == 1e-4 and not args.sparse_grad and not args.split_lists \
+        and args.infer_dtype == "same" else None
 
     result = {
         "metric": "DVP fwd+bwd rows/s and achieved HBM GB/s (% of peak), V=151936 bf16",
@@ -306,15 +323,19 @@ def main():
                    "storage_dtype": str(wl.z_train.dtype)[6:], "infer_storage_dtype": str(wl.z_infer.dtype)[6:],
                    "n_rows": n, "vocab": v,
                    "rho": args.rho,
-                   "entry_point": "dvp_forward_backward_sparse (list capacity %d)" % args.sparse_grad
-                   if args.sparse_grad else "dvp_forward_backward",
+                   "entry_point": "dvp_forward_backward_sparse (grad_out = 1, list capacity %d) + dvp_lists_to_dense"
+                                  % args.split_lists if args.split_lists else
+                                  "dvp_forward_backward_sparse (list capacity %d)" % args.sparse_grad
+                                  if args.sparse_grad else "dvp_forward_backward",
                    "row_kernel": "resident" if dvp.lib().dvp_row_path(
                        dvp.DvpParams(n, v, v, v, v, 1 if elem == 2 else 0, lr,
                                      2 if infer_elem == 1 else (1 if elem == 2 else 0)), 1) == 1 else "streaming",
                    "input_generation_s": round(t_gen, 2)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": "rows_resident_kernel (gradient as lists)" if args.sparse_grad else
+                     "kernel": "rows_resident_kernel (lists) + lists_zero_kernel + lists_scatter_kernel (+ "
+                               "backward_kernel on overflowing rows); durations summed" if args.split_lists else
+                               "rows_resident_kernel (gradient as lists)" if args.sparse_grad else
                                "rows_resident_kernel + grad_zero_kernel + grad_scatter_kernel "
                                "(one dvp_forward_backward call; durations summed)",
                      "kernel_ms_avg": kernel_ms, "kernel_ms_min": min(per_launch),
@@ -328,6 +349,11 @@ def main():
                           "y_in_train_safe_frac": (flags & 1).to(torch.float64).mean().item()}
     if args.sparse_grad:
         result["overflow_rows"] = int(((flags & 8) != 0).sum().item())
+    if args.split_lists:
+        result["overflow_rows"] = int(((flags & 8) != 0).sum().item())
+        # the lists are written once and read once on top of the dense figure
+        listed = glen[(flags & 8) == 0].to(torch.int64).sum().item()
+        result["roofline"]["list_bytes_per_launch"] = 16 * listed
     if not args.no_sweep and not args.sparse_grad:
         sweep = []
         for rho in wl.rhos:

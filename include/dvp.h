@@ -207,6 +207,29 @@ dvp_status dvp_forward_backward_sparse(const dvp_params *params, const void *z_t
                                        int32_t list_cap, void *stream);
 
 /*
+ * Dense gradient from the lists of dvp_forward_backward_sparse, for callers that learn grad_out only
+ * after the forward pass (with importance weights, dL/dlogp depends on the log-probs themselves).
+ * Prop. 5.4's gradient is linear in grad_out: run dvp_forward_backward_sparse with grad_out = 1, keep
+ * its lists, and once grad_out is known this call writes
+ *     dz_ik = grad_out_i * value_ik  for row i's entries,   0 elsewhere
+ * without reading the logits again: zeros over the matrix, then the scaled entries dropped in place.
+ *   params     n_rows, vocab, ld_grad, dtype (of dz), mode as in the forward call; log_rho and ld_train
+ *              are used only with z_train below.
+ *   entries, grad_len, list_cap, row_flags   as written by dvp_forward_backward_sparse.
+ *   grad_out   DEVICE float [N], or NULL for 1.
+ *   z_train, ids, row_max_train, lse_safe_train   NULL, or the forward's inputs and outputs: then the
+ *              rows flagged DVP_ROW_GRAD_OVERFLOW (safe set longer than list_cap) are computed from
+ *              the logits as dvp_backward does (grad_out is then required).  With z_train NULL those
+ *              rows of dz are not written.
+ *   dz         DEVICE [N, ld_grad], overwritten.
+ */
+dvp_status dvp_lists_to_dense(const dvp_params *params, const dvp_grad_entry *entries,
+                              const int32_t *grad_len, int32_t list_cap, const uint8_t *row_flags,
+                              const float *grad_out, const void *z_train, const int64_t *ids,
+                              const float *row_max_train, const float *lse_safe_train, void *dz,
+                              void *stream);
+
+/*
  * LM-head variant: the logits z = H W^T are produced tile by tile on the
  * matrix cores and consumed in the tile epilogues; the [N, V] logits are never
  * stored.  Same per-row definitions as above (Def. 5.1, 5.2, Prop. 5.4); the

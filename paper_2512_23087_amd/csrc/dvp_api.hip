@@ -200,9 +200,49 @@ dvp_status dvp_backward(const dvp_params *params, const void *z_train, const int
     a.dz = dz; a.ld_grad = params->ld_grad;
     a.n_rows = params->n_rows; a.vocab = (int32_t)params->vocab; a.log_rho = params->log_rho;
     a.finite_mask = params->mode == DVP_MODE_FINITE_MASK;
+    a.only_flagged = 0;
     const bool vec = rows_vector_ok(params, z_train, nullptr, dz);
     hipError_t e = dvp::launch_backward(params->dtype, a, vec, (hipStream_t)stream);
     return e == hipSuccess ? DVP_OK : DVP_ERR_HIP;
+}
+
+dvp_status dvp_lists_to_dense(const dvp_params *params, const dvp_grad_entry *entries, const int32_t *grad_len,
+                              int32_t list_cap, const uint8_t *row_flags, const float *grad_out,
+                              const void *z_train, const int64_t *ids, const float *row_max_train,
+                              const float *lse_safe_train, void *dz, void *stream)
+{
+    dvp_status st = check_params(params, false, true);
+    if (st != DVP_OK) return st;
+    if (list_cap < 1 || list_cap > DVP_MAX_LIST_CAP) return DVP_ERR_PARAM;
+    if (params->mode != DVP_MODE_EXACT) return DVP_ERR_UNSUPPORTED;
+    if (params->n_rows == 0) return DVP_OK;
+    if (!entries || !grad_len || !row_flags || !dz) return DVP_ERR_NULL;
+    if (z_train && (!ids || !row_max_train || !lse_safe_train || !grad_out)) return DVP_ERR_NULL;
+    const size_t es = elem_size(params->dtype);
+    if (!aligned_to(entries, 8) || !aligned_to(grad_len, 4) || !aligned_to(grad_out, 4) || !aligned_to(dz, es) ||
+        !aligned_to(z_train, es) || !aligned_to(ids, 8) || !aligned_to(row_max_train, 4) ||
+        !aligned_to(lse_safe_train, 4))
+        return DVP_ERR_ALIGN;
+
+    dvp::ListsArgs l;
+    l.entries = entries; l.grad_len = grad_len; l.row_flags = row_flags; l.scale = grad_out;
+    l.dz = dz; l.ld_grad = params->ld_grad; l.n_rows = params->n_rows; l.vocab = (int32_t)params->vocab;
+    l.list_cap = list_cap;
+    const bool vec_dz = aligned_to(dz, 16) && (params->ld_grad * es) % 16 == 0;
+    if (dvp::launch_lists_to_dense(params->dtype, l, vec_dz, (hipStream_t)stream) != hipSuccess) return DVP_ERR_HIP;
+    if (z_train) {   // rows whose safe set did not fit their list: from the logits
+        BackwardArgs a;
+        a.z = z_train; a.ld = params->ld_train;
+        a.ids = ids; a.grad_out = grad_out;
+        a.row_max = row_max_train; a.lse_safe = lse_safe_train; a.row_flags = row_flags;
+        a.dz = dz; a.ld_grad = params->ld_grad;
+        a.n_rows = params->n_rows; a.vocab = (int32_t)params->vocab; a.log_rho = params->log_rho;
+        a.finite_mask = 0;
+        a.only_flagged = DVP_ROW_GRAD_OVERFLOW;
+        const bool vec = rows_vector_ok(params, z_train, nullptr, dz);
+        if (dvp::launch_backward(params->dtype, a, vec, (hipStream_t)stream) != hipSuccess) return DVP_ERR_HIP;
+    }
+    return DVP_OK;
 }
 
 dvp_status dvp_sequence_weights(int64_t n_tokens, int64_t n_seq, const float *logp_train,

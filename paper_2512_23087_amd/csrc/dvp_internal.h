@@ -73,6 +73,20 @@ struct BackwardArgs {
     int32_t vocab;
     float log_rho;
     int32_t finite_mask;     // see RowArgs
+    uint32_t only_flagged;   // non-zero: only rows with one of these row_flags bits are written
+};
+
+// Dense gradient from per-row lists (launch_lists_to_dense)
+struct ListsArgs {
+    const void *entries;     // [n_rows, list_cap] of (index, value)
+    const int32_t *grad_len;
+    const uint8_t *row_flags;
+    const float *scale;      // [n_rows] or null (1)
+    void *dz;
+    int64_t ld_grad;
+    int64_t n_rows;
+    int32_t vocab;
+    int32_t list_cap;
 };
 
 struct SequenceArgs {
@@ -96,6 +110,7 @@ hipError_t launch_rows_resident(int dtype, int dtype_infer, const RowArgs &a, hi
 hipError_t launch_rows_streaming(int dtype, int dtype_infer, const RowArgs &a, hipStream_t stream);
 hipError_t launch_grad_fill(int dtype, const FillArgs &a, hipStream_t stream);
 hipError_t launch_backward(int dtype, const BackwardArgs &a, bool vector_ok, hipStream_t stream);
+hipError_t launch_lists_to_dense(int dtype, const ListsArgs &a, bool vector_ok, hipStream_t stream);
 hipError_t launch_sequences(const SequenceArgs &a, hipStream_t stream);
 
 }  // namespace dvp

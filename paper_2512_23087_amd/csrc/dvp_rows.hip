@@ -726,6 +726,7 @@ __global__ __launch_bounds__(NT) void backward_kernel(const BackwardArgs a)
     const int V = a.vocab;
 
     for (int64_t row = blockIdx.x; row < a.n_rows; row += gridDim.x) {
+        if (a.only_flagged && !(a.row_flags[row] & a.only_flagged)) continue;   // workgroup-uniform
         const T *zrow = (const T *)a.z + row * a.ld;
         T *dzrow = (T *)a.dz + row * a.ld_grad;
         const float m = a.row_max[row];
@@ -854,6 +855,57 @@ __global__ __launch_bounds__(kFillThreads) void grad_scatter_kernel(const FillAr
     for (int i = tid; i < len; i += kFillThreads) {
         const uint2 e = lds_list[i];
         store_elem(dzrow + e.x, __uint_as_float(e.y));
+    }
+}
+
+// ---------------------------------------------------------------------------
+// dense gradient from lists: dz[i, index] = scale_i * value for row i's entries, zero elsewhere.  Two
+// write-only kernels: zeros over every row that has a list (rows flagged as overflowing are left to
+// the caller of the launcher), then one workgroup per row drops the scaled values in place.
+// ---------------------------------------------------------------------------
+constexpr int kListsZeroThreads = 1024, kListsZeroVecs = 2;
+template <typename T, bool VEC>
+__global__ __launch_bounds__(kListsZeroThreads) void lists_zero_kernel(const ListsArgs a, int chunks_per_row)
+{
+    constexpr int EPV = elem_traits<T>::kPerVec;
+    const int64_t row = blockIdx.x / chunks_per_row;
+    const int chunk = blockIdx.x - (int)(row * chunks_per_row);
+    if (a.row_flags[row] & DVP_ROW_GRAD_OVERFLOW) return;
+    T *dzrow = (T *)a.dz + row * a.ld_grad;
+    const int V = a.vocab;
+    if constexpr (VEC) {
+        const int nvec = V / EPV;
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int u = 0; u < kListsZeroVecs; ++u) {
+            const int idx = (chunk * kListsZeroVecs + u) * kListsZeroThreads + threadIdx.x;
+            if (idx < nvec) ((u32x4 *)dzrow)[idx] = zero;
+        }
+        if (chunk == chunks_per_row - 1) {
+            const int k = nvec * EPV + threadIdx.x;
+            if (k < V) store_elem(dzrow + k, 0.0f);
+        }
+    } else {
+        const int per = kListsZeroThreads * kListsZeroVecs * EPV;   // elements per workgroup
+        for (int k = chunk * per + threadIdx.x; k < (chunk + 1) * per && k < V; k += kListsZeroThreads)
+            store_elem(dzrow + k, 0.0f);
+    }
+}
+
+constexpr int kListsScatterThreads = 64;
+template <typename T>
+__global__ __launch_bounds__(kListsScatterThreads) void lists_scatter_kernel(const ListsArgs a)
+{
+    const int64_t row = blockIdx.x;
+    if (a.row_flags[row] & DVP_ROW_GRAD_OVERFLOW) return;
+    int len = a.grad_len[row];
+    if (len > a.list_cap) len = a.list_cap;
+    const uint2 *list = (const uint2 *)a.entries + row * (int64_t)a.list_cap;
+    const float g = a.scale ? a.scale[row] : 1.0f;
+    T *dzrow = (T *)a.dz + row * a.ld_grad;
+    for (int i = threadIdx.x; i < len; i += kListsScatterThreads) {
+        const uint2 e = list[i];
+        if (e.x < (uint32_t)a.vocab) store_elem(dzrow + e.x, g * __uint_as_float(e.y));
     }
 }
 
@@ -988,6 +1040,38 @@ hipError_t launch_rows_streaming(int dtype, int dtype_infer, const RowArgs &a, h
         else    hipLaunchKernelGGL((rows_streaming_kernel<float, float, NT>), g, b, 0, stream, a);
     }
     return hipGetLastError();
+}
+
+hipError_t launch_lists_to_dense(int dtype, const ListsArgs &a, bool vector_ok, hipStream_t stream)
+{
+    if (a.n_rows == 0) return hipSuccess;
+    const int epv = dtype == DVP_BF16 ? 8 : 4;
+    const int64_t per = (int64_t)kListsZeroThreads * kListsZeroVecs * epv;
+    const int chunks = (int)((a.vocab + per - 1) / per);
+    const int64_t max_rows = 0x7fffffff / chunks;
+    for (int64_t r0 = 0; r0 < a.n_rows; r0 += max_rows) {
+        ListsArgs b = a;
+        b.n_rows = a.n_rows - r0 < max_rows ? a.n_rows - r0 : max_rows;
+        b.entries = (const char *)a.entries + r0 * a.list_cap * 8;
+        b.grad_len = a.grad_len + r0;
+        b.row_flags = a.row_flags + r0;
+        b.scale = a.scale ? a.scale + r0 : nullptr;
+        b.dz = (char *)a.dz + r0 * a.ld_grad * (dtype == DVP_BF16 ? 2 : 4);
+        const dim3 gz((unsigned)(b.n_rows * chunks)), bz(kListsZeroThreads);
+        const dim3 gs((unsigned)b.n_rows), bs(kListsScatterThreads);
+        if (dtype == DVP_BF16) {
+            if (vector_ok) hipLaunchKernelGGL((lists_zero_kernel<bf16_t, true>), gz, bz, 0, stream, b, chunks);
+            else           hipLaunchKernelGGL((lists_zero_kernel<bf16_t, false>), gz, bz, 0, stream, b, chunks);
+            hipLaunchKernelGGL((lists_scatter_kernel<bf16_t>), gs, bs, 0, stream, b);
+        } else {
+            if (vector_ok) hipLaunchKernelGGL((lists_zero_kernel<float, true>), gz, bz, 0, stream, b, chunks);
+            else           hipLaunchKernelGGL((lists_zero_kernel<float, false>), gz, bz, 0, stream, b, chunks);
+            hipLaunchKernelGGL((lists_scatter_kernel<float>), gs, bs, 0, stream, b);
+        }
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 hipError_t launch_backward(int dtype, const BackwardArgs &a, bool vector_ok, hipStream_t stream)

@@ -23,7 +23,7 @@ ROW_Y_IN_TRAIN_SAFE, ROW_Y_IN_INFER_SAFE, ROW_ID_OUT_OF_RANGE, ROW_GRAD_OVERFLOW
 EXPORTS = ("dvp_forward", "dvp_backward", "dvp_forward_backward", "dvp_fused_lmhead",
            "dvp_fused_lmhead_workspace_bytes", "dvp_log_rho", "dvp_status_string", "dvp_row_path",
            "dvp_sequence_weights", "dvp_log_threshold", "dvp_forward_backward_sparse",
-           "dvp_fused_lmhead_f8infer")
+           "dvp_fused_lmhead_f8infer", "dvp_lists_to_dense")
 
 
 class DvpParams(ctypes.Structure):
@@ -94,6 +94,8 @@ def lib():
         L.dvp_row_path.argtypes = [pp, ctypes.c_int]
         L.dvp_forward_backward_sparse.restype = ctypes.c_int
         L.dvp_forward_backward_sparse.argtypes = [pp, vp, vp, i64p, vp, sp, sp, vp, vp, vp, ctypes.c_int32, vp]
+        L.dvp_lists_to_dense.restype = ctypes.c_int
+        L.dvp_lists_to_dense.argtypes = [pp, vp, vp, ctypes.c_int32, vp, vp, vp, i64p, vp, vp, vp, vp]
         L.dvp_sequence_weights.restype = ctypes.c_int
         L.dvp_sequence_weights.argtypes = [ctypes.c_int64, ctypes.c_int64, vp, vp, i64p, ctypes.c_float,
                                            vp, vp, vp, vp, vp]
@@ -301,6 +303,29 @@ def dvp_forward_backward_sparse(z_train, z_infer, ids, grad_out, log_rho_value, 
     if st != 0:
         raise DvpError(st, "dvp_forward_backward_sparse")
     return SparseResult(out_train, out_infer, row_flags, entries, grad_len)
+
+
+def dvp_lists_to_dense(sparse: SparseResult, vocab, dtype, grad_out=None, log_rho_value=-1.0, *, z_train=None,
+                       ids=None, dz: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Dense [N, vocab] gradient of `dtype` from the lists of dvp_forward_backward_sparse, scaled row by
+    row with grad_out.  With z_train (and ids) the rows whose list overflowed are computed from the logits."""
+    n, cap = sparse.entries.shape[0], sparse.entries.shape[1]
+    dev = sparse.entries.device
+    if dz is None:
+        dz = torch.empty(n, vocab, dtype=dtype, device=dev)
+    code = DVP_F32 if dz.dtype == torch.float32 else DVP_BF16
+    if dz.dtype not in (torch.float32, torch.bfloat16):
+        raise TypeError("dz must be float32 or bfloat16")
+    p = DvpParams(n, vocab, z_train.stride(0) if z_train is not None else vocab, 0, dz.stride(0), code,
+                  float(log_rho_value), code, DVP_MODE_EXACT, 0.0)
+    st = lib().dvp_lists_to_dense(ctypes.byref(p), _ptr(sparse.entries), _ptr(sparse.grad_len), int(cap),
+                                  _ptr(sparse.row_flags), _ptr(grad_out), _ptr(z_train), _ptr(ids),
+                                  _ptr(sparse.train.row_max) if z_train is not None else None,
+                                  _ptr(sparse.train.lse_safe) if z_train is not None else None, _ptr(dz),
+                                  _stream(stream))
+    if st != 0:
+        raise DvpError(st, "dvp_lists_to_dense")
+    return dz
 
 
 class LmHeadResult:

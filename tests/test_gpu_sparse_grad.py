@@ -128,3 +128,60 @@ def test_full_size_sampled_rows(dvp):
     _check_lists(dvp, wl, 1e-4, 256, rows=rows)
     del wl
     torch.cuda.empty_cache()
+
+
+# ---------------------------------------------------------------------------
+# dense gradient from the saved lists (grad_out known only after the forward)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_lists_to_dense_matches_the_fused_gradient(dvp, dtype):
+    """Forward with grad_out = 1 and lists, then dz = grad_out * lists: the dense matrix equals the
+    oracle's to the usual gradient bar; rows whose list overflowed are taken from the logits."""
+    n, v = 40, 40000
+    g = torch.Generator().manual_seed(99)
+    zt = (12.0 * torch.randn(n, v, generator=g)).to(dtype)              # safe sets from a handful to hundreds
+    zi = (zt.float() + 0.01 * torch.randn(n, v, generator=g)).to(dtype)
+    ids = torch.argmax(zi.float(), dim=1)
+    ids[3] = int(torch.argmin(zt[3].float()))                           # a pruned sampled token: zero row
+    go = torch.randn(n, generator=g)
+    zt, zi, ids, go = zt.cuda(), zi.cuda(), ids.cuda(), go.cuda()
+    lr = dvp.log_rho(1e-6)
+    ones = torch.ones(n, device="cuda")
+    cap = 64
+    sp = dvp.dvp_forward_backward_sparse(zt, zi, ids, ones, lr, cap)
+    torch.cuda.synchronize()
+    over = (sp.row_flags.cpu().numpy() & 8) != 0
+    assert 3 < over.sum() < n - 3                                        # both kinds of rows are present
+    dz = torch.full((n, v), 7.0, dtype=dtype, device="cuda")             # stale contents must not survive
+    dvp.dvp_lists_to_dense(sp, v, dtype, go, lr, z_train=zt, ids=ids, dz=dz)
+    torch.cuda.synchronize()
+    tol = parity.TOL[dtype]
+    parity.check_gradient("dz from lists", dz, zt.cpu(), ids.cpu(), go.cpu(), lr, tol, threads=4)
+    # without the logits the overflowing rows are left alone, the others are identical
+    dz2 = torch.full((n, v), 7.0, dtype=dtype, device="cuda")
+    dvp.dvp_lists_to_dense(sp, v, dtype, go, lr, dz=dz2)
+    torch.cuda.synchronize()
+    keep = torch.as_tensor(~over, device="cuda")
+    assert torch.equal(dz2[keep], dz[keep])
+    assert torch.all(dz2[~keep] == 7.0)
+    # no scale: the lists as they are
+    dz3 = dvp.dvp_lists_to_dense(sp, v, dtype, None, lr)
+    torch.cuda.synchronize()
+    idx, val = sp.row(int(np.nonzero(~over)[0][0]))
+    row = dz3[int(np.nonzero(~over)[0][0])].float().cpu()
+    assert torch.equal(row[idx], val.to(dtype).float()) and row.abs().sum() == val.to(dtype).float().abs().sum()
+
+
+def test_lists_to_dense_ragged_and_padded(dvp):
+    from tests.test_gpu_rows import _random_case
+    v, ld = 20011, 20016
+    wl = _random_case(7, v, torch.bfloat16, seed=5, ld=ld)
+    lr = dvp.log_rho(1e-2)
+    sp = dvp.dvp_forward_backward_sparse(wl.z_train, wl.z_infer, wl.ids, torch.ones(7, device="cuda"), lr, 4096)
+    store = torch.full((7, ld + 3), 7.0, dtype=torch.bfloat16, device="cuda")
+    for dz in (store[:, :v], store[:, 1:v + 1]):                       # 16-byte aligned rows, then odd ones
+        store.fill_(7.0)
+        dvp.dvp_lists_to_dense(sp, v, torch.bfloat16, wl.grad_out, lr, dz=dz)
+        torch.cuda.synchronize()
+        parity.check_gradient("dz", dz, wl.z_train.cpu(), wl.ids.cpu(), wl.grad_out.cpu(), lr, 2e-3, threads=2)
+    assert torch.all(store[:, v + 1:] == 7.0) and torch.all(store[:, 0] == 7.0)   # nothing outside the rows

@@ -155,6 +155,22 @@ def test_sparse_gradient_validation_needs_no_gpu():
     assert call(z=FAKE + 2) == 5             # base pointer not 16-byte aligned
 
 
+def test_lists_to_dense_validation_needs_no_gpu():
+    L = dvp.lib()
+
+    def call(n_rows=1, vocab=32000, cap=64, entries=FAKE, glen=FAKE, flags=FAKE, grad=FAKE, z=None, ids=None,
+             m=None, lse=None, dz=FAKE, ld_grad=None, mode=0):
+        p = dvp.DvpParams(n_rows, vocab, vocab, 0, vocab if ld_grad is None else ld_grad, 1, -3.0, 1, mode, -50.0)
+        return L.dvp_lists_to_dense(ctypes.byref(p), entries, glen, cap, flags, grad, z, ids, m, lse, dz, None)
+
+    assert call(n_rows=0) == 0
+    assert call(cap=0) == 3 and call(mode=1) == 5
+    assert call(entries=None) == 1 and call(glen=None) == 1 and call(flags=None) == 1 and call(dz=None) == 1
+    assert call(z=FAKE) == 1 and call(z=FAKE, ids=FAKE, m=FAKE, lse=FAKE, grad=None) == 1
+    assert call(ld_grad=31999) == 2
+    assert call(entries=FAKE + 4) == 4 and call(dz=FAKE + 1) == 4
+
+
 def test_lmhead_argument_validation_needs_no_gpu():
     L = dvp.lib()
     so = dvp.DvpSideOut(FAKE, FAKE, FAKE, None, FAKE, None)

@@ -112,8 +112,20 @@ def bench_lmhead(args):
     dh = torch.empty(n, d, dtype=torch.float32, device="cuda:0")
     dw = torch.empty(v, d, dtype=torch.float32, device="cuda:0")
 
+    two_calls = bool(args.split_lists)      # --split-lists on this workload: forward and backward as two calls
+    if two_calls:
+        p = dvp.DvpLmHeadParams(n, d, v, wl.hidden.stride(0), wl.w_train.stride(0), lr)
+        import ctypes
+        saved = torch.empty(int(dvp.lib().dvp_fused_lmhead_saved_bytes(ctypes.byref(p))), dtype=torch.uint8,
+                            device="cuda:0")
+
     def step():
-        if f8:
+        if two_calls:
+            _, kept = dvp.dvp_fused_lmhead_forward(wl.hidden, wl.w_train, None if f8 else wl.w_infer, wl.ids, lr,
+                                                   infer_f8=(wl.hidden8, wl.w8, wl.scale_infer) if f8 else None,
+                                                   saved=saved, workspace=ws)
+            dvp.dvp_fused_lmhead_backward(kept, wl.grad_out, d_hidden=dh, d_w=dw)
+        elif f8:
             dvp.dvp_fused_lmhead(wl.hidden, wl.w_train, None, wl.ids, wl.grad_out, lr, workspace=ws, d_hidden=dh,
                                  d_w=dw, infer_f8=(wl.hidden8, wl.w8, wl.scale_infer))
         else:
@@ -140,8 +152,9 @@ def bench_lmhead(args):
                                 "engine: E4M3 activations and head with per-tensor factors, rho=%g" if f8 else
                                 "configs[4]: hidden [%d, %d] bf16 x W [%d, %d] bf16 (train) and its "
                                 "fp8-e4m3-rounded copy (infer), rho=%g") % (n, d, v, d, args.rho),
-                   "entry_point": "dvp_fused_lmhead_f8infer" if f8 else "dvp_fused_lmhead",
-                   "workspace_bytes": ws.numel()},
+                   "entry_point": "dvp_fused_lmhead_forward + dvp_fused_lmhead_backward" if two_calls else
+                                  "dvp_fused_lmhead_f8infer" if f8 else "dvp_fused_lmhead",
+                   "workspace_bytes": ws.numel(), "saved_bytes": saved.numel() if two_calls else 0},
         "roofline": {"bound": "mfma", "achieved": executed / (ms * 1e-3) / 1e12,
                      "peak": peak, "unit": "TFLOP/s",
                      "frac": executed / (ms * 1e-3) / 1e12 / peak, "traffic": None,
@@ -214,7 +227,9 @@ def main():
                     help="deliver the gradient as per-row (index, value) lists of at most CAP entries "
                          "(dvp_forward_backward_sparse) instead of the dense matrix")
     ap.add_argument("--split-lists", type=int, default=0, metavar="CAP",
-                    help="the flow of a caller that learns grad_out only after the forward: one step = "
+                    help="(with --workload lmhead, any CAP > 0: one step = dvp_fused_lmhead_forward + "
+                         "dvp_fused_lmhead_backward)  "
+                         "the flow of a caller that learns grad_out only after the forward: one step = "
                          "dvp_forward_backward_sparse with grad_out = 1 (lists of at most CAP entries) followed by "
                          "dvp_lists_to_dense with the real grad_out (dense gradient, logits not read again)")
     ap.add_argument("--infer-dtype", default="same", choices=["same", "f8"],

@@ -272,6 +272,36 @@ dvp_status dvp_fused_lmhead(const dvp_lmhead_params *params, const void *hidden,
                             float *d_w, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The LM-head variant in two calls, for callers that learn grad_out only after the forward (with
+ * importance weights dL/dlogp depends on the log-probs).  Prop. 5.4's gradient is linear in grad_out, so
+ * the forward leaves the masked exponentials of the training side (bf16, both orientations, every row
+ * block) and two factors per row in `saved`, and the backward turns them into dH and dW with two
+ * matrix products per row block: six GEMM passes in all, as in the fused call, and results identical to
+ * it.
+ *   saved      DEVICE, 256-byte aligned, dvp_fused_lmhead_saved_bytes(params) bytes (about
+ *              4 N V bytes: 10 GB at N = 16384, V = 151936); written by the forward, read by the
+ *              backward, owned by the caller in between.
+ *   forward:   arguments as dvp_fused_lmhead without grad_out / d_hidden / d_w; the inference side is
+ *              w_infer (bf16), or infer8 (see dvp_fused_lmhead_f8infer), or neither (both NULL).
+ *   backward:  hidden, w_train, ids as in the forward; grad_out, d_hidden, d_w as in dvp_fused_lmhead.
+ * workspace as for dvp_fused_lmhead (its contents need not survive between the two calls).
+ */
+size_t dvp_fused_lmhead_saved_bytes(const dvp_lmhead_params *params);
+
+struct dvp_lmhead_f8_side_s;
+dvp_status dvp_fused_lmhead_forward(const dvp_lmhead_params *params, const void *hidden,
+                                    const void *w_train, const void *w_infer,
+                                    const struct dvp_lmhead_f8_side_s *infer8, const int64_t *ids,
+                                    const dvp_side_out *out_train, const dvp_side_out *out_infer,
+                                    uint8_t *row_flags, void *saved, size_t saved_bytes,
+                                    void *workspace, size_t workspace_bytes, void *stream);
+
+dvp_status dvp_fused_lmhead_backward(const dvp_lmhead_params *params, const void *hidden,
+                                     const void *w_train, const int64_t *ids, const float *grad_out,
+                                     const void *saved, size_t saved_bytes, float *d_hidden, float *d_w,
+                                     void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * The same call when the inference engine is an 8-bit (W8A8) engine (the FP8
  * rollout engines of Sec. 4.2): its logits are
  *     z' = scale * (hidden8 . w8^T)
@@ -286,7 +316,7 @@ dvp_status dvp_fused_lmhead(const dvp_lmhead_params *params, const void *hidden,
  *   scale          finite, > 0
  * Further limit: hidden a multiple of 128 (DVP_ERR_UNSUPPORTED otherwise).
  */
-typedef struct {
+typedef struct dvp_lmhead_f8_side_s {
     const void *hidden;
     const void *w;
     int64_t ld_hidden;

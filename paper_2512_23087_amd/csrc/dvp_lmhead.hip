@@ -588,7 +588,8 @@ __global__ void after_max_kernel(RowStats st, int n, float log_rho)
 constexpr int kAfterRows = 32, kAfterSegs = 8;
 __global__ __launch_bounds__(kAfterRows * kAfterSegs) void after_sum_kernel(RowStats st, SideOut out, const int64_t *ids,
                                                                             const float *grad_out, uint8_t *row_flags,
-                                                                            int n, int vocab, int col_tiles, int side)
+                                                                            int n, int vocab, int col_tiles, int side,
+                                                                            int unit_grad)
 {
     __shared__ float seg_s[kAfterSegs][kAfterRows], seg_f[kAfterSegs][kAfterRows];
     __shared__ int seg_c[kAfterSegs][kAfterRows];
@@ -618,7 +619,8 @@ __global__ __launch_bounds__(kAfterRows * kAfterSegs) void after_sum_kernel(RowS
     const float zy = st.zy[i];
     const bool y_safe = y_ok && zy >= tau;
     if (side == 0) {
-        const float c_i = (grad_out && y_safe) ? grad_out[i] : 0.0f;
+        // unit_grad: the factors of a gradient still to come, q / g and s / g (Prop. 5.4 is linear in g)
+        const float c_i = !y_safe ? 0.0f : (unit_grad ? 1.0f : (grad_out ? grad_out[i] : 0.0f));
         st.coef[i] = c_i != 0.0f ? c_i * (1.0f - __expf(zy - m) / s) : 0.0f;
         st.scale[i] = -c_i / s;
     }
@@ -742,6 +744,41 @@ static LmLayout lm_layout(int64_t n, int64_t d, int64_t v)
     return L;
 }
 
+// What the forward leaves behind for a backward in a later call: per row block the masked exponentials in
+// both orientations, and per row the two factors the gradient multiplies (1 - p_y and -1 / S, zero for
+// a row whose sampled token is pruned).
+struct LmSaved {
+    size_t total, off_ucoef, off_uscale, off_e, off_et, block_bytes;
+    int n_blocks;
+};
+
+static LmSaved lm_saved_layout(int64_t n, int64_t v)
+{
+    LmSaved S;
+    const int64_t block = n < kRowBlock ? n : kRowBlock;
+    const int64_t block_pad = (block + BM - 1) / BM * BM, v_pad = (v + BN - 1) / BN * BN;
+    S.n_blocks = (int)((n + kRowBlock - 1) / kRowBlock);
+    if (S.n_blocks < 1) S.n_blocks = 1;
+    S.block_bytes = align256((size_t)block_pad * v_pad * 2);
+    size_t o = 0;
+    S.off_ucoef = o; o += align256(n * 4);
+    S.off_uscale = o; o += align256(n * 4);
+    S.off_e = o; o += S.block_bytes * S.n_blocks;
+    S.off_et = o; o += S.block_bytes * S.n_blocks;
+    S.total = o;
+    return S;
+}
+
+// coef[i] = g[i] * unit_coef[i], scale[i] = g[i] * unit_scale[i]
+__global__ void apply_grad_kernel(float *coef, float *scale, const float *unit_coef, const float *unit_scale,
+                                  const float *g, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) { coef[i] = g[i] * unit_coef[i]; scale[i] = g[i] * unit_scale[i]; }
+}
+
+enum LmPhase { LM_FUSED = 0, LM_FORWARD_SAVE = 1, LM_BACKWARD_SAVED = 2 };
+
 static bool lm_params_ok(const dvp_lmhead_params *p)
 {
     if (!p) return false;
@@ -760,7 +797,8 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
                              const void *w_infer, const dvp_lmhead_f8_side *f8, const int64_t *ids,
                              const float *grad_out, const dvp_side_out *out_train, const dvp_side_out *out_infer,
                              uint8_t *row_flags, float *d_hidden, float *d_w, void *workspace,
-                             size_t workspace_bytes, void *stream_)
+                             size_t workspace_bytes, void *stream_, LmPhase phase = LM_FUSED, void *saved = nullptr,
+                             size_t saved_bytes = 0)
 {
     if (!p) return DVP_ERR_NULL;
     if (p->log_rho != p->log_rho || p->log_rho > 0.0f) return DVP_ERR_PARAM;
@@ -768,8 +806,9 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
         return DVP_ERR_SHAPE;
     if (!lm_params_ok(p)) return DVP_ERR_UNSUPPORTED;
     if (p->n_rows == 0) return DVP_OK;
-    if (!hidden || !w_train || !ids || !out_train) return DVP_ERR_NULL;
+    if (!hidden || !w_train || !ids || (!out_train && phase != LM_BACKWARD_SAVED)) return DVP_ERR_NULL;
     if (grad_out && (!d_hidden || !d_w)) return DVP_ERR_NULL;
+    if (phase == LM_BACKWARD_SAVED && !grad_out) return DVP_ERR_NULL;
     if ((out_train && (out_train->safe_bits || out_train->entropy)) ||
         ((w_infer || f8) && out_infer && (out_infer->safe_bits || out_infer->entropy)))
         return DVP_ERR_UNSUPPORTED;
@@ -787,6 +826,8 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
     const bool infer_side = w_infer != nullptr || f8 != nullptr;
     const LmLayout L = lm_layout(p->n_rows, p->hidden, p->vocab);
     if (!workspace || ((uintptr_t)workspace % 256) || workspace_bytes < L.total) return DVP_ERR_WORKSPACE;
+    const LmSaved SV = lm_saved_layout(p->n_rows, p->vocab);
+    if (phase != LM_FUSED && (!saved || ((uintptr_t)saved % 256) || saved_bytes < SV.total)) return DVP_ERR_WORKSPACE;
 
     hipStream_t stream = (hipStream_t)stream_;
     const int n = (int)p->n_rows, d = (int)p->hidden, v = (int)p->vocab;
@@ -799,7 +840,15 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
         if (o) outs[s] = SideOut{o->logp, o->row_max, o->lse_safe, o->lse_full, o->safe_count, nullptr};
     }
     uint16_t *ht = (uint16_t *)(ws + L.off_ht), *wt = (uint16_t *)(ws + L.off_wt);
-    uint16_t *E = (uint16_t *)(ws + L.off_e), *Et = (uint16_t *)(ws + L.off_et);
+    uint16_t *E = (uint16_t *)(ws + L.off_e), *Et = (uint16_t *)(ws + L.off_et);   // of the current row block
+    float *unit_coef = saved ? (float *)((char *)saved + SV.off_ucoef) : nullptr;
+    float *unit_scale = saved ? (float *)((char *)saved + SV.off_uscale) : nullptr;
+    auto use_block = [&](int r0) {   // saved phases keep every block's E; the fused call reuses one
+        if (phase == LM_FUSED) return;
+        const size_t b = (size_t)(r0 / kRowBlock) * SV.block_bytes;
+        E = (uint16_t *)((char *)saved + SV.off_e + b);
+        Et = (uint16_t *)((char *)saved + SV.off_et + b);
+    };
     const int tb = 256;
 #define DVP_CHECK_LAUNCH() do { if (hipGetLastError() != hipSuccess) return DVP_ERR_HIP; } while (0)
 
@@ -809,6 +858,7 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
         st.max_key = (int *)(ws + L.off_i32[s]); st.zy = (float *)(ws + L.off_zy[s]);
         st.m = (float *)(ws + L.off_m[s]); st.tau = (float *)(ws + L.off_tau[s]);
         st.coef = (float *)(ws + L.off_coef); st.scale = (float *)(ws + L.off_scale);
+        if (phase == LM_FORWARD_SAVE) { st.coef = unit_coef + r0; st.scale = unit_scale + r0; }
         st.part_s = (float *)(ws + L.off_ps[s]); st.part_c = (int *)(ws + L.off_pc[s]);
         st.part_f = outs[s].lse_full ? (float *)(ws + L.off_pf[s]) : nullptr;
         SideOut o = outs[s];
@@ -851,48 +901,76 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
         hipLaunchKernelGGL(after_sum_kernel, dim3((rows + kAfterRows - 1) / kAfterRows),
                            dim3(kAfterRows * kAfterSegs), 0, stream, st, o, ids + r0,
                            grad_out ? grad_out + r0 : nullptr, row_flags ? row_flags + r0 : nullptr, rows, v,
-                           L.col_tiles, s);
+                           L.col_tiles, s, phase == LM_FORWARD_SAVE ? 1 : 0);
         DVP_CHECK_LAUNCH();
         return DVP_OK;
     };
 
     RowStats st;
     dvp_status rc;
-    if (!grad_out) {
-        if ((rc = forward(0, 0, n, false, st)) != DVP_OK) return rc;
-    } else {
-        // training side with gradient, in blocks of kRowBlock token rows
+    // dH and dW of the row block at r0 from its E / E^T and the per-row factors coef (q) and scale (s)
+    auto backward_block = [&](int r0, int rows, const float *coef, const float *scale) -> dvp_status {
+        const int rows_pad = (rows + BM - 1) / BM * BM;
+        const uint16_t *hblock = (const uint16_t *)hidden + (int64_t)r0 * p->ld_hidden;
+        hipLaunchKernelGGL(transpose_bf16_kernel, dim3((d + 31) / 32, (rows_pad + 31) / 32), dim3(32, 8), 0, stream,
+                           hblock, p->ld_hidden, ht, (int64_t)L.block_pad, rows, d, rows_pad, scale);
+        DVP_CHECK_LAUNCH();
+        // dH[r0 : r0 + rows, :] = diag(s) . E [rows, v_pad] . (W^T [d, v_pad])^T + diag(q) . W[y, :]
+        GemmArgs gh;
+        gh.A = E; gh.lda = L.v_pad; gh.B = wt; gh.ldb = L.v_pad;
+        gh.M = rows; gh.N = d; gh.K = L.v_pad; gh.scale = 1.0f;
+        const EpiStore eh{d_hidden + (int64_t)r0 * p->ld_hidden, p->ld_hidden, 0, scale, coef, ids + r0,
+                          (const uint16_t *)w_train, p->ld_w};
+        if (launch_gemm<EpiStore, false>(gh, eh, stream) != hipSuccess) return DVP_ERR_HIP;
+        // dW (+)= E^T [v, rows_pad] . ((diag(s) H)^T [d, rows_pad])^T, then the sampled tokens' rows
+        GemmArgs gw;
+        gw.A = Et; gw.lda = L.block_pad; gw.B = ht; gw.ldb = L.block_pad;
+        gw.M = v; gw.N = d; gw.K = rows_pad; gw.scale = 1.0f;
+        const EpiStore ew{d_w, p->ld_w, r0 > 0, nullptr, nullptr, nullptr, nullptr, 0};
+        if (launch_gemm<EpiStore, false>(gw, ew, stream) != hipSuccess) return DVP_ERR_HIP;
+        for (int q0 = 0; q0 < rows; q0 += kOnehotRows) {   // in row order: launches on one stream run in order
+            const int qrows = (rows - q0) < kOnehotRows ? (rows - q0) : kOnehotRows;
+            hipLaunchKernelGGL(onehot_dw_kernel, dim3(qrows), dim3(kOnehotThreads), 0, stream, ids + r0 + q0,
+                               coef + q0, hblock + (int64_t)q0 * p->ld_hidden, p->ld_hidden, d_w, p->ld_w, qrows, d);
+            DVP_CHECK_LAUNCH();
+        }
+        return DVP_OK;
+    };
+    auto transpose_w = [&]() -> dvp_status {
         hipLaunchKernelGGL(transpose_bf16_kernel, dim3((d + 31) / 32, (L.v_pad + 31) / 32), dim3(32, 8), 0, stream,
                            (const uint16_t *)w_train, p->ld_w, wt, (int64_t)L.v_pad, v, d, L.v_pad, (const float *)nullptr);
         DVP_CHECK_LAUNCH();
+        return DVP_OK;
+    };
+
+    if (phase == LM_BACKWARD_SAVED) {
+        if ((rc = transpose_w()) != DVP_OK) return rc;
+        float *coef = (float *)(ws + L.off_coef), *scale = (float *)(ws + L.off_scale);
         for (int r0 = 0; r0 < n; r0 += kRowBlock) {
             const int rows = (n - r0) < kRowBlock ? (n - r0) : kRowBlock;
-            const int rows_pad = (rows + BM - 1) / BM * BM;
-            if ((rc = forward(0, r0, rows, true, st)) != DVP_OK) return rc;
-            const uint16_t *hblock = (const uint16_t *)hidden + (int64_t)r0 * p->ld_hidden;
-            hipLaunchKernelGGL(transpose_bf16_kernel, dim3((d + 31) / 32, (rows_pad + 31) / 32), dim3(32, 8), 0, stream,
-                               hblock, p->ld_hidden, ht, (int64_t)L.block_pad, rows, d, rows_pad, (const float *)st.scale);
+            use_block(r0);
+            hipLaunchKernelGGL(apply_grad_kernel, dim3((rows + tb - 1) / tb), dim3(tb), 0, stream, coef, scale,
+                               (const float *)unit_coef + r0, (const float *)unit_scale + r0, grad_out + r0, rows);
             DVP_CHECK_LAUNCH();
-            // dH[r0 : r0 + rows, :] = diag(s) . E [rows, v_pad] . (W^T [d, v_pad])^T + diag(q) . W[y, :]
-            GemmArgs gh;
-            gh.A = E; gh.lda = L.v_pad; gh.B = wt; gh.ldb = L.v_pad;
-            gh.M = rows; gh.N = d; gh.K = L.v_pad;
-            const EpiStore eh{d_hidden + (int64_t)r0 * p->ld_hidden, p->ld_hidden, 0, st.scale, st.coef, ids + r0,
-                              (const uint16_t *)w_train, p->ld_w};
-            if (launch_gemm<EpiStore, false>(gh, eh, stream) != hipSuccess) return DVP_ERR_HIP;
-            // dW (+)= E^T [v, rows_pad] . ((diag(s) H)^T [d, rows_pad])^T, then the sampled tokens' rows
-            GemmArgs gw;
-            gw.A = Et; gw.lda = L.block_pad; gw.B = ht; gw.ldb = L.block_pad;
-            gw.M = v; gw.N = d; gw.K = rows_pad;
-            const EpiStore ew{d_w, p->ld_w, r0 > 0, nullptr, nullptr, nullptr, nullptr, 0};
-            if (launch_gemm<EpiStore, false>(gw, ew, stream) != hipSuccess) return DVP_ERR_HIP;
-            for (int q0 = 0; q0 < rows; q0 += kOnehotRows) {   // in row order: launches on one stream run in order
-                const int qrows = (rows - q0) < kOnehotRows ? (rows - q0) : kOnehotRows;
-                hipLaunchKernelGGL(onehot_dw_kernel, dim3(qrows), dim3(kOnehotThreads), 0, stream, ids + r0 + q0,
-                                   (const float *)st.coef + q0, hblock + (int64_t)q0 * p->ld_hidden, p->ld_hidden,
-                                   d_w, p->ld_w, qrows, d);
-                DVP_CHECK_LAUNCH();
-            }
+            if ((rc = backward_block(r0, rows, coef, scale)) != DVP_OK) return rc;
+        }
+        return DVP_OK;
+    }
+    if (phase == LM_FORWARD_SAVE) {
+        for (int r0 = 0; r0 < n; r0 += kRowBlock) {
+            const int rows = (n - r0) < kRowBlock ? (n - r0) : kRowBlock;
+            use_block(r0);
+            if ((rc = forward(0, r0, rows, true, st)) != DVP_OK) return rc;
+        }
+    } else if (!grad_out) {
+        if ((rc = forward(0, 0, n, false, st)) != DVP_OK) return rc;
+    } else {
+        // training side with gradient, in blocks of kRowBlock token rows
+        if ((rc = transpose_w()) != DVP_OK) return rc;
+        for (int r0 = 0; r0 < n; r0 += kRowBlock) {
+            const int rows = (n - r0) < kRowBlock ? (n - r0) : kRowBlock;
+            if ((rc = forward(0, r0, rows, true, st)) != DVP_OK) return rc;
+            if ((rc = backward_block(r0, rows, st.coef, st.scale)) != DVP_OK) return rc;
         }
     }
     if (infer_side) {
@@ -920,6 +998,35 @@ dvp_status dvp_fused_lmhead(const dvp_lmhead_params *p, const void *hidden, cons
 {
     return dvp::run_lmhead(p, hidden, w_train, w_infer, nullptr, ids, grad_out, out_train, out_infer, row_flags,
                            d_hidden, d_w, workspace, workspace_bytes, stream);
+}
+
+size_t dvp_fused_lmhead_saved_bytes(const dvp_lmhead_params *p)
+{
+    if (!dvp::lm_params_ok(p)) return 0;
+    return dvp::lm_saved_layout(p->n_rows, p->vocab).total;
+}
+
+dvp_status dvp_fused_lmhead_forward(const dvp_lmhead_params *p, const void *hidden, const void *w_train,
+                                    const void *w_infer, const dvp_lmhead_f8_side *infer8, const int64_t *ids,
+                                    const dvp_side_out *out_train, const dvp_side_out *out_infer,
+                                    uint8_t *row_flags, void *saved, size_t saved_bytes, void *workspace,
+                                    size_t workspace_bytes, void *stream)
+{
+    if (w_infer && infer8) return DVP_ERR_PARAM;
+    return dvp::run_lmhead(p, hidden, w_train, w_infer, infer8, ids, nullptr, out_train, out_infer, row_flags,
+                           nullptr, nullptr, workspace, workspace_bytes, stream, dvp::LM_FORWARD_SAVE, saved,
+                           saved_bytes);
+}
+
+dvp_status dvp_fused_lmhead_backward(const dvp_lmhead_params *p, const void *hidden, const void *w_train,
+                                     const int64_t *ids, const float *grad_out, const void *saved,
+                                     size_t saved_bytes, float *d_hidden, float *d_w, void *workspace,
+                                     size_t workspace_bytes, void *stream)
+{
+    if (!grad_out || !d_hidden || !d_w) return p ? DVP_ERR_NULL : DVP_ERR_NULL;
+    return dvp::run_lmhead(p, hidden, w_train, nullptr, nullptr, ids, grad_out, nullptr, nullptr, nullptr, d_hidden,
+                           d_w, workspace, workspace_bytes, stream, dvp::LM_BACKWARD_SAVED, (void *)saved,
+                           saved_bytes);
 }
 
 dvp_status dvp_fused_lmhead_f8infer(const dvp_lmhead_params *p, const void *hidden, const void *w_train,

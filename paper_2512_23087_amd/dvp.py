@@ -23,7 +23,8 @@ ROW_Y_IN_TRAIN_SAFE, ROW_Y_IN_INFER_SAFE, ROW_ID_OUT_OF_RANGE, ROW_GRAD_OVERFLOW
 EXPORTS = ("dvp_forward", "dvp_backward", "dvp_forward_backward", "dvp_fused_lmhead",
            "dvp_fused_lmhead_workspace_bytes", "dvp_log_rho", "dvp_status_string", "dvp_row_path",
            "dvp_sequence_weights", "dvp_log_threshold", "dvp_forward_backward_sparse",
-           "dvp_fused_lmhead_f8infer", "dvp_lists_to_dense")
+           "dvp_fused_lmhead_f8infer", "dvp_lists_to_dense", "dvp_fused_lmhead_saved_bytes",
+           "dvp_fused_lmhead_forward", "dvp_fused_lmhead_backward")
 
 
 class DvpParams(ctypes.Structure):
@@ -86,6 +87,14 @@ def lib():
         L.dvp_fused_lmhead_f8infer.restype = ctypes.c_int
         L.dvp_fused_lmhead_f8infer.argtypes = [lp, vp, vp, ctypes.POINTER(DvpLmHeadF8Side), i64p, vp, sp, sp, vp, vp,
                                                vp, vp, ctypes.c_size_t, vp]
+        L.dvp_fused_lmhead_saved_bytes.restype = ctypes.c_size_t
+        L.dvp_fused_lmhead_saved_bytes.argtypes = [lp]
+        L.dvp_fused_lmhead_forward.restype = ctypes.c_int
+        L.dvp_fused_lmhead_forward.argtypes = [lp, vp, vp, vp, ctypes.POINTER(DvpLmHeadF8Side), i64p, sp, sp, vp, vp,
+                                               ctypes.c_size_t, vp, ctypes.c_size_t, vp]
+        L.dvp_fused_lmhead_backward.restype = ctypes.c_int
+        L.dvp_fused_lmhead_backward.argtypes = [lp, vp, vp, i64p, vp, vp, ctypes.c_size_t, vp, vp, vp,
+                                                ctypes.c_size_t, vp]
         L.dvp_log_rho.restype = ctypes.c_float
         L.dvp_log_rho.argtypes = [ctypes.c_double]
         L.dvp_status_string.restype = ctypes.c_char_p
@@ -386,6 +395,66 @@ def dvp_fused_lmhead(hidden, w_train, w_infer, ids, grad_out, log_rho_value, *, 
     if st != 0:
         raise DvpError(st, "dvp_fused_lmhead")
     return LmHeadResult(out_train, out_infer, row_flags, d_hidden, d_w)
+
+
+class LmHeadSaved:
+    """What dvp_fused_lmhead_forward leaves for dvp_fused_lmhead_backward."""
+
+    def __init__(self, params, saved, workspace, hidden, w_train, ids):
+        self.params, self.saved, self.workspace = params, saved, workspace
+        self.hidden, self.w_train, self.ids = hidden, w_train, ids
+
+
+def dvp_fused_lmhead_forward(hidden, w_train, w_infer, ids, log_rho_value, *, lse_full=False, infer_f8=None,
+                             saved: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                             stream=None):
+    """Forward of both sides; keeps what the backward needs.  Returns (LmHeadResult without gradients, LmHeadSaved)."""
+    for name, t in (("hidden", hidden), ("w_train", w_train)):
+        if not t.is_cuda or t.dtype != torch.bfloat16 or t.dim() != 2 or t.stride(1) != 1:
+            raise ValueError("%s must be a bf16 [rows, d] GPU tensor with unit inner stride" % name)
+    n, d = hidden.shape
+    v = w_train.shape[0]
+    dev = hidden.device
+    p = DvpLmHeadParams(n, d, v, hidden.stride(0), w_train.stride(0), float(log_rho_value))
+    if workspace is None:
+        workspace = torch.empty(max(int(lib().dvp_fused_lmhead_workspace_bytes(ctypes.byref(p))), 256),
+                                dtype=torch.uint8, device=dev)
+    if saved is None:
+        saved = torch.empty(max(int(lib().dvp_fused_lmhead_saved_bytes(ctypes.byref(p))), 256), dtype=torch.uint8,
+                            device=dev)
+    out_train = SideOutputs(n, v, dev, lse_full, False)
+    has_infer = w_infer is not None or infer_f8 is not None
+    out_infer = SideOutputs(n, v, dev, lse_full, False) if has_infer else None
+    row_flags = torch.empty(n, dtype=torch.uint8, device=dev)
+    side = None
+    if infer_f8 is not None:
+        h8, w8, scale = infer_f8
+        side = ctypes.byref(DvpLmHeadF8Side(h8.data_ptr(), w8.data_ptr(), h8.stride(0), w8.stride(0), float(scale)))
+    st = lib().dvp_fused_lmhead_forward(ctypes.byref(p), _ptr(hidden), _ptr(w_train), _ptr(w_infer), side, _ptr(ids),
+                                        ctypes.byref(out_train.struct()),
+                                        ctypes.byref(out_infer.struct()) if out_infer is not None else None,
+                                        _ptr(row_flags), _ptr(saved), saved.numel(), _ptr(workspace),
+                                        workspace.numel(), _stream(stream))
+    if st != 0:
+        raise DvpError(st, "dvp_fused_lmhead_forward")
+    return (LmHeadResult(out_train, out_infer, row_flags, None, None),
+            LmHeadSaved(p, saved, workspace, hidden, w_train, ids))
+
+
+def dvp_fused_lmhead_backward(kept: LmHeadSaved, grad_out, *, d_hidden=None, d_w=None, stream=None):
+    """dH, dW from what the forward kept and the now known grad_out."""
+    p = kept.params
+    dev = kept.hidden.device
+    if d_hidden is None:
+        d_hidden = torch.empty(p.n_rows, p.ld_hidden, dtype=torch.float32, device=dev)[:, :p.hidden]
+    if d_w is None:
+        d_w = torch.empty(p.vocab, p.ld_w, dtype=torch.float32, device=dev)[:, :p.hidden]
+    st = lib().dvp_fused_lmhead_backward(ctypes.byref(p), _ptr(kept.hidden), _ptr(kept.w_train), _ptr(kept.ids),
+                                         _ptr(grad_out), _ptr(kept.saved), kept.saved.numel(), _ptr(d_hidden),
+                                         _ptr(d_w), _ptr(kept.workspace), kept.workspace.numel(), _stream(stream))
+    if st != 0:
+        raise DvpError(st, "dvp_fused_lmhead_backward")
+    return d_hidden, d_w
 
 
 class SequenceResult:

@@ -377,3 +377,72 @@ def test_f8_engine_rejects_bad_arguments(dvp):
     with pytest.raises(ValueError):
         dvp.dvp_fused_lmhead(wl.hidden, wl.w_train, wl.w_infer, wl.ids, None, lr,
                              infer_f8=(wl.hidden8, wl.w8, wl.scale_infer))
+
+
+# ---------------------------------------------------------------------------
+# forward and backward in two calls (grad_out known only after the forward)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("shape", [(200, 128, 1000), (2 * 8192 + 300, 64, 700), (513, 384, 777)])
+def test_forward_then_backward_equals_the_fused_call(dvp, shape):
+    n, d, v = shape
+    wl = workloads.make_lmhead(device="cuda", n=n, d=d, v=v)
+    with torch.no_grad():
+        wl.ids[1] = -3                      # an id out of range: no gradient from that row
+    lr = dvp.log_rho(1e-3)
+    fused = dvp.dvp_fused_lmhead(wl.hidden, wl.w_train, wl.w_infer, wl.ids, wl.grad_out, lr, lse_full=True)
+    fwd, kept = dvp.dvp_fused_lmhead_forward(wl.hidden, wl.w_train, wl.w_infer, wl.ids, lr, lse_full=True)
+    kept.workspace.fill_(0x5a)              # the workspace need not survive between the two calls
+    dh, dw = dvp.dvp_fused_lmhead_backward(kept, wl.grad_out)
+    torch.cuda.synchronize()
+    for side in ("train", "infer"):
+        for k in ("logp", "row_max", "lse_safe", "lse_full", "safe_count"):
+            a, b = getattr(getattr(fwd, side), k), getattr(getattr(fused, side), k)
+            assert torch.equal(torch.nan_to_num(a.float(), nan=-1.0), torch.nan_to_num(b.float(), nan=-1.0)), (side, k)
+    assert torch.equal(fwd.row_flags, fused.row_flags)
+    # the same E and the same products; only the row factor s = g * (-1 / S) instead of -g / S differs, by
+    # one fp32 rounding: invisible in dH (applied in fp32), and in dW it can move a bf16 rounding of s H
+    assert (dh - fused.d_hidden).abs().max().item() <= 1e-5 * fused.d_hidden.abs().max().item()
+    assert (dw - fused.d_w).abs().max().item() <= 2e-3 * fused.d_w.abs().max().item()
+    # and a second backward with another grad_out from the same saved state
+    g2 = -2.0 * wl.grad_out
+    dh2, dw2 = dvp.dvp_fused_lmhead_backward(kept, g2)
+    fused2 = dvp.dvp_fused_lmhead(wl.hidden, wl.w_train, None, wl.ids, g2, lr)
+    torch.cuda.synchronize()
+    assert (dh2 - fused2.d_hidden).abs().max().item() <= 1e-5 * fused2.d_hidden.abs().max().item()
+    assert (dw2 - fused2.d_w).abs().max().item() <= 2e-3 * fused2.d_w.abs().max().item()
+
+
+def test_two_call_gradient_against_oracle(dvp):
+    wl = workloads.make_lmhead(device="cuda", n=300, d=128, v=1500)
+    lr = dvp.log_rho(1e-4)
+    fwd, kept = dvp.dvp_fused_lmhead_forward(wl.hidden, wl.w_train, wl.w_infer, wl.ids, lr)
+    dh, dw = dvp.dvp_fused_lmhead_backward(kept, wl.grad_out)
+    torch.cuda.synchronize()
+    ids = wl.ids.cpu().numpy()
+    g = wl.grad_out.cpu().numpy().astype(np.float64)
+    ot = orc.lmhead(wl.hidden.cpu(), wl.w_train.cpu(), ids, np.float32(lr), grad_out=g, band=BAND, threads=8)
+    H64, W64 = wl.hidden.cpu().double().numpy(), wl.w_train.cpu().double().numpy()
+    soft = np.abs(ot["dz"]); safe_rows = np.nonzero(ot["y_in_safe"])[0]
+    soft[safe_rows, ids[safe_rows]] = 0.0
+    bound_h = 2.0 ** -8 * (soft @ np.abs(W64)) + 1e-5 + 2.0 ** -20 * np.abs(ot["d_hidden"])
+    bound_w = 2.0 ** -7 * (soft.T @ np.abs(H64)) + 1e-5 + 2.0 ** -20 * np.abs(ot["d_w"])
+    assert (np.abs(dh.cpu().double().numpy() - ot["d_hidden"]) / bound_h).max() <= 1.0
+    assert (np.abs(dw.cpu().double().numpy() - ot["d_w"]) / bound_w).max() <= 1.0
+
+
+def test_two_call_form_with_the_8bit_engine_and_bad_arguments(dvp):
+    wl = workloads.make_lmhead(device="cuda", n=200, d=128, v=1000, f8_engine=True)
+    lr = dvp.log_rho(1e-4)
+    ref = dvp.dvp_fused_lmhead(wl.hidden, wl.w_train, None, wl.ids, None, lr,
+                               infer_f8=(wl.hidden8, wl.w8, wl.scale_infer))
+    fwd, kept = dvp.dvp_fused_lmhead_forward(wl.hidden, wl.w_train, None, wl.ids, lr,
+                                             infer_f8=(wl.hidden8, wl.w8, wl.scale_infer))
+    torch.cuda.synchronize()
+    assert torch.equal(fwd.infer.logp, ref.infer.logp) and torch.equal(fwd.train.logp, ref.train.logp)
+    with pytest.raises(dvp.DvpError) as e:      # saved buffer too small
+        dvp.dvp_fused_lmhead_forward(wl.hidden, wl.w_train, None, wl.ids, lr,
+                                     saved=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == 6
+    with pytest.raises(dvp.DvpError) as e:
+        dvp.dvp_fused_lmhead_backward(kept, None)
+    assert e.value.status == 1

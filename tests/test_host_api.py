@@ -195,6 +195,23 @@ def test_lmhead_argument_validation_needs_no_gpu():
     assert call(P(), hidden=FAKE + 8) == 4
     assert call(P(), bytes_=16) == 6 and call(P(), workspace=None) == 6
 
+    # forward and backward as two calls
+    assert L.dvp_fused_lmhead_saved_bytes(ctypes.byref(P(n=300, v=1000))) >= 2 * 512 * 1024 * 2
+    assert L.dvp_fused_lmhead_saved_bytes(ctypes.byref(P(d=100))) == 0
+
+    def fwd(p, saved=ws, saved_bytes=1 << 40, w_infer=FAKE, side=None):
+        return L.dvp_fused_lmhead_forward(ctypes.byref(p), FAKE, FAKE, w_infer, side, FAKE, ctypes.byref(so),
+                                          ctypes.byref(so), FAKE, saved, saved_bytes, ws, 1 << 40, None)
+
+    def bwd(p, grad=FAKE, saved=ws, saved_bytes=1 << 40, dh=FAKE, dw=FAKE):
+        return L.dvp_fused_lmhead_backward(ctypes.byref(p), FAKE, FAKE, FAKE, grad, saved, saved_bytes, dh, dw, ws,
+                                           1 << 40, None)
+
+    assert fwd(P(n=0)) == 0 and bwd(P(n=0)) == 0
+    assert fwd(P(), saved=None) == 6 and fwd(P(), saved_bytes=100) == 6 and fwd(P(), saved=FAKE + 16) == 6
+    assert bwd(P(), grad=None) == 1 and bwd(P(), dh=None) == 1 and bwd(P(), saved_bytes=100) == 6
+    assert fwd(P(d=96)) == 5 and bwd(P(lr=0.5)) == 3
+
     def call8(p, side, hidden=FAKE):
         return L.dvp_fused_lmhead_f8infer(ctypes.byref(p), hidden, FAKE, side, FAKE, None, ctypes.byref(so),
                                           ctypes.byref(so), FAKE, None, None, ws, 1 << 40, None)
@@ -210,3 +227,5 @@ def test_lmhead_argument_validation_needs_no_gpu():
     assert call8(P(), S(ld_h=136)) == 5             # byte rows not 16-byte aligned
     assert call8(P(), S(w=FAKE + 8)) == 4
     assert call8(P(n=0), S()) == 0
+    assert fwd(P(), side=S()) == 3                  # a bf16 and an 8-bit inference side at once
+    assert fwd(P(), w_infer=None, side=S(scale=0.0)) == 3

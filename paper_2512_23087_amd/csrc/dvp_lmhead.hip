@@ -24,6 +24,8 @@
 // that form too.
 #include <math.h>
 
+#include <atomic>
+
 #include "dvp_device.h"
 #include "dvp_internal.h"
 
@@ -531,27 +533,27 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs
 
 static int gemm_cu_count()
 {
-    static int cached = 0;
-    if (cached == 0) {
+    static std::atomic<int> cached{0};   // callers may come from several host threads
+    if (cached.load(std::memory_order_relaxed) == 0) {
         int dev = 0, n = 0;
         if (hipGetDevice(&dev) == hipSuccess &&
             hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-            cached = n;
+            cached.store(n, std::memory_order_relaxed);
         else
             return 256;
     }
-    return cached;
+    return cached.load(std::memory_order_relaxed);
 }
 
 template <class Epi, bool NEEDS_FINISH, bool F8 = false>
 static hipError_t launch_gemm(const GemmArgs &g, const Epi &epi, hipStream_t stream)
 {
-    static bool configured = false;
-    if (!configured) {   // more than 64 KB of LDS per workgroup has to be asked for
+    static std::atomic<bool> configured{false};
+    if (!configured.load(std::memory_order_acquire)) {   // more than 64 KB of LDS per workgroup has to be asked for
         hipError_t e = hipFuncSetAttribute((const void *)gemm_nt_kernel<Epi, NEEDS_FINISH, F8>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
         if (e != hipSuccess) return e;
-        configured = true;
+        configured.store(true, std::memory_order_release);
     }
     const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
     const int total = tiles_m * tiles_n;

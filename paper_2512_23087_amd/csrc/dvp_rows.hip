@@ -11,6 +11,8 @@
 // (one V = 151936 bf16 row is 297 KB; a CU's register file is 512 KB) so HBM
 // sees every logit once; the streaming kernel re-reads the row per phase and
 // takes any shape or alignment.
+#include <atomic>
+
 #include "dvp_device.h"
 #include "dvp_internal.h"
 
@@ -914,16 +916,16 @@ __global__ __launch_bounds__(kListsScatterThreads) void lists_scatter_kernel(con
 // ---------------------------------------------------------------------------
 static int device_cu_count()
 {
-    static int cached = 0;
-    if (cached == 0) {
+    static std::atomic<int> cached{0};   // callers may come from several host threads
+    if (cached.load(std::memory_order_relaxed) == 0) {
         int dev = 0, n = 0;
         if (hipGetDevice(&dev) == hipSuccess &&
             hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-            cached = n;
+            cached.store(n, std::memory_order_relaxed);
         else
             return 256;
     }
-    return cached;
+    return cached.load(std::memory_order_relaxed);
 }
 
 template <typename Kernel>
@@ -940,8 +942,12 @@ static hipError_t launch_resident_inst(const RowArgs &a, hipStream_t stream)
     void (*kernel)(const RowArgs);
     if constexpr (F8_INFER) kernel = rows_resident_f8infer_kernel<T, NV, NVFULL, NT, MINW, EXTRAS>;
     else                    kernel = rows_resident_kernel<T, NV, NVFULL, NT, MINW, EXTRAS, OVF>;
-    static int per_cu = 0;
-    if (per_cu == 0) per_cu = blocks_per_cu(kernel, NT);
+    static std::atomic<int> per_cu_cache{0};
+    int per_cu = per_cu_cache.load(std::memory_order_relaxed);
+    if (per_cu == 0) {
+        per_cu = blocks_per_cu(kernel, NT);
+        per_cu_cache.store(per_cu, std::memory_order_relaxed);
+    }
     int64_t grid = (int64_t)device_cu_count() * per_cu;
     if (grid > a.n_rows) grid = a.n_rows;
     hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(NT), 0, stream, a);

@@ -96,3 +96,33 @@ def test_lmhead_replayed_from_a_graph(dvp):
         assert torch.equal(res.train.logp, ref.train.logp) and torch.equal(res.infer.logp, ref.infer.logp)
         assert torch.equal(res.row_flags, ref.row_flags)
     assert first.train.logp.shape == res.train.logp.shape
+
+
+def test_concurrent_callers_on_their_own_streams(dvp):
+    """The library keeps no state between calls: host threads with a stream each get the same results
+    as one thread."""
+    import threading
+    wls = [workloads.make_rows(2, device="cuda", n=64, v=40000), workloads.make_rows(3, device="cuda", n=64, v=32000)]
+    lr = dvp.log_rho(1e-4)
+    ref = [dvp.dvp_forward_backward(w.z_train, w.z_infer, w.ids, w.grad_out, lr) for w in wls]
+    torch.cuda.synchronize()
+    out, errs = [None, None], []
+
+    def work(i):
+        try:
+            s = torch.cuda.Stream()
+            s.wait_stream(torch.cuda.default_stream())
+            with torch.cuda.stream(s):
+                for _ in range(20):
+                    out[i] = dvp.dvp_forward_backward(wls[i].z_train, wls[i].z_infer, wls[i].ids, wls[i].grad_out, lr)
+            s.synchronize()
+        except Exception as e:          # noqa: BLE001 - reported below
+            errs.append(e)
+
+    ts = [threading.Thread(target=work, args=(i,)) for i in range(2)]
+    [t.start() for t in ts]
+    [t.join() for t in ts]
+    assert not errs, errs
+    for i in range(2):
+        assert torch.equal(out[i].dz, ref[i].dz) and torch.equal(out[i].train.logp, ref[i].train.logp)
+        assert torch.equal(out[i].row_flags, ref[i].row_flags)

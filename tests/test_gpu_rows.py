@@ -332,3 +332,16 @@ def test_rows_on_both_sides_of_the_list_capacity(dvp, dtype):
     counts = res.train.safe_count.cpu().numpy()
     assert (counts <= 64).sum() >= 5 and (counts > 64).sum() >= 5 and counts.max() < 2000
     _run_case(dvp, wl, 1e-6, backward=True, threads=4)
+
+
+def test_a_million_short_rows(dvp):
+    """Many more rows than workgroups, a row of three 16-byte vectors: every row against the oracle."""
+    n, v = (1 << 20) + 3, 24
+    g = torch.Generator(device="cuda").manual_seed(12)
+    zt = (3.0 * torch.randn(n, v, generator=g, device="cuda")).to(torch.bfloat16)
+    zi = (zt.float() + 0.05 * torch.randn(n, v, generator=g, device="cuda")).to(torch.bfloat16)
+    ids = torch.randint(0, v, (n,), generator=g, device="cuda")
+    go = torch.randn(n, generator=g, device="cuda")
+    wl = workloads.RowWorkload(name="short", z_train=zt, z_infer=zi, ids=ids, grad_out=go, rhos=[])
+    st = _run_case(dvp, wl, 1e-1, backward=True, threads=8)
+    assert 0.05 < st["train"]["y_in_safe"].mean() < 0.95      # both kinds of rows in numbers

@@ -684,26 +684,46 @@ __global__ __launch_bounds__(kOnehotThreads) void onehot_dw_kernel(const int64_t
 }
 
 // out[c, r] = bf16(scale[r] * in[r, c]) (scale null: a plain copy) for r < rows, c < cols;
-// out rows are ld_out long and zero padded up to rows_pad
-__global__ void transpose_bf16_kernel(const uint16_t *in, int64_t ld_in, uint16_t *out, int64_t ld_out,
-                                      int rows, int cols, int rows_pad, const float *scale)
+// out rows are ld_out long and zero padded up to rows_pad.  64 x 64 tiles, 16-byte accesses on both
+// sides: cols and ld_in are multiples of 8 (cols of 64), rows_pad and ld_out multiples of 64.
+constexpr int kTrTile = 64, kTrThreads = 256;
+__global__ __launch_bounds__(kTrThreads) void transpose_bf16_kernel(const uint16_t *in, int64_t ld_in, uint16_t *out,
+                                                                    int64_t ld_out, int rows, int cols, int rows_pad,
+                                                                    const float *scale)
 {
-    __shared__ uint16_t tile[32][33];
-    const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
-    const int tx = threadIdx.x, ty = threadIdx.y;     // 32 x 8
-    for (int k = ty; k < 32; k += 8) {
-        const int r = r0 + k, c = c0 + tx;
-        uint16_t v = 0;
-        if (r < rows && c < cols) {
-            v = in[(int64_t)r * ld_in + c];
-            if (scale) v = (uint16_t)f32_to_bf16_rne(scale[r] * __uint_as_float((uint32_t)v << 16));
+    __shared__ __attribute__((aligned(16))) uint16_t tile[kTrTile][kTrTile + 8];   // 144-byte rows: 16-byte aligned, skewed banks
+    const int r0 = blockIdx.y * kTrTile, c0 = blockIdx.x * kTrTile;
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int k = 0; k < kTrTile * 8 / kTrThreads; ++k) {
+        const int p = tid + k * kTrThreads, r = p >> 3, ch = p & 7;
+        const int row = r0 + r;
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (row < rows && c0 + ch * 8 < cols) {
+            v = *(const u32x4 *)(in + (int64_t)row * ld_in + c0 + ch * 8);
+            if (scale) {
+                const float sc = scale[row];
+                uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float lo = sc * __uint_as_float(w[i] << 16), hi = sc * __uint_as_float(w[i] & 0xffff0000u);
+                    w[i] = f32_to_bf16_rne(lo) | (f32_to_bf16_rne(hi) << 16);
+                }
+                v = (u32x4){w[0], w[1], w[2], w[3]};
+            }
         }
-        tile[k][tx] = v;
+        *(u32x4 *)&tile[r][ch * 8] = v;
     }
     __syncthreads();
-    for (int k = ty; k < 32; k += 8) {
-        const int c = c0 + k, r = r0 + tx;
-        if (c < cols && r < rows_pad) out[(int64_t)c * ld_out + r] = tile[tx][k];
+#pragma unroll
+    for (int k = 0; k < kTrTile * 8 / kTrThreads; ++k) {
+        const int p = tid + k * kTrThreads, c = p & 63, ch = p >> 6;   // lanes of a wavefront: 64 columns, one row chunk
+        if (c0 + c >= cols || r0 + ch * 8 >= rows_pad) continue;
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            w[i] = (uint32_t)tile[ch * 8 + 2 * i][c] | ((uint32_t)tile[ch * 8 + 2 * i + 1][c] << 16);
+        *(u32x4 *)(out + (int64_t)(c0 + c) * ld_out + r0 + ch * 8) = (u32x4){w[0], w[1], w[2], w[3]};
     }
 }
 
@@ -914,7 +934,8 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
     auto backward_block = [&](int r0, int rows, const float *coef, const float *scale) -> dvp_status {
         const int rows_pad = (rows + BM - 1) / BM * BM;
         const uint16_t *hblock = (const uint16_t *)hidden + (int64_t)r0 * p->ld_hidden;
-        hipLaunchKernelGGL(transpose_bf16_kernel, dim3((d + 31) / 32, (rows_pad + 31) / 32), dim3(32, 8), 0, stream,
+        hipLaunchKernelGGL(transpose_bf16_kernel, dim3((d + kTrTile - 1) / kTrTile, (rows_pad + kTrTile - 1) / kTrTile),
+                           dim3(kTrThreads), 0, stream,
                            hblock, p->ld_hidden, ht, (int64_t)L.block_pad, rows, d, rows_pad, scale);
         DVP_CHECK_LAUNCH();
         // dH[r0 : r0 + rows, :] = diag(s) . E [rows, v_pad] . (W^T [d, v_pad])^T + diag(q) . W[y, :]
@@ -939,7 +960,8 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
         return DVP_OK;
     };
     auto transpose_w = [&]() -> dvp_status {
-        hipLaunchKernelGGL(transpose_bf16_kernel, dim3((d + 31) / 32, (L.v_pad + 31) / 32), dim3(32, 8), 0, stream,
+        hipLaunchKernelGGL(transpose_bf16_kernel, dim3((d + kTrTile - 1) / kTrTile, (L.v_pad + kTrTile - 1) / kTrTile),
+                           dim3(kTrThreads), 0, stream,
                            (const uint16_t *)w_train, p->ld_w, wt, (int64_t)L.v_pad, v, d, L.v_pad, (const float *)nullptr);
         DVP_CHECK_LAUNCH();
         return DVP_OK;

@@ -263,7 +263,8 @@ size_t dvp_fused_lmhead_workspace_bytes(const dvp_lmhead_params *params);
  *   d_w       DEVICE float [V, ld_w], overwritten
  *   workspace DEVICE, 256-byte aligned, at least the size reported above;
  *             contents on entry are ignored and on exit are unspecified.
- * safe_bits and entropy members of the output structs must be NULL (not produced here).
+ * The entropy member of the output structs must be NULL (not produced here); safe_bits is produced
+ * (membership of every token at the fp32-accumulated logit the matrix cores delivered).
  */
 dvp_status dvp_fused_lmhead(const dvp_lmhead_params *params, const void *hidden,
                             const void *w_train, const void *w_infer, const int64_t *ids,

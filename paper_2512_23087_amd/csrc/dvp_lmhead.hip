@@ -135,7 +135,8 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)   // hardwar
 // E [rows (padded to 256), ld_e] and transposed in Et [columns (padded), ld_et];
 // rows beyond M and columns beyond N are stored as zeros (they pad the K
 // dimension of the two gradient products).
-template <bool WRITE_E>
+// WRITE_BITS: also store the side's membership bitmask.
+template <bool WRITE_E, bool WRITE_BITS = false>
 struct EpiSum {
     static constexpr bool kUsesTileLds = WRITE_E;   // the bf16 staging lives in the operand tiles
     RowStats st;
@@ -143,6 +144,8 @@ struct EpiSum {
     const int64_t *ids;      // WRITE_E: the sampled token's own entry of E is stored as zero
     uint16_t *E, *Et;
     int64_t ld_e, ld_et;
+    uint32_t *bits;          // membership bitmask [n_rows, bits_ld] of the side, or null
+    int64_t bits_ld;
     __device__ __forceinline__ void operator()(const GemmArgs &g, f32x16 (&acc)[MI][NI], int r0, int c0, int lane, uint8_t *lds, int wave, int wn) const
     {
         const bool want_full = st.part_f != nullptr;
@@ -166,6 +169,11 @@ struct EpiSum {
                     const int col = c0 + ni * 32 + (lane % 32);
                     const float z = acc[mi][ni][i];
                     float kept = 0.0f;
+                    if constexpr (WRITE_BITS) {   // lanes 0..31 hold 32 consecutive columns of one row, lanes 32..63 of the row 4 below
+                        const unsigned long long b = __builtin_amdgcn_ballot_w64(col < g.N && row_ok && z >= tau);
+                        const int64_t w = (c0 + ni * 32) >> 5;
+                        if ((lane % 32) == 0 && row_ok && w < bits_ld) bits[(int64_t)row * bits_ld + w] = (uint32_t)(b >> (lane & 32));
+                    }
                     if (col < g.N && row_ok) {
                         const bool safe = z >= tau;
                         c += safe ? 1 : 0;
@@ -831,8 +839,7 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
     if (!hidden || !w_train || !ids || (!out_train && phase != LM_BACKWARD_SAVED)) return DVP_ERR_NULL;
     if (grad_out && (!d_hidden || !d_w)) return DVP_ERR_NULL;
     if (phase == LM_BACKWARD_SAVED && !grad_out) return DVP_ERR_NULL;
-    if ((out_train && (out_train->safe_bits || out_train->entropy)) ||
-        ((w_infer || f8) && out_infer && (out_infer->safe_bits || out_infer->entropy)))
+    if ((out_train && out_train->entropy) || ((w_infer || f8) && out_infer && out_infer->entropy))
         return DVP_ERR_UNSUPPORTED;
     if (((uintptr_t)hidden | (uintptr_t)w_train | (uintptr_t)w_infer) % 16) return DVP_ERR_ALIGN;
     if (f8) {
@@ -856,10 +863,15 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
     char *ws = (char *)workspace;
     const void *w_side[2] = {w_train, w_infer};
     SideOut outs[2];
+    uint32_t *side_bits[2];
     for (int s = 0; s < 2; ++s) {
         const dvp_side_out *o = s == 0 ? out_train : (infer_side ? out_infer : nullptr);
         outs[s] = SideOut{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
-        if (o) outs[s] = SideOut{o->logp, o->row_max, o->lse_safe, o->lse_full, o->safe_count, nullptr};
+        side_bits[s] = nullptr;
+        if (o) {
+            outs[s] = SideOut{o->logp, o->row_max, o->lse_safe, o->lse_full, o->safe_count, nullptr};
+            side_bits[s] = o->safe_bits;
+        }
     }
     uint16_t *ht = (uint16_t *)(ws + L.off_ht), *wt = (uint16_t *)(ws + L.off_wt);
     uint16_t *E = (uint16_t *)(ws + L.off_e), *Et = (uint16_t *)(ws + L.off_et);   // of the current row block
@@ -891,6 +903,8 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
         if (o.safe_count) o.safe_count += r0;
         const int nb = (rows + tb - 1) / tb;
         const bool bytes = s == 1 && f8 != nullptr;
+        const int64_t bits_ld = (v + 31) / 32;
+        uint32_t *bits = side_bits[s] ? side_bits[s] + (int64_t)r0 * bits_ld : nullptr;
         GemmArgs g;
         g.A = (const uint16_t *)hidden + (int64_t)r0 * p->ld_hidden; g.lda = p->ld_hidden;
         g.B = (const uint16_t *)w_side[s]; g.ldb = p->ld_w;
@@ -909,17 +923,20 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
         }
         hipLaunchKernelGGL(after_max_kernel, dim3(nb), dim3(tb), 0, stream, st, rows, p->log_rho);
         DVP_CHECK_LAUNCH();
+        // pass B in the build that matches the side: 8-bit operands or bf16, with E or not, with the bitmask or not
+        hipError_t eb;
+        const int64_t lde = L.v_pad, ldet = L.block_pad;
         if (bytes) {
-            if (launch_gemm<EpiSum<false>, true, true>(g, EpiSum<false>{st, rows, nullptr, nullptr, nullptr, 0, 0}, stream) !=
-                hipSuccess)
-                return DVP_ERR_HIP;
+            eb = bits ? launch_gemm<EpiSum<false, true>, true, true>(g, EpiSum<false, true>{st, rows, nullptr, nullptr, nullptr, 0, 0, bits, bits_ld}, stream)
+                      : launch_gemm<EpiSum<false>, true, true>(g, EpiSum<false>{st, rows, nullptr, nullptr, nullptr, 0, 0, nullptr, 0}, stream);
         } else if (write_e) {
-            if (launch_gemm<EpiSum<true>, true>(g, EpiSum<true>{st, rows, ids + r0, E, Et, (int64_t)L.v_pad, (int64_t)L.block_pad},
-                                                stream) != hipSuccess) return DVP_ERR_HIP;
+            eb = bits ? launch_gemm<EpiSum<true, true>, true>(g, EpiSum<true, true>{st, rows, ids + r0, E, Et, lde, ldet, bits, bits_ld}, stream)
+                      : launch_gemm<EpiSum<true>, true>(g, EpiSum<true>{st, rows, ids + r0, E, Et, lde, ldet, nullptr, 0}, stream);
         } else {
-            if (launch_gemm<EpiSum<false>, true>(g, EpiSum<false>{st, rows, nullptr, nullptr, nullptr, 0, 0}, stream) != hipSuccess)
-                return DVP_ERR_HIP;
+            eb = bits ? launch_gemm<EpiSum<false, true>, true>(g, EpiSum<false, true>{st, rows, nullptr, nullptr, nullptr, 0, 0, bits, bits_ld}, stream)
+                      : launch_gemm<EpiSum<false>, true>(g, EpiSum<false>{st, rows, nullptr, nullptr, nullptr, 0, 0, nullptr, 0}, stream);
         }
+        if (eb != hipSuccess) return DVP_ERR_HIP;
         hipLaunchKernelGGL(after_sum_kernel, dim3((rows + kAfterRows - 1) / kAfterRows),
                            dim3(kAfterRows * kAfterSegs), 0, stream, st, o, ids + r0,
                            grad_out ? grad_out + r0 : nullptr, row_flags ? row_flags + r0 : nullptr, rows, v,

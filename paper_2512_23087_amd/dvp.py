@@ -348,7 +348,7 @@ def lmhead_workspace_bytes(n, d, v, ld_hidden=None, ld_w=None) -> int:
     return int(lib().dvp_fused_lmhead_workspace_bytes(ctypes.byref(p)))
 
 
-def dvp_fused_lmhead(hidden, w_train, w_infer, ids, grad_out, log_rho_value, *, lse_full=False,
+def dvp_fused_lmhead(hidden, w_train, w_infer, ids, grad_out, log_rho_value, *, lse_full=False, safe_bits=False,
                      workspace: Optional[torch.Tensor] = None, d_hidden=None, d_w=None,
                      stream=None, infer_f8=None) -> LmHeadResult:
     """infer_f8 = (hidden8, w8, scale): the inference side is an 8-bit engine with float8_e4m3fn
@@ -369,8 +369,8 @@ def dvp_fused_lmhead(hidden, w_train, w_infer, ids, grad_out, log_rho_value, *, 
     need = int(lib().dvp_fused_lmhead_workspace_bytes(ctypes.byref(p)))
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
-    out_train = SideOutputs(n, v, dev, lse_full, False)
-    out_infer = SideOutputs(n, v, dev, lse_full, False) if (w_infer is not None or infer_f8 is not None) else None
+    out_train = SideOutputs(n, v, dev, lse_full, safe_bits)
+    out_infer = SideOutputs(n, v, dev, lse_full, safe_bits) if (w_infer is not None or infer_f8 is not None) else None
     row_flags = torch.empty(n, dtype=torch.uint8, device=dev)
     if grad_out is not None:
         if d_hidden is None:

@@ -446,3 +446,28 @@ def test_two_call_form_with_the_8bit_engine_and_bad_arguments(dvp):
     with pytest.raises(dvp.DvpError) as e:
         dvp.dvp_fused_lmhead_backward(kept, None)
     assert e.value.status == 1
+
+
+def test_membership_bits(dvp):
+    """The bitmask of both sides against the oracle's flags, token by token, for every token whose fp64
+    logit is farther than the band from the threshold (inside the band the fp32 logit decides)."""
+    wl = workloads.make_lmhead(device="cuda", n=300, d=128, v=1500 + 13)
+    for rho in (1e-2, 1e-4, 0.0):
+        lr = dvp.log_rho(rho)
+        res = dvp.dvp_fused_lmhead(wl.hidden, wl.w_train, wl.w_infer, wl.ids, wl.grad_out, lr, safe_bits=True)
+        plain = dvp.dvp_fused_lmhead(wl.hidden, wl.w_train, wl.w_infer, wl.ids, wl.grad_out, lr)
+        torch.cuda.synchronize()
+        v = wl.w_train.shape[0]
+        for side, w in ((res.train, wl.w_train), (res.infer, wl.w_infer)):
+            o = orc.lmhead(wl.hidden.cpu(), w.cpu(), wl.ids.cpu().numpy(), np.float32(lr), want_flags=True, band=BAND,
+                           threads=8)
+            got = side.flags_matrix(v).cpu().numpy()
+            tau_ideal = o["row_max"] + float(lr)
+            clear = np.abs(o["z"] - tau_ideal[:, None]) > BAND if np.isfinite(lr) else np.ones_like(got, bool)
+            np.testing.assert_array_equal(got[clear], o["safe_flags"][clear])
+            np.testing.assert_array_equal(got.sum(1), side.safe_count.cpu().numpy())     # the bits are the counted set
+            words = side.safe_bits.cpu().numpy().view(np.uint32)
+            assert np.all((words[:, -1] >> (v % 32)) == 0)
+        # asking for the bits changes nothing else
+        assert torch.equal(res.d_w, plain.d_w) and torch.equal(res.train.logp, plain.train.logp)
+        assert torch.equal(res.infer.safe_count, plain.infer.safe_count)

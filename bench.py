@@ -104,11 +104,24 @@ def bench_lmhead(args):
     import torch
     from paper_2512_23087_amd import dvp, workloads
     f8 = args.infer_dtype == "f8"
-    wl = workloads.make_lmhead(device="cuda:0", n=args.rows, f8_engine=f8)
+    wl = workloads.make_lmhead(device="cuda:0", n=args.rows, f8_engine=f8, hidden_scale=args.hidden_scale)
+    lists_cap = args.sparse_grad            # --sparse-grad on this workload: the gradient kept as per-row lists
+    if lists_cap and (f8 or args.split_lists):
+        print("bench.py: --sparse-grad on the lmhead workload goes with neither --infer-dtype f8 nor --split-lists",
+              file=sys.stderr)
+        sys.exit(2)
     n, d = wl.hidden.shape
     v = wl.w_train.shape[0]
     lr = dvp.log_rho(args.rho)
-    ws = torch.empty(dvp.lmhead_workspace_bytes(n, d, v), dtype=torch.uint8, device="cuda:0")
+    if lists_cap:
+        import ctypes
+        pl = dvp.DvpLmHeadParams(n, d, v, wl.hidden.stride(0), wl.w_train.stride(0), lr)
+        ws = torch.empty(int(dvp.lib().dvp_fused_lmhead_lists_workspace_bytes(ctypes.byref(pl), lists_cap)),
+                         dtype=torch.uint8, device="cuda:0")
+        entries = torch.empty(n, lists_cap, 2, dtype=torch.int32, device="cuda:0")
+        grad_len = torch.empty(n, dtype=torch.int32, device="cuda:0")
+    else:
+        ws = torch.empty(dvp.lmhead_workspace_bytes(n, d, v), dtype=torch.uint8, device="cuda:0")
     dh = torch.empty(n, d, dtype=torch.float32, device="cuda:0")
     dw = torch.empty(v, d, dtype=torch.float32, device="cuda:0")
 
@@ -119,8 +132,13 @@ def bench_lmhead(args):
         saved = torch.empty(int(dvp.lib().dvp_fused_lmhead_saved_bytes(ctypes.byref(p))), dtype=torch.uint8,
                             device="cuda:0")
 
+    last = {}
+
     def step():
-        if two_calls:
+        if lists_cap:
+            last["res"] = dvp.dvp_fused_lmhead_lists(wl.hidden, wl.w_train, wl.w_infer, wl.ids, wl.grad_out, lr, lists_cap,
+                                                     workspace=ws, d_hidden=dh, d_w=dw, entries=entries, grad_len=grad_len)
+        elif two_calls:
             _, kept = dvp.dvp_fused_lmhead_forward(wl.hidden, wl.w_train, None if f8 else wl.w_infer, wl.ids, lr,
                                                    infer_f8=(wl.hidden8, wl.w8, wl.scale_infer) if f8 else None,
                                                    saved=saved, workspace=ws)
@@ -137,11 +155,21 @@ def bench_lmhead(args):
     ms = sum(per_launch) / len(per_launch)
     gemm = 2.0 * n * v * d
     useful, executed = 4 * gemm, 6 * gemm          # train fwd, infer fwd, dH, dW; vs the passes actually run
+    extra = {}
+    if lists_cap:
+        res = last["res"]
+        over = int(((res.row_flags & dvp.ROW_GRAD_OVERFLOW) != 0).sum().item())
+        listed = int(torch.where((res.row_flags & dvp.ROW_GRAD_OVERFLOW) != 0, torch.zeros_like(res.grad_len),
+                                 res.grad_len).sum().item())
+        # two forwards as matrix products (each run twice), the gradient as |lists| x d multiply-adds, twice
+        useful, executed = 2 * gemm + 4.0 * listed * d, 4 * gemm + 4.0 * listed * d
+        extra = {"list_cap": lists_cap, "list_entries": listed, "rows_over_cap": over,
+                 "mean_safe_set": float(res.train.safe_count.float().mean().item())}
     # (each side's forward produces the logits twice: row max first, then sums at the threshold)
     # Peak for the mix of passes: each contraction is priced at the peak of its own operand type, so the
     # call's floor is sum(flop_i / peak_i) and the peak quoted is executed flop over that floor.
     n_f8 = 2 if f8 else 0
-    floor_s = ((6 - n_f8) * gemm / MFMA_BF16_PEAK_TFLOPS + n_f8 * gemm / MFMA_FP8_PEAK_TFLOPS) / 1e12
+    floor_s = ((executed / gemm - n_f8) * gemm / MFMA_BF16_PEAK_TFLOPS + n_f8 * gemm / MFMA_FP8_PEAK_TFLOPS) / 1e12
     peak = executed / floor_s / 1e12
     result = {
         "metric": "DVP fused LM-head fwd+bwd rows/s and MFMA TFLOP/s, V=%d bf16" % v,
@@ -151,15 +179,18 @@ def bench_lmhead(args):
         "config": {"workload": ("configs[4]: hidden [%d, %d] bf16 x W [%d, %d] bf16 (train); inference side an 8-bit "
                                 "engine: E4M3 activations and head with per-tensor factors, rho=%g" if f8 else
                                 "configs[4]: hidden [%d, %d] bf16 x W [%d, %d] bf16 (train) and its "
-                                "fp8-e4m3-rounded copy (infer), rho=%g") % (n, d, v, d, args.rho),
-                   "entry_point": "dvp_fused_lmhead_forward + dvp_fused_lmhead_backward" if two_calls else
+                                "fp8-e4m3-rounded copy (infer), rho=%g") % (n, d, v, d, args.rho)
+                               + (", hidden states scaled by %g (peaked rows)" % args.hidden_scale
+                                  if args.hidden_scale != 1.0 else ""),
+                   "entry_point": "dvp_fused_lmhead_lists" if lists_cap else
+                                  "dvp_fused_lmhead_forward + dvp_fused_lmhead_backward" if two_calls else
                                   "dvp_fused_lmhead_f8infer" if f8 else "dvp_fused_lmhead",
-                   "workspace_bytes": ws.numel(), "saved_bytes": saved.numel() if two_calls else 0},
+                   "workspace_bytes": ws.numel(), "saved_bytes": saved.numel() if two_calls else 0, **extra},
         "roofline": {"bound": "mfma", "achieved": executed / (ms * 1e-3) / 1e12,
                      "peak": peak, "unit": "TFLOP/s",
                      "frac": executed / (ms * 1e-3) / 1e12 / peak, "traffic": None,
-                     "kernel": "gemm_nt_kernel (6 GEMM passes of 2*N*V*d flop each per call%s)"
-                               % (": 4 bf16 at 2.5 PFLOP/s peak, 2 fp8 at 5.0" if f8 else ""),
+                     "kernel": "gemm_nt_kernel (%d GEMM passes of 2*N*V*d flop each per call%s)"
+                               % (4 if lists_cap else 6, ": 4 bf16 at 2.5 PFLOP/s peak, 2 fp8 at 5.0" if f8 else ""),
                      "kernel_ms_avg": ms, "executed_tflop": executed / 1e12,
                      "useful_tflop": useful / 1e12,
                      "useful_tflops": useful / (ms * 1e-3) / 1e12},
@@ -232,6 +263,9 @@ def main():
                          "the flow of a caller that learns grad_out only after the forward: one step = "
                          "dvp_forward_backward_sparse with grad_out = 1 (lists of at most CAP entries) followed by "
                          "dvp_lists_to_dense with the real grad_out (dense gradient, logits not read again)")
+    ap.add_argument("--hidden-scale", type=float, default=1.0,
+                    help="(lmhead workload) multiply the hidden states: 20 gives peaked rows with a few safe tokens "
+                         "each; with --sparse-grad CAP one step = dvp_fused_lmhead_lists")
     ap.add_argument("--infer-dtype", default="same", choices=["same", "f8"],
                     help="f8: the inference logits are rounded through E4M3 (saturating) and handed over as "
                          "one byte per token")

@@ -273,6 +273,38 @@ dvp_status dvp_fused_lmhead(const dvp_lmhead_params *params, const void *hidden,
                             float *d_w, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The LM-head variant with the gradient kept as per-row lists (Prop. 5.4: dz is zero outside the safe
+ * set).  Where safe sets are short (peaked distributions: a handful of tokens per row) dz has a few
+ * entries per row and the two gradient products are not matrix products any more: dH_i is a sum of
+ * |V_S| rows of W, dW_k a sum of the hidden states of the rows whose safe set holds k.  The call runs
+ * the four forward passes of dvp_fused_lmhead (no block of masked exponentials is kept: workspace is
+ * small), collects each row's safe tokens in the second training pass, and forms dH and dW from the
+ * lists in fp32: four GEMM passes instead of six, and no entry of dz passes through bf16.
+ *   entries, grad_len, list_cap   as for dvp_forward_backward_sparse, with list_cap at most 1024;
+ *              a row's entries come out sorted by token; what lies beyond grad_len[i] in a row of
+ *              entries is unspecified.  grad_len and row_flags are required.
+ *   A row with |V_S| > list_cap gets DVP_ROW_GRAD_OVERFLOW and no entries; its row of d_hidden is
+ *   zero and it adds nothing to d_w: the caller runs dvp_fused_lmhead on those rows and adds.
+ *   d_hidden  DEVICE float [N, ld_hidden], overwritten;  d_w  DEVICE float [V, ld_w], overwritten;
+ *              both 16-byte aligned.
+ *   out_train / out_infer: safe_bits and entropy must be NULL.
+ *   workspace  DEVICE, 256-byte aligned, dvp_fused_lmhead_lists_workspace_bytes(params, list_cap) bytes
+ *              (0: invalid params, or list_cap outside 1..1024, or N * list_cap >= 2^31).
+ * All sums have a fixed order (a row's entries by token, a token's rows by row): results are run-to-run
+ * identical.  Cost grows with the lists (|lists| x d multiply-adds, one workgroup per row and per
+ * token): meant for list_cap well below the vocabulary.
+ */
+size_t dvp_fused_lmhead_lists_workspace_bytes(const dvp_lmhead_params *params, int32_t list_cap);
+
+dvp_status dvp_fused_lmhead_lists(const dvp_lmhead_params *params, const void *hidden,
+                                  const void *w_train, const void *w_infer, const int64_t *ids,
+                                  const float *grad_out, const dvp_side_out *out_train,
+                                  const dvp_side_out *out_infer, uint8_t *row_flags,
+                                  dvp_grad_entry *entries, int32_t *grad_len, int32_t list_cap,
+                                  float *d_hidden, float *d_w, void *workspace,
+                                  size_t workspace_bytes, void *stream);
+
+/*
  * The LM-head variant in two calls, for callers that learn grad_out only after the forward (with
  * importance weights dL/dlogp depends on the log-probs).  Prop. 5.4's gradient is linear in grad_out, so
  * the forward leaves the masked exponentials of the training side (bf16, both orientations, every row

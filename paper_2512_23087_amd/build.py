@@ -14,7 +14,7 @@ PKG = Path(__file__).resolve().parent
 CSRC = PKG / "csrc"
 OBJ = PKG / "_build"
 LIB = PKG / "libdvp_hip.so"
-SOURCES = ["dvp_api.hip", "dvp_rows.hip", "dvp_lmhead.hip", "dvp_sequences.hip"]
+SOURCES = ["dvp_api.hip", "dvp_rows.hip", "dvp_lmhead.hip", "dvp_lmhead_lists.hip", "dvp_sequences.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -30,7 +30,7 @@ def _compile(src: str) -> Path:
 def build(verbose: bool = True) -> Path:
     """Compile every source for gfx950 and link libdvp_hip.so next to this file."""
     OBJ.mkdir(exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(4, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=min(5, len(SOURCES))) as ex:
         objs = list(ex.map(_compile, SOURCES))
     tmp = LIB.with_suffix(".so.tmp%d" % os.getpid())
     subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-rdc",

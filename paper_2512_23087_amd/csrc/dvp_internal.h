@@ -101,6 +101,31 @@ struct SequenceArgs {
     float log_threshold;
 };
 
+// LM-head variant with the gradient kept as per-row lists (launch_lmhead_lists_backward): what pass B's
+// epilogue left behind, and where dH = dz W and dW = dz^T H go.
+constexpr int kLmListMax = 1024;  // longest list the LM-head variant sorts in LDS
+struct LmListArgs {
+    dvp_grad_entry *entries;      // [n, list_cap]; in: (token, exp(z - m)) in arrival order; out: (token, dz) by token
+    int32_t *grad_len;            // [n] out
+    uint8_t *row_flags;           // [n] in/out (DVP_ROW_GRAD_OVERFLOW is added)
+    const int32_t *safe_count;    // [n]
+    const int64_t *ids;           // [n]
+    const float *coef, *scale;    // [n] q = c (1 - p_y) and s = -c / S
+    const uint16_t *W;            // [v, ld_w] bf16
+    const uint16_t *H;            // [n, ld_h] bf16
+    int64_t ld_w, ld_h;
+    float *d_hidden;              // [n, ld_h]
+    float *d_w;                   // [v, ld_w]
+    int32_t n, d, v, list_cap;
+    // column-major copy of the lists: workspace
+    int32_t *blk_cnt;             // [n_blk, v]
+    int32_t *col_start;           // [v + 1]
+    int32_t *grp_total;           // [ceil(v / 256) + 1]
+    int32_t *csc_row;             // [n * list_cap]
+    float *csc_val;               // [n * list_cap]
+    int32_t n_blk, rows_per_blk;
+};
+
 // true when the register-resident kernel can take rows of this many elements
 // (dtype: training rows and gradient; dtype_infer: inference rows)
 bool row_fits_resident(int dtype, int dtype_infer, int64_t vocab);
@@ -112,5 +137,6 @@ hipError_t launch_grad_fill(int dtype, const FillArgs &a, hipStream_t stream);
 hipError_t launch_backward(int dtype, const BackwardArgs &a, bool vector_ok, hipStream_t stream);
 hipError_t launch_lists_to_dense(int dtype, const ListsArgs &a, bool vector_ok, hipStream_t stream);
 hipError_t launch_sequences(const SequenceArgs &a, hipStream_t stream);
+hipError_t launch_lmhead_lists_backward(const LmListArgs &a, hipStream_t stream);
 
 }  // namespace dvp

@@ -136,7 +136,10 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)   // hardwar
 // rows beyond M and columns beyond N are stored as zeros (they pad the K
 // dimension of the two gradient products).
 // WRITE_BITS: also store the side's membership bitmask.
-template <bool WRITE_E, bool WRITE_BITS = false>
+// WRITE_LIST: also append every safe token of a row, with exp(z - m), to that row's list (arrival
+// order; at most list_cap entries are kept, the cursor stops a little above that).  Meant for rows
+// whose safe sets are short: the branch is then rarely taken.
+template <bool WRITE_E, bool WRITE_BITS = false, bool WRITE_LIST = false>
 struct EpiSum {
     static constexpr bool kUsesTileLds = WRITE_E;   // the bf16 staging lives in the operand tiles
     RowStats st;
@@ -146,6 +149,9 @@ struct EpiSum {
     int64_t ld_e, ld_et;
     uint32_t *bits;          // membership bitmask [n_rows, bits_ld] of the side, or null
     int64_t bits_ld;
+    dvp_grad_entry *entries; // WRITE_LIST: [n_rows, list_cap]
+    int *cursor;             // WRITE_LIST: [n_rows] entries appended so far, zero before the launch
+    int list_cap;
     __device__ __forceinline__ void operator()(const GemmArgs &g, f32x16 (&acc)[MI][NI], int r0, int c0, int lane, uint8_t *lds, int wave, int wn) const
     {
         const bool want_full = st.part_f != nullptr;
@@ -185,6 +191,18 @@ struct EpiSum {
                             kept = __expf(z - m);
                         }
                         s += kept;
+                        if constexpr (WRITE_LIST) {
+                            if (safe) {
+                                int *cur = cursor + row;   // read past the L1: a full list stops the appends
+                                if (__hip_atomic_load(cur, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) <= list_cap) {
+                                    const int pos = atomicAdd(cur, 1);
+                                    if (pos < list_cap) {
+                                        dvp_grad_entry *e = entries + (int64_t)row * list_cap + pos;
+                                        e->index = (uint32_t)col; e->value = kept;
+                                    }
+                                }
+                            }
+                        }
                     }
                     if constexpr (WRITE_E) acc[mi][ni][i] = (int64_t)col == y ? 0.0f : kept;   // the accumulators now hold E
                 }
@@ -556,12 +574,17 @@ static int gemm_cu_count()
 template <class Epi, bool NEEDS_FINISH, bool F8 = false>
 static hipError_t launch_gemm(const GemmArgs &g, const Epi &epi, hipStream_t stream)
 {
-    static std::atomic<bool> configured{false};
-    if (!configured.load(std::memory_order_acquire)) {   // more than 64 KB of LDS per workgroup has to be asked for
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_nt_kernel<Epi, NEEDS_FINISH, F8>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
+    // More than 64 KB of LDS per workgroup has to be asked for, once per device (bit d: device d has it).
+    static std::atomic<uint64_t> configured{0};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t bit = 1ull << (dev & 63);
+    if (dev > 63 || !(configured.load(std::memory_order_acquire) & bit)) {
+        e = hipFuncSetAttribute((const void *)gemm_nt_kernel<Epi, NEEDS_FINISH, F8>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
         if (e != hipSuccess) return e;
-        configured.store(true, std::memory_order_release);
+        configured.fetch_or(bit, std::memory_order_release);
     }
     const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
     const int total = tiles_m * tiles_n;
@@ -748,7 +771,7 @@ struct LmLayout {
     int block_pad, v_pad, col_tiles;
 };
 
-static LmLayout lm_layout(int64_t n, int64_t d, int64_t v)
+static LmLayout lm_layout(int64_t n, int64_t d, int64_t v, bool dense_buffers = true)
 {
     LmLayout L;
     const int64_t block = n < kRowBlock ? n : kRowBlock;
@@ -766,10 +789,43 @@ static LmLayout lm_layout(int64_t n, int64_t d, int64_t v)
     }
     L.off_coef = take(n * 4);
     L.off_scale = take(n * 4);
-    L.off_ht = take((size_t)d * L.block_pad * 2);
-    L.off_wt = take((size_t)d * L.v_pad * 2);
-    L.off_e = take((size_t)L.block_pad * L.v_pad * 2);
-    L.off_et = take((size_t)L.v_pad * L.block_pad * 2);
+    L.off_ht = L.off_wt = L.off_e = L.off_et = 0;
+    if (dense_buffers) {
+        L.off_ht = take((size_t)d * L.block_pad * 2);
+        L.off_wt = take((size_t)d * L.v_pad * 2);
+        L.off_e = take((size_t)L.block_pad * L.v_pad * 2);
+        L.off_et = take((size_t)L.v_pad * L.block_pad * 2);
+    }
+    L.total = o;
+    return L;
+}
+
+// The list form keeps no E: per-row statistics as above, then the list cursors, the safe-set sizes and
+// the column-major copy of the lists.  Rows are cut into at most 256 blocks for the counting sort.
+struct LmListLayout {
+    LmLayout stats;
+    size_t total, off_cursor, off_count, off_blk, off_colstart, off_grp, off_cscrow, off_cscval;
+    int n_blk, rows_per_blk;
+};
+
+static LmListLayout lm_list_layout(int64_t n, int64_t d, int64_t v, int64_t cap)
+{
+    LmListLayout L;
+    L.stats = lm_layout(n, d, v, false);
+    int64_t per = (n + 255) / 256;
+    if (per < 64) per = 64;
+    L.rows_per_blk = (int)per;
+    L.n_blk = (int)((n + per - 1) / per);
+    if (L.n_blk < 1) L.n_blk = 1;
+    size_t o = L.stats.total;
+    auto take = [&](size_t bytes) { size_t at = o; o += align256(bytes); return at; };
+    L.off_cursor = take(n * 4);
+    L.off_count = take(n * 4);
+    L.off_blk = take((size_t)L.n_blk * v * 4);
+    L.off_colstart = take((size_t)(v + 1) * 4);
+    L.off_grp = take((size_t)((v + 255) / 256 + 1) * 4);
+    L.off_cscrow = take((size_t)n * cap * 4);
+    L.off_cscval = take((size_t)n * cap * 4);
     L.total = o;
     return L;
 }
@@ -1021,9 +1077,126 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
     return DVP_OK;
 }
 
+static bool lm_list_cap_ok(const dvp_lmhead_params *p, int32_t cap)
+{
+    return cap >= 1 && cap <= kLmListMax && p->n_rows * (int64_t)cap < ((int64_t)1 << 31);
+}
+
+__global__ void zero_cursor_kernel(int *p, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
+// List form of the call: the four forward passes as above (no row blocks: nothing of size N x V is kept),
+// pass B of the training side appending to the lists, then the list kernels for dH and dW.
+static dvp_status run_lmhead_lists(const dvp_lmhead_params *p, const void *hidden, const void *w_train,
+                                   const void *w_infer, const int64_t *ids, const float *grad_out,
+                                   const dvp_side_out *out_train, const dvp_side_out *out_infer, uint8_t *row_flags,
+                                   dvp_grad_entry *entries, int32_t *grad_len, int32_t list_cap, float *d_hidden,
+                                   float *d_w, void *workspace, size_t workspace_bytes, void *stream_)
+{
+    if (!p) return DVP_ERR_NULL;
+    if (p->log_rho != p->log_rho || p->log_rho > 0.0f) return DVP_ERR_PARAM;
+    if (p->n_rows < 0 || p->vocab < 1 || p->hidden < 1 || p->ld_hidden < p->hidden || p->ld_w < p->hidden)
+        return DVP_ERR_SHAPE;
+    if (list_cap < 1) return DVP_ERR_PARAM;
+    if (!lm_params_ok(p) || !lm_list_cap_ok(p, list_cap)) return DVP_ERR_UNSUPPORTED;
+    if (p->n_rows == 0) return DVP_OK;
+    if (!hidden || !w_train || !ids || !grad_out || !out_train || !row_flags || !entries || !grad_len || !d_hidden ||
+        !d_w)
+        return DVP_ERR_NULL;
+    if (out_train->entropy || (w_infer && out_infer && out_infer->entropy)) return DVP_ERR_UNSUPPORTED;
+    if (out_train->safe_bits || (w_infer && out_infer && out_infer->safe_bits)) return DVP_ERR_UNSUPPORTED;
+    if (((uintptr_t)hidden | (uintptr_t)w_train | (uintptr_t)w_infer | (uintptr_t)d_hidden | (uintptr_t)d_w) % 16)
+        return DVP_ERR_ALIGN;
+    if (((uintptr_t)entries % 8) || ((uintptr_t)grad_len % 4)) return DVP_ERR_ALIGN;
+    const LmListLayout LL = lm_list_layout(p->n_rows, p->hidden, p->vocab, list_cap);
+    const LmLayout &L = LL.stats;
+    if (!workspace || ((uintptr_t)workspace % 256) || workspace_bytes < LL.total) return DVP_ERR_WORKSPACE;
+
+    hipStream_t stream = (hipStream_t)stream_;
+    const int n = (int)p->n_rows, d = (int)p->hidden, v = (int)p->vocab;
+    char *ws = (char *)workspace;
+    int *cursor = (int *)(ws + LL.off_cursor);
+    const int tb = 256, nb = (n + tb - 1) / tb;
+#define DVP_CHECK_LAUNCH() do { if (hipGetLastError() != hipSuccess) return DVP_ERR_HIP; } while (0)
+    hipLaunchKernelGGL(zero_cursor_kernel, dim3(nb), dim3(tb), 0, stream, cursor, n);
+    DVP_CHECK_LAUNCH();
+    RowStats st0;
+    int32_t *count0 = nullptr;
+    for (int s = 0; s < (w_infer ? 2 : 1); ++s) {
+        RowStats st;
+        st.max_key = (int *)(ws + L.off_i32[s]); st.zy = (float *)(ws + L.off_zy[s]);
+        st.m = (float *)(ws + L.off_m[s]); st.tau = (float *)(ws + L.off_tau[s]);
+        st.coef = (float *)(ws + L.off_coef); st.scale = (float *)(ws + L.off_scale);
+        st.part_s = (float *)(ws + L.off_ps[s]); st.part_c = (int *)(ws + L.off_pc[s]);
+        const dvp_side_out *so = s == 0 ? out_train : out_infer;
+        SideOut o = SideOut{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+        if (so) o = SideOut{so->logp, so->row_max, so->lse_safe, so->lse_full, so->safe_count, nullptr};
+        if (s == 0) {
+            if (!o.safe_count) o.safe_count = (int32_t *)(ws + LL.off_count);   // the list kernels need the sizes
+            count0 = o.safe_count;
+            st0 = st;
+        }
+        st.part_f = o.lse_full ? (float *)(ws + L.off_pf[s]) : nullptr;
+        GemmArgs g;
+        g.A = (const uint16_t *)hidden; g.lda = p->ld_hidden;
+        g.B = (const uint16_t *)(s == 0 ? w_train : w_infer); g.ldb = p->ld_w;
+        g.M = n; g.N = v; g.K = d; g.scale = 1.0f;
+        hipLaunchKernelGGL(init_stats_kernel, dim3(nb), dim3(tb), 0, stream, st, n);
+        DVP_CHECK_LAUNCH();
+        if (launch_gemm<EpiMax, false>(g, EpiMax{st, ids}, stream) != hipSuccess) return DVP_ERR_HIP;
+        hipLaunchKernelGGL(after_max_kernel, dim3(nb), dim3(tb), 0, stream, st, n, p->log_rho);
+        DVP_CHECK_LAUNCH();
+        hipError_t eb;
+        if (s == 0)
+            eb = launch_gemm<EpiSum<false, false, true>, true>(
+                g, EpiSum<false, false, true>{st, n, nullptr, nullptr, nullptr, 0, 0, nullptr, 0, entries, cursor, list_cap}, stream);
+        else
+            eb = launch_gemm<EpiSum<false>, true>(g, EpiSum<false>{st, n, nullptr, nullptr, nullptr, 0, 0, nullptr, 0}, stream);
+        if (eb != hipSuccess) return DVP_ERR_HIP;
+        hipLaunchKernelGGL(after_sum_kernel, dim3((n + kAfterRows - 1) / kAfterRows), dim3(kAfterRows * kAfterSegs), 0,
+                           stream, st, o, ids, grad_out, row_flags, n, v, L.col_tiles, s, 0);
+        DVP_CHECK_LAUNCH();
+        if (s == 0) {   // before the inference side adds its bit to row_flags: the list kernels only add theirs
+            LmListArgs a;
+            a.entries = entries; a.grad_len = grad_len; a.row_flags = row_flags; a.safe_count = count0;
+            a.ids = ids; a.coef = st0.coef; a.scale = st0.scale;
+            a.W = (const uint16_t *)w_train; a.H = (const uint16_t *)hidden; a.ld_w = p->ld_w; a.ld_h = p->ld_hidden;
+            a.d_hidden = d_hidden; a.d_w = d_w;
+            a.n = n; a.d = d; a.v = v; a.list_cap = list_cap;
+            a.blk_cnt = (int32_t *)(ws + LL.off_blk); a.col_start = (int32_t *)(ws + LL.off_colstart);
+            a.grp_total = (int32_t *)(ws + LL.off_grp);
+            a.csc_row = (int32_t *)(ws + LL.off_cscrow); a.csc_val = (float *)(ws + LL.off_cscval);
+            a.n_blk = LL.n_blk; a.rows_per_blk = LL.rows_per_blk;
+            if (launch_lmhead_lists_backward(a, stream) != hipSuccess) return DVP_ERR_HIP;
+        }
+    }
+#undef DVP_CHECK_LAUNCH
+    return DVP_OK;
+}
+
 }  // namespace dvp
 
 extern "C" {
+
+size_t dvp_fused_lmhead_lists_workspace_bytes(const dvp_lmhead_params *p, int32_t list_cap)
+{
+    if (!dvp::lm_params_ok(p) || !dvp::lm_list_cap_ok(p, list_cap)) return 0;
+    return dvp::lm_list_layout(p->n_rows, p->hidden, p->vocab, list_cap).total;
+}
+
+dvp_status dvp_fused_lmhead_lists(const dvp_lmhead_params *p, const void *hidden, const void *w_train,
+                                  const void *w_infer, const int64_t *ids, const float *grad_out,
+                                  const dvp_side_out *out_train, const dvp_side_out *out_infer,
+                                  uint8_t *row_flags, dvp_grad_entry *entries, int32_t *grad_len,
+                                  int32_t list_cap, float *d_hidden, float *d_w, void *workspace,
+                                  size_t workspace_bytes, void *stream)
+{
+    return dvp::run_lmhead_lists(p, hidden, w_train, w_infer, ids, grad_out, out_train, out_infer, row_flags,
+                                 entries, grad_len, list_cap, d_hidden, d_w, workspace, workspace_bytes, stream);
+}
 
 size_t dvp_fused_lmhead_workspace_bytes(const dvp_lmhead_params *p)
 {

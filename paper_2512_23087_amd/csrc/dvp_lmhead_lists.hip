@@ -1,0 +1,250 @@
+// LM-head variant, gradient through per-row lists (Prop. 5.4: dz is zero outside
+// the safe set, so a row with a short safe set has a short gradient).
+//
+// Pass B's epilogue has appended every safe token of a row to that row's list in
+// arrival order, with exp(z - m).  Here each list is sorted by token and turned
+// into gradient entries, dH = dz W is summed per row in token order, the lists
+// are copied into column-major order (a counting sort whose positions do not
+// depend on the launch order) and dW = dz^T H is summed per token in row order:
+// every sum has a fixed order, results are run-to-run identical.  No matrix
+// product is involved: the work is |lists| x d multiply-adds.
+#include "dvp_internal.h"
+
+namespace dvp {
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+constexpr int kThreads = 256;
+constexpr int kWave = 64;
+
+__device__ __forceinline__ void fma8(float (&acc)[8], float v, const u32x4 w)
+{
+    const uint32_t x[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        acc[2 * i] += v * __uint_as_float(x[i] << 16);
+        acc[2 * i + 1] += v * __uint_as_float(x[i] & 0xffff0000u);
+    }
+}
+__device__ __forceinline__ void store8(float *dst, const float (&acc)[8])
+{
+    *(float4 *)dst = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    *(float4 *)(dst + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+}
+
+__device__ __forceinline__ int effective_len(const LmListArgs &a, int row)
+{
+    return (a.row_flags[row] & DVP_ROW_GRAD_OVERFLOW) ? 0 : a.grad_len[row];
+}
+
+// One workgroup per token row: flags and length, the list sorted by token, values turned into dz,
+// and the row of dH.
+__global__ __launch_bounds__(kThreads) void lm_lists_finish_kernel(const LmListArgs a)
+{
+    __shared__ unsigned long long key[kLmListMax];
+    __shared__ uint32_t tok[kLmListMax];
+    __shared__ float val[kLmListMax];
+    const int i = blockIdx.x, tid = threadIdx.x;
+    const int c = a.safe_count[i];
+    const uint32_t fl = a.row_flags[i];
+    const bool y_safe = (fl & DVP_ROW_Y_IN_TRAIN_SAFE) != 0;
+    const bool overflow = y_safe && c > a.list_cap;
+    const int len = (y_safe && !overflow) ? c : 0;     // <= list_cap <= kLmListMax
+    if (tid == 0) {
+        a.grad_len[i] = y_safe ? c : 0;
+        if (overflow) a.row_flags[i] = (uint8_t)(fl | DVP_ROW_GRAD_OVERFLOW);
+    }
+    float *dh = a.d_hidden + (int64_t)i * a.ld_h;
+    if (len == 0) {                                    // zero gradient, or left to the caller
+        const float zero[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+        for (int j0 = tid * 8; j0 < a.d; j0 += kThreads * 8) store8(dh + j0, zero);
+        return;
+    }
+    dvp_grad_entry *list = a.entries + (int64_t)i * a.list_cap;
+    int pow2 = 1;
+    while (pow2 < len) pow2 <<= 1;
+    for (int p = tid; p < pow2; p += kThreads) {
+        unsigned long long k = ~0ull;
+        if (p < len) k = ((unsigned long long)list[p].index << 32) | (unsigned long long)__float_as_uint(list[p].value);
+        key[p] = k;
+    }
+    for (int k = 2; k <= pow2; k <<= 1) {              // bitonic sort, ascending
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            __syncthreads();
+            for (int p = tid; p < pow2; p += kThreads) {
+                const int q = p ^ j;
+                if (q > p) {
+                    const unsigned long long x = key[p], y = key[q];
+                    const bool up = (p & k) == 0;
+                    if ((x > y) == up) { key[p] = y; key[q] = x; }
+                }
+            }
+        }
+    }
+    __syncthreads();
+    const uint32_t y = (uint32_t)a.ids[i];             // in range: the row's sampled token is safe
+    const float qy = a.coef[i], s = a.scale[i];
+    for (int p = tid; p < len; p += kThreads) {
+        const uint32_t t = (uint32_t)(key[p] >> 32);
+        const float e = __uint_as_float((uint32_t)key[p]);
+        const float g = t == y ? qy : s * e;           // Prop. 5.4, the sampled token's entry formed as c (1 - p_y)
+        tok[p] = t; val[p] = g;
+        list[p].index = t; list[p].value = g;
+    }
+    __syncthreads();
+    for (int j0 = tid * 8; j0 < a.d; j0 += kThreads * 8) {
+        float acc[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+        for (int p = 0; p < len; ++p)
+            fma8(acc, val[p], *(const u32x4 *)(a.W + (int64_t)tok[p] * a.ld_w + j0));
+        store8(dh + j0, acc);
+    }
+}
+
+__global__ void lm_zero_i32_kernel(int32_t *p, int64_t n)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = 0;
+}
+
+// blk_cnt[b][t] = number of rows of row block b whose list holds token t
+__global__ __launch_bounds__(kThreads) void lm_csc_count_kernel(const LmListArgs a)
+{
+    const int b = blockIdx.x, wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int r0 = b * a.rows_per_blk;
+    const int r1 = (r0 + a.rows_per_blk) < a.n ? (r0 + a.rows_per_blk) : a.n;
+    int32_t *cnt = a.blk_cnt + (int64_t)b * a.v;
+    for (int r = r0 + wave; r < r1; r += kThreads / kWave) {
+        const int len = effective_len(a, r);
+        const dvp_grad_entry *list = a.entries + (int64_t)r * a.list_cap;
+        for (int p = lane; p < len; p += kWave) atomicAdd(cnt + list[p].index, 1);
+    }
+}
+
+// Inclusive scan of one value per thread over a 256-thread workgroup, through LDS.
+__device__ __forceinline__ int block_scan_inclusive(int x, int *part, int tid)
+{
+    part[tid] = x;
+    __syncthreads();
+    for (int off = 1; off < kThreads; off <<= 1) {
+        const int add = tid >= off ? part[tid - off] : 0;
+        __syncthreads();
+        part[tid] += add;
+        __syncthreads();
+    }
+    return part[tid];
+}
+
+// per token: counts of the row blocks -> exclusive prefix over the blocks; the token's total is scanned
+// within the workgroup's 256 tokens (col_start[t] = entries of the workgroup's earlier tokens) and the
+// workgroup's total goes to grp_total
+__global__ __launch_bounds__(kThreads) void lm_csc_prefix_kernel(const LmListArgs a, int32_t *grp_total)
+{
+    __shared__ int part[kThreads];
+    const int tid = threadIdx.x, t = blockIdx.x * kThreads + tid;
+    int run = 0;
+    if (t < a.v) {
+        for (int b = 0; b < a.n_blk; ++b) {
+            int32_t *c = a.blk_cnt + (int64_t)b * a.v + t;
+            const int here = *c;
+            *c = run;
+            run += here;
+        }
+    }
+    const int incl = block_scan_inclusive(run, part, tid);
+    if (t < a.v) a.col_start[t] = incl - run;
+    if (tid == kThreads - 1) grp_total[blockIdx.x] = incl;
+}
+
+// grp_total[0 .. n_grp): totals -> exclusive prefix sums in place, grand total to grp_total[n_grp];
+// one workgroup, a contiguous chunk per thread (n_grp = ceil(v / 256) <= 2^14)
+__global__ __launch_bounds__(kThreads) void lm_csc_scan_kernel(int32_t *grp_total, int n_grp)
+{
+    __shared__ int part[kThreads];
+    const int tid = threadIdx.x;
+    const int per = (n_grp + kThreads - 1) / kThreads;
+    const int g0 = tid * per < n_grp ? tid * per : n_grp, g1 = (g0 + per) < n_grp ? (g0 + per) : n_grp;
+    int sum = 0;
+    for (int g = g0; g < g1; ++g) sum += grp_total[g];
+    const int incl = block_scan_inclusive(sum, part, tid);
+    int run = incl - sum;
+    for (int g = g0; g < g1; ++g) {
+        const int here = grp_total[g];
+        grp_total[g] = run;
+        run += here;
+    }
+    if (tid == kThreads - 1) grp_total[n_grp] = incl;
+}
+
+// col_start[t] += entries of the earlier workgroups' tokens; col_start[v] = all entries
+__global__ __launch_bounds__(kThreads) void lm_csc_offset_kernel(int32_t *col_start, const int32_t *grp_total, int v, int n_grp)
+{
+    const int t = blockIdx.x * kThreads + threadIdx.x;
+    if (t < v) col_start[t] += grp_total[blockIdx.x];
+    if (t == v) col_start[v] = grp_total[n_grp];
+}
+
+// One wavefront per row block walks its rows in order; entry (r, t) goes to position
+// col_start[t] + (rows before r that hold t): earlier blocks from the prefix, earlier rows of this
+// block from the running counter, which only this wavefront touches.
+__global__ __launch_bounds__(kWave) void lm_csc_fill_kernel(const LmListArgs a)
+{
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const int r0 = b * a.rows_per_blk;
+    const int r1 = (r0 + a.rows_per_blk) < a.n ? (r0 + a.rows_per_blk) : a.n;
+    int32_t *cnt = a.blk_cnt + (int64_t)b * a.v;
+    for (int r = r0; r < r1; ++r) {
+        const int len = effective_len(a, r);
+        const dvp_grad_entry *list = a.entries + (int64_t)r * a.list_cap;
+        for (int p = lane; p < len; p += kWave) {       // tokens of one row are distinct
+            const dvp_grad_entry e = list[p];
+            const int pos = a.col_start[e.index] + atomicAdd(cnt + e.index, 1);
+            a.csc_row[pos] = r;
+            a.csc_val[pos] = e.value;
+        }
+    }
+}
+
+// One workgroup per token: dW[t, :] = sum over the token's entries, in row order, of dz * H[row, :]
+__global__ __launch_bounds__(kThreads) void lm_dw_gather_kernel(const LmListArgs a)
+{
+    const int t = blockIdx.x, tid = threadIdx.x;
+    const int q0 = a.col_start[t], q1 = a.col_start[t + 1];
+    float *dw = a.d_w + (int64_t)t * a.ld_w;
+    for (int j0 = tid * 8; j0 < a.d; j0 += kThreads * 8) {
+        float acc[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+        for (int q = q0; q < q1; ++q)
+            fma8(acc, a.csc_val[q], *(const u32x4 *)(a.H + (int64_t)a.csc_row[q] * a.ld_h + j0));
+        store8(dw + j0, acc);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_lmhead_lists_backward(const LmListArgs &a, hipStream_t stream)
+{
+#define DVP_LAUNCHED() do { hipError_t e_ = hipGetLastError(); if (e_ != hipSuccess) return e_; } while (0)
+    hipLaunchKernelGGL(lm_lists_finish_kernel, dim3((unsigned)a.n), dim3(kThreads), 0, stream, a);
+    DVP_LAUNCHED();
+    const int64_t cells = (int64_t)a.n_blk * a.v;
+    const int64_t zero_grid = (cells + 256 * 16 - 1) / (256 * 16);
+    hipLaunchKernelGGL(lm_zero_i32_kernel, dim3((unsigned)(zero_grid < 4096 ? (zero_grid < 1 ? 1 : zero_grid) : 4096)), dim3(256),
+                       0, stream, a.blk_cnt, cells);
+    DVP_LAUNCHED();
+    hipLaunchKernelGGL(lm_csc_count_kernel, dim3((unsigned)a.n_blk), dim3(kThreads), 0, stream, a);
+    DVP_LAUNCHED();
+    const int n_grp = (a.v + kThreads - 1) / kThreads;
+    hipLaunchKernelGGL(lm_csc_prefix_kernel, dim3((unsigned)n_grp), dim3(kThreads), 0, stream, a, a.grp_total);
+    DVP_LAUNCHED();
+    hipLaunchKernelGGL(lm_csc_scan_kernel, dim3(1), dim3(kThreads), 0, stream, a.grp_total, n_grp);
+    DVP_LAUNCHED();
+    hipLaunchKernelGGL(lm_csc_offset_kernel, dim3((unsigned)(a.v / kThreads + 1)), dim3(kThreads), 0, stream, a.col_start,
+                       (const int32_t *)a.grp_total, a.v, n_grp);
+    DVP_LAUNCHED();
+    hipLaunchKernelGGL(lm_csc_fill_kernel, dim3((unsigned)a.n_blk), dim3(kWave), 0, stream, a);
+    DVP_LAUNCHED();
+    hipLaunchKernelGGL(lm_dw_gather_kernel, dim3((unsigned)a.v), dim3(kThreads), 0, stream, a);
+    DVP_LAUNCHED();
+#undef DVP_LAUNCHED
+    return hipSuccess;
+}
+
+}  // namespace dvp

@@ -914,6 +914,8 @@ __global__ __launch_bounds__(kListsScatterThreads) void lists_scatter_kernel(con
 // ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
+// Compute units of the first device asked about, cached for the process (and so is the occupancy below):
+// the kernels walk their rows from any grid size, so on another device the figure only costs speed.
 static int device_cu_count()
 {
     static std::atomic<int> cached{0};   // callers may come from several host threads

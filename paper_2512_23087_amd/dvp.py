@@ -24,7 +24,8 @@ EXPORTS = ("dvp_forward", "dvp_backward", "dvp_forward_backward", "dvp_fused_lmh
            "dvp_fused_lmhead_workspace_bytes", "dvp_log_rho", "dvp_status_string", "dvp_row_path",
            "dvp_sequence_weights", "dvp_log_threshold", "dvp_forward_backward_sparse",
            "dvp_fused_lmhead_f8infer", "dvp_lists_to_dense", "dvp_fused_lmhead_saved_bytes",
-           "dvp_fused_lmhead_forward", "dvp_fused_lmhead_backward")
+           "dvp_fused_lmhead_forward", "dvp_fused_lmhead_backward", "dvp_fused_lmhead_lists",
+           "dvp_fused_lmhead_lists_workspace_bytes")
 
 
 class DvpParams(ctypes.Structure):
@@ -95,6 +96,11 @@ def lib():
         L.dvp_fused_lmhead_backward.restype = ctypes.c_int
         L.dvp_fused_lmhead_backward.argtypes = [lp, vp, vp, i64p, vp, vp, ctypes.c_size_t, vp, vp, vp,
                                                 ctypes.c_size_t, vp]
+        L.dvp_fused_lmhead_lists_workspace_bytes.restype = ctypes.c_size_t
+        L.dvp_fused_lmhead_lists_workspace_bytes.argtypes = [lp, ctypes.c_int32]
+        L.dvp_fused_lmhead_lists.restype = ctypes.c_int
+        L.dvp_fused_lmhead_lists.argtypes = [lp, vp, vp, vp, i64p, vp, sp, sp, vp, vp, vp, ctypes.c_int32, vp, vp, vp,
+                                             ctypes.c_size_t, vp]
         L.dvp_log_rho.restype = ctypes.c_float
         L.dvp_log_rho.argtypes = [ctypes.c_double]
         L.dvp_status_string.restype = ctypes.c_char_p
@@ -395,6 +401,49 @@ def dvp_fused_lmhead(hidden, w_train, w_infer, ids, grad_out, log_rho_value, *, 
     if st != 0:
         raise DvpError(st, "dvp_fused_lmhead")
     return LmHeadResult(out_train, out_infer, row_flags, d_hidden, d_w)
+
+
+class LmHeadListsResult(LmHeadResult):
+    def __init__(self, train, infer, row_flags, d_hidden, d_w, entries, grad_len):
+        super().__init__(train, infer, row_flags, d_hidden, d_w)
+        self.entries, self.grad_len = entries, grad_len      # entries: int32 [N, cap, 2] = (token, fp32 bits)
+
+    row = SparseResult.row
+
+
+def dvp_fused_lmhead_lists(hidden, w_train, w_infer, ids, grad_out, log_rho_value, list_cap, *, lse_full=False,
+                           workspace: Optional[torch.Tensor] = None, d_hidden=None, d_w=None, entries=None,
+                           grad_len=None, stream=None) -> LmHeadListsResult:
+    """LM-head variant with the gradient kept as per-row lists (short safe sets)."""
+    for name, t in (("hidden", hidden), ("w_train", w_train)):
+        if not t.is_cuda or t.dtype != torch.bfloat16 or t.dim() != 2 or t.stride(1) != 1:
+            raise ValueError("%s must be a bf16 [rows, d] GPU tensor with unit inner stride" % name)
+    n, d = hidden.shape
+    v = w_train.shape[0]
+    dev = hidden.device
+    p = DvpLmHeadParams(n, d, v, hidden.stride(0), w_train.stride(0), float(log_rho_value))
+    need = int(lib().dvp_fused_lmhead_lists_workspace_bytes(ctypes.byref(p), int(list_cap)))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    out_train = SideOutputs(n, v, dev, lse_full, False)
+    out_infer = SideOutputs(n, v, dev, lse_full, False) if w_infer is not None else None
+    row_flags = torch.empty(n, dtype=torch.uint8, device=dev)
+    if d_hidden is None:
+        d_hidden = torch.empty(n, hidden.stride(0), dtype=torch.float32, device=dev)[:, :d]
+    if d_w is None:
+        d_w = torch.empty(v, w_train.stride(0), dtype=torch.float32, device=dev)[:, :d]
+    if entries is None:
+        entries = torch.empty(n, max(int(list_cap), 1), 2, dtype=torch.int32, device=dev)
+    if grad_len is None:
+        grad_len = torch.empty(n, dtype=torch.int32, device=dev)
+    st = lib().dvp_fused_lmhead_lists(ctypes.byref(p), _ptr(hidden), _ptr(w_train), _ptr(w_infer), _ptr(ids),
+                                      _ptr(grad_out), ctypes.byref(out_train.struct()),
+                                      ctypes.byref(out_infer.struct()) if out_infer is not None else None,
+                                      _ptr(row_flags), _ptr(entries), _ptr(grad_len), int(list_cap),
+                                      _ptr(d_hidden), _ptr(d_w), _ptr(workspace), workspace.numel(), _stream(stream))
+    if st != 0:
+        raise DvpError(st, "dvp_fused_lmhead_lists")
+    return LmHeadListsResult(out_train, out_infer, row_flags, d_hidden, d_w, entries, grad_len)
 
 
 class LmHeadSaved:

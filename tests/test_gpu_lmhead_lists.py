@@ -1,0 +1,229 @@
+"""GPU parity of dvp_fused_lmhead_lists (the LM-head variant with the gradient kept as per-row lists)
+against the fp64 oracle, through the C ABI.
+
+Forward outputs: the bars of tests/test_gpu_lmhead.py (the same two GEMM passes produce them).
+Gradient: nothing passes through bf16 here, so what separates the GPU from the oracle is the fp32
+accumulation of the logits and of the sums.  A logit is accumulated over d / 16 matrix-instruction steps,
+each rounding a partial sum of magnitude up to max|z| to fp32: half a unit in the last place per step,
+adding up like a random walk, is sqrt(d / 16) 2^-24 max|z| (2^-20 max|z| at d = 4096); the bound used is twice
+that at the largest d, dz = 2^-19 (max|z| + 10), and it moves a probability by at most 2 p dz to first
+order.  Per element
+    |dH_gpu - dH| <= 2 dz (|c| p) |W| + 1e-5 + 2^-20 |dH|,   |dW_gpu - dW| <= 2 dz (|c| p)^T |H| + 1e-5 + 2^-20 |dW|,
+and a list value is within 2 dz |c| p_k + 1e-6 of the oracle's dz.  Rows with a logit inside the band
+around the threshold (membership may differ between fp32 and fp64 logits) are given grad_out = 0 on both
+sides, so they drop out of dH and dW; their forward outputs are still compared, band-aware.
+Rows whose safe set is longer than the list are flagged and contribute nothing: the oracle is given
+grad_out = 0 for them.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dvp_oracle as orc
+from paper_2512_23087_amd import workloads
+from tests.test_gpu_lmhead import BAND, _check_side
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dvp():
+    from paper_2512_23087_amd import dvp as binding
+    binding.lib()
+    return binding
+
+
+def _run(dvp, wl, rho, cap, infer=True):
+    lr = dvp.log_rho(rho)
+    ids = wl.ids.cpu().numpy()
+    n = ids.shape[0]
+    H, Wt, Wi = wl.hidden.cpu(), wl.w_train.cpu(), wl.w_infer.cpu()
+    fwd = orc.lmhead(H, Wt, ids, np.float32(lr), band=BAND, want_flags=True, threads=8)
+    band_rows = fwd["band_count"] > 0
+    g = wl.grad_out.cpu().numpy().astype(np.float64).copy()
+    g[band_rows] = 0.0
+    gout = torch.tensor(g, dtype=torch.float32, device="cuda")
+    res = dvp.dvp_fused_lmhead_lists(wl.hidden, wl.w_train, wl.w_infer if infer else None, wl.ids, gout, lr, cap)
+    torch.cuda.synchronize()
+
+    same_t = _check_side("train", res.train, fwd, fwd)
+    flags = res.row_flags.cpu().numpy()
+    np.testing.assert_array_equal((flags & 1)[same_t], fwd["y_in_safe"][same_t])
+    if infer:
+        oi = orc.lmhead(H, Wi, ids, np.float32(lr), band=BAND, threads=8)
+        same_i = _check_side("infer", res.infer, oi, oi)
+        np.testing.assert_array_equal(((flags >> 1) & 1)[same_i], oi["y_in_safe"][same_i])
+    else:
+        assert res.infer is None and not (flags & 2).any()
+
+    clean = ~band_rows
+    y_safe = fwd["y_in_safe"] == 1
+    over = y_safe & (fwd["safe_count"] > cap)
+    np.testing.assert_array_equal(((flags & dvp.ROW_GRAD_OVERFLOW) != 0)[clean], over[clean])
+    glen = res.grad_len.cpu().numpy()
+    np.testing.assert_array_equal(glen[clean], np.where(y_safe, fwd["safe_count"], 0)[clean])
+
+    g_eff = g.copy()
+    g_eff[over] = 0.0
+    ot = orc.lmhead(H, Wt, ids, np.float32(lr), grad_out=g_eff, band=BAND, threads=8)
+    dz_round = 2.0 ** -19 * (np.abs(ot["row_max"]).max() + 10.0)
+    listed = clean & y_safe & ~over
+    for i in np.nonzero(listed)[0]:
+        idx, val = res.row(int(i))
+        want = np.nonzero(fwd["safe_flags"][i])[0]
+        np.testing.assert_array_equal(idx.numpy(), want)
+        stored = res.entries[i, :len(want), 0].cpu().numpy().astype(np.int64) & 0xFFFFFFFF
+        np.testing.assert_array_equal(stored, want)                      # sorted by token on the device
+        ref = ot["dz"][i, want]
+        pk = np.abs(ref).copy()
+        pk[want == ids[i]] = abs(g[i]) * np.exp(ot["logp"][i])
+        assert np.all(np.abs(val.double().numpy() - ref) <= 2 * dz_round * pk + 1e-6 * max(1.0, abs(g[i])))
+    full = np.abs(ot["dz"])
+    rows = np.nonzero(listed)[0]
+    full[rows, ids[rows]] = np.abs(g[rows]) * np.exp(ot["logp"][rows])
+    H64, W64 = H.double().numpy(), Wt.double().numpy()
+    bound_h = 2 * dz_round * (full @ np.abs(W64)) + 1e-5 + 2.0 ** -20 * np.abs(ot["d_hidden"])
+    bound_w = 2 * dz_round * (full.T @ np.abs(H64)) + 1e-5 + 2.0 ** -20 * np.abs(ot["d_w"])
+    dh = res.d_hidden.cpu().double().numpy()
+    dw = res.d_w.cpu().double().numpy()
+    err_h = (np.abs(dh - ot["d_hidden"]) / bound_h).max()
+    err_w = (np.abs(dw - ot["d_w"]) / bound_w).max()
+    print("cap %d: %d listed rows, %d overflow, %d band; dH at %.3f, dW at %.3f of their bounds" %
+          (cap, listed.sum(), (over & clean).sum(), band_rows.sum(), err_h, err_w))
+    assert err_h <= 1.0 and err_w <= 1.0
+    assert np.abs(dh - ot["d_hidden"]).max() <= 2e-3 and np.abs(dw - ot["d_w"]).max() <= 2e-3    # the bf16-input bar
+    assert np.all(dh[~listed] == 0.0)
+    return res, fwd, listed
+
+
+def test_peaked_rows_against_oracle(dvp):
+    wl = workloads.make_lmhead(device="cuda", n=300, d=128, v=3000, hidden_scale=60.0)
+    for rho, cap in ((1e-4, 64), (1e-2, 16), (1e-4, 8)):
+        res, fwd, listed = _run(dvp, wl, rho, cap)
+        assert listed.sum() > 50
+    assert np.median(fwd["safe_count"]) < 64
+
+
+@pytest.mark.parametrize("n,d,v,cap", [(1, 64, 3, 4), (2, 64, 1, 1), (257, 192, 257, 300), (33, 64, 513, 1024),
+                                       (700, 64, 900, 1000), (300, 64, 1500, 1000)])
+def test_shapes_and_long_lists(dvp, n, d, v, cap):
+    # flat logits: every token is safe, lists as long as the vocabulary (or overflowing), several row blocks
+    wl = workloads.make_lmhead(device="cuda", n=n, d=d, v=v)
+    _run(dvp, wl, 1e-2, cap)
+    _run(dvp, wl, 0.0, cap, infer=False)
+
+
+def test_agrees_with_the_dense_call_and_repeats_bit_for_bit(dvp):
+    wl = workloads.make_lmhead(device="cuda", n=1000, d=256, v=5000, hidden_scale=40.0)
+    lr = dvp.log_rho(1e-4)
+    a = dvp.dvp_fused_lmhead_lists(wl.hidden, wl.w_train, wl.w_infer, wl.ids, wl.grad_out, lr, 1024)
+    b = dvp.dvp_fused_lmhead_lists(wl.hidden, wl.w_train, wl.w_infer, wl.ids, wl.grad_out, lr, 1024)
+    ref = dvp.dvp_fused_lmhead(wl.hidden, wl.w_train, wl.w_infer, wl.ids, wl.grad_out, lr)
+    torch.cuda.synchronize()
+    assert not (a.row_flags & dvp.ROW_GRAD_OVERFLOW).any()
+    valid = torch.arange(1024, device="cuda")[None, :] < a.grad_len[:, None]     # entries past a row's length are unspecified
+    for x, y in ((a.d_hidden, b.d_hidden), (a.d_w, b.d_w), (a.entries[valid], b.entries[valid]), (a.grad_len, b.grad_len)):
+        assert torch.equal(x, y)
+    # the same forward kernels: identical outputs; the dense call rounds E to bf16, so gradients agree to 2^-8 relative
+    assert torch.equal(a.train.logp, ref.train.logp) and torch.equal(a.infer.logp, ref.infer.logp)
+    assert torch.equal(a.train.safe_count, ref.train.safe_count) and torch.equal(a.row_flags, ref.row_flags)
+    scale_h = ref.d_hidden.abs().max().item()
+    scale_w = ref.d_w.abs().max().item()
+    assert (a.d_hidden - ref.d_hidden).abs().max().item() <= 2.0 ** -6 * scale_h
+    assert (a.d_w - ref.d_w).abs().max().item() <= 2.0 ** -6 * scale_w
+
+
+def test_validation(dvp):
+    wl = workloads.make_lmhead(device="cuda", n=16, d=64, v=100)
+    lr = dvp.log_rho(1e-2)
+    for cap, status in ((0, 3), (1025, 5)):
+        with pytest.raises(dvp.DvpError) as e:
+            dvp.dvp_fused_lmhead_lists(wl.hidden, wl.w_train, None, wl.ids, wl.grad_out, lr, cap,
+                                       workspace=torch.empty(1 << 20, dtype=torch.uint8, device="cuda"))
+        assert e.value.status == status
+    with pytest.raises(dvp.DvpError) as e:
+        dvp.dvp_fused_lmhead_lists(wl.hidden, wl.w_train, None, wl.ids, wl.grad_out, lr, 8,
+                                   workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == 6
+
+
+def test_full_size_peaked_sampled_rows(dvp):
+    """configs[4]'s shape (N=16384, d=4096, V=151936) with the hidden states scaled by 20 (a few safe
+    tokens per row), list_cap 64, as the benchmark runs it: forward outputs, list entries and dH on sampled
+    rows against the oracle.  dW[k, :] needs every row's statistics, so at this size it is checked through
+    properties: its columns sum to zero (each row's dz does, Prop. 5.4); rows of tokens that no list holds
+    are exactly zero; and it equals the lists' own transpose product formed in fp64 by torch (the lists
+    being checked against the oracle on the sampled rows): that covers the column-major copy at full size."""
+    wl = workloads.make_lmhead(device="cuda", hidden_scale=20.0)
+    n, d = wl.hidden.shape
+    v = wl.w_train.shape[0]
+    cap = 64
+    lr = dvp.log_rho(1e-4)
+    res = dvp.dvp_fused_lmhead_lists(wl.hidden, wl.w_train, wl.w_infer, wl.ids, wl.grad_out, lr, cap)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(2)
+    rows = np.unique(np.concatenate([[0, n - 1], rng.choice(n, 46, replace=False)]))
+    ridx = torch.as_tensor(rows, device="cuda")
+    H = wl.hidden[ridx].cpu()
+    ids = wl.ids[ridx].cpu().numpy()
+    g = wl.grad_out[ridx].cpu().numpy().astype(np.float64)
+    Wt, Wi = wl.w_train.cpu(), wl.w_infer.cpu()
+    ot = orc.lmhead(H, Wt, ids, np.float32(lr), grad_out=g, band=BAND, want_flags=True, threads=8)
+    oi = orc.lmhead(H, Wi, ids, np.float32(lr), band=BAND, threads=8)
+
+    class Sub:
+        pass
+
+    def cut(side):
+        s = Sub()
+        for k in ("logp", "row_max", "lse_safe", "safe_count"):
+            setattr(s, k, getattr(side, k)[ridx])
+        s.lse_full = None
+        return s
+
+    _check_side("train", cut(res.train), ot, ot)
+    _check_side("infer", cut(res.infer), oi, oi)
+    clean = (ot["band_count"] == 0) & (ot["y_in_safe"] == 1) & (ot["safe_count"] <= cap)
+    assert clean.sum() >= 30
+    W64 = Wt.double().numpy()
+    dz_round = 2.0 ** -19 * (np.abs(ot["row_max"]).max() + 10.0)
+    dh = res.d_hidden[ridx].cpu().double().numpy()
+    for j in np.nonzero(clean)[0]:
+        idx, val = res.row(int(rows[j]))
+        want = np.nonzero(ot["safe_flags"][j])[0]
+        np.testing.assert_array_equal(idx.numpy(), want)
+        ref = ot["dz"][j, want]
+        pk = np.abs(ref).copy()
+        pk[want == ids[j]] = abs(g[j]) * np.exp(ot["logp"][j])
+        assert np.all(np.abs(val.double().numpy() - ref) <= 2 * dz_round * pk + 1e-6 * max(1.0, abs(g[j])))
+        bound = 2 * dz_round * (pk @ np.abs(W64[want])) + 1e-5 + 2.0 ** -20 * np.abs(ot["d_hidden"][j])
+        assert (np.abs(dh[j] - ot["d_hidden"][j]) / bound).max() <= 1.0
+        assert np.abs(dh[j] - ot["d_hidden"][j]).max() <= 2e-3
+    # any-size properties on every row and token
+    flags = res.row_flags
+    over = (flags & dvp.ROW_GRAD_OVERFLOW) != 0
+    glen = torch.where(over, torch.zeros_like(res.grad_len), res.grad_len)
+    assert torch.all(res.train.safe_count >= 1)
+    assert torch.equal(res.grad_len, torch.where((flags & 1) != 0, res.train.safe_count, torch.zeros_like(res.grad_len)))
+    assert torch.isfinite(res.d_w).all() and torch.isfinite(res.d_hidden).all()
+    valid = torch.arange(cap, device="cuda")[None, :] < glen[:, None]
+    tok = (res.entries[..., 0].to(torch.int64) & 0xFFFFFFFF)[valid]
+    val = res.entries[..., 1].contiguous().view(torch.float32)[valid].double()
+    row_of = torch.arange(n, device="cuda")[:, None].expand(n, cap)[valid]
+    touched = torch.zeros(v, dtype=torch.bool, device="cuda")
+    touched[tok] = True
+    assert torch.all(res.d_w[~touched] == 0.0)
+    used = torch.nonzero(touched).squeeze(1)
+    slot = torch.full((v,), -1, dtype=torch.int64, device="cuda")
+    slot[used] = torch.arange(used.numel(), device="cuda")
+    want_w = torch.zeros(used.numel(), d, dtype=torch.float64, device="cuda")
+    for s0 in range(0, tok.numel(), 8192):                 # in pieces: the products are [pieces, d] fp64
+        sl = slice(s0, s0 + 8192)
+        want_w.index_add_(0, slot[tok[sl]], val[sl, None] * wl.hidden[row_of[sl]].double())
+    got_w = res.d_w[used].double()
+    assert (got_w - want_w).abs().max().item() <= 1e-5 + 2.0 ** -18 * want_w.abs().max().item()
+    col = res.d_w.double().sum(dim=0).abs().max().item()
+    scale = res.d_w.double().abs().sum(dim=0).max().item()
+    assert col <= 2.0 ** -16 * scale
+    del wl, res
+    torch.cuda.empty_cache()

@@ -229,3 +229,22 @@ def test_lmhead_argument_validation_needs_no_gpu():
     assert call8(P(n=0), S()) == 0
     assert fwd(P(), side=S()) == 3                  # a bf16 and an 8-bit inference side at once
     assert fwd(P(), w_infer=None, side=S(scale=0.0)) == 3
+
+    # gradient as per-row lists
+    def lists(p, cap=64, grad=FAKE, flags=FAKE, entries=FAKE, glen=FAKE, dh=FAKE, dw=FAKE, bytes_=1 << 40, side=so):
+        return L.dvp_fused_lmhead_lists(ctypes.byref(p), FAKE, FAKE, FAKE, FAKE, grad, ctypes.byref(side), ctypes.byref(side),
+                                        flags, entries, glen, cap, dh, dw, ws, bytes_, None)
+
+    small = L.dvp_fused_lmhead_lists_workspace_bytes(ctypes.byref(P(n=16384, d=4096, v=151936)), 64)
+    assert 0 < small < L.dvp_fused_lmhead_workspace_bytes(ctypes.byref(P(n=16384, d=4096, v=151936))) // 8
+    assert L.dvp_fused_lmhead_lists_workspace_bytes(ctypes.byref(P()), 0) == 0
+    assert L.dvp_fused_lmhead_lists_workspace_bytes(ctypes.byref(P()), 1025) == 0
+    assert L.dvp_fused_lmhead_lists_workspace_bytes(ctypes.byref(P(n=1 << 22)), 1024) == 0     # N * cap >= 2^31
+    assert lists(P(n=0)) == 0
+    assert lists(P(), cap=0) == 3 and lists(P(), cap=1025) == 5 and lists(P(n=1 << 22), cap=1024) == 5
+    assert lists(P(), grad=None) == 1 and lists(P(), flags=None) == 1 and lists(P(), entries=None) == 1
+    assert lists(P(), glen=None) == 1 and lists(P(), dh=None) == 1 and lists(P(), dw=None) == 1
+    assert lists(P(), entries=FAKE + 4) == 4 and lists(P(), dw=FAKE + 8) == 4
+    assert lists(P(), side=dvp.DvpSideOut(FAKE, FAKE, FAKE, None, FAKE, FAKE)) == 5             # no bitmask in this form
+    assert lists(P(d=96)) == 5 and lists(P(lr=0.5)) == 3
+    assert lists(P(), bytes_=1000) == 6

@@ -161,9 +161,12 @@ def bench_lmhead(args):
         over = int(((res.row_flags & dvp.ROW_GRAD_OVERFLOW) != 0).sum().item())
         listed = int(torch.where((res.row_flags & dvp.ROW_GRAD_OVERFLOW) != 0, torch.zeros_like(res.grad_len),
                                  res.grad_len).sum().item())
-        # two forwards as matrix products (each run twice), the gradient as |lists| x d multiply-adds, twice
-        useful, executed = 2 * gemm + 4.0 * listed * d, 4 * gemm + 4.0 * listed * d
-        extra = {"list_cap": lists_cap, "list_entries": listed, "rows_over_cap": over,
+        # two forwards as matrix products (one pass each, two where a side needed its second pass), the
+        # gradient as |lists| x d multiply-adds, twice
+        second = [int(x) for x in res.second_pass.cpu().tolist()]
+        passes = 2 + sum(second)
+        useful, executed = 2 * gemm + 4.0 * listed * d, passes * gemm + 4.0 * listed * d
+        extra = {"list_cap": lists_cap, "list_entries": listed, "rows_over_cap": over, "gemm_passes": passes,
                  "mean_safe_set": float(res.train.safe_count.float().mean().item())}
     # (each side's forward produces the logits twice: row max first, then sums at the threshold)
     # Peak for the mix of passes: each contraction is priced at the peak of its own operand type, so the
@@ -190,7 +193,7 @@ def bench_lmhead(args):
                      "peak": peak, "unit": "TFLOP/s",
                      "frac": executed / (ms * 1e-3) / 1e12 / peak, "traffic": None,
                      "kernel": "gemm_nt_kernel (%d GEMM passes of 2*N*V*d flop each per call%s)"
-                               % (4 if lists_cap else 6, ": 4 bf16 at 2.5 PFLOP/s peak, 2 fp8 at 5.0" if f8 else ""),
+                               % (extra.get("gemm_passes", 6), ": 4 bf16 at 2.5 PFLOP/s peak, 2 fp8 at 5.0" if f8 else ""),
                      "kernel_ms_avg": ms, "executed_tflop": executed / 1e12,
                      "useful_tflop": useful / 1e12,
                      "useful_tflops": useful / (ms * 1e-3) / 1e12},

@@ -277,9 +277,15 @@ dvp_status dvp_fused_lmhead(const dvp_lmhead_params *params, const void *hidden,
  * set).  Where safe sets are short (peaked distributions: a handful of tokens per row) dz has a few
  * entries per row and the two gradient products are not matrix products any more: dH_i is a sum of
  * |V_S| rows of W, dW_k a sum of the hidden states of the rows whose safe set holds k.  The call runs
- * the four forward passes of dvp_fused_lmhead (no block of masked exponentials is kept: workspace is
- * small), collects each row's safe tokens in the second training pass, and forms dH and dW from the
- * lists in fp32: four GEMM passes instead of six, and no entry of dz passes through bf16.
+ * the forward passes of dvp_fused_lmhead (no block of masked exponentials is kept: workspace is
+ * small), collects each row's safe tokens on the way, and forms dH and dW from the lists in fp32: at
+ * most four GEMM passes instead of six, and no entry of dz passes through bf16.
+ * Where rows are peaked the forward of a side needs only one pass: the first pass collects, next to the
+ * row maxima, every token that can still be safe (those at or above a lower bound of the final
+ * threshold, formed from the row's maximum over a block of 128 columns and from the sampled token's own
+ * logit), and the safe set, its sum and the list are read off these candidates; a side whose rows hold more
+ * candidates than are kept, or whose lse_full is asked for, runs its second pass as in dvp_fused_lmhead.
+ * Which happens depends on the inputs only, never on timing.
  *   entries, grad_len, list_cap   as for dvp_forward_backward_sparse, with list_cap at most 1024;
  *              a row's entries come out sorted by token; what lies beyond grad_len[i] in a row of
  *              entries is unspecified.  grad_len and row_flags are required.
@@ -295,6 +301,14 @@ dvp_status dvp_fused_lmhead(const dvp_lmhead_params *params, const void *hidden,
  * token): meant for list_cap well below the vocabulary.
  */
 size_t dvp_fused_lmhead_lists_workspace_bytes(const dvp_lmhead_params *params, int32_t list_cap);
+
+/*
+ * Byte offset, inside that workspace, of two DEVICE int32 that tell after a dvp_fused_lmhead_lists call
+ * which sides (training, inference) needed their second pass over the logits although lse_full was
+ * not asked for: 1 when some row had more candidates than are kept (2048), else 0.  For measurement:
+ * a side without second pass costs one GEMM pass instead of two.  0 on invalid arguments.
+ */
+size_t dvp_fused_lmhead_lists_second_pass_flags(const dvp_lmhead_params *params, int32_t list_cap);
 
 dvp_status dvp_fused_lmhead_lists(const dvp_lmhead_params *params, const void *hidden,
                                   const void *w_train, const void *w_infer, const int64_t *ids,

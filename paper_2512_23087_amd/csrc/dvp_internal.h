@@ -126,6 +126,24 @@ struct LmListArgs {
     int32_t n_blk, rows_per_blk;
 };
 
+// One side of the LM-head forward finished from the candidates pass A collected
+// (launch_lmhead_candidates_finish), and the bound pass A used (launch_lmhead_zy_low).
+constexpr int kLmCandMax = 2048;  // candidates kept per row
+struct LmCandArgs {
+    const dvp_grad_entry *cand;   // [n, kLmCandMax] (token, logit) in arrival order
+    const int32_t *cand_count;    // [n] candidates appended (may exceed kLmCandMax: then the side is redone)
+    const float *m, *tau, *zy;    // [n] row maximum, threshold, the sampled token's logit
+    const int64_t *ids;
+    const float *grad_out;        // [n] or null; side 0 only
+    SideOut out;                  // logp, row_max, lse_safe, safe_count (required); the rest unused
+    uint8_t *row_flags;
+    float *coef, *scale;          // [n], side 0 only
+    dvp_grad_entry *entries;      // side 0: [n, list_cap] (token, exp(z - m)) for rows that fit; else null
+    int32_t list_cap;
+    int32_t *need_second_pass;    // set to 1 when a row's candidates did not fit
+    int32_t n, v, side;
+};
+
 // true when the register-resident kernel can take rows of this many elements
 // (dtype: training rows and gradient; dtype_infer: inference rows)
 bool row_fits_resident(int dtype, int dtype_infer, int64_t vocab);
@@ -138,5 +156,8 @@ hipError_t launch_backward(int dtype, const BackwardArgs &a, bool vector_ok, hip
 hipError_t launch_lists_to_dense(int dtype, const ListsArgs &a, bool vector_ok, hipStream_t stream);
 hipError_t launch_sequences(const SequenceArgs &a, hipStream_t stream);
 hipError_t launch_lmhead_lists_backward(const LmListArgs &a, hipStream_t stream);
+hipError_t launch_lmhead_zy_low(const uint16_t *H, int64_t ld_h, const uint16_t *W, int64_t ld_w, const int64_t *ids,
+                                float *zy_low, int n, int d, int v, hipStream_t stream);
+hipError_t launch_lmhead_candidates_finish(const LmCandArgs &a, hipStream_t stream);
 
 }  // namespace dvp

@@ -95,6 +95,7 @@ struct GemmArgs {
 // ---------------------------------------------------------------------------
 struct EpiMax {
     static constexpr bool kUsesTileLds = false;
+    static constexpr bool kGated = false;
     RowStats st;
     const int64_t *ids;
     __device__ __forceinline__ void operator()(const GemmArgs &g, f32x16 (&acc)[MI][NI], int r0, int c0, int lane, uint8_t *, int, int) const
@@ -124,6 +125,66 @@ struct EpiMax {
     }
 };
 
+// Pass A that also collects candidates for the safe set.  The threshold is m + log_rho with m the
+// row maximum over the whole vocabulary, unknown here; any lower bound of m gives a lower threshold and
+// so a superset of the safe set.  The bound used is the larger of the maximum over this wavefront's
+// 128 columns and a value known to lie below the sampled token's logit (zy_low): both depend on the
+// inputs only, not on the order in which tiles run, so a row's candidate set is the same in every run.
+// Candidates (token, z) are appended in arrival order; at most cand_cap are kept.
+struct EpiMaxCand {
+    static constexpr bool kUsesTileLds = false;
+    static constexpr bool kGated = false;
+    RowStats st;
+    const int64_t *ids;
+    const float *zy_low;     // [n] lower bound of the row maximum, -inf where there is none
+    dvp_grad_entry *cand;    // [n, cand_cap]
+    int *cursor;             // [n], zero before the launch
+    int cand_cap;
+    float log_rho;
+    __device__ __forceinline__ void operator()(const GemmArgs &g, f32x16 (&acc)[MI][NI], int r0, int c0, int lane, uint8_t *, int, int) const
+    {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int row = r0 + mi * 32 + (i / 4) * 8 + (lane / 32) * 4 + (i % 4);
+                const bool row_ok = row < g.M;
+                const int64_t y = row_ok ? ids[row] : -1;
+                float v = -INFINITY;
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni) {
+                    const int col = c0 + ni * 32 + (lane % 32);
+                    const float z = acc[mi][ni][i];
+                    if (col < g.N) {
+                        v = fmaxf(v, z);
+                        if (row_ok && (int64_t)col == y) st.zy[row] = z;
+                    }
+                }
+#pragma unroll
+                for (int off = 16; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+                if ((lane % 32) == 0 && row_ok) atomicMax(st.max_key + row, float_to_ordered(v));
+                if (!row_ok) continue;
+                const float thr = fmaxf(v, zy_low[row]) + log_rho;   // <= the row's final threshold (fp32 addition is monotone)
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni) {
+                    const int col = c0 + ni * 32 + (lane % 32);
+                    const float z = acc[mi][ni][i];
+                    if (col < g.N && z >= thr) {
+                        int *cur = cursor + row;
+                        if (__hip_atomic_load(cur, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) <= cand_cap) {
+                            const int pos = atomicAdd(cur, 1);
+                            if (pos < cand_cap) {
+                                dvp_grad_entry *e = cand + (int64_t)row * cand_cap + pos;
+                                e->index = (uint32_t)col; e->value = z;
+                            }
+                        }
+                    }
+                }
+            }
+        }
+    }
+};
+
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)   // hardware pack-convert, round to nearest even
@@ -139,9 +200,12 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)   // hardwar
 // WRITE_LIST: also append every safe token of a row, with exp(z - m), to that row's list (arrival
 // order; at most list_cap entries are kept, the cursor stops a little above that).  Meant for rows
 // whose safe sets are short: the branch is then rarely taken.
-template <bool WRITE_E, bool WRITE_BITS = false, bool WRITE_LIST = false>
+// GATED: the launch does nothing unless *run_if is non-zero (a pass that an earlier kernel may have made
+// unnecessary).
+template <bool WRITE_E, bool WRITE_BITS = false, bool WRITE_LIST = false, bool GATED = false>
 struct EpiSum {
     static constexpr bool kUsesTileLds = WRITE_E;   // the bf16 staging lives in the operand tiles
+    static constexpr bool kGated = GATED;
     RowStats st;
     int n_rows;
     const int64_t *ids;      // WRITE_E: the sampled token's own entry of E is stored as zero
@@ -152,6 +216,7 @@ struct EpiSum {
     dvp_grad_entry *entries; // WRITE_LIST: [n_rows, list_cap]
     int *cursor;             // WRITE_LIST: [n_rows] entries appended so far, zero before the launch
     int list_cap;
+    const int *run_if;       // GATED
     __device__ __forceinline__ void operator()(const GemmArgs &g, f32x16 (&acc)[MI][NI], int r0, int c0, int lane, uint8_t *lds, int wave, int wn) const
     {
         const bool want_full = st.part_f != nullptr;
@@ -284,6 +349,7 @@ struct EpiSum {
 
 struct EpiStore {
     static constexpr bool kUsesTileLds = false;
+    static constexpr bool kGated = false;
     float *C;                // [M, ldc] fp32
     int64_t ldc;
     int accumulate;          // 0: C = v, 1: C += v
@@ -375,6 +441,9 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];   // [stage][A | B][256 rows][128 B], then sums scratch
 
+    if constexpr (Epi::kGated) {
+        if (*epi.run_if == 0) return;   // the same for every lane of the grid
+    }
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave), lane = tid % kWave;
     const int wm = wave / WN, wn = wave % WN;
@@ -622,8 +691,9 @@ constexpr int kAfterRows = 32, kAfterSegs = 8;
 __global__ __launch_bounds__(kAfterRows * kAfterSegs) void after_sum_kernel(RowStats st, SideOut out, const int64_t *ids,
                                                                             const float *grad_out, uint8_t *row_flags,
                                                                             int n, int vocab, int col_tiles, int side,
-                                                                            int unit_grad)
+                                                                            int unit_grad, const int *run_if)
 {
+    if (run_if && *run_if == 0) return;   // see EpiSum's GATED
     __shared__ float seg_s[kAfterSegs][kAfterRows], seg_f[kAfterSegs][kAfterRows];
     __shared__ int seg_c[kAfterSegs][kAfterRows];
     const int r = threadIdx.x % kAfterRows, seg = threadIdx.x / kAfterRows;
@@ -805,6 +875,7 @@ static LmLayout lm_layout(int64_t n, int64_t d, int64_t v, bool dense_buffers = 
 struct LmListLayout {
     LmLayout stats;
     size_t total, off_cursor, off_count, off_blk, off_colstart, off_grp, off_cscrow, off_cscval;
+    size_t off_zylow, off_cand, off_candcur, off_need;
     int n_blk, rows_per_blk;
 };
 
@@ -826,6 +897,10 @@ static LmListLayout lm_list_layout(int64_t n, int64_t d, int64_t v, int64_t cap)
     L.off_grp = take((size_t)((v + 255) / 256 + 1) * 4);
     L.off_cscrow = take((size_t)n * cap * 4);
     L.off_cscval = take((size_t)n * cap * 4);
+    L.off_zylow = take(n * 4);
+    L.off_cand = take((size_t)n * kLmCandMax * sizeof(dvp_grad_entry));
+    L.off_candcur = take(n * 4);
+    L.off_need = take(2 * 4);
     L.total = o;
     return L;
 }
@@ -996,7 +1071,7 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
         hipLaunchKernelGGL(after_sum_kernel, dim3((rows + kAfterRows - 1) / kAfterRows),
                            dim3(kAfterRows * kAfterSegs), 0, stream, st, o, ids + r0,
                            grad_out ? grad_out + r0 : nullptr, row_flags ? row_flags + r0 : nullptr, rows, v,
-                           L.col_tiles, s, phase == LM_FORWARD_SAVE ? 1 : 0);
+                           L.col_tiles, s, phase == LM_FORWARD_SAVE ? 1 : 0, (const int *)nullptr);
         DVP_CHECK_LAUNCH();
         return DVP_OK;
     };
@@ -1088,8 +1163,12 @@ __global__ void zero_cursor_kernel(int *p, int n)
     if (i < n) p[i] = 0;
 }
 
-// List form of the call: the four forward passes as above (no row blocks: nothing of size N x V is kept),
-// pass B of the training side appending to the lists, then the list kernels for dH and dW.
+// List form of the call.  No row blocks: nothing of size N x V is kept.  A side's forward is one pass over
+// the logits where that is enough: pass A collects, next to the row maxima, every token that can still
+// be safe (EpiMaxCand), and the safe set, its sum and the list are then read off the candidates.  Where a
+// row has more candidates than are kept (flat rows), and where lse_full is asked for, the side's second
+// pass runs as in the dense call, appending to the lists on the training side.  Which of the two
+// happens depends on the inputs only.  Then the list kernels form dH and dW.
 static dvp_status run_lmhead_lists(const dvp_lmhead_params *p, const void *hidden, const void *w_train,
                                    const void *w_infer, const int64_t *ids, const float *grad_out,
                                    const dvp_side_out *out_train, const dvp_side_out *out_infer, uint8_t *row_flags,
@@ -1123,6 +1202,11 @@ static dvp_status run_lmhead_lists(const dvp_lmhead_params *p, const void *hidde
 #define DVP_CHECK_LAUNCH() do { if (hipGetLastError() != hipSuccess) return DVP_ERR_HIP; } while (0)
     hipLaunchKernelGGL(zero_cursor_kernel, dim3(nb), dim3(tb), 0, stream, cursor, n);
     DVP_CHECK_LAUNCH();
+    int *need = (int *)(ws + LL.off_need), *cand_cur = (int *)(ws + LL.off_candcur);
+    float *zy_low = (float *)(ws + LL.off_zylow);
+    dvp_grad_entry *cand = (dvp_grad_entry *)(ws + LL.off_cand);
+    hipLaunchKernelGGL(zero_cursor_kernel, dim3(1), dim3(tb), 0, stream, need, 2);
+    DVP_CHECK_LAUNCH();
     RowStats st0;
     int32_t *count0 = nullptr;
     for (int s = 0; s < (w_infer ? 2 : 1); ++s) {
@@ -1146,18 +1230,50 @@ static dvp_status run_lmhead_lists(const dvp_lmhead_params *p, const void *hidde
         g.M = n; g.N = v; g.K = d; g.scale = 1.0f;
         hipLaunchKernelGGL(init_stats_kernel, dim3(nb), dim3(tb), 0, stream, st, n);
         DVP_CHECK_LAUNCH();
-        if (launch_gemm<EpiMax, false>(g, EpiMax{st, ids}, stream) != hipSuccess) return DVP_ERR_HIP;
+        const bool one_pass = o.lse_full == nullptr;   // the full sum needs every token's exponential
+        const int *gate = one_pass ? need + s : nullptr;
+        if (one_pass) {
+            if (launch_lmhead_zy_low((const uint16_t *)hidden, p->ld_hidden, g.B, p->ld_w, ids, zy_low, n, d, v, stream) !=
+                hipSuccess)
+                return DVP_ERR_HIP;
+            hipLaunchKernelGGL(zero_cursor_kernel, dim3(nb), dim3(tb), 0, stream, cand_cur, n);
+            DVP_CHECK_LAUNCH();
+            if (launch_gemm<EpiMaxCand, false>(g, EpiMaxCand{st, ids, zy_low, cand, cand_cur, kLmCandMax, p->log_rho},
+                                               stream) != hipSuccess)
+                return DVP_ERR_HIP;
+        } else {
+            if (launch_gemm<EpiMax, false>(g, EpiMax{st, ids}, stream) != hipSuccess) return DVP_ERR_HIP;
+        }
         hipLaunchKernelGGL(after_max_kernel, dim3(nb), dim3(tb), 0, stream, st, n, p->log_rho);
         DVP_CHECK_LAUNCH();
+        if (one_pass) {
+            LmCandArgs c;
+            c.cand = cand; c.cand_count = cand_cur; c.m = st.m; c.tau = st.tau; c.zy = st.zy;
+            c.ids = ids; c.grad_out = grad_out; c.out = o; c.row_flags = row_flags;
+            c.coef = st.coef; c.scale = st.scale;
+            c.entries = s == 0 ? entries : nullptr; c.list_cap = list_cap;
+            c.need_second_pass = need + s; c.n = n; c.v = v; c.side = s;
+            if (launch_lmhead_candidates_finish(c, stream) != hipSuccess) return DVP_ERR_HIP;
+        }
+        // second pass: always where lse_full is wanted, else only if the candidates of some row did not fit
         hipError_t eb;
-        if (s == 0)
+        if (s == 0 && one_pass)
+            eb = launch_gemm<EpiSum<false, false, true, true>, true>(
+                g, EpiSum<false, false, true, true>{st, n, nullptr, nullptr, nullptr, 0, 0, nullptr, 0, entries, cursor, list_cap, gate},
+                stream);
+        else if (s == 0)
             eb = launch_gemm<EpiSum<false, false, true>, true>(
-                g, EpiSum<false, false, true>{st, n, nullptr, nullptr, nullptr, 0, 0, nullptr, 0, entries, cursor, list_cap}, stream);
+                g, EpiSum<false, false, true>{st, n, nullptr, nullptr, nullptr, 0, 0, nullptr, 0, entries, cursor, list_cap, nullptr},
+                stream);
+        else if (one_pass)
+            eb = launch_gemm<EpiSum<false, false, false, true>, true>(
+                g, EpiSum<false, false, false, true>{st, n, nullptr, nullptr, nullptr, 0, 0, nullptr, 0, nullptr, nullptr, 0, gate},
+                stream);
         else
             eb = launch_gemm<EpiSum<false>, true>(g, EpiSum<false>{st, n, nullptr, nullptr, nullptr, 0, 0, nullptr, 0}, stream);
         if (eb != hipSuccess) return DVP_ERR_HIP;
         hipLaunchKernelGGL(after_sum_kernel, dim3((n + kAfterRows - 1) / kAfterRows), dim3(kAfterRows * kAfterSegs), 0,
-                           stream, st, o, ids, grad_out, row_flags, n, v, L.col_tiles, s, 0);
+                           stream, st, o, ids, grad_out, row_flags, n, v, L.col_tiles, s, 0, gate);
         DVP_CHECK_LAUNCH();
         if (s == 0) {   // before the inference side adds its bit to row_flags: the list kernels only add theirs
             LmListArgs a;
@@ -1185,6 +1301,12 @@ size_t dvp_fused_lmhead_lists_workspace_bytes(const dvp_lmhead_params *p, int32_
 {
     if (!dvp::lm_params_ok(p) || !dvp::lm_list_cap_ok(p, list_cap)) return 0;
     return dvp::lm_list_layout(p->n_rows, p->hidden, p->vocab, list_cap).total;
+}
+
+size_t dvp_fused_lmhead_lists_second_pass_flags(const dvp_lmhead_params *p, int32_t list_cap)
+{
+    if (!dvp::lm_params_ok(p) || !dvp::lm_list_cap_ok(p, list_cap)) return 0;
+    return dvp::lm_list_layout(p->n_rows, p->hidden, p->vocab, list_cap).off_need;
 }
 
 dvp_status dvp_fused_lmhead_lists(const dvp_lmhead_params *p, const void *hidden, const void *w_train,

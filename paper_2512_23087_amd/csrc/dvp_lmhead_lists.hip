@@ -217,7 +217,130 @@ __global__ __launch_bounds__(kThreads) void lm_dw_gather_kernel(const LmListArgs
     }
 }
 
+// zy_low[i]: a value safely below the logit of row i's sampled token as the matrix cores will form it
+// (the same dot product summed in another order: they differ by accumulation rounding, far less than the
+// margin taken off here), hence below the row maximum.  One wavefront per row.
+__global__ __launch_bounds__(kWave) void lm_zy_low_kernel(const uint16_t *H, int64_t ld_h, const uint16_t *W, int64_t ld_w,
+                                                          const int64_t *ids, float *zy_low, int d, int v)
+{
+    const int i = blockIdx.x, lane = threadIdx.x;
+    const int64_t y = ids[i];
+    if (y < 0 || y >= (int64_t)v) {
+        if (lane == 0) zy_low[i] = -INFINITY;
+        return;
+    }
+    const uint16_t *h = H + (int64_t)i * ld_h, *w = W + y * ld_w;
+    float acc = 0.0f;
+    for (int j0 = lane * 8; j0 < d; j0 += kWave * 8) {
+        const u32x4 a = *(const u32x4 *)(h + j0), b = *(const u32x4 *)(w + j0);
+        const uint32_t x[4] = {a.x, a.y, a.z, a.w}, u[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            acc += __uint_as_float(x[k] << 16) * __uint_as_float(u[k] << 16);
+            acc += __uint_as_float(x[k] & 0xffff0000u) * __uint_as_float(u[k] & 0xffff0000u);
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, kWave);
+    if (lane == 0) zy_low[i] = acc - 1e-3f * (1.0f + fabsf(acc));
+}
+
+// One workgroup per token row: the candidates at or above the final threshold are the safe set.
+// Sorted by token, so the sum has a fixed order whatever the arrival order was.
+__global__ __launch_bounds__(kThreads) void lm_candidates_finish_kernel(const LmCandArgs a)
+{
+    __shared__ unsigned long long key[kLmCandMax];
+    __shared__ float part[kThreads];
+    __shared__ int n_safe;
+    const int i = blockIdx.x, tid = threadIdx.x;
+    const int nc = a.cand_count[i];
+    if (nc > kLmCandMax) {                             // this side is redone with a second pass over the logits
+        if (tid == 0) *a.need_second_pass = 1;
+        return;
+    }
+    const float m = a.m[i], tau = a.tau[i];
+    const dvp_grad_entry *cand = a.cand + (int64_t)i * kLmCandMax;
+    int pow2 = 1;
+    while (pow2 < nc) pow2 <<= 1;
+    if (tid == 0) n_safe = 0;
+    int mine = 0;
+    for (int p = tid; p < pow2; p += kThreads) {
+        unsigned long long k = ~0ull;
+        if (p < nc) {
+            const dvp_grad_entry e = cand[p];
+            if (e.value >= tau) { k = ((unsigned long long)e.index << 32) | (unsigned long long)__float_as_uint(e.value); ++mine; }
+        }
+        key[p] = k;
+    }
+    for (int k = 2; k <= pow2; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            __syncthreads();
+            for (int p = tid; p < pow2; p += kThreads) {
+                const int q = p ^ j;
+                if (q > p) {
+                    const unsigned long long x = key[p], y = key[q];
+                    const bool up = (p & k) == 0;
+                    if ((x > y) == up) { key[p] = y; key[q] = x; }
+                }
+            }
+        }
+    }
+    __syncthreads();
+    if (mine) atomicAdd(&n_safe, mine);
+    __syncthreads();
+    const int c = n_safe;                              // the safe tokens are key[0 .. c), by token
+    float s = 0.0f;
+    for (int p = tid; p < c; p += kThreads) s += __expf(__uint_as_float((uint32_t)key[p]) - m);
+    part[tid] = s;
+    __syncthreads();
+    for (int off = kThreads / 2; off > 0; off >>= 1) {
+        if (tid < off) part[tid] += part[tid + off];
+        __syncthreads();
+    }
+    const float sum = part[0];
+    if (a.entries && c <= a.list_cap) {
+        dvp_grad_entry *list = a.entries + (int64_t)i * a.list_cap;
+        for (int p = tid; p < c; p += kThreads) {
+            list[p].index = (uint32_t)(key[p] >> 32);
+            list[p].value = __expf(__uint_as_float((uint32_t)key[p]) - m);
+        }
+    }
+    if (tid != 0) return;
+    const float log_s = logf(sum);
+    const int64_t y = a.ids[i];
+    const bool y_ok = y >= 0 && y < (int64_t)a.v;
+    const float zy = a.zy[i];
+    const bool y_safe = y_ok && zy >= tau;
+    if (a.side == 0) {
+        const float c_i = !y_safe ? 0.0f : (a.grad_out ? a.grad_out[i] : 0.0f);
+        a.coef[i] = c_i != 0.0f ? c_i * (1.0f - __expf(zy - m) / sum) : 0.0f;
+        a.scale[i] = -c_i / sum;
+    }
+    if (a.out.row_max) a.out.row_max[i] = m;
+    if (a.out.lse_safe) a.out.lse_safe[i] = m + log_s;
+    if (a.out.safe_count) a.out.safe_count[i] = c;
+    if (a.out.logp) a.out.logp[i] = !y_ok ? __uint_as_float(0x7fc00000u) : (y_safe ? (zy - m) - log_s : -INFINITY);
+    if (a.row_flags) {
+        uint32_t fl = a.side == 0 ? (y_ok ? 0u : (uint32_t)DVP_ROW_ID_OUT_OF_RANGE) : a.row_flags[i];
+        if (y_safe) fl |= a.side == 0 ? DVP_ROW_Y_IN_TRAIN_SAFE : DVP_ROW_Y_IN_INFER_SAFE;
+        a.row_flags[i] = (uint8_t)fl;
+    }
+}
+
 }  // namespace
+
+hipError_t launch_lmhead_zy_low(const uint16_t *H, int64_t ld_h, const uint16_t *W, int64_t ld_w, const int64_t *ids,
+                                float *zy_low, int n, int d, int v, hipStream_t stream)
+{
+    hipLaunchKernelGGL(lm_zy_low_kernel, dim3((unsigned)n), dim3(kWave), 0, stream, H, ld_h, W, ld_w, ids, zy_low, d, v);
+    return hipGetLastError();
+}
+
+hipError_t launch_lmhead_candidates_finish(const LmCandArgs &a, hipStream_t stream)
+{
+    hipLaunchKernelGGL(lm_candidates_finish_kernel, dim3((unsigned)a.n), dim3(kThreads), 0, stream, a);
+    return hipGetLastError();
+}
 
 hipError_t launch_lmhead_lists_backward(const LmListArgs &a, hipStream_t stream)
 {

@@ -33,7 +33,7 @@ def dvp():
     return binding
 
 
-def _run(dvp, wl, rho, cap, infer=True):
+def _run(dvp, wl, rho, cap, infer=True, lse_full=False):
     lr = dvp.log_rho(rho)
     ids = wl.ids.cpu().numpy()
     n = ids.shape[0]
@@ -43,7 +43,8 @@ def _run(dvp, wl, rho, cap, infer=True):
     g = wl.grad_out.cpu().numpy().astype(np.float64).copy()
     g[band_rows] = 0.0
     gout = torch.tensor(g, dtype=torch.float32, device="cuda")
-    res = dvp.dvp_fused_lmhead_lists(wl.hidden, wl.w_train, wl.w_infer if infer else None, wl.ids, gout, lr, cap)
+    res = dvp.dvp_fused_lmhead_lists(wl.hidden, wl.w_train, wl.w_infer if infer else None, wl.ids, gout, lr, cap,
+                                     lse_full=lse_full)
     torch.cuda.synchronize()
 
     same_t = _check_side("train", res.train, fwd, fwd)
@@ -97,11 +98,32 @@ def _run(dvp, wl, rho, cap, infer=True):
 
 
 def test_peaked_rows_against_oracle(dvp):
+    """Short safe sets: each side's forward is finished from the candidates of its first pass; with
+    lse_full every token's exponential is needed and the second pass runs instead."""
     wl = workloads.make_lmhead(device="cuda", n=300, d=128, v=3000, hidden_scale=60.0)
     for rho, cap in ((1e-4, 64), (1e-2, 16), (1e-4, 8)):
         res, fwd, listed = _run(dvp, wl, rho, cap)
         assert listed.sum() > 50
+        assert res.second_pass.tolist() == [0, 0]          # one pass over the logits per side was enough
     assert np.median(fwd["safe_count"]) < 64
+    _run(dvp, wl, 1e-4, 64, lse_full=True)
+
+
+def test_flat_rows_among_peaked_ones(dvp):
+    """A few rows with tiny hidden states (flat logits: every token is a candidate, more than are kept)
+    send the whole side through its second pass; the peaked rows still get their lists."""
+    wl = workloads.make_lmhead(device="cuda", n=520, d=128, v=3000, hidden_scale=60.0)
+    wl.hidden[::37] = (wl.hidden[::37].float() * 1e-3).to(torch.bfloat16)
+    res, fwd, listed = _run(dvp, wl, 1e-4, 64)
+    assert (fwd["safe_count"][::37] == 3000).all() and listed.sum() > 300
+    assert res.second_pass.tolist() == [1, 1]
+    # and a row whose sampled token is far below the maximum: no help from it for the bound
+    wl = workloads.make_lmhead(device="cuda", n=300, d=128, v=900, hidden_scale=60.0)
+    z = wl.hidden.float() @ wl.w_train.float().T
+    wl.ids[:50] = z[:50].argmin(dim=1)
+    res, fwd, listed = _run(dvp, wl, 1e-4, 64)
+    assert (fwd["y_in_safe"][:50] == 0).all() and (res.grad_len[:50] == 0).all()
+    assert res.second_pass.tolist() == [0, 0]              # 900 tokens: whatever the bound, the candidates fit
 
 
 @pytest.mark.parametrize("n,d,v,cap", [(1, 64, 3, 4), (2, 64, 1, 1), (257, 192, 257, 300), (33, 64, 513, 1024),
@@ -124,9 +146,14 @@ def test_agrees_with_the_dense_call_and_repeats_bit_for_bit(dvp):
     valid = torch.arange(1024, device="cuda")[None, :] < a.grad_len[:, None]     # entries past a row's length are unspecified
     for x, y in ((a.d_hidden, b.d_hidden), (a.d_w, b.d_w), (a.entries[valid], b.entries[valid]), (a.grad_len, b.grad_len)):
         assert torch.equal(x, y)
-    # the same forward kernels: identical outputs; the dense call rounds E to bf16, so gradients agree to 2^-8 relative
-    assert torch.equal(a.train.logp, ref.train.logp) and torch.equal(a.infer.logp, ref.infer.logp)
+    assert torch.equal(a.train.logp, b.train.logp) and torch.equal(a.infer.lse_safe, b.infer.lse_safe)
+    # the same logits, thresholds and safe sets as the dense call; the sums run in another order (by token
+    # here, by tile there); the dense call rounds E to bf16, so gradients agree to 2^-8 relative
+    assert torch.equal(a.train.row_max, ref.train.row_max) and torch.equal(a.infer.row_max, ref.infer.row_max)
     assert torch.equal(a.train.safe_count, ref.train.safe_count) and torch.equal(a.row_flags, ref.row_flags)
+    for x, y in ((a.train.logp, ref.train.logp), (a.infer.logp, ref.infer.logp), (a.train.lse_safe, ref.train.lse_safe)):
+        fin = torch.isfinite(y)
+        assert torch.equal(torch.isfinite(x), fin) and (x[fin] - y[fin]).abs().max().item() <= 2e-6 * (1 + y[fin].abs().max().item())
     scale_h = ref.d_hidden.abs().max().item()
     scale_w = ref.d_w.abs().max().item()
     assert (a.d_hidden - ref.d_hidden).abs().max().item() <= 2.0 ** -6 * scale_h
@@ -161,6 +188,7 @@ def test_full_size_peaked_sampled_rows(dvp):
     lr = dvp.log_rho(1e-4)
     res = dvp.dvp_fused_lmhead_lists(wl.hidden, wl.w_train, wl.w_infer, wl.ids, wl.grad_out, lr, cap)
     torch.cuda.synchronize()
+    assert res.second_pass.tolist() == [0, 0]
     rng = np.random.default_rng(2)
     rows = np.unique(np.concatenate([[0, n - 1], rng.choice(n, 46, replace=False)]))
     ridx = torch.as_tensor(rows, device="cuda")

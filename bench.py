@@ -163,10 +163,10 @@ def bench_lmhead(args):
                                  res.grad_len).sum().item())
         # two forwards as matrix products (one pass each, two where a side needed its second pass), the
         # gradient as |lists| x d multiply-adds, twice
-        second = [int(x) for x in res.second_pass.cpu().tolist()]
-        passes = 2 + sum(second)
+        second = [int(x) for x in res.second_pass.cpu().tolist()]      # rows of each side that went through a second pass
+        passes = 2 + sum(second) / n
         useful, executed = 2 * gemm + 4.0 * listed * d, passes * gemm + 4.0 * listed * d
-        extra = {"list_cap": lists_cap, "list_entries": listed, "rows_over_cap": over, "gemm_passes": passes,
+        extra = {"list_cap": lists_cap, "list_entries": listed, "rows_over_cap": over, "gemm_passes": passes, "second_pass_rows": second,
                  "mean_safe_set": float(res.train.safe_count.float().mean().item())}
     # (each side's forward produces the logits twice: row max first, then sums at the threshold)
     # Peak for the mix of passes: each contraction is priced at the peak of its own operand type, so the
@@ -192,7 +192,7 @@ def bench_lmhead(args):
         "roofline": {"bound": "mfma", "achieved": executed / (ms * 1e-3) / 1e12,
                      "peak": peak, "unit": "TFLOP/s",
                      "frac": executed / (ms * 1e-3) / 1e12 / peak, "traffic": None,
-                     "kernel": "gemm_nt_kernel (%d GEMM passes of 2*N*V*d flop each per call%s)"
+                     "kernel": "gemm_nt_kernel (%.4g GEMM passes of 2*N*V*d flop each per call%s)"
                                % (extra.get("gemm_passes", 6), ": 4 bf16 at 2.5 PFLOP/s peak, 2 fp8 at 5.0" if f8 else ""),
                      "kernel_ms_avg": ms, "executed_tflop": executed / 1e12,
                      "useful_tflop": useful / 1e12,

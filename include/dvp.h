@@ -283,9 +283,10 @@ dvp_status dvp_fused_lmhead(const dvp_lmhead_params *params, const void *hidden,
  * Where rows are peaked the forward of a side needs only one pass: the first pass collects, next to the
  * row maxima, every token that can still be safe (those at or above a lower bound of the final
  * threshold, formed from the row's maximum over a block of 128 columns and from the sampled token's own
- * logit), and the safe set, its sum and the list are read off these candidates; a side whose rows hold more
- * candidates than are kept, or whose lse_full is asked for, runs its second pass as in dvp_fused_lmhead.
- * Which happens depends on the inputs only, never on timing.
+ * logit), and the safe set, its sum and the list are read off these candidates.  Rows that hold more
+ * candidates than are kept (flat rows) are gathered and go through a second pass as in dvp_fused_lmhead;
+ * so does every row of a side whose lse_full is asked for.  Which rows do depends on the inputs only,
+ * never on timing.
  *   entries, grad_len, list_cap   as for dvp_forward_backward_sparse, with list_cap at most 1024;
  *              a row's entries come out sorted by token; what lies beyond grad_len[i] in a row of
  *              entries is unspecified.  grad_len and row_flags are required.
@@ -303,12 +304,12 @@ dvp_status dvp_fused_lmhead(const dvp_lmhead_params *params, const void *hidden,
 size_t dvp_fused_lmhead_lists_workspace_bytes(const dvp_lmhead_params *params, int32_t list_cap);
 
 /*
- * Byte offset, inside that workspace, of two DEVICE int32 that tell after a dvp_fused_lmhead_lists call
- * which sides (training, inference) needed their second pass over the logits although lse_full was
- * not asked for: 1 when some row had more candidates than are kept (2048), else 0.  For measurement:
- * a side without second pass costs one GEMM pass instead of two.  0 on invalid arguments.
+ * Byte offset, inside that workspace, of two DEVICE int32 that hold after a dvp_fused_lmhead_lists call
+ * the number of rows of each side (training, inference) that went through a second pass over their
+ * logits although lse_full was not asked for: the rows with more candidates than are kept (2048).
+ * For measurement: a side costs one GEMM pass over all rows plus one over these.  0 on invalid arguments.
  */
-size_t dvp_fused_lmhead_lists_second_pass_flags(const dvp_lmhead_params *params, int32_t list_cap);
+size_t dvp_fused_lmhead_lists_second_pass_rows(const dvp_lmhead_params *params, int32_t list_cap);
 
 dvp_status dvp_fused_lmhead_lists(const dvp_lmhead_params *params, const void *hidden,
                                   const void *w_train, const void *w_infer, const int64_t *ids,

@@ -140,7 +140,7 @@ struct LmCandArgs {
     float *coef, *scale;          // [n], side 0 only
     dvp_grad_entry *entries;      // side 0: [n, list_cap] (token, exp(z - m)) for rows that fit; else null
     int32_t list_cap;
-    int32_t *need_second_pass;    // set to 1 when a row's candidates did not fit
+    int32_t *overflow;            // [n] out: 1 where the row's candidates did not fit (nothing else is written for it)
     int32_t n, v, side;
 };
 
@@ -159,5 +159,20 @@ hipError_t launch_lmhead_lists_backward(const LmListArgs &a, hipStream_t stream)
 hipError_t launch_lmhead_zy_low(const uint16_t *H, int64_t ld_h, const uint16_t *W, int64_t ld_w, const int64_t *ids,
                                 float *zy_low, int n, int d, int v, hipStream_t stream);
 hipError_t launch_lmhead_candidates_finish(const LmCandArgs &a, hipStream_t stream);
+
+// The rows flagged in `overflow`, in row order: their indices (rowmap), their number (*n_sub, and a copy
+// in *n_report), their hidden states gathered into consecutive rows of Hc [n, d] and their
+// m and tau into m_sub, tau_sub.
+struct LmSubsetArgs {
+    const int32_t *overflow;
+    int32_t *rowmap, *n_sub, *n_report;
+    const uint16_t *H;
+    int64_t ld_h;
+    uint16_t *Hc;
+    const float *m, *tau;
+    float *m_sub, *tau_sub;
+    int32_t n, d;
+};
+hipError_t launch_lmhead_subset(const LmSubsetArgs &a, hipStream_t stream);
 
 }  // namespace dvp

@@ -95,7 +95,7 @@ struct GemmArgs {
 // ---------------------------------------------------------------------------
 struct EpiMax {
     static constexpr bool kUsesTileLds = false;
-    static constexpr bool kGated = false;
+    static constexpr bool kRowMap = false;
     RowStats st;
     const int64_t *ids;
     __device__ __forceinline__ void operator()(const GemmArgs &g, f32x16 (&acc)[MI][NI], int r0, int c0, int lane, uint8_t *, int, int) const
@@ -133,7 +133,7 @@ struct EpiMax {
 // Candidates (token, z) are appended in arrival order; at most cand_cap are kept.
 struct EpiMaxCand {
     static constexpr bool kUsesTileLds = false;
-    static constexpr bool kGated = false;
+    static constexpr bool kRowMap = false;
     RowStats st;
     const int64_t *ids;
     const float *zy_low;     // [n] lower bound of the row maximum, -inf where there is none
@@ -200,12 +200,13 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)   // hardwar
 // WRITE_LIST: also append every safe token of a row, with exp(z - m), to that row's list (arrival
 // order; at most list_cap entries are kept, the cursor stops a little above that).  Meant for rows
 // whose safe sets are short: the branch is then rarely taken.
-// GATED: the launch does nothing unless *run_if is non-zero (a pass that an earlier kernel may have made
-// unnecessary).
-template <bool WRITE_E, bool WRITE_BITS = false, bool WRITE_LIST = false, bool GATED = false>
+// ROWMAP: the launch covers a subset of the token rows, gathered into consecutive rows of A: their
+// number is read from device memory (*n_sub; zero: nothing to do), the per-row statistics and partials
+// are indexed by position in the subset, and lists by the row's own index rowmap[position].
+template <bool WRITE_E, bool WRITE_BITS = false, bool WRITE_LIST = false, bool ROWMAP = false>
 struct EpiSum {
     static constexpr bool kUsesTileLds = WRITE_E;   // the bf16 staging lives in the operand tiles
-    static constexpr bool kGated = GATED;
+    static constexpr bool kRowMap = ROWMAP;
     RowStats st;
     int n_rows;
     const int64_t *ids;      // WRITE_E: the sampled token's own entry of E is stored as zero
@@ -216,7 +217,8 @@ struct EpiSum {
     dvp_grad_entry *entries; // WRITE_LIST: [n_rows, list_cap]
     int *cursor;             // WRITE_LIST: [n_rows] entries appended so far, zero before the launch
     int list_cap;
-    const int *run_if;       // GATED
+    const int *rowmap;       // ROWMAP
+    const int *n_sub;        // ROWMAP
     __device__ __forceinline__ void operator()(const GemmArgs &g, f32x16 (&acc)[MI][NI], int r0, int c0, int lane, uint8_t *lds, int wave, int wn) const
     {
         const bool want_full = st.part_f != nullptr;
@@ -258,11 +260,13 @@ struct EpiSum {
                         s += kept;
                         if constexpr (WRITE_LIST) {
                             if (safe) {
-                                int *cur = cursor + row;   // read past the L1: a full list stops the appends
+                                int lrow = row;
+                                if constexpr (ROWMAP) lrow = rowmap[row];
+                                int *cur = cursor + lrow;   // read past the L1: a full list stops the appends
                                 if (__hip_atomic_load(cur, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) <= list_cap) {
                                     const int pos = atomicAdd(cur, 1);
                                     if (pos < list_cap) {
-                                        dvp_grad_entry *e = entries + (int64_t)row * list_cap + pos;
+                                        dvp_grad_entry *e = entries + (int64_t)lrow * list_cap + pos;
                                         e->index = (uint32_t)col; e->value = kept;
                                     }
                                 }
@@ -349,7 +353,7 @@ struct EpiSum {
 
 struct EpiStore {
     static constexpr bool kUsesTileLds = false;
-    static constexpr bool kGated = false;
+    static constexpr bool kRowMap = false;
     float *C;                // [M, ldc] fp32
     int64_t ldc;
     int accumulate;          // 0: C = v, 1: C += v
@@ -437,12 +441,15 @@ struct TilePlace {
 // four.  Lane l takes the 32 bytes (two swizzled 16-byte chunks) 4 * pair + 2 * (l / 32) of its row, of A
 // and of B alike, so both operands present the same k to the same position of the instruction.
 template <class Epi, bool NEEDS_FINISH, bool F8>
-__global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs g, const Epi epi, int tiles_m, int tiles_n)
+__global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs g_host, const Epi epi, int tiles_m, int tiles_n)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];   // [stage][A | B][256 rows][128 B], then sums scratch
 
-    if constexpr (Epi::kGated) {
-        if (*epi.run_if == 0) return;   // the same for every lane of the grid
+    GemmArgs g = g_host;
+    if constexpr (Epi::kRowMap) {       // the row count comes from an earlier kernel; the grid was sized for g_host.M
+        g.M = *epi.n_sub;
+        tiles_m = (g.M + BM - 1) / BM;
+        if ((int)blockIdx.x >= tiles_m * tiles_n) return;
     }
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave), lane = tid % kWave;
@@ -691,9 +698,11 @@ constexpr int kAfterRows = 32, kAfterSegs = 8;
 __global__ __launch_bounds__(kAfterRows * kAfterSegs) void after_sum_kernel(RowStats st, SideOut out, const int64_t *ids,
                                                                             const float *grad_out, uint8_t *row_flags,
                                                                             int n, int vocab, int col_tiles, int side,
-                                                                            int unit_grad, const int *run_if)
+                                                                            int unit_grad, const int *rowmap, const int *n_sub)
 {
-    if (run_if && *run_if == 0) return;   // see EpiSum's GATED
+    // rowmap / n_sub: see EpiSum's ROWMAP; n stays the stride of the partials
+    const int n_rows = n_sub ? *n_sub : n;
+    if ((int)blockIdx.x * kAfterRows >= n_rows) return;
     __shared__ float seg_s[kAfterSegs][kAfterRows], seg_f[kAfterSegs][kAfterRows];
     __shared__ int seg_c[kAfterSegs][kAfterRows];
     const int r = threadIdx.x % kAfterRows, seg = threadIdx.x / kAfterRows;
@@ -702,7 +711,7 @@ __global__ __launch_bounds__(kAfterRows * kAfterSegs) void after_sum_kernel(RowS
     const int t0 = seg * per, t1 = (t0 + per) < col_tiles ? (t0 + per) : col_tiles;
     float s = 0.0f, f = 0.0f;
     int c = 0;
-    if (i < n) {
+    if (i < n_rows) {
         for (int t = t0; t < t1; ++t) {
             const int64_t o = (int64_t)t * n + i;
             s += st.part_s[o];
@@ -712,31 +721,32 @@ __global__ __launch_bounds__(kAfterRows * kAfterSegs) void after_sum_kernel(RowS
     }
     seg_s[seg][r] = s; seg_f[seg][r] = f; seg_c[seg][r] = c;
     __syncthreads();
-    if (seg != 0 || i >= n) return;
+    if (seg != 0 || i >= n_rows) return;
 #pragma unroll
     for (int q = 1; q < kAfterSegs; ++q) { s += seg_s[q][r]; f += seg_f[q][r]; c += seg_c[q][r]; }
     const float m = st.m[i], tau = st.tau[i];
+    const int w = rowmap ? rowmap[i] : i;            // the row everything but m, tau and the partials is indexed by
     const float log_s = logf(s);
-    const int64_t y = ids[i];
+    const int64_t y = ids[w];
     const bool y_ok = y >= 0 && y < (int64_t)vocab;
-    const float zy = st.zy[i];
+    const float zy = st.zy[w];
     const bool y_safe = y_ok && zy >= tau;
     if (side == 0) {
         // unit_grad: the factors of a gradient still to come, q / g and s / g (Prop. 5.4 is linear in g)
-        const float c_i = !y_safe ? 0.0f : (unit_grad ? 1.0f : (grad_out ? grad_out[i] : 0.0f));
-        st.coef[i] = c_i != 0.0f ? c_i * (1.0f - __expf(zy - m) / s) : 0.0f;
-        st.scale[i] = -c_i / s;
+        const float c_i = !y_safe ? 0.0f : (unit_grad ? 1.0f : (grad_out ? grad_out[w] : 0.0f));
+        st.coef[w] = c_i != 0.0f ? c_i * (1.0f - __expf(zy - m) / s) : 0.0f;
+        st.scale[w] = -c_i / s;
     }
-    if (out.row_max) out.row_max[i] = m;
-    if (out.lse_safe) out.lse_safe[i] = m + log_s;
-    if (out.lse_full) out.lse_full[i] = m + logf(f);
-    if (out.safe_count) out.safe_count[i] = c;
+    if (out.row_max) out.row_max[w] = m;
+    if (out.lse_safe) out.lse_safe[w] = m + log_s;
+    if (out.lse_full) out.lse_full[w] = m + logf(f);
+    if (out.safe_count) out.safe_count[w] = c;
     if (out.logp)
-        out.logp[i] = !y_ok ? __uint_as_float(0x7fc00000u) : (y_safe ? (zy - m) - log_s : -INFINITY);
+        out.logp[w] = !y_ok ? __uint_as_float(0x7fc00000u) : (y_safe ? (zy - m) - log_s : -INFINITY);
     if (row_flags) {
-        uint32_t fl = side == 0 ? (y_ok ? 0u : (uint32_t)DVP_ROW_ID_OUT_OF_RANGE) : row_flags[i];
+        uint32_t fl = side == 0 ? (y_ok ? 0u : (uint32_t)DVP_ROW_ID_OUT_OF_RANGE) : row_flags[w];
         if (y_safe) fl |= side == 0 ? DVP_ROW_Y_IN_TRAIN_SAFE : DVP_ROW_Y_IN_INFER_SAFE;
-        row_flags[i] = (uint8_t)fl;
+        row_flags[w] = (uint8_t)fl;
     }
 }
 
@@ -875,7 +885,7 @@ static LmLayout lm_layout(int64_t n, int64_t d, int64_t v, bool dense_buffers = 
 struct LmListLayout {
     LmLayout stats;
     size_t total, off_cursor, off_count, off_blk, off_colstart, off_grp, off_cscrow, off_cscval;
-    size_t off_zylow, off_cand, off_candcur, off_need;
+    size_t off_zylow, off_cand, off_candcur, off_need, off_ovf, off_rowmap, off_nsub, off_hc, off_msub, off_tausub;
     int n_blk, rows_per_blk;
 };
 
@@ -901,6 +911,12 @@ static LmListLayout lm_list_layout(int64_t n, int64_t d, int64_t v, int64_t cap)
     L.off_cand = take((size_t)n * kLmCandMax * sizeof(dvp_grad_entry));
     L.off_candcur = take(n * 4);
     L.off_need = take(2 * 4);
+    L.off_ovf = take(n * 4);
+    L.off_rowmap = take(n * 4);
+    L.off_nsub = take(4);
+    L.off_hc = take((size_t)n * d * 2);
+    L.off_msub = take(n * 4);
+    L.off_tausub = take(n * 4);
     L.total = o;
     return L;
 }
@@ -1071,7 +1087,7 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
         hipLaunchKernelGGL(after_sum_kernel, dim3((rows + kAfterRows - 1) / kAfterRows),
                            dim3(kAfterRows * kAfterSegs), 0, stream, st, o, ids + r0,
                            grad_out ? grad_out + r0 : nullptr, row_flags ? row_flags + r0 : nullptr, rows, v,
-                           L.col_tiles, s, phase == LM_FORWARD_SAVE ? 1 : 0, (const int *)nullptr);
+                           L.col_tiles, s, phase == LM_FORWARD_SAVE ? 1 : 0, (const int *)nullptr, (const int *)nullptr);
         DVP_CHECK_LAUNCH();
         return DVP_OK;
     };
@@ -1231,7 +1247,6 @@ static dvp_status run_lmhead_lists(const dvp_lmhead_params *p, const void *hidde
         hipLaunchKernelGGL(init_stats_kernel, dim3(nb), dim3(tb), 0, stream, st, n);
         DVP_CHECK_LAUNCH();
         const bool one_pass = o.lse_full == nullptr;   // the full sum needs every token's exponential
-        const int *gate = one_pass ? need + s : nullptr;
         if (one_pass) {
             if (launch_lmhead_zy_low((const uint16_t *)hidden, p->ld_hidden, g.B, p->ld_w, ids, zy_low, n, d, v, stream) !=
                 hipSuccess)
@@ -1252,29 +1267,51 @@ static dvp_status run_lmhead_lists(const dvp_lmhead_params *p, const void *hidde
             c.ids = ids; c.grad_out = grad_out; c.out = o; c.row_flags = row_flags;
             c.coef = st.coef; c.scale = st.scale;
             c.entries = s == 0 ? entries : nullptr; c.list_cap = list_cap;
-            c.need_second_pass = need + s; c.n = n; c.v = v; c.side = s;
+            c.overflow = (int32_t *)(ws + LL.off_ovf); c.n = n; c.v = v; c.side = s;
             if (launch_lmhead_candidates_finish(c, stream) != hipSuccess) return DVP_ERR_HIP;
         }
-        // second pass: always where lse_full is wanted, else only if the candidates of some row did not fit
+        // Second pass: over every row where lse_full is wanted; else over the rows whose candidates did
+        // not fit, gathered into consecutive rows (their number is only known on the device: the launches
+        // are sized for all rows and find out there; none: they exit at once).
         hipError_t eb;
-        if (s == 0 && one_pass)
-            eb = launch_gemm<EpiSum<false, false, true, true>, true>(
-                g, EpiSum<false, false, true, true>{st, n, nullptr, nullptr, nullptr, 0, 0, nullptr, 0, entries, cursor, list_cap, gate},
-                stream);
-        else if (s == 0)
-            eb = launch_gemm<EpiSum<false, false, true>, true>(
-                g, EpiSum<false, false, true>{st, n, nullptr, nullptr, nullptr, 0, 0, nullptr, 0, entries, cursor, list_cap, nullptr},
-                stream);
-        else if (one_pass)
-            eb = launch_gemm<EpiSum<false, false, false, true>, true>(
-                g, EpiSum<false, false, false, true>{st, n, nullptr, nullptr, nullptr, 0, 0, nullptr, 0, nullptr, nullptr, 0, gate},
-                stream);
-        else
-            eb = launch_gemm<EpiSum<false>, true>(g, EpiSum<false>{st, n, nullptr, nullptr, nullptr, 0, 0, nullptr, 0}, stream);
-        if (eb != hipSuccess) return DVP_ERR_HIP;
-        hipLaunchKernelGGL(after_sum_kernel, dim3((n + kAfterRows - 1) / kAfterRows), dim3(kAfterRows * kAfterSegs), 0,
-                           stream, st, o, ids, grad_out, row_flags, n, v, L.col_tiles, s, 0, gate);
-        DVP_CHECK_LAUNCH();
+        if (one_pass) {
+            int *rowmap = (int *)(ws + LL.off_rowmap), *n_sub = (int *)(ws + LL.off_nsub);
+            LmSubsetArgs sa;
+            sa.overflow = (const int32_t *)(ws + LL.off_ovf); sa.rowmap = rowmap; sa.n_sub = n_sub; sa.n_report = need + s;
+            sa.H = (const uint16_t *)hidden; sa.ld_h = p->ld_hidden; sa.Hc = (uint16_t *)(ws + LL.off_hc);
+            sa.m = st.m; sa.tau = st.tau; sa.m_sub = (float *)(ws + LL.off_msub); sa.tau_sub = (float *)(ws + LL.off_tausub);
+            sa.n = n; sa.d = d;
+            if (launch_lmhead_subset(sa, stream) != hipSuccess) return DVP_ERR_HIP;
+            GemmArgs gs = g;
+            gs.A = sa.Hc; gs.lda = d;
+            RowStats sub = st;                    // m, tau and the partials by position in the subset
+            sub.m = sa.m_sub; sub.tau = sa.tau_sub;
+            if (s == 0)
+                eb = launch_gemm<EpiSum<false, false, true, true>, true>(
+                    gs, EpiSum<false, false, true, true>{sub, n, nullptr, nullptr, nullptr, 0, 0, nullptr, 0, entries, cursor, list_cap,
+                                                         rowmap, n_sub}, stream);
+            else
+                eb = launch_gemm<EpiSum<false, false, false, true>, true>(
+                    gs, EpiSum<false, false, false, true>{sub, n, nullptr, nullptr, nullptr, 0, 0, nullptr, 0, nullptr, nullptr, 0,
+                                                          rowmap, n_sub}, stream);
+            if (eb != hipSuccess) return DVP_ERR_HIP;
+            hipLaunchKernelGGL(after_sum_kernel, dim3((n + kAfterRows - 1) / kAfterRows), dim3(kAfterRows * kAfterSegs), 0,
+                               stream, sub, o, ids, grad_out, row_flags, n, v, L.col_tiles, s, 0, (const int *)rowmap,
+                               (const int *)n_sub);
+            DVP_CHECK_LAUNCH();
+        } else {
+            if (s == 0)
+                eb = launch_gemm<EpiSum<false, false, true>, true>(
+                    g, EpiSum<false, false, true>{st, n, nullptr, nullptr, nullptr, 0, 0, nullptr, 0, entries, cursor, list_cap,
+                                                  nullptr, nullptr}, stream);
+            else
+                eb = launch_gemm<EpiSum<false>, true>(g, EpiSum<false>{st, n, nullptr, nullptr, nullptr, 0, 0, nullptr, 0}, stream);
+            if (eb != hipSuccess) return DVP_ERR_HIP;
+            hipLaunchKernelGGL(after_sum_kernel, dim3((n + kAfterRows - 1) / kAfterRows), dim3(kAfterRows * kAfterSegs), 0,
+                               stream, st, o, ids, grad_out, row_flags, n, v, L.col_tiles, s, 0, (const int *)nullptr,
+                               (const int *)nullptr);
+            DVP_CHECK_LAUNCH();
+        }
         if (s == 0) {   // before the inference side adds its bit to row_flags: the list kernels only add theirs
             LmListArgs a;
             a.entries = entries; a.grad_len = grad_len; a.row_flags = row_flags; a.safe_count = count0;
@@ -1303,7 +1340,7 @@ size_t dvp_fused_lmhead_lists_workspace_bytes(const dvp_lmhead_params *p, int32_
     return dvp::lm_list_layout(p->n_rows, p->hidden, p->vocab, list_cap).total;
 }
 
-size_t dvp_fused_lmhead_lists_second_pass_flags(const dvp_lmhead_params *p, int32_t list_cap)
+size_t dvp_fused_lmhead_lists_second_pass_rows(const dvp_lmhead_params *p, int32_t list_cap)
 {
     if (!dvp::lm_params_ok(p) || !dvp::lm_list_cap_ok(p, list_cap)) return 0;
     return dvp::lm_list_layout(p->n_rows, p->hidden, p->vocab, list_cap).off_need;

@@ -254,10 +254,8 @@ __global__ __launch_bounds__(kThreads) void lm_candidates_finish_kernel(const Lm
     __shared__ int n_safe;
     const int i = blockIdx.x, tid = threadIdx.x;
     const int nc = a.cand_count[i];
-    if (nc > kLmCandMax) {                             // this side is redone with a second pass over the logits
-        if (tid == 0) *a.need_second_pass = 1;
-        return;
-    }
+    if (tid == 0) a.overflow[i] = nc > kLmCandMax ? 1 : 0;
+    if (nc > kLmCandMax) return;                       // this row goes through a second pass over its logits
     const float m = a.m[i], tau = a.tau[i];
     const dvp_grad_entry *cand = a.cand + (int64_t)i * kLmCandMax;
     int pow2 = 1;
@@ -327,7 +325,56 @@ __global__ __launch_bounds__(kThreads) void lm_candidates_finish_kernel(const Lm
     }
 }
 
+// One workgroup: the flagged rows in row order (a contiguous chunk of rows per thread, a scan of the
+// chunk counts, then each thread writes its chunk's rows).
+constexpr int kCompactThreads = 1024;
+__global__ __launch_bounds__(kCompactThreads) void lm_subset_compact_kernel(const LmSubsetArgs a)
+{
+    __shared__ int part[kCompactThreads];
+    const int tid = threadIdx.x;
+    const int per = (a.n + kCompactThreads - 1) / kCompactThreads;
+    const int r0 = tid * per < a.n ? tid * per : a.n, r1 = (r0 + per) < a.n ? (r0 + per) : a.n;
+    int cnt = 0;
+    for (int r = r0; r < r1; ++r) cnt += a.overflow[r] != 0;
+    part[tid] = cnt;
+    __syncthreads();
+    for (int off = 1; off < kCompactThreads; off <<= 1) {
+        const int add = tid >= off ? part[tid - off] : 0;
+        __syncthreads();
+        part[tid] += add;
+        __syncthreads();
+    }
+    int at = part[tid] - cnt;
+    for (int r = r0; r < r1; ++r)
+        if (a.overflow[r] != 0) a.rowmap[at++] = r;
+    if (tid == kCompactThreads - 1) {
+        *a.n_sub = part[tid];
+        *a.n_report = part[tid];
+    }
+}
+
+// One wavefront per position of the subset (launched for every row; positions past the subset exit)
+__global__ __launch_bounds__(kWave) void lm_subset_gather_kernel(const LmSubsetArgs a)
+{
+    const int j = blockIdx.x, lane = threadIdx.x;
+    if (j >= *a.n_sub) return;
+    const int r = a.rowmap[j];
+    const uint16_t *src = a.H + (int64_t)r * a.ld_h;
+    uint16_t *dst = a.Hc + (int64_t)j * a.d;
+    for (int j0 = lane * 8; j0 < a.d; j0 += kWave * 8) *(u32x4 *)(dst + j0) = *(const u32x4 *)(src + j0);
+    if (lane == 0) { a.m_sub[j] = a.m[r]; a.tau_sub[j] = a.tau[r]; }
+}
+
 }  // namespace
+
+hipError_t launch_lmhead_subset(const LmSubsetArgs &a, hipStream_t stream)
+{
+    hipLaunchKernelGGL(lm_subset_compact_kernel, dim3(1), dim3(kCompactThreads), 0, stream, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(lm_subset_gather_kernel, dim3((unsigned)a.n), dim3(kWave), 0, stream, a);
+    return hipGetLastError();
+}
 
 hipError_t launch_lmhead_zy_low(const uint16_t *H, int64_t ld_h, const uint16_t *W, int64_t ld_w, const int64_t *ids,
                                 float *zy_low, int n, int d, int v, hipStream_t stream)

@@ -25,7 +25,7 @@ EXPORTS = ("dvp_forward", "dvp_backward", "dvp_forward_backward", "dvp_fused_lmh
            "dvp_sequence_weights", "dvp_log_threshold", "dvp_forward_backward_sparse",
            "dvp_fused_lmhead_f8infer", "dvp_lists_to_dense", "dvp_fused_lmhead_saved_bytes",
            "dvp_fused_lmhead_forward", "dvp_fused_lmhead_backward", "dvp_fused_lmhead_lists",
-           "dvp_fused_lmhead_lists_workspace_bytes", "dvp_fused_lmhead_lists_second_pass_flags")
+           "dvp_fused_lmhead_lists_workspace_bytes", "dvp_fused_lmhead_lists_second_pass_rows")
 
 
 class DvpParams(ctypes.Structure):
@@ -98,8 +98,8 @@ def lib():
                                                 ctypes.c_size_t, vp]
         L.dvp_fused_lmhead_lists_workspace_bytes.restype = ctypes.c_size_t
         L.dvp_fused_lmhead_lists_workspace_bytes.argtypes = [lp, ctypes.c_int32]
-        L.dvp_fused_lmhead_lists_second_pass_flags.restype = ctypes.c_size_t
-        L.dvp_fused_lmhead_lists_second_pass_flags.argtypes = [lp, ctypes.c_int32]
+        L.dvp_fused_lmhead_lists_second_pass_rows.restype = ctypes.c_size_t
+        L.dvp_fused_lmhead_lists_second_pass_rows.argtypes = [lp, ctypes.c_int32]
         L.dvp_fused_lmhead_lists.restype = ctypes.c_int
         L.dvp_fused_lmhead_lists.argtypes = [lp, vp, vp, vp, i64p, vp, sp, sp, vp, vp, vp, ctypes.c_int32, vp, vp, vp,
                                              ctypes.c_size_t, vp]
@@ -446,8 +446,8 @@ def dvp_fused_lmhead_lists(hidden, w_train, w_infer, ids, grad_out, log_rho_valu
     if st != 0:
         raise DvpError(st, "dvp_fused_lmhead_lists")
     res = LmHeadListsResult(out_train, out_infer, row_flags, d_hidden, d_w, entries, grad_len)
-    off = int(lib().dvp_fused_lmhead_lists_second_pass_flags(ctypes.byref(p), int(list_cap)))
-    res.second_pass = workspace[off:off + 8].view(torch.int32)      # device int32 [2]: training, inference side
+    off = int(lib().dvp_fused_lmhead_lists_second_pass_rows(ctypes.byref(p), int(list_cap)))
+    res.second_pass = workspace[off:off + 8].view(torch.int32)      # device int32 [2]: rows of each side that needed a second pass
     return res
 
 

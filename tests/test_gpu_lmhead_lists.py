@@ -111,12 +111,12 @@ def test_peaked_rows_against_oracle(dvp):
 
 def test_flat_rows_among_peaked_ones(dvp):
     """A few rows with tiny hidden states (flat logits: every token is a candidate, more than are kept)
-    send the whole side through its second pass; the peaked rows still get their lists."""
+    go through the second pass, gathered; the peaked rows are finished from their candidates."""
     wl = workloads.make_lmhead(device="cuda", n=520, d=128, v=3000, hidden_scale=60.0)
     wl.hidden[::37] = (wl.hidden[::37].float() * 1e-3).to(torch.bfloat16)
     res, fwd, listed = _run(dvp, wl, 1e-4, 64)
     assert (fwd["safe_count"][::37] == 3000).all() and listed.sum() > 300
-    assert res.second_pass.tolist() == [1, 1]
+    assert res.second_pass.tolist() == [len(range(0, 520, 37))] * 2    # exactly the flat rows, on both sides
     # and a row whose sampled token is far below the maximum: no help from it for the bound
     wl = workloads.make_lmhead(device="cuda", n=300, d=128, v=900, hidden_scale=60.0)
     z = wl.hidden.float() @ wl.w_train.float().T

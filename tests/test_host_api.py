@@ -236,7 +236,7 @@ def test_lmhead_argument_validation_needs_no_gpu():
                                         flags, entries, glen, cap, dh, dw, ws, bytes_, None)
 
     small = L.dvp_fused_lmhead_lists_workspace_bytes(ctypes.byref(P(n=16384, d=4096, v=151936)), 64)
-    assert 0 < small < L.dvp_fused_lmhead_workspace_bytes(ctypes.byref(P(n=16384, d=4096, v=151936))) // 8
+    assert 0 < small < L.dvp_fused_lmhead_workspace_bytes(ctypes.byref(P(n=16384, d=4096, v=151936))) // 4
     assert L.dvp_fused_lmhead_lists_workspace_bytes(ctypes.byref(P()), 0) == 0
     assert L.dvp_fused_lmhead_lists_workspace_bytes(ctypes.byref(P()), 1025) == 0
     assert L.dvp_fused_lmhead_lists_workspace_bytes(ctypes.byref(P(n=1 << 22)), 1024) == 0     # N * cap >= 2^31

@@ -104,7 +104,8 @@ def bench_lmhead(args):
     import torch
     from paper_2512_23087_amd import dvp, workloads
     f8 = args.infer_dtype == "f8"
-    wl = workloads.make_lmhead(device="cuda:0", n=args.rows, f8_engine=f8, hidden_scale=args.hidden_scale)
+    wl = workloads.make_lmhead(device="cuda:0", n=args.rows, f8_engine=f8, hidden_scale=args.hidden_scale,
+                               flat_every=args.flat_every)
     lists_cap = args.sparse_grad            # --sparse-grad on this workload: the gradient kept as per-row lists
     if lists_cap and (f8 or args.split_lists):
         print("bench.py: --sparse-grad on the lmhead workload goes with neither --infer-dtype f8 nor --split-lists",
@@ -184,7 +185,8 @@ def bench_lmhead(args):
                                 "configs[4]: hidden [%d, %d] bf16 x W [%d, %d] bf16 (train) and its "
                                 "fp8-e4m3-rounded copy (infer), rho=%g") % (n, d, v, d, args.rho)
                                + (", hidden states scaled by %g (peaked rows)" % args.hidden_scale
-                                  if args.hidden_scale != 1.0 else ""),
+                                  if args.hidden_scale != 1.0 else "")
+                               + (", every %d-th row left at scale 1 (flat)" % args.flat_every if args.flat_every else ""),
                    "entry_point": "dvp_fused_lmhead_lists" if lists_cap else
                                   "dvp_fused_lmhead_forward + dvp_fused_lmhead_backward" if two_calls else
                                   "dvp_fused_lmhead_f8infer" if f8 else "dvp_fused_lmhead",
@@ -269,6 +271,8 @@ def main():
     ap.add_argument("--hidden-scale", type=float, default=1.0,
                     help="(lmhead workload) multiply the hidden states: 20 gives peaked rows with a few safe tokens "
                          "each; with --sparse-grad CAP one step = dvp_fused_lmhead_lists")
+    ap.add_argument("--flat-every", type=int, default=0, metavar="K",
+                    help="(lmhead workload, with --hidden-scale) every K-th row keeps the scale 1: flat rows among peaked ones")
     ap.add_argument("--infer-dtype", default="same", choices=["same", "f8"],
                     help="f8: the inference logits are rounded through E4M3 (saturating) and handed over as "
                          "one byte per token")

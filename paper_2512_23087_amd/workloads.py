@@ -151,7 +151,7 @@ def make_rows(config: int, device="cpu", n: Optional[int] = None, v: Optional[in
 
 def make_lmhead(device="cpu", n: Optional[int] = None, d: Optional[int] = None,
                 v: Optional[int] = None, chunk: int = 1024, f8_engine: bool = False,
-                hidden_scale: float = 1.0) -> LmHeadWorkload:
+                hidden_scale: float = 1.0, flat_every: int = 0) -> LmHeadWorkload:
     """Hidden states ~ N(0,1), head weights ~ N(0, 0.02^2), both bf16; the
     inference head is the same matrix rounded through fp8-e4m3.  Tokens are
     sampled from the softmax of the inference logits H W_infer^T.
@@ -160,6 +160,8 @@ def make_lmhead(device="cpu", n: Optional[int] = None, d: Optional[int] = None,
     a standard deviation of 0.02 sqrt(d) (1.28 at d = 4096) and nearly every
     token is within log(1e-4) of the row maximum; at 20 they are peaked the way
     a trained model's are, and a row's safe set at rho = 1e-4 is a few tokens.
+    flat_every = k > 0: every k-th row keeps the scale 1 (a batch of peaked rows
+    with flat, high-entropy ones among them).
 
     f8_engine: the inference side is instead an 8-bit engine: activations
     e4m3(H / s_h) and head e4m3(W / s_w) with per-tensor factors s = max|.| / 448
@@ -171,7 +173,12 @@ def make_lmhead(device="cpu", n: Optional[int] = None, d: Optional[int] = None,
     v = c["v"] if v is None else v
     dev = torch.device(device)
     g = _gen(dev, BASE_SEED + 4)
-    hidden = (hidden_scale * torch.randn(n, d, generator=g, device=dev)).to(torch.bfloat16)
+    h32 = torch.randn(n, d, generator=g, device=dev)
+    row_scale = torch.full((n, 1), float(hidden_scale), device=dev)
+    if flat_every > 0:
+        row_scale[::flat_every] = 1.0
+    hidden = (row_scale * h32).to(torch.bfloat16)
+    del h32, row_scale
     w32 = c["w_sigma"] * torch.randn(v, d, generator=g, device=dev)
     w_train = w32.to(torch.bfloat16)
     w_infer = through_e4m3(w_train.to(torch.float32)).to(torch.bfloat16)

@@ -163,21 +163,31 @@ struct EpiMaxCand {
 #pragma unroll
                 for (int off = 16; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
                 if ((lane % 32) == 0 && row_ok) atomicMax(st.max_key + row, float_to_ordered(v));
-                if (!row_ok) continue;
-                const float thr = fmaxf(v, zy_low[row]) + log_rho;   // <= the row's final threshold (fp32 addition is monotone)
+                // <= the row's final threshold (fp32 addition is monotone)
+                const float thr = row_ok ? fmaxf(v, zy_low[row]) + log_rho : INFINITY;
+                bool mine = false;
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni) mine |= (c0 + ni * 32 + (lane % 32)) < g.N && acc[mi][ni][i] >= thr;
+                if (__builtin_amdgcn_ballot_w64(mine) == 0ull) continue;      // the same for the whole wavefront
+                int *cur = cursor + (row_ok ? row : 0);
+                // one look per lane and row: a full buffer stops the appends (a stale value only costs appends)
+                const bool open = mine && __hip_atomic_load(cur, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) <= cand_cap;
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni) {
                     const int col = c0 + ni * 32 + (lane % 32);
                     const float z = acc[mi][ni][i];
-                    if (col < g.N && z >= thr) {
-                        int *cur = cursor + row;
-                        if (__hip_atomic_load(cur, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) <= cand_cap) {
-                            const int pos = atomicAdd(cur, 1);
-                            if (pos < cand_cap) {
-                                dvp_grad_entry *e = cand + (int64_t)row * cand_cap + pos;
-                                e->index = (uint32_t)col; e->value = z;
-                            }
-                        }
+                    const bool take = open && col < g.N && z >= thr;
+                    // the 32 lanes of a row reserve their slots with one atomic (lanes 32..63 hold another row)
+                    const uint32_t group = (uint32_t)(__builtin_amdgcn_ballot_w64(take) >> (lane & 32));
+                    if (group == 0u) continue;
+                    const int leader = __builtin_ctz(group) + (lane & 32);
+                    int base = 0;
+                    if (lane == leader) base = atomicAdd(cur, __builtin_popcount(group));
+                    base = __shfl(base, leader, kWave);
+                    const int pos = base + __builtin_popcount(group & ((1u << (lane % 32)) - 1u));
+                    if (take && pos < cand_cap) {
+                        dvp_grad_entry *e = cand + (int64_t)row * cand_cap + pos;
+                        e->index = (uint32_t)col; e->value = z;
                     }
                 }
             }
@@ -237,6 +247,7 @@ struct EpiSum {
                 if constexpr (WRITE_E) y = row_ok ? ids[row] : -1;
                 float s = 0.0f, f = 0.0f;
                 int c = 0;
+                [[maybe_unused]] int list_open = -1, list_row = 0;   // WRITE_LIST
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni) {
                     const int col = c0 + ni * 32 + (lane % 32);
@@ -260,10 +271,14 @@ struct EpiSum {
                         s += kept;
                         if constexpr (WRITE_LIST) {
                             if (safe) {
-                                int lrow = row;
-                                if constexpr (ROWMAP) lrow = rowmap[row];
-                                int *cur = cursor + lrow;   // read past the L1: a full list stops the appends
-                                if (__hip_atomic_load(cur, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) <= list_cap) {
+                                if (list_open < 0) {       // one look per lane and row: a full list stops the appends
+                                    list_row = row;
+                                    if constexpr (ROWMAP) list_row = rowmap[row];
+                                    list_open = __hip_atomic_load(cursor + list_row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) <= list_cap;
+                                }
+                                const int lrow = list_row;
+                                int *cur = cursor + lrow;
+                                if (list_open) {
                                     const int pos = atomicAdd(cur, 1);
                                     if (pos < list_cap) {
                                         dvp_grad_entry *e = entries + (int64_t)lrow * list_cap + pos;

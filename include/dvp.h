@@ -287,6 +287,9 @@ dvp_status dvp_fused_lmhead(const dvp_lmhead_params *params, const void *hidden,
  * candidates than are kept (flat rows) are gathered and go through a second pass as in dvp_fused_lmhead;
  * so does every row of a side whose lse_full is asked for.  Which rows do depends on the inputs only,
  * never on timing.
+ *   grad_out  DEVICE float [N], or NULL: then only the forward of both sides runs (one pass per side
+ *              where rows are peaked) and entries, grad_len, d_hidden, d_w are ignored; row_flags is
+ *              then optional and list_cap only sizes the workspace.
  *   entries, grad_len, list_cap   as for dvp_forward_backward_sparse, with list_cap at most 1024;
  *              a row's entries come out sorted by token; what lies beyond grad_len[i] in a row of
  *              entries is unspecified.  grad_len and row_flags are required.

@@ -1213,14 +1213,14 @@ static dvp_status run_lmhead_lists(const dvp_lmhead_params *p, const void *hidde
     if (list_cap < 1) return DVP_ERR_PARAM;
     if (!lm_params_ok(p) || !lm_list_cap_ok(p, list_cap)) return DVP_ERR_UNSUPPORTED;
     if (p->n_rows == 0) return DVP_OK;
-    if (!hidden || !w_train || !ids || !grad_out || !out_train || !row_flags || !entries || !grad_len || !d_hidden ||
-        !d_w)
-        return DVP_ERR_NULL;
+    if (!hidden || !w_train || !ids || !out_train) return DVP_ERR_NULL;
+    const bool lists = grad_out != nullptr;        // without grad_out: the forward of both sides only
+    if (lists && (!row_flags || !entries || !grad_len || !d_hidden || !d_w)) return DVP_ERR_NULL;
     if (out_train->entropy || (w_infer && out_infer && out_infer->entropy)) return DVP_ERR_UNSUPPORTED;
     if (out_train->safe_bits || (w_infer && out_infer && out_infer->safe_bits)) return DVP_ERR_UNSUPPORTED;
-    if (((uintptr_t)hidden | (uintptr_t)w_train | (uintptr_t)w_infer | (uintptr_t)d_hidden | (uintptr_t)d_w) % 16)
+    if (((uintptr_t)hidden | (uintptr_t)w_train | (uintptr_t)w_infer) % 16) return DVP_ERR_ALIGN;
+    if (lists && (((uintptr_t)d_hidden | (uintptr_t)d_w) % 16 || ((uintptr_t)entries % 8) || ((uintptr_t)grad_len % 4)))
         return DVP_ERR_ALIGN;
-    if (((uintptr_t)entries % 8) || ((uintptr_t)grad_len % 4)) return DVP_ERR_ALIGN;
     const LmListLayout LL = lm_list_layout(p->n_rows, p->hidden, p->vocab, list_cap);
     const LmLayout &L = LL.stats;
     if (!workspace || ((uintptr_t)workspace % 256) || workspace_bytes < LL.total) return DVP_ERR_WORKSPACE;
@@ -1281,7 +1281,7 @@ static dvp_status run_lmhead_lists(const dvp_lmhead_params *p, const void *hidde
             c.cand = cand; c.cand_count = cand_cur; c.m = st.m; c.tau = st.tau; c.zy = st.zy;
             c.ids = ids; c.grad_out = grad_out; c.out = o; c.row_flags = row_flags;
             c.coef = st.coef; c.scale = st.scale;
-            c.entries = s == 0 ? entries : nullptr; c.list_cap = list_cap;
+            c.entries = (s == 0 && lists) ? entries : nullptr; c.list_cap = list_cap;
             c.overflow = (int32_t *)(ws + LL.off_ovf); c.n = n; c.v = v; c.side = s;
             if (launch_lmhead_candidates_finish(c, stream) != hipSuccess) return DVP_ERR_HIP;
         }
@@ -1301,7 +1301,7 @@ static dvp_status run_lmhead_lists(const dvp_lmhead_params *p, const void *hidde
             gs.A = sa.Hc; gs.lda = d;
             RowStats sub = st;                    // m, tau and the partials by position in the subset
             sub.m = sa.m_sub; sub.tau = sa.tau_sub;
-            if (s == 0)
+            if (s == 0 && lists)
                 eb = launch_gemm<EpiSum<false, false, true, true>, true>(
                     gs, EpiSum<false, false, true, true>{sub, n, nullptr, nullptr, nullptr, 0, 0, nullptr, 0, entries, cursor, list_cap,
                                                          rowmap, n_sub}, stream);
@@ -1315,7 +1315,7 @@ static dvp_status run_lmhead_lists(const dvp_lmhead_params *p, const void *hidde
                                (const int *)n_sub);
             DVP_CHECK_LAUNCH();
         } else {
-            if (s == 0)
+            if (s == 0 && lists)
                 eb = launch_gemm<EpiSum<false, false, true>, true>(
                     g, EpiSum<false, false, true>{st, n, nullptr, nullptr, nullptr, 0, 0, nullptr, 0, entries, cursor, list_cap,
                                                   nullptr, nullptr}, stream);
@@ -1327,7 +1327,7 @@ static dvp_status run_lmhead_lists(const dvp_lmhead_params *p, const void *hidde
                                (const int *)nullptr);
             DVP_CHECK_LAUNCH();
         }
-        if (s == 0) {   // before the inference side adds its bit to row_flags: the list kernels only add theirs
+        if (s == 0 && lists) {   // before the inference side adds its bit to row_flags: the list kernels only add theirs
             LmListArgs a;
             a.entries = entries; a.grad_len = grad_len; a.row_flags = row_flags; a.safe_count = count0;
             a.ids = ids; a.coef = st0.coef; a.scale = st0.scale;

@@ -416,7 +416,8 @@ class LmHeadListsResult(LmHeadResult):
 def dvp_fused_lmhead_lists(hidden, w_train, w_infer, ids, grad_out, log_rho_value, list_cap, *, lse_full=False,
                            workspace: Optional[torch.Tensor] = None, d_hidden=None, d_w=None, entries=None,
                            grad_len=None, stream=None) -> LmHeadListsResult:
-    """LM-head variant with the gradient kept as per-row lists (short safe sets)."""
+    """LM-head variant with the gradient kept as per-row lists (short safe sets).  grad_out None: the
+    forward of both sides only."""
     for name, t in (("hidden", hidden), ("w_train", w_train)):
         if not t.is_cuda or t.dtype != torch.bfloat16 or t.dim() != 2 or t.stride(1) != 1:
             raise ValueError("%s must be a bf16 [rows, d] GPU tensor with unit inner stride" % name)
@@ -430,14 +431,15 @@ def dvp_fused_lmhead_lists(hidden, w_train, w_infer, ids, grad_out, log_rho_valu
     out_train = SideOutputs(n, v, dev, lse_full, False)
     out_infer = SideOutputs(n, v, dev, lse_full, False) if w_infer is not None else None
     row_flags = torch.empty(n, dtype=torch.uint8, device=dev)
-    if d_hidden is None:
-        d_hidden = torch.empty(n, hidden.stride(0), dtype=torch.float32, device=dev)[:, :d]
-    if d_w is None:
-        d_w = torch.empty(v, w_train.stride(0), dtype=torch.float32, device=dev)[:, :d]
-    if entries is None:
-        entries = torch.empty(n, max(int(list_cap), 1), 2, dtype=torch.int32, device=dev)
-    if grad_len is None:
-        grad_len = torch.empty(n, dtype=torch.int32, device=dev)
+    if grad_out is not None:
+        if d_hidden is None:
+            d_hidden = torch.empty(n, hidden.stride(0), dtype=torch.float32, device=dev)[:, :d]
+        if d_w is None:
+            d_w = torch.empty(v, w_train.stride(0), dtype=torch.float32, device=dev)[:, :d]
+        if entries is None:
+            entries = torch.empty(n, max(int(list_cap), 1), 2, dtype=torch.int32, device=dev)
+        if grad_len is None:
+            grad_len = torch.empty(n, dtype=torch.int32, device=dev)
     st = lib().dvp_fused_lmhead_lists(ctypes.byref(p), _ptr(hidden), _ptr(w_train), _ptr(w_infer), _ptr(ids),
                                       _ptr(grad_out), ctypes.byref(out_train.struct()),
                                       ctypes.byref(out_infer.struct()) if out_infer is not None else None,

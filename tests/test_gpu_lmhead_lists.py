@@ -160,6 +160,28 @@ def test_agrees_with_the_dense_call_and_repeats_bit_for_bit(dvp):
     assert (a.d_w - ref.d_w).abs().max().item() <= 2.0 ** -6 * scale_w
 
 
+def test_forward_only(dvp):
+    """Without grad_out the call is the forward of both sides: one pass per side over peaked rows, a
+    gathered second pass for the flat ones."""
+    wl = workloads.make_lmhead(device="cuda", n=520, d=128, v=3000, hidden_scale=60.0)
+    wl.hidden[::41] = (wl.hidden[::41].float() * 1e-3).to(torch.bfloat16)
+    lr = dvp.log_rho(1e-4)
+    res = dvp.dvp_fused_lmhead_lists(wl.hidden, wl.w_train, wl.w_infer, wl.ids, None, lr, 64)
+    torch.cuda.synchronize()
+    assert res.d_hidden is None and res.entries is None
+    assert res.second_pass.tolist() == [len(range(0, 520, 41))] * 2
+    ids = wl.ids.cpu().numpy()
+    H = wl.hidden.cpu()
+    ot = orc.lmhead(H, wl.w_train.cpu(), ids, np.float32(lr), band=BAND, threads=8)
+    oi = orc.lmhead(H, wl.w_infer.cpu(), ids, np.float32(lr), band=BAND, threads=8)
+    same_t = _check_side("train", res.train, ot, ot)
+    same_i = _check_side("infer", res.infer, oi, oi)
+    flags = res.row_flags.cpu().numpy()
+    np.testing.assert_array_equal((flags & 1)[same_t], ot["y_in_safe"][same_t])
+    np.testing.assert_array_equal(((flags >> 1) & 1)[same_i], oi["y_in_safe"][same_i])
+    assert not (flags & 0xFC).any()
+
+
 def test_validation(dvp):
     wl = workloads.make_lmhead(device="cuda", n=16, d=64, v=100)
     lr = dvp.log_rho(1e-2)

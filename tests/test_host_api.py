@@ -242,7 +242,8 @@ def test_lmhead_argument_validation_needs_no_gpu():
     assert L.dvp_fused_lmhead_lists_workspace_bytes(ctypes.byref(P(n=1 << 22)), 1024) == 0     # N * cap >= 2^31
     assert lists(P(n=0)) == 0
     assert lists(P(), cap=0) == 3 and lists(P(), cap=1025) == 5 and lists(P(n=1 << 22), cap=1024) == 5
-    assert lists(P(), grad=None) == 1 and lists(P(), flags=None) == 1 and lists(P(), entries=None) == 1
+    assert lists(P(), flags=None) == 1 and lists(P(), entries=None) == 1
+    assert lists(P(), grad=None, flags=None, entries=None, glen=None, dh=None, dw=None, bytes_=1000) == 6   # forward only: accepted up to the workspace check
     assert lists(P(), glen=None) == 1 and lists(P(), dh=None) == 1 and lists(P(), dw=None) == 1
     assert lists(P(), entries=FAKE + 4) == 4 and lists(P(), dw=FAKE + 8) == 4
     assert lists(P(), side=dvp.DvpSideOut(FAKE, FAKE, FAKE, None, FAKE, FAKE)) == 5             # no bitmask in this form

@@ -107,9 +107,8 @@ def bench_lmhead(args):
     wl = workloads.make_lmhead(device="cuda:0", n=args.rows, f8_engine=f8, hidden_scale=args.hidden_scale,
                                flat_every=args.flat_every)
     lists_cap = args.sparse_grad            # --sparse-grad on this workload: the gradient kept as per-row lists
-    if lists_cap and (f8 or args.split_lists):
-        print("bench.py: --sparse-grad on the lmhead workload goes with neither --infer-dtype f8 nor --split-lists",
-              file=sys.stderr)
+    if lists_cap and args.split_lists:
+        print("bench.py: --sparse-grad on the lmhead workload does not go with --split-lists", file=sys.stderr)
         sys.exit(2)
     n, d = wl.hidden.shape
     v = wl.w_train.shape[0]
@@ -137,8 +136,10 @@ def bench_lmhead(args):
 
     def step():
         if lists_cap:
-            last["res"] = dvp.dvp_fused_lmhead_lists(wl.hidden, wl.w_train, wl.w_infer, wl.ids, wl.grad_out, lr, lists_cap,
-                                                     workspace=ws, d_hidden=dh, d_w=dw, entries=entries, grad_len=grad_len)
+            last["res"] = dvp.dvp_fused_lmhead_lists(wl.hidden, wl.w_train, None if f8 else wl.w_infer, wl.ids, wl.grad_out, lr,
+                                                     lists_cap, workspace=ws, d_hidden=dh, d_w=dw, entries=entries,
+                                                     grad_len=grad_len,
+                                                     infer_f8=(wl.hidden8, wl.w8, wl.scale_infer) if f8 else None)
         elif two_calls:
             _, kept = dvp.dvp_fused_lmhead_forward(wl.hidden, wl.w_train, None if f8 else wl.w_infer, wl.ids, lr,
                                                    infer_f8=(wl.hidden8, wl.w8, wl.scale_infer) if f8 else None,
@@ -167,12 +168,13 @@ def bench_lmhead(args):
         second = [int(x) for x in res.second_pass.cpu().tolist()]      # rows of each side that went through a second pass
         passes = 2 + sum(second) / n
         useful, executed = 2 * gemm + 4.0 * listed * d, passes * gemm + 4.0 * listed * d
+        n_f8_passes = (1 + second[1] / n) if f8 else 0.0
         extra = {"list_cap": lists_cap, "list_entries": listed, "rows_over_cap": over, "gemm_passes": passes, "second_pass_rows": second,
                  "mean_safe_set": float(res.train.safe_count.float().mean().item())}
     # (each side's forward produces the logits twice: row max first, then sums at the threshold)
     # Peak for the mix of passes: each contraction is priced at the peak of its own operand type, so the
     # call's floor is sum(flop_i / peak_i) and the peak quoted is executed flop over that floor.
-    n_f8 = 2 if f8 else 0
+    n_f8 = (n_f8_passes if lists_cap else 2) if f8 else 0
     floor_s = ((executed / gemm - n_f8) * gemm / MFMA_BF16_PEAK_TFLOPS + n_f8 * gemm / MFMA_FP8_PEAK_TFLOPS) / 1e12
     peak = executed / floor_s / 1e12
     result = {
@@ -187,7 +189,7 @@ def bench_lmhead(args):
                                + (", hidden states scaled by %g (peaked rows)" % args.hidden_scale
                                   if args.hidden_scale != 1.0 else "")
                                + (", every %d-th row left at scale 1 (flat)" % args.flat_every if args.flat_every else ""),
-                   "entry_point": "dvp_fused_lmhead_lists" if lists_cap else
+                   "entry_point": ("dvp_fused_lmhead_lists_f8infer" if f8 else "dvp_fused_lmhead_lists") if lists_cap else
                                   "dvp_fused_lmhead_forward + dvp_fused_lmhead_backward" if two_calls else
                                   "dvp_fused_lmhead_f8infer" if f8 else "dvp_fused_lmhead",
                    "workspace_bytes": ws.numel(), "saved_bytes": saved.numel() if two_calls else 0, **extra},

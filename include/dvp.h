@@ -323,6 +323,12 @@ dvp_status dvp_fused_lmhead_lists(const dvp_lmhead_params *params, const void *h
                                   size_t workspace_bytes, void *stream);
 
 /*
+ * dvp_fused_lmhead_lists with an 8-bit inference engine (see dvp_fused_lmhead_f8infer for `infer`): the
+ * inference side's passes run on the fp8 matrix instruction, one pass where rows are peaked.  Declared
+ * after dvp_lmhead_f8_side below.
+ */
+
+/*
  * The LM-head variant in two calls, for callers that learn grad_out only after the forward (with
  * importance weights dL/dlogp depends on the log-probs).  Prop. 5.4's gradient is linear in grad_out, so
  * the forward leaves the masked exponentials of the training side (bf16, both orientations, every row
@@ -381,6 +387,14 @@ dvp_status dvp_fused_lmhead_f8infer(const dvp_lmhead_params *params, const void 
                                     const dvp_side_out *out_train, const dvp_side_out *out_infer,
                                     uint8_t *row_flags, float *d_hidden, float *d_w, void *workspace,
                                     size_t workspace_bytes, void *stream);
+
+dvp_status dvp_fused_lmhead_lists_f8infer(const dvp_lmhead_params *params, const void *hidden,
+                                          const void *w_train, const dvp_lmhead_f8_side *infer,
+                                          const int64_t *ids, const float *grad_out,
+                                          const dvp_side_out *out_train, const dvp_side_out *out_infer,
+                                          uint8_t *row_flags, dvp_grad_entry *entries, int32_t *grad_len,
+                                          int32_t list_cap, float *d_hidden, float *d_w, void *workspace,
+                                          size_t workspace_bytes, void *stream);
 
 /*
  * Sequence-level importance weights and token veto, from the per-token

@@ -156,8 +156,10 @@ hipError_t launch_backward(int dtype, const BackwardArgs &a, bool vector_ok, hip
 hipError_t launch_lists_to_dense(int dtype, const ListsArgs &a, bool vector_ok, hipStream_t stream);
 hipError_t launch_sequences(const SequenceArgs &a, hipStream_t stream);
 hipError_t launch_lmhead_lists_backward(const LmListArgs &a, hipStream_t stream);
+// H, W, their strides and d in 2-byte units; scale8 > 0: the rows are E4M3 bytes (two per unit) and the
+// dot product is multiplied by scale8; 0: bf16
 hipError_t launch_lmhead_zy_low(const uint16_t *H, int64_t ld_h, const uint16_t *W, int64_t ld_w, const int64_t *ids,
-                                float *zy_low, int n, int d, int v, hipStream_t stream);
+                                float *zy_low, int n, int d, int v, float scale8, hipStream_t stream);
 hipError_t launch_lmhead_candidates_finish(const LmCandArgs &a, hipStream_t stream);
 
 // The rows flagged in `overflow`, in row order: their indices (rowmap), their number (*n_sub, and a copy

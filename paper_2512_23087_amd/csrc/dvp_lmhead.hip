@@ -1201,7 +1201,8 @@ __global__ void zero_cursor_kernel(int *p, int n)
 // pass runs as in the dense call, appending to the lists on the training side.  Which of the two
 // happens depends on the inputs only.  Then the list kernels form dH and dW.
 static dvp_status run_lmhead_lists(const dvp_lmhead_params *p, const void *hidden, const void *w_train,
-                                   const void *w_infer, const int64_t *ids, const float *grad_out,
+                                   const void *w_infer, const dvp_lmhead_f8_side *f8, const int64_t *ids,
+                                   const float *grad_out,
                                    const dvp_side_out *out_train, const dvp_side_out *out_infer, uint8_t *row_flags,
                                    dvp_grad_entry *entries, int32_t *grad_len, int32_t list_cap, float *d_hidden,
                                    float *d_w, void *workspace, size_t workspace_bytes, void *stream_)
@@ -1216,8 +1217,18 @@ static dvp_status run_lmhead_lists(const dvp_lmhead_params *p, const void *hidde
     if (!hidden || !w_train || !ids || !out_train) return DVP_ERR_NULL;
     const bool lists = grad_out != nullptr;        // without grad_out: the forward of both sides only
     if (lists && (!row_flags || !entries || !grad_len || !d_hidden || !d_w)) return DVP_ERR_NULL;
-    if (out_train->entropy || (w_infer && out_infer && out_infer->entropy)) return DVP_ERR_UNSUPPORTED;
-    if (out_train->safe_bits || (w_infer && out_infer && out_infer->safe_bits)) return DVP_ERR_UNSUPPORTED;
+    const bool infer_side = w_infer != nullptr || f8 != nullptr;
+    if (out_train->entropy || (infer_side && out_infer && out_infer->entropy)) return DVP_ERR_UNSUPPORTED;
+    if (out_train->safe_bits || (infer_side && out_infer && out_infer->safe_bits)) return DVP_ERR_UNSUPPORTED;
+    if (f8) {   // as in run_lmhead
+        if (!f8->hidden || !f8->w) return DVP_ERR_NULL;
+        if (f8->ld_hidden < p->hidden || f8->ld_w < p->hidden) return DVP_ERR_SHAPE;
+        if (!(f8->scale == f8->scale) || f8->scale <= 0.0f || isinf(f8->scale)) return DVP_ERR_PARAM;
+        if (p->hidden % (2 * BK) || f8->ld_hidden % 16 || f8->ld_w % 16 || f8->ld_hidden > (1 << 23) ||
+            f8->ld_w > (1 << 23))
+            return DVP_ERR_UNSUPPORTED;
+        if (((uintptr_t)f8->hidden | (uintptr_t)f8->w) % 16) return DVP_ERR_ALIGN;
+    }
     if (((uintptr_t)hidden | (uintptr_t)w_train | (uintptr_t)w_infer) % 16) return DVP_ERR_ALIGN;
     if (lists && (((uintptr_t)d_hidden | (uintptr_t)d_w) % 16 || ((uintptr_t)entries % 8) || ((uintptr_t)grad_len % 4)))
         return DVP_ERR_ALIGN;
@@ -1240,7 +1251,7 @@ static dvp_status run_lmhead_lists(const dvp_lmhead_params *p, const void *hidde
     DVP_CHECK_LAUNCH();
     RowStats st0;
     int32_t *count0 = nullptr;
-    for (int s = 0; s < (w_infer ? 2 : 1); ++s) {
+    for (int s = 0; s < (infer_side ? 2 : 1); ++s) {
         RowStats st;
         st.max_key = (int *)(ws + L.off_i32[s]); st.zy = (float *)(ws + L.off_zy[s]);
         st.m = (float *)(ws + L.off_m[s]); st.tau = (float *)(ws + L.off_tau[s]);
@@ -1259,20 +1270,28 @@ static dvp_status run_lmhead_lists(const dvp_lmhead_params *p, const void *hidde
         g.A = (const uint16_t *)hidden; g.lda = p->ld_hidden;
         g.B = (const uint16_t *)(s == 0 ? w_train : w_infer); g.ldb = p->ld_w;
         g.M = n; g.N = v; g.K = d; g.scale = 1.0f;
+        const bool bytes = s == 1 && f8 != nullptr;
+        if (bytes) {   // two bytes count as one element
+            g.A = (const uint16_t *)f8->hidden; g.lda = f8->ld_hidden / 2;
+            g.B = (const uint16_t *)f8->w; g.ldb = f8->ld_w / 2;
+            g.K = d / 2; g.scale = f8->scale;
+        }
         hipLaunchKernelGGL(init_stats_kernel, dim3(nb), dim3(tb), 0, stream, st, n);
         DVP_CHECK_LAUNCH();
         const bool one_pass = o.lse_full == nullptr;   // the full sum needs every token's exponential
         if (one_pass) {
-            if (launch_lmhead_zy_low((const uint16_t *)hidden, p->ld_hidden, g.B, p->ld_w, ids, zy_low, n, d, v, stream) !=
-                hipSuccess)
+            if (launch_lmhead_zy_low(g.A, g.lda, g.B, g.ldb, ids, zy_low, n, g.K, v, bytes ? g.scale : 0.0f, stream) != hipSuccess)
                 return DVP_ERR_HIP;
             hipLaunchKernelGGL(zero_cursor_kernel, dim3(nb), dim3(tb), 0, stream, cand_cur, n);
             DVP_CHECK_LAUNCH();
-            if (launch_gemm<EpiMaxCand, false>(g, EpiMaxCand{st, ids, zy_low, cand, cand_cur, kLmCandMax, p->log_rho},
-                                               stream) != hipSuccess)
+            const EpiMaxCand ec{st, ids, zy_low, cand, cand_cur, kLmCandMax, p->log_rho};
+            if ((bytes ? launch_gemm<EpiMaxCand, false, true>(g, ec, stream) : launch_gemm<EpiMaxCand, false>(g, ec, stream)) !=
+                hipSuccess)
                 return DVP_ERR_HIP;
         } else {
-            if (launch_gemm<EpiMax, false>(g, EpiMax{st, ids}, stream) != hipSuccess) return DVP_ERR_HIP;
+            if ((bytes ? launch_gemm<EpiMax, false, true>(g, EpiMax{st, ids}, stream)
+                       : launch_gemm<EpiMax, false>(g, EpiMax{st, ids}, stream)) != hipSuccess)
+                return DVP_ERR_HIP;
         }
         hipLaunchKernelGGL(after_max_kernel, dim3(nb), dim3(tb), 0, stream, st, n, p->log_rho);
         DVP_CHECK_LAUNCH();
@@ -1293,22 +1312,24 @@ static dvp_status run_lmhead_lists(const dvp_lmhead_params *p, const void *hidde
             int *rowmap = (int *)(ws + LL.off_rowmap), *n_sub = (int *)(ws + LL.off_nsub);
             LmSubsetArgs sa;
             sa.overflow = (const int32_t *)(ws + LL.off_ovf); sa.rowmap = rowmap; sa.n_sub = n_sub; sa.n_report = need + s;
-            sa.H = (const uint16_t *)hidden; sa.ld_h = p->ld_hidden; sa.Hc = (uint16_t *)(ws + LL.off_hc);
+            sa.H = g.A; sa.ld_h = g.lda; sa.Hc = (uint16_t *)(ws + LL.off_hc);
             sa.m = st.m; sa.tau = st.tau; sa.m_sub = (float *)(ws + LL.off_msub); sa.tau_sub = (float *)(ws + LL.off_tausub);
-            sa.n = n; sa.d = d;
+            sa.n = n; sa.d = g.K;
             if (launch_lmhead_subset(sa, stream) != hipSuccess) return DVP_ERR_HIP;
             GemmArgs gs = g;
-            gs.A = sa.Hc; gs.lda = d;
+            gs.A = sa.Hc; gs.lda = g.K;
             RowStats sub = st;                    // m, tau and the partials by position in the subset
             sub.m = sa.m_sub; sub.tau = sa.tau_sub;
             if (s == 0 && lists)
                 eb = launch_gemm<EpiSum<false, false, true, true>, true>(
                     gs, EpiSum<false, false, true, true>{sub, n, nullptr, nullptr, nullptr, 0, 0, nullptr, 0, entries, cursor, list_cap,
                                                          rowmap, n_sub}, stream);
-            else
-                eb = launch_gemm<EpiSum<false, false, false, true>, true>(
-                    gs, EpiSum<false, false, false, true>{sub, n, nullptr, nullptr, nullptr, 0, 0, nullptr, 0, nullptr, nullptr, 0,
-                                                          rowmap, n_sub}, stream);
+            else {
+                const EpiSum<false, false, false, true> es{sub, n, nullptr, nullptr, nullptr, 0, 0, nullptr, 0, nullptr, nullptr, 0,
+                                                           rowmap, n_sub};
+                eb = bytes ? launch_gemm<EpiSum<false, false, false, true>, true, true>(gs, es, stream)
+                           : launch_gemm<EpiSum<false, false, false, true>, true>(gs, es, stream);
+            }
             if (eb != hipSuccess) return DVP_ERR_HIP;
             hipLaunchKernelGGL(after_sum_kernel, dim3((n + kAfterRows - 1) / kAfterRows), dim3(kAfterRows * kAfterSegs), 0,
                                stream, sub, o, ids, grad_out, row_flags, n, v, L.col_tiles, s, 0, (const int *)rowmap,
@@ -1319,6 +1340,8 @@ static dvp_status run_lmhead_lists(const dvp_lmhead_params *p, const void *hidde
                 eb = launch_gemm<EpiSum<false, false, true>, true>(
                     g, EpiSum<false, false, true>{st, n, nullptr, nullptr, nullptr, 0, 0, nullptr, 0, entries, cursor, list_cap,
                                                   nullptr, nullptr}, stream);
+            else if (bytes)
+                eb = launch_gemm<EpiSum<false>, true, true>(g, EpiSum<false>{st, n, nullptr, nullptr, nullptr, 0, 0, nullptr, 0}, stream);
             else
                 eb = launch_gemm<EpiSum<false>, true>(g, EpiSum<false>{st, n, nullptr, nullptr, nullptr, 0, 0, nullptr, 0}, stream);
             if (eb != hipSuccess) return DVP_ERR_HIP;
@@ -1368,7 +1391,19 @@ dvp_status dvp_fused_lmhead_lists(const dvp_lmhead_params *p, const void *hidden
                                   int32_t list_cap, float *d_hidden, float *d_w, void *workspace,
                                   size_t workspace_bytes, void *stream)
 {
-    return dvp::run_lmhead_lists(p, hidden, w_train, w_infer, ids, grad_out, out_train, out_infer, row_flags,
+    return dvp::run_lmhead_lists(p, hidden, w_train, w_infer, nullptr, ids, grad_out, out_train, out_infer, row_flags,
+                                 entries, grad_len, list_cap, d_hidden, d_w, workspace, workspace_bytes, stream);
+}
+
+dvp_status dvp_fused_lmhead_lists_f8infer(const dvp_lmhead_params *p, const void *hidden, const void *w_train,
+                                          const dvp_lmhead_f8_side *infer, const int64_t *ids, const float *grad_out,
+                                          const dvp_side_out *out_train, const dvp_side_out *out_infer,
+                                          uint8_t *row_flags, dvp_grad_entry *entries, int32_t *grad_len,
+                                          int32_t list_cap, float *d_hidden, float *d_w, void *workspace,
+                                          size_t workspace_bytes, void *stream)
+{
+    if (!infer) return DVP_ERR_NULL;
+    return dvp::run_lmhead_lists(p, hidden, w_train, nullptr, infer, ids, grad_out, out_train, out_infer, row_flags,
                                  entries, grad_len, list_cap, d_hidden, d_w, workspace, workspace_bytes, stream);
 }
 

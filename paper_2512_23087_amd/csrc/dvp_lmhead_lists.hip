@@ -220,8 +220,9 @@ __global__ __launch_bounds__(kThreads) void lm_dw_gather_kernel(const LmListArgs
 // zy_low[i]: a value safely below the logit of row i's sampled token as the matrix cores will form it
 // (the same dot product summed in another order: they differ by accumulation rounding, far less than the
 // margin taken off here), hence below the row maximum.  One wavefront per row.
+template <bool BYTES>
 __global__ __launch_bounds__(kWave) void lm_zy_low_kernel(const uint16_t *H, int64_t ld_h, const uint16_t *W, int64_t ld_w,
-                                                          const int64_t *ids, float *zy_low, int d, int v)
+                                                          const int64_t *ids, float *zy_low, int d, int v, float scale8)
 {
     const int i = blockIdx.x, lane = threadIdx.x;
     const int64_t y = ids[i];
@@ -236,12 +237,20 @@ __global__ __launch_bounds__(kWave) void lm_zy_low_kernel(const uint16_t *H, int
         const uint32_t x[4] = {a.x, a.y, a.z, a.w}, u[4] = {b.x, b.y, b.z, b.w};
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            acc += __uint_as_float(x[k] << 16) * __uint_as_float(u[k] << 16);
-            acc += __uint_as_float(x[k] & 0xffff0000u) * __uint_as_float(u[k] & 0xffff0000u);
+            if constexpr (BYTES) {      // four E4M3 codes per word, widened exactly by the hardware converter
+                typedef float f32x2 __attribute__((ext_vector_type(2)));
+                const f32x2 xl = __builtin_amdgcn_cvt_pk_f32_fp8((int)x[k], false), xh = __builtin_amdgcn_cvt_pk_f32_fp8((int)x[k], true);
+                const f32x2 ul = __builtin_amdgcn_cvt_pk_f32_fp8((int)u[k], false), uh = __builtin_amdgcn_cvt_pk_f32_fp8((int)u[k], true);
+                acc += xl.x * ul.x; acc += xl.y * ul.y; acc += xh.x * uh.x; acc += xh.y * uh.y;
+            } else {
+                acc += __uint_as_float(x[k] << 16) * __uint_as_float(u[k] << 16);
+                acc += __uint_as_float(x[k] & 0xffff0000u) * __uint_as_float(u[k] & 0xffff0000u);
+            }
         }
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, kWave);
+    if constexpr (BYTES) acc *= scale8;
     if (lane == 0) zy_low[i] = acc - 1e-3f * (1.0f + fabsf(acc));
 }
 
@@ -377,9 +386,12 @@ hipError_t launch_lmhead_subset(const LmSubsetArgs &a, hipStream_t stream)
 }
 
 hipError_t launch_lmhead_zy_low(const uint16_t *H, int64_t ld_h, const uint16_t *W, int64_t ld_w, const int64_t *ids,
-                                float *zy_low, int n, int d, int v, hipStream_t stream)
+                                float *zy_low, int n, int d, int v, float scale8, hipStream_t stream)
 {
-    hipLaunchKernelGGL(lm_zy_low_kernel, dim3((unsigned)n), dim3(kWave), 0, stream, H, ld_h, W, ld_w, ids, zy_low, d, v);
+    if (scale8 > 0.0f)
+        hipLaunchKernelGGL(lm_zy_low_kernel<true>, dim3((unsigned)n), dim3(kWave), 0, stream, H, ld_h, W, ld_w, ids, zy_low, d, v, scale8);
+    else
+        hipLaunchKernelGGL(lm_zy_low_kernel<false>, dim3((unsigned)n), dim3(kWave), 0, stream, H, ld_h, W, ld_w, ids, zy_low, d, v, 0.0f);
     return hipGetLastError();
 }
 

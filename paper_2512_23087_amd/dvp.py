@@ -25,7 +25,8 @@ EXPORTS = ("dvp_forward", "dvp_backward", "dvp_forward_backward", "dvp_fused_lmh
            "dvp_sequence_weights", "dvp_log_threshold", "dvp_forward_backward_sparse",
            "dvp_fused_lmhead_f8infer", "dvp_lists_to_dense", "dvp_fused_lmhead_saved_bytes",
            "dvp_fused_lmhead_forward", "dvp_fused_lmhead_backward", "dvp_fused_lmhead_lists",
-           "dvp_fused_lmhead_lists_workspace_bytes", "dvp_fused_lmhead_lists_second_pass_rows")
+           "dvp_fused_lmhead_lists_workspace_bytes", "dvp_fused_lmhead_lists_second_pass_rows",
+           "dvp_fused_lmhead_lists_f8infer")
 
 
 class DvpParams(ctypes.Structure):
@@ -103,6 +104,9 @@ def lib():
         L.dvp_fused_lmhead_lists.restype = ctypes.c_int
         L.dvp_fused_lmhead_lists.argtypes = [lp, vp, vp, vp, i64p, vp, sp, sp, vp, vp, vp, ctypes.c_int32, vp, vp, vp,
                                              ctypes.c_size_t, vp]
+        L.dvp_fused_lmhead_lists_f8infer.restype = ctypes.c_int
+        L.dvp_fused_lmhead_lists_f8infer.argtypes = [lp, vp, vp, ctypes.POINTER(DvpLmHeadF8Side), i64p, vp, sp, sp, vp, vp, vp,
+                                                     ctypes.c_int32, vp, vp, vp, ctypes.c_size_t, vp]
         L.dvp_log_rho.restype = ctypes.c_float
         L.dvp_log_rho.argtypes = [ctypes.c_double]
         L.dvp_status_string.restype = ctypes.c_char_p
@@ -415,7 +419,7 @@ class LmHeadListsResult(LmHeadResult):
 
 def dvp_fused_lmhead_lists(hidden, w_train, w_infer, ids, grad_out, log_rho_value, list_cap, *, lse_full=False,
                            workspace: Optional[torch.Tensor] = None, d_hidden=None, d_w=None, entries=None,
-                           grad_len=None, stream=None) -> LmHeadListsResult:
+                           grad_len=None, stream=None, infer_f8=None) -> LmHeadListsResult:
     """LM-head variant with the gradient kept as per-row lists (short safe sets).  grad_out None: the
     forward of both sides only."""
     for name, t in (("hidden", hidden), ("w_train", w_train)):
@@ -429,7 +433,9 @@ def dvp_fused_lmhead_lists(hidden, w_train, w_infer, ids, grad_out, log_rho_valu
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
     out_train = SideOutputs(n, v, dev, lse_full, False)
-    out_infer = SideOutputs(n, v, dev, lse_full, False) if w_infer is not None else None
+    if infer_f8 is not None and w_infer is not None:
+        raise ValueError("give either w_infer or infer_f8")
+    out_infer = SideOutputs(n, v, dev, lse_full, False) if (w_infer is not None or infer_f8 is not None) else None
     row_flags = torch.empty(n, dtype=torch.uint8, device=dev)
     if grad_out is not None:
         if d_hidden is None:
@@ -440,11 +446,23 @@ def dvp_fused_lmhead_lists(hidden, w_train, w_infer, ids, grad_out, log_rho_valu
             entries = torch.empty(n, max(int(list_cap), 1), 2, dtype=torch.int32, device=dev)
         if grad_len is None:
             grad_len = torch.empty(n, dtype=torch.int32, device=dev)
-    st = lib().dvp_fused_lmhead_lists(ctypes.byref(p), _ptr(hidden), _ptr(w_train), _ptr(w_infer), _ptr(ids),
-                                      _ptr(grad_out), ctypes.byref(out_train.struct()),
-                                      ctypes.byref(out_infer.struct()) if out_infer is not None else None,
-                                      _ptr(row_flags), _ptr(entries), _ptr(grad_len), int(list_cap),
-                                      _ptr(d_hidden), _ptr(d_w), _ptr(workspace), workspace.numel(), _stream(stream))
+    if infer_f8 is not None:
+        h8, w8, scale = infer_f8
+        for name, t in (("infer_f8 hidden", h8), ("infer_f8 w", w8)):
+            if not t.is_cuda or t.dtype != torch.float8_e4m3fn or t.dim() != 2 or t.stride(1) != 1:
+                raise ValueError("%s must be a float8_e4m3fn [rows, d] GPU tensor with unit inner stride" % name)
+        side = DvpLmHeadF8Side(h8.data_ptr(), w8.data_ptr(), h8.stride(0), w8.stride(0), float(scale))
+        st = lib().dvp_fused_lmhead_lists_f8infer(ctypes.byref(p), _ptr(hidden), _ptr(w_train), ctypes.byref(side),
+                                                  _ptr(ids), _ptr(grad_out), ctypes.byref(out_train.struct()),
+                                                  ctypes.byref(out_infer.struct()), _ptr(row_flags), _ptr(entries),
+                                                  _ptr(grad_len), int(list_cap), _ptr(d_hidden), _ptr(d_w),
+                                                  _ptr(workspace), workspace.numel(), _stream(stream))
+    else:
+        st = lib().dvp_fused_lmhead_lists(ctypes.byref(p), _ptr(hidden), _ptr(w_train), _ptr(w_infer), _ptr(ids),
+                                          _ptr(grad_out), ctypes.byref(out_train.struct()),
+                                          ctypes.byref(out_infer.struct()) if out_infer is not None else None,
+                                          _ptr(row_flags), _ptr(entries), _ptr(grad_len), int(list_cap),
+                                          _ptr(d_hidden), _ptr(d_w), _ptr(workspace), workspace.numel(), _stream(stream))
     if st != 0:
         raise DvpError(st, "dvp_fused_lmhead_lists")
     res = LmHeadListsResult(out_train, out_infer, row_flags, d_hidden, d_w, entries, grad_len)

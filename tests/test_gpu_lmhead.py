@@ -46,9 +46,9 @@ def dvp():
     return binding
 
 
-def _check_side(name, side, o, band_o):
+def _check_side(name, side, o, band_o, band=BAND):
     got_m = side.row_max.cpu().double().numpy()
-    assert np.abs(got_m - o["row_max"]).max() <= BAND, name + ": row_max"
+    assert np.abs(got_m - o["row_max"]).max() <= band, name + ": row_max"
     cnt = side.safe_count.cpu().numpy()
     slack = band_o["band_count"]
     assert np.all(np.abs(cnt - o["safe_count"]) <= slack), \

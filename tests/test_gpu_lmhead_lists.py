@@ -182,6 +182,36 @@ def test_forward_only(dvp):
     assert not (flags & 0xFC).any()
 
 
+def test_8bit_inference_engine(dvp):
+    """The inference side as an E4M3 engine (activations, head and a scale): checked against the oracle's
+    logits from the codes; the training side, the lists and the gradient do not depend on it.
+    Peaked rows need logits of +-40 here, which the engine forms from products of up to 448 x 448 summed in
+    fp32 before the scale: their accumulation rounding reaches 8e-4 (2e-5 relative), so the membership band
+    and the row-maximum bar are 2e-3, the absolute tolerance of low-precision inputs, instead of 2e-4."""
+    wl = workloads.make_lmhead(device="cuda", n=520, d=256, v=3000, hidden_scale=40.0, f8_engine=True)
+    wl.hidden[::53] = (wl.hidden[::53].float() * 1e-3).to(torch.bfloat16)          # flat training rows
+    wl.hidden8.view(torch.uint8)[::47] = 0                                         # flat inference rows (all logits 0)
+    lr = dvp.log_rho(1e-4)
+    res = dvp.dvp_fused_lmhead_lists(wl.hidden, wl.w_train, None, wl.ids, wl.grad_out, lr, 64,
+                                     infer_f8=(wl.hidden8, wl.w8, wl.scale_infer))
+    ref = dvp.dvp_fused_lmhead_lists(wl.hidden, wl.w_train, None, wl.ids, wl.grad_out, lr, 64)
+    torch.cuda.synchronize()
+    assert res.second_pass.tolist() == [len(range(0, 520, 53)), len(range(0, 520, 47))]
+    ids = wl.ids.cpu().numpy()
+    h8 = wl.hidden8.view(torch.uint8).cpu().numpy()
+    w8 = wl.w8.view(torch.uint8).cpu().numpy()
+    oi = orc.lmhead(h8, w8, ids, np.float32(lr), band=2e-3, threads=8, scale=wl.scale_infer)
+    same_i = _check_side("infer", res.infer, oi, oi, band=2e-3)
+    flags = res.row_flags.cpu().numpy()
+    np.testing.assert_array_equal(((flags >> 1) & 1)[same_i], oi["y_in_safe"][same_i])
+    assert (oi["safe_count"][::47] == 3000).all() and (oi["band_count"] == 0).mean() > 0.9
+    for k in ("logp", "row_max", "lse_safe", "safe_count"):
+        assert torch.equal(getattr(res.train, k), getattr(ref.train, k)), k
+    assert torch.equal(res.row_flags & 13, ref.row_flags & 13)
+    assert torch.equal(res.d_hidden, ref.d_hidden) and torch.equal(res.d_w, ref.d_w)
+    assert torch.equal(res.grad_len, ref.grad_len)
+
+
 def test_validation(dvp):
     wl = workloads.make_lmhead(device="cuda", n=16, d=64, v=100)
     lr = dvp.log_rho(1e-2)

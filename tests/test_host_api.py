@@ -249,3 +249,12 @@ def test_lmhead_argument_validation_needs_no_gpu():
     assert lists(P(), side=dvp.DvpSideOut(FAKE, FAKE, FAKE, None, FAKE, FAKE)) == 5             # no bitmask in this form
     assert lists(P(d=96)) == 5 and lists(P(lr=0.5)) == 3
     assert lists(P(), bytes_=1000) == 6
+
+    def lists8(p, side, cap=64):
+        return L.dvp_fused_lmhead_lists_f8infer(ctypes.byref(p), FAKE, FAKE, side, FAKE, FAKE, ctypes.byref(so), ctypes.byref(so),
+                                                FAKE, FAKE, FAKE, cap, FAKE, FAKE, ws, 1000, None)
+
+    assert lists8(P(), None) == 1 and lists8(P(), S(hidden=None)) == 1
+    assert lists8(P(), S(scale=0.0)) == 3 and lists8(P(), S(ld_h=136)) == 5 and lists8(P(), S(w=FAKE + 8)) == 4
+    assert lists8(P(), S()) == 6                    # everything accepted up to the workspace check
+    assert lists8(P(n=0), S()) == 0

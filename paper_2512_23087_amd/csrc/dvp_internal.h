@@ -101,49 +101,6 @@ struct SequenceArgs {
     float log_threshold;
 };
 
-// LM-head variant with the gradient kept as per-row lists (launch_lmhead_lists_backward): what pass B's
-// epilogue left behind, and where dH = dz W and dW = dz^T H go.
-constexpr int kLmListMax = 1024;  // longest list the LM-head variant sorts in LDS
-struct LmListArgs {
-    dvp_grad_entry *entries;      // [n, list_cap]; in: (token, exp(z - m)) in arrival order; out: (token, dz) by token
-    int32_t *grad_len;            // [n] out
-    uint8_t *row_flags;           // [n] in/out (DVP_ROW_GRAD_OVERFLOW is added)
-    const int32_t *safe_count;    // [n]
-    const int64_t *ids;           // [n]
-    const float *coef, *scale;    // [n] q = c (1 - p_y) and s = -c / S
-    const uint16_t *W;            // [v, ld_w] bf16
-    const uint16_t *H;            // [n, ld_h] bf16
-    int64_t ld_w, ld_h;
-    float *d_hidden;              // [n, ld_h]
-    float *d_w;                   // [v, ld_w]
-    int32_t n, d, v, list_cap;
-    // column-major copy of the lists: workspace
-    int32_t *blk_cnt;             // [n_blk, v]
-    int32_t *col_start;           // [v + 1]
-    int32_t *grp_total;           // [ceil(v / 256) + 1]
-    int32_t *csc_row;             // [n * list_cap]
-    float *csc_val;               // [n * list_cap]
-    int32_t n_blk, rows_per_blk;
-};
-
-// One side of the LM-head forward finished from the candidates pass A collected
-// (launch_lmhead_candidates_finish), and the bound pass A used (launch_lmhead_zy_low).
-constexpr int kLmCandMax = 2048;  // candidates kept per row
-struct LmCandArgs {
-    const dvp_grad_entry *cand;   // [n, kLmCandMax] (token, logit) in arrival order
-    const int32_t *cand_count;    // [n] candidates appended (may exceed kLmCandMax: then the side is redone)
-    const float *m, *tau, *zy;    // [n] row maximum, threshold, the sampled token's logit
-    const int64_t *ids;
-    const float *grad_out;        // [n] or null; side 0 only
-    SideOut out;                  // logp, row_max, lse_safe, safe_count (required); the rest unused
-    uint8_t *row_flags;
-    float *coef, *scale;          // [n], side 0 only
-    dvp_grad_entry *entries;      // side 0: [n, list_cap] (token, exp(z - m)) for rows that fit; else null
-    int32_t list_cap;
-    int32_t *overflow;            // [n] out: 1 where the row's candidates did not fit (nothing else is written for it)
-    int32_t n, v, side;
-};
-
 // true when the register-resident kernel can take rows of this many elements
 // (dtype: training rows and gradient; dtype_infer: inference rows)
 bool row_fits_resident(int dtype, int dtype_infer, int64_t vocab);
@@ -155,26 +112,5 @@ hipError_t launch_grad_fill(int dtype, const FillArgs &a, hipStream_t stream);
 hipError_t launch_backward(int dtype, const BackwardArgs &a, bool vector_ok, hipStream_t stream);
 hipError_t launch_lists_to_dense(int dtype, const ListsArgs &a, bool vector_ok, hipStream_t stream);
 hipError_t launch_sequences(const SequenceArgs &a, hipStream_t stream);
-hipError_t launch_lmhead_lists_backward(const LmListArgs &a, hipStream_t stream);
-// H, W, their strides and d in 2-byte units; scale8 > 0: the rows are E4M3 bytes (two per unit) and the
-// dot product is multiplied by scale8; 0: bf16
-hipError_t launch_lmhead_zy_low(const uint16_t *H, int64_t ld_h, const uint16_t *W, int64_t ld_w, const int64_t *ids,
-                                float *zy_low, int n, int d, int v, float scale8, hipStream_t stream);
-hipError_t launch_lmhead_candidates_finish(const LmCandArgs &a, hipStream_t stream);
-
-// The rows flagged in `overflow`, in row order: their indices (rowmap), their number (*n_sub, and a copy
-// in *n_report), their hidden states gathered into consecutive rows of Hc [n, d] and their
-// m and tau into m_sub, tau_sub.
-struct LmSubsetArgs {
-    const int32_t *overflow;
-    int32_t *rowmap, *n_sub, *n_report;
-    const uint16_t *H;
-    int64_t ld_h;
-    uint16_t *Hc;
-    const float *m, *tau;
-    float *m_sub, *tau_sub;
-    int32_t n, d;
-};
-hipError_t launch_lmhead_subset(const LmSubsetArgs &a, hipStream_t stream);
 
 }  // namespace dvp

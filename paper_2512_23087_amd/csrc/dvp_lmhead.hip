@@ -27,7 +27,7 @@
 #include <atomic>
 
 #include "dvp_device.h"
-#include "dvp_internal.h"
+#include "dvp_lmhead_internal.h"
 
 namespace dvp {
 

@@ -8,7 +8,7 @@
 // depend on the launch order) and dW = dz^T H is summed per token in row order:
 // every sum has a fixed order, results are run-to-run identical.  No matrix
 // product is involved: the work is |lists| x d multiply-adds.
-#include "dvp_internal.h"
+#include "dvp_lmhead_internal.h"
 
 namespace dvp {
 namespace {

@@ -212,6 +212,42 @@ def test_8bit_inference_engine(dvp):
     assert torch.equal(res.grad_len, ref.grad_len)
 
 
+def test_padded_strides_and_out_of_range_ids(dvp):
+    """Row strides larger than the hidden size (NaN in the padding) and sampled ids outside [0, V):
+    flagged per row, NaN log-probs, an empty list, nothing else disturbed."""
+    n, d, v, pad = 300, 128, 3000, 8
+    wl = workloads.make_lmhead(device="cuda", n=n, d=d, v=v, hidden_scale=60.0)
+    H = torch.full((n, d + pad), float("nan"), dtype=torch.bfloat16, device="cuda")
+    W = torch.full((v, d + pad), float("nan"), dtype=torch.bfloat16, device="cuda")
+    H[:, :d] = wl.hidden
+    W[:, :d] = wl.w_train
+    ids = wl.ids.clone()
+    ids[3] = -1
+    ids[77] = v
+    lr = dvp.log_rho(1e-4)
+    a = dvp.dvp_fused_lmhead_lists(H[:, :d], W[:, :d], None, ids, wl.grad_out, lr, 64)
+    torch.cuda.synchronize()
+    flags = a.row_flags.cpu().numpy()
+    assert flags[3] == 4 and flags[77] == 4 and (np.delete(flags, [3, 77]) & 4).sum() == 0
+    assert torch.isnan(a.train.logp[3]) and torch.isnan(a.train.logp[77])
+    assert a.grad_len[3] == 0 and a.grad_len[77] == 0
+    assert torch.all(a.d_hidden[3] == 0) and torch.all(a.d_hidden[77] == 0)
+    assert torch.isfinite(a.d_w).all() and torch.isfinite(a.d_hidden).all()
+    assert a.d_hidden.stride(0) == d + pad and a.d_w.stride(0) == d + pad
+    g2 = wl.grad_out.clone()
+    g2[3] = 0
+    g2[77] = 0
+    ids2 = ids.clone()
+    ids2[3] = 0
+    ids2[77] = 0
+    b = dvp.dvp_fused_lmhead_lists(wl.hidden, wl.w_train, None, ids2, g2, lr, 64)
+    torch.cuda.synchronize()
+    keep = torch.ones(n, dtype=torch.bool, device="cuda")
+    keep[3] = keep[77] = False
+    assert torch.equal(a.train.logp[keep], b.train.logp[keep]) and torch.equal(a.train.safe_count, b.train.safe_count)
+    assert torch.equal(a.d_hidden[keep], b.d_hidden[keep]) and torch.equal(a.d_w, b.d_w)
+
+
 def test_validation(dvp):
     wl = workloads.make_lmhead(device="cuda", n=16, d=64, v=100)
     lr = dvp.log_rho(1e-2)

@@ -98,6 +98,44 @@ def test_lmhead_replayed_from_a_graph(dvp):
     assert first.train.logp.shape == res.train.logp.shape
 
 
+def test_lmhead_list_form_replayed_from_a_graph(dvp):
+    """The list form decides on the device which rows need a second pass: one captured graph serves
+    inputs that need none and inputs with flat rows among the peaked ones."""
+    n, d, v, cap = 300, 128, 3000, 64
+    wl = workloads.make_lmhead(device="cuda", n=n, d=d, v=v, hidden_scale=60.0)
+    lr = dvp.log_rho(1e-4)
+    hidden = wl.hidden.clone()
+    flat = wl.hidden.clone()
+    flat[::29] = (flat[::29].float() * 1e-3).to(torch.bfloat16)
+    import ctypes
+    p = dvp.DvpLmHeadParams(n, d, v, d, d, lr)
+    nbytes = int(dvp.lib().dvp_fused_lmhead_lists_workspace_bytes(ctypes.byref(p), cap))
+    ws, ws2 = (torch.empty(nbytes, dtype=torch.uint8, device="cuda") for _ in range(2))
+    bufs = [dict(d_hidden=torch.empty(n, d, device="cuda"), d_w=torch.empty(v, d, device="cuda"),
+                 entries=torch.zeros(n, cap, 2, dtype=torch.int32, device="cuda"),
+                 grad_len=torch.empty(n, dtype=torch.int32, device="cuda")) for _ in range(2)]
+    dvp.dvp_fused_lmhead_lists(hidden, wl.w_train, wl.w_infer, wl.ids, wl.grad_out, lr, cap, workspace=ws2, **bufs[1])
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        res = dvp.dvp_fused_lmhead_lists(hidden, wl.w_train, wl.w_infer, wl.ids, wl.grad_out, lr, cap, workspace=ws, **bufs[0])
+    want_second = [0, len(range(0, n, 29)), 0]
+    for rep in range(3):
+        hidden.copy_(flat if rep == 1 else wl.hidden)
+        ref = dvp.dvp_fused_lmhead_lists(hidden, wl.w_train, wl.w_infer, wl.ids, wl.grad_out, lr, cap, workspace=ws2, **bufs[1])
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert res.second_pass.tolist() == [want_second[rep]] * 2 == ref.second_pass.tolist(), rep
+        assert torch.equal(bufs[0]["d_hidden"], bufs[1]["d_hidden"]) and torch.equal(bufs[0]["d_w"], bufs[1]["d_w"]), rep
+        assert torch.equal(res.grad_len, ref.grad_len) and torch.equal(res.row_flags, ref.row_flags)
+        valid = torch.arange(cap, device="cuda")[None, :] < torch.where((res.row_flags & 8) != 0, 0, res.grad_len)[:, None]
+        assert torch.equal(bufs[0]["entries"][valid], bufs[1]["entries"][valid])
+        for side in ("train", "infer"):
+            for k in ("logp", "row_max", "lse_safe", "safe_count"):
+                assert torch.equal(getattr(getattr(res, side), k), getattr(getattr(ref, side), k)), (rep, side, k)
+
+
 def test_concurrent_callers_on_their_own_streams(dvp):
     """The library keeps no state between calls: host threads with a stream each get the same results
     as one thread."""

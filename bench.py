@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MEASURED_TRAFFIC = {
     # sha256 of csrc/dvp_rows.hip + dvp_device.h + dvp_internal.h -> HBM bytes per launch; see
     # profiles/rows_cfg3_hbm_traffic.md for the counter values and scale factors
-    "50866bdb26c4aa08141acb74aeda5f9d5db70edd62d487b501058aafca9e4e52": {"cfg3": 29894924000},
+    "da5f035eb7ab63057ccd3c378112de220225eed736ba3fc25b28182308f7454c": {"cfg3": 29894924000},
 }
 
 

@@ -133,6 +133,16 @@ def bench_lmhead(args):
                             device="cuda:0")
 
     last = {}
+    over_rows = ws_rows = None
+    if lists_cap and args.dense_rows:
+        # the rows over the list cap, found once (the inputs do not change between steps; a training loop
+        # reads row_flags back each step or keeps an upper bound), and the workspace of their dense call
+        first = dvp.dvp_fused_lmhead_lists(wl.hidden, wl.w_train, None if f8 else wl.w_infer, wl.ids, wl.grad_out, lr,
+                                           lists_cap, workspace=ws, d_hidden=dh, d_w=dw, entries=entries, grad_len=grad_len,
+                                           infer_f8=(wl.hidden8, wl.w8, wl.scale_infer) if f8 else None)
+        over_rows = torch.nonzero((first.row_flags & dvp.ROW_GRAD_OVERFLOW) != 0).squeeze(1).to(torch.int32)
+        ws_rows = torch.empty(max(int(dvp.lib().dvp_fused_lmhead_rows_workspace_bytes(ctypes.byref(pl), over_rows.numel())), 256),
+                              dtype=torch.uint8, device="cuda:0")
 
     def step():
         if lists_cap:
@@ -140,6 +150,8 @@ def bench_lmhead(args):
                                                      lists_cap, workspace=ws, d_hidden=dh, d_w=dw, entries=entries,
                                                      grad_len=grad_len,
                                                      infer_f8=(wl.hidden8, wl.w8, wl.scale_infer) if f8 else None)
+            if over_rows is not None and over_rows.numel():
+                dvp.dvp_fused_lmhead_rows(wl.hidden, wl.w_train, wl.ids, wl.grad_out, lr, over_rows, dh, dw, workspace=ws_rows)
         elif two_calls:
             _, kept = dvp.dvp_fused_lmhead_forward(wl.hidden, wl.w_train, None if f8 else wl.w_infer, wl.ids, lr,
                                                    infer_f8=(wl.hidden8, wl.w8, wl.scale_infer) if f8 else None,
@@ -169,8 +181,17 @@ def bench_lmhead(args):
         passes = 2 + sum(second) / n
         useful, executed = 2 * gemm + 4.0 * listed * d, passes * gemm + 4.0 * listed * d
         n_f8_passes = (1 + second[1] / n) if f8 else 0.0
+        if over_rows is not None:       # the dense call on those rows: its two forward passes and the two gradient products
+            dense = 4.0 * over_rows.numel() / n
+            passes += dense
+            executed += dense * gemm
+            useful += 2.0 * over_rows.numel() / n * gemm
+            extra_dense = {"dense_rows": int(over_rows.numel())}
         extra = {"list_cap": lists_cap, "list_entries": listed, "rows_over_cap": over, "gemm_passes": passes, "second_pass_rows": second,
                  "mean_safe_set": float(res.train.safe_count.float().mean().item())}
+        if over_rows is not None:
+            extra.update(extra_dense)
+            extra["gemm_passes"] = passes
     # (each side's forward produces the logits twice: row max first, then sums at the threshold)
     # Peak for the mix of passes: each contraction is priced at the peak of its own operand type, so the
     # call's floor is sum(flop_i / peak_i) and the peak quoted is executed flop over that floor.
@@ -189,7 +210,8 @@ def bench_lmhead(args):
                                + (", hidden states scaled by %g (peaked rows)" % args.hidden_scale
                                   if args.hidden_scale != 1.0 else "")
                                + (", every %d-th row left at scale 1 (flat)" % args.flat_every if args.flat_every else ""),
-                   "entry_point": ("dvp_fused_lmhead_lists_f8infer" if f8 else "dvp_fused_lmhead_lists") if lists_cap else
+                   "entry_point": (("dvp_fused_lmhead_lists_f8infer" if f8 else "dvp_fused_lmhead_lists")
+                                   + (" + dvp_fused_lmhead_rows" if over_rows is not None else "")) if lists_cap else
                                   "dvp_fused_lmhead_forward + dvp_fused_lmhead_backward" if two_calls else
                                   "dvp_fused_lmhead_f8infer" if f8 else "dvp_fused_lmhead",
                    "workspace_bytes": ws.numel(), "saved_bytes": saved.numel() if two_calls else 0, **extra},
@@ -273,6 +295,9 @@ def main():
     ap.add_argument("--hidden-scale", type=float, default=1.0,
                     help="(lmhead workload) multiply the hidden states: 20 gives peaked rows with a few safe tokens "
                          "each; with --sparse-grad CAP one step = dvp_fused_lmhead_lists")
+    ap.add_argument("--dense-rows", action="store_true",
+                    help="(lmhead workload with --sparse-grad) one step = the list-form call followed by "
+                         "dvp_fused_lmhead_rows on the rows over the list cap: the gradient of every row")
     ap.add_argument("--flat-every", type=int, default=0, metavar="K",
                     help="(lmhead workload, with --hidden-scale) every K-th row keeps the scale 1: flat rows among peaked ones")
     ap.add_argument("--infer-dtype", default="same", choices=["same", "f8"],

@@ -294,7 +294,7 @@ dvp_status dvp_fused_lmhead(const dvp_lmhead_params *params, const void *hidden,
  *              a row's entries come out sorted by token; what lies beyond grad_len[i] in a row of
  *              entries is unspecified.  grad_len and row_flags are required.
  *   A row with |V_S| > list_cap gets DVP_ROW_GRAD_OVERFLOW and no entries; its row of d_hidden is
- *   zero and it adds nothing to d_w: the caller runs dvp_fused_lmhead on those rows and adds.
+ *   zero and it adds nothing to d_w: dvp_fused_lmhead_rows on those rows completes both.
  *   d_hidden  DEVICE float [N, ld_hidden], overwritten;  d_w  DEVICE float [V, ld_w], overwritten;
  *              both 16-byte aligned.
  *   out_train / out_infer: safe_bits and entropy must be NULL.
@@ -321,6 +321,29 @@ dvp_status dvp_fused_lmhead_lists(const dvp_lmhead_params *params, const void *h
                                   dvp_grad_entry *entries, int32_t *grad_len, int32_t list_cap,
                                   float *d_hidden, float *d_w, void *workspace,
                                   size_t workspace_bytes, void *stream);
+
+/*
+ * Dense gradient of some of the token rows, added to what is there: for the rows that a
+ * dvp_fused_lmhead_lists call flagged DVP_ROW_GRAD_OVERFLOW (safe set longer than the list).  The rows'
+ * hidden states, ids and upstream gradients are gathered, the training side of dvp_fused_lmhead runs on
+ * them (Prop. 5.4; masked exponentials through bf16 as there), and
+ *     d_hidden[rows[j], :]  is overwritten with row rows[j]'s dH,     d_w += sum_j dz[rows[j]]^T H[rows[j]].
+ * After dvp_fused_lmhead_lists followed by this call on the flagged rows, d_hidden and d_w hold the gradient
+ * of every row.
+ *   params    as for the call whose rows these are (n_rows = N: the bound for rows[])
+ *   rows      DEVICE int32 [n_sub], distinct row indices (a repeated index is counted twice in d_w); an
+ *             index outside [0, N) is skipped.  n_sub is a HOST value, 0 <= n_sub <= N: the caller
+ *             reads row_flags back (or keeps an upper bound and pads rows[] with -1).
+ *   grad_out, ids   DEVICE [N], indexed by row.
+ *   d_w       DEVICE float [V, ld_w]: must hold valid numbers on entry (e.g. the list-form call's result).
+ *   workspace DEVICE, 256-byte aligned, dvp_fused_lmhead_rows_workspace_bytes(params, n_sub) bytes.
+ */
+size_t dvp_fused_lmhead_rows_workspace_bytes(const dvp_lmhead_params *params, int64_t n_sub);
+
+dvp_status dvp_fused_lmhead_rows(const dvp_lmhead_params *params, const void *hidden, const void *w_train,
+                                 const int64_t *ids, const float *grad_out, const int32_t *rows,
+                                 int64_t n_sub, float *d_hidden, float *d_w, void *workspace,
+                                 size_t workspace_bytes, void *stream);
 
 /*
  * dvp_fused_lmhead_lists with an 8-bit inference engine (see dvp_fused_lmhead_f8infer for `infer`): the

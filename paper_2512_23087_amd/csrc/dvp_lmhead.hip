@@ -990,7 +990,7 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
                              const float *grad_out, const dvp_side_out *out_train, const dvp_side_out *out_infer,
                              uint8_t *row_flags, float *d_hidden, float *d_w, void *workspace,
                              size_t workspace_bytes, void *stream_, LmPhase phase = LM_FUSED, void *saved = nullptr,
-                             size_t saved_bytes = 0)
+                             size_t saved_bytes = 0, bool dw_accumulate = false)
 {
     if (!p) return DVP_ERR_NULL;
     if (p->log_rho != p->log_rho || p->log_rho > 0.0f) return DVP_ERR_PARAM;
@@ -1128,7 +1128,7 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
         GemmArgs gw;
         gw.A = Et; gw.lda = L.block_pad; gw.B = ht; gw.ldb = L.block_pad;
         gw.M = v; gw.N = d; gw.K = rows_pad; gw.scale = 1.0f;
-        const EpiStore ew{d_w, p->ld_w, r0 > 0, nullptr, nullptr, nullptr, nullptr, 0};
+        const EpiStore ew{d_w, p->ld_w, r0 > 0 || dw_accumulate, nullptr, nullptr, nullptr, nullptr, 0};
         if (launch_gemm<EpiStore, false>(gw, ew, stream) != hipSuccess) return DVP_ERR_HIP;
         for (int q0 = 0; q0 < rows; q0 += kOnehotRows) {   // in row order: launches on one stream run in order
             const int qrows = (rows - q0) < kOnehotRows ? (rows - q0) : kOnehotRows;
@@ -1368,9 +1368,79 @@ static dvp_status run_lmhead_lists(const dvp_lmhead_params *p, const void *hidde
     return DVP_OK;
 }
 
+// Dense gradient of a subset of the token rows (the rows a list-form call left out): their hidden
+// states, ids and upstream gradients are gathered into consecutive rows, the dense call runs on those
+// (training side only, dW accumulated), and the rows of dH go back to their places.
+struct LmRowsLayout {
+    size_t total, off_h, off_ids, off_g, off_dh, off_dense;
+};
+
+static LmRowsLayout lm_rows_layout(int64_t n_sub, int64_t d, int64_t v)
+{
+    LmRowsLayout R;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o += align256(bytes); return at; };
+    R.off_h = take((size_t)n_sub * d * 2);
+    R.off_ids = take((size_t)n_sub * 8);
+    R.off_g = take((size_t)n_sub * 4);
+    R.off_dh = take((size_t)n_sub * d * 4);
+    R.off_dense = o;
+    R.total = o + lm_layout(n_sub, d, v).total;
+    return R;
+}
+
+static dvp_status run_lmhead_rows(const dvp_lmhead_params *p, const void *hidden, const void *w_train,
+                                  const int64_t *ids, const float *grad_out, const int32_t *rows, int64_t n_sub,
+                                  float *d_hidden, float *d_w, void *workspace, size_t workspace_bytes, void *stream_)
+{
+    if (!p) return DVP_ERR_NULL;
+    if (p->log_rho != p->log_rho || p->log_rho > 0.0f) return DVP_ERR_PARAM;
+    if (p->n_rows < 0 || p->vocab < 1 || p->hidden < 1 || p->ld_hidden < p->hidden || p->ld_w < p->hidden || n_sub < 0 ||
+        n_sub > p->n_rows)
+        return DVP_ERR_SHAPE;
+    if (!lm_params_ok(p)) return DVP_ERR_UNSUPPORTED;
+    if (n_sub == 0) return DVP_OK;
+    if (!hidden || !w_train || !ids || !grad_out || !rows || !d_hidden || !d_w) return DVP_ERR_NULL;
+    if (((uintptr_t)hidden | (uintptr_t)w_train | (uintptr_t)d_hidden | (uintptr_t)d_w) % 16 || (uintptr_t)rows % 4)
+        return DVP_ERR_ALIGN;
+    const LmRowsLayout R = lm_rows_layout(n_sub, p->hidden, p->vocab);
+    if (!workspace || ((uintptr_t)workspace % 256) || workspace_bytes < R.total) return DVP_ERR_WORKSPACE;
+    hipStream_t stream = (hipStream_t)stream_;
+    char *ws = (char *)workspace;
+    LmRowsArgs a;
+    a.rows = rows; a.n_sub = (int32_t)n_sub; a.n = (int32_t)p->n_rows; a.d = (int32_t)p->hidden;
+    a.H = (const uint16_t *)hidden; a.ld_h = p->ld_hidden; a.ids = ids; a.grad_out = grad_out;
+    a.Hc = (uint16_t *)(ws + R.off_h); a.ids_c = (int64_t *)(ws + R.off_ids); a.g_c = (float *)(ws + R.off_g);
+    a.dHc = (float *)(ws + R.off_dh); a.d_hidden = d_hidden;
+    if (launch_lmhead_rows_gather(a, stream) != hipSuccess) return DVP_ERR_HIP;
+    dvp_lmhead_params sub = *p;
+    sub.n_rows = n_sub; sub.ld_hidden = p->hidden;
+    const dvp_side_out none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+    const dvp_status st = run_lmhead(&sub, a.Hc, w_train, nullptr, nullptr, a.ids_c, a.g_c, &none, nullptr, nullptr, a.dHc,
+                                     d_w, ws + R.off_dense, workspace_bytes - R.off_dense, stream_, LM_FUSED, nullptr, 0,
+                                     true);
+    if (st != DVP_OK) return st;
+    if (launch_lmhead_rows_scatter(a, stream) != hipSuccess) return DVP_ERR_HIP;
+    return DVP_OK;
+}
+
 }  // namespace dvp
 
 extern "C" {
+
+size_t dvp_fused_lmhead_rows_workspace_bytes(const dvp_lmhead_params *p, int64_t n_sub)
+{
+    if (!dvp::lm_params_ok(p) || n_sub < 0 || n_sub > p->n_rows) return 0;
+    return dvp::lm_rows_layout(n_sub, p->hidden, p->vocab).total;
+}
+
+dvp_status dvp_fused_lmhead_rows(const dvp_lmhead_params *p, const void *hidden, const void *w_train,
+                                 const int64_t *ids, const float *grad_out, const int32_t *rows, int64_t n_sub,
+                                 float *d_hidden, float *d_w, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return dvp::run_lmhead_rows(p, hidden, w_train, ids, grad_out, rows, n_sub, d_hidden, d_w, workspace, workspace_bytes,
+                                stream);
+}
 
 size_t dvp_fused_lmhead_lists_workspace_bytes(const dvp_lmhead_params *p, int32_t list_cap)
 {

@@ -69,4 +69,23 @@ struct LmSubsetArgs {
 };
 hipError_t launch_lmhead_subset(const LmSubsetArgs &a, hipStream_t stream);
 
+
+// Dense gradient of a subset of the rows: gather before the dense call, scatter after it.
+// rows[j] outside [0, n) is tolerated: the position gets id -1 (no gradient) and nothing is written back.
+struct LmRowsArgs {
+    const int32_t *rows;          // [n_sub]
+    int32_t n_sub, n, d;
+    const uint16_t *H;            // [n, ld_h]
+    int64_t ld_h;
+    const int64_t *ids;           // [n]
+    const float *grad_out;        // [n]
+    uint16_t *Hc;                 // [n_sub, d]
+    int64_t *ids_c;               // [n_sub]
+    float *g_c;                   // [n_sub]
+    float *dHc;                   // [n_sub, d], written by the dense call in between
+    float *d_hidden;              // [n, ld_h]
+};
+hipError_t launch_lmhead_rows_gather(const LmRowsArgs &a, hipStream_t stream);
+hipError_t launch_lmhead_rows_scatter(const LmRowsArgs &a, hipStream_t stream);
+
 }  // namespace dvp

@@ -374,7 +374,44 @@ __global__ __launch_bounds__(kWave) void lm_subset_gather_kernel(const LmSubsetA
     if (lane == 0) { a.m_sub[j] = a.m[r]; a.tau_sub[j] = a.tau[r]; }
 }
 
+// One wavefront per position of the subset
+__global__ __launch_bounds__(kWave) void lm_rows_gather_kernel(const LmRowsArgs a)
+{
+    const int j = blockIdx.x, lane = threadIdx.x;
+    const int r = a.rows[j];
+    const bool ok = r >= 0 && r < a.n;
+    uint16_t *dst = a.Hc + (int64_t)j * a.d;
+    const uint16_t *src = a.H + (int64_t)(ok ? r : 0) * a.ld_h;
+    for (int j0 = lane * 8; j0 < a.d; j0 += kWave * 8) *(u32x4 *)(dst + j0) = *(const u32x4 *)(src + j0);
+    if (lane == 0) {
+        a.ids_c[j] = ok ? a.ids[r] : -1;
+        a.g_c[j] = ok ? a.grad_out[r] : 0.0f;
+    }
+}
+
+__global__ __launch_bounds__(kWave) void lm_rows_scatter_kernel(const LmRowsArgs a)
+{
+    const int j = blockIdx.x, lane = threadIdx.x;
+    const int r = a.rows[j];
+    if (r < 0 || r >= a.n) return;
+    const float *src = a.dHc + (int64_t)j * a.d;
+    float *dst = a.d_hidden + (int64_t)r * a.ld_h;
+    for (int j0 = lane * 4; j0 < a.d; j0 += kWave * 4) *(float4 *)(dst + j0) = *(const float4 *)(src + j0);
+}
+
 }  // namespace
+
+hipError_t launch_lmhead_rows_gather(const LmRowsArgs &a, hipStream_t stream)
+{
+    hipLaunchKernelGGL(lm_rows_gather_kernel, dim3((unsigned)a.n_sub), dim3(kWave), 0, stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_lmhead_rows_scatter(const LmRowsArgs &a, hipStream_t stream)
+{
+    hipLaunchKernelGGL(lm_rows_scatter_kernel, dim3((unsigned)a.n_sub), dim3(kWave), 0, stream, a);
+    return hipGetLastError();
+}
 
 hipError_t launch_lmhead_subset(const LmSubsetArgs &a, hipStream_t stream)
 {

@@ -26,7 +26,7 @@ EXPORTS = ("dvp_forward", "dvp_backward", "dvp_forward_backward", "dvp_fused_lmh
            "dvp_fused_lmhead_f8infer", "dvp_lists_to_dense", "dvp_fused_lmhead_saved_bytes",
            "dvp_fused_lmhead_forward", "dvp_fused_lmhead_backward", "dvp_fused_lmhead_lists",
            "dvp_fused_lmhead_lists_workspace_bytes", "dvp_fused_lmhead_lists_second_pass_rows",
-           "dvp_fused_lmhead_lists_f8infer")
+           "dvp_fused_lmhead_lists_f8infer", "dvp_fused_lmhead_rows", "dvp_fused_lmhead_rows_workspace_bytes")
 
 
 class DvpParams(ctypes.Structure):
@@ -107,6 +107,10 @@ def lib():
         L.dvp_fused_lmhead_lists_f8infer.restype = ctypes.c_int
         L.dvp_fused_lmhead_lists_f8infer.argtypes = [lp, vp, vp, ctypes.POINTER(DvpLmHeadF8Side), i64p, vp, sp, sp, vp, vp, vp,
                                                      ctypes.c_int32, vp, vp, vp, ctypes.c_size_t, vp]
+        L.dvp_fused_lmhead_rows_workspace_bytes.restype = ctypes.c_size_t
+        L.dvp_fused_lmhead_rows_workspace_bytes.argtypes = [lp, ctypes.c_int64]
+        L.dvp_fused_lmhead_rows.restype = ctypes.c_int
+        L.dvp_fused_lmhead_rows.argtypes = [lp, vp, vp, i64p, vp, vp, ctypes.c_int64, vp, vp, vp, ctypes.c_size_t, vp]
         L.dvp_log_rho.restype = ctypes.c_float
         L.dvp_log_rho.argtypes = [ctypes.c_double]
         L.dvp_status_string.restype = ctypes.c_char_p
@@ -469,6 +473,24 @@ def dvp_fused_lmhead_lists(hidden, w_train, w_infer, ids, grad_out, log_rho_valu
     off = int(lib().dvp_fused_lmhead_lists_second_pass_rows(ctypes.byref(p), int(list_cap)))
     res.second_pass = workspace[off:off + 8].view(torch.int32)      # device int32 [2]: rows of each side that needed a second pass
     return res
+
+
+def dvp_fused_lmhead_rows(hidden, w_train, ids, grad_out, log_rho_value, rows, d_hidden, d_w, *,
+                          workspace: Optional[torch.Tensor] = None, stream=None):
+    """Dense gradient of the token rows listed in `rows` (int32, device): d_hidden[rows] overwritten, d_w += ."""
+    n, d = hidden.shape
+    v = w_train.shape[0]
+    if rows.dtype != torch.int32 or not rows.is_cuda or rows.dim() != 1:
+        raise ValueError("rows must be a 1-D int32 GPU tensor")
+    p = DvpLmHeadParams(n, d, v, hidden.stride(0), w_train.stride(0), float(log_rho_value))
+    n_sub = rows.numel()
+    if workspace is None:
+        need = int(lib().dvp_fused_lmhead_rows_workspace_bytes(ctypes.byref(p), n_sub))
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=hidden.device)
+    st = lib().dvp_fused_lmhead_rows(ctypes.byref(p), _ptr(hidden), _ptr(w_train), _ptr(ids), _ptr(grad_out), _ptr(rows),
+                                     n_sub, _ptr(d_hidden), _ptr(d_w), _ptr(workspace), workspace.numel(), _stream(stream))
+    if st != 0:
+        raise DvpError(st, "dvp_fused_lmhead_rows")
 
 
 class LmHeadSaved:

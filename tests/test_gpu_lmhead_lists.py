@@ -248,6 +248,50 @@ def test_padded_strides_and_out_of_range_ids(dvp):
     assert torch.equal(a.d_hidden[keep], b.d_hidden[keep]) and torch.equal(a.d_w, b.d_w)
 
 
+def test_lists_then_dense_rows_give_the_whole_gradient(dvp):
+    """Peaked rows with flat ones among them: the list form covers the rows whose safe set fits the list,
+    dvp_fused_lmhead_rows adds the dense gradient of the flagged ones.  Together: the gradient of every
+    row, against the oracle with the dense call's per-element bounds (the flagged rows' entries pass
+    through bf16 there) and against the dense call itself."""
+    n, d, v, cap = 520, 128, 3000, 64
+    wl = workloads.make_lmhead(device="cuda", n=n, d=d, v=v, hidden_scale=60.0)
+    wl.hidden[::13] = (wl.hidden[::13].float() * 0.05).to(torch.bfloat16)          # wide rows: hundreds of safe tokens
+    lr = dvp.log_rho(1e-4)
+    ids = wl.ids.cpu().numpy()
+    H, Wt = wl.hidden.cpu(), wl.w_train.cpu()
+    fwd = orc.lmhead(H, Wt, ids, np.float32(lr), band=BAND, threads=8)
+    g = wl.grad_out.cpu().numpy().astype(np.float64).copy()
+    g[fwd["band_count"] > 0] = 0.0
+    gout = torch.tensor(g, dtype=torch.float32, device="cuda")
+    res = dvp.dvp_fused_lmhead_lists(wl.hidden, wl.w_train, None, wl.ids, gout, lr, cap)
+    torch.cuda.synchronize()
+    over = torch.nonzero((res.row_flags & dvp.ROW_GRAD_OVERFLOW) != 0).squeeze(1).to(torch.int32)
+    assert 20 <= over.numel() <= 60
+    # an index out of range among them is skipped
+    rows = torch.cat([over, torch.tensor([-1, n], dtype=torch.int32, device="cuda")])
+    dvp.dvp_fused_lmhead_rows(wl.hidden, wl.w_train, wl.ids, gout, lr, rows, res.d_hidden, res.d_w)
+    torch.cuda.synchronize()
+    ot = orc.lmhead(H, Wt, ids, np.float32(lr), grad_out=g, band=BAND, threads=8)
+    H64, W64 = H.double().numpy(), Wt.double().numpy()
+    dense_rows = np.zeros(n, bool)
+    dense_rows[over.cpu().numpy()] = True
+    soft = np.abs(ot["dz"]) * dense_rows[:, None]           # the entries that went through bf16
+    safe_rows = np.nonzero(ot["y_in_safe"])[0]
+    soft[safe_rows, ids[safe_rows]] = 0.0
+    full = np.abs(ot["dz"])
+    full[safe_rows, ids[safe_rows]] = np.abs(g[safe_rows]) * np.exp(ot["logp"][safe_rows])
+    dz_round = 2.0 ** -19 * (np.abs(ot["row_max"]).max() + 10.0)
+    bound_h = 2.0 ** -8 * (soft @ np.abs(W64)) + 2 * dz_round * (full @ np.abs(W64)) + 1e-5 + 2.0 ** -20 * np.abs(ot["d_hidden"])
+    bound_w = 2.0 ** -7 * (soft.T @ np.abs(H64)) + 2 * dz_round * (full.T @ np.abs(H64)) + 1e-5 + 2.0 ** -20 * np.abs(ot["d_w"])
+    dh = res.d_hidden.cpu().double().numpy()
+    dw = res.d_w.cpu().double().numpy()
+    err_h, err_w = (np.abs(dh - ot["d_hidden"]) / bound_h).max(), (np.abs(dw - ot["d_w"]) / bound_w).max()
+    print("dH at %.3f, dW at %.3f of their bounds (%d rows dense)" % (err_h, err_w, over.numel()))
+    assert err_h <= 1.0 and err_w <= 1.0
+    assert np.abs(dh - ot["d_hidden"]).max() <= 2e-3 and np.abs(dw - ot["d_w"]).max() <= 2e-3
+    assert np.abs(ot["d_hidden"][dense_rows]).max() > 0
+
+
 def test_validation(dvp):
     wl = workloads.make_lmhead(device="cuda", n=16, d=64, v=100)
     lr = dvp.log_rho(1e-2)

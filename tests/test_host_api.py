@@ -258,3 +258,15 @@ def test_lmhead_argument_validation_needs_no_gpu():
     assert lists8(P(), S(scale=0.0)) == 3 and lists8(P(), S(ld_h=136)) == 5 and lists8(P(), S(w=FAKE + 8)) == 4
     assert lists8(P(), S()) == 6                    # everything accepted up to the workspace check
     assert lists8(P(n=0), S()) == 0
+
+    # dense gradient of a subset of rows
+    def rows_call(p, n_sub=1, rows=FAKE, grad=FAKE, dh=FAKE, dw=FAKE, bytes_=1000):
+        return L.dvp_fused_lmhead_rows(ctypes.byref(p), FAKE, FAKE, FAKE, grad, rows, n_sub, dh, dw, ws, bytes_, None)
+
+    assert L.dvp_fused_lmhead_rows_workspace_bytes(ctypes.byref(P(n=100)), 10) > 0
+    assert L.dvp_fused_lmhead_rows_workspace_bytes(ctypes.byref(P(n=100)), 101) == 0
+    assert rows_call(P(n=4), n_sub=0) == 0
+    assert rows_call(P(n=4), n_sub=5) == 2 and rows_call(P(n=4), n_sub=-1) == 2
+    assert rows_call(P(n=4), rows=None) == 1 and rows_call(P(n=4), grad=None) == 1 and rows_call(P(n=4), dw=None) == 1
+    assert rows_call(P(n=4), rows=FAKE + 2) == 4 and rows_call(P(n=4, d=96)) == 5
+    assert rows_call(P(n=4)) == 6                   # everything accepted up to the workspace check

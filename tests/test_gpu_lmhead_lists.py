@@ -210,6 +210,15 @@ def test_8bit_inference_engine(dvp):
     assert torch.equal(res.row_flags & 13, ref.row_flags & 13)
     assert torch.equal(res.d_hidden, ref.d_hidden) and torch.equal(res.d_w, ref.d_w)
     assert torch.equal(res.grad_len, ref.grad_len)
+    # with lse_full both sides run both passes over all rows (every token's exponential is needed)
+    full = dvp.dvp_fused_lmhead_lists(wl.hidden, wl.w_train, None, wl.ids, wl.grad_out, lr, 64, lse_full=True,
+                                      infer_f8=(wl.hidden8, wl.w8, wl.scale_infer))
+    torch.cuda.synchronize()
+    assert full.second_pass.tolist() == [0, 0]
+    _check_side("infer", full.infer, oi, oi, band=2e-3)
+    assert torch.equal(full.infer.safe_count, res.infer.safe_count) and torch.equal(full.row_flags, res.row_flags)
+    assert torch.equal(full.grad_len, res.grad_len)
+    assert (full.d_w - res.d_w).abs().max().item() <= 1e-5 * (1 + res.d_w.abs().max().item())
 
 
 def test_padded_strides_and_out_of_range_ids(dvp):

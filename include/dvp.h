@@ -346,9 +346,9 @@ dvp_status dvp_fused_lmhead_rows(const dvp_lmhead_params *params, const void *hi
                                  size_t workspace_bytes, void *stream);
 
 /*
- * dvp_fused_lmhead_lists with an 8-bit inference engine (see dvp_fused_lmhead_f8infer for `infer`): the
- * inference side's passes run on the fp8 matrix instruction, one pass where rows are peaked.  Declared
- * after dvp_lmhead_f8_side below.
+ * dvp_fused_lmhead_lists with an 8-bit inference engine, the mismatch setting of Sec. 4.2 (bf16 trainer,
+ * FP8 rollout engine; see dvp_fused_lmhead_f8infer for `infer`): the inference side's passes run on the
+ * fp8 matrix instruction, one pass where rows are peaked.  Declared after dvp_lmhead_f8_side below.
  */
 
 /*

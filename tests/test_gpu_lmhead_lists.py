@@ -33,7 +33,7 @@ def dvp():
     return binding
 
 
-def _run(dvp, wl, rho, cap, infer=True, lse_full=False):
+def _run(dvp, wl, rho, cap, infer=True, lse_full=False, abs_check=True):
     lr = dvp.log_rho(rho)
     ids = wl.ids.cpu().numpy()
     n = ids.shape[0]
@@ -92,7 +92,8 @@ def _run(dvp, wl, rho, cap, infer=True, lse_full=False):
     print("cap %d: %d listed rows, %d overflow, %d band; dH at %.3f, dW at %.3f of their bounds" %
           (cap, listed.sum(), (over & clean).sum(), band_rows.sum(), err_h, err_w))
     assert err_h <= 1.0 and err_w <= 1.0
-    assert np.abs(dh - ot["d_hidden"]).max() <= 2e-3 and np.abs(dw - ot["d_w"]).max() <= 2e-3    # the bf16-input bar
+    if abs_check:   # the bf16-input bar, where the gradients are O(1)
+        assert np.abs(dh - ot["d_hidden"]).max() <= 2e-3 and np.abs(dw - ot["d_w"]).max() <= 2e-3
     assert np.all(dh[~listed] == 0.0)
     return res, fwd, listed
 
@@ -299,6 +300,18 @@ def test_lists_then_dense_rows_give_the_whole_gradient(dvp):
     assert err_h <= 1.0 and err_w <= 1.0
     assert np.abs(dh - ot["d_hidden"]).max() <= 2e-3 and np.abs(dw - ot["d_w"]).max() <= 2e-3
     assert np.abs(ot["d_hidden"][dense_rows]).max() > 0
+
+
+def test_many_rows(dvp):
+    """100,000 token rows of a small head: 256 row blocks of 391 rows in the column-major copy, several
+    rows per thread in the compaction of the second-pass rows."""
+    wl = workloads.make_lmhead(device="cuda", n=100000, d=64, v=2500, hidden_scale=150.0)
+    wl.hidden[::997] = (wl.hidden[::997].float() * 1e-3).to(torch.bfloat16)
+    # dW sums 100,000 rows of hidden states of magnitude 150: entries reach 500, so only the per-element
+    # bound (relative 2^-20 and up) is meaningful, not the absolute figure
+    res, fwd, listed = _run(dvp, wl, 1e-4, 32, abs_check=False)
+    assert res.second_pass.tolist() == [len(range(0, 100000, 997))] * 2
+    assert listed.sum() > 50000
 
 
 def test_validation(dvp):

@@ -217,9 +217,10 @@ __global__ __launch_bounds__(kThreads) void lm_dw_gather_kernel(const LmListArgs
     }
 }
 
-// zy_low[i]: a value safely below the logit of row i's sampled token as the matrix cores will form it
-// (the same dot product summed in another order: they differ by accumulation rounding, far less than the
-// margin taken off here), hence below the row maximum.  One wavefront per row.
+// zy_low[i]: a value below the logit of row i's sampled token as the matrix cores will form it, hence
+// below the row maximum.  The two are the same dot product of exactly representable terms summed in fp32
+// in different orders: each is within K 2^-24 sum|terms| of the exact value (K terms), so twice that, plus a
+// relative 2^-20 for the scale of an 8-bit engine, is taken off.  One wavefront per row.
 template <bool BYTES>
 __global__ __launch_bounds__(kWave) void lm_zy_low_kernel(const uint16_t *H, int64_t ld_h, const uint16_t *W, int64_t ld_w,
                                                           const int64_t *ids, float *zy_low, int d, int v, float scale8)
@@ -231,7 +232,7 @@ __global__ __launch_bounds__(kWave) void lm_zy_low_kernel(const uint16_t *H, int
         return;
     }
     const uint16_t *h = H + (int64_t)i * ld_h, *w = W + y * ld_w;
-    float acc = 0.0f;
+    float acc = 0.0f, mag = 0.0f;     // the dot product and the sum of its terms' magnitudes
     for (int j0 = lane * 8; j0 < d; j0 += kWave * 8) {
         const u32x4 a = *(const u32x4 *)(h + j0), b = *(const u32x4 *)(w + j0);
         const uint32_t x[4] = {a.x, a.y, a.z, a.w}, u[4] = {b.x, b.y, b.z, b.w};
@@ -241,17 +242,26 @@ __global__ __launch_bounds__(kWave) void lm_zy_low_kernel(const uint16_t *H, int
                 typedef float f32x2 __attribute__((ext_vector_type(2)));
                 const f32x2 xl = __builtin_amdgcn_cvt_pk_f32_fp8((int)x[k], false), xh = __builtin_amdgcn_cvt_pk_f32_fp8((int)x[k], true);
                 const f32x2 ul = __builtin_amdgcn_cvt_pk_f32_fp8((int)u[k], false), uh = __builtin_amdgcn_cvt_pk_f32_fp8((int)u[k], true);
-                acc += xl.x * ul.x; acc += xl.y * ul.y; acc += xh.x * uh.x; acc += xh.y * uh.y;
+                const float t[4] = {xl.x * ul.x, xl.y * ul.y, xh.x * uh.x, xh.y * uh.y};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) { acc += t[q]; mag += fabsf(t[q]); }
             } else {
-                acc += __uint_as_float(x[k] << 16) * __uint_as_float(u[k] << 16);
-                acc += __uint_as_float(x[k] & 0xffff0000u) * __uint_as_float(u[k] & 0xffff0000u);
+                const float t0 = __uint_as_float(x[k] << 16) * __uint_as_float(u[k] << 16);
+                const float t1 = __uint_as_float(x[k] & 0xffff0000u) * __uint_as_float(u[k] & 0xffff0000u);
+                acc += t0; acc += t1;
+                mag += fabsf(t0) + fabsf(t1);
             }
         }
     }
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, kWave);
-    if constexpr (BYTES) acc *= scale8;
-    if (lane == 0) zy_low[i] = acc - 1e-3f * (1.0f + fabsf(acc));
+    for (int off = 32; off > 0; off >>= 1) {
+        acc += __shfl_xor(acc, off, kWave);
+        mag += __shfl_xor(mag, off, kWave);
+    }
+    const float terms = (float)(BYTES ? 2 * d : d);
+    float low = acc - 0x1p-23f * terms * mag;
+    if constexpr (BYTES) low = low * scale8 - 0x1p-20f * fabsf(low * scale8);
+    if (lane == 0) zy_low[i] = low - 1e-6f;
 }
 
 // One workgroup per token row: the candidates at or above the final threshold are the safe set.

@@ -1,6 +1,7 @@
 """Build the gfx950 shared library from csrc/ with hipcc (in-tree, no JIT cache).
 
-    python -m paper_2512_23087_amd.build          # rebuild everything
+    python -m paper_2512_23087_amd.build            # rebuild everything
+    python -m paper_2512_23087_amd.build --changed  # only the sources newer than their objects
 """
 from __future__ import annotations
 
@@ -27,11 +28,23 @@ def _compile(src: str) -> Path:
     return obj
 
 
-def build(verbose: bool = True) -> Path:
-    """Compile every source for gfx950 and link libdvp_hip.so next to this file."""
+def _stale(src: str) -> bool:
+    """An object is up to date when it is newer than its source and every header."""
+    obj = OBJ / (src + ".o")
+    if not obj.exists():
+        return True
+    deps = [CSRC / src, *CSRC.glob("*.h"), *(PKG.parent / "include").glob("*.h")]
+    return any(d.stat().st_mtime > obj.stat().st_mtime for d in deps)
+
+
+def build(verbose: bool = True, only_changed: bool = False) -> Path:
+    """Compile every source for gfx950 (or, with only_changed, the stale ones) and link
+    libdvp_hip.so next to this file."""
     OBJ.mkdir(exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(5, len(SOURCES))) as ex:
-        objs = list(ex.map(_compile, SOURCES))
+    todo = [s for s in SOURCES if not only_changed or _stale(s)]
+    with ThreadPoolExecutor(max_workers=min(5, max(1, len(todo)))) as ex:
+        list(ex.map(_compile, todo))
+    objs = [OBJ / (s + ".o") for s in SOURCES]
     tmp = LIB.with_suffix(".so.tmp%d" % os.getpid())
     subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-rdc",
                            "-o", str(tmp), *map(str, objs)])
@@ -42,5 +55,5 @@ def build(verbose: bool = True) -> Path:
 
 
 if __name__ == "__main__":
-    build()
+    build(only_changed="--changed" in sys.argv[1:])
     sys.exit(0)

@@ -251,7 +251,15 @@ __device__ __forceinline__ bool row_task(const RowArgs &a, TaskState &s, u32x4 (
         if (tid < tail_n) nxt_raw = load_raw(znext + (int64_t)nvec_n * EPV_N + tid);
     }
     {   // ragged end: one element per thread
-        wave_count += __builtin_popcountll(__builtin_amdgcn_ballot_w64(xt >= tau));
+        const unsigned long long tail_ballot = __builtin_amdgcn_ballot_w64(xt >= tau);
+        wave_count += __builtin_popcountll(tail_ballot);
+        if constexpr (EXTRAS != 0 && !OVF) {
+            // The ragged end's membership bits travel with the slot after the last whole vector.  A row
+            // whose whole vectors fill every slot has no such slot: its last bitmask word then holds the
+            // ragged end alone (NT * NVS vectors are a multiple of 32 tokens) and is written from here.
+            if (bits_row && tail && nvec == NT * NVS && tid == 0)
+                ((uint32_t *)bits_row)[(int64_t)nvec * EPV / 32] = (uint32_t)tail_ballot & ((1u << tail) - 1u);
+        }
         const float ex = __expf(xt - m);
         s_safe += (xt >= tau) ? ex : 0.0f;
         if (want_full) s_full += ex;

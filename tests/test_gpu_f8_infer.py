@@ -120,6 +120,31 @@ def test_shapes_single_read_path(dvp, v, ld_t, ld_i):
     _run(dvp, wl, 1e-3, backward=False, extras=False, threads=3)
 
 
+@pytest.mark.parametrize("slots", [256 * 4, 256 * 8, 256 * 16, 1024 * 8, 1024 * 12, 1024 * 16, 1024 * 20])
+@pytest.mark.parametrize("extra", [1, 7])
+def test_membership_bits_when_whole_vectors_fill_every_register_slot(dvp, slots, extra):
+    """Rows whose whole vectors fill every slot of a kernel build exactly (bf16: `slots` vectors of 8;
+    bytes: half as many of 16), plus a ragged end that then has no slot to carry its membership bits.
+    The bit buffers start as all ones, so a word the kernel leaves alone shows."""
+    v = slots * 8 + extra
+    n = 3
+    wl = _case(n, v, seed=slots + extra, ld_t=slots * 8 + 8, ld_i=slots * 8 + 16)
+    with torch.no_grad():
+        wl.z_train[0, v - 1] = 30.0
+        wl.z_infer.view(torch.uint8)[1, v - 1] = 0x7E      # 448, the largest E4M3 value
+    for rho in (1e-2, 0.0):
+        lr = dvp.log_rho(rho)
+        out_t = dvp.SideOutputs(n, v, "cuda", lse_full=True, safe_bits=True)
+        out_i = dvp.SideOutputs(n, v, "cuda", lse_full=True, safe_bits=True)
+        out_t.safe_bits.fill_(-1)
+        out_i.safe_bits.fill_(-1)
+        res = dvp.dvp_forward(wl.z_train, wl.z_infer, wl.ids, lr, out_train=out_t, out_infer=out_i)
+        torch.cuda.synchronize()
+        ids = wl.ids.cpu()
+        parity.check_side("train", res.train, wl.z_train.cpu(), ids, lr, 2e-3, v, threads=4)
+        parity.check_side("infer", res.infer, _codes(wl.z_infer), ids, lr, 1e-4, v, threads=4)
+
+
 @pytest.mark.parametrize("train_dtype", [torch.bfloat16, torch.float32])
 @pytest.mark.parametrize("v", [1, 5, 15, 1001, 40000])
 def test_shapes_rereading_path(dvp, train_dtype, v):

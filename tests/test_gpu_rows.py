@@ -155,6 +155,35 @@ def test_shapes_resident_path(dvp, dtype, v):
 
 
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("slots", [256 * 4, 256 * 8, 256 * 16, 1024 * 8, 1024 * 12, 1024 * 16, 1024 * 19, 1024 * 20])
+@pytest.mark.parametrize("extra", ["one", "all_but_one"])
+def test_membership_bits_when_whole_vectors_fill_every_register_slot(dvp, dtype, slots, extra):
+    """Rows whose whole 16-byte vectors fill every slot of a kernel build exactly, plus a ragged end:
+    the ragged end's bits have no slot of their own there.  The bit buffers start as all ones, so a word
+    the kernel does not write shows."""
+    epv = 8 if dtype == torch.bfloat16 else 4
+    v = slots * epv + (1 if extra == "one" else epv - 1)
+    n = 3
+    ld = (v + epv - 1) // epv * epv
+    wl = _random_case(n, v, dtype, seed=slots + len(extra), ld=ld)
+    with torch.no_grad():       # ragged-end tokens on both sides of the threshold
+        wl.z_train[0, v - 1] = 30.0
+        wl.z_infer[1, v - 1] = 30.0
+    for rho in (1e-2, 0.0):
+        lr = dvp.log_rho(rho)
+        out_t = dvp.SideOutputs(n, v, "cuda", lse_full=True, safe_bits=True)
+        out_i = dvp.SideOutputs(n, v, "cuda", lse_full=True, safe_bits=True)
+        out_t.safe_bits.fill_(-1)
+        out_i.safe_bits.fill_(-1)
+        res = dvp.dvp_forward(wl.z_train, wl.z_infer, wl.ids, lr, out_train=out_t, out_infer=out_i)
+        torch.cuda.synchronize()
+        ids = wl.ids.cpu()
+        tol = parity.TOL[dtype]
+        parity.check_side("train", res.train, wl.z_train.cpu(), ids, lr, tol, v, threads=4)
+        parity.check_side("infer", res.infer, wl.z_infer.cpu(), ids, lr, tol, v, threads=4)
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
 @pytest.mark.parametrize("v", [1, 5, 64, 1001, 5000, 40000])
 def test_shapes_streaming_path_misaligned(dvp, dtype, v):
     # odd leading dimension and an element offset: rows are not 16-byte aligned

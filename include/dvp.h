@@ -13,6 +13,11 @@
  *     caller; the library never allocates, frees or retains them.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
  *     Work is enqueued on it; no entry point synchronises.
+ *   - The first launch of a kernel build on a device also asks the runtime how
+ *     many of its workgroups a CU holds, or raises its LDS limit (host calls,
+ *     nothing is enqueued).  dvp_prepare() does all of that ahead of time; call
+ *     it once per device before capturing an entry point into a HIP graph whose
+ *     first call would otherwise fall inside the capture.
  *   - The return value reports only what the host can see (null pointers,
  *     shapes, parameters, launch failures).  Conditions only the device can
  *     see (a sampled id outside [0, V)) are reported per row in `row_flags`.
@@ -446,6 +451,16 @@ dvp_status dvp_sequence_weights(int64_t n_tokens, int64_t n_seq, const float *lo
                                 const float *logp_infer, const int64_t *seq_offsets, float log_threshold,
                                 float *weight, float *seq_log_ratio, float *seq_min_weight,
                                 uint8_t *seq_veto, void *stream);
+
+/*
+ * One-time set-up of every kernel build for the CURRENT device (hipSetDevice): occupancy queries, the
+ * LDS-size attribute of the matrix-core kernels, the device's CU count.  Host only; enqueues nothing,
+ * allocates nothing.  Optional: an entry point whose build has not been prepared on the current device
+ * does its own part at its first call there.  After dvp_prepare() every entry point only validates its
+ * arguments and enqueues kernels, so it can be called under stream capture right away.
+ * Returns DVP_OK, or DVP_ERR_HIP when the runtime refuses a query (no usable device).
+ */
+dvp_status dvp_prepare(void);
 
 /* (float)log(threshold) for threshold > 0; NaN otherwise.  Host only. */
 float dvp_log_threshold(double threshold);

@@ -5,6 +5,16 @@
 
 #include "dvp_internal.h"
 
+namespace dvp {
+
+std::vector<PrepareFn> &prepare_list()
+{
+    static std::vector<PrepareFn> list;   // built while the library is loaded, read-only afterwards
+    return list;
+}
+
+}  // namespace dvp
+
 namespace {
 
 using dvp::BackwardArgs;
@@ -262,6 +272,13 @@ dvp_status dvp_sequence_weights(int64_t n_tokens, int64_t n_seq, const float *lo
     a.weight = weight; a.seq_log_ratio = seq_log_ratio; a.seq_min_weight = seq_min_weight;
     a.seq_veto = seq_veto; a.n_tokens = n_tokens; a.n_seq = n_seq; a.log_threshold = log_threshold;
     return dvp::launch_sequences(a, (hipStream_t)stream) == hipSuccess ? DVP_OK : DVP_ERR_HIP;
+}
+
+dvp_status dvp_prepare(void)
+{
+    for (dvp::PrepareFn f : dvp::prepare_list())
+        if (f() != hipSuccess) return DVP_ERR_HIP;
+    return DVP_OK;
 }
 
 float dvp_log_threshold(double threshold)

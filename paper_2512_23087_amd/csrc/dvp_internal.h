@@ -3,9 +3,21 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "../../include/dvp.h"
 
 namespace dvp {
+
+// One-time set-up steps of the launchers (occupancy queries, the LDS-size attribute of the GEMM
+// kernels, the device's CU count).  Every launcher that has one registers it while the library is
+// loaded; dvp_prepare() runs them all for the current device.  A launcher whose step has not run yet
+// on the current device still runs it at its first launch there.
+typedef hipError_t (*PrepareFn)();
+std::vector<PrepareFn> &prepare_list();
+struct PrepareRegistrar {
+    explicit PrepareRegistrar(PrepareFn f) { prepare_list().push_back(f); }
+};
 
 struct SideOut {
     float *logp;

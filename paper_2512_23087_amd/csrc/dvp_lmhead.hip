@@ -648,34 +648,52 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs
     }
 }
 
+static std::atomic<int> g_gemm_cus{0};   // callers may come from several host threads
+static hipError_t prepare_gemm_cu_count()
+{
+    int dev = 0, n = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e == hipSuccess && n > 0) g_gemm_cus.store(n, std::memory_order_relaxed);
+    return e;
+}
+static PrepareRegistrar g_gemm_cus_registrar(&prepare_gemm_cu_count);
 static int gemm_cu_count()
 {
-    static std::atomic<int> cached{0};   // callers may come from several host threads
-    if (cached.load(std::memory_order_relaxed) == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-            cached.store(n, std::memory_order_relaxed);
-        else
-            return 256;
-    }
-    return cached.load(std::memory_order_relaxed);
+    if (g_gemm_cus.load(std::memory_order_relaxed) == 0 && prepare_gemm_cu_count() != hipSuccess) return 256;
+    const int n = g_gemm_cus.load(std::memory_order_relaxed);
+    return n > 0 ? n : 256;
 }
+
+// More than 64 KB of LDS per workgroup has to be asked for, once per kernel and device (bit d of
+// `configured`: device d has it).
+template <class Epi, bool NEEDS_FINISH, bool F8>
+struct GemmBuild {
+    static inline std::atomic<uint64_t> configured{0};
+    static hipError_t prepare()
+    {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute((const void *)gemm_nt_kernel<Epi, NEEDS_FINISH, F8>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
+        if (e == hipSuccess && dev < 64) configured.fetch_or(1ull << dev, std::memory_order_release);
+        return e;
+    }
+    static inline PrepareRegistrar registrar{&prepare};
+};
 
 template <class Epi, bool NEEDS_FINISH, bool F8 = false>
 static hipError_t launch_gemm(const GemmArgs &g, const Epi &epi, hipStream_t stream)
 {
-    // More than 64 KB of LDS per workgroup has to be asked for, once per device (bit d: device d has it).
-    static std::atomic<uint64_t> configured{0};
+    typedef GemmBuild<Epi, NEEDS_FINISH, F8> Build;
+    (void)&Build::registrar;             // instantiates the registration of this build
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
-    const uint64_t bit = 1ull << (dev & 63);
-    if (dev > 63 || !(configured.load(std::memory_order_acquire) & bit)) {
-        e = hipFuncSetAttribute((const void *)gemm_nt_kernel<Epi, NEEDS_FINISH, F8>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
+    if (dev > 63 || !(Build::configured.load(std::memory_order_acquire) & (1ull << dev))) {
+        e = Build::prepare();
         if (e != hipSuccess) return e;
-        configured.fetch_or(bit, std::memory_order_release);
     }
     const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
     const int total = tiles_m * tiles_n;
@@ -1015,7 +1033,8 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
         if (((uintptr_t)f8->hidden | (uintptr_t)f8->w) % 16) return DVP_ERR_ALIGN;
     }
     const bool infer_side = w_infer != nullptr || f8 != nullptr;
-    const LmLayout L = lm_layout(p->n_rows, p->hidden, p->vocab);
+    // (a forward-only call uses the per-row statistics and partials only, which come first in the layout)
+    const LmLayout L = lm_layout(p->n_rows, p->hidden, p->vocab, phase != LM_FUSED || grad_out != nullptr);
     if (!workspace || ((uintptr_t)workspace % 256) || workspace_bytes < L.total) return DVP_ERR_WORKSPACE;
     const LmSaved SV = lm_saved_layout(p->n_rows, p->vocab);
     if (phase != LM_FUSED && (!saved || ((uintptr_t)saved % 256) || saved_bytes < SV.total)) return DVP_ERR_WORKSPACE;

@@ -924,43 +924,52 @@ __global__ __launch_bounds__(kListsScatterThreads) void lists_scatter_kernel(con
 // ---------------------------------------------------------------------------
 // Compute units of the first device asked about, cached for the process (and so is the occupancy below):
 // the kernels walk their rows from any grid size, so on another device the figure only costs speed.
+static std::atomic<int> g_cu_count{0};   // callers may come from several host threads
+static hipError_t prepare_cu_count()
+{
+    int dev = 0, n = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e == hipSuccess && n > 0) g_cu_count.store(n, std::memory_order_relaxed);
+    return e;
+}
+static PrepareRegistrar g_cu_count_registrar(&prepare_cu_count);
 static int device_cu_count()
 {
-    static std::atomic<int> cached{0};   // callers may come from several host threads
-    if (cached.load(std::memory_order_relaxed) == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-            cached.store(n, std::memory_order_relaxed);
-        else
-            return 256;
-    }
-    return cached.load(std::memory_order_relaxed);
+    if (g_cu_count.load(std::memory_order_relaxed) == 0 && prepare_cu_count() != hipSuccess) return 256;
+    const int n = g_cu_count.load(std::memory_order_relaxed);
+    return n > 0 ? n : 256;
 }
 
-template <typename Kernel>
-static int blocks_per_cu(Kernel k, int threads)
-{
-    int nb = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, k, threads, 0) != hipSuccess || nb < 1) nb = 1;
-    return nb;
-}
+// One build of the resident kernel and how many of its workgroups a CU holds (queried once).
+template <typename T, bool F8_INFER, int NV, int NVFULL, int NT, int MINW, int EXTRAS, bool OVF>
+struct ResidentBuild {
+    typedef void (*Kernel)(const RowArgs);
+    static Kernel kernel()
+    {
+        if constexpr (F8_INFER) return rows_resident_f8infer_kernel<T, NV, NVFULL, NT, MINW, EXTRAS>;
+        else                    return rows_resident_kernel<T, NV, NVFULL, NT, MINW, EXTRAS, OVF>;
+    }
+    static inline std::atomic<int> per_cu{0};
+    static hipError_t prepare()
+    {
+        int nb = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kernel(), NT, 0) != hipSuccess || nb < 1) nb = 1;
+        per_cu.store(nb, std::memory_order_relaxed);
+        return hipSuccess;
+    }
+    static inline PrepareRegistrar registrar{&prepare};
+};
 
 template <typename T, bool F8_INFER, int NV, int NVFULL, int NT, int MINW, int EXTRAS, bool OVF = false>
 static hipError_t launch_resident_inst(const RowArgs &a, hipStream_t stream)
 {
-    void (*kernel)(const RowArgs);
-    if constexpr (F8_INFER) kernel = rows_resident_f8infer_kernel<T, NV, NVFULL, NT, MINW, EXTRAS>;
-    else                    kernel = rows_resident_kernel<T, NV, NVFULL, NT, MINW, EXTRAS, OVF>;
-    static std::atomic<int> per_cu_cache{0};
-    int per_cu = per_cu_cache.load(std::memory_order_relaxed);
-    if (per_cu == 0) {
-        per_cu = blocks_per_cu(kernel, NT);
-        per_cu_cache.store(per_cu, std::memory_order_relaxed);
-    }
-    int64_t grid = (int64_t)device_cu_count() * per_cu;
+    typedef ResidentBuild<T, F8_INFER, NV, NVFULL, NT, MINW, EXTRAS, OVF> Build;
+    (void)&Build::registrar;             // instantiates the registration of this build
+    if (Build::per_cu.load(std::memory_order_relaxed) == 0) (void)Build::prepare();
+    int64_t grid = (int64_t)device_cu_count() * Build::per_cu.load(std::memory_order_relaxed);
     if (grid > a.n_rows) grid = a.n_rows;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(NT), 0, stream, a);
+    hipLaunchKernelGGL(Build::kernel(), dim3((unsigned)grid), dim3(NT), 0, stream, a);
     return hipGetLastError();
 }
 

@@ -26,7 +26,8 @@ EXPORTS = ("dvp_forward", "dvp_backward", "dvp_forward_backward", "dvp_fused_lmh
            "dvp_fused_lmhead_f8infer", "dvp_lists_to_dense", "dvp_fused_lmhead_saved_bytes",
            "dvp_fused_lmhead_forward", "dvp_fused_lmhead_backward", "dvp_fused_lmhead_lists",
            "dvp_fused_lmhead_lists_workspace_bytes", "dvp_fused_lmhead_lists_second_pass_rows",
-           "dvp_fused_lmhead_lists_f8infer", "dvp_fused_lmhead_rows", "dvp_fused_lmhead_rows_workspace_bytes")
+           "dvp_fused_lmhead_lists_f8infer", "dvp_fused_lmhead_rows", "dvp_fused_lmhead_rows_workspace_bytes",
+           "dvp_prepare")
 
 
 class DvpParams(ctypes.Structure):
@@ -126,12 +127,21 @@ def lib():
                                            vp, vp, vp, vp, vp]
         L.dvp_log_threshold.restype = ctypes.c_float
         L.dvp_log_threshold.argtypes = [ctypes.c_double]
+        L.dvp_prepare.restype = ctypes.c_int
+        L.dvp_prepare.argtypes = []
         _lib = L
     return _lib
 
 
 def status_string(status: int) -> str:
     return lib().dvp_status_string(int(status)).decode()
+
+
+def prepare() -> None:
+    """One-time set-up of every kernel build on the current device (see dvp_prepare in dvp.h)."""
+    st = lib().dvp_prepare()
+    if st != 0:
+        raise DvpError(st, "dvp_prepare")
 
 
 def log_rho(rho: float) -> float:

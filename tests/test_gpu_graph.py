@@ -164,3 +164,46 @@ def test_concurrent_callers_on_their_own_streams(dvp):
     for i in range(2):
         assert torch.equal(out[i].dz, ref[i].dz) and torch.equal(out[i].train.logp, ref[i].train.logp)
         assert torch.equal(out[i].row_flags, ref[i].row_flags)
+
+
+FRESH_PROCESS = r"""
+import sys
+import torch
+from paper_2512_23087_amd import dvp, workloads
+
+dvp.prepare()                               # the only library call before the capture
+wl = workloads.make_rows(2, device="cuda", n=64, v=40000)
+lm = workloads.make_lmhead(device="cuda", n=300, d=128, v=1500)
+lr = dvp.log_rho(1e-4)
+ws = torch.empty(dvp.lmhead_workspace_bytes(300, 128, 1500), dtype=torch.uint8, device="cuda")
+dh, dw = torch.empty(300, 128, device="cuda"), torch.empty(1500, 128, device="cuda")
+torch.cuda.synchronize()
+g = torch.cuda.CUDAGraph()
+with torch.cuda.graph(g):
+    rows = dvp.dvp_forward_backward(wl.z_train, wl.z_infer, wl.ids, wl.grad_out, lr, lse_full=True, safe_bits=True)
+    head = dvp.dvp_fused_lmhead(lm.hidden, lm.w_train, lm.w_infer, lm.ids, lm.grad_out, lr, workspace=ws,
+                                d_hidden=dh, d_w=dw)
+for rep in range(2):
+    g.replay()
+    torch.cuda.synchronize()
+    ref = dvp.dvp_forward_backward(wl.z_train, wl.z_infer, wl.ids, wl.grad_out, lr, lse_full=True, safe_bits=True)
+    ref_head = dvp.dvp_fused_lmhead(lm.hidden, lm.w_train, lm.w_infer, lm.ids, lm.grad_out, lr)
+    torch.cuda.synchronize()
+    assert torch.equal(rows.dz, ref.dz) and torch.equal(rows.train.logp, ref.train.logp), rep
+    assert torch.equal(rows.train.safe_bits, ref.train.safe_bits) and torch.equal(rows.row_flags, ref.row_flags), rep
+    assert torch.equal(dh, ref_head.d_hidden) and torch.equal(dw, ref_head.d_w), rep
+    assert torch.equal(head.train.logp, ref_head.train.logp) and torch.equal(head.infer.logp, ref_head.infer.logp), rep
+print("fresh-process capture ok")
+"""
+
+
+def test_capture_as_the_first_call_of_a_fresh_process_after_prepare():
+    """dvp_prepare() does every kernel build's one-time host set-up (occupancy queries, LDS limits), so the
+    very first call of an entry point can already sit inside a stream capture.  Runs in a process of its
+    own: in this one earlier tests have made those first calls."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, "-c", FRESH_PROCESS], cwd=root, capture_output=True, text=True, timeout=600)
+    assert res.returncode == 0 and "fresh-process capture ok" in res.stdout, res.stdout[-2000:] + res.stderr[-4000:]

@@ -270,3 +270,82 @@ def test_lmhead_argument_validation_needs_no_gpu():
     assert rows_call(P(n=4), rows=None) == 1 and rows_call(P(n=4), grad=None) == 1 and rows_call(P(n=4), dw=None) == 1
     assert rows_call(P(n=4), rows=FAKE + 2) == 4 and rows_call(P(n=4, d=96)) == 5
     assert rows_call(P(n=4)) == 6                   # everything accepted up to the workspace check
+
+
+C_PROGRAM = r"""
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+#include "dvp.h"
+
+#define CHECK(cond) do { if (!(cond)) { printf("FAILED line %d: %s\n", __LINE__, #cond); return 1; } } while (0)
+
+int main(void)
+{
+    dvp_params p;
+    dvp_side_out out;
+    dvp_lmhead_params lp;
+    memset(&p, 0, sizeof p);
+    memset(&out, 0, sizeof out);
+    memset(&lp, 0, sizeof lp);
+
+    CHECK(dvp_log_rho(1.0) == 0.0f);
+    CHECK(dvp_log_rho(0.0) == -INFINITY);
+    CHECK(isnan(dvp_log_rho(1.5)));
+    CHECK(fabsf(dvp_log_rho(1e-4) - (float)log(1e-4)) == 0.0f);
+    CHECK(fabsf(dvp_log_threshold(1e-4) - (float)log(1e-4)) == 0.0f);
+    CHECK(strcmp(dvp_status_string(DVP_OK), "ok") == 0);
+
+    CHECK(dvp_forward(NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL) == DVP_ERR_NULL);
+    p.n_rows = 1; p.vocab = 100; p.ld_train = 100; p.ld_infer = 100; p.ld_grad = 100;
+    p.dtype = DVP_BF16; p.dtype_infer = DVP_BF16; p.log_rho = -3.0f; p.mode = DVP_MODE_EXACT;
+    CHECK(dvp_forward(&p, NULL, NULL, NULL, &out, NULL, NULL, NULL) == DVP_ERR_NULL);
+    p.log_rho = 1.0f;
+    CHECK(dvp_forward(&p, NULL, NULL, NULL, &out, NULL, NULL, NULL) == DVP_ERR_PARAM);
+    p.log_rho = -3.0f; p.ld_train = 99;
+    CHECK(dvp_forward(&p, NULL, NULL, NULL, &out, NULL, NULL, NULL) == DVP_ERR_SHAPE);
+    p.ld_train = 100; p.n_rows = 0;
+    CHECK(dvp_forward(&p, NULL, NULL, NULL, &out, NULL, NULL, NULL) == DVP_OK);
+    CHECK(dvp_backward(&p, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL) == DVP_OK);
+    CHECK(dvp_forward_backward(&p, NULL, NULL, NULL, NULL, &out, NULL, NULL, NULL, NULL) == DVP_OK);
+    CHECK(dvp_row_path(&p, 1) == 0);                     /* 200-byte rows: not 16-byte aligned */
+    p.vocab = 104; p.ld_train = 104; p.ld_infer = 104; p.ld_grad = 104;
+    CHECK(dvp_row_path(&p, 1) == 1);
+    CHECK(dvp_row_path(NULL, 1) == -1);
+
+    lp.n_rows = 16; lp.hidden = 128; lp.vocab = 1000; lp.ld_hidden = 128; lp.ld_w = 128; lp.log_rho = -2.0f;
+    CHECK(dvp_fused_lmhead_workspace_bytes(&lp) > 0);
+    CHECK(dvp_fused_lmhead_workspace_bytes(NULL) == 0);
+    CHECK(dvp_fused_lmhead(&lp, NULL, NULL, NULL, NULL, NULL, &out, NULL, NULL, NULL, NULL, NULL, 0, NULL) == DVP_ERR_NULL);
+    lp.hidden = 100; lp.ld_hidden = 104; lp.ld_w = 104;
+    CHECK(dvp_fused_lmhead(&lp, NULL, NULL, NULL, NULL, NULL, &out, NULL, NULL, NULL, NULL, NULL, 0, NULL) == DVP_ERR_UNSUPPORTED);
+    CHECK(dvp_sequence_weights(-1, 1, NULL, NULL, NULL, -9.0f, NULL, NULL, NULL, NULL, NULL) == DVP_ERR_SHAPE);
+    CHECK(sizeof(dvp_grad_entry) == 8);
+    printf("ok\n");
+    return 0;
+}
+"""
+
+
+def test_header_is_plain_c11_and_host_entry_points_work_from_c(tmp_path):
+    """include/dvp.h compiles as C11 (pedantic, warnings are errors) and a C program linked against the
+    library gets the host-only results and the validation codes without a GPU."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    dvp.lib()
+    src = tmp_path / "host_check.c"
+    src.write_text(C_PROGRAM)
+    exe = tmp_path / "host_check"
+    libdir = str(dvp.LIB_PATH.parent)
+    subprocess.check_call(["gcc", "-std=c11", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", str(ROOT / "include"),
+                           str(src), "-o", str(exe), "-L", libdir, "-l:libdvp_hip.so", "-lm",
+                           "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib"])
+    res = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert res.returncode == 0 and res.stdout.strip() == "ok", res.stdout + res.stderr
+
+
+def test_prepare_is_a_host_call():
+    """dvp_prepare touches no data: DVP_OK with a usable GPU, DVP_ERR_HIP without one, never a crash."""
+    assert dvp.lib().dvp_prepare() in (0, 7)

@@ -53,7 +53,8 @@ typedef enum {
     DVP_ERR_ALIGN = 4,       /* a pointer is not aligned to its element size */
     DVP_ERR_UNSUPPORTED = 5, /* shape or alignment outside what the entry point handles */
     DVP_ERR_WORKSPACE = 6,   /* workspace missing or too small */
-    DVP_ERR_HIP = 7          /* the HIP runtime refused a launch */
+    DVP_ERR_HIP = 7,         /* the HIP runtime refused a launch */
+    DVP_ERR_SCRATCH = 8      /* dvp_fused_lmhead_forward_noalloc: the sizes need more than DVP_NOALLOC_SCRATCH_BYTES */
 } dvp_status;
 
 typedef enum {
@@ -276,6 +277,30 @@ dvp_status dvp_fused_lmhead(const dvp_lmhead_params *params, const void *hidden,
                             const float *grad_out, const dvp_side_out *out_train,
                             const dvp_side_out *out_infer, uint8_t *row_flags, float *d_hidden,
                             float *d_w, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * dvp_fused_lmhead without grad_out (the forward of both sides: log-probs, row maxima, lse, safe-set
+ * sizes, membership bits, row_flags) for callers that cannot allocate device memory and so have no
+ * workspace to hand over: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  The per-row statistics and per-tile partials that dvp_fused_lmhead keeps in its
+ * workspace live in a buffer of DVP_NOALLOC_SCRATCH_BYTES inside the library instead (one per GPU,
+ * held until the process ends).  The call allocates nothing, frees nothing and synchronises nothing;
+ * same kernels, same results as dvp_fused_lmhead(..., grad_out = NULL, ...).
+ *   Arguments as for dvp_fused_lmhead; inputs and outputs are still the caller's.
+ *   Limit: the call needs about N * (24 * ceil(V / 256) + 40) bytes of that buffer (N = 4600 at
+ *   V = 151936, N = 16384 up to V = 43000); beyond it the call returns DVP_ERR_SCRATCH and enqueues
+ *   nothing.
+ *   Every call on a GPU uses that GPU's one buffer: two calls that overlap in time on one GPU (two
+ *   streams, two host threads) race on it.  Calls on one stream, or ordered by events, are fine; what a
+ *   call leaves in the buffer is never read by the next.
+ *   The buffer's address is looked up once per device (by dvp_prepare(), else by the first call there).
+ */
+#define DVP_NOALLOC_SCRATCH_BYTES (64u << 20)
+
+dvp_status dvp_fused_lmhead_forward_noalloc(const dvp_lmhead_params *params, const void *hidden,
+                                            const void *w_train, const void *w_infer, const int64_t *ids,
+                                            const dvp_side_out *out_train, const dvp_side_out *out_infer,
+                                            uint8_t *row_flags, void *stream);
 
 /*
  * The LM-head variant with the gradient kept as per-row lists (Prop. 5.4: dz is zero outside the safe

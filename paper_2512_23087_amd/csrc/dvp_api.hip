@@ -316,6 +316,7 @@ const char *dvp_status_string(dvp_status status)
     case DVP_ERR_UNSUPPORTED: return "shape or alignment not supported by this entry point";
     case DVP_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case DVP_ERR_HIP: return "HIP runtime error at kernel launch";
+    case DVP_ERR_SCRATCH: return "sizes need more than the library's static scratch buffer (DVP_NOALLOC_SCRATCH_BYTES)";
     }
     return "unknown status";
 }

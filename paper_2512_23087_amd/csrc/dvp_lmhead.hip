@@ -1008,7 +1008,7 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
                              const float *grad_out, const dvp_side_out *out_train, const dvp_side_out *out_infer,
                              uint8_t *row_flags, float *d_hidden, float *d_w, void *workspace,
                              size_t workspace_bytes, void *stream_, LmPhase phase = LM_FUSED, void *saved = nullptr,
-                             size_t saved_bytes = 0, bool dw_accumulate = false)
+                             size_t saved_bytes = 0, bool dw_accumulate = false, bool stats_only_ws = false)
 {
     if (!p) return DVP_ERR_NULL;
     if (p->log_rho != p->log_rho || p->log_rho > 0.0f) return DVP_ERR_PARAM;
@@ -1033,8 +1033,10 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
         if (((uintptr_t)f8->hidden | (uintptr_t)f8->w) % 16) return DVP_ERR_ALIGN;
     }
     const bool infer_side = w_infer != nullptr || f8 != nullptr;
-    // (a forward-only call uses the per-row statistics and partials only, which come first in the layout)
-    const LmLayout L = lm_layout(p->n_rows, p->hidden, p->vocab, phase != LM_FUSED || grad_out != nullptr);
+    // stats_only_ws: a forward-only call uses the per-row statistics and partials only, which come first in
+    // the layout; the caller vouches for a workspace of that size
+    if (stats_only_ws && (phase != LM_FUSED || grad_out)) return DVP_ERR_PARAM;
+    const LmLayout L = lm_layout(p->n_rows, p->hidden, p->vocab, !stats_only_ws);
     if (!workspace || ((uintptr_t)workspace % 256) || workspace_bytes < L.total) return DVP_ERR_WORKSPACE;
     const LmSaved SV = lm_saved_layout(p->n_rows, p->vocab);
     if (phase != LM_FUSED && (!saved || ((uintptr_t)saved % 256) || saved_bytes < SV.total)) return DVP_ERR_WORKSPACE;
@@ -1443,9 +1445,58 @@ static dvp_status run_lmhead_rows(const dvp_lmhead_params *p, const void *hidden
     return DVP_OK;
 }
 
+// The forward-only call for callers that cannot allocate: its per-row statistics and per-tile partials
+// live in this array instead of a caller's workspace.  In host code the array's name is only a handle:
+// the address kernels and launchers use is asked for once per device (each device holds its own copy).
+static __device__ __align__(256) unsigned char scratch[DVP_NOALLOC_SCRATCH_BYTES];
+constexpr int kScratchDevices = 64;
+static std::atomic<void *> g_scratch_ptr[kScratchDevices];
+
+static hipError_t prepare_scratch()
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kScratchDevices) return hipErrorInvalidDevice;
+    void *ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+    return hipSuccess;
+}
+static PrepareRegistrar g_scratch_registrar(&prepare_scratch);
+
+static dvp_status run_lmhead_forward_noalloc(const dvp_lmhead_params *p, const void *hidden, const void *w_train,
+                                             const void *w_infer, const int64_t *ids, const dvp_side_out *out_train,
+                                             const dvp_side_out *out_infer, uint8_t *row_flags, void *stream)
+{
+    if (p && lm_params_ok(p) && p->n_rows > 0 &&
+        lm_layout(p->n_rows, p->hidden, p->vocab, false).total > (size_t)DVP_NOALLOC_SCRATCH_BYTES)
+        return DVP_ERR_SCRATCH;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kScratchDevices) return DVP_ERR_HIP;
+    void *ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {                       // first call on this device and dvp_prepare() has not run there
+        if (prepare_scratch() != hipSuccess) return DVP_ERR_HIP;
+        ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    }
+    // every per-row statistic is initialised and every partial overwritten by the call's own kernels:
+    // what the previous call left in the array is never read
+    return run_lmhead(p, hidden, w_train, w_infer, nullptr, ids, nullptr, out_train, out_infer, row_flags, nullptr,
+                      nullptr, ptr, (size_t)DVP_NOALLOC_SCRATCH_BYTES, stream, LM_FUSED, nullptr, 0, false, true);
+}
+
 }  // namespace dvp
 
 extern "C" {
+
+dvp_status dvp_fused_lmhead_forward_noalloc(const dvp_lmhead_params *p, const void *hidden, const void *w_train,
+                                            const void *w_infer, const int64_t *ids, const dvp_side_out *out_train,
+                                            const dvp_side_out *out_infer, uint8_t *row_flags, void *stream)
+{
+    return dvp::run_lmhead_forward_noalloc(p, hidden, w_train, w_infer, ids, out_train, out_infer, row_flags, stream);
+}
 
 size_t dvp_fused_lmhead_rows_workspace_bytes(const dvp_lmhead_params *p, int64_t n_sub)
 {

@@ -27,7 +27,7 @@ EXPORTS = ("dvp_forward", "dvp_backward", "dvp_forward_backward", "dvp_fused_lmh
            "dvp_fused_lmhead_forward", "dvp_fused_lmhead_backward", "dvp_fused_lmhead_lists",
            "dvp_fused_lmhead_lists_workspace_bytes", "dvp_fused_lmhead_lists_second_pass_rows",
            "dvp_fused_lmhead_lists_f8infer", "dvp_fused_lmhead_rows", "dvp_fused_lmhead_rows_workspace_bytes",
-           "dvp_prepare")
+           "dvp_prepare", "dvp_fused_lmhead_forward_noalloc")
 
 
 class DvpParams(ctypes.Structure):
@@ -129,6 +129,8 @@ def lib():
         L.dvp_log_threshold.argtypes = [ctypes.c_double]
         L.dvp_prepare.restype = ctypes.c_int
         L.dvp_prepare.argtypes = []
+        L.dvp_fused_lmhead_forward_noalloc.restype = ctypes.c_int
+        L.dvp_fused_lmhead_forward_noalloc.argtypes = [lp, vp, vp, vp, i64p, sp, sp, vp, vp]
         _lib = L
     return _lib
 
@@ -421,6 +423,24 @@ def dvp_fused_lmhead(hidden, w_train, w_infer, ids, grad_out, log_rho_value, *, 
     if st != 0:
         raise DvpError(st, "dvp_fused_lmhead")
     return LmHeadResult(out_train, out_infer, row_flags, d_hidden, d_w)
+
+
+NOALLOC_SCRATCH_BYTES = 64 << 20
+
+
+def dvp_fused_lmhead_forward_noalloc(hidden, w_train, w_infer, ids, log_rho_value, out_train: SideOutputs,
+                                     out_infer: Optional[SideOutputs], row_flags, *, stream=None) -> LmHeadResult:
+    """Forward of both sides with the library's own scratch buffer instead of a workspace; every output
+    buffer comes from the caller, so nothing is allocated here either."""
+    p = DvpLmHeadParams(hidden.shape[0], hidden.shape[1], w_train.shape[0], hidden.stride(0), w_train.stride(0),
+                        float(log_rho_value))
+    st = lib().dvp_fused_lmhead_forward_noalloc(ctypes.byref(p), _ptr(hidden), _ptr(w_train), _ptr(w_infer), _ptr(ids),
+                                                ctypes.byref(out_train.struct()),
+                                                ctypes.byref(out_infer.struct()) if out_infer is not None else None,
+                                                _ptr(row_flags), _stream(stream))
+    if st != 0:
+        raise DvpError(st, "dvp_fused_lmhead_forward_noalloc")
+    return LmHeadResult(out_train, out_infer, row_flags, None, None)
 
 
 class LmHeadListsResult(LmHeadResult):

@@ -28,8 +28,8 @@ def test_log_rho_and_status_strings():
     assert dvp.log_rho(0.0) == -math.inf
     assert math.isnan(dvp.log_rho(2.0)) and math.isnan(dvp.log_rho(-1.0))
     assert dvp.status_string(0) == "ok"
-    texts = {dvp.status_string(i) for i in range(8)}
-    assert len(texts) == 8 and dvp.status_string(99) == "unknown status"
+    texts = {dvp.status_string(i) for i in range(9)}
+    assert len(texts) == 9 and dvp.status_string(99) == "unknown status"
 
 
 def _fwd(p, z_train=FAKE, z_infer=FAKE, ids=FAKE, out_train=True, out_infer=True):
@@ -295,6 +295,7 @@ int main(void)
     CHECK(fabsf(dvp_log_rho(1e-4) - (float)log(1e-4)) == 0.0f);
     CHECK(fabsf(dvp_log_threshold(1e-4) - (float)log(1e-4)) == 0.0f);
     CHECK(strcmp(dvp_status_string(DVP_OK), "ok") == 0);
+    CHECK(strlen(dvp_status_string(DVP_ERR_SCRATCH)) > 0);
 
     CHECK(dvp_forward(NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL) == DVP_ERR_NULL);
     p.n_rows = 1; p.vocab = 100; p.ld_train = 100; p.ld_infer = 100; p.ld_grad = 100;

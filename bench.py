@@ -22,13 +22,12 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 
-# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by the
-# same counters' reading on a plain copy kernel of known size.  Only valid for the kernel
-# source it was measured on: keyed by the sha256 of the kernel sources.
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by the same
+# counters' reading on a plain copy kernel of known size.  A figure is only valid for the kernel
+# sources it was measured on: the table is keyed by the sha256 of those sources, then by the run's
+# configuration; see profiles/rows_*_hbm_traffic.md for the counter values and scale factors.
+# A run whose sources or configuration have no entry reports "traffic": null, "traffic_stale": true.
 MEASURED_TRAFFIC = {
-    # sha256 of csrc/dvp_rows.hip + dvp_device.h + dvp_internal.h -> HBM bytes per launch; see
-    # profiles/rows_cfg3_hbm_traffic.md for the counter values and scale factors
-    "da5f035eb7ab63057ccd3c378112de220225eed736ba3fc25b28182308f7454c": {"cfg3": 29894924000},
 }
 
 
@@ -41,6 +40,20 @@ def kernel_source_hash() -> str:
     return h.hexdigest()
 
 
+def traffic_key(args) -> str:
+    """Names the configuration a traffic figure belongs to."""
+    key = "%s/rho=%g" % (args.workload, args.rho)
+    if args.rows is not None:
+        key += "/rows=%d" % args.rows
+    if args.sparse_grad:
+        key += "/lists=%d" % args.sparse_grad
+    if args.split_lists:
+        key += "/split=%d" % args.split_lists
+    if args.infer_dtype != "same":
+        key += "/infer=" + args.infer_dtype
+    return key
+
+
 def algorithmic_bytes_per_row(vocab: int, elem: int, infer_elem: int) -> int:
     """What the method must move per row: read the training row, read the
     inference row, write the gradient row, plus the per-row scalars
@@ -48,34 +61,31 @@ def algorithmic_bytes_per_row(vocab: int, elem: int, infer_elem: int) -> int:
     return 2 * vocab * elem + vocab * infer_elem + 8 + 4 + 16 * 2 + 1
 
 
-def cpu_baseline(wl, log_rho, target_seconds=12.0):
-    """The fp64 oracle, as it stands, on a bounded sample of the same workload."""
+def host_threads() -> int:
+    return min(os.cpu_count() or 1, 16)
+
+
+def oracle_one_core(wl, log_rho, rows=1024):
+    """The fp64 oracle on ONE thread over the first rows of the workload: rows/s."""
     import numpy as np
     from oracle import dvp_oracle as orc
-    threads = min(os.cpu_count() or 1, 16)
-    n = wl.z_train.shape[0]
-
-    chunk = 512
-    done, spent, r0 = 0, 0.0, 0
-    while spent < target_seconds:            # walks the workload's rows, wrapping around if it is short
-        r1 = min(n, r0 + chunk)
-        zt = wl.z_train[r0:r1].cpu()
-        zi = wl.z_infer[r0:r1].cpu()
+    n = min(rows, wl.z_train.shape[0])
+    spent = 0.0
+    for r0 in range(0, n, 256):
+        r1 = min(n, r0 + 256)
+        zt, zi = wl.z_train[r0:r1].cpu(), wl.z_infer[r0:r1].cpu()
         ids = wl.ids[r0:r1].cpu().numpy()
         g = wl.grad_out[r0:r1].cpu().numpy().astype(np.float64)
         t0 = time.perf_counter()
-        orc.rows(zt, ids, np.float32(log_rho), grad_out=g, want_dz=True, threads=threads)
-        orc.rows(zi, ids, np.float32(log_rho), threads=threads)
+        orc.rows(zt, ids, np.float32(log_rho), grad_out=g, want_dz=True, threads=1)
+        orc.rows(zi, ids, np.float32(log_rho), threads=1)
         spent += time.perf_counter() - t0
-        done += r1 - r0
-        r0 = r1 if r1 < n else 0
-    return {"value": done / spent, "unit": "rows/s", "cores": threads, "kind": "oracle",
-            "sample": "%d rows of the workload in chunks of %d (wrapping around after its %d rows), forward "
-                      "(both sides) + backward, fp64 C oracle on %d threads, %.1f s of CPU wall time"
-                      % (done, chunk, n, threads, spent)}
+    return n / spent, n, spent
 
 
 def time_launches(fn, steps, warmup):
+    """W untimed calls, then K calls between two synchronisations: wall time of the K calls and each
+    call's duration from HIP events recorded around it on the stream it is launched on."""
     import torch
     for _ in range(warmup):
         fn()
@@ -94,8 +104,15 @@ def time_launches(fn, steps, warmup):
     return wall, per_launch_ms
 
 
+def median(xs):
+    ys = sorted(xs)
+    k = len(ys)
+    return ys[k // 2] if k % 2 else 0.5 * (ys[k // 2 - 1] + ys[k // 2])
+
+
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 matrix peak
 MFMA_FP8_PEAK_TFLOPS = 5000.0    # and dense fp8
+EXECUTED_TRAIN_PASSES, EXECUTED_INFER_PASSES = 4, 2   # GEMM passes dvp_fused_lmhead runs per side (2 forward + dH + dW; 2 forward)
 
 
 def bench_lmhead(args):
@@ -153,22 +170,26 @@ def bench_lmhead(args):
             if over_rows is not None and over_rows.numel():
                 dvp.dvp_fused_lmhead_rows(wl.hidden, wl.w_train, wl.ids, wl.grad_out, lr, over_rows, dh, dw, workspace=ws_rows)
         elif two_calls:
-            _, kept = dvp.dvp_fused_lmhead_forward(wl.hidden, wl.w_train, None if f8 else wl.w_infer, wl.ids, lr,
-                                                   infer_f8=(wl.hidden8, wl.w8, wl.scale_infer) if f8 else None,
-                                                   saved=saved, workspace=ws)
+            fwd, kept = dvp.dvp_fused_lmhead_forward(wl.hidden, wl.w_train, None if f8 else wl.w_infer, wl.ids, lr,
+                                                     infer_f8=(wl.hidden8, wl.w8, wl.scale_infer) if f8 else None,
+                                                     saved=saved, workspace=ws)
             dvp.dvp_fused_lmhead_backward(kept, wl.grad_out, d_hidden=dh, d_w=dw)
+            fwd.d_hidden, fwd.d_w = dh, dw
+            last["res"] = fwd
         elif f8:
-            dvp.dvp_fused_lmhead(wl.hidden, wl.w_train, None, wl.ids, wl.grad_out, lr, workspace=ws, d_hidden=dh,
-                                 d_w=dw, infer_f8=(wl.hidden8, wl.w8, wl.scale_infer))
+            last["res"] = dvp.dvp_fused_lmhead(wl.hidden, wl.w_train, None, wl.ids, wl.grad_out, lr, workspace=ws,
+                                               d_hidden=dh, d_w=dw, infer_f8=(wl.hidden8, wl.w8, wl.scale_infer))
         else:
-            dvp.dvp_fused_lmhead(wl.hidden, wl.w_train, wl.w_infer, wl.ids, wl.grad_out, lr,
-                                 workspace=ws, d_hidden=dh, d_w=dw)
+            last["res"] = dvp.dvp_fused_lmhead(wl.hidden, wl.w_train, wl.w_infer, wl.ids, wl.grad_out, lr,
+                                               workspace=ws, d_hidden=dh, d_w=dw)
 
     steps = min(args.steps, 5)
     wall, per_launch = time_launches(step, steps, min(args.warmup, 2))
     ms = sum(per_launch) / len(per_launch)
     gemm = 2.0 * n * v * d
-    useful, executed = 4 * gemm, 6 * gemm          # train fwd, infer fwd, dH, dW; vs the passes actually run
+    # useful: train forward, inference forward, dH, dW; executed: each side's forward produces the logits
+    # twice (row maxima first, then the sums at the threshold)
+    useful, executed = 4 * gemm, (EXECUTED_TRAIN_PASSES + EXECUTED_INFER_PASSES) * gemm
     extra = {}
     if lists_cap:
         res = last["res"]
@@ -192,12 +213,16 @@ def bench_lmhead(args):
         if over_rows is not None:
             extra.update(extra_dense)
             extra["gemm_passes"] = passes
-    # (each side's forward produces the logits twice: row max first, then sums at the threshold)
-    # Peak for the mix of passes: each contraction is priced at the peak of its own operand type, so the
-    # call's floor is sum(flop_i / peak_i) and the peak quoted is executed flop over that floor.
-    n_f8 = (n_f8_passes if lists_cap else 2) if f8 else 0
-    floor_s = ((executed / gemm - n_f8) * gemm / MFMA_BF16_PEAK_TFLOPS + n_f8 * gemm / MFMA_FP8_PEAK_TFLOPS) / 1e12
-    peak = executed / floor_s / 1e12
+    # Peak for a mix of passes: each contraction is priced at the peak of its own operand type, so a
+    # call's floor is sum(flop_i / peak_i) and the peak quoted is its flop over that floor.  The roofline
+    # fraction is on the USEFUL flop (the method's own work: train forward, inference forward, dH, dW,
+    # or the list form's shorter sums); the passes actually executed are reported beside it.
+    def mixed_peak(total_flop, f8_flop):
+        return total_flop / ((total_flop - f8_flop) / MFMA_BF16_PEAK_TFLOPS + f8_flop / MFMA_FP8_PEAK_TFLOPS)
+    n_f8 = (n_f8_passes if lists_cap else EXECUTED_INFER_PASSES) if f8 else 0
+    peak_exec = mixed_peak(executed, n_f8 * gemm)
+    peak_useful = mixed_peak(useful, gemm if f8 else 0.0)
+    useful_rate = useful / (ms * 1e-3) / 1e12
     result = {
         "metric": "DVP fused LM-head fwd+bwd rows/s and MFMA TFLOP/s, V=%d bf16" % v,
         "value": n * steps / wall, "unit": "rows/s", "n_gpus": 1, "steps": steps,
@@ -215,16 +240,53 @@ def bench_lmhead(args):
                                   "dvp_fused_lmhead_forward + dvp_fused_lmhead_backward" if two_calls else
                                   "dvp_fused_lmhead_f8infer" if f8 else "dvp_fused_lmhead",
                    "workspace_bytes": ws.numel(), "saved_bytes": saved.numel() if two_calls else 0, **extra},
-        "roofline": {"bound": "mfma", "achieved": executed / (ms * 1e-3) / 1e12,
-                     "peak": peak, "unit": "TFLOP/s",
-                     "frac": executed / (ms * 1e-3) / 1e12 / peak, "traffic": None,
-                     "kernel": "gemm_nt_kernel (%.4g GEMM passes of 2*N*V*d flop each per call%s)"
-                               % (extra.get("gemm_passes", 6), ": 4 bf16 at 2.5 PFLOP/s peak, 2 fp8 at 5.0" if f8 else ""),
-                     "kernel_ms_avg": ms, "executed_tflop": executed / 1e12,
-                     "useful_tflop": useful / 1e12,
-                     "useful_tflops": useful / (ms * 1e-3) / 1e12},
+        "roofline": {"bound": "mfma", "achieved": useful_rate, "peak": peak_useful, "unit": "TFLOP/s",
+                     "frac": useful_rate / peak_useful, "traffic": None, "basis": "useful flop",
+                     "kernel": "gemm_nt_kernel (%.4g GEMM passes of 2*N*V*d flop each executed per call%s)"
+                               % (executed / gemm, "; bf16 passes priced at 2.5 PFLOP/s, fp8 passes at 5.0" if f8 else ""),
+                     "kernel_ms_avg": ms, "kernel_ms_median": median(per_launch), "kernel_ms_min": min(per_launch),
+                     "timed_launches": len(per_launch),
+                     "useful_tflop": useful / 1e12, "executed_tflop": executed / 1e12,
+                     "gemm_passes_executed": executed / gemm, "gemm_passes_useful": useful / gemm,
+                     "executed_tflops": executed / (ms * 1e-3) / 1e12, "executed_peak": peak_exec,
+                     "executed_frac": executed / (ms * 1e-3) / 1e12 / peak_exec},
     }
+    # ---- sampled rows of the last timed call against the oracle (fp64 logits from the stored H and W with
+    # ---- a BLAS matrix product, then the row oracle), and that oracle's speed as the CPU baseline
+    if not args.no_cpu_baseline:
+        import numpy as np
+        from tests import parity
+        torch.cuda.synchronize()
+        rng = np.random.default_rng(4)
+        k = min(n, args.parity_rows if args.parity_rows > 0 else 256)
+        rows = np.unique(np.concatenate([[0, n - 1], rng.choice(n, k - 2, replace=False)])) if k > 2 else np.arange(k)
+        threads = host_threads()
+        res = last.get("res")
+        if lists_cap:       # rows over the list cap carry no dH in the list form: forward outputs only
+            import types
+            res = types.SimpleNamespace(train=res.train, infer=res.infer, d_hidden=None)
+        band = 2e-3 if f8 else 2e-4
+        chk, spent = parity.lmhead_sampled_rows(wl, res, rows, lr, band=band, threads=threads,
+                                                infer_scale=wl.scale_infer if f8 else None)
+        chk.update(what="outputs of the last timed call on %d sampled token rows: forward of both sides%s" %
+                        (len(rows), " and the rows of dH" if res.d_hidden is not None else ""), of_rows=n, rho=args.rho)
+        result["parity"] = {"ok": chk["ok"], "checks": [chk]}
+        from threadpoolctl import threadpool_limits
+        one = rows[:8]
+        with threadpool_limits(limits=1):
+            _, spent1 = parity.lmhead_sampled_rows(wl, res, one, lr, band=band, threads=1,
+                                                   infer_scale=wl.scale_infer if f8 else None)
+        result["cpu_baseline"] = {
+            "value": len(rows) / spent, "unit": "rows/s", "cores": threads, "kind": "oracle",
+            "value_1core": len(one) / spent1,
+            "sample": "fp64 oracle with BLAS matrix products for the logits (H W^T of both sides, and dz W for dH) and the "
+                      "C row oracle on them: %d sampled rows on %d threads in %.1f s, %d rows on 1 thread in %.1f s; the "
+                      "full workload is %d rows, so the whole-job figure is this rate as it stands (no dW in it)"
+                      % (len(rows), threads, spent, len(one), spent1, n)}
     print(json.dumps(result))
+    if result.get("parity") and not result["parity"]["ok"]:
+        print("bench.py: the timed outputs do NOT match the oracle", file=sys.stderr)
+        sys.exit(1)
 
 
 def bench_sequences(args):
@@ -278,7 +340,7 @@ def bench_sequences(args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "lmhead", "seq"])
     ap.add_argument("--rho", type=float, default=1e-4)
@@ -303,7 +365,10 @@ def main():
     ap.add_argument("--infer-dtype", default="same", choices=["same", "f8"],
                     help="f8: the inference logits are rounded through E4M3 (saturating) and handed over as "
                          "one byte per token")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true",
+                    help="leave the oracle out: no cpu_baseline, no parity check of the timed outputs")
+    ap.add_argument("--parity-rows", type=int, default=0, metavar="K",
+                    help="check about K evenly spaced rows of the timed call against the oracle instead of every row")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run 3 plain device-to-device copies of one logits matrix (known "
@@ -326,6 +391,15 @@ def main():
         return bench_lmhead(args)
     if args.workload == "seq":
         return bench_sequences(args)
+    return bench_rows(args)
+
+
+def bench_rows(args):
+    """configs[1..3]: one step = one fused forward+backward call over the whole batch."""
+    import numpy as np
+    import torch
+    from paper_2512_23087_amd import dvp, workloads
+
     cfg = int(args.workload[-1])
     t_gen = time.perf_counter()
     wl = workloads.make_rows(cfg, device="cuda:0", n=args.rows)
@@ -342,55 +416,63 @@ def main():
         torch.cuda.synchronize()
     infer_elem = wl.z_infer.element_size()
 
-    out_t = dvp.SideOutputs(n, v, wl.z_train.device)
-    out_i = dvp.SideOutputs(n, v, wl.z_train.device)
-    flags = torch.empty(n, dtype=torch.uint8, device="cuda:0")
-    dz = torch.empty_like(wl.z_train)
-
-    if args.split_lists:
-        cap = args.split_lists
-        entries = torch.empty(n, cap, 2, dtype=torch.int32, device="cuda:0")
-        glen = torch.empty(n, dtype=torch.int32, device="cuda:0")
+    # Buffer sets.  A working set smaller than the 256 MB last-level cache would be served from it, so
+    # such a workload (configs[1]: 393 MB per set, close to it) is rotated over several copies of its
+    # inputs and outputs: every call then finds its rows in HBM, as a training step would.
+    set_bytes = n * v * (2 * elem + infer_elem)
+    n_sets = 1 if set_bytes > (2 << 30) else max(3, -(-(1 << 30) // set_bytes))
+    sets = []
+    for k in range(n_sets):
+        sets.append(dict(
+            zt=wl.z_train if k == 0 else wl.z_train.clone(), zi=wl.z_infer if k == 0 else wl.z_infer.clone(),
+            ids=wl.ids if k == 0 else wl.ids.clone(), go=wl.grad_out if k == 0 else wl.grad_out.clone(),
+            out_t=dvp.SideOutputs(n, v, wl.z_train.device), out_i=dvp.SideOutputs(n, v, wl.z_train.device),
+            flags=torch.empty(n, dtype=torch.uint8, device="cuda:0"),
+            dz=None if args.sparse_grad else torch.empty_like(wl.z_train)))
+    cap = args.split_lists or args.sparse_grad
+    if cap:
+        for b in sets:
+            b["entries"] = torch.empty(n, cap, 2, dtype=torch.int32, device="cuda:0")
+            b["glen"] = torch.empty(n, dtype=torch.int32, device="cuda:0")
         ones = torch.ones(n, dtype=torch.float32, device="cuda:0")
+    turn = [0]
 
-        def step(log_rho_value=lr):
-            sp = dvp.dvp_forward_backward_sparse(wl.z_train, wl.z_infer, wl.ids, ones, log_rho_value, cap,
-                                                 out_train=out_t, out_infer=out_i, row_flags=flags,
-                                                 entries=entries, grad_len=glen)
-            dvp.dvp_lists_to_dense(sp, v, wl.z_train.dtype, wl.grad_out, log_rho_value, z_train=wl.z_train,
-                                   ids=wl.ids, dz=dz)
-    elif args.sparse_grad:
-        del dz
-        entries = torch.empty(n, args.sparse_grad, 2, dtype=torch.int32, device="cuda:0")
-        glen = torch.empty(n, dtype=torch.int32, device="cuda:0")
-
-        def step(log_rho_value=lr):
-            dvp.dvp_forward_backward_sparse(wl.z_train, wl.z_infer, wl.ids, wl.grad_out, log_rho_value,
-                                            args.sparse_grad, out_train=out_t, out_infer=out_i,
-                                            row_flags=flags, entries=entries, grad_len=glen)
-    else:
-        def step(log_rho_value=lr):
-            dvp.dvp_forward_backward(wl.z_train, wl.z_infer, wl.ids, wl.grad_out, log_rho_value,
-                                     out_train=out_t, out_infer=out_i, row_flags=flags, dz=dz)
+    def step(log_rho_value=lr):
+        b = sets[turn[0] % n_sets]
+        turn[0] += 1
+        if args.split_lists:
+            sp = dvp.dvp_forward_backward_sparse(b["zt"], b["zi"], b["ids"], ones, log_rho_value, cap,
+                                                 out_train=b["out_t"], out_infer=b["out_i"], row_flags=b["flags"],
+                                                 entries=b["entries"], grad_len=b["glen"])
+            dvp.dvp_lists_to_dense(sp, v, b["zt"].dtype, b["go"], log_rho_value, z_train=b["zt"], ids=b["ids"], dz=b["dz"])
+        elif args.sparse_grad:
+            dvp.dvp_forward_backward_sparse(b["zt"], b["zi"], b["ids"], b["go"], log_rho_value, cap,
+                                            out_train=b["out_t"], out_infer=b["out_i"], row_flags=b["flags"],
+                                            entries=b["entries"], grad_len=b["glen"])
+        else:
+            dvp.dvp_forward_backward(b["zt"], b["zi"], b["ids"], b["go"], log_rho_value,
+                                     out_train=b["out_t"], out_infer=b["out_i"], row_flags=b["flags"], dz=b["dz"])
+        return b
 
     if args.copy_probe:
         for _ in range(3):
-            dz.copy_(wl.z_train)
+            sets[0]["dz"].copy_(wl.z_train)
         torch.cuda.synchronize()
     wall, per_launch = time_launches(step, args.steps, args.warmup)
     ms_per_step = wall * 1e3 / args.steps
     kernel_ms = sum(per_launch) / len(per_launch)
+    last = sets[(turn[0] - 1) % n_sets]                 # the buffer set the last timed call wrote
+    out_t, out_i, flags, dz = last["out_t"], last["out_i"], last["flags"], last["dz"]
     bytes_per_launch = algorithmic_bytes_per_row(v, elem, infer_elem) * n
     if args.sparse_grad:
         # no dense gradient row; the lists that were written (8 bytes per entry) and their lengths instead
-        listed = glen[(flags & 8) == 0].to(torch.int64).sum().item()
+        listed = last["glen"][(flags & 8) == 0].to(torch.int64).sum().item()
         bytes_per_launch += -v * elem * n + 8 * listed + 4 * n
     achieved = bytes_per_launch / (kernel_ms * 1e-3) / 1e9
 
-    traffic = MEASURED_TRAFFIC.get(kernel_source_hash(), {}).get(args.workload) \
-        if args.rows is None and args.rho == 1e-4 and not args.sparse_grad and not args.split_lists \
-        and args.infer_dtype == "same" else None
+    traffic = MEASURED_TRAFFIC.get(kernel_source_hash(), {}).get(traffic_key(args))
 
+    dense_call = not args.sparse_grad and not args.split_lists
     result = {
         "metric": "DVP fwd+bwd rows/s and achieved HBM GB/s (% of peak), V=151936 bf16",
         "value": n * args.steps / wall,
@@ -406,6 +488,7 @@ def main():
                    "storage_dtype": str(wl.z_train.dtype)[6:], "infer_storage_dtype": str(wl.z_infer.dtype)[6:],
                    "n_rows": n, "vocab": v,
                    "rho": args.rho,
+                   "buffer_sets": n_sets,
                    "entry_point": "dvp_forward_backward_sparse (grad_out = 1, list capacity %d) + dvp_lists_to_dense"
                                   % args.split_lists if args.split_lists else
                                   "dvp_forward_backward_sparse (list capacity %d)" % args.sparse_grad
@@ -415,17 +498,19 @@ def main():
                                      2 if infer_elem == 1 else (1 if elem == 2 else 0)), 1) == 1 else "streaming",
                    "input_generation_s": round(t_gen, 2)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_stale": traffic is None,
                      "kernel": "rows_resident_kernel (lists) + lists_zero_kernel + lists_scatter_kernel (+ "
                                "backward_kernel on overflowing rows); durations summed" if args.split_lists else
                                "rows_resident_kernel (gradient as lists)" if args.sparse_grad else
                                "rows_resident_kernel + grad_zero_kernel + grad_scatter_kernel "
                                "(one dvp_forward_backward call; durations summed)",
-                     "kernel_ms_avg": kernel_ms, "kernel_ms_min": min(per_launch),
+                     "kernel_ms_avg": kernel_ms, "kernel_ms_median": median(per_launch),
+                     "kernel_ms_min": min(per_launch), "timed_launches": len(per_launch),
+                     "frac_at_median": bytes_per_launch / (median(per_launch) * 1e-3) / 1e9 / HBM_PEAK_GBS,
                      "algorithmic_bytes_per_launch": bytes_per_launch},
     }
 
-    # safe-set sizes at the headline threshold, and the threshold sweep of configs[3]
+    # safe-set sizes at the headline threshold
     cnt = out_t.safe_count.to(torch.float64)
     result["safe_set"] = {"mean": cnt.mean().item(), "median": cnt.median().item(),
                           "max": cnt.max().item(),
@@ -435,27 +520,90 @@ def main():
     if args.split_lists:
         result["overflow_rows"] = int(((flags & 8) != 0).sum().item())
         # the lists are written once and read once on top of the dense figure
-        listed = glen[(flags & 8) == 0].to(torch.int64).sum().item()
+        listed = last["glen"][(flags & 8) == 0].to(torch.int64).sum().item()
         result["roofline"]["list_bytes_per_launch"] = 16 * listed
+
+    # ---- parity of the timed call's outputs with the fp64 oracle (outside the timed region), and the
+    # ---- oracle's own speed on the same rows as the CPU baseline
+    use_oracle = not args.no_cpu_baseline
+    threads = host_threads()
+    sample = np.arange(0, n, max(1, n // 2048), dtype=np.int64)      # the rows checked at the sweep's other thresholds
+    parity_out = None
+
+    def membership_bits(b, log_rho_value):
+        """An untimed dvp_forward with lse_full and the membership bitmask on a gathered copy of the
+        sampled rows (the timed call runs the lean build), compared bit by bit with the oracle."""
+        from tests import parity
+        idx = torch.as_tensor(sample, device="cuda:0")
+        sub = workloads.RowWorkload("sample", b["zt"][idx].contiguous(), b["zi"][idx].contiguous(),
+                                    b["ids"][idx].contiguous(), b["go"][idx].contiguous(), [])
+        res = dvp.dvp_forward(sub.z_train, sub.z_infer, sub.ids, log_rho_value, lse_full=True, safe_bits=True)
+        torch.cuda.synchronize()
+        return parity.compare_workload(sub, log_rho_value, res.train, res.infer, res.row_flags, None, threads=threads,
+                                       bits=(res.train, res.infer)).result()
+
+    def with_bits(chk, bits):
+        chk["membership_bit_mismatches"] = bits["membership_bit_mismatches"]
+        chk["membership_rows_checked"] = bits["membership_rows_checked"]
+        chk["lse_full_max_abs_err"] = bits["lse_full_max_abs_err"]
+        chk["ok"] = bool(chk["ok"] and bits["ok"])
+        return chk
+
+    if use_oracle and dense_call:
+        from tests import parity
+        torch.cuda.synchronize()
+        view = workloads.RowWorkload("timed", last["zt"], last["zi"], last["ids"], last["go"], [])
+        rows_all = None if args.parity_rows <= 0 or args.parity_rows >= n else \
+            np.arange(0, n, max(1, n // args.parity_rows), dtype=np.int64)
+        t0 = time.perf_counter()
+        rp = parity.compare_workload(view, lr, out_t, out_i, flags, dz, rows=rows_all, threads=threads)
+        head = rp.result()
+        head["rho"] = args.rho
+        head["of_rows"] = n
+        head["what"] = "outputs of the last timed call, %s" % ("every row" if rows_all is None else "every %d-th row" % (n // args.parity_rows))
+        with_bits(head, membership_bits(last, lr))
+        head["seconds"] = round(time.perf_counter() - t0, 1)
+        parity_out = {"ok": head["ok"], "checks": [head]}
+        one_rate, one_rows, one_s = oracle_one_core(view, lr)
+        result["cpu_baseline"] = {
+            "value": rp.rows / rp.oracle_seconds, "unit": "rows/s", "cores": threads, "kind": "oracle",
+            "value_1core": one_rate,
+            "sample": "fp64 C oracle, forward (both sides) + backward: %d rows of the workload on %d threads in %.1f s "
+                      "(the same pass that checks the timed outputs); %d rows on 1 thread in %.1f s"
+                      % (rp.rows, threads, rp.oracle_seconds, one_rows, one_s)}
+
     if not args.no_sweep and not args.sparse_grad:
         sweep = []
         for rho in wl.rhos:
             lr_s = dvp.log_rho(rho)
             w, pl = time_launches(lambda: step(lr_s), max(3, args.steps // 3), 2)
             k_ms = sum(pl) / len(pl)
-            c = out_t.safe_count
+            b = sets[(turn[0] - 1) % n_sets]
+            c = b["out_t"].safe_count
             edges = [1, 2, 4, 16, 256, 4096, 65536, v + 1]
             hist = torch.bucketize(c.to(torch.int64), torch.tensor(edges, device=c.device), right=True)
-            sweep.append({"rho": rho, "kernel_ms_avg": k_ms,
+            sweep.append({"rho": rho, "kernel_ms_avg": k_ms, "kernel_ms_median": median(pl),
                           "rows_per_s": n / (k_ms * 1e-3),
                           "hbm_frac": bytes_per_launch / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                           "safe_size_hist": {"edges": edges,
                                              "counts": torch.bincount(hist, minlength=len(edges) + 1).tolist()}})
+            if use_oracle and dense_call and rho != args.rho:
+                from tests import parity
+                view = workloads.RowWorkload("timed", b["zt"], b["zi"], b["ids"], b["go"], [])
+                t0 = time.perf_counter()
+                rp = parity.compare_workload(view, lr_s, b["out_t"], b["out_i"], b["flags"], b["dz"], rows=sample, threads=threads)
+                chk = with_bits(rp.result(), membership_bits(b, lr_s))
+                chk.update(rho=rho, of_rows=n, what="outputs of the last timed call at this threshold, %d rows (every %d-th)"
+                           % (len(sample), max(1, n // 2048)), seconds=round(time.perf_counter() - t0, 1))
+                parity_out["checks"].append(chk)
+                parity_out["ok"] = bool(parity_out["ok"] and chk["ok"])
         result["threshold_sweep"] = sweep
 
-    if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(wl, lr)
+    result["parity"] = parity_out
     print(json.dumps(result))
+    if parity_out is not None and not parity_out["ok"]:
+        print("bench.py: the timed outputs do NOT match the oracle", file=sys.stderr)
+        sys.exit(1)
 
 
 if __name__ == "__main__":

@@ -320,16 +320,49 @@ def test_repeated_runs_are_bit_identical(dvp):
 # full benchmark size, in the launch configuration the benchmark times:
 # sampled rows against the oracle, plus properties that hold at any size
 # ---------------------------------------------------------------------------
-def test_full_size_large_vocab_sampled_rows(dvp):
+def _full_size_check(dvp, wl, rho, rows, bits_rows=256):
+    """One fused call on the whole workload in the benchmark's launch configuration (lean build, caller's
+    buffers), its outputs on `rows` (None: every row) against the oracle; then the membership bitmask and
+    lse_full of a second call on the first `bits_rows` of those rows, bit by bit."""
+    lr = dvp.log_rho(rho)
+    n, v = wl.z_train.shape
+    res = dvp.dvp_forward_backward(wl.z_train, wl.z_infer, wl.ids, wl.grad_out, lr)
+    torch.cuda.synchronize()
+    rp = parity.compare_workload(wl, lr, res.train, res.infer, res.row_flags, res.dz, rows=rows, threads=16)
+    out = rp.result()
+    assert out["ok"], out
+    sel = np.arange(n)[:bits_rows] if rows is None else rows[:bits_rows]
+    idx = torch.as_tensor(sel, device="cuda")
+    sub = workloads.RowWorkload("sub", wl.z_train[idx].contiguous(), wl.z_infer[idx].contiguous(),
+                                wl.ids[idx].contiguous(), wl.grad_out[idx].contiguous(), [])
+    ext = dvp.dvp_forward(sub.z_train, sub.z_infer, sub.ids, lr, lse_full=True, safe_bits=True)
+    torch.cuda.synchronize()
+    bits = parity.compare_workload(sub, lr, ext.train, ext.infer, ext.row_flags, None, threads=16,
+                                   bits=(ext.train, ext.infer)).result()
+    assert bits["ok"] and bits["membership_rows_checked"] == 2 * len(sel), bits
+    print("rho %g: %d rows, logp err %.2e, gradient at %.3f of its bound (raw %.2e), %d rows with the sampled token "
+          "pruned, %d tokens within 1e-6 of the ideal threshold" %
+          (rho, out["rows_checked"], out["logp_max_abs_err"], out["grad_worst_ratio_to_bound"],
+           out["grad_raw_max_abs_err"], out["rows_sampled_token_pruned_train"],
+           out["band_tokens_train"] + out["band_tokens_infer"]))
+    return out, res
+
+
+def test_config1_full_size_every_row(dvp):
+    wl = workloads.make_rows(1, device="cuda")            # 2048 x 32000 bf16, thousands of safe tokens per row
+    out, _ = _full_size_check(dvp, wl, 1e-4, None)
+    assert out["rows_checked"] == 2048
+
+
+def test_config2_full_size_one_row_in_eight(dvp):
     wl = workloads.make_rows(2, device="cuda")            # 8192 x 151936 bf16
     n, v = wl.z_train.shape
-    rng = np.random.default_rng(0)
-    forced = torch.nonzero(wl.forced_rows).flatten().cpu().numpy()
-    rows = np.unique(np.concatenate([[0, 1, n - 1], rng.choice(n, 120, replace=False),
-                                     rng.choice(forced, 24, replace=False)]))
-    for rho in (1e-4, 0.0):
-        st = _run_case(dvp, wl, rho, backward=True, bits=False, lse_full=(rho == 0.0), rows=rows)
-        res = st["result"]
+    rows = np.arange(0, n, 8)                             # 1024 rows; every fifth of them has a forced (uniform) token
+    forced = wl.forced_rows.cpu().numpy()[rows]
+    assert forced.sum() >= 50
+    for rho in (1e-4, math.exp(-13.0), 0.0):
+        out, res = _full_size_check(dvp, wl, rho, rows)
+        assert out["rows_checked"] == 1024
         # any-size properties on every row
         cnt = res.train.safe_count
         assert int(cnt.min()) >= 1 and int(cnt.max()) <= v
@@ -340,6 +373,26 @@ def test_full_size_large_vocab_sampled_rows(dvp):
         assert torch.all(res.train.logp[ys] <= 0)
         if rho == 0.0:
             assert torch.all(cnt == v)
+        else:
+            assert out["rows_sampled_token_pruned_train"] >= forced.sum() - 2
+    del wl
+    torch.cuda.empty_cache()
+
+
+def test_config3_full_size_every_threshold(dvp):
+    """The workload the headline figure is quoted on (32768 x 151936 bf16), at each of its four thresholds:
+    2048 rows of the full-size call against the oracle, and nested safe sets across the thresholds."""
+    wl = workloads.make_rows(3, device="cuda")
+    n, v = wl.z_train.shape
+    rows = np.arange(0, n, 16)
+    counts = {}
+    for rho in (1e-2, 1e-4, 1e-6, 0.0):
+        out, res = _full_size_check(dvp, wl, rho, rows)
+        assert out["rows_checked"] == 2048
+        counts[rho] = res.train.safe_count.clone()
+        del res
+    assert torch.all(counts[1e-2] <= counts[1e-4]) and torch.all(counts[1e-4] <= counts[1e-6])   # Def. 5.1: nested in rho
+    assert torch.all(counts[0.0] == v)
     del wl
     torch.cuda.empty_cache()
 

@@ -265,6 +265,84 @@ def test_full_size_sampled_rows(dvp):
     torch.cuda.empty_cache()
 
 
+def test_full_size_every_row_forward_and_rows_of_dw(dvp):
+    """configs[4] at full size, the oracle over EVERY token row of the training side (fp64 logits in chunks
+    of 1024 rows: a BLAS product, then the row oracle): the forward outputs of all 16384 rows, dH on 256
+    sampled rows, and 64 rows of dW element by element -- a row of dW sums dz_ik H_i over every token row i,
+    so it sees the accumulation over the row blocks and the sampled-token launches.  The 64 vocabulary rows
+    are the 16 most often sampled tokens and 48 random ones."""
+    wl = workloads.make_lmhead(device="cuda")
+    n, d = wl.hidden.shape
+    v = wl.w_train.shape[0]
+    lr = dvp.log_rho(1e-4)
+    res = dvp.dvp_fused_lmhead(wl.hidden, wl.w_train, wl.w_infer, wl.ids, wl.grad_out, lr)
+    torch.cuda.synchronize()
+    ids_all = wl.ids.cpu().numpy()
+    g_all = wl.grad_out.cpu().numpy().astype(np.float64)
+    rng = np.random.default_rng(7)
+    top = np.argsort(-np.bincount(ids_all, minlength=v))[:16]
+    cols = np.unique(np.concatenate([top, rng.choice(v, 48, replace=False)]))
+    dh_rows = np.sort(rng.choice(n, 256, replace=False))
+    W64 = wl.w_train.cpu().double().numpy()
+    absW = np.abs(W64)
+    H64_all = wl.hidden.cpu().double().numpy()
+    dz_cols = np.empty((n, len(cols)))
+    soft_cols = np.empty((n, len(cols)))
+    band_rows = 0
+    worst_h = 0.0
+
+    class Sub:
+        lse_full = None
+
+    chunk = 1024
+    for r0 in range(0, n, chunk):
+        r1 = min(n, r0 + chunk)
+        z = H64_all[r0:r1] @ W64.T
+        o = orc.rows(z, ids_all[r0:r1], np.float32(lr), grad_out=g_all[r0:r1], want_dz=True, band=BAND, threads=16)
+        del z
+        sub = Sub()
+        for k in ("logp", "row_max", "lse_safe", "safe_count"):
+            setattr(sub, k, getattr(res.train, k)[r0:r1])
+        same = _check_side("train rows %d..%d" % (r0, r1), sub, o, o)
+        band_rows += int((~same).sum())
+        flags = res.row_flags[r0:r1].cpu().numpy()
+        np.testing.assert_array_equal((flags & 1)[same], o["y_in_safe"][same])
+        soft = np.abs(o["dz"])                     # the part of dz that passes through bf16: every token but the sampled one
+        safe_rows = np.nonzero(o["y_in_safe"])[0]
+        soft[safe_rows, ids_all[r0:r1][safe_rows]] = 0.0
+        dz_cols[r0:r1] = o["dz"][:, cols]
+        soft_cols[r0:r1] = soft[:, cols]
+        # a row whose sampled token changed sides inside the band has another gradient altogether: leave it out of dW's reference
+        dz_cols[r0:r1][~same] = np.nan
+        mine = dh_rows[(dh_rows >= r0) & (dh_rows < r1)] - r0
+        mine = mine[same[mine]]
+        if len(mine):
+            ref = o["dz"][mine] @ W64
+            bound = 2.0 ** -8 * (soft[mine] @ absW) + 1e-5 + 2.0 ** -20 * np.abs(ref)
+            got = res.d_hidden[torch.as_tensor(mine + r0, device="cuda")].cpu().double().numpy()
+            worst_h = max(worst_h, float((np.abs(got - ref) / bound).max()))
+            assert np.abs(got - ref).max() <= 2e-3
+        del o, soft
+    assert worst_h <= 1.0, "dH error is %.2f x its bound" % worst_h
+    assert band_rows <= 8                           # sampled tokens within 2e-4 of their threshold are rare
+    assert not np.isnan(dz_cols).any() or band_rows > 0
+    if np.isnan(dz_cols).any():                     # such a row: compare dW without it on both sides is not possible; require none in these columns
+        bad = np.isnan(dz_cols).any(axis=1)
+        dz_cols[bad] = 0.0
+        pytest.skip("a sampled token sits inside the membership band: dW has no unique reference")
+    ref_w = dz_cols.T @ H64_all
+    bound_w = 2.0 ** -7 * (soft_cols.T @ np.abs(H64_all)) + 1e-5 + 2.0 ** -20 * np.abs(ref_w)
+    got_w = res.d_w[torch.as_tensor(cols, device="cuda")].cpu().double().numpy()
+    err = np.abs(got_w - ref_w)
+    print("dW rows: %.3f of the bound, max abs error %.2e (largest entry %.2e); dH %.3f of its bound" %
+          ((err / bound_w).max(), err.max(), np.abs(ref_w).max(), worst_h))
+    assert (err / bound_w).max() <= 1.0, "dW error is %.2f x its bound" % (err / bound_w).max()
+    assert err.max() <= 2e-3
+    assert np.abs(ref_w).max() > 100 * np.median(bound_w)     # the bound is not vacuous
+    del wl, res
+    torch.cuda.empty_cache()
+
+
 def test_padded_strides_and_out_of_range_ids(dvp):
     """Row strides larger than the hidden size, and sampled ids outside [0, V): flagged per row,
     NaN log-probs, zero gradient contribution, nothing else disturbed."""

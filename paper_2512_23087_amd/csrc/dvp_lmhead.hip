@@ -51,7 +51,7 @@ constexpr int kWaveStageBytes = kPipeLdsBytes / kGemmWaves;   // 16 KB: a wavefr
 static_assert(kWaveStageBytes == MI * 32 * NI * 32 * 2, "epilogue staging assumes one bf16 block per wavefront");
 constexpr int kCopiesPerWave = BM * (BK / 8) / kWave / kGemmWaves;   // 1 KB wavefront copies per operand tile and wavefront
 static_assert(BM == BN, "the operand tiles share one copy schedule");
-constexpr int kRowBlock = 8192;                 // token rows whose masked exponentials are held at a time
+constexpr int kRowBlock = 8192;                 // token rows whose logits and masked exponentials are held at a time
 
 __device__ __forceinline__ int float_to_ordered(float f)
 {
@@ -93,11 +93,17 @@ struct GemmArgs {
 // dynamic LDS: the operand tiles (dead by now) and, behind them, the scratch of
 // pass B's sums.
 // ---------------------------------------------------------------------------
+// STORE_Z: the tile's logits are also stored as fp32, row-major in Z [rows of the launch, ldz]: the
+// statistics at the threshold are then taken from them by a streaming kernel instead of a second
+// pass of the product (re-reading a row block's logits costs a fraction of recomputing them).
+template <bool STORE_Z>
 struct EpiMax {
     static constexpr bool kUsesTileLds = false;
     static constexpr bool kRowMap = false;
     RowStats st;
     const int64_t *ids;
+    float *Z;
+    int64_t ldz;
     __device__ __forceinline__ void operator()(const GemmArgs &g, f32x16 (&acc)[MI][NI], int r0, int c0, int lane, uint8_t *, int, int) const
     {
 #pragma unroll
@@ -115,6 +121,9 @@ struct EpiMax {
                     if (col < g.N) {
                         v = fmaxf(v, z);
                         if (row_ok && (int64_t)col == y) st.zy[row] = z;
+                        if constexpr (STORE_Z) {
+                            if (row_ok) __builtin_nontemporal_store(z, Z + (int64_t)row * ldz + col);
+                        }
                     }
                 }
 #pragma unroll
@@ -724,6 +733,112 @@ __global__ void after_max_kernel(RowStats st, int n, float log_rho)
     }
 }
 
+// A row's outputs and gradient factors from its sums over the safe set (s), over all tokens (f) and its
+// safe-set size (c).  i indexes m and tau, w everything else (they differ for a gathered subset of rows).
+__device__ __forceinline__ void finish_row(const RowStats &st, const SideOut &out, const int64_t *ids, const float *grad_out,
+                                           uint8_t *row_flags, int i, int w, int vocab, int side, int unit_grad, float s,
+                                           float f, int c)
+{
+    const float m = st.m[i], tau = st.tau[i];
+    const float log_s = logf(s);
+    const int64_t y = ids[w];
+    const bool y_ok = y >= 0 && y < (int64_t)vocab;
+    const float zy = st.zy[w];
+    const bool y_safe = y_ok && zy >= tau;
+    if (side == 0) {
+        // unit_grad: the factors of a gradient still to come, q / g and s / g (Prop. 5.4 is linear in g)
+        const float c_i = !y_safe ? 0.0f : (unit_grad ? 1.0f : (grad_out ? grad_out[w] : 0.0f));
+        st.coef[w] = c_i != 0.0f ? c_i * (1.0f - __expf(zy - m) / s) : 0.0f;
+        st.scale[w] = -c_i / s;
+    }
+    if (out.row_max) out.row_max[w] = m;
+    if (out.lse_safe) out.lse_safe[w] = m + log_s;
+    if (out.lse_full) out.lse_full[w] = m + logf(f);
+    if (out.safe_count) out.safe_count[w] = c;
+    if (out.logp)
+        out.logp[w] = !y_ok ? __uint_as_float(0x7fc00000u) : (y_safe ? (zy - m) - log_s : -INFINITY);
+    if (row_flags) {
+        uint32_t fl = side == 0 ? (y_ok ? 0u : (uint32_t)DVP_ROW_ID_OUT_OF_RANGE) : row_flags[w];
+        if (y_safe) fl |= side == 0 ? DVP_ROW_Y_IN_TRAIN_SAFE : DVP_ROW_Y_IN_INFER_SAFE;
+        row_flags[w] = (uint8_t)fl;
+    }
+}
+
+// The statistics at the threshold from a row block's stored logits (Def. 5.1 / 5.2), one workgroup per
+// token row, one streaming pass: safe-set size, masked sum (and the full sum when lse_full is wanted),
+// the side's outputs and the gradient factors; WRITE_E also stores the row's masked exponentials
+// E_ik = [z_ik >= tau_i] exp(z_ik - m_i) as bf16 with a zero at the sampled token's column and zeros in
+// the padding columns (they pad the K dimension of the dH product); WRITE_BITS the membership bitmask.
+// Every thread owns fixed columns and the partial sums are combined in a fixed order: run-to-run identical.
+constexpr int kZRowThreads = 512;
+struct ZRowArgs {
+    const float *Z;          // [rows, ldz] fp32 logits of the block
+    int64_t ldz;
+    RowStats st;             // m, tau, zy of the block's rows (index 0 = first row of the block)
+    SideOut out;             // output pointers, already offset to the block's first row
+    const int64_t *ids;
+    const float *grad_out;
+    uint8_t *row_flags;
+    uint16_t *E;             // WRITE_E: [rows, ld_e] bf16
+    int64_t ld_e;
+    uint32_t *bits;          // WRITE_BITS: [rows, bits_ld]
+    int64_t bits_ld;
+    int vocab, v_pad, side, unit_grad;
+};
+
+template <bool WRITE_E, bool WRITE_BITS>
+__global__ __launch_bounds__(kZRowThreads) void lm_rows_from_z_kernel(const ZRowArgs a)
+{
+    constexpr int NW = kZRowThreads / kWave;
+    __shared__ float lds_f[2 * NW];
+    __shared__ int lds_i[NW];
+    const int i = blockIdx.x, tid = threadIdx.x;
+    const float m = a.st.m[i], tau = a.st.tau[i];
+    const bool want_full = a.out.lse_full != nullptr;
+    int64_t y = -1;
+    if constexpr (WRITE_E) y = a.ids[i];
+    const u32x4 *zrow = (const u32x4 *)(a.Z + (int64_t)i * a.ldz);
+    const int units = a.v_pad / 8;              // 8 columns at a time: two 16-byte loads, one 16-byte store
+    RowSums acc = {0.0f, 0.0f, 0};
+#pragma unroll 2
+    for (int u = tid; u < units; u += kZRowThreads) {
+        const u32x4 lo = __builtin_nontemporal_load(zrow + 2 * u), hi = __builtin_nontemporal_load(zrow + 2 * u + 1);
+        const float x[8] = {__uint_as_float(lo.x), __uint_as_float(lo.y), __uint_as_float(lo.z), __uint_as_float(lo.w),
+                            __uint_as_float(hi.x), __uint_as_float(hi.y), __uint_as_float(hi.z), __uint_as_float(hi.w)};
+        const int col0 = u * 8;
+        float e[8];
+        uint32_t mask = 0;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const bool in = col0 + k < a.vocab;   // the padding columns of Z hold nothing
+            const bool safe = in && x[k] >= tau;
+            float kept = 0.0f;
+            if (want_full) {
+                const float ex = in ? __expf(x[k] - m) : 0.0f;
+                acc.s_full += ex;
+                kept = safe ? ex : 0.0f;
+            } else if (safe) {
+                kept = __expf(x[k] - m);
+            }
+            acc.s_safe += kept;
+            acc.count += safe ? 1 : 0;
+            mask |= (safe ? 1u : 0u) << k;
+            e[k] = (int64_t)(col0 + k) == y ? 0.0f : kept;
+        }
+        if constexpr (WRITE_E) {
+            const u32x4 v = {pack_bf16x2(e[0], e[1]), pack_bf16x2(e[2], e[3]), pack_bf16x2(e[4], e[5]), pack_bf16x2(e[6], e[7])};
+            __builtin_nontemporal_store(v, (u32x4 *)(a.E + (int64_t)i * a.ld_e + col0));
+        }
+        if constexpr (WRITE_BITS) {
+            if (u < 4 * a.bits_ld) ((uint8_t *)(a.bits + (int64_t)i * a.bits_ld))[u] = (uint8_t)mask;
+        }
+    }
+    acc = block_sums<kZRowThreads>(acc, lds_f, lds_i);
+    if (tid == 0)
+        finish_row(a.st, a.out, a.ids, a.grad_out, a.row_flags, i, i, a.vocab, a.side, a.unit_grad, acc.s_safe, acc.s_full,
+                   acc.count);
+}
+
 // Reduce the per-tile partials and write the side's outputs.  A workgroup takes 32 rows; the
 // column tiles are cut into 8 contiguous segments, each summed in tile order by one thread per
 // row, and the 8 segment sums are combined in segment order: a fixed order, run-to-run identical.
@@ -757,30 +872,7 @@ __global__ __launch_bounds__(kAfterRows * kAfterSegs) void after_sum_kernel(RowS
     if (seg != 0 || i >= n_rows) return;
 #pragma unroll
     for (int q = 1; q < kAfterSegs; ++q) { s += seg_s[q][r]; f += seg_f[q][r]; c += seg_c[q][r]; }
-    const float m = st.m[i], tau = st.tau[i];
-    const int w = rowmap ? rowmap[i] : i;            // the row everything but m, tau and the partials is indexed by
-    const float log_s = logf(s);
-    const int64_t y = ids[w];
-    const bool y_ok = y >= 0 && y < (int64_t)vocab;
-    const float zy = st.zy[w];
-    const bool y_safe = y_ok && zy >= tau;
-    if (side == 0) {
-        // unit_grad: the factors of a gradient still to come, q / g and s / g (Prop. 5.4 is linear in g)
-        const float c_i = !y_safe ? 0.0f : (unit_grad ? 1.0f : (grad_out ? grad_out[w] : 0.0f));
-        st.coef[w] = c_i != 0.0f ? c_i * (1.0f - __expf(zy - m) / s) : 0.0f;
-        st.scale[w] = -c_i / s;
-    }
-    if (out.row_max) out.row_max[w] = m;
-    if (out.lse_safe) out.lse_safe[w] = m + log_s;
-    if (out.lse_full) out.lse_full[w] = m + logf(f);
-    if (out.safe_count) out.safe_count[w] = c;
-    if (out.logp)
-        out.logp[w] = !y_ok ? __uint_as_float(0x7fc00000u) : (y_safe ? (zy - m) - log_s : -INFINITY);
-    if (row_flags) {
-        uint32_t fl = side == 0 ? (y_ok ? 0u : (uint32_t)DVP_ROW_ID_OUT_OF_RANGE) : row_flags[w];
-        if (y_safe) fl |= side == 0 ? DVP_ROW_Y_IN_TRAIN_SAFE : DVP_ROW_Y_IN_INFER_SAFE;
-        row_flags[w] = (uint8_t)fl;
-    }
+    finish_row(st, out, ids, grad_out, row_flags, i, rowmap ? rowmap[i] : i, vocab, side, unit_grad, s, f, c);
 }
 
 // Sampled-token part of dW (Prop. 5.4): dW[y_i, :] += q_i H_i for the `rows` token rows of a block, in
@@ -880,7 +972,7 @@ struct LmLayout {
     size_t total;
     size_t off_i32[2], off_zy[2], off_m[2], off_tau[2], off_coef, off_scale;
     size_t off_ps[2], off_pf[2], off_pc[2];
-    size_t off_ht, off_wt, off_e, off_et;
+    size_t off_ht, off_wt, off_e, off_et, off_z;
     int block_pad, v_pad, col_tiles;
 };
 
@@ -902,8 +994,9 @@ static LmLayout lm_layout(int64_t n, int64_t d, int64_t v, bool dense_buffers = 
     }
     L.off_coef = take(n * 4);
     L.off_scale = take(n * 4);
-    L.off_ht = L.off_wt = L.off_e = L.off_et = 0;
+    L.off_ht = L.off_wt = L.off_e = L.off_et = L.off_z = 0;
     if (dense_buffers) {
+        L.off_z = take((size_t)L.block_pad * L.v_pad * 4);      // fp32 logits of one row block
         L.off_ht = take((size_t)d * L.block_pad * 2);
         L.off_wt = take((size_t)d * L.v_pad * 2);
         L.off_e = take((size_t)L.block_pad * L.v_pad * 2);
@@ -1099,22 +1192,53 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
         }
         hipLaunchKernelGGL(init_stats_kernel, dim3(nb), dim3(tb), 0, stream, st, rows);
         DVP_CHECK_LAUNCH();
+        const int64_t lde = L.v_pad, ldet = L.block_pad;
+        if (!stats_only_ws) {
+            // One pass of the product: row maxima, and the block's logits kept as fp32; the sums at the
+            // threshold (and E) are then read off the stored logits.  Re-reading them costs a few percent
+            // of what producing them a second time would.
+            float *Z = (float *)(ws + L.off_z);
+            const EpiMax<true> em{st, ids + r0, Z, (int64_t)L.v_pad};
+            if ((bytes ? launch_gemm<EpiMax<true>, false, true>(g, em, stream) : launch_gemm<EpiMax<true>, false>(g, em, stream)) !=
+                hipSuccess)
+                return DVP_ERR_HIP;
+            hipLaunchKernelGGL(after_max_kernel, dim3(nb), dim3(tb), 0, stream, st, rows, p->log_rho);
+            DVP_CHECK_LAUNCH();
+            ZRowArgs za;
+            za.Z = Z; za.ldz = L.v_pad; za.st = st; za.out = o; za.ids = ids + r0;
+            za.grad_out = grad_out ? grad_out + r0 : nullptr; za.row_flags = row_flags ? row_flags + r0 : nullptr;
+            za.E = E; za.ld_e = lde; za.bits = bits; za.bits_ld = bits_ld;
+            za.vocab = v; za.v_pad = L.v_pad; za.side = s; za.unit_grad = phase == LM_FORWARD_SAVE ? 1 : 0;
+            const dim3 zg((unsigned)rows), zb(kZRowThreads);
+            if (write_e) {
+                if (bits) hipLaunchKernelGGL((lm_rows_from_z_kernel<true, true>), zg, zb, 0, stream, za);
+                else      hipLaunchKernelGGL((lm_rows_from_z_kernel<true, false>), zg, zb, 0, stream, za);
+                DVP_CHECK_LAUNCH();
+                // E^T for the dW product (zero padded to a whole row tile)
+                const int rows_pad = (rows + BM - 1) / BM * BM;
+                hipLaunchKernelGGL(transpose_bf16_kernel, dim3((L.v_pad + kTrTile - 1) / kTrTile, (rows_pad + kTrTile - 1) / kTrTile),
+                                   dim3(kTrThreads), 0, stream, (const uint16_t *)E, lde, Et, ldet, rows, L.v_pad, rows_pad,
+                                   (const float *)nullptr);
+            } else {
+                if (bits) hipLaunchKernelGGL((lm_rows_from_z_kernel<false, true>), zg, zb, 0, stream, za);
+                else      hipLaunchKernelGGL((lm_rows_from_z_kernel<false, false>), zg, zb, 0, stream, za);
+            }
+            DVP_CHECK_LAUNCH();
+            return DVP_OK;
+        }
+        // No room for a block's logits (the caller vouched for the statistics part of the workspace only):
+        // the logits are produced twice, row maxima first, then the sums at the threshold per column tile.
         if (bytes) {
-            if (launch_gemm<EpiMax, false, true>(g, EpiMax{st, ids + r0}, stream) != hipSuccess) return DVP_ERR_HIP;
+            if (launch_gemm<EpiMax<false>, false, true>(g, EpiMax<false>{st, ids + r0, nullptr, 0}, stream) != hipSuccess) return DVP_ERR_HIP;
         } else {
-            if (launch_gemm<EpiMax, false>(g, EpiMax{st, ids + r0}, stream) != hipSuccess) return DVP_ERR_HIP;
+            if (launch_gemm<EpiMax<false>, false>(g, EpiMax<false>{st, ids + r0, nullptr, 0}, stream) != hipSuccess) return DVP_ERR_HIP;
         }
         hipLaunchKernelGGL(after_max_kernel, dim3(nb), dim3(tb), 0, stream, st, rows, p->log_rho);
         DVP_CHECK_LAUNCH();
-        // pass B in the build that matches the side: 8-bit operands or bf16, with E or not, with the bitmask or not
         hipError_t eb;
-        const int64_t lde = L.v_pad, ldet = L.block_pad;
         if (bytes) {
             eb = bits ? launch_gemm<EpiSum<false, true>, true, true>(g, EpiSum<false, true>{st, rows, nullptr, nullptr, nullptr, 0, 0, bits, bits_ld}, stream)
                       : launch_gemm<EpiSum<false>, true, true>(g, EpiSum<false>{st, rows, nullptr, nullptr, nullptr, 0, 0, nullptr, 0}, stream);
-        } else if (write_e) {
-            eb = bits ? launch_gemm<EpiSum<true, true>, true>(g, EpiSum<true, true>{st, rows, ids + r0, E, Et, lde, ldet, bits, bits_ld}, stream)
-                      : launch_gemm<EpiSum<true>, true>(g, EpiSum<true>{st, rows, ids + r0, E, Et, lde, ldet, nullptr, 0}, stream);
         } else {
             eb = bits ? launch_gemm<EpiSum<false, true>, true>(g, EpiSum<false, true>{st, rows, nullptr, nullptr, nullptr, 0, 0, bits, bits_ld}, stream)
                       : launch_gemm<EpiSum<false>, true>(g, EpiSum<false>{st, rows, nullptr, nullptr, nullptr, 0, 0, nullptr, 0}, stream);
@@ -1167,6 +1291,18 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
         return DVP_OK;
     };
 
+    // a side's forward without E: row block by row block where the logits are stored (one block's worth of
+    // room), all rows at once where they are produced twice
+    auto forward_all = [&](int side) -> dvp_status {
+        if (stats_only_ws) return forward(side, 0, n, false, st);
+        for (int r0 = 0; r0 < n; r0 += kRowBlock) {
+            const int rows = (n - r0) < kRowBlock ? (n - r0) : kRowBlock;
+            const dvp_status rs = forward(side, r0, rows, false, st);
+            if (rs != DVP_OK) return rs;
+        }
+        return DVP_OK;
+    };
+
     if (phase == LM_BACKWARD_SAVED) {
         if ((rc = transpose_w()) != DVP_OK) return rc;
         float *coef = (float *)(ws + L.off_coef), *scale = (float *)(ws + L.off_scale);
@@ -1187,7 +1323,7 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
             if ((rc = forward(0, r0, rows, true, st)) != DVP_OK) return rc;
         }
     } else if (!grad_out) {
-        if ((rc = forward(0, 0, n, false, st)) != DVP_OK) return rc;
+        if ((rc = forward_all(0)) != DVP_OK) return rc;
     } else {
         // training side with gradient, in blocks of kRowBlock token rows
         if ((rc = transpose_w()) != DVP_OK) return rc;
@@ -1198,7 +1334,7 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
         }
     }
     if (infer_side) {
-        if ((rc = forward(1, 0, n, false, st)) != DVP_OK) return rc;
+        if ((rc = forward_all(1)) != DVP_OK) return rc;
     }
 #undef DVP_CHECK_LAUNCH
     return DVP_OK;
@@ -1310,8 +1446,8 @@ static dvp_status run_lmhead_lists(const dvp_lmhead_params *p, const void *hidde
                 hipSuccess)
                 return DVP_ERR_HIP;
         } else {
-            if ((bytes ? launch_gemm<EpiMax, false, true>(g, EpiMax{st, ids}, stream)
-                       : launch_gemm<EpiMax, false>(g, EpiMax{st, ids}, stream)) != hipSuccess)
+            if ((bytes ? launch_gemm<EpiMax<false>, false, true>(g, EpiMax<false>{st, ids, nullptr, 0}, stream)
+                       : launch_gemm<EpiMax<false>, false>(g, EpiMax<false>{st, ids, nullptr, 0}, stream)) != hipSuccess)
                 return DVP_ERR_HIP;
         }
         hipLaunchKernelGGL(after_max_kernel, dim3(nb), dim3(tb), 0, stream, st, n, p->log_rho);

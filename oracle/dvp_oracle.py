@@ -40,10 +40,11 @@ def build(force: bool = False) -> Path:
 def _load():
     global _lib
     if _lib is None:
-        alt = os.environ.get("DVP_ORACLE_SRC")   # tests plant mistakes in a copy of the C source
-        if alt:
+        alt = os.environ.get("DVP_ORACLE_SRC")   # tests plant mistakes in a copy of the C source,
+        if alt:                                  # or build it with other flags (DVP_ORACLE_CFLAGS: sanitizers)
             out = Path(alt).with_suffix(".so")
-            subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-ffp-contract=off",
+            extra = os.environ.get("DVP_ORACLE_CFLAGS", "").split()
+            subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-ffp-contract=off", *extra,
                                    "-o", str(out), alt, "-lm", "-lpthread"])
             path = out
         else:

@@ -1454,7 +1454,7 @@ static dvp_status run_lmhead_lists(const dvp_lmhead_params *p, const void *hidde
         DVP_CHECK_LAUNCH();
         if (one_pass) {
             LmCandArgs c;
-            c.cand = cand; c.cand_count = cand_cur; c.m = st.m; c.tau = st.tau; c.zy = st.zy;
+            c.cand = cand; c.cand_count = cand_cur; c.m = st.m; c.tau = st.tau; c.zy = st.zy; c.zy_low = zy_low;
             c.ids = ids; c.grad_out = grad_out; c.out = o; c.row_flags = row_flags;
             c.coef = st.coef; c.scale = st.scale;
             c.entries = (s == 0 && lists) ? entries : nullptr; c.list_cap = list_cap;

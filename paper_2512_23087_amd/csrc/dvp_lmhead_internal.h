@@ -36,6 +36,7 @@ struct LmCandArgs {
     const dvp_grad_entry *cand;   // [n, kLmCandMax] (token, logit) in arrival order
     const int32_t *cand_count;    // [n] candidates appended (may exceed kLmCandMax: then the side is redone)
     const float *m, *tau, *zy;    // [n] row maximum, threshold, the sampled token's logit
+    const float *zy_low;          // [n] the bound below zy that the candidates were collected with
     const int64_t *ids;
     const float *grad_out;        // [n] or null; side 0 only
     SideOut out;                  // logp, row_max, lse_safe, safe_count (required); the rest unused

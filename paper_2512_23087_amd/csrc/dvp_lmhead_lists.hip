@@ -273,8 +273,15 @@ __global__ __launch_bounds__(kThreads) void lm_candidates_finish_kernel(const Lm
     __shared__ int n_safe;
     const int i = blockIdx.x, tid = threadIdx.x;
     const int nc = a.cand_count[i];
-    if (tid == 0) a.overflow[i] = nc > kLmCandMax ? 1 : 0;
-    if (nc > kLmCandMax) return;                       // this row goes through a second pass over its logits
+    // The candidates are a superset of the safe set only if the bound they were collected with really
+    // lies at or below the sampled token's logit as the matrix cores delivered it.  It is built to (twice
+    // the fp32 accumulation bound below a plain dot product); should it ever fail, the row takes the
+    // second pass over its logits like a row with too many candidates, instead of losing safe tokens.
+    const int64_t y0 = a.ids[i];
+    const bool bound_broken = y0 >= 0 && y0 < (int64_t)a.v && a.zy[i] < a.zy_low[i];
+    const bool redo = nc > kLmCandMax || bound_broken;
+    if (tid == 0) a.overflow[i] = redo ? 1 : 0;
+    if (redo) return;                                  // this row goes through a second pass over its logits
     const float m = a.m[i], tau = a.tau[i];
     const dvp_grad_entry *cand = a.cand + (int64_t)i * kLmCandMax;
     int pow2 = 1;

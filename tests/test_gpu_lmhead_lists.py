@@ -127,6 +127,19 @@ def test_flat_rows_among_peaked_ones(dvp):
     assert res.second_pass.tolist() == [0, 0]              # 900 tokens: whatever the bound, the candidates fit
 
 
+def test_large_magnitude_hidden_states_never_break_the_sampled_token_bound(dvp):
+    """The one-pass route collects candidates above a bound built to lie below the sampled token's logit as
+    the matrix cores deliver it; a row where it did not would be sent through the second pass.  With logits
+    in the hundreds (hidden states x 100 and x 250) no row is: the second-pass counters stay at zero and
+    every output still matches the oracle."""
+    for scale, d in ((100.0, 512), (250.0, 128)):
+        wl = workloads.make_lmhead(device="cuda", n=300, d=d, v=3000, hidden_scale=scale)
+        res, fwd, listed = _run(dvp, wl, 1e-4, 64, abs_check=False)
+        assert np.abs(fwd["row_max"]).max() > 100.0
+        assert res.second_pass.tolist() == [0, 0]
+        assert listed.sum() > 100
+
+
 @pytest.mark.parametrize("n,d,v,cap", [(1, 64, 3, 4), (2, 64, 1, 1), (257, 192, 257, 300), (33, 64, 513, 1024),
                                        (700, 64, 900, 1000), (300, 64, 1500, 1000)])
 def test_shapes_and_long_lists(dvp, n, d, v, cap):

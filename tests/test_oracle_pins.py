@@ -84,11 +84,10 @@ def test_masked_lse_against_scipy_and_torch(rho):
     np.testing.assert_array_equal(out["tau"], thr.astype(np.float64))
     lse_m = scipy.special.logsumexp(z64, axis=1, b=mask.astype(np.float64))
     np.testing.assert_allclose(out["lse_safe"], lse_m, rtol=0, atol=1e-12)
-    # masked-logit form (Sec. 5.5): logits below the threshold go to -inf, then log-softmax
-    zt = torch.from_numpy(z64)
-    masked = torch.where(zt < torch.from_numpy(thr.astype(np.float64))[:, None],
-                         torch.tensor(-math.inf, dtype=torch.float64), zt)
-    lsm = torch.log_softmax(masked, dim=-1).numpy()
+    # Prop. 5.6 part 1: the constrained policy is the softmax of the logits with -inf outside the safe set
+    outside = np.full_like(z64, -np.inf)
+    outside[mask] = z64[mask]
+    lsm = scipy.special.log_softmax(outside, axis=1)
     want = lsm[np.arange(len(ids)), ids]
     np.testing.assert_allclose(out["logp"], want, rtol=0, atol=1e-12)  # -inf == -inf passes
     np.testing.assert_array_equal(out["y_in_safe"].astype(bool), mask[np.arange(len(ids)), ids])
@@ -296,15 +295,20 @@ def test_gradient_against_autograd_masked_log_softmax():
     g = rng.standard_normal(len(ids))
     lr = orc.log_rho_f32(1e-2)
     out = orc.rows(z, ids, lr, grad_out=g, want_dz=True, want_flags=True)
+    # Def. 5.2 in closed form, row by row: log pi_mp(y) = z_y - log sum_{k in V_S} e^{z_k}, with V_S a fixed
+    # index set built here from Def. 5.1 (numpy, independent of the oracle); autograd differentiates that.
     zt = torch.from_numpy(z.astype(np.float64)).requires_grad_(True)
-    with torch.no_grad():
-        thr = torch.from_numpy((z.max(axis=1) + lr).astype(np.float32).astype(np.float64))[:, None]
-        pruned = zt < thr
-    masked = torch.where(pruned, torch.tensor(-math.inf, dtype=torch.float64), zt)
-    lp = torch.log_softmax(masked, dim=-1)[torch.arange(len(ids)), torch.from_numpy(ids)]
-    keep = torch.from_numpy(out["y_in_safe"].astype(bool))
-    assert keep.any() and (~keep).any()
-    (lp[keep] * torch.from_numpy(g)[keep]).sum().backward()
+    tau = (z.max(axis=1) + lr).astype(np.float32).astype(np.float64)
+    loss = torch.zeros((), dtype=torch.float64)
+    rows_with_grad = 0
+    for i in range(len(ids)):
+        safe = np.nonzero(z[i].astype(np.float64) >= tau[i])[0]
+        if ids[i] not in safe:
+            continue                                    # probability zero: no term in the objective (Sec. 5.3)
+        rows_with_grad += 1
+        loss = loss + g[i] * (zt[i, ids[i]] - torch.logsumexp(zt[i, torch.from_numpy(safe)], dim=0))
+    assert 0 < rows_with_grad < len(ids)
+    loss.backward()
     want = zt.grad.numpy()
     np.testing.assert_allclose(out["dz"], want, rtol=0, atol=1e-12)   # rows with y pruned: all zero
 
@@ -393,15 +397,19 @@ def test_lmhead_oracle_against_autograd():
     W = wl.w_train.to(torch.float64).requires_grad_(True)
     z = H @ W.T
     np.testing.assert_allclose(out["z"], z.detach().numpy(), rtol=0, atol=1e-13)
-    with torch.no_grad():
-        m = z.max(dim=-1, keepdim=True).values
-        thr = (m + float(lr)).to(torch.float32).to(torch.float64)
-        pruned = z < thr
-    masked = torch.where(pruned, torch.tensor(-math.inf, dtype=torch.float64), z)
-    lp = torch.log_softmax(masked, dim=-1)[torch.arange(10), wl.ids]
-    keep = torch.from_numpy(out["y_in_safe"].astype(bool))
-    np.testing.assert_allclose(out["logp"][keep.numpy()], lp[keep].detach().numpy(), atol=1e-12)
-    (lp[keep] * torch.from_numpy(g)[keep]).sum().backward()
+    z_np = z.detach().numpy()
+    tau = (z_np.max(axis=1) + np.float64(lr)).astype(np.float32).astype(np.float64)
+    loss = torch.zeros((), dtype=torch.float64)
+    for i in range(10):                                 # Def. 5.2 in closed form over the fixed index set of Def. 5.1
+        safe = np.nonzero(z_np[i] >= tau[i])[0]
+        y = int(wl.ids[i])
+        assert (y in safe) == bool(out["y_in_safe"][i])
+        if y not in safe:
+            continue
+        lp_i = z[i, y] - torch.logsumexp(z[i, torch.from_numpy(safe)], dim=0)
+        assert abs(out["logp"][i] - lp_i.item()) <= 1e-12
+        loss = loss + g[i] * lp_i
+    loss.backward()
     np.testing.assert_allclose(out["d_hidden"], H.grad.numpy(), rtol=0, atol=1e-12)
     np.testing.assert_allclose(out["d_w"], W.grad.numpy(), rtol=0, atol=1e-12)
 
@@ -544,26 +552,33 @@ def test_entropy_against_scipy_and_closed_forms():
 # the finite-mask variant (Sec. 5.5 "Logit Masking Strategy", App. A item 3)
 # ---------------------------------------------------------------------------
 def _torch_finite_mask(z, ids, rho, mask_value, g):
-    """The variant written with torch operators: threshold and comparison in the tensor's own dtype,
-    a constant in place of the pruned logits, log-softmax over the whole row (in float64), autograd."""
-    zz = z.clone().requires_grad_(True)
-    with torch.no_grad():
-        m = zz.max(dim=-1, keepdim=True).values
-        if zz.dtype == torch.bfloat16:
-            # On the GPU, where the method runs, torch adds a Python scalar to a bf16 tensor in fp32 and
-            # rounds the sum; its CPU kernel rounds the scalar to bf16 first (observed: 8.375 + log(0.01)
-            # gives 3.78125 instead of 3.765625).  The GPU behaviour is the one followed, written out
-            # here; tests/test_gpu_finite_mask.py checks it against torch's own GPU add.
-            thr = (m.float() + torch.tensor(math.log(rho), dtype=torch.float32)).to(torch.bfloat16)
-        else:
-            thr = m + math.log(rho)
-        pruned = zz < thr
-    masked = torch.where(pruned, torch.tensor(mask_value, dtype=zz.dtype), zz)
-    lp = torch.log_softmax(masked.to(torch.float64), dim=-1)
-    picked = lp.gather(1, torch.as_tensor(ids).view(-1, 1)).squeeze(1)
+    """The variant from its closed form, row by row.  Every pruned logit counts as the constant `mask_value`
+    (Sec. 5.5), so with K the kept index set, decided in the tensor's own dtype (App. A item 3),
+        lse = log( sum_{k in K} e^{z_k} + (V - |K|) e^{mask_value} ),
+        log-prob of y = (z_y if y in K else mask_value) - lse,
+    evaluated in float64 and differentiated by autograd.  Returns (pruned flags, thresholds, log-probs, gradient)."""
+    n, v = z.shape
+    zz = z.clone().to(torch.float64).requires_grad_(True)
+    top = z.amax(dim=1)
+    if z.dtype == torch.bfloat16:
+        # On the GPU, where the method runs, torch adds a Python scalar to a bf16 tensor in fp32 and
+        # rounds the sum; its CPU kernel rounds the scalar to bf16 first (observed: 8.375 + log(0.01)
+        # gives 3.78125 instead of 3.765625).  The GPU behaviour is the one followed, written out
+        # here; tests/test_gpu_finite_mask.py checks it against torch's own GPU add.
+        thr = (top.float() + torch.tensor(math.log(rho), dtype=torch.float32)).to(torch.bfloat16)
+    else:
+        thr = top + math.log(rho)
+    kept = z >= thr[:, None]                            # comparison in the storage dtype
+    picked = []
+    for i in range(n):
+        idx = torch.nonzero(kept[i]).flatten()
+        const = torch.full((v - idx.numel(),), float(mask_value), dtype=torch.float64)
+        lse = torch.logsumexp(torch.cat([zz[i, idx], const]), dim=0)
+        y = int(ids[i])
+        picked.append((zz[i, y] if bool(kept[i, y]) else torch.tensor(float(mask_value), dtype=torch.float64)) - lse)
+    picked = torch.stack(picked)
     (picked * torch.as_tensor(g, dtype=torch.float64)).sum().backward()
-    return pruned.numpy(), thr.to(torch.float64).squeeze(1).numpy(), picked.detach().numpy(), \
-        zz.grad.to(torch.float64).numpy()
+    return (~kept).numpy(), thr.to(torch.float64).numpy(), picked.detach().numpy(), zz.grad.numpy()
 
 
 @pytest.mark.parametrize("dtype", [torch.float64, torch.float32, torch.bfloat16])

@@ -108,6 +108,16 @@ __device__ __forceinline__ void store_elem(bf16_t *p, float v)
 __device__ __forceinline__ float storage_rounded(float t, float) { return t; }
 __device__ __forceinline__ float storage_rounded(float t, bf16_t) { return bits_to_float(f32_to_bf16_rne(t) << 16); }
 
+// Asynchronous copy from global memory straight into LDS, no register staging: lane l moves the 16
+// bytes at gbase + voff (per lane) to LDS byte lds_addr + 16 l (gbase and lds_addr wavefront-uniform).
+// The compiler's wait-count bookkeeping does not see these copies: whoever reads the LDS bytes waits for
+// them explicitly (s_waitcnt vmcnt) first.
+__device__ __forceinline__ void copy16_to_lds(const void *gbase, uint32_t voff, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_addr), "v"(voff), "s"(gbase) : "memory");
+}
+
 // ---- wavefront reductions (all 64 lanes end with the result) ----
 __device__ __forceinline__ float wave_max(float v)
 {

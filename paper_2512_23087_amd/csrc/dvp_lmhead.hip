@@ -438,12 +438,6 @@ struct EpiStore {
 // issued into tile j's buffer and the first fragments of tile j+1 are fetched
 // while the matrix cores still have the last slice of tile j to do.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ void copy16_to_lds(const void *gbase, uint32_t voff, uint32_t lds_addr)
-{
-    // lane l: 16 bytes from gbase + voff (per lane) to LDS byte lds_addr + 16 l (lds_addr wavefront-uniform)
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :: "s"(lds_addr), "v"(voff), "s"(gbase) : "memory");
-}
 __device__ __forceinline__ void wait_copies_and_barrier()
 {
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");

@@ -27,6 +27,12 @@ namespace dvp {
 // the next, which overflows the register file.
 __device__ __forceinline__ void keep_packed(u32x4 &v) { asm volatile("" : "+v"(v)); }
 __device__ __forceinline__ int fresh(int v) { asm volatile("" : "+v"(v)); return v; }
+__device__ __forceinline__ bool opaque_true()
+{
+    int one;
+    asm volatile("s_mov_b32 %0, 1" : "=s"(one));
+    return one != 0;
+}
 
 // Register slot j of thread t holds vector (j * NT + t) of the row.  Slots
 // below NVFULL hold a whole vector in every thread of every row the
@@ -123,6 +129,7 @@ struct TaskState {
     uint32_t zy_raw;     // the sampled token's logit (stored form)
     uint32_t xt_raw;     // this thread's element of the ragged end (stored form), or -inf
     uint32_t flags;
+    bool dense_hint;     // the task before this one had more safe tokens than a list holds (see NL below)
 };
 
 // One task: everything one side of one row needs, from the registers.
@@ -134,10 +141,24 @@ struct TaskState {
 //   OVF                   the row is longer than the slots hold: vectors from NT * NVS on are
 //                         re-read from memory in every phase (all slots are then full, and both
 //                         tasks have the same type)
+//   NL                    slots of the next row that may be fetched ahead into LDS (lds_pf, NL * NT * 16
+//                         bytes): the LAST NL of its slots.  A densely written training row keeps every
+//                         register slot until its gradient vector is stored, so without this nothing
+//                         could be in flight during its sum phase, and the loads of the next row would
+//                         all be issued during the last phase, the last of them right before the next
+//                         task needs it.  With it those vectors are copied straight into LDS while the
+//                         sum phase runs and move to the registers at the end of the last phase; the
+//                         other slots are refilled from memory before them, so every load has been on
+//                         its way for a while when the phase ends.  Used when the task before was dense
+//                         (for a training row that is the same row's inference side, whose safe set is
+//                         about the same); rows with short safe sets free their slots early anyway.
+//   ALLSAFE               the build for log_rho = -inf (nothing is pruned: plain log-softmax and its
+//                         gradient): every token passes the threshold, so the per-token comparisons,
+//                         the counting and the selects are left out (the safe-set size is V)
 template <typename TS, int NVS, int NVFULL_S, typename TN, int NVN, int NVFULL_N, int NV, int NT, int EXTRAS,
-          bool CAN_BWD, bool OVF = false>
+          bool CAN_BWD, bool OVF = false, int NL = 0, bool ALLSAFE = false>
 __device__ __forceinline__ bool row_task(const RowArgs &a, TaskState &s, u32x4 (&r)[NV], float *lds_max,
-                                         float *lds_f, int *lds_i, int *lds_list_count)
+                                         float *lds_f, int *lds_i, int *lds_list_count, uint8_t *lds_pf = nullptr)
 {
     using TR = elem_traits<TS>;
     constexpr int EPV = TR::kPerVec;
@@ -148,6 +169,8 @@ __device__ __forceinline__ bool row_task(const RowArgs &a, TaskState &s, u32x4 (
     static_assert(NVS <= NV && NVN <= NV, "slots");
     static_assert(!CAN_BWD || PARTS == 1, "gradient rows are widened whole");
     static_assert(!OVF || (PARTS == 1 && NVFULL_S == NVS && NVS == NVN), "overflow builds: full slots, one type");
+    static_assert(NL <= NVN && (NL == 0 || (!OVF && CAN_BWD && NVS == NVN)), "slots fetched ahead into LDS: rows of one type that fit the registers");
+    constexpr int L0 = NVN - NL;           // first slot that can be fetched ahead
     constexpr int FIRST_OVF = NT * NVS;    // first vector that lives outside the registers (OVF)
     constexpr int OVF_BATCH = 4;           // vectors a thread has in flight while it walks that part
 
@@ -242,10 +265,38 @@ __device__ __forceinline__ bool row_task(const RowArgs &a, TaskState &s, u32x4 (
 
     // ---- threshold, membership, size, masked sum (Def. 5.1 / 5.2) ----
     const float tau = m + log_rho;   // one fp32 rounding
+
     float s_safe = 0.0f, s_full = 0.0f;
     float s_ent = 0.0f;              // sum over the safe set of exp(z - m) (z - m): entropy (EXTRAS builds)
     int wave_count = 0;              // wavefront-uniform: lanes are counted with scalar popcounts
     uint32_t any_mask = 0;           // bit j: some lane of this wavefront has a safe token in slot j
+    // A training row that is going to be written densely holds every slot until the gradient phase: the
+    // next row's first NL vectors per thread start their way into LDS now (workgroup-uniform decision).
+    [[maybe_unused]] bool ahead = false;
+    if constexpr (NL > 0) {
+        // (a task without gradient phase refills its slots during this phase: the same holds for it when
+        // the exponentials make the phase long, which is when the row before was dense)
+        ahead = !a.sparse_only && has_next && (ALLSAFE || s.dense_hint);
+        if (ahead) {
+            // this wavefront's earlier reads of these LDS bytes fed registers the max phase has consumed
+            const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+            const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)lds_pf + wave * 1024;
+            const uint8_t *src = (const uint8_t *)znext + wave * 1024;
+            const uint32_t lane_off = (uint32_t)(fresh(tid) & (kWave - 1)) * 16u;
+#pragma unroll
+            for (int j = L0; j < NVN; ++j) {
+                // (a lane past the end of the row copies nothing; its LDS bytes are not read either)
+                if (j < NVFULL_N || j * NT + fresh(tid) < nvec_n)
+                    copy16_to_lds(src + (size_t)j * NT * 16, lane_off, lds_base + (j - L0) * NT * 16);
+            }
+        }
+    }
+    // slot j of the next row out of LDS (padding where the row has ended, as load_slot gives it)
+    [[maybe_unused]] auto take_ahead = [&](int j, int t) {
+        u32x4 v = {elem_traits<TN>::kPadWord, elem_traits<TN>::kPadWord, elem_traits<TN>::kPadWord, elem_traits<TN>::kPadWord};
+        if (j < NVFULL_N || j * NT + t < nvec_n) v = *(const u32x4 *)(lds_pf + (size_t)(j - L0) * NT * 16 + (size_t)t * 16);
+        return v;
+    };
     if (has_next) {   // the next task's single elements, fetched early and left in stored form
         if (ny_ok) nzy_raw = load_raw(znext + ny);
         if (tid < tail_n) nxt_raw = load_raw(znext + (int64_t)nvec_n * EPV_N + tid);
@@ -274,10 +325,15 @@ __device__ __forceinline__ bool row_task(const RowArgs &a, TaskState &s, u32x4 (
             float x[EPP];
             unpack_part<TS, NT, NVFULL_S>(r[j], x, part, j, tid, nvec);
             const int before = wave_count;
+            if constexpr (!ALLSAFE) {
 #pragma unroll
-            for (int e = 0; e < EPP; ++e)
-                wave_count += __builtin_popcountll(__builtin_amdgcn_ballot_w64(x[e] >= tau));
-            const bool any_part = wave_count != before;
+                for (int e = 0; e < EPP; ++e)
+                    wave_count += __builtin_popcountll(__builtin_amdgcn_ballot_w64(x[e] >= tau));
+            }
+            // (ALLSAFE: always true, but through a scalar register the optimiser cannot see through, so
+            // that each slot keeps its own wavefront-uniform branch: as one straight block the 19 slots
+            // are widened together and the row no longer fits the registers)
+            const bool any_part = ALLSAFE ? opaque_true() : wave_count != before;
             any |= any_part;
             if (want_full) {
 #pragma unroll
@@ -289,7 +345,7 @@ __device__ __forceinline__ bool row_task(const RowArgs &a, TaskState &s, u32x4 (
                 }
             } else if (any_part) {   // wavefront-uniform: all-pruned vectors cost no exp
 #pragma unroll
-                for (int e = 0; e < EPP; ++e) s_safe += (x[e] >= tau) ? __expf(x[e] - m) : 0.0f;
+                for (int e = 0; e < EPP; ++e) s_safe += (ALLSAFE || x[e] >= tau) ? __expf(x[e] - m) : 0.0f;
             }
             if (EXTRAS && bits_row) {
                 const int idx = j * NT + fresh(tid);
@@ -319,7 +375,17 @@ __device__ __forceinline__ bool row_task(const RowArgs &a, TaskState &s, u32x4 (
         }
         // a slot the gradient phase will not read again (no safe token in this
         // wavefront's part of it) is refilled right away
-        if (j < NVN && has_next && (!bwd_here || !any)) r[j] = load_slot<TN, NT, NVFULL_N>(znext, j, fresh(tid), nvec_n);
+        if (j < NVN && has_next && (!bwd_here || !any) && !(NL > 0 && ahead && j >= L0))
+            r[j] = load_slot<TN, NT, NVFULL_N>(znext, j, fresh(tid), nvec_n);
+    }
+    if constexpr (NL > 0) {
+        if (ahead && !bwd_here) {
+            // younger than the copies into LDS are only this loop's refills of the other slots, the last of
+            // them issued NL slots of work ago
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+            for (int j = L0; j < NVN; ++j) r[j] = take_ahead(j, fresh(tid));
+        }
     }
     if constexpr (OVF) {
         for (int q0 = tid; q0 < novf_round; q0 += NT * OVF_BATCH) {   // uniform trip count: the ballots need every lane
@@ -424,8 +490,21 @@ __device__ __forceinline__ bool row_task(const RowArgs &a, TaskState &s, u32x4 (
         const bool listed = a.split_grad && !(y_safe && acc.count > a.list_cap);
         const bool grad_row = y_safe && !overflow;     // an overflowing row is only walked to refill its slots
         const float neg_g = -g;
+        // exp((x - m) - log S) for a gradient stored as bf16: the exact difference x - m, then one fused
+        // multiply-add and one exp2, exp2((x - m) log2(e) - log S log2(e)); rounding the constant moves the
+        // result by |log S| 2^-24 relative (log S <= log V), far below half a unit of a bf16 value
+        constexpr bool FOLD = sizeof(TS) == 2;
+        constexpr float kLog2e = 1.4426950408889634f;
+        const float fold_s = -log_s * kLog2e;
         const int t = fresh(tid);
         const int64_t y_slot = grad_row ? (y / EPV) : -1;
+        if constexpr (NL > 0) {
+            // The copies into LDS were issued a whole sum phase ago and nothing younger is in flight on a
+            // dense row (its slots are all still taken): waiting here, before this phase's stores are issued,
+            // costs nothing then (a wait further down, where the slots are taken out of LDS, would also wait
+            // for those stores).
+            if (ahead) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
         {   // ragged end
             const int64_t k = (int64_t)nvec * EPV + t;
             const bool safe = grad_row && t < tail && xt >= tau;
@@ -444,7 +523,7 @@ __device__ __forceinline__ bool row_task(const RowArgs &a, TaskState &s, u32x4 (
                 unpack(r[j], x, TS());
 #pragma unroll
                 for (int e = 0; e < EPV; ++e)
-                    d[e] = (x[e] >= tau) ? neg_g * __expf((x[e] - m) - log_s) : 0.0f;
+                    d[e] = (ALLSAFE || x[e] >= tau) ? neg_g * (FOLD ? __builtin_amdgcn_exp2f(fmaf(x[e] - m, kLog2e, fold_s)) : __expf((x[e] - m) - log_s)) : 0.0f;
                 if ((int64_t)idx == y_slot) {          // the sampled token: g * (1 - p)
                     const int ey = (int)(y - (int64_t)idx * EPV);
 #pragma unroll
@@ -461,7 +540,11 @@ __device__ __forceinline__ bool row_task(const RowArgs &a, TaskState &s, u32x4 (
                 }
             }
             if (!listed && dense_out && (j < NVFULL_S || idx < nvec)) __builtin_nontemporal_store(o, dzvec + idx);
-            if (j < NVN && has_next && ((any_mask >> j) & 1u)) r[j] = load_slot<TN, NT, NVFULL_N>(znext, j, t, nvec_n);
+            if (NL > 0 && ahead && j >= L0) {
+                r[j] = take_ahead(j, t);
+            } else if (j < NVN && has_next && ((any_mask >> j) & 1u)) {
+                r[j] = load_slot<TN, NT, NVFULL_N>(znext, j, t, nvec_n);
+            }
         }
         if constexpr (OVF) {
             // the part beyond the slots, read once more; a listed row without gradient has nothing to add
@@ -512,6 +595,7 @@ __device__ __forceinline__ bool row_task(const RowArgs &a, TaskState &s, u32x4 (
     if (nrow != row) flags = ny_ok ? 0u : (uint32_t)DVP_ROW_ID_OUT_OF_RANGE;
     s.row = nrow; s.side = nside; s.y = ny; s.y_ok = ny_ok; s.g = ng; s.zy_raw = nzy_raw; s.xt_raw = nxt_raw;
     s.flags = flags;
+    s.dense_hint = acc.count > a.list_cap;
     return true;
 }
 
@@ -523,12 +607,14 @@ __device__ __forceinline__ bool row_task(const RowArgs &a, TaskState &s, u32x4 (
 // EXTRAS builds also produce lse_full and the membership bitmask (1), and the entropy on top (2).
 // OVF builds take rows longer than the registers hold: the first NT * NV vectors are resident, the rest
 // is re-read in every phase (from the last-level cache when the workgroups' rows fit it).
-template <typename T, int NV, int NVFULL, int NT, int MINW, int EXTRAS, bool OVF = false>
+// NL > 0: NL * NT * 16 bytes of dynamic LDS hold vectors of the next row fetched ahead (see row_task).
+template <typename T, int NV, int NVFULL, int NT, int MINW, int EXTRAS, bool OVF = false, int NL = 0, bool ALLSAFE = false>
 __global__ __launch_bounds__(NT, MINW) void rows_resident_kernel(const RowArgs a)
 {
     using TR = elem_traits<T>;
     constexpr int EPV = TR::kPerVec;
     constexpr int NW = NT / kWave;
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds_ahead[];
     __shared__ float lds_max[NW];
     __shared__ float lds_f[3 * NW];
     __shared__ int lds_i[NW];
@@ -549,6 +635,7 @@ __global__ __launch_bounds__(NT, MINW) void rows_resident_kernel(const RowArgs a
     s.xt_raw = raw_neg_inf<T>();
     s.zy_raw = 0;
     s.flags = s.y_ok ? 0u : (uint32_t)DVP_ROW_ID_OUT_OF_RANGE;
+    s.dense_hint = false;
     u32x4 r[NV];
     {
         const T *zrow = (const T *)a.z[s.side] + s.row * a.ld[s.side];
@@ -558,7 +645,8 @@ __global__ __launch_bounds__(NT, MINW) void rows_resident_kernel(const RowArgs a
         if (t < tail) s.xt_raw = load_raw(zrow + (int64_t)nvec * EPV + t);
         if (s.y_ok) s.zy_raw = load_raw(zrow + s.y);
     }
-    while (row_task<T, NV, NVFULL, T, NV, NVFULL, NV, NT, EXTRAS, true, OVF>(a, s, r, lds_max, lds_f, lds_i, &lds_list_count)) {}
+    while (row_task<T, NV, NVFULL, T, NV, NVFULL, NV, NT, EXTRAS, true, OVF, NL, ALLSAFE>(a, s, r, lds_max, lds_f, lds_i,
+                                                                                         &lds_list_count, lds_ahead)) {}
 }
 
 // The same walk when the inference logits are stored as 8-bit E4M3 codes: an
@@ -590,6 +678,7 @@ __global__ __launch_bounds__(NT, MINW) void rows_resident_f8infer_kernel(const R
     s.xt_raw = raw_neg_inf<f8_t>();
     s.zy_raw = 0;
     s.flags = s.y_ok ? 0u : (uint32_t)DVP_ROW_ID_OUT_OF_RANGE;
+    s.dense_hint = false;
     u32x4 r[NV];
     {
         const f8_t *zrow = (const f8_t *)a.z[1] + s.row * a.ld[1];
@@ -942,34 +1031,58 @@ static int device_cu_count()
 }
 
 // One build of the resident kernel and how many of its workgroups a CU holds (queried once).
-template <typename T, bool F8_INFER, int NV, int NVFULL, int NT, int MINW, int EXTRAS, bool OVF>
+// NOPRUNE: the build for log_rho = -inf.  Every row is then written densely, so it fetches slots of the
+// next row ahead into LDS (as many 16 KB slots as the LDS holds beside the reduction scratch; its
+// workgroup owns the CU) and leaves the threshold tests out.  The other builds keep the LDS free: on rows
+// with short safe sets the fetch-ahead code costs more than it brings (measured: 1.5 % on the row kernel).
+template <typename T, bool F8_INFER, int NV, int NVFULL, int NT, int MINW, int EXTRAS, bool OVF, bool NOPRUNE>
 struct ResidentBuild {
     typedef void (*Kernel)(const RowArgs);
+    static_assert(!NOPRUNE || (!F8_INFER && !OVF && NT == 1024 && EXTRAS == 0), "the no-pruning build");
+    static constexpr int NL = NOPRUNE ? (NV < 9 ? NV : 9) : 0;
+    static constexpr int kDynLds = NL * NT * 16;
     static Kernel kernel()
     {
         if constexpr (F8_INFER) return rows_resident_f8infer_kernel<T, NV, NVFULL, NT, MINW, EXTRAS>;
-        else                    return rows_resident_kernel<T, NV, NVFULL, NT, MINW, EXTRAS, OVF>;
+        else                    return rows_resident_kernel<T, NV, NVFULL, NT, MINW, EXTRAS, OVF, NL, NOPRUNE>;
     }
     static inline std::atomic<int> per_cu{0};
+    static inline std::atomic<uint64_t> configured{0};   // bit d: device d allows this build its dynamic LDS
     static hipError_t prepare()
     {
+        if (kDynLds > 0) {      // more than 64 KB of LDS per workgroup has to be asked for, once per device
+            int dev = 0;
+            hipError_t e = hipGetDevice(&dev);
+            if (e == hipSuccess) e = hipFuncSetAttribute((const void *)kernel(), hipFuncAttributeMaxDynamicSharedMemorySize, kDynLds);
+            if (e != hipSuccess) return e;
+            if (dev >= 0 && dev < 64) configured.fetch_or(1ull << dev, std::memory_order_release);
+        }
         int nb = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kernel(), NT, 0) != hipSuccess || nb < 1) nb = 1;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kernel(), NT, kDynLds) != hipSuccess || nb < 1) nb = 1;
         per_cu.store(nb, std::memory_order_relaxed);
         return hipSuccess;
     }
     static inline PrepareRegistrar registrar{&prepare};
 };
 
-template <typename T, bool F8_INFER, int NV, int NVFULL, int NT, int MINW, int EXTRAS, bool OVF = false>
+template <typename T, bool F8_INFER, int NV, int NVFULL, int NT, int MINW, int EXTRAS, bool OVF = false, bool NOPRUNE = false>
 static hipError_t launch_resident_inst(const RowArgs &a, hipStream_t stream)
 {
-    typedef ResidentBuild<T, F8_INFER, NV, NVFULL, NT, MINW, EXTRAS, OVF> Build;
+    typedef ResidentBuild<T, F8_INFER, NV, NVFULL, NT, MINW, EXTRAS, OVF, NOPRUNE> Build;
     (void)&Build::registrar;             // instantiates the registration of this build
-    if (Build::per_cu.load(std::memory_order_relaxed) == 0) (void)Build::prepare();
+    bool ready = Build::per_cu.load(std::memory_order_relaxed) != 0;
+    if (ready && Build::kDynLds > 0) {
+        int dev = 0;
+        ready = hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 64 &&
+                (Build::configured.load(std::memory_order_acquire) & (1ull << dev));
+    }
+    if (!ready) {
+        const hipError_t e = Build::prepare();
+        if (e != hipSuccess) return e;
+    }
     int64_t grid = (int64_t)device_cu_count() * Build::per_cu.load(std::memory_order_relaxed);
     if (grid > a.n_rows) grid = a.n_rows;
-    hipLaunchKernelGGL(Build::kernel(), dim3((unsigned)grid), dim3(NT), 0, stream, a);
+    hipLaunchKernelGGL(Build::kernel(), dim3((unsigned)grid), dim3(NT), Build::kDynLds, stream, a);
     return hipGetLastError();
 }
 
@@ -985,6 +1098,16 @@ static hipError_t launch_resident_t(const RowArgs &a, hipStream_t stream)
     if (slots <= 256 * 4)   return launch_resident_inst<T, F8_INFER, 4, 0, 256, 4, EXTRAS>(a, stream);
     if (slots <= 256 * 8)   return launch_resident_inst<T, F8_INFER, 8, 4, 256, 6, EXTRAS>(a, stream);
     if (slots <= 256 * 16)  return launch_resident_inst<T, F8_INFER, 16, 8, 256, 4, EXTRAS>(a, stream);
+    if constexpr (!F8_INFER && EXTRAS == 0) {
+        // nothing pruned and a dense gradient matrix: the build without threshold tests, with LDS fetch-ahead
+        if (a.log_rho == -INFINITY && !a.sparse_only && a.grad_out != nullptr) {
+            if (slots <= 1024 * 8)  return launch_resident_inst<T, false, 8, 4, 1024, 5, 0, false, true>(a, stream);
+            if (slots <= 1024 * 12) return launch_resident_inst<T, false, 12, 8, 1024, 4, 0, false, true>(a, stream);
+            if (slots <= 1024 * 16) return launch_resident_inst<T, false, 16, 12, 1024, 4, 0, false, true>(a, stream);
+            if (slots <= 1024 * 19) return launch_resident_inst<T, false, 19, 16, 1024, 4, 0, false, true>(a, stream);
+            if (slots <= 1024 * 20) return launch_resident_inst<T, false, 20, 19, 1024, 4, 0, false, true>(a, stream);
+        }
+    }
     if (slots <= 1024 * 8)  return launch_resident_inst<T, F8_INFER, 8, 4, 1024, 5, EXTRAS>(a, stream);
     if (slots <= 1024 * 12) return launch_resident_inst<T, F8_INFER, 12, 8, 1024, 4, EXTRAS>(a, stream);
     if (slots <= 1024 * 16) return launch_resident_inst<T, F8_INFER, 16, 12, 1024, 4, EXTRAS>(a, stream);

@@ -600,6 +600,26 @@ def bench_rows(args):
         result["threshold_sweep"] = sweep
 
     result["parity"] = parity_out
+
+    # ---- what the machine delivers for this call's traffic mixes with no arithmetic at all (same buffers,
+    # ---- same session): reads only, writes only, and rows read twice and written once from one workgroup
+    if dense_call and not args.no_sweep and infer_elem == elem and v * elem <= 19 * 16384 and (v * elem) % 16 == 0:
+        b = sets[0]
+
+        def probe(mode):
+            _, pl = time_launches(lambda: dvp.hbm_probe(mode, b["zt"], b["zi"], b["dz"]), 10, 2)
+            return median(pl)
+        mat = n * v * elem
+        t_read, t_fill, t_rows = probe(dvp.PROBE_READ), probe(dvp.PROBE_FILL), probe(dvp.PROBE_ROWS_2R1W)
+        read_gbs, fill_gbs, rows_gbs = 2 * mat / t_read / 1e6, mat / t_fill / 1e6, 3 * mat / t_rows / 1e6
+        result["stream_ceiling"] = {
+            "what": "streaming kernels without arithmetic over this workload's own matrices (dvp_hbm_probe), median of 10 launches",
+            "read_two_matrices_gbs": read_gbs, "fill_one_matrix_gbs": fill_gbs, "rows_2_reads_1_write_gbs": rows_gbs,
+            # a call whose row kernel only reads and whose gradient is written by a write-only kernel: 2 parts read, 1 part filled
+            "separate_phases_frac_of_peak": 3.0 / (2.0 / read_gbs + 1.0 / fill_gbs) / HBM_PEAK_GBS,
+            # a call whose row kernel writes every gradient row itself (dense rows: no pruning, flat logits)
+            "interleaved_rows_frac_of_peak": rows_gbs / HBM_PEAK_GBS}
+
     print(json.dumps(result))
     if parity_out is not None and not parity_out["ok"]:
         print("bench.py: the timed outputs do NOT match the oracle", file=sys.stderr)

@@ -478,6 +478,22 @@ dvp_status dvp_sequence_weights(int64_t n_tokens, int64_t n_seq, const float *lo
                                 uint8_t *seq_veto, void *stream);
 
 /*
+ * Measurement support (no part of the method): streaming kernels with the row path's access pattern and no
+ * arithmetic, so that a benchmark can state what this machine delivers for the traffic mixes of the fused
+ * call next to what the call achieves (Sec. 6 of the paper reports no kernel figures; the bound is the
+ * machine's).  a, b, c are DEVICE matrices of n_rows contiguous rows of row_bytes (a multiple of 16), 16-byte
+ * aligned, never aliased.
+ *   DVP_PROBE_READ       every byte of a and of b is read once
+ *   DVP_PROBE_FILL       zeros are written over c (a, b ignored)
+ *   DVP_PROBE_ROWS_2R1W  one workgroup per CU walks the rows: b's row into registers, then a's row, then a's
+ *                        row out to c: reads and writes interleaved the way a densely written gradient
+ *                        interleaves them; row_bytes at most 19 * 16384 (DVP_ERR_UNSUPPORTED beyond)
+ */
+enum { DVP_PROBE_READ = 0, DVP_PROBE_FILL = 1, DVP_PROBE_ROWS_2R1W = 2 };
+dvp_status dvp_hbm_probe(int mode, const void *a, const void *b, void *c, int64_t n_rows, int64_t row_bytes,
+                         void *stream);
+
+/*
  * One-time set-up of every kernel build for the CURRENT device (hipSetDevice): occupancy queries, the
  * LDS-size attribute of the matrix-core kernels, the device's CU count.  Host only; enqueues nothing,
  * allocates nothing.  Optional: an entry point whose build has not been prepared on the current device

@@ -15,7 +15,7 @@ PKG = Path(__file__).resolve().parent
 CSRC = PKG / "csrc"
 OBJ = PKG / "_build"
 LIB = PKG / "libdvp_hip.so"
-SOURCES = ["dvp_api.hip", "dvp_rows.hip", "dvp_lmhead.hip", "dvp_lmhead_lists.hip", "dvp_sequences.hip"]
+SOURCES = ["dvp_api.hip", "dvp_rows.hip", "dvp_lmhead.hip", "dvp_lmhead_lists.hip", "dvp_sequences.hip", "dvp_probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -42,7 +42,7 @@ def build(verbose: bool = True, only_changed: bool = False) -> Path:
     libdvp_hip.so next to this file."""
     OBJ.mkdir(exist_ok=True)
     todo = [s for s in SOURCES if not only_changed or _stale(s)]
-    with ThreadPoolExecutor(max_workers=min(5, max(1, len(todo)))) as ex:
+    with ThreadPoolExecutor(max_workers=min(6, max(1, len(todo)))) as ex:
         list(ex.map(_compile, todo))
     objs = [OBJ / (s + ".o") for s in SOURCES]
     tmp = LIB.with_suffix(".so.tmp%d" % os.getpid())

@@ -27,7 +27,7 @@ EXPORTS = ("dvp_forward", "dvp_backward", "dvp_forward_backward", "dvp_fused_lmh
            "dvp_fused_lmhead_forward", "dvp_fused_lmhead_backward", "dvp_fused_lmhead_lists",
            "dvp_fused_lmhead_lists_workspace_bytes", "dvp_fused_lmhead_lists_second_pass_rows",
            "dvp_fused_lmhead_lists_f8infer", "dvp_fused_lmhead_rows", "dvp_fused_lmhead_rows_workspace_bytes",
-           "dvp_prepare", "dvp_fused_lmhead_forward_noalloc")
+           "dvp_prepare", "dvp_fused_lmhead_forward_noalloc", "dvp_hbm_probe")
 
 
 class DvpParams(ctypes.Structure):
@@ -129,6 +129,8 @@ def lib():
         L.dvp_log_threshold.argtypes = [ctypes.c_double]
         L.dvp_prepare.restype = ctypes.c_int
         L.dvp_prepare.argtypes = []
+        L.dvp_hbm_probe.restype = ctypes.c_int
+        L.dvp_hbm_probe.argtypes = [ctypes.c_int, vp, vp, vp, ctypes.c_int64, ctypes.c_int64, vp]
         L.dvp_fused_lmhead_forward_noalloc.restype = ctypes.c_int
         L.dvp_fused_lmhead_forward_noalloc.argtypes = [lp, vp, vp, vp, i64p, sp, sp, vp, vp]
         _lib = L
@@ -144,6 +146,18 @@ def prepare() -> None:
     st = lib().dvp_prepare()
     if st != 0:
         raise DvpError(st, "dvp_prepare")
+
+
+PROBE_READ, PROBE_FILL, PROBE_ROWS_2R1W = 0, 1, 2
+
+
+def hbm_probe(mode: int, a, b, c, *, stream=None) -> None:
+    """A streaming kernel without arithmetic over [N, row] matrices (see dvp_hbm_probe in dvp.h)."""
+    ref = c if mode == PROBE_FILL else a
+    st = lib().dvp_hbm_probe(int(mode), _ptr(a), _ptr(b), _ptr(c), ref.shape[0], ref.stride(0) * ref.element_size(),
+                             _stream(stream))
+    if st != 0:
+        raise DvpError(st, "dvp_hbm_probe")
 
 
 def log_rho(rho: float) -> float:

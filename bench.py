@@ -43,6 +43,8 @@ def kernel_source_hash() -> str:
 def traffic_key(args) -> str:
     """Names the configuration a traffic figure belongs to."""
     key = "%s/rho=%g" % (args.workload, args.rho)
+    if args.entry != "fused":
+        key += "/entry=" + args.entry
     if args.rows is not None:
         key += "/rows=%d" % args.rows
     if args.sparse_grad:
@@ -370,6 +372,9 @@ def main():
     ap.add_argument("--parity-rows", type=int, default=0, metavar="K",
                     help="check about K evenly spaced rows of the timed call against the oracle instead of every row")
     ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--entry", default="fused", choices=["fused", "split", "backward"],
+                    help="row workloads: one step = dvp_forward_backward (fused, the default), dvp_forward followed by "
+                         "dvp_backward (split), or dvp_backward alone on a forward done beforehand (backward)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run 3 plain device-to-device copies of one logits matrix (known "
                          "size: reads and writes N*V*elem bytes each) to calibrate HBM counters")
@@ -449,9 +454,16 @@ def bench_rows(args):
             dvp.dvp_forward_backward_sparse(b["zt"], b["zi"], b["ids"], b["go"], log_rho_value, cap,
                                             out_train=b["out_t"], out_infer=b["out_i"], row_flags=b["flags"],
                                             entries=b["entries"], grad_len=b["glen"])
-        else:
+        elif args.entry == "fused":
             dvp.dvp_forward_backward(b["zt"], b["zi"], b["ids"], b["go"], log_rho_value,
                                      out_train=b["out_t"], out_infer=b["out_i"], row_flags=b["flags"], dz=b["dz"])
+        else:
+            if args.entry == "split" or b.get("forward_at") != log_rho_value:
+                dvp.dvp_forward(b["zt"], b["zi"], b["ids"], log_rho_value, out_train=b["out_t"], out_infer=b["out_i"],
+                                row_flags=b["flags"])
+                b["forward_at"] = log_rho_value
+            dvp.dvp_backward(b["zt"], b["ids"], b["go"], b["out_t"].row_max, b["out_t"].lse_safe, b["flags"], log_rho_value,
+                             dz=b["dz"])
         return b
 
     if args.copy_probe:
@@ -464,6 +476,10 @@ def bench_rows(args):
     last = sets[(turn[0] - 1) % n_sets]                 # the buffer set the last timed call wrote
     out_t, out_i, flags, dz = last["out_t"], last["out_i"], last["flags"], last["dz"]
     bytes_per_launch = algorithmic_bytes_per_row(v, elem, infer_elem) * n
+    if args.entry == "split":        # the training row is read a second time by the backward
+        bytes_per_launch += v * elem * n
+    if args.entry == "backward":     # training row in, gradient row out; id, grad_out, row_max, lse_safe, flags per row
+        bytes_per_launch = (2 * v * elem + 8 + 4 + 4 + 4 + 1) * n
     if args.sparse_grad:
         # no dense gradient row; the lists that were written (8 bytes per entry) and their lengths instead
         listed = last["glen"][(flags & 8) == 0].to(torch.int64).sum().item()
@@ -472,7 +488,7 @@ def bench_rows(args):
 
     traffic = MEASURED_TRAFFIC.get(kernel_source_hash(), {}).get(traffic_key(args))
 
-    dense_call = not args.sparse_grad and not args.split_lists
+    dense_call = not args.sparse_grad and not args.split_lists and args.entry == "fused"
     result = {
         "metric": "DVP fwd+bwd rows/s and achieved HBM GB/s (% of peak), V=151936 bf16",
         "value": n * args.steps / wall,
@@ -492,7 +508,8 @@ def bench_rows(args):
                    "entry_point": "dvp_forward_backward_sparse (grad_out = 1, list capacity %d) + dvp_lists_to_dense"
                                   % args.split_lists if args.split_lists else
                                   "dvp_forward_backward_sparse (list capacity %d)" % args.sparse_grad
-                                  if args.sparse_grad else "dvp_forward_backward",
+                                  if args.sparse_grad else {"fused": "dvp_forward_backward", "split": "dvp_forward + dvp_backward",
+                                                            "backward": "dvp_backward"}[args.entry],
                    "row_kernel": "resident" if dvp.lib().dvp_row_path(
                        dvp.DvpParams(n, v, v, v, v, 1 if elem == 2 else 0, lr,
                                      2 if infer_elem == 1 else (1 if elem == 2 else 0)), 1) == 1 else "streaming",
@@ -503,7 +520,9 @@ def bench_rows(args):
                                "backward_kernel on overflowing rows); durations summed" if args.split_lists else
                                "rows_resident_kernel (gradient as lists)" if args.sparse_grad else
                                "rows_resident_kernel + grad_zero_kernel + grad_scatter_kernel "
-                               "(one dvp_forward_backward call; durations summed)",
+                               "(one dvp_forward_backward call; durations summed)" if args.entry == "fused" else
+                               ("rows_resident_kernel (forward) + " if args.entry == "split" else "") +
+                               "backward_zero_kernel + backward_kernel (durations summed)",
                      "kernel_ms_avg": kernel_ms, "kernel_ms_median": median(per_launch),
                      "kernel_ms_min": min(per_launch), "timed_launches": len(per_launch),
                      "frac_at_median": bytes_per_launch / (median(per_launch) * 1e-3) / 1e9 / HBM_PEAK_GBS,

@@ -70,9 +70,14 @@ enum {
     DVP_ROW_Y_IN_TRAIN_SAFE = 1, /* sampled id is in V_S  (training logits)  */
     DVP_ROW_Y_IN_INFER_SAFE = 2, /* sampled id is in V'_S (inference logits) */
     DVP_ROW_ID_OUT_OF_RANGE = 4, /* id < 0 or id >= V: log-probs are NaN, gradient row is zero */
-    DVP_ROW_GRAD_OVERFLOW = 8    /* dvp_forward_backward_sparse only: the safe set has more than
+    DVP_ROW_GRAD_OVERFLOW = 8,   /* dvp_forward_backward_sparse only: the safe set has more than
                                     list_cap tokens, no gradient entry was written for this row */
+    DVP_ROW_SHORT_SAFE_SET = 16  /* row path: V_S (training logits) has at most DVP_SHORT_SAFE_SET_MAX tokens.
+                                    dvp_backward writes such a row as zeros plus a few values instead of
+                                    streaming it; a caller that builds row_flags itself may leave the bit
+                                    clear (the row is then streamed, same result) */
 };
+#define DVP_SHORT_SAFE_SET_MAX 64
 
 /*
  * dvp_params.mode
@@ -165,6 +170,11 @@ dvp_status dvp_forward(const dvp_params *params, const void *z_train, const void
  * "pruned softmax minus one-hot".  row_max_train, lse_safe_train and row_flags
  * are the forward's outputs (all required).  dz is DEVICE [N, ld_grad] of
  * params->dtype (bf16 is rounded to nearest even) and may not alias z_train.
+ * Two kernels: zeros over the rows that have no gradient or a short safe set
+ * (DVP_ROW_SHORT_SAFE_SET), written without reading anything; then the logits
+ * of the rows that have a gradient are read once, short rows dropping their few
+ * values into the zeros, the others written as they are read.  Rows without a
+ * gradient are not read at all.
  */
 dvp_status dvp_backward(const dvp_params *params, const void *z_train, const int64_t *ids,
                         const float *grad_out, const float *row_max_train,

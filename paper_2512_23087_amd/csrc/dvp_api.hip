@@ -211,6 +211,7 @@ dvp_status dvp_backward(const dvp_params *params, const void *z_train, const int
     a.n_rows = params->n_rows; a.vocab = (int32_t)params->vocab; a.log_rho = params->log_rho;
     a.finite_mask = params->mode == DVP_MODE_FINITE_MASK;
     a.only_flagged = 0;
+    a.split = 1;
     const bool vec = rows_vector_ok(params, z_train, nullptr, dz);
     hipError_t e = dvp::launch_backward(params->dtype, a, vec, (hipStream_t)stream);
     return e == hipSuccess ? DVP_OK : DVP_ERR_HIP;
@@ -249,6 +250,7 @@ dvp_status dvp_lists_to_dense(const dvp_params *params, const dvp_grad_entry *en
         a.n_rows = params->n_rows; a.vocab = (int32_t)params->vocab; a.log_rho = params->log_rho;
         a.finite_mask = 0;
         a.only_flagged = DVP_ROW_GRAD_OVERFLOW;
+        a.split = 0;
         const bool vec = rows_vector_ok(params, z_train, nullptr, dz);
         if (dvp::launch_backward(params->dtype, a, vec, (hipStream_t)stream) != hipSuccess) return DVP_ERR_HIP;
     }

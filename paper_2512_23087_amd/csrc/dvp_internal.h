@@ -86,6 +86,7 @@ struct BackwardArgs {
     float log_rho;
     int32_t finite_mask;     // see RowArgs
     uint32_t only_flagged;   // non-zero: only rows with one of these row_flags bits are written
+    int32_t split;           // rows without gradient or with a short safe set are zero-filled first (see launch_backward)
 };
 
 // Dense gradient from per-row lists (launch_lists_to_dense)

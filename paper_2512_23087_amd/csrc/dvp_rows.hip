@@ -459,6 +459,7 @@ __device__ __forceinline__ bool row_task(const RowArgs &a, TaskState &s, u32x4 (
     const float log_s = logf(acc.s_safe);
     const bool y_safe = y_ok && (zy >= tau);
     if (y_safe) flags |= (side == 0 ? DVP_ROW_Y_IN_TRAIN_SAFE : DVP_ROW_Y_IN_INFER_SAFE);
+    if (side == 0 && acc.count <= DVP_SHORT_SAFE_SET_MAX) flags |= DVP_ROW_SHORT_SAFE_SET;
     // list-only output: a safe set longer than the list's capacity is reported, not written
     const bool overflow = a.sparse_only && bwd_here && y_safe && acc.count > a.list_cap;
     if (overflow) flags |= DVP_ROW_GRAD_OVERFLOW;
@@ -779,6 +780,7 @@ __global__ __launch_bounds__(NT) void rows_streaming_kernel(const RowArgs a)
             }
             const bool y_safe = y_ok && (zy >= tau);
             if (y_safe) flags |= (side == 0 ? DVP_ROW_Y_IN_TRAIN_SAFE : DVP_ROW_Y_IN_INFER_SAFE);
+            if (side == 0 && acc.count <= DVP_SHORT_SAFE_SET_MAX) flags |= DVP_ROW_SHORT_SAFE_SET;
             if (tid == 0) {
                 if (out.row_max) out.row_max[row] = m;
                 if (out.lse_safe) out.lse_safe[row] = ref + log_s;
@@ -816,6 +818,47 @@ __global__ __launch_bounds__(NT) void rows_streaming_kernel(const RowArgs a)
 // stand-alone backward: one pass over the training row with the forward's
 // row_max / lse_safe / flags (Prop. 5.4; the set is a constant of the backward)
 // ---------------------------------------------------------------------------
+// Which rows the zero kernel writes when the call is split (a.split): the rows without a gradient and
+// the rows whose safe set is short.  Both kernels derive it from the same flags.
+__device__ __forceinline__ bool backward_has_gradient(const BackwardArgs &a, uint32_t fl)
+{
+    // "gradient row": the sampled token is safe; in the finite-mask variant, any id in range
+    return a.finite_mask ? (fl & DVP_ROW_ID_OUT_OF_RANGE) == 0 : (fl & DVP_ROW_Y_IN_TRAIN_SAFE) != 0;
+}
+__device__ __forceinline__ bool backward_row_is_zero_filled(const BackwardArgs &a, uint32_t fl)
+{
+    return a.split && (!backward_has_gradient(a, fl) || (fl & DVP_ROW_SHORT_SAFE_SET) != 0);
+}
+
+constexpr int kBwdZeroThreads = 1024, kBwdZeroVecs = 2;
+template <typename T, bool VEC>
+__global__ __launch_bounds__(kBwdZeroThreads) void backward_zero_kernel(const BackwardArgs a, int chunks_per_row)
+{
+    constexpr int EPV = elem_traits<T>::kPerVec;
+    const int64_t row = blockIdx.x / chunks_per_row;
+    const int chunk = blockIdx.x - (int)(row * chunks_per_row);
+    if (!backward_row_is_zero_filled(a, a.row_flags[row])) return;
+    T *dzrow = (T *)a.dz + row * a.ld_grad;
+    const int V = a.vocab;
+    if constexpr (VEC) {
+        const int nvec = V / EPV;
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int u = 0; u < kBwdZeroVecs; ++u) {
+            const int idx = (chunk * kBwdZeroVecs + u) * kBwdZeroThreads + threadIdx.x;
+            if (idx < nvec) ((u32x4 *)dzrow)[idx] = zero;
+        }
+        if (chunk == chunks_per_row - 1) {
+            const int k = nvec * EPV + threadIdx.x;
+            if (k < V) store_elem(dzrow + k, 0.0f);
+        }
+    } else {
+        const int per = kBwdZeroThreads * kBwdZeroVecs * EPV;   // elements per workgroup
+        for (int k = chunk * per + threadIdx.x; k < (chunk + 1) * per && k < V; k += kBwdZeroThreads)
+            store_elem(dzrow + k, 0.0f);
+    }
+}
+
 template <typename T, int NT, bool VEC>
 __global__ __launch_bounds__(NT) void backward_kernel(const BackwardArgs a)
 {
@@ -825,7 +868,11 @@ __global__ __launch_bounds__(NT) void backward_kernel(const BackwardArgs a)
     const int V = a.vocab;
 
     for (int64_t row = blockIdx.x; row < a.n_rows; row += gridDim.x) {
-        if (a.only_flagged && !(a.row_flags[row] & a.only_flagged)) continue;   // workgroup-uniform
+        const uint32_t fl = a.row_flags[row];
+        if (a.only_flagged && !(fl & a.only_flagged)) continue;   // workgroup-uniform
+        const bool y_safe = backward_has_gradient(a, fl);
+        const bool zeroed = backward_row_is_zero_filled(a, fl);     // the zero kernel has written this row
+        if (zeroed && !y_safe) continue;                            // ... and it has no gradient: not even read
         const T *zrow = (const T *)a.z + row * a.ld;
         T *dzrow = (T *)a.dz + row * a.ld_grad;
         const float m = a.row_max[row];
@@ -834,9 +881,6 @@ __global__ __launch_bounds__(NT) void backward_kernel(const BackwardArgs a)
         if (a.finite_mask) tau = storage_rounded(tau, T());
         const float g = a.grad_out[row];
         const int64_t y = a.ids[row];
-        // "gradient row": the sampled token is safe; in the finite-mask variant, any id in range
-        const bool y_safe = a.finite_mask ? (a.row_flags[row] & DVP_ROW_ID_OUT_OF_RANGE) == 0
-                                          : (a.row_flags[row] & DVP_ROW_Y_IN_TRAIN_SAFE) != 0;
         int k_scalar = 0;
         if constexpr (VEC) {
             const int nvec = V / EPV;
@@ -847,12 +891,12 @@ __global__ __launch_bounds__(NT) void backward_kernel(const BackwardArgs a)
             for (int idx = tid; idx < nvec_round; idx += NT) {
                 const bool in = idx < nvec;
                 u32x4 o = zero;
+                bool any_safe = false;
                 if (y_safe) {
                     float x[EPV];
                     const u32x4 v = in ? __builtin_nontemporal_load(zvec + idx)
                                        : (u32x4){TR::kPadWord, TR::kPadWord, TR::kPadWord, TR::kPadWord};
                     unpack(v, x, T());
-                    bool any_safe = false;
 #pragma unroll
                     for (int e = 0; e < EPV; ++e) any_safe |= (x[e] >= tau);
                     if (__any(any_safe)) {
@@ -867,20 +911,24 @@ __global__ __launch_bounds__(NT) void backward_kernel(const BackwardArgs a)
                         o = pack(d, T());
                     }
                 }
-                if (in) __builtin_nontemporal_store(o, dzvec + idx);
+                // a zero-filled row takes only the vectors that hold a safe token (a -inf threshold makes the
+                // padding lanes pass: they are not in the row)
+                if (in && (!zeroed || any_safe)) __builtin_nontemporal_store(o, dzvec + idx);
             }
             k_scalar = nvec * EPV;
         }
         for (int k = k_scalar + tid; k < V; k += NT) {
             float d = 0.0f;
+            bool safe = false;
             if (y_safe) {
                 const float x = load_elem(zrow + k);
                 if (x >= tau) {
                     const float p = __expf((x - m) - log_s);
                     d = g * (((int64_t)k == y ? 1.0f : 0.0f) - p);
+                    safe = true;
                 }
             }
-            store_elem(dzrow + k, d);
+            if (!zeroed || safe) store_elem(dzrow + k, d);
         }
     }
 }
@@ -1225,6 +1273,28 @@ hipError_t launch_lists_to_dense(int dtype, const ListsArgs &a, bool vector_ok, 
 hipError_t launch_backward(int dtype, const BackwardArgs &a, bool vector_ok, hipStream_t stream)
 {
     if (a.n_rows == 0) return hipSuccess;
+    if (a.split) {      // zeros over the rows without gradient or with a short safe set: write-only, before any read
+        const int epv = dtype == DVP_BF16 ? 8 : 4;
+        const int64_t per = (int64_t)kBwdZeroThreads * kBwdZeroVecs * epv;
+        const int chunks = (int)((a.vocab + per - 1) / per);
+        const int64_t max_rows = 0x7fffffff / chunks;
+        for (int64_t r0 = 0; r0 < a.n_rows; r0 += max_rows) {
+            BackwardArgs b = a;
+            b.n_rows = a.n_rows - r0 < max_rows ? a.n_rows - r0 : max_rows;
+            b.row_flags = a.row_flags + r0;
+            b.dz = (char *)a.dz + r0 * a.ld_grad * (dtype == DVP_BF16 ? 2 : 4);
+            const dim3 gz((unsigned)(b.n_rows * chunks)), bz(kBwdZeroThreads);
+            if (dtype == DVP_BF16) {
+                if (vector_ok) hipLaunchKernelGGL((backward_zero_kernel<bf16_t, true>), gz, bz, 0, stream, b, chunks);
+                else           hipLaunchKernelGGL((backward_zero_kernel<bf16_t, false>), gz, bz, 0, stream, b, chunks);
+            } else {
+                if (vector_ok) hipLaunchKernelGGL((backward_zero_kernel<float, true>), gz, bz, 0, stream, b, chunks);
+                else           hipLaunchKernelGGL((backward_zero_kernel<float, false>), gz, bz, 0, stream, b, chunks);
+            }
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
+    }
     constexpr int NT = 512;
     int64_t grid = (int64_t)device_cu_count() * 8;
     if (grid > a.n_rows) grid = a.n_rows;

@@ -18,7 +18,8 @@ _PKG = Path(__file__).resolve().parent
 LIB_PATH = _PKG / "libdvp_hip.so"
 
 DVP_F32, DVP_BF16, DVP_F8E4M3 = 0, 1, 2
-ROW_Y_IN_TRAIN_SAFE, ROW_Y_IN_INFER_SAFE, ROW_ID_OUT_OF_RANGE, ROW_GRAD_OVERFLOW = 1, 2, 4, 8
+ROW_Y_IN_TRAIN_SAFE, ROW_Y_IN_INFER_SAFE, ROW_ID_OUT_OF_RANGE, ROW_GRAD_OVERFLOW, ROW_SHORT_SAFE_SET = 1, 2, 4, 8, 16
+SHORT_SAFE_SET_MAX = 64
 
 EXPORTS = ("dvp_forward", "dvp_backward", "dvp_forward_backward", "dvp_fused_lmhead",
            "dvp_fused_lmhead_workspace_bytes", "dvp_log_rho", "dvp_status_string", "dvp_row_path",

@@ -71,8 +71,12 @@ def check_side(name, gpu_side, z_host, ids_host, log_rho, tol, vocab, rows=None,
                 safe_count=o["safe_count"])
 
 
-def check_flags(row_flags, y_train_safe, y_infer_safe, ids_host, vocab, rows=None):
+def check_flags(row_flags, y_train_safe, y_infer_safe, ids_host, vocab, rows=None, train_safe_count=None):
+    """train_safe_count: the oracle's safe-set sizes of the training side; given, the short-safe-set bit
+    (at most 64 tokens) is checked as well, else it is ignored."""
     got = row_flags.cpu().numpy()
+    if train_safe_count is None:
+        got = got & ~np.uint8(16)
     if rows is not None:
         got = got[np.asarray(rows)]
         ids = ids_host.numpy()[np.asarray(rows)]
@@ -82,6 +86,8 @@ def check_flags(row_flags, y_train_safe, y_infer_safe, ids_host, vocab, rows=Non
     if y_infer_safe is not None:
         want = want | (y_infer_safe.astype(np.uint8) * 2)
     want = want | (((ids < 0) | (ids >= vocab)).astype(np.uint8) * 4)
+    if train_safe_count is not None:
+        want = want | ((np.asarray(train_safe_count) <= 64).astype(np.uint8) * 16)
     np.testing.assert_array_equal(got, want, err_msg="row_flags")
 
 
@@ -171,7 +177,8 @@ class RowParity:
         self._side("train", train, ot)
         self._side("infer", infer, oi)
         want_flags = (ot["y_in_safe"].astype(np.uint8) | (oi["y_in_safe"].astype(np.uint8) << 1)
-                      | (((ids < 0) | (ids >= v)).astype(np.uint8) << 2))
+                      | (((ids < 0) | (ids >= v)).astype(np.uint8) << 2)
+                      | ((ot["safe_count"] <= 64).astype(np.uint8) << 4))      # the short-safe-set bit
         self.c["row_flag_mismatches"] += int((row_flags != want_flags).sum())
         for bits, o in ((bits_train, ot), (bits_infer, oi)):
             if bits is not None:

@@ -67,7 +67,7 @@ def _run(dvp, wl, rho, *, backward=True, extras=True, tol_i=1e-5, threads=8):
     zt, zi, ids = wl.z_train.cpu(), _codes(wl.z_infer), wl.ids.cpu()
     st = parity.check_side("train", res.train, zt, ids, lr, tol_t, v, threads=threads)
     si = parity.check_side("infer", res.infer, zi, ids, lr, tol_i, v, threads=threads)
-    parity.check_flags(res.row_flags, st["y_in_safe"], si["y_in_safe"], ids, v)
+    parity.check_flags(res.row_flags, st["y_in_safe"], si["y_in_safe"], ids, v, train_safe_count=st["safe_count"])
     out = dict(train=st, infer=si, result=res)
     if backward:
         out.update(parity.check_gradient("dz", res.dz, zt, ids, wl.grad_out.cpu(), lr, tol_t, threads=threads))

@@ -40,7 +40,7 @@ def _run_case(dvp, wl, rho, *, backward, lse_full=True, bits=True, rows=None, th
     if rows is None:
         st = parity.check_side("train", res.train, zt, ids, lr, tol, v, threads=threads)
         si = parity.check_side("infer", res.infer, zi, ids, lr, tol, v, threads=threads)
-        parity.check_flags(res.row_flags, st["y_in_safe"], si["y_in_safe"], ids, v)
+        parity.check_flags(res.row_flags, st["y_in_safe"], si["y_in_safe"], ids, v, train_safe_count=st["safe_count"])
         if backward:
             stats.update(parity.check_gradient("dz", res.dz, zt, ids, wl.grad_out.cpu(), lr, tol,
                                                threads=threads))
@@ -49,7 +49,7 @@ def _run_case(dvp, wl, rho, *, backward, lse_full=True, bits=True, rows=None, th
         ids_s = ids[torch.as_tensor(rows)]
         st = parity.check_side("train", sub.train, zt, ids_s, lr, tol, v, threads=threads)
         si = parity.check_side("infer", sub.infer, zi, ids_s, lr, tol, v, threads=threads)
-        parity.check_flags(sub.row_flags, st["y_in_safe"], si["y_in_safe"], ids_s, v)
+        parity.check_flags(sub.row_flags, st["y_in_safe"], si["y_in_safe"], ids_s, v, train_safe_count=st["safe_count"])
         if backward:
             stats.update(parity.check_gradient("dz", sub.dz, zt, ids_s,
                                                wl.grad_out.cpu()[torch.as_tensor(rows)], lr, tol,
@@ -249,7 +249,7 @@ def test_adversarial_rows(dvp, dtype):
         # fp32 outputs carry half an ulp of |lse| (about 1.5e-5 at 300): widen the bound by it
         st = parity.check_side("train", res.train, z, ids, lr, max(tol, 4e-5), v, threads=2)
         si = parity.check_side("infer", res.infer, zi, ids, lr, max(tol, 4e-5), v, threads=2)
-        parity.check_flags(res.row_flags, st["y_in_safe"], si["y_in_safe"], ids, v)
+        parity.check_flags(res.row_flags, st["y_in_safe"], si["y_in_safe"], ids, v, train_safe_count=st["safe_count"])
         parity.check_gradient("dz", res.dz, z, ids, gout, lr, tol, threads=2)
         if lr == -2.0:
             assert st["safe_count"][0] == v and st["safe_count"][1] == 1 and st["safe_count"][2] == 3
@@ -280,7 +280,7 @@ def test_empty_batch_and_no_infer_side(dvp):
     res = dvp.dvp_forward(wl.z_train, None, wl.ids, lr, lse_full=True, safe_bits=True)
     torch.cuda.synchronize()
     st = parity.check_side("train", res.train, wl.z_train.cpu(), wl.ids.cpu(), lr, 1e-5, 3000)
-    parity.check_flags(res.row_flags, st["y_in_safe"], None, wl.ids.cpu(), 3000)
+    parity.check_flags(res.row_flags, st["y_in_safe"], None, wl.ids.cpu(), 3000, train_safe_count=st["safe_count"])
 
 
 # ---------------------------------------------------------------------------

@@ -70,7 +70,7 @@ def test_small_safe_sets_large_vocab(dvp):
     for side in ("train", "infer"):
         for k in ("logp", "row_max", "lse_safe", "safe_count"):
             assert torch.equal(getattr(getattr(res, side), k), getattr(getattr(ref, side), k)), (side, k)
-    assert torch.equal(res.row_flags & 7, ref.row_flags)
+    assert torch.equal(res.row_flags & 0xF7, ref.row_flags)          # all but the list-overflow bit
     # and the lists scatter to the dense gradient (bf16-rounded there)
     dense = ref.dz.float().cpu()
     for i in (0, 1, 20, 300):

@@ -28,6 +28,13 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # configuration; see profiles/rows_*_hbm_traffic.md for the counter values and scale factors.
 # A run whose sources or configuration have no entry reports "traffic": null, "traffic_stale": true.
 MEASURED_TRAFFIC = {
+    "44788444598978593893fb8db51b79ad57650001c52e05fb0b3c42e3e8ed6c53": {
+        "cfg3/rho=0.0001": 29894904804,                     # profiles/rows_cfg3_hbm_traffic.md
+        "cfg3/rho=0": 29891360775,                          # profiles/rows_cfg3_rho0_hbm_traffic.md
+        "cfg2/rho=0.0001": 7474413643,                      # profiles/rows_cfg2_hbm_traffic.md
+        "cfg3/rho=0.0001/lists=64": 19925261062,            # profiles/rows_cfg3_lists_hbm_traffic.md
+        "cfg3/rho=0.0001/entry=backward": 19422836899,      # profiles/rows_cfg3_backward_hbm_traffic.md
+    },
 }
 
 

@@ -161,13 +161,18 @@ def bench_lmhead(args):
     last = {}
     over_rows = ws_rows = None
     if lists_cap and args.dense_rows:
-        # the rows over the list cap, found once (the inputs do not change between steps; a training loop
-        # reads row_flags back each step or keeps an upper bound), and the workspace of their dense call
+        # The rows over the list cap get their dense gradient from a second call.  Which rows those are, and
+        # how many, stays on the device (dvp_fused_lmhead_select_rows / dvp_fused_lmhead_rows_counted): the
+        # host only provides an upper bound, taken here from one look before the timed region (a training
+        # loop would keep a bound of its own) and rounded up to a whole row tile.
         first = dvp.dvp_fused_lmhead_lists(wl.hidden, wl.w_train, None if f8 else wl.w_infer, wl.ids, wl.grad_out, lr,
                                            lists_cap, workspace=ws, d_hidden=dh, d_w=dw, entries=entries, grad_len=grad_len,
                                            infer_f8=(wl.hidden8, wl.w8, wl.scale_infer) if f8 else None)
         over_rows = torch.nonzero((first.row_flags & dvp.ROW_GRAD_OVERFLOW) != 0).squeeze(1).to(torch.int32)
-        ws_rows = torch.empty(max(int(dvp.lib().dvp_fused_lmhead_rows_workspace_bytes(ctypes.byref(pl), over_rows.numel())), 256),
+        max_rows = max(256, -(-over_rows.numel() // 256) * 256)
+        rows_buf = torch.empty(max_rows, dtype=torch.int32, device="cuda:0")
+        n_sub_dev = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+        ws_rows = torch.empty(max(int(dvp.lib().dvp_fused_lmhead_rows_workspace_bytes(ctypes.byref(pl), max_rows)), 256),
                               dtype=torch.uint8, device="cuda:0")
 
     def step():
@@ -176,8 +181,10 @@ def bench_lmhead(args):
                                                      lists_cap, workspace=ws, d_hidden=dh, d_w=dw, entries=entries,
                                                      grad_len=grad_len,
                                                      infer_f8=(wl.hidden8, wl.w8, wl.scale_infer) if f8 else None)
-            if over_rows is not None and over_rows.numel():
-                dvp.dvp_fused_lmhead_rows(wl.hidden, wl.w_train, wl.ids, wl.grad_out, lr, over_rows, dh, dw, workspace=ws_rows)
+            if over_rows is not None:
+                dvp.dvp_fused_lmhead_select_rows(last["res"].row_flags, dvp.ROW_GRAD_OVERFLOW, rows_buf, n_sub_dev)
+                dvp.dvp_fused_lmhead_rows_counted(wl.hidden, wl.w_train, wl.ids, wl.grad_out, lr, rows_buf, n_sub_dev, dh, dw,
+                                                  workspace=ws_rows)
         elif two_calls:
             fwd, kept = dvp.dvp_fused_lmhead_forward(wl.hidden, wl.w_train, None if f8 else wl.w_infer, wl.ids, lr,
                                                      infer_f8=(wl.hidden8, wl.w8, wl.scale_infer) if f8 else None,
@@ -211,8 +218,8 @@ def bench_lmhead(args):
         passes = 2 + sum(second) / n
         useful, executed = 2 * gemm + 4.0 * listed * d, passes * gemm + 4.0 * listed * d
         n_f8_passes = (1 + second[1] / n) if f8 else 0.0
-        if over_rows is not None:       # the dense call on those rows: its two forward passes and the two gradient products
-            dense = 4.0 * over_rows.numel() / n
+        if over_rows is not None:       # the dense call on those rows: its forward product and the two gradient products
+            dense = 3.0 * over_rows.numel() / n
             passes += dense
             executed += dense * gemm
             useful += 2.0 * over_rows.numel() / n * gemm
@@ -245,7 +252,8 @@ def bench_lmhead(args):
                                   if args.hidden_scale != 1.0 else "")
                                + (", every %d-th row left at scale 1 (flat)" % args.flat_every if args.flat_every else ""),
                    "entry_point": (("dvp_fused_lmhead_lists_f8infer" if f8 else "dvp_fused_lmhead_lists")
-                                   + (" + dvp_fused_lmhead_rows" if over_rows is not None else "")) if lists_cap else
+                                   + (" + dvp_fused_lmhead_select_rows + dvp_fused_lmhead_rows_counted (no host read-back)"
+                                      if over_rows is not None else "")) if lists_cap else
                                   "dvp_fused_lmhead_forward + dvp_fused_lmhead_backward" if two_calls else
                                   "dvp_fused_lmhead_f8infer" if f8 else "dvp_fused_lmhead",
                    "workspace_bytes": ws.numel(), "saved_bytes": saved.numel() if two_calls else 0, **extra},

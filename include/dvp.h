@@ -386,6 +386,30 @@ dvp_status dvp_fused_lmhead_rows(const dvp_lmhead_params *params, const void *hi
                                  size_t workspace_bytes, void *stream);
 
 /*
+ * The same two steps with nothing read back by the host: which rows were flagged, and how many, stays on the
+ * device (Prop. 5.4's gradient of the flagged rows, as dvp_fused_lmhead_rows computes it).
+ *   dvp_fused_lmhead_select_rows   rows[0 .. m) = the rows r < n_rows with (row_flags[r] & mask) != 0 in
+ *              ascending order, m = min(their number, max_rows); the rest of rows[0 .. max_rows) = -1;
+ *              *n_sub = m; *n_flagged (or NULL) = their number, so that a caller can find out afterwards
+ *              whether max_rows was enough.  All DEVICE pointers; rows int32 [max_rows].
+ *   dvp_fused_lmhead_rows_counted  dvp_fused_lmhead_rows with the number of rows[] entries in use read from
+ *              the DEVICE int32 *n_sub (0 <= *n_sub <= max_rows; a larger value counts as max_rows).
+ *              max_rows is the host's upper bound: it sizes the workspace
+ *              (dvp_fused_lmhead_rows_workspace_bytes(params, max_rows)) and the launches, whose
+ *              workgroups find out on the device how far the rows go; with *n_sub = 0 the call changes
+ *              nothing.  Results are identical to dvp_fused_lmhead_rows with n_sub given by the host.
+ * Typical use, all on one stream: dvp_fused_lmhead_lists, dvp_fused_lmhead_select_rows(N, row_flags,
+ * DVP_ROW_GRAD_OVERFLOW, rows, max_rows, n_sub, NULL), dvp_fused_lmhead_rows_counted(..., rows, n_sub, max_rows, ...).
+ */
+dvp_status dvp_fused_lmhead_select_rows(int64_t n_rows, const uint8_t *row_flags, uint32_t mask, int32_t *rows,
+                                        int64_t max_rows, int32_t *n_sub, int32_t *n_flagged, void *stream);
+
+dvp_status dvp_fused_lmhead_rows_counted(const dvp_lmhead_params *params, const void *hidden, const void *w_train,
+                                         const int64_t *ids, const float *grad_out, const int32_t *rows,
+                                         const int32_t *n_sub, int64_t max_rows, float *d_hidden, float *d_w,
+                                         void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * dvp_fused_lmhead_lists with an 8-bit inference engine, the mismatch setting of Sec. 4.2 (bf16 trainer,
  * FP8 rollout engine; see dvp_fused_lmhead_f8infer for `infer`): the inference side's passes run on the
  * fp8 matrix instruction, one pass where rows are peaked.  Declared after dvp_lmhead_f8_side below.

@@ -84,7 +84,21 @@ struct GemmArgs {
     float scale;         // 8-bit operands only: the accumulators are multiplied by it before the epilogue
     // 8-bit (E4M3) operands are described in the same units: two bytes count as one element, so a K
     // step is still 128 bytes of every row and the copy schedule does not change.
+    // A row count that only the device knows (a subset of rows chosen by an earlier kernel): n_dev
+    // non-null says that the launch's rows are rows n_off .. of *n_dev rows in all.  dev_dim = 1: they
+    // are the rows of A, M = clamp(*n_dev - n_off, 0, M) (the launch is sized for M; workgroups without a
+    // tile leave at once); dev_dim = 2: they are the K dimension, K = that count rounded up to a whole row
+    // tile (the operands are zero padded that far); none left: the launch does nothing.
+    const int *n_dev = nullptr;
+    int n_off = 0, dev_dim = 0;
 };
+
+__device__ __forceinline__ int rows_on_device(const int *n_dev, int n_off, int rows_host)
+{
+    if (!n_dev) return rows_host;
+    const int left = *n_dev - n_off;
+    return left < 0 ? 0 : (left > rows_host ? rows_host : left);
+}
 
 // ---------------------------------------------------------------------------
 // epilogues: called once per wavefront with its 64x128 accumulator block.
@@ -469,6 +483,14 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs
         tiles_m = (g.M + BM - 1) / BM;
         if ((int)blockIdx.x >= tiles_m * tiles_n) return;
     }
+    if (g_host.dev_dim == 1) {
+        g.M = rows_on_device(g_host.n_dev, g_host.n_off, g_host.M);
+        tiles_m = (g.M + BM - 1) / BM;
+        if ((int)blockIdx.x >= tiles_m * tiles_n) return;
+    } else if (g_host.dev_dim == 2) {
+        g.K = (rows_on_device(g_host.n_dev, g_host.n_off, g_host.K) + BM - 1) / BM * BM;
+        if (g.K == 0) return;           // (only launched with an accumulating epilogue: nothing to add)
+    }
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave), lane = tid % kWave;
     const int wm = wave / WN, wn = wave % WN;
@@ -778,6 +800,8 @@ struct ZRowArgs {
     uint32_t *bits;          // WRITE_BITS: [rows, bits_ld]
     int64_t bits_ld;
     int vocab, v_pad, side, unit_grad;
+    const int *n_dev;        // see GemmArgs: the launch is sized for an upper bound of the rows
+    int n_off, rows;
 };
 
 template <bool WRITE_E, bool WRITE_BITS>
@@ -787,6 +811,7 @@ __global__ __launch_bounds__(kZRowThreads) void lm_rows_from_z_kernel(const ZRow
     __shared__ float lds_f[2 * NW];
     __shared__ int lds_i[NW];
     const int i = blockIdx.x, tid = threadIdx.x;
+    if (i >= rows_on_device(a.n_dev, a.n_off, a.rows)) return;
     const float m = a.st.m[i], tau = a.st.tau[i];
     const bool want_full = a.out.lse_full != nullptr;
     int64_t y = -1;
@@ -877,8 +902,11 @@ __global__ __launch_bounds__(kAfterRows * kAfterSegs) void after_sum_kernel(RowS
 constexpr int kOnehotThreads = 256;
 constexpr int kOnehotRows = 4096;       // rows per launch: every workgroup scans its launch's sampled tokens
 __global__ __launch_bounds__(kOnehotThreads) void onehot_dw_kernel(const int64_t *ids, const float *coef, const uint16_t *H,
-                                                                   int64_t ld_h, float *dW, int64_t ld_w, int rows, int d)
+                                                                   int64_t ld_h, float *dW, int64_t ld_w, int rows, int d,
+                                                                   const int *n_dev = nullptr, int n_off = 0)
 {
+    rows = rows_on_device(n_dev, n_off, rows);
+    if ((int)blockIdx.x >= rows) return;
     __shared__ int tok[kOnehotRows];    // sampled token per row, -1 where the row contributes nothing
     __shared__ uint16_t match[kOnehotRows];   // rows that sampled this workgroup's token, ascending
     __shared__ int n_match;
@@ -917,10 +945,16 @@ __global__ __launch_bounds__(kOnehotThreads) void onehot_dw_kernel(const int64_t
 // out rows are ld_out long and zero padded up to rows_pad.  64 x 64 tiles, 16-byte accesses on both
 // sides: cols and ld_in are multiples of 8 (cols of 64), rows_pad and ld_out multiples of 64.
 constexpr int kTrTile = 64, kTrThreads = 256;
+// n_dev non-null: the rows are rows n_off .. of *n_dev in all (see GemmArgs); rows and rows_pad are then upper
+// bounds and the padding ends at the next whole row tile.
 __global__ __launch_bounds__(kTrThreads) void transpose_bf16_kernel(const uint16_t *in, int64_t ld_in, uint16_t *out,
                                                                     int64_t ld_out, int rows, int cols, int rows_pad,
-                                                                    const float *scale)
+                                                                    const float *scale, const int *n_dev = nullptr, int n_off = 0)
 {
+    if (n_dev) {
+        rows = rows_on_device(n_dev, n_off, rows);
+        rows_pad = (rows + BM - 1) / BM * BM;
+    }
     __shared__ __attribute__((aligned(16))) uint16_t tile[kTrTile][kTrTile + 8];   // 144-byte rows: 16-byte aligned, skewed banks
     const int r0 = blockIdx.y * kTrTile, c0 = blockIdx.x * kTrTile;
     const int tid = threadIdx.x;
@@ -1095,8 +1129,12 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
                              const float *grad_out, const dvp_side_out *out_train, const dvp_side_out *out_infer,
                              uint8_t *row_flags, float *d_hidden, float *d_w, void *workspace,
                              size_t workspace_bytes, void *stream_, LmPhase phase = LM_FUSED, void *saved = nullptr,
-                             size_t saved_bytes = 0, bool dw_accumulate = false, bool stats_only_ws = false)
+                             size_t saved_bytes = 0, bool dw_accumulate = false, bool stats_only_ws = false,
+                             const int *n_dev = nullptr)
 {
+    // n_dev (device int32): the call's real row count, at most p->n_rows; every launch is sized for p->n_rows
+    // and finds out on the device how far its rows go.  Training side with gradient, accumulated dW only.
+    if (n_dev && (phase != LM_FUSED || !grad_out || !dw_accumulate || stats_only_ws || w_infer || f8)) return DVP_ERR_PARAM;
     if (!p) return DVP_ERR_NULL;
     if (p->log_rho != p->log_rho || p->log_rho > 0.0f) return DVP_ERR_PARAM;
     if (p->n_rows < 0 || p->vocab < 1 || p->hidden < 1 || p->ld_hidden < p->hidden || p->ld_w < p->hidden)
@@ -1179,6 +1217,7 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
         g.A = (const uint16_t *)hidden + (int64_t)r0 * p->ld_hidden; g.lda = p->ld_hidden;
         g.B = (const uint16_t *)w_side[s]; g.ldb = p->ld_w;
         g.M = rows; g.N = v; g.K = d; g.scale = 1.0f;
+        if (n_dev) { g.n_dev = n_dev; g.n_off = r0; g.dev_dim = 1; }
         if (bytes) {   // two bytes count as one element
             g.A = (const uint16_t *)((const uint8_t *)f8->hidden + (int64_t)r0 * f8->ld_hidden); g.lda = f8->ld_hidden / 2;
             g.B = (const uint16_t *)f8->w; g.ldb = f8->ld_w / 2;
@@ -1203,6 +1242,7 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
             za.grad_out = grad_out ? grad_out + r0 : nullptr; za.row_flags = row_flags ? row_flags + r0 : nullptr;
             za.E = E; za.ld_e = lde; za.bits = bits; za.bits_ld = bits_ld;
             za.vocab = v; za.v_pad = L.v_pad; za.side = s; za.unit_grad = phase == LM_FORWARD_SAVE ? 1 : 0;
+            za.n_dev = n_dev; za.n_off = r0; za.rows = rows;
             const dim3 zg((unsigned)rows), zb(kZRowThreads);
             if (write_e) {
                 if (bits) hipLaunchKernelGGL((lm_rows_from_z_kernel<true, true>), zg, zb, 0, stream, za);
@@ -1212,7 +1252,7 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
                 const int rows_pad = (rows + BM - 1) / BM * BM;
                 hipLaunchKernelGGL(transpose_bf16_kernel, dim3((L.v_pad + kTrTile - 1) / kTrTile, (rows_pad + kTrTile - 1) / kTrTile),
                                    dim3(kTrThreads), 0, stream, (const uint16_t *)E, lde, Et, ldet, rows, L.v_pad, rows_pad,
-                                   (const float *)nullptr);
+                                   (const float *)nullptr, n_dev, r0);
             } else {
                 if (bits) hipLaunchKernelGGL((lm_rows_from_z_kernel<false, true>), zg, zb, 0, stream, za);
                 else      hipLaunchKernelGGL((lm_rows_from_z_kernel<false, false>), zg, zb, 0, stream, za);
@@ -1254,12 +1294,13 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
         const uint16_t *hblock = (const uint16_t *)hidden + (int64_t)r0 * p->ld_hidden;
         hipLaunchKernelGGL(transpose_bf16_kernel, dim3((d + kTrTile - 1) / kTrTile, (rows_pad + kTrTile - 1) / kTrTile),
                            dim3(kTrThreads), 0, stream,
-                           hblock, p->ld_hidden, ht, (int64_t)L.block_pad, rows, d, rows_pad, scale);
+                           hblock, p->ld_hidden, ht, (int64_t)L.block_pad, rows, d, rows_pad, scale, n_dev, r0);
         DVP_CHECK_LAUNCH();
         // dH[r0 : r0 + rows, :] = diag(s) . E [rows, v_pad] . (W^T [d, v_pad])^T + diag(q) . W[y, :]
         GemmArgs gh;
         gh.A = E; gh.lda = L.v_pad; gh.B = wt; gh.ldb = L.v_pad;
         gh.M = rows; gh.N = d; gh.K = L.v_pad; gh.scale = 1.0f;
+        if (n_dev) { gh.n_dev = n_dev; gh.n_off = r0; gh.dev_dim = 1; }
         const EpiStore eh{d_hidden + (int64_t)r0 * p->ld_hidden, p->ld_hidden, 0, scale, coef, ids + r0,
                           (const uint16_t *)w_train, p->ld_w};
         if (launch_gemm<EpiStore, false>(gh, eh, stream) != hipSuccess) return DVP_ERR_HIP;
@@ -1267,12 +1308,14 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
         GemmArgs gw;
         gw.A = Et; gw.lda = L.block_pad; gw.B = ht; gw.ldb = L.block_pad;
         gw.M = v; gw.N = d; gw.K = rows_pad; gw.scale = 1.0f;
+        if (n_dev) { gw.n_dev = n_dev; gw.n_off = r0; gw.dev_dim = 2; }
         const EpiStore ew{d_w, p->ld_w, r0 > 0 || dw_accumulate, nullptr, nullptr, nullptr, nullptr, 0};
         if (launch_gemm<EpiStore, false>(gw, ew, stream) != hipSuccess) return DVP_ERR_HIP;
         for (int q0 = 0; q0 < rows; q0 += kOnehotRows) {   // in row order: launches on one stream run in order
             const int qrows = (rows - q0) < kOnehotRows ? (rows - q0) : kOnehotRows;
             hipLaunchKernelGGL(onehot_dw_kernel, dim3(qrows), dim3(kOnehotThreads), 0, stream, ids + r0 + q0,
-                               coef + q0, hblock + (int64_t)q0 * p->ld_hidden, p->ld_hidden, d_w, p->ld_w, qrows, d);
+                               coef + q0, hblock + (int64_t)q0 * p->ld_hidden, p->ld_hidden, d_w, p->ld_w, qrows, d, n_dev,
+                               r0 + q0);
             DVP_CHECK_LAUNCH();
         }
         return DVP_OK;
@@ -1540,9 +1583,12 @@ static LmRowsLayout lm_rows_layout(int64_t n_sub, int64_t d, int64_t v)
     return R;
 }
 
+// n_dev (device int32, nullable): the number of rows[] entries in use; n_sub is then the host's upper bound
+// that sizes the workspace and the launches.
 static dvp_status run_lmhead_rows(const dvp_lmhead_params *p, const void *hidden, const void *w_train,
                                   const int64_t *ids, const float *grad_out, const int32_t *rows, int64_t n_sub,
-                                  float *d_hidden, float *d_w, void *workspace, size_t workspace_bytes, void *stream_)
+                                  float *d_hidden, float *d_w, void *workspace, size_t workspace_bytes, void *stream_,
+                                  const int32_t *n_dev = nullptr)
 {
     if (!p) return DVP_ERR_NULL;
     if (p->log_rho != p->log_rho || p->log_rho > 0.0f) return DVP_ERR_PARAM;
@@ -1562,14 +1608,14 @@ static dvp_status run_lmhead_rows(const dvp_lmhead_params *p, const void *hidden
     a.rows = rows; a.n_sub = (int32_t)n_sub; a.n = (int32_t)p->n_rows; a.d = (int32_t)p->hidden;
     a.H = (const uint16_t *)hidden; a.ld_h = p->ld_hidden; a.ids = ids; a.grad_out = grad_out;
     a.Hc = (uint16_t *)(ws + R.off_h); a.ids_c = (int64_t *)(ws + R.off_ids); a.g_c = (float *)(ws + R.off_g);
-    a.dHc = (float *)(ws + R.off_dh); a.d_hidden = d_hidden;
+    a.dHc = (float *)(ws + R.off_dh); a.d_hidden = d_hidden; a.n_dev = n_dev;
     if (launch_lmhead_rows_gather(a, stream) != hipSuccess) return DVP_ERR_HIP;
     dvp_lmhead_params sub = *p;
     sub.n_rows = n_sub; sub.ld_hidden = p->hidden;
     const dvp_side_out none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
     const dvp_status st = run_lmhead(&sub, a.Hc, w_train, nullptr, nullptr, a.ids_c, a.g_c, &none, nullptr, nullptr, a.dHc,
                                      d_w, ws + R.off_dense, workspace_bytes - R.off_dense, stream_, LM_FUSED, nullptr, 0,
-                                     true);
+                                     true, false, (const int *)n_dev);
     if (st != DVP_OK) return st;
     if (launch_lmhead_rows_scatter(a, stream) != hipSuccess) return DVP_ERR_HIP;
     return DVP_OK;
@@ -1640,6 +1686,27 @@ dvp_status dvp_fused_lmhead_rows(const dvp_lmhead_params *p, const void *hidden,
 {
     return dvp::run_lmhead_rows(p, hidden, w_train, ids, grad_out, rows, n_sub, d_hidden, d_w, workspace, workspace_bytes,
                                 stream);
+}
+
+dvp_status dvp_fused_lmhead_select_rows(int64_t n_rows, const uint8_t *row_flags, uint32_t mask, int32_t *rows,
+                                        int64_t max_rows, int32_t *n_sub, int32_t *n_flagged, void *stream)
+{
+    if (n_rows < 0 || n_rows > (1 << 30) || max_rows < 0 || max_rows > (1 << 30)) return DVP_ERR_SHAPE;
+    if (!n_sub || (n_rows > 0 && !row_flags) || (max_rows > 0 && !rows)) return DVP_ERR_NULL;
+    if (((uintptr_t)rows | (uintptr_t)n_sub | (uintptr_t)n_flagged) % 4) return DVP_ERR_ALIGN;
+    return dvp::launch_lmhead_select_rows(row_flags, mask, n_rows, rows, max_rows, n_sub, n_flagged, (hipStream_t)stream) ==
+                   hipSuccess ? DVP_OK : DVP_ERR_HIP;
+}
+
+dvp_status dvp_fused_lmhead_rows_counted(const dvp_lmhead_params *p, const void *hidden, const void *w_train,
+                                         const int64_t *ids, const float *grad_out, const int32_t *rows,
+                                         const int32_t *n_sub, int64_t max_rows, float *d_hidden, float *d_w,
+                                         void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!n_sub) return DVP_ERR_NULL;
+    if ((uintptr_t)n_sub % 4) return DVP_ERR_ALIGN;
+    return dvp::run_lmhead_rows(p, hidden, w_train, ids, grad_out, rows, max_rows, d_hidden, d_w, workspace, workspace_bytes,
+                                stream, n_sub);
 }
 
 size_t dvp_fused_lmhead_lists_workspace_bytes(const dvp_lmhead_params *p, int32_t list_cap)

@@ -85,8 +85,13 @@ struct LmRowsArgs {
     float *g_c;                   // [n_sub]
     float *dHc;                   // [n_sub, d], written by the dense call in between
     float *d_hidden;              // [n, ld_h]
+    const int32_t *n_dev;         // null, or the device's count of rows[] entries in use (n_sub is then an upper bound)
 };
 hipError_t launch_lmhead_rows_gather(const LmRowsArgs &a, hipStream_t stream);
 hipError_t launch_lmhead_rows_scatter(const LmRowsArgs &a, hipStream_t stream);
+// rows[0 .. min(count, max_rows)) = the rows r < n with (row_flags[r] & mask) != 0, ascending; the rest of
+// rows[] = -1; *n_sub = min(count, max_rows); *n_flagged (nullable) = count
+hipError_t launch_lmhead_select_rows(const uint8_t *row_flags, uint32_t mask, int64_t n, int32_t *rows, int64_t max_rows,
+                                     int32_t *n_sub, int32_t *n_flagged, hipStream_t stream);
 
 }  // namespace dvp

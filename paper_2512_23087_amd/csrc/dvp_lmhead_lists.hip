@@ -395,6 +395,7 @@ __global__ __launch_bounds__(kWave) void lm_subset_gather_kernel(const LmSubsetA
 __global__ __launch_bounds__(kWave) void lm_rows_gather_kernel(const LmRowsArgs a)
 {
     const int j = blockIdx.x, lane = threadIdx.x;
+    if (a.n_dev && j >= *a.n_dev) return;
     const int r = a.rows[j];
     const bool ok = r >= 0 && r < a.n;
     uint16_t *dst = a.Hc + (int64_t)j * a.d;
@@ -409,6 +410,7 @@ __global__ __launch_bounds__(kWave) void lm_rows_gather_kernel(const LmRowsArgs 
 __global__ __launch_bounds__(kWave) void lm_rows_scatter_kernel(const LmRowsArgs a)
 {
     const int j = blockIdx.x, lane = threadIdx.x;
+    if (a.n_dev && j >= *a.n_dev) return;
     const int r = a.rows[j];
     if (r < 0 || r >= a.n) return;
     const float *src = a.dHc + (int64_t)j * a.d;
@@ -416,7 +418,51 @@ __global__ __launch_bounds__(kWave) void lm_rows_scatter_kernel(const LmRowsArgs
     for (int j0 = lane * 4; j0 < a.d; j0 += kWave * 4) *(float4 *)(dst + j0) = *(const float4 *)(src + j0);
 }
 
+// One workgroup: the rows whose flags meet the mask, in row order (a contiguous chunk of rows per thread, a
+// scan of the chunk counts, then each thread writes its chunk's rows); what is left of rows[] becomes -1.
+__global__ __launch_bounds__(kCompactThreads) void lm_select_rows_kernel(const uint8_t *row_flags, uint32_t mask, int64_t n,
+                                                                         int32_t *rows, int64_t max_rows, int32_t *n_sub,
+                                                                         int32_t *n_flagged)
+{
+    __shared__ int part[kCompactThreads];
+    const int tid = threadIdx.x;
+    const int64_t per = (n + kCompactThreads - 1) / kCompactThreads;
+    const int64_t r0 = tid * per < n ? tid * per : n, r1 = (r0 + per) < n ? (r0 + per) : n;
+    int cnt = 0;
+    for (int64_t r = r0; r < r1; ++r) cnt += (row_flags[r] & mask) != 0;
+    part[tid] = cnt;
+    __syncthreads();
+    for (int off = 1; off < kCompactThreads; off <<= 1) {
+        const int add = tid >= off ? part[tid - off] : 0;
+        __syncthreads();
+        part[tid] += add;
+        __syncthreads();
+    }
+    const int total = part[kCompactThreads - 1];
+    int64_t pos = part[tid] - cnt;                       // rows flagged before this thread's chunk
+    for (int64_t r = r0; r < r1; ++r) {
+        if ((row_flags[r] & mask) != 0) {
+            if (pos < max_rows) rows[pos] = (int32_t)r;
+            ++pos;
+        }
+    }
+    const int64_t used = total < max_rows ? total : max_rows;
+    for (int64_t q = used + tid; q < max_rows; q += kCompactThreads) rows[q] = -1;
+    if (tid == 0) {
+        *n_sub = (int32_t)used;
+        if (n_flagged) *n_flagged = total;
+    }
+}
+
 }  // namespace
+
+hipError_t launch_lmhead_select_rows(const uint8_t *row_flags, uint32_t mask, int64_t n, int32_t *rows, int64_t max_rows,
+                                     int32_t *n_sub, int32_t *n_flagged, hipStream_t stream)
+{
+    hipLaunchKernelGGL(lm_select_rows_kernel, dim3(1), dim3(kCompactThreads), 0, stream, row_flags, mask, n, rows, max_rows,
+                       n_sub, n_flagged);
+    return hipGetLastError();
+}
 
 hipError_t launch_lmhead_rows_gather(const LmRowsArgs &a, hipStream_t stream)
 {

@@ -28,7 +28,8 @@ EXPORTS = ("dvp_forward", "dvp_backward", "dvp_forward_backward", "dvp_fused_lmh
            "dvp_fused_lmhead_forward", "dvp_fused_lmhead_backward", "dvp_fused_lmhead_lists",
            "dvp_fused_lmhead_lists_workspace_bytes", "dvp_fused_lmhead_lists_second_pass_rows",
            "dvp_fused_lmhead_lists_f8infer", "dvp_fused_lmhead_rows", "dvp_fused_lmhead_rows_workspace_bytes",
-           "dvp_prepare", "dvp_fused_lmhead_forward_noalloc", "dvp_hbm_probe")
+           "dvp_prepare", "dvp_fused_lmhead_forward_noalloc", "dvp_hbm_probe",
+           "dvp_fused_lmhead_select_rows", "dvp_fused_lmhead_rows_counted")
 
 
 class DvpParams(ctypes.Structure):
@@ -113,6 +114,10 @@ def lib():
         L.dvp_fused_lmhead_rows_workspace_bytes.argtypes = [lp, ctypes.c_int64]
         L.dvp_fused_lmhead_rows.restype = ctypes.c_int
         L.dvp_fused_lmhead_rows.argtypes = [lp, vp, vp, i64p, vp, vp, ctypes.c_int64, vp, vp, vp, ctypes.c_size_t, vp]
+        L.dvp_fused_lmhead_select_rows.restype = ctypes.c_int
+        L.dvp_fused_lmhead_select_rows.argtypes = [ctypes.c_int64, vp, ctypes.c_uint32, vp, ctypes.c_int64, vp, vp, vp]
+        L.dvp_fused_lmhead_rows_counted.restype = ctypes.c_int
+        L.dvp_fused_lmhead_rows_counted.argtypes = [lp, vp, vp, i64p, vp, vp, vp, ctypes.c_int64, vp, vp, vp, ctypes.c_size_t, vp]
         L.dvp_log_rho.restype = ctypes.c_float
         L.dvp_log_rho.argtypes = [ctypes.c_double]
         L.dvp_status_string.restype = ctypes.c_char_p
@@ -536,6 +541,32 @@ def dvp_fused_lmhead_rows(hidden, w_train, ids, grad_out, log_rho_value, rows, d
                                      n_sub, _ptr(d_hidden), _ptr(d_w), _ptr(workspace), workspace.numel(), _stream(stream))
     if st != 0:
         raise DvpError(st, "dvp_fused_lmhead_rows")
+
+
+def dvp_fused_lmhead_select_rows(row_flags, mask, rows, n_sub, *, n_flagged=None, stream=None):
+    """rows (int32 [max_rows], device) <- the rows whose flags meet `mask`, ascending, padded with -1;
+    n_sub (int32 [1], device) <- how many of them are in rows; n_flagged (optional) <- how many there are."""
+    st = lib().dvp_fused_lmhead_select_rows(row_flags.numel(), _ptr(row_flags), int(mask), _ptr(rows), rows.numel(),
+                                            _ptr(n_sub), _ptr(n_flagged), _stream(stream))
+    if st != 0:
+        raise DvpError(st, "dvp_fused_lmhead_select_rows")
+
+
+def dvp_fused_lmhead_rows_counted(hidden, w_train, ids, grad_out, log_rho_value, rows, n_sub, d_hidden, d_w, *,
+                                  workspace: Optional[torch.Tensor] = None, stream=None):
+    """dvp_fused_lmhead_rows with the number of rows[] entries in use read on the device (n_sub: int32 [1])."""
+    n, d = hidden.shape
+    v = w_train.shape[0]
+    p = DvpLmHeadParams(n, d, v, hidden.stride(0), w_train.stride(0), float(log_rho_value))
+    max_rows = rows.numel()
+    if workspace is None:
+        need = int(lib().dvp_fused_lmhead_rows_workspace_bytes(ctypes.byref(p), max_rows))
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=hidden.device)
+    st = lib().dvp_fused_lmhead_rows_counted(ctypes.byref(p), _ptr(hidden), _ptr(w_train), _ptr(ids), _ptr(grad_out),
+                                             _ptr(rows), _ptr(n_sub), max_rows, _ptr(d_hidden), _ptr(d_w), _ptr(workspace),
+                                             workspace.numel(), _stream(stream))
+    if st != 0:
+        raise DvpError(st, "dvp_fused_lmhead_rows_counted")
 
 
 class LmHeadSaved:

@@ -136,6 +136,57 @@ def test_lmhead_list_form_replayed_from_a_graph(dvp):
                 assert torch.equal(getattr(getattr(res, side), k), getattr(getattr(ref, side), k)), (rep, side, k)
 
 
+def test_lists_and_counted_dense_rows_replayed_from_a_graph(dvp):
+    """The list form followed by the dense gradient of its flagged rows, chosen and counted on the device: one
+    captured graph serves inputs with no flagged row, with some, and with others, and matches eager calls."""
+    n, d, v, cap, max_rows = 300, 128, 3000, 64, 80
+    wl = workloads.make_lmhead(device="cuda", n=n, d=d, v=v, hidden_scale=60.0)
+    lr = dvp.log_rho(1e-4)
+    import ctypes
+    p = dvp.DvpLmHeadParams(n, d, v, d, d, lr)
+    nbytes = int(dvp.lib().dvp_fused_lmhead_lists_workspace_bytes(ctypes.byref(p), cap))
+    rbytes = int(dvp.lib().dvp_fused_lmhead_rows_workspace_bytes(ctypes.byref(p), max_rows))
+    hidden = wl.hidden.clone()
+    variants = [wl.hidden.clone() for _ in range(3)]
+    variants[1][::29] = (variants[1][::29].float() * 0.05).to(torch.bfloat16)
+    variants[2][5::17] = (variants[2][5::17].float() * 0.05).to(torch.bfloat16)
+
+    def buffers():
+        return dict(ws=torch.empty(nbytes, dtype=torch.uint8, device="cuda"), wr=torch.empty(rbytes, dtype=torch.uint8, device="cuda"),
+                    d_hidden=torch.empty(n, d, device="cuda"), d_w=torch.empty(v, d, device="cuda"),
+                    entries=torch.zeros(n, cap, 2, dtype=torch.int32, device="cuda"),
+                    grad_len=torch.empty(n, dtype=torch.int32, device="cuda"),
+                    rows=torch.empty(max_rows, dtype=torch.int32, device="cuda"),
+                    n_sub=torch.empty(1, dtype=torch.int32, device="cuda"))
+
+    def run(b):
+        res = dvp.dvp_fused_lmhead_lists(hidden, wl.w_train, wl.w_infer, wl.ids, wl.grad_out, lr, cap, workspace=b["ws"],
+                                         d_hidden=b["d_hidden"], d_w=b["d_w"], entries=b["entries"], grad_len=b["grad_len"])
+        dvp.dvp_fused_lmhead_select_rows(res.row_flags, dvp.ROW_GRAD_OVERFLOW, b["rows"], b["n_sub"])
+        dvp.dvp_fused_lmhead_rows_counted(hidden, wl.w_train, wl.ids, wl.grad_out, lr, b["rows"], b["n_sub"], b["d_hidden"],
+                                          b["d_w"], workspace=b["wr"])
+        return res
+
+    eager, graph = buffers(), buffers()
+    run(eager)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        res_g = run(graph)
+    counts = []
+    for rep in (0, 1, 2, 0):
+        hidden.copy_(variants[rep])
+        res_e = run(eager)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        counts.append(int(graph["n_sub"].item()))
+        assert graph["n_sub"].item() == eager["n_sub"].item() == int(((res_e.row_flags & 8) != 0).sum().item())
+        assert torch.equal(graph["d_hidden"], eager["d_hidden"]) and torch.equal(graph["d_w"], eager["d_w"]), rep
+        assert torch.equal(res_g.row_flags, res_e.row_flags)
+    assert counts[0] == 0 and counts[1] > 5 and counts[2] > 5 and counts[1] != counts[2] and counts[3] == 0
+
+
 def test_concurrent_callers_on_their_own_streams(dvp):
     """The library keeps no state between calls: host threads with a stream each get the same results
     as one thread."""

@@ -315,6 +315,78 @@ def test_lists_then_dense_rows_give_the_whole_gradient(dvp):
     assert np.abs(ot["d_hidden"][dense_rows]).max() > 0
 
 
+def test_flagged_rows_chosen_and_counted_on_the_device(dvp):
+    """The same two steps with no read-back: dvp_fused_lmhead_select_rows lists the flagged rows and counts them
+    on the device, dvp_fused_lmhead_rows_counted sizes its launches for an upper bound and finds the count
+    there.  Results are identical to the host-counted call, for a bound well above the count, for a bound
+    equal to it, for inputs without a flagged row, and for more than one row block's worth of bound."""
+    n, d, v, cap = 520, 128, 3000, 64
+    wl = workloads.make_lmhead(device="cuda", n=n, d=d, v=v, hidden_scale=60.0)
+    peaked = wl.hidden.clone()
+    wl.hidden[::13] = (wl.hidden[::13].float() * 0.05).to(torch.bfloat16)
+    lr = dvp.log_rho(1e-4)
+
+    def lists(hidden):
+        r = dvp.dvp_fused_lmhead_lists(hidden, wl.w_train, None, wl.ids, wl.grad_out, lr, cap)
+        torch.cuda.synchronize()
+        return r
+
+    ref = lists(wl.hidden)
+    over = torch.nonzero((ref.row_flags & dvp.ROW_GRAD_OVERFLOW) != 0).squeeze(1).to(torch.int32)
+    dvp.dvp_fused_lmhead_rows(wl.hidden, wl.w_train, wl.ids, wl.grad_out, lr, over, ref.d_hidden, ref.d_w)
+    torch.cuda.synchronize()
+    for max_rows in (over.numel(), 100, 300):
+        res = lists(wl.hidden)
+        rows = torch.full((max_rows,), 12345, dtype=torch.int32, device="cuda")
+        n_sub = torch.full((1,), -5, dtype=torch.int32, device="cuda")
+        n_flag = torch.full((1,), -5, dtype=torch.int32, device="cuda")
+        dvp.dvp_fused_lmhead_select_rows(res.row_flags, dvp.ROW_GRAD_OVERFLOW, rows, n_sub, n_flagged=n_flag)
+        dvp.dvp_fused_lmhead_rows_counted(wl.hidden, wl.w_train, wl.ids, wl.grad_out, lr, rows, n_sub, res.d_hidden, res.d_w)
+        torch.cuda.synchronize()
+        assert n_sub.item() == over.numel() == n_flag.item()
+        assert torch.equal(rows[:over.numel()], over) and torch.all(rows[over.numel():] == -1)
+        assert torch.equal(res.d_hidden, ref.d_hidden) and torch.equal(res.d_w, ref.d_w), max_rows
+    # a bound below the count: the first rows only, and the true count is still reported
+    rows = torch.empty(7, dtype=torch.int32, device="cuda")
+    dvp.dvp_fused_lmhead_select_rows(ref.row_flags, dvp.ROW_GRAD_OVERFLOW, rows, n_sub, n_flagged=n_flag)
+    torch.cuda.synchronize()
+    assert n_sub.item() == 7 and n_flag.item() == over.numel() and torch.equal(rows, over[:7])
+    # no flagged row: the counted call changes nothing
+    res = lists(peaked)
+    assert not ((res.row_flags & dvp.ROW_GRAD_OVERFLOW) != 0).any()
+    dh0, dw0 = res.d_hidden.clone(), res.d_w.clone()
+    rows = torch.empty(64, dtype=torch.int32, device="cuda")
+    dvp.dvp_fused_lmhead_select_rows(res.row_flags, dvp.ROW_GRAD_OVERFLOW, rows, n_sub)
+    dvp.dvp_fused_lmhead_rows_counted(peaked, wl.w_train, wl.ids, wl.grad_out, lr, rows, n_sub, res.d_hidden, res.d_w)
+    torch.cuda.synchronize()
+    assert n_sub.item() == 0 and torch.equal(res.d_hidden, dh0) and torch.equal(res.d_w, dw0)
+
+
+def test_flagged_rows_beyond_one_row_block(dvp):
+    """An upper bound of more than 8192 rows (two row blocks of the dense call), the count inside the first
+    block or reaching into the second: identical to the host-counted call."""
+    n, d, v = 9000, 64, 700
+    wl = workloads.make_lmhead(device="cuda", n=n, d=d, v=v)
+    lr = dvp.log_rho(1e-4)
+    for count in (300, 8400):
+        flags = torch.zeros(n, dtype=torch.uint8, device="cuda")
+        pick = torch.randperm(n, device="cuda", generator=torch.Generator(device="cuda").manual_seed(count))[:count]
+        flags[pick] = 8
+        chosen = torch.nonzero(flags != 0).squeeze(1).to(torch.int32)
+        dh_ref = torch.zeros(n, d, device="cuda")
+        dw_ref = torch.zeros(v, d, device="cuda")
+        dvp.dvp_fused_lmhead_rows(wl.hidden, wl.w_train, wl.ids, wl.grad_out, lr, chosen, dh_ref, dw_ref)
+        dh, dw = torch.zeros(n, d, device="cuda"), torch.zeros(v, d, device="cuda")
+        rows = torch.empty(n, dtype=torch.int32, device="cuda")
+        n_sub = torch.zeros(1, dtype=torch.int32, device="cuda")
+        dvp.dvp_fused_lmhead_select_rows(flags, 8, rows, n_sub)
+        dvp.dvp_fused_lmhead_rows_counted(wl.hidden, wl.w_train, wl.ids, wl.grad_out, lr, rows, n_sub, dh, dw)
+        torch.cuda.synchronize()
+        assert n_sub.item() == count
+        assert torch.equal(dh, dh_ref) and torch.equal(dw, dw_ref), count
+        assert dh_ref.abs().max().item() > 0
+
+
 def test_many_rows(dvp):
     """100,000 token rows of a small head: 256 row blocks of 391 rows in the column-major copy, several
     rows per thread in the compaction of the second-pass rows."""

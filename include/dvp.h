@@ -182,9 +182,15 @@ dvp_status dvp_backward(const dvp_params *params, const void *z_train, const int
                         void *stream);
 
 /*
- * Forward and backward in one launch: every training row is read from HBM
+ * Forward and backward in one call: every training row is read from HBM
  * once, every inference row once, every gradient row written once.
  * Arguments as in dvp_forward plus grad_out and dz as in dvp_backward.
+ * When row_flags and out_train->safe_count are given, log_rho is finite and the
+ * gradient matrix has at least dvp_set_split_min_bytes() bytes, rows with a short
+ * safe set (or without gradient) are finished by two write-only kernels after the
+ * row kernel (one burst of zeros instead of zeros mixed into the reads); smaller
+ * matrices, and every matrix when nothing is pruned, are written by the row kernel
+ * alone.  The values are the same either way.
  */
 dvp_status dvp_forward_backward(const dvp_params *params, const void *z_train,
                                 const void *z_infer, const int64_t *ids, const float *grad_out,
@@ -536,6 +542,16 @@ dvp_status dvp_hbm_probe(int mode, const void *a, const void *b, void *c, int64_
  * Returns DVP_OK, or DVP_ERR_HIP when the runtime refuses a query (no usable device).
  */
 dvp_status dvp_prepare(void);
+
+/*
+ * Size in bytes from which dvp_forward_backward writes the gradient in two steps (see there).  Process-wide
+ * tuning value, host only: bytes >= 0 sets it (0: always, INT64_MAX: never) and returns the previous value,
+ * bytes < 0 only returns the current one.  Default DVP_SPLIT_MIN_BYTES_DEFAULT: below about half a
+ * gigabyte the two extra launches cost more than the separate burst of writes saves (measured at
+ * V = 32000 and V = 151936, bf16).
+ */
+#define DVP_SPLIT_MIN_BYTES_DEFAULT ((int64_t)512 << 20)
+int64_t dvp_set_split_min_bytes(int64_t bytes);
 
 /* (float)log(threshold) for threshold > 0; NaN otherwise.  Host only. */
 float dvp_log_threshold(double threshold);

@@ -2,6 +2,7 @@
 // Every entry point only validates, fills an argument block and enqueues work
 // on the caller's stream; nothing here allocates or synchronises.
 #include <math.h>
+#include <atomic>
 
 #include "dvp_internal.h"
 
@@ -71,6 +72,9 @@ bool rows_vector_ok(const dvp_params *p, const void *z_train, const void *z_infe
     return true;
 }
 
+// gradient matrices smaller than this are written by the row kernel alone (dvp_set_split_min_bytes)
+std::atomic<int64_t> g_split_min_bytes{DVP_SPLIT_MIN_BYTES_DEFAULT};
+
 dvp_status run_rows(const dvp_params *p, const void *z_train, const void *z_infer,
                     const int64_t *ids, const float *grad_out, const dvp_side_out *out_train,
                     const dvp_side_out *out_infer, uint8_t *row_flags, void *dz, bool backward,
@@ -110,9 +114,13 @@ dvp_status run_rows(const dvp_params *p, const void *z_train, const void *z_infe
     if (a.finite_mask && (a.out[0].entropy || a.out[1].entropy)) return DVP_ERR_UNSUPPORTED;   // defined for the exact rule only
     const bool resident = !a.finite_mask && dvp::row_fits_resident(p->dtype, dtype_infer, p->vocab) &&
                           rows_vector_ok(p, z_train, z_infer, backward ? dz : nullptr);
-    // Split gradient: possible when the per-row flags and safe-set sizes are
-    // produced anyway (the fill kernel reads them back).
-    a.split_grad = (resident && backward && row_flags && a.out[0].safe_count) ? 1 : 0;
+    // Split gradient (rows with a short safe set leave a list, two write-only kernels finish them): possible
+    // when the per-row flags and safe-set sizes are produced anyway (the fill kernel reads them back), and
+    // worth it when rows can be short at all (with log_rho = -inf none is) and the gradient matrix is large:
+    // below the limit the two extra launches cost more than the separate write burst saves.
+    const int64_t grad_bytes = backward ? p->n_rows * p->vocab * (int64_t)es : 0;
+    a.split_grad = (resident && backward && row_flags && a.out[0].safe_count && p->log_rho != -INFINITY &&
+                    grad_bytes >= g_split_min_bytes.load(std::memory_order_relaxed)) ? 1 : 0;
     const int64_t cap = (int64_t)(p->vocab * es / 8) - 2;
     a.list_cap = (int32_t)(cap < 0 ? 0 : (cap > dvp::kListMax ? dvp::kListMax : cap));
     hipError_t e = resident ? dvp::launch_rows_resident(p->dtype, dtype_infer, a, (hipStream_t)stream)
@@ -287,6 +295,12 @@ float dvp_log_threshold(double threshold)
 {
     if (!(threshold > 0.0)) return NAN;
     return (float)log(threshold);
+}
+
+int64_t dvp_set_split_min_bytes(int64_t bytes)
+{
+    if (bytes < 0) return g_split_min_bytes.load(std::memory_order_relaxed);
+    return g_split_min_bytes.exchange(bytes, std::memory_order_relaxed);
 }
 
 int dvp_row_path(const dvp_params *params, int aligned16)

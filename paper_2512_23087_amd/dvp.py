@@ -29,7 +29,7 @@ EXPORTS = ("dvp_forward", "dvp_backward", "dvp_forward_backward", "dvp_fused_lmh
            "dvp_fused_lmhead_lists_workspace_bytes", "dvp_fused_lmhead_lists_second_pass_rows",
            "dvp_fused_lmhead_lists_f8infer", "dvp_fused_lmhead_rows", "dvp_fused_lmhead_rows_workspace_bytes",
            "dvp_prepare", "dvp_fused_lmhead_forward_noalloc", "dvp_hbm_probe",
-           "dvp_fused_lmhead_select_rows", "dvp_fused_lmhead_rows_counted")
+           "dvp_fused_lmhead_select_rows", "dvp_fused_lmhead_rows_counted", "dvp_set_split_min_bytes")
 
 
 class DvpParams(ctypes.Structure):
@@ -135,6 +135,8 @@ def lib():
         L.dvp_log_threshold.argtypes = [ctypes.c_double]
         L.dvp_prepare.restype = ctypes.c_int
         L.dvp_prepare.argtypes = []
+        L.dvp_set_split_min_bytes.restype = ctypes.c_int64
+        L.dvp_set_split_min_bytes.argtypes = [ctypes.c_int64]
         L.dvp_hbm_probe.restype = ctypes.c_int
         L.dvp_hbm_probe.argtypes = [ctypes.c_int, vp, vp, vp, ctypes.c_int64, ctypes.c_int64, vp]
         L.dvp_fused_lmhead_forward_noalloc.restype = ctypes.c_int
@@ -145,6 +147,15 @@ def lib():
 
 def status_string(status: int) -> str:
     return lib().dvp_status_string(int(status)).decode()
+
+
+SPLIT_MIN_BYTES_DEFAULT = 512 << 20
+
+
+def set_split_min_bytes(nbytes: int) -> int:
+    """Gradient size from which dvp_forward_backward writes the gradient in two steps; returns the
+    previous value (a negative argument only reads it).  See dvp_set_split_min_bytes in dvp.h."""
+    return int(lib().dvp_set_split_min_bytes(int(nbytes)))
 
 
 def prepare() -> None:

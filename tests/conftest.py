@@ -27,3 +27,13 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture(params=["two_steps", "one_step"])
+def gradient_steps(request):
+    """Both ways dvp_forward_backward has of writing the gradient, whatever the size of the matrix
+    (by default the size decides: dvp_set_split_min_bytes in include/dvp.h)."""
+    from paper_2512_23087_amd import dvp
+    old = dvp.set_split_min_bytes(0 if request.param == "two_steps" else 2 ** 63 - 1)
+    yield request.param
+    dvp.set_split_min_bytes(old)

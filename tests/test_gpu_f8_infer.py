@@ -30,6 +30,15 @@ def dvp():
     return binding
 
 
+@pytest.fixture(autouse=True, scope="module")
+def _small_gradients_in_two_steps_too(dvp):
+    # the test matrices are far below the size from which the gradient is written in two steps: force that
+    # way for the module (tests that take `gradient_steps` run both ways, the full-size ones the default)
+    old = dvp.set_split_min_bytes(0)
+    yield
+    dvp.set_split_min_bytes(old)
+
+
 def _codes(t):
     """uint8 view of an fp8 tensor on the host (what the oracle takes)."""
     return t.view(torch.uint8).cpu().contiguous()
@@ -110,7 +119,7 @@ def test_every_code_is_widened_exactly(dvp):
     (16, 16, 16), (33, 40, 48), (1001, 1008, 1008), (4096, 4096, 4096), (5000, 5000, 5008),
     (12345, 12352, 12352), (32000, 32000, 32000), (40000, 40000, 40000), (70001, 70008, 70016),
     (100000, 100000, 100000), (131072, 131072, 131072), (151936, 151936, 151936), (163840, 163840, 163840)])
-def test_shapes_single_read_path(dvp, v, ld_t, ld_i):
+def test_shapes_single_read_path(dvp, v, ld_t, ld_i, gradient_steps):
     n = 5 if v > 20000 else 9
     wl = _case(n, v, seed=v, ld_t=ld_t, ld_i=ld_i)
     p = dvp.DvpParams(n, v, ld_t, ld_i, ld_t, 1, -1.0, 2)
@@ -154,7 +163,7 @@ def test_shapes_rereading_path(dvp, train_dtype, v):
         _run(dvp, wl, rho, threads=3)
 
 
-def test_config1_recipe_with_byte_inference_logits(dvp):
+def test_config1_recipe_with_byte_inference_logits(dvp, gradient_steps):
     """configs[1]: the inference logits of that recipe are E4M3 values already; stored as bytes they
     give the same numbers as stored as bf16."""
     wl = workloads.make_rows(1, device="cuda", n=192)

@@ -19,6 +19,15 @@ def dvp():
     return binding
 
 
+@pytest.fixture(autouse=True, scope="module")
+def _small_gradients_in_two_steps_too(dvp):
+    # the test matrices are far below the size from which the gradient is written in two steps: force that
+    # way for the module (tests that take `gradient_steps` run both ways, the full-size ones the default)
+    old = dvp.set_split_min_bytes(0)
+    yield
+    dvp.set_split_min_bytes(old)
+
+
 def _run_case(dvp, wl, rho, *, backward, lse_full=True, bits=True, rows=None, threads=8):
     lr = dvp.log_rho(rho)
     assert lr == float(parity.orc.log_rho_f32(rho))      # one shared fp32 constant
@@ -89,14 +98,14 @@ def test_config0_fp32_forward_full_size(dvp):
     assert st["train"]["safe_count"].min() > 100     # the spike recipe keeps thousands of tokens
 
 
-def test_config1_bf16_forward_backward(dvp):
+def test_config1_bf16_forward_backward(dvp, gradient_steps):
     wl = workloads.make_rows(1, device="cuda", n=192)
     st = _run_case(dvp, wl, 1e-4, backward=True)
     assert st["err_grad"] <= 1.0
 
 
 @pytest.mark.parametrize("rho", [1e-4, math.exp(-13.0)])
-def test_config2_heavy_tail_large_vocab(dvp, rho):
+def test_config2_heavy_tail_large_vocab(dvp, rho, gradient_steps):
     wl = workloads.make_rows(2, device="cuda", n=80)
     st = _run_case(dvp, wl, rho, backward=True)
     # rows with a uniformly drawn token: (nearly) all outside the safe set, gradient row zero
@@ -106,7 +115,7 @@ def test_config2_heavy_tail_large_vocab(dvp, rho):
 
 
 @pytest.mark.parametrize("rho", [1e-2, 1e-4, 1e-6, 0.0])
-def test_config3_threshold_sweep(dvp, rho):
+def test_config3_threshold_sweep(dvp, rho, gradient_steps):
     wl = workloads.make_rows(3, device="cuda", n=48)
     st = _run_case(dvp, wl, rho, backward=True)
     if rho == 0.0:
@@ -141,7 +150,7 @@ def _random_case(n, v, dtype, seed, device="cuda", ld=None, offset=0):
 
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
 @pytest.mark.parametrize("v", [1, 2, 7, 8, 16, 33, 1000, 2047, 4104, 8200, 20001, 33000, 70003])
-def test_shapes_resident_path(dvp, dtype, v):
+def test_shapes_resident_path(dvp, dtype, v, gradient_steps):
     n = 5 if v > 20000 else 9
     es = 2 if dtype == torch.bfloat16 else 4
     ld = (v * es + 15) // 16 * 16 // es          # 16-byte aligned rows -> single-read kernel
@@ -200,7 +209,7 @@ def test_shapes_streaming_path_misaligned(dvp, dtype, v):
     (torch.float32, 4 * 1024 * 20 + 4, None),
     (torch.float32, 151936, None),                    # fp32 logits at the 152k vocabulary
     (torch.float32, 100003, 100004)])
-def test_rows_longer_than_the_register_file(dvp, dtype, v, ld):
+def test_rows_longer_than_the_register_file(dvp, dtype, v, ld, gradient_steps):
     """The first 1024 x 20 vectors of a row stay in registers, the rest is re-read in every phase by the
     same kernel: every output and both gradient forms (lists for short safe sets, dense rows) to the
     usual bars, membership bits included."""
@@ -223,7 +232,7 @@ def test_rows_longer_than_the_register_file(dvp, dtype, v, ld):
 # degenerate rows
 # ---------------------------------------------------------------------------
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
-def test_adversarial_rows(dvp, dtype):
+def test_adversarial_rows(dvp, dtype, gradient_steps):
     v = 4104
     rows = []
     rows.append(torch.full((v,), -3.25))                       # all equal: every token safe
@@ -256,7 +265,7 @@ def test_adversarial_rows(dvp, dtype):
             assert st["y_in_safe"][5] == 1        # boundary token is inside (Def. 5.1 uses >=)
 
 
-def test_out_of_range_ids_are_flagged_not_faulted(dvp):
+def test_out_of_range_ids_are_flagged_not_faulted(dvp, gradient_steps):
     wl = _random_case(6, 1000, torch.bfloat16, seed=5)
     ids = wl.ids.clone()
     ids[1] = -1
@@ -348,13 +357,21 @@ def _full_size_check(dvp, wl, rho, rows, bits_rows=256):
     return out, res
 
 
-def test_config1_full_size_every_row(dvp):
+@pytest.fixture
+def default_gradient_steps(dvp):
+    # the full-size tests run the configuration the benchmark times: the size decides how the gradient is written
+    old = dvp.set_split_min_bytes(dvp.SPLIT_MIN_BYTES_DEFAULT)
+    yield
+    dvp.set_split_min_bytes(old)
+
+
+def test_config1_full_size_every_row(dvp, default_gradient_steps):
     wl = workloads.make_rows(1, device="cuda")            # 2048 x 32000 bf16, thousands of safe tokens per row
-    out, _ = _full_size_check(dvp, wl, 1e-4, None)
+    out, _ = _full_size_check(dvp, wl, 1e-4, None)        # (a 131 MB gradient: written by the row kernel alone)
     assert out["rows_checked"] == 2048
 
 
-def test_config2_full_size_one_row_in_eight(dvp):
+def test_config2_full_size_one_row_in_eight(dvp, default_gradient_steps):
     wl = workloads.make_rows(2, device="cuda")            # 8192 x 151936 bf16
     n, v = wl.z_train.shape
     rows = np.arange(0, n, 8)                             # 1024 rows; every fifth of them has a forced (uniform) token
@@ -379,7 +396,7 @@ def test_config2_full_size_one_row_in_eight(dvp):
     torch.cuda.empty_cache()
 
 
-def test_config3_full_size_every_threshold(dvp):
+def test_config3_full_size_every_threshold(dvp, default_gradient_steps):
     """The workload the headline figure is quoted on (32768 x 151936 bf16), at each of its four thresholds:
     2048 rows of the full-size call against the oracle, and nested safe sets across the thresholds."""
     wl = workloads.make_rows(3, device="cuda")
@@ -398,7 +415,7 @@ def test_config3_full_size_every_threshold(dvp):
 
 
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
-def test_rows_on_both_sides_of_the_list_capacity(dvp, dtype):
+def test_rows_on_both_sides_of_the_list_capacity(dvp, dtype, gradient_steps):
     """Gaussian logits whose safe sets straddle the 64-token list capacity: some rows leave a list
     for the fill kernels, the others are written densely by the row kernel, in one call."""
     n, v = 48, 40000

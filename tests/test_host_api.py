@@ -322,6 +322,9 @@ int main(void)
     CHECK(dvp_fused_lmhead(&lp, NULL, NULL, NULL, NULL, NULL, &out, NULL, NULL, NULL, NULL, NULL, 0, NULL) == DVP_ERR_UNSUPPORTED);
     CHECK(dvp_sequence_weights(-1, 1, NULL, NULL, NULL, -9.0f, NULL, NULL, NULL, NULL, NULL) == DVP_ERR_SHAPE);
     CHECK(sizeof(dvp_grad_entry) == 8);
+    CHECK(dvp_set_split_min_bytes(-1) == DVP_SPLIT_MIN_BYTES_DEFAULT);
+    CHECK(dvp_set_split_min_bytes(0) == DVP_SPLIT_MIN_BYTES_DEFAULT);
+    CHECK(dvp_set_split_min_bytes(DVP_SPLIT_MIN_BYTES_DEFAULT) == 0);
     printf("ok\n");
     return 0;
 }
@@ -350,3 +353,11 @@ def test_header_is_plain_c11_and_host_entry_points_work_from_c(tmp_path):
 def test_prepare_is_a_host_call():
     """dvp_prepare touches no data: DVP_OK with a usable GPU, DVP_ERR_HIP without one, never a crash."""
     assert dvp.lib().dvp_prepare() in (0, 7)
+
+
+def test_split_limit_is_a_process_wide_setting():
+    """dvp_set_split_min_bytes: a negative argument reads, anything else sets and returns the value before."""
+    assert dvp.set_split_min_bytes(-1) == dvp.SPLIT_MIN_BYTES_DEFAULT
+    assert dvp.set_split_min_bytes(12345) == dvp.SPLIT_MIN_BYTES_DEFAULT
+    assert dvp.set_split_min_bytes(-7) == 12345
+    assert dvp.set_split_min_bytes(dvp.SPLIT_MIN_BYTES_DEFAULT) == 12345

@@ -28,10 +28,11 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # configuration; see profiles/rows_*_hbm_traffic.md for the counter values and scale factors.
 # A run whose sources or configuration have no entry reports "traffic": null, "traffic_stale": true.
 MEASURED_TRAFFIC = {
-    "44788444598978593893fb8db51b79ad57650001c52e05fb0b3c42e3e8ed6c53": {
+    "5965ad63298d46e121c343d4e79450cd80ae973c1ea9272fd3ac9be139a8e91a": {
         "cfg3/rho=0.0001": 29894904804,                     # profiles/rows_cfg3_hbm_traffic.md
-        "cfg3/rho=0": 29891360775,                          # profiles/rows_cfg3_rho0_hbm_traffic.md
+        "cfg3/rho=0": 29888220865,                          # profiles/rows_cfg3_rho0_hbm_traffic.md
         "cfg2/rho=0.0001": 7474413643,                      # profiles/rows_cfg2_hbm_traffic.md
+        "cfg1/rho=0.0001": 394667252,                       # profiles/rows_cfg1_hbm_traffic.md
         "cfg3/rho=0.0001/lists=64": 19925261062,            # profiles/rows_cfg3_lists_hbm_traffic.md
         "cfg3/rho=0.0001/entry=backward": 19422836899,      # profiles/rows_cfg3_backward_hbm_traffic.md
     },
@@ -41,7 +42,7 @@ MEASURED_TRAFFIC = {
 def kernel_source_hash() -> str:
     import hashlib
     h = hashlib.sha256()
-    for name in ("dvp_rows.hip", "dvp_device.h", "dvp_internal.h"):
+    for name in ("dvp_rows.hip", "dvp_device.h", "dvp_internal.h", "dvp_api.hip"):
         with open(os.path.join(ROOT, "paper_2512_23087_amd", "csrc", name), "rb") as f:
             h.update(f.read())
     return h.hexdigest()

@@ -830,7 +830,7 @@ __device__ __forceinline__ bool backward_row_is_zero_filled(const BackwardArgs &
     return a.split && (!backward_has_gradient(a, fl) || (fl & DVP_ROW_SHORT_SAFE_SET) != 0);
 }
 
-constexpr int kBwdZeroThreads = 1024, kBwdZeroVecs = 2;
+constexpr int kBwdZeroThreads = 256, kBwdZeroVecs = 1;     // see the zero kernel of the gradient fill
 template <typename T, bool VEC>
 __global__ __launch_bounds__(kBwdZeroThreads) void backward_zero_kernel(const BackwardArgs a, int chunks_per_row)
 {
@@ -846,7 +846,7 @@ __global__ __launch_bounds__(kBwdZeroThreads) void backward_zero_kernel(const Ba
 #pragma unroll
         for (int u = 0; u < kBwdZeroVecs; ++u) {
             const int idx = (chunk * kBwdZeroVecs + u) * kBwdZeroThreads + threadIdx.x;
-            if (idx < nvec) ((u32x4 *)dzrow)[idx] = zero;
+            if (idx < nvec) __builtin_nontemporal_store(zero, (u32x4 *)dzrow + idx);
         }
         if (chunk == chunks_per_row - 1) {
             const int k = nvec * EPV + threadIdx.x;
@@ -935,15 +935,24 @@ __global__ __launch_bounds__(NT) void backward_kernel(const BackwardArgs a)
 
 // ---------------------------------------------------------------------------
 // gradient fill: finishes the rows the resident kernel left as lists.
-//   zero kernel     one workgroup per 16 KB chunk of a row, in memory order:
+//   zero kernel     one workgroup per 4 KB chunk of a row, in memory order:
 //                   writes zeros everywhere except over the row's list.  Apart
 //                   from two words per chunk it only writes, so HBM sees one
 //                   long burst of stores instead of stores mixed into reads.
 //   scatter kernel  one workgroup per row: reads the list, zeroes the bytes it
 //                   occupied, drops the values in place.
+// Shape of the zero kernels (this one, backward_zero_kernel, lists_zero_kernel): 256 threads, one
+// nontemporal 16-byte store each.  How fast a write-only kernel drains depends on how its stores are paced,
+// not only on how many there are: with 8 small workgroups per CU, each waiting for its row's information
+// (about a microsecond) before its single store, stores are issued at about the rate HBM takes them.
+// Measured on 32768 x 151936 bf16 (9.96 GB), stand-alone, same row lookup: 256 x 1 nontemporal 1.44 ms
+// (6.9 TB/s), 512 x 1 nontemporal 1.55, 1024 x 2 nontemporal 1.67, 1024 x 2 plain stores 1.75 (what this
+// kernel used first), 256 x 1 plain stores 2.1; in the fused call 4.56 ms against 4.80 ms.  The price: a
+// row the row kernel wrote itself now costs 75 workgroups that look it up and leave instead of 10
+// (+3 % on a call whose rows are all dense).
 // ---------------------------------------------------------------------------
-constexpr int kZeroThreads = 1024;     // measured best among 64..1024 threads x 1..16 stores per thread
-constexpr int kFillVecPerThread = 2;   // 32 KB per workgroup amortises the row-info lookup
+constexpr int kZeroThreads = 256;
+constexpr int kFillVecPerThread = 1;
 constexpr int kFillChunk = kZeroThreads * kFillVecPerThread;   // vectors per workgroup
 constexpr int kFillThreads = 256;      // scatter kernel
 
@@ -973,7 +982,7 @@ __global__ __launch_bounds__(kZeroThreads) void grad_zero_kernel(const FillArgs 
 #pragma unroll
     for (int u = 0; u < kFillVecPerThread; ++u) {
         const int idx = chunk * kFillChunk + u * kZeroThreads + threadIdx.x;
-        if (idx >= first && idx < nvec) dzvec[idx] = zero;
+        if (idx >= first && idx < nvec) __builtin_nontemporal_store(zero, dzvec + idx);
     }
     if (chunk == chunks_per_row - 1) {          // ragged end of the row (a list never reaches the last 16 bytes)
         const int k = nvec * EPV + threadIdx.x;
@@ -1010,7 +1019,7 @@ __global__ __launch_bounds__(kFillThreads) void grad_scatter_kernel(const FillAr
 // write-only kernels: zeros over every row that has a list (rows flagged as overflowing are left to
 // the caller of the launcher), then one workgroup per row drops the scaled values in place.
 // ---------------------------------------------------------------------------
-constexpr int kListsZeroThreads = 1024, kListsZeroVecs = 2;
+constexpr int kListsZeroThreads = 256, kListsZeroVecs = 1;   // see the zero kernel of the gradient fill
 template <typename T, bool VEC>
 __global__ __launch_bounds__(kListsZeroThreads) void lists_zero_kernel(const ListsArgs a, int chunks_per_row)
 {
@@ -1026,7 +1035,7 @@ __global__ __launch_bounds__(kListsZeroThreads) void lists_zero_kernel(const Lis
 #pragma unroll
         for (int u = 0; u < kListsZeroVecs; ++u) {
             const int idx = (chunk * kListsZeroVecs + u) * kListsZeroThreads + threadIdx.x;
-            if (idx < nvec) ((u32x4 *)dzrow)[idx] = zero;
+            if (idx < nvec) __builtin_nontemporal_store(zero, (u32x4 *)dzrow + idx);
         }
         if (chunk == chunks_per_row - 1) {
             const int k = nvec * EPV + threadIdx.x;

@@ -28,13 +28,13 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # configuration; see profiles/rows_*_hbm_traffic.md for the counter values and scale factors.
 # A run whose sources or configuration have no entry reports "traffic": null, "traffic_stale": true.
 MEASURED_TRAFFIC = {
-    "5965ad63298d46e121c343d4e79450cd80ae973c1ea9272fd3ac9be139a8e91a": {
-        "cfg3/rho=0.0001": 29894904804,                     # profiles/rows_cfg3_hbm_traffic.md
-        "cfg3/rho=0": 29888220865,                          # profiles/rows_cfg3_rho0_hbm_traffic.md
-        "cfg2/rho=0.0001": 7474413643,                      # profiles/rows_cfg2_hbm_traffic.md
-        "cfg1/rho=0.0001": 394667252,                       # profiles/rows_cfg1_hbm_traffic.md
-        "cfg3/rho=0.0001/lists=64": 19925261062,            # profiles/rows_cfg3_lists_hbm_traffic.md
-        "cfg3/rho=0.0001/entry=backward": 19422836899,      # profiles/rows_cfg3_backward_hbm_traffic.md
+    "71b5ffbd96474e94f6ed13f9ab79d80cb73cdb4b66dfa98240e54f23f30e6117": {
+        "cfg3/rho=0.0001": 29902097257,                     # profiles/rows_cfg3_hbm_traffic.md
+        "cfg3/rho=0": 29888018094,                          # profiles/rows_cfg3_rho0_hbm_traffic.md
+        "cfg2/rho=0.0001": 7476724585,                      # profiles/rows_cfg2_hbm_traffic.md
+        "cfg1/rho=0.0001": 394668532,                       # profiles/rows_cfg1_hbm_traffic.md
+        "cfg3/rho=0.0001/lists=64": 19929263163,            # profiles/rows_cfg3_lists_hbm_traffic.md
+        "cfg3/rho=0.0001/entry=backward": 19429795740,      # profiles/rows_cfg3_backward_hbm_traffic.md
     },
 }
 

@@ -948,7 +948,11 @@ __global__ __launch_bounds__(kOnehotThreads) void onehot_dw_kernel(const int64_t
 // out[c, r] = bf16(scale[r] * in[r, c]) (scale null: a plain copy) for r < rows, c < cols;
 // out rows are ld_out long and zero padded up to rows_pad.  64 x 64 tiles, 16-byte accesses on both
 // sides: cols and ld_in are multiples of 8 (cols of 64), rows_pad and ld_out multiples of 64.
-constexpr int kTrTile = 64, kTrThreads = 256;
+// The tile is transposed on its way INTO LDS (two-byte writes, pitch 66 halfwords: two lanes per bank),
+// so that on the way out eight neighbouring lanes hold the 128 bytes of one output row and a wavefront's
+// store covers eight whole lines (written as 64 separate 16-byte pieces per store, the output ran at
+// 3.2 TB/s for read plus write).
+constexpr int kTrTile = 64, kTrThreads = 256, kTrPitch = kTrTile + 2;
 // n_dev non-null: the rows are rows n_off .. of *n_dev in all (see GemmArgs); rows and rows_pad are then upper
 // bounds and the padding ends at the next whole row tile.
 __global__ __launch_bounds__(kTrThreads) void transpose_bf16_kernel(const uint16_t *in, int64_t ld_in, uint16_t *out,
@@ -959,39 +963,39 @@ __global__ __launch_bounds__(kTrThreads) void transpose_bf16_kernel(const uint16
         rows = rows_on_device(n_dev, n_off, rows);
         rows_pad = (rows + BM - 1) / BM * BM;
     }
-    __shared__ __attribute__((aligned(16))) uint16_t tile[kTrTile][kTrTile + 8];   // 144-byte rows: 16-byte aligned, skewed banks
+    __shared__ __attribute__((aligned(16))) uint16_t tile[kTrTile * kTrPitch];   // tile[c][r]
     const int r0 = blockIdx.y * kTrTile, c0 = blockIdx.x * kTrTile;
     const int tid = threadIdx.x;
 #pragma unroll
     for (int k = 0; k < kTrTile * 8 / kTrThreads; ++k) {
         const int p = tid + k * kTrThreads, r = p >> 3, ch = p & 7;
         const int row = r0 + r;
-        u32x4 v = {0u, 0u, 0u, 0u};
+        uint32_t w[4] = {0u, 0u, 0u, 0u};
         if (row < rows && c0 + ch * 8 < cols) {
-            v = *(const u32x4 *)(in + (int64_t)row * ld_in + c0 + ch * 8);
+            const u32x4 v = *(const u32x4 *)(in + (int64_t)row * ld_in + c0 + ch * 8);
+            w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
             if (scale) {
                 const float sc = scale[row];
-                uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const float lo = sc * __uint_as_float(w[i] << 16), hi = sc * __uint_as_float(w[i] & 0xffff0000u);
                     w[i] = f32_to_bf16_rne(lo) | (f32_to_bf16_rne(hi) << 16);
                 }
-                v = (u32x4){w[0], w[1], w[2], w[3]};
             }
         }
-        *(u32x4 *)&tile[r][ch * 8] = v;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            tile[(ch * 8 + 2 * i) * kTrPitch + r] = (uint16_t)w[i];
+            tile[(ch * 8 + 2 * i + 1) * kTrPitch + r] = (uint16_t)(w[i] >> 16);
+        }
     }
     __syncthreads();
 #pragma unroll
     for (int k = 0; k < kTrTile * 8 / kTrThreads; ++k) {
-        const int p = tid + k * kTrThreads, c = p & 63, ch = p >> 6;   // lanes of a wavefront: 64 columns, one row chunk
-        if (c0 + c >= cols || r0 + ch * 8 >= rows_pad) continue;
-        uint32_t w[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            w[i] = (uint32_t)tile[ch * 8 + 2 * i][c] | ((uint32_t)tile[ch * 8 + 2 * i + 1][c] << 16);
-        *(u32x4 *)(out + (int64_t)(c0 + c) * ld_out + r0 + ch * 8) = (u32x4){w[0], w[1], w[2], w[3]};
+        const int q = tid + k * kTrThreads, c = q >> 3, rc = q & 7;   // eight lanes: the 128 bytes of one output row
+        if (c0 + c >= cols || r0 + rc * 8 >= rows_pad) continue;
+        const uint32_t *src = (const uint32_t *)(tile + c * kTrPitch + rc * 8);   // 4-byte aligned
+        *(u32x4 *)(out + (int64_t)(c0 + c) * ld_out + r0 + rc * 8) = (u32x4){src[0], src[1], src[2], src[3]};
     }
 }
 

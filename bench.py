@@ -650,10 +650,15 @@ def bench_rows(args):
             return median(pl)
         mat = n * v * elem
         t_read, t_fill, t_rows = probe(dvp.PROBE_READ), probe(dvp.PROBE_FILL), probe(dvp.PROBE_ROWS_2R1W)
+        t_wide, t_once = probe(dvp.PROBE_FILL_WIDE), probe(dvp.PROBE_READ_ONESHOT)
         read_gbs, fill_gbs, rows_gbs = 2 * mat / t_read / 1e6, mat / t_fill / 1e6, 3 * mat / t_rows / 1e6
         result["stream_ceiling"] = {
             "what": "streaming kernels without arithmetic over this workload's own matrices (dvp_hbm_probe), median of 10 launches",
             "read_two_matrices_gbs": read_gbs, "fill_one_matrix_gbs": fill_gbs, "rows_2_reads_1_write_gbs": rows_gbs,
+            # the same bytes in other shapes: a fill from 1024-thread workgroups with two plain stores each (slower), and
+            # reads by workgroups that take 16 KB and leave (faster; not a shape a kernel that keeps a row in one CU's
+            # registers can have)
+            "fill_wide_workgroups_gbs": mat / t_wide / 1e6, "read_oneshot_workgroups_gbs": 2 * mat / t_once / 1e6,
             # a call whose row kernel only reads and whose gradient is written by a write-only kernel: 2 parts read, 1 part filled
             "separate_phases_frac_of_peak": 3.0 / (2.0 / read_gbs + 1.0 / fill_gbs) / HBM_PEAK_GBS,
             # a call whose row kernel writes every gradient row itself (dense rows: no pruning, flat logits)

@@ -528,8 +528,14 @@ dvp_status dvp_sequence_weights(int64_t n_tokens, int64_t n_seq, const float *lo
  *   DVP_PROBE_ROWS_2R1W  one workgroup per CU walks the rows: b's row into registers, then a's row, then a's
  *                        row out to c: reads and writes interleaved the way a densely written gradient
  *                        interleaves them; row_bytes at most 19 * 16384 (DVP_ERR_UNSUPPORTED beyond)
+ *   DVP_PROBE_FILL_WIDE  the fill again, from workgroups of 1024 threads with two plain stores each instead of
+ *                        256 threads with one nontemporal store: the same bytes, drained more slowly (how a
+ *                        write-only kernel's stores are paced matters; the zero kernels use the fast shape)
+ *   DVP_PROBE_READ_ONESHOT  a, then b, read by workgroups that take 16 KB each and leave, where
+ *                        DVP_PROBE_READ keeps a few workgroups per CU walking the matrices the way the row
+ *                        kernel (which holds a row in one CU's registers) has to
  */
-enum { DVP_PROBE_READ = 0, DVP_PROBE_FILL = 1, DVP_PROBE_ROWS_2R1W = 2 };
+enum { DVP_PROBE_READ = 0, DVP_PROBE_FILL = 1, DVP_PROBE_ROWS_2R1W = 2, DVP_PROBE_FILL_WIDE = 3, DVP_PROBE_READ_ONESHOT = 4 };
 dvp_status dvp_hbm_probe(int mode, const void *a, const void *b, void *c, int64_t n_rows, int64_t row_bytes,
                          void *stream);
 

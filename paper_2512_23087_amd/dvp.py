@@ -165,12 +165,12 @@ def prepare() -> None:
         raise DvpError(st, "dvp_prepare")
 
 
-PROBE_READ, PROBE_FILL, PROBE_ROWS_2R1W = 0, 1, 2
+PROBE_READ, PROBE_FILL, PROBE_ROWS_2R1W, PROBE_FILL_WIDE, PROBE_READ_ONESHOT = 0, 1, 2, 3, 4
 
 
 def hbm_probe(mode: int, a, b, c, *, stream=None) -> None:
     """A streaming kernel without arithmetic over [N, row] matrices (see dvp_hbm_probe in dvp.h)."""
-    ref = c if mode == PROBE_FILL else a
+    ref = c if mode in (PROBE_FILL, PROBE_FILL_WIDE) else a
     st = lib().dvp_hbm_probe(int(mode), _ptr(a), _ptr(b), _ptr(c), ref.shape[0], ref.stride(0) * ref.element_size(),
                              _stream(stream))
     if st != 0:

@@ -322,6 +322,10 @@ int main(void)
     CHECK(dvp_fused_lmhead(&lp, NULL, NULL, NULL, NULL, NULL, &out, NULL, NULL, NULL, NULL, NULL, 0, NULL) == DVP_ERR_UNSUPPORTED);
     CHECK(dvp_sequence_weights(-1, 1, NULL, NULL, NULL, -9.0f, NULL, NULL, NULL, NULL, NULL) == DVP_ERR_SHAPE);
     CHECK(sizeof(dvp_grad_entry) == 8);
+    CHECK(dvp_hbm_probe(9, NULL, NULL, NULL, 1, 16, NULL) == DVP_ERR_PARAM);
+    CHECK(dvp_hbm_probe(DVP_PROBE_FILL, NULL, NULL, NULL, 1, 16, NULL) == DVP_ERR_NULL);
+    CHECK(dvp_hbm_probe(DVP_PROBE_FILL_WIDE, NULL, NULL, NULL, 1, 24, NULL) == DVP_ERR_SHAPE);
+    CHECK(dvp_hbm_probe(DVP_PROBE_READ_ONESHOT, NULL, NULL, NULL, 0, 16, NULL) == DVP_OK);
     CHECK(dvp_set_split_min_bytes(-1) == DVP_SPLIT_MIN_BYTES_DEFAULT);
     CHECK(dvp_set_split_min_bytes(0) == DVP_SPLIT_MIN_BYTES_DEFAULT);
     CHECK(dvp_set_split_min_bytes(DVP_SPLIT_MIN_BYTES_DEFAULT) == 0);

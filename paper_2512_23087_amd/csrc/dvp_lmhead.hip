@@ -33,6 +33,7 @@ namespace dvp {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x8 __attribute__((ext_vector_type(8)));
 
@@ -103,7 +104,7 @@ __device__ __forceinline__ int rows_on_device(const int *n_dev, int n_off, int r
 // ---------------------------------------------------------------------------
 // epilogues: called once per wavefront with its 64x128 accumulator block.
 // Element (mi, ni, i) of lane l is row r0 + mi*32 + (i/4)*8 + (l/32)*4 + i%4,
-// column c0 + ni*32 + l%32 of the launch's output.  `lds` is the workgroup's
+// column c0 + ni*32 + l%32 of the launch's output (kSwapped epilogues: see EpiMax).  `lds` is the workgroup's
 // dynamic LDS: the operand tiles (dead by now) and, behind them, the scratch of
 // pass B's sums.
 // ---------------------------------------------------------------------------
@@ -114,36 +115,48 @@ template <bool STORE_Z>
 struct EpiMax {
     static constexpr bool kUsesTileLds = false;
     static constexpr bool kRowMap = false;
+    // The products of this epilogue are taken with the operands swapped (the B fragment is the matrix
+    // instruction's row operand): element (mi, ni, i) of lane l is then token row r0 + mi*32 + l%32 and
+    // vocabulary column c0 + ni*32 + (i/4)*8 + (l/32)*4 + i%4.  A lane owns one token row per mi and
+    // four consecutive columns per register quad: the row maximum is 63 in-lane maxima and one exchange
+    // with lane l ^ 32 (the column-per-lane layout needs five exchanges for each of 32 rows and 32 atomic
+    // instructions of two lanes each), the sampled token's id is loaded once per lane, and the logits
+    // leave as 16-byte stores.  Measured on the forward product of configs[4] (9.44 ms per block of 8192
+    // rows with the column-per-lane epilogue): 0.57 ms of it were the maxima, 0.85 ms the 4-byte stores.
+    static constexpr bool kSwapped = true;
     RowStats st;
     const int64_t *ids;
-    float *Z;
+    float *Z;            // [rows padded to BM, ldz]; ldz covers whole column tiles, so every tile element has a place
     int64_t ldz;
     __device__ __forceinline__ void operator()(const GemmArgs &g, f32x16 (&acc)[MI][NI], int r0, int c0, int lane, uint8_t *, int, int) const
     {
+        const int half = lane / 32;
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
+            const int row = r0 + mi * 32 + (lane % 32);
+            const bool row_ok = row < g.M;
+            const int64_t y = row_ok ? ids[row] : -1;
+            // the sampled token's column inside this wavefront's NI * 32 columns, or -1 (columns past N repeat
+            // column N - 1 and are never the sampled one: y < N)
+            const int yc = (y >= (int64_t)c0 && y < (int64_t)c0 + NI * 32) ? (int)(y - c0) : -1;
+            float v = -INFINITY;
+            float *zrow = Z + (int64_t)row * ldz + c0;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int row = r0 + mi * 32 + (i / 4) * 8 + (lane / 32) * 4 + (i % 4);
-                const bool row_ok = row < g.M;
-                const int64_t y = row_ok ? ids[row] : -1;
-                float v = -INFINITY;
+            for (int ni = 0; ni < NI; ++ni) {
 #pragma unroll
-                for (int ni = 0; ni < NI; ++ni) {
-                    const int col = c0 + ni * 32 + (lane % 32);
-                    const float z = acc[mi][ni][i];
-                    if (col < g.N) {
-                        v = fmaxf(v, z);
-                        if (row_ok && (int64_t)col == y) st.zy[row] = z;
-                        if constexpr (STORE_Z) {
-                            if (row_ok) __builtin_nontemporal_store(z, Z + (int64_t)row * ldz + col);
-                        }
+                for (int q = 0; q < 4; ++q) {
+                    const int colb = ni * 32 + q * 8 + half * 4;
+                    const float z0 = acc[mi][ni][q * 4], z1 = acc[mi][ni][q * 4 + 1], z2 = acc[mi][ni][q * 4 + 2],
+                                z3 = acc[mi][ni][q * 4 + 3];
+                    v = fmaxf(fmaxf(v, fmaxf(z0, z1)), fmaxf(z2, z3));    // (repeated columns repeat a real logit)
+                    if (yc >= colb && yc < colb + 4) st.zy[row] = yc == colb ? z0 : (yc == colb + 1 ? z1 : (yc == colb + 2 ? z2 : z3));
+                    if constexpr (STORE_Z) {
+                        if (row_ok) *(f32x4 *)(zrow + colb) = (f32x4){z0, z1, z2, z3};
                     }
                 }
-#pragma unroll
-                for (int off = 16; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
-                if ((lane % 32) == 0 && row_ok) atomicMax(st.max_key + row, float_to_ordered(v));
             }
+            v = fmaxf(v, __shfl_xor(v, 32, kWave));
+            if (half == 0 && row_ok) atomicMax(st.max_key + row, float_to_ordered(v));
         }
     }
 };
@@ -157,6 +170,7 @@ struct EpiMax {
 struct EpiMaxCand {
     static constexpr bool kUsesTileLds = false;
     static constexpr bool kRowMap = false;
+    static constexpr bool kSwapped = false;
     RowStats st;
     const int64_t *ids;
     const float *zy_low;     // [n] lower bound of the row maximum, -inf where there is none
@@ -240,6 +254,7 @@ template <bool WRITE_E, bool WRITE_BITS = false, bool WRITE_LIST = false, bool R
 struct EpiSum {
     static constexpr bool kUsesTileLds = WRITE_E;   // the bf16 staging lives in the operand tiles
     static constexpr bool kRowMap = ROWMAP;
+    static constexpr bool kSwapped = false;
     RowStats st;
     int n_rows;
     const int64_t *ids;      // WRITE_E: the sampled token's own entry of E is stored as zero
@@ -392,6 +407,7 @@ struct EpiSum {
 struct EpiStore {
     static constexpr bool kUsesTileLds = false;
     static constexpr bool kRowMap = false;
+    static constexpr bool kSwapped = false;
     float *C;                // [M, ldc] fp32
     int64_t ldc;
     int accumulate;          // 0: C = v, 1: C += v
@@ -580,8 +596,9 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs
             for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni)   // formats 0, 0: E4M3 x E4M3; zero scale operands: the unscaled instruction
-                    acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fa8[buf][mi], fb8[buf][ni], acc[mi][ni],
-                                                                                 0, 0, 0, 0, 0, 0);
+                    acc[mi][ni] = Epi::kSwapped
+                        ? __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb8[buf][ni], fa8[buf][mi], acc[mi][ni], 0, 0, 0, 0, 0, 0)
+                        : __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fa8[buf][mi], fb8[buf][ni], acc[mi][ni], 0, 0, 0, 0, 0, 0);
             // twelve 16-byte LDS reads of the next pair between these eight MFMAs
 #pragma unroll
             for (int i = 0; i < MI * NI / 2; ++i) {
@@ -599,7 +616,9 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni)
-                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][mi], fb[buf][ni], acc[mi][ni], 0, 0, 0);
+                acc[mi][ni] = Epi::kSwapped   // (both operands have the same lane layout: 32 rows x 8 k per half)
+                    ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][ni], fa[buf][mi], acc[mi][ni], 0, 0, 0)
+                    : __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][mi], fb[buf][ni], acc[mi][ni], 0, 0, 0);
         // scheduling hint: spread the LDS reads of the next slice between this slice's MFMAs
         constexpr int NM = MI * NI, NR = MI + NI, PER = NM / NR;
 #pragma unroll

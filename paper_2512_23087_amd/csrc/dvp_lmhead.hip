@@ -844,7 +844,7 @@ __global__ __launch_bounds__(kZRowThreads) void lm_rows_from_z_kernel(const ZRow
     RowSums acc = {0.0f, 0.0f, 0};
 #pragma unroll 2
     for (int u = tid; u < units; u += kZRowThreads) {
-        const u32x4 lo = __builtin_nontemporal_load(zrow + 2 * u), hi = __builtin_nontemporal_load(zrow + 2 * u + 1);
+        const u32x4 lo = zrow[2 * u], hi = zrow[2 * u + 1];
         const float x[8] = {__uint_as_float(lo.x), __uint_as_float(lo.y), __uint_as_float(lo.z), __uint_as_float(lo.w),
                             __uint_as_float(hi.x), __uint_as_float(hi.y), __uint_as_float(hi.z), __uint_as_float(hi.w)};
         const int col0 = u * 8;

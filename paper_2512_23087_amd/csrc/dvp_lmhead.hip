@@ -407,7 +407,7 @@ struct EpiSum {
 struct EpiStore {
     static constexpr bool kUsesTileLds = false;
     static constexpr bool kRowMap = false;
-    static constexpr bool kSwapped = false;
+    static constexpr bool kSwapped = true;    // a lane owns an output row and four consecutive columns: see EpiMax
     float *C;                // [M, ldc] fp32
     int64_t ldc;
     int accumulate;          // 0: C = v, 1: C += v
@@ -418,35 +418,54 @@ struct EpiStore {
     int64_t ld_src;
     __device__ __forceinline__ void operator()(const GemmArgs &g, f32x16 (&acc)[MI][NI], int r0, int c0, int lane, uint8_t *, int, int) const
     {
+        const int half = lane / 32;
+        // 16-byte accesses when the output rows allow them (the same for every lane), single elements otherwise
+        const bool vec = ((((uintptr_t)C) | (uintptr_t)(ldc * 4)) & 15u) == 0 && (g.N & 3) == 0;
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
+            const int row = r0 + mi * 32 + (lane % 32);
+            const bool row_ok = row < g.M;
+            float *crow = C + (int64_t)(row_ok ? row : 0) * ldc + c0;
+            const float sc = (row_ok && row_scale) ? row_scale[row] : 1.0f;
+            const float co = (row_ok && row_coef) ? row_coef[row] : 0.0f;
+            const uint16_t *srow = co != 0.0f ? src + ids[row] * ld_src + c0 : nullptr;
             // accumulate: fetch the block's old values first, all loads in flight together
-            float old[16][NI];
+            f32x4 old[NI][4];
             if (accumulate) {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int row = r0 + mi * 32 + (i / 4) * 8 + (lane / 32) * 4 + (i % 4);
+                for (int ni = 0; ni < NI; ++ni) {
 #pragma unroll
-                    for (int ni = 0; ni < NI; ++ni) {
-                        const int col = c0 + ni * 32 + (lane % 32);
-                        old[i][ni] = (row < g.M && col < g.N) ? C[(int64_t)row * ldc + col] : 0.0f;
+                    for (int q = 0; q < 4; ++q) {
+                        const int colb = ni * 32 + q * 8 + half * 4;
+                        old[ni][q] = (f32x4){0.0f, 0.0f, 0.0f, 0.0f};
+                        if (!row_ok || c0 + colb >= g.N) continue;
+                        if (vec) old[ni][q] = *(const f32x4 *)(crow + colb);
+                        else {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) old[ni][q][e] = c0 + colb + e < g.N ? crow[colb + e] : 0.0f;
+                        }
                     }
                 }
             }
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int row = r0 + mi * 32 + (i / 4) * 8 + (lane / 32) * 4 + (i % 4);
-                if (row >= g.M) continue;
-                const float sc = row_scale ? row_scale[row] : 1.0f;
-                const float co = row_coef ? row_coef[row] : 0.0f;
-                const uint16_t *srow = co != 0.0f ? src + ids[row] * ld_src : nullptr;
+            for (int ni = 0; ni < NI; ++ni) {
 #pragma unroll
-                for (int ni = 0; ni < NI; ++ni) {
-                    const int col = c0 + ni * 32 + (lane % 32);
-                    if (col >= g.N) continue;
-                    float v = sc * acc[mi][ni][i];
-                    if (srow) v += co * __uint_as_float((uint32_t)srow[col] << 16);
-                    C[(int64_t)row * ldc + col] = accumulate ? old[i][ni] + v : v;
+                for (int q = 0; q < 4; ++q) {
+                    const int colb = ni * 32 + q * 8 + half * 4;
+                    if (!row_ok || c0 + colb >= g.N) continue;
+                    f32x4 v;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        v[e] = sc * acc[mi][ni][q * 4 + e];
+                        if (srow && c0 + colb + e < g.N) v[e] += co * __uint_as_float((uint32_t)srow[colb + e] << 16);
+                        if (accumulate) v[e] += old[ni][q][e];
+                    }
+                    if (vec) *(f32x4 *)(crow + colb) = v;
+                    else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (c0 + colb + e < g.N) crow[colb + e] = v[e];
+                    }
                 }
             }
         }

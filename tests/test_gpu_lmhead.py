@@ -165,6 +165,25 @@ def test_many_column_tiles(dvp):
     res2, _, _ = _run(dvp, wl, math.exp(-13.0))
 
 
+def test_gradient_outputs_at_four_byte_alignment(dvp):
+    """dH and dW buffers that are only 4-byte aligned take the element-wise stores of the output epilogue instead of
+    the 16-byte ones: same values, bit for bit; d = 192 leaves the last column tile of dH / dW ragged."""
+    wl = workloads.make_lmhead(device="cuda", n=8192 + 300, d=192, v=700)     # two row blocks: dW is accumulated
+    lr = dvp.log_rho(1e-2)
+    n, d, v = wl.hidden.shape[0], wl.hidden.shape[1], wl.w_train.shape[0]
+    ref = dvp.dvp_fused_lmhead(wl.hidden, wl.w_train, wl.w_infer, wl.ids, wl.grad_out, lr)
+    base_h = torch.full((n * d + 8,), float("nan"), dtype=torch.float32, device="cuda")
+    base_w = torch.full((v * d + 8,), float("nan"), dtype=torch.float32, device="cuda")
+    dh = base_h[1:1 + n * d].view(n, d)
+    dw = base_w[3:3 + v * d].view(v, d)
+    assert dh.data_ptr() % 16 == 4 and dw.data_ptr() % 16 == 12
+    got = dvp.dvp_fused_lmhead(wl.hidden, wl.w_train, wl.w_infer, wl.ids, wl.grad_out, lr, d_hidden=dh, d_w=dw)
+    torch.cuda.synchronize()
+    assert torch.equal(got.d_hidden, ref.d_hidden) and torch.equal(got.d_w, ref.d_w)
+    assert torch.isnan(base_h[0]) and torch.isnan(base_h[1 + n * d:]).all()      # nothing written outside
+    assert torch.isnan(base_w[:3]).all() and torch.isnan(base_w[3 + v * d:]).all()
+
+
 def test_forward_only_and_train_only(dvp):
     wl = workloads.make_lmhead(device="cuda", n=130, d=64, v=777)
     lr = dvp.log_rho(1e-3)

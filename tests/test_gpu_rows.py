@@ -396,6 +396,61 @@ def test_config2_full_size_one_row_in_eight(dvp, default_gradient_steps):
     torch.cuda.empty_cache()
 
 
+def _every_row_properties(wl, res, lr, chunk=1024):
+    """What holds on every row whatever the size (Def. 5.1 / 5.2, Prop. 5.4), from the call's own outputs with torch
+    on the GPU (no oracle): the safe set recounted from tau = fl32(m + log_rho) has the reported size, the pruned
+    probabilities exp(z - lse_safe) over it sum to one, the gradient is zero outside it and sums to
+    g (1 - sum of the pruned probabilities) ~ 0 over the row, and its entry at the sampled token is g (1 - p_y)."""
+    n, v = wl.z_train.shape
+    lr32 = torch.tensor(lr, dtype=torch.float32, device="cuda")
+    worst = dict(prob_sum=0.0, grad_sum=0.0, grad_y=0.0)
+    for r0 in range(0, n, chunk):
+        r1 = min(n, r0 + chunk)
+        z = wl.z_train[r0:r1].float()
+        m = res.train.row_max[r0:r1]
+        assert torch.equal(m, z.max(dim=1).values)
+        tau = (m + lr32).unsqueeze(1)                                        # one fp32 add, as in the kernel
+        safe = z >= tau
+        assert torch.equal(safe.sum(dim=1).to(torch.int32), res.train.safe_count[r0:r1])
+        p = torch.where(safe, torch.exp(z.double() - res.train.lse_safe[r0:r1].double().unsqueeze(1)), torch.zeros((), dtype=torch.float64, device="cuda"))
+        # lse_safe is an fp32 number near the row maximum (hundreds here): exp(z - lse_safe) carries its half unit
+        lse_ulp = res.train.lse_safe[r0:r1].double().abs() * 2.0 ** -23 + 1e-6
+        worst["prob_sum"] = max(worst["prob_sum"], ((p.sum(dim=1) - 1.0).abs() / lse_ulp).max().item())
+        dz = res.dz[r0:r1].double()
+        ys = (res.row_flags[r0:r1] & 1).bool()
+        assert torch.count_nonzero(dz[~safe]).item() == 0                    # zero outside the safe set
+        assert torch.count_nonzero(dz[~ys]).item() == 0                      # and on rows whose sampled token is pruned
+        g = wl.grad_out[r0:r1].double()
+        scale = g.abs().clamp(min=1.0)
+        worst["grad_sum"] = max(worst["grad_sum"], (dz.sum(dim=1).abs() / scale)[ys].max().item())
+        y = wl.ids[r0:r1]
+        py = p.gather(1, y.unsqueeze(1)).squeeze(1)
+        dzy = dz.gather(1, y.unsqueeze(1)).squeeze(1)
+        worst["grad_y"] = max(worst["grad_y"], ((dzy - g * (1.0 - py)).abs() / scale)[ys].max().item())
+        del z, safe, p, dz
+    return worst
+
+
+def test_config3_full_size_properties_on_every_row(dvp, default_gradient_steps):
+    """Every one of the 32768 rows of the workload the headline figure is quoted on, at the headline threshold and
+    with nothing pruned: the any-size properties above (bf16 gradient entries are rounded to 8 bits, so a row's
+    gradient sums to zero within the roundings of its few large entries)."""
+    wl = workloads.make_rows(3, device="cuda")
+    for rho in (1e-4, 0.0):
+        lr = dvp.log_rho(rho)
+        res = dvp.dvp_forward_backward(wl.z_train, wl.z_infer, wl.ids, wl.grad_out, lr)
+        torch.cuda.synchronize()
+        w = _every_row_properties(wl, res, lr)
+        print("rho %g: |sum p - 1| <= %.2f units of lse_safe, |sum dz| / max(1,|g|) <= %.2e, |dz_y - g (1 - p_y)| / max(1,|g|) <= %.2e"
+              % (rho, w["prob_sum"], w["grad_sum"], w["grad_y"]))
+        assert w["prob_sum"] <= 1.0                # within one unit in the last place of the fp32 lse_safe
+        assert w["grad_sum"] <= 2.0 ** -6          # the roundings of the row's few entries of magnitude up to |g| (2^-8 each)
+        assert w["grad_y"] <= 2.0 ** -8 + 1e-6     # one bf16 rounding (half a unit of 8 bits) of an entry of magnitude at most |g|
+        del res
+    del wl
+    torch.cuda.empty_cache()
+
+
 def test_config3_full_size_every_threshold(dvp, default_gradient_steps):
     """The workload the headline figure is quoted on (32768 x 151936 bf16), at each of its four thresholds:
     2048 rows of the full-size call against the oracle, and nested safe sets across the thresholds."""

@@ -424,12 +424,12 @@ dvp_status dvp_fused_lmhead_rows_counted(const dvp_lmhead_params *params, const 
 /*
  * The LM-head variant in two calls, for callers that learn grad_out only after the forward (with
  * importance weights dL/dlogp depends on the log-probs).  Prop. 5.4's gradient is linear in grad_out, so
- * the forward leaves the masked exponentials of the training side (bf16, both orientations, every row
- * block) and two factors per row in `saved`, and the backward turns them into dH and dW with two
- * matrix products per row block: six GEMM passes in all, as in the fused call, and results identical to
- * it.
+ * the forward leaves the masked exponentials of the training side (bf16, every row block) and two
+ * factors per row in `saved`, and the backward turns them into dH and dW with two
+ * matrix products per row block: the same GEMM passes as the fused call (one per side for the logits, two
+ * for the gradient), and results identical to it.
  *   saved      DEVICE, 256-byte aligned, dvp_fused_lmhead_saved_bytes(params) bytes (about
- *              4 N V bytes: 10 GB at N = 16384, V = 151936); written by the forward, read by the
+ *              2 N V bytes: 5 GB at N = 16384, V = 151936); written by the forward, read by the
  *              backward, owned by the caller in between.
  *   forward:   arguments as dvp_fused_lmhead without grad_out / d_hidden / d_w; the inference side is
  *              w_infer (bf16), or infer8 (see dvp_fused_lmhead_f8infer), or neither (both NULL).

@@ -9,7 +9,7 @@
 //           (Def. 5.1 / 5.2), per 256-column partials, reduced in fixed order
 // When a gradient is asked for, the training side runs in blocks of 8192 token
 // rows and pass B also leaves the block's masked exponentials
-//   E_ik = [z_ik >= tau_i] exp(z_ik - m_i)          (bf16, both orientations)
+//   E_ik = [z_ik >= tau_i] exp(z_ik - m_i)          (bf16, [rows, V] in panels of 256 columns)
 // behind, with the sampled token's own entry E_iy set to zero.  With S_i the
 // row sum (sampled token included), c_i = grad_out_i (0 when y_i is pruned),
 // s_i = -c_i / S_i and q_i = c_i (1 - p_iy) the sampled token's gradient entry,
@@ -19,12 +19,17 @@
 // fp32 when dH is written and folded into H for dW, which is accumulated over
 // the row blocks); the sampled token's entry, the one that cancels when the
 // distribution is peaked, is formed and added in fp32 and never rounded to bf16.
-// Every GEMM is C = A B^T with both operands K-major; W is transposed once per
-// call and the scaled H once per row block so that the two E products have
-// that form too.
+// The forward products are C = A B^T with both operands K-major.  The two E products are not of that form
+// (dH contracts over W's rows, dW over the token rows of E and of diag(s) H): the GEMM kernel has builds that
+// take an operand as it lies, [K, ld], and fetch its fragments with the transposing LDS read, so that no
+// transposed copy of W or E is ever written (dW still takes a transposed copy of its small operand, the row
+// block's diag(s) H).  E is stored in panels of 256 columns, each panel [rows, 256] contiguous: as dW's
+// first operand (rows = k) a tile's K step is then one 32 KB run; with E row-major (rows 300 KB apart) that
+// product was a quarter slower than from a transposed copy.
 #include <math.h>
 
 #include <atomic>
+#include <utility>
 
 #include "dvp_device.h"
 #include "dvp_lmhead_internal.h"
@@ -92,6 +97,17 @@ struct GemmArgs {
     // tile (the operands are zero padded that far); none left: the launch does nothing.
     const int *n_dev = nullptr;
     int n_off = 0, dev_dim = 0;
+    // Operands stored the other way round (the kernel's ATR / BTR builds): A is then [K, lda] with its M index
+    // contiguous, B [K, ldb] with its N index contiguous (lda, ldb multiples of 8, at least a whole number of
+    // 16-byte pieces per row).  kb_rows says how many of B's K rows exist in memory: rows past them are read from
+    // the last one (the other operand carries zeros there); A's K rows all exist.  a_cols / b_cols: elements of a row that may be
+    // read (a multiple of 8, at least 8; 0: the whole pitch): 16-byte pieces past them are read from the last piece.
+    int kb_rows = 0, a_cols = 0, b_cols = 0;
+    // A stored in panels (a_panel > 0, elements): the matrix [R, C] is cut into panels of 256 columns, each a
+    // contiguous [R, 256] block, element (r, c) at (c / 256) * a_panel + r * 256 + c % 256; lda is 256.  As a K-major
+    // operand its columns are k (a K step is a quarter of a panel row), as a [K, lda] operand its rows are k and a
+    // tile of 256 m is one panel, 64 rows of k a contiguous 32 KB.
+    int64_t a_panel = 0;
 };
 
 __device__ __forceinline__ int rows_on_device(const int *n_dev, int n_off, int rows_host)
@@ -113,7 +129,6 @@ __device__ __forceinline__ int rows_on_device(const int *n_dev, int n_off, int r
 // pass of the product (re-reading a row block's logits costs a fraction of recomputing them).
 template <bool STORE_Z>
 struct EpiMax {
-    static constexpr bool kUsesTileLds = false;
     static constexpr bool kRowMap = false;
     // The products of this epilogue are taken with the operands swapped (the B fragment is the matrix
     // instruction's row operand): element (mi, ni, i) of lane l is then token row r0 + mi*32 + l%32 and
@@ -168,7 +183,6 @@ struct EpiMax {
 // inputs only, not on the order in which tiles run, so a row's candidate set is the same in every run.
 // Candidates (token, z) are appended in arrival order; at most cand_cap are kept.
 struct EpiMaxCand {
-    static constexpr bool kUsesTileLds = false;
     static constexpr bool kRowMap = false;
     static constexpr bool kSwapped = false;
     RowStats st;
@@ -239,10 +253,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)   // hardwar
     return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){lo, hi}, bf16x2));
 }
 
-// WRITE_E: also store the masked exponentials of the tile, as bf16, row-major in
-// E [rows (padded to 256), ld_e] and transposed in Et [columns (padded), ld_et];
-// rows beyond M and columns beyond N are stored as zeros (they pad the K
-// dimension of the two gradient products).
+// Sums at the threshold per column tile.
 // WRITE_BITS: also store the side's membership bitmask.
 // WRITE_LIST: also append every safe token of a row, with exp(z - m), to that row's list (arrival
 // order; at most list_cap entries are kept, the cursor stops a little above that).  Meant for rows
@@ -250,16 +261,12 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)   // hardwar
 // ROWMAP: the launch covers a subset of the token rows, gathered into consecutive rows of A: their
 // number is read from device memory (*n_sub; zero: nothing to do), the per-row statistics and partials
 // are indexed by position in the subset, and lists by the row's own index rowmap[position].
-template <bool WRITE_E, bool WRITE_BITS = false, bool WRITE_LIST = false, bool ROWMAP = false>
+template <bool WRITE_BITS = false, bool WRITE_LIST = false, bool ROWMAP = false>
 struct EpiSum {
-    static constexpr bool kUsesTileLds = WRITE_E;   // the bf16 staging lives in the operand tiles
     static constexpr bool kRowMap = ROWMAP;
     static constexpr bool kSwapped = false;
     RowStats st;
     int n_rows;
-    const int64_t *ids;      // WRITE_E: the sampled token's own entry of E is stored as zero
-    uint16_t *E, *Et;
-    int64_t ld_e, ld_et;
     uint32_t *bits;          // membership bitmask [n_rows, bits_ld] of the side, or null
     int64_t bits_ld;
     dvp_grad_entry *entries; // WRITE_LIST: [n_rows, list_cap]
@@ -281,8 +288,6 @@ struct EpiSum {
                 const bool row_ok = row < g.M;
                 const float m = row_ok ? st.m[row] : 0.0f;
                 const float tau = row_ok ? st.tau[row] : INFINITY;
-                int64_t y = -1;
-                if constexpr (WRITE_E) y = row_ok ? ids[row] : -1;
                 float s = 0.0f, f = 0.0f;
                 int c = 0;
                 [[maybe_unused]] int list_open = -1, list_row = 0;   // WRITE_LIST
@@ -326,7 +331,6 @@ struct EpiSum {
                             }
                         }
                     }
-                    if constexpr (WRITE_E) acc[mi][ni][i] = (int64_t)col == y ? 0.0f : kept;   // the accumulators now hold E
                 }
 #pragma unroll
                 for (int off = 16; off > 0; off >>= 1) {
@@ -340,52 +344,6 @@ struct EpiSum {
                     lf[wn * BM + lr] = f;
                     lc[wn * BM + lr] = c;
                 }
-            }
-        }
-        if constexpr (WRITE_E) {
-            // Each wavefront turns its block into 16-byte stores through its own 16 KB of the dead
-            // operand tiles: LDS operations of one wavefront complete in order, no barrier is needed.
-            uint8_t *stage = lds + wave * kWaveStageBytes;
-            const int l32 = lane % 32, up = lane / 32;
-            // row-major: [64 rows][128 columns] bf16.  Neighbouring lanes hold neighbouring columns of
-            // the same row; they trade one value so that each writes a whole 32-bit word.
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-                    for (int i = 0; i < 16; i += 2) {
-                        const float a = acc[mi][ni][i], b = acc[mi][ni][i + 1];
-                        const bool odd = lane & 1;
-                        const float got = __shfl_xor(odd ? a : b, 1, kWave);
-                        const uint32_t word = odd ? pack_bf16x2(got, b) : pack_bf16x2(a, got);
-                        const int lrow = mi * 32 + (i / 4) * 8 + up * 4 + (i % 4) + (odd ? 1 : 0);
-                        const int lcol = ni * 32 + (l32 & ~1);
-                        *(uint32_t *)(stage + lrow * (NI * 32 * 2) + lcol * 2) = word;
-                    }
-#pragma unroll
-            for (int t = 0; t < MI * 32 / 4; ++t) {
-                const int lrow = t * 4 + lane / 16, chunk = lane % 16;
-                const u32x4 v = *(const u32x4 *)(stage + lrow * (NI * 32 * 2) + chunk * 16);
-                *(u32x4 *)(E + (int64_t)(r0 + lrow) * ld_e + c0 + chunk * 8) = v;
-            }
-            // transposed: [128 columns][64 rows] bf16; a lane holds 4 consecutive rows of a column
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const uint32_t w0 = pack_bf16x2(acc[mi][ni][q * 4], acc[mi][ni][q * 4 + 1]);
-                        const uint32_t w1 = pack_bf16x2(acc[mi][ni][q * 4 + 2], acc[mi][ni][q * 4 + 3]);
-                        const int lcol = ni * 32 + l32, lrow = mi * 32 + q * 8 + up * 4;
-                        *(uint2 *)(stage + lcol * (MI * 32 * 2) + lrow * 2) = make_uint2(w0, w1);
-                    }
-#pragma unroll
-            for (int t = 0; t < NI * 32 / 8; ++t) {
-                const int lcol = t * 8 + lane / 8, chunk = lane % 8;
-                const u32x4 v = *(const u32x4 *)(stage + lcol * (MI * 32 * 2) + chunk * 16);
-                *(u32x4 *)(Et + (int64_t)(c0 + lcol) * ld_et + r0 + chunk * 8) = v;
             }
         }
     }
@@ -405,7 +363,6 @@ struct EpiSum {
 };
 
 struct EpiStore {
-    static constexpr bool kUsesTileLds = false;
     static constexpr bool kRowMap = false;
     static constexpr bool kSwapped = true;    // a lane owns an output row and four consecutive columns: see EpiMax
     float *C;                // [M, ldc] fp32
@@ -492,6 +449,14 @@ __device__ __forceinline__ void wait_copies_and_barrier()
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+// scheduling hint for a slice with more LDS reads than matrix instructions: after instruction i, its share of the reads
+template <int NM, int NR, int... I>
+__device__ __forceinline__ void spread_reads(std::integer_sequence<int, I...>)
+{
+    ((__builtin_amdgcn_sched_group_barrier(0x008, 1, 0),
+      __builtin_amdgcn_sched_group_barrier(0x100, NR * (I + 1) / NM - NR * I / NM, 0)), ...);
+}
+
 // where a workgroup's tile sits and how its lanes address the operand rows
 struct TilePlace {
     const uint8_t *baseA, *baseB;                        // first row of the A tile / B tile
@@ -499,17 +464,28 @@ struct TilePlace {
     int tile_m, tile_n;
 };
 
-// Persistent: the grid has one workgroup per CU and each walks its share of the tiles.  Unless the
-// epilogue needs the tile buffers, the first two K steps of the next tile are copied under the last
-// two K steps of the current one, so only the epilogue itself separates the MFMA streams of two tiles.
+// Persistent: the grid has one workgroup per CU and each walks its share of the tiles.  The first two
+// K steps of the next tile are copied under the last two K steps of the current one (no epilogue touches
+// the tile buffers), so only the epilogue itself separates the MFMA streams of two tiles.
 //
 // F8: both operands are E4M3 bytes and the products run on the 64-deep 8-bit matrix instruction, whose
 // operands are 32 bytes per lane: a K step (128 bytes of every row) is two instructions deep instead of
 // four.  Lane l takes the 32 bytes (two swizzled 16-byte chunks) 4 * pair + 2 * (l / 32) of its row, of A
 // and of B alike, so both operands present the same k to the same position of the instruction.
-template <class Epi, bool NEEDS_FINISH, bool F8>
+//
+// ATR / BTR: the operand lies in memory as [K, ld], its M (N) index contiguous, and is NOT transposed beforehand:
+// its tile goes into LDS as 64 rows of k, 512 bytes (256 m) each, and the fragments are fetched with the
+// transposing LDS read of this chip (ds_read_b64_tr_b16: among 16 lanes, lane i receives element i % 4 of the 8
+// bytes that lanes i / 4, 4 + i / 4, 8 + i / 4, 12 + i / 4 point at).  Lanes 4 e + j of a group of 16 point at row
+// k0 + e, columns m0 + 4 j .. + 3, so lane i ends up with column m0 + i of rows k0 .. k0 + 3: two such reads are the
+// eight consecutive k the matrix instruction wants from that lane.  A read touches 8 rows of k, 64 bytes each;
+// rows are 512 bytes apart (the same banks), so the 16-byte chunks of row k sit at position chunk ^ 4 (k & 3):
+// 165 B/clk per CU measured in this pattern against 63 unswizzled; a K step's fragments take 1200 cycles, under
+// the 2048 of its matrix instructions.
+template <class Epi, bool NEEDS_FINISH, bool F8, bool ATR = false, bool BTR = false>
 __global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs g_host, const Epi epi, int tiles_m, int tiles_n)
 {
+    static_assert(!(F8 && (ATR || BTR)), "8-bit operands are K-major");
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];   // [stage][A | B][256 rows][128 B], then sums scratch
 
     GemmArgs g = g_host;
@@ -553,28 +529,64 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs
         const int in_group = pid - group * per_group;
         tp.tile_m = first_m + in_group % group_rows;
         tp.tile_n = in_group / group_rows;
-        tp.baseA = (const uint8_t *)(g.A + (int64_t)tp.tile_m * BM * g.lda);
-        tp.baseB = (const uint8_t *)(g.B + (int64_t)tp.tile_n * BN * g.ldb);
+        tp.baseA = (const uint8_t *)(ATR ? g.A + (int64_t)tp.tile_m * (g.a_panel > 0 ? g.a_panel : (int64_t)BM)
+                                         : g.A + (int64_t)tp.tile_m * BM * g.lda);
+        tp.baseB = (const uint8_t *)(BTR ? g.B + (int64_t)tp.tile_n * BN : g.B + (int64_t)tp.tile_n * BN * g.ldb);
         const int rows_a = g.M - tp.tile_m * BM, rows_b = g.N - tp.tile_n * BN;   // >= 1; rows past the end repeat the last one
+        // [K, ld] operands: columns the row still has from the tile's first one (pieces past them repeat the last piece)
+        const int cols_a = g.a_panel > 0 ? BM : (int)((g.a_cols > 0 ? g.a_cols : g.lda) - (int64_t)tp.tile_m * BM);
+        const int cols_b = (int)((g.b_cols > 0 ? g.b_cols : g.ldb) - (int64_t)tp.tile_n * BN);
 #pragma unroll
         for (int i = 0; i < kCopiesPerWave; ++i) {
             const int p = (i * kGemmWaves + wave) * kWave + lane;
             const int row = p >> 3, kc = (p & 7) ^ ((row >> 1) & 7);
             const int ra = row < rows_a ? row : rows_a - 1;
             const int rb = row < rows_b ? row : rows_b - 1;
-            tp.off_a[i] = (uint32_t)(((int64_t)ra * g.lda + kc * 8) * 2);
-            tp.off_b[i] = (uint32_t)(((int64_t)rb * g.ldb + kc * 8) * 2);
+            // [K, ld] operands: a wavefront copy is two rows of k; lane -> (k, physical chunk), logical chunk = physical ^ 4 (k & 3).
+            // Copy i of a wavefront lies 16 i rows of k below its copy 0, same columns: only off[0] is used, the rest
+            // of the way is a step of the wavefront's base address.
+            const int tk = p >> 5, tc = ((p & 31) ^ (4 * (tk & 3))) * 8;
+            const int ca = tc + 8 <= cols_a ? tc : cols_a - 8, cb = tc + 8 <= cols_b ? tc : cols_b - 8;
+            tp.off_a[i] = ATR ? (uint32_t)(((int64_t)tk * g.lda + ca) * 2) : (uint32_t)(((int64_t)ra * g.lda + kc * 8) * 2);
+            tp.off_b[i] = BTR ? (uint32_t)(((int64_t)tk * g.ldb + cb) * 2) : (uint32_t)(((int64_t)rb * g.ldb + kc * 8) * 2);
         }
     };
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)lds;
+    // rows of k a [K, ld] operand has in memory (K itself when the caller says nothing)
+    const int kb_rows = g.kb_rows > 0 ? g.kb_rows : g.K;
+    constexpr int kTrCopyRows = 2 * kGemmWaves;      // rows of k between a wavefront's successive copies of a [K, ld] tile
     auto issue_copies = [&](const TilePlace &tp, int kt, int stage) {
-        const uint8_t *pa = tp.baseA + (size_t)kt * kRowBytes;
-        const uint8_t *pb = tp.baseB + (size_t)kt * kRowBytes;
+        const uint8_t *pa = tp.baseA + (ATR ? (size_t)kt * BK * (size_t)g.lda * 2
+                                            : g.a_panel > 0 ? (size_t)(kt / (BM / BK)) * (size_t)g.a_panel * 2 + (size_t)(kt % (BM / BK)) * kRowBytes
+                                                            : (size_t)kt * kRowBytes);
+        const uint8_t *pb = tp.baseB + (BTR ? (size_t)kt * BK * (size_t)g.ldb * 2 : (size_t)kt * kRowBytes);
         const uint32_t sa = lds_base + stage * kStageBytes;
 #pragma unroll
-        for (int i = 0; i < kCopiesPerWave; ++i) copy16_to_lds(pa, tp.off_a[i], sa + (i * kGemmWaves + wave) * 1024);
+        for (int i = 0; i < kCopiesPerWave; ++i) {
+            if constexpr (ATR) copy16_to_lds(pa + (size_t)i * kTrCopyRows * (size_t)g.lda * 2, tp.off_a[0], sa + (i * kGemmWaves + wave) * 1024);
+            else               copy16_to_lds(pa, tp.off_a[i], sa + (i * kGemmWaves + wave) * 1024);
+        }
+        // A [K, ld] B operand whose rows of k end inside or before this step: the rows past the end repeat the last one.
+        // (`last` is that row relative to the step; when the whole step lies past it the base moves back to it, so that
+        // the per-lane offsets, which are unsigned, never have to go below zero: a lane's row is 16 i + its row of copy 0,
+        // it goes back by at most that.)
+        if (BTR && (kt + 1) * BK > kb_rows) {
+            const int last = kb_rows - 1 - kt * BK, lim = last < 0 ? 0 : last;
+            const uint8_t *pb2 = last < 0 ? pb + (int64_t)last * g.ldb * 2 : pb;
+            const int tk0 = (wave * kWave + lane) >> 5;
 #pragma unroll
-        for (int i = 0; i < kCopiesPerWave; ++i) copy16_to_lds(pb, tp.off_b[i], sa + kTileBytes + (i * kGemmWaves + wave) * 1024);
+            for (int i = 0; i < kCopiesPerWave; ++i) {
+                const int tk = tk0 + i * kTrCopyRows;
+                const int row = tk > lim ? lim : tk;
+                copy16_to_lds(pb2, tp.off_b[0] + (uint32_t)(row - tk0) * (uint32_t)(g.ldb * 2), sa + kTileBytes + (i * kGemmWaves + wave) * 1024);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < kCopiesPerWave; ++i) {
+                if constexpr (BTR) copy16_to_lds(pb + (size_t)i * kTrCopyRows * (size_t)g.ldb * 2, tp.off_b[0], sa + kTileBytes + (i * kGemmWaves + wave) * 1024);
+                else               copy16_to_lds(pb, tp.off_b[i], sa + kTileBytes + (i * kGemmWaves + wave) * 1024);
+            }
+        }
     };
 
     // operand fetch: lane l reads row (l % 32), the 8 consecutive k of chunk 2 * ks + l / 32.
@@ -582,6 +594,33 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs
     const int frow = lane % 32, half = lane / 32, key = (frow >> 1) & 7;
     const int a_off = (wm * MI * 32 + frow) * kRowBytes;
     const int b_off = kTileBytes + (wn * NI * 32 + frow) * kRowBytes;
+    // [K, ld] operands: this lane of its group of 16 points at row 8 (lane / 32) + (lane % 16) / 4 of a 16-deep slice,
+    // columns 32 blk + 16 ((lane / 16) % 2) + 4 (lane % 4) .. + 3; the second read of a fragment is 4 rows further
+    constexpr int kTrRowBytes = BM * 2;          // one row of k in LDS: 256 m
+    int tr_a[MI], tr_b[NI];
+    {
+        const int e = (lane % 16) / 4, j = lane % 4, g2 = (lane / 16) % 2;
+        const int row = 8 * half + e;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+            const int chunk = (4 * (wm * MI + mi) + 2 * g2 + j / 2) ^ (4 * e);
+            tr_a[mi] = row * kTrRowBytes + chunk * 16 + (j % 2) * 8;
+        }
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+            const int chunk = (4 * (wn * NI + ni) + 2 * g2 + j / 2) ^ (4 * e);
+            tr_b[ni] = row * kTrRowBytes + chunk * 16 + (j % 2) * 8;
+        }
+    }
+    auto fetch_tr = [&](uint32_t lds_addr) {     // two transposing reads, 4 rows of k apart: eight consecutive k of this lane's column
+        typedef short v4i16 __attribute__((ext_vector_type(4)));
+        typedef short v8i16 __attribute__((ext_vector_type(8)));
+        typedef v4i16 __attribute__((address_space(3))) *lds_v4;
+        const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(uintptr_t)lds_addr);
+        const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(uintptr_t)(lds_addr + 4 * kTrRowBytes));
+        const v8i16 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        return __builtin_bit_cast(bf16x8, both);
+    };
     f32x16 acc[MI][NI];
     bf16x8 fa[2][MI], fb[2][NI];
     i32x8 fa8[2][MI], fb8[2][NI];       // F8 only
@@ -604,9 +643,15 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs
         } else {
             const int chunk = ((ks * 2 + half) ^ key) * 16;
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi) fa[buf][mi] = *(const bf16x8 *)(sb + a_off + mi * 32 * kRowBytes + chunk);
+            for (int mi = 0; mi < MI; ++mi) {
+                if constexpr (ATR) fa[buf][mi] = fetch_tr(lds_base + stage * kStageBytes + tr_a[mi] + ks * 16 * kTrRowBytes);
+                else               fa[buf][mi] = *(const bf16x8 *)(sb + a_off + mi * 32 * kRowBytes + chunk);
+            }
 #pragma unroll
-            for (int ni = 0; ni < NI; ++ni) fb[buf][ni] = *(const bf16x8 *)(sb + b_off + ni * 32 * kRowBytes + chunk);
+            for (int ni = 0; ni < NI; ++ni) {
+                if constexpr (BTR) fb[buf][ni] = fetch_tr(lds_base + stage * kStageBytes + kTileBytes + tr_b[ni] + ks * 16 * kTrRowBytes);
+                else               fb[buf][ni] = *(const bf16x8 *)(sb + b_off + ni * 32 * kRowBytes + chunk);
+            }
         }
     };
     auto multiply = [&](int buf) {
@@ -639,17 +684,29 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs
                     ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][ni], fa[buf][mi], acc[mi][ni], 0, 0, 0)
                     : __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][mi], fb[buf][ni], acc[mi][ni], 0, 0, 0);
         // scheduling hint: spread the LDS reads of the next slice between this slice's MFMAs
-        constexpr int NM = MI * NI, NR = MI + NI, PER = NM / NR;
+        constexpr int NM = MI * NI, NR = (ATR ? 2 : 1) * MI + (BTR ? 2 : 1) * NI;
+        if constexpr (NR == NM) {      // two reads behind each of the first half of the instructions: every fragment is
+#pragma unroll                          // asked for at least half a slice before it is used
+            for (int i = 0; i < NM / 2; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, NM / 2, 0);
+        } else if constexpr (NR < NM) {
+            constexpr int PER = NM / NR;
 #pragma unroll
-        for (int i = 0; i < NR; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, PER, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            for (int i = 0; i < NR; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, PER, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            if constexpr (NM - PER * NR > 0) __builtin_amdgcn_sched_group_barrier(0x008, NM - PER * NR, 0);
+        } else {
+            spread_reads<NM, NR>(std::make_integer_sequence<int, NM>());
         }
-        if constexpr (NM - PER * NR > 0) __builtin_amdgcn_sched_group_barrier(0x008, NM - PER * NR, 0);
     };
 
     const int nk = g.K / BK;
-    const bool chain = !Epi::kUsesTileLds && nk >= 2;
+    const bool chain = nk >= 2;
     int t = blockIdx.x;                 // < total: the launcher never starts more workgroups than tiles
     int sp = 0;                         // LDS stage that holds K step 0 of the current tile
     TilePlace cur, nxt;
@@ -734,7 +791,7 @@ static int gemm_cu_count()
 
 // More than 64 KB of LDS per workgroup has to be asked for, once per kernel and device (bit d of
 // `configured`: device d has it).
-template <class Epi, bool NEEDS_FINISH, bool F8>
+template <class Epi, bool NEEDS_FINISH, bool F8, bool ATR = false, bool BTR = false>
 struct GemmBuild {
     static inline std::atomic<uint64_t> configured{0};
     static hipError_t prepare()
@@ -742,7 +799,7 @@ struct GemmBuild {
         int dev = 0;
         hipError_t e = hipGetDevice(&dev);
         if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute((const void *)gemm_nt_kernel<Epi, NEEDS_FINISH, F8>,
+        e = hipFuncSetAttribute((const void *)gemm_nt_kernel<Epi, NEEDS_FINISH, F8, ATR, BTR>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
         if (e == hipSuccess && dev < 64) configured.fetch_or(1ull << dev, std::memory_order_release);
         return e;
@@ -750,10 +807,10 @@ struct GemmBuild {
     static inline PrepareRegistrar registrar{&prepare};
 };
 
-template <class Epi, bool NEEDS_FINISH, bool F8 = false>
+template <class Epi, bool NEEDS_FINISH, bool F8 = false, bool ATR = false, bool BTR = false>
 static hipError_t launch_gemm(const GemmArgs &g, const Epi &epi, hipStream_t stream)
 {
-    typedef GemmBuild<Epi, NEEDS_FINISH, F8> Build;
+    typedef GemmBuild<Epi, NEEDS_FINISH, F8, ATR, BTR> Build;
     (void)&Build::registrar;             // instantiates the registration of this build
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -767,7 +824,7 @@ static hipError_t launch_gemm(const GemmArgs &g, const Epi &epi, hipStream_t str
     int grid = gemm_cu_count() / 8 * 8;     // one workgroup per CU; a multiple of the XCD count
     if (grid < 8) grid = 8;
     if (grid > total) grid = total;
-    hipLaunchKernelGGL((gemm_nt_kernel<Epi, NEEDS_FINISH, F8>), dim3((unsigned)grid), dim3(kGemmThreads),
+    hipLaunchKernelGGL((gemm_nt_kernel<Epi, NEEDS_FINISH, F8, ATR, BTR>), dim3((unsigned)grid), dim3(kGemmThreads),
                        kGemmLdsBytes, stream, g, epi, tiles_m, tiles_n);
     return hipGetLastError();
 }
@@ -826,7 +883,9 @@ __device__ __forceinline__ void finish_row(const RowStats &st, const SideOut &ou
 // token row, one streaming pass: safe-set size, masked sum (and the full sum when lse_full is wanted),
 // the side's outputs and the gradient factors; WRITE_E also stores the row's masked exponentials
 // E_ik = [z_ik >= tau_i] exp(z_ik - m_i) as bf16 with a zero at the sampled token's column and zeros in
-// the padding columns (they pad the K dimension of the dH product); WRITE_BITS the membership bitmask.
+// the padding columns (they pad the K dimension of the dH product), in panels of 256 columns so that both
+// gradient products find their tiles in compact memory (a row's 512 bytes of a panel are one run of a
+// wavefront's store); WRITE_BITS the membership bitmask.
 // Every thread owns fixed columns and the partial sums are combined in a fixed order: run-to-run identical.
 constexpr int kZRowThreads = 512;
 struct ZRowArgs {
@@ -837,8 +896,8 @@ struct ZRowArgs {
     const int64_t *ids;
     const float *grad_out;
     uint8_t *row_flags;
-    uint16_t *E;             // WRITE_E: [rows, ld_e] bf16
-    int64_t ld_e;
+    uint16_t *E;             // WRITE_E: bf16 [rows, v_pad] in panels of 256 columns, e_panel elements each (see GemmArgs)
+    int64_t e_panel;
     uint32_t *bits;          // WRITE_BITS: [rows, bits_ld]
     int64_t bits_ld;
     int vocab, v_pad, side, unit_grad;
@@ -853,7 +912,19 @@ __global__ __launch_bounds__(kZRowThreads) void lm_rows_from_z_kernel(const ZRow
     __shared__ float lds_f[2 * NW];
     __shared__ int lds_i[NW];
     const int i = blockIdx.x, tid = threadIdx.x;
-    if (i >= rows_on_device(a.n_dev, a.n_off, a.rows)) return;
+    const int rows = rows_on_device(a.n_dev, a.n_off, a.rows);
+    if (i >= rows) {
+        // WRITE_E launches cover the rows up to the next whole row tile: those rows of E are zeros (they pad the K
+        // dimension of the dW product)
+        if constexpr (WRITE_E) {
+            if (i < (rows + BM - 1) / BM * BM) {
+                const u32x4 zero = {0u, 0u, 0u, 0u};
+                for (int u = tid; u < a.v_pad / 8; u += kZRowThreads)
+                    __builtin_nontemporal_store(zero, (u32x4 *)(a.E + (int64_t)(u * 8 / BM) * a.e_panel + (int64_t)i * BM + u * 8 % BM));
+            }
+        }
+        return;
+    }
     const float m = a.st.m[i], tau = a.st.tau[i];
     const bool want_full = a.out.lse_full != nullptr;
     int64_t y = -1;
@@ -888,7 +959,7 @@ __global__ __launch_bounds__(kZRowThreads) void lm_rows_from_z_kernel(const ZRow
         }
         if constexpr (WRITE_E) {
             const u32x4 v = {pack_bf16x2(e[0], e[1]), pack_bf16x2(e[2], e[3]), pack_bf16x2(e[4], e[5]), pack_bf16x2(e[6], e[7])};
-            __builtin_nontemporal_store(v, (u32x4 *)(a.E + (int64_t)i * a.ld_e + col0));
+            __builtin_nontemporal_store(v, (u32x4 *)(a.E + (int64_t)(col0 / BM) * a.e_panel + (int64_t)i * BM + col0 % BM));
         }
         if constexpr (WRITE_BITS) {
             if (u < 4 * a.bits_ld) ((uint8_t *)(a.bits + (int64_t)i * a.bits_ld))[u] = (uint8_t)mask;
@@ -1046,7 +1117,7 @@ struct LmLayout {
     size_t total;
     size_t off_i32[2], off_zy[2], off_m[2], off_tau[2], off_coef, off_scale;
     size_t off_ps[2], off_pf[2], off_pc[2];
-    size_t off_ht, off_wt, off_e, off_et, off_z;
+    size_t off_hst, off_e, off_z;
     int block_pad, v_pad, col_tiles;
 };
 
@@ -1068,13 +1139,11 @@ static LmLayout lm_layout(int64_t n, int64_t d, int64_t v, bool dense_buffers = 
     }
     L.off_coef = take(n * 4);
     L.off_scale = take(n * 4);
-    L.off_ht = L.off_wt = L.off_e = L.off_et = L.off_z = 0;
+    L.off_hst = L.off_e = L.off_z = 0;
     if (dense_buffers) {
         L.off_z = take((size_t)L.block_pad * L.v_pad * 4);      // fp32 logits of one row block
-        L.off_ht = take((size_t)d * L.block_pad * 2);
-        L.off_wt = take((size_t)d * L.v_pad * 2);
-        L.off_e = take((size_t)L.block_pad * L.v_pad * 2);
-        L.off_et = take((size_t)L.v_pad * L.block_pad * 2);
+        L.off_hst = take((size_t)d * L.block_pad * 2);          // (diag(s) H)^T of one row block
+        L.off_e = take((size_t)L.block_pad * L.v_pad * 2);      // masked exponentials of one row block
     }
     L.total = o;
     return L;
@@ -1121,11 +1190,11 @@ static LmListLayout lm_list_layout(int64_t n, int64_t d, int64_t v, int64_t cap)
     return L;
 }
 
-// What the forward leaves behind for a backward in a later call: per row block the masked exponentials in
-// both orientations, and per row the two factors the gradient multiplies (1 - p_y and -1 / S, zero for
+// What the forward leaves behind for a backward in a later call: per row block the masked exponentials,
+// and per row the two factors the gradient multiplies (1 - p_y and -1 / S, zero for
 // a row whose sampled token is pruned).
 struct LmSaved {
-    size_t total, off_ucoef, off_uscale, off_e, off_et, block_bytes;
+    size_t total, off_ucoef, off_uscale, off_e, block_bytes;
     int n_blocks;
 };
 
@@ -1141,7 +1210,6 @@ static LmSaved lm_saved_layout(int64_t n, int64_t v)
     S.off_ucoef = o; o += align256(n * 4);
     S.off_uscale = o; o += align256(n * 4);
     S.off_e = o; o += S.block_bytes * S.n_blocks;
-    S.off_et = o; o += S.block_bytes * S.n_blocks;
     S.total = o;
     return S;
 }
@@ -1227,15 +1295,14 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
             side_bits[s] = o->safe_bits;
         }
     }
-    uint16_t *ht = (uint16_t *)(ws + L.off_ht), *wt = (uint16_t *)(ws + L.off_wt);
-    uint16_t *E = (uint16_t *)(ws + L.off_e), *Et = (uint16_t *)(ws + L.off_et);   // of the current row block
+    uint16_t *hst = (uint16_t *)(ws + L.off_hst);
+    uint16_t *E = (uint16_t *)(ws + L.off_e);   // of the current row block
     float *unit_coef = saved ? (float *)((char *)saved + SV.off_ucoef) : nullptr;
     float *unit_scale = saved ? (float *)((char *)saved + SV.off_uscale) : nullptr;
     auto use_block = [&](int r0) {   // saved phases keep every block's E; the fused call reuses one
         if (phase == LM_FUSED) return;
         const size_t b = (size_t)(r0 / kRowBlock) * SV.block_bytes;
         E = (uint16_t *)((char *)saved + SV.off_e + b);
-        Et = (uint16_t *)((char *)saved + SV.off_et + b);
     };
     const int tb = 256;
 #define DVP_CHECK_LAUNCH() do { if (hipGetLastError() != hipSuccess) return DVP_ERR_HIP; } while (0)
@@ -1271,7 +1338,7 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
         }
         hipLaunchKernelGGL(init_stats_kernel, dim3(nb), dim3(tb), 0, stream, st, rows);
         DVP_CHECK_LAUNCH();
-        const int64_t lde = L.v_pad, ldet = L.block_pad;
+        const int64_t e_panel = (int64_t)L.block_pad * BM;
         if (!stats_only_ws) {
             // One pass of the product: row maxima, and the block's logits kept as fp32; the sums at the
             // threshold (and E) are then read off the stored logits.  Re-reading them costs a few percent
@@ -1286,19 +1353,14 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
             ZRowArgs za;
             za.Z = Z; za.ldz = L.v_pad; za.st = st; za.out = o; za.ids = ids + r0;
             za.grad_out = grad_out ? grad_out + r0 : nullptr; za.row_flags = row_flags ? row_flags + r0 : nullptr;
-            za.E = E; za.ld_e = lde; za.bits = bits; za.bits_ld = bits_ld;
+            za.E = E; za.e_panel = e_panel; za.bits = bits; za.bits_ld = bits_ld;
             za.vocab = v; za.v_pad = L.v_pad; za.side = s; za.unit_grad = phase == LM_FORWARD_SAVE ? 1 : 0;
             za.n_dev = n_dev; za.n_off = r0; za.rows = rows;
             const dim3 zg((unsigned)rows), zb(kZRowThreads);
             if (write_e) {
-                if (bits) hipLaunchKernelGGL((lm_rows_from_z_kernel<true, true>), zg, zb, 0, stream, za);
-                else      hipLaunchKernelGGL((lm_rows_from_z_kernel<true, false>), zg, zb, 0, stream, za);
-                DVP_CHECK_LAUNCH();
-                // E^T for the dW product (zero padded to a whole row tile)
-                const int rows_pad = (rows + BM - 1) / BM * BM;
-                hipLaunchKernelGGL(transpose_bf16_kernel, dim3((L.v_pad + kTrTile - 1) / kTrTile, (rows_pad + kTrTile - 1) / kTrTile),
-                                   dim3(kTrThreads), 0, stream, (const uint16_t *)E, lde, Et, ldet, rows, L.v_pad, rows_pad,
-                                   (const float *)nullptr, n_dev, r0);
+                const dim3 zge((unsigned)((rows + BM - 1) / BM * BM));   // E's rows up to the row tile: zeros past `rows`
+                if (bits) hipLaunchKernelGGL((lm_rows_from_z_kernel<true, true>), zge, zb, 0, stream, za);
+                else      hipLaunchKernelGGL((lm_rows_from_z_kernel<true, false>), zge, zb, 0, stream, za);
             } else {
                 if (bits) hipLaunchKernelGGL((lm_rows_from_z_kernel<false, true>), zg, zb, 0, stream, za);
                 else      hipLaunchKernelGGL((lm_rows_from_z_kernel<false, false>), zg, zb, 0, stream, za);
@@ -1317,11 +1379,11 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
         DVP_CHECK_LAUNCH();
         hipError_t eb;
         if (bytes) {
-            eb = bits ? launch_gemm<EpiSum<false, true>, true, true>(g, EpiSum<false, true>{st, rows, nullptr, nullptr, nullptr, 0, 0, bits, bits_ld}, stream)
-                      : launch_gemm<EpiSum<false>, true, true>(g, EpiSum<false>{st, rows, nullptr, nullptr, nullptr, 0, 0, nullptr, 0}, stream);
+            eb = bits ? launch_gemm<EpiSum<true>, true, true>(g, EpiSum<true>{st, rows, bits, bits_ld}, stream)
+                      : launch_gemm<EpiSum<>, true, true>(g, EpiSum<>{st, rows, nullptr, 0}, stream);
         } else {
-            eb = bits ? launch_gemm<EpiSum<false, true>, true>(g, EpiSum<false, true>{st, rows, nullptr, nullptr, nullptr, 0, 0, bits, bits_ld}, stream)
-                      : launch_gemm<EpiSum<false>, true>(g, EpiSum<false>{st, rows, nullptr, nullptr, nullptr, 0, 0, nullptr, 0}, stream);
+            eb = bits ? launch_gemm<EpiSum<true>, true>(g, EpiSum<true>{st, rows, bits, bits_ld}, stream)
+                      : launch_gemm<EpiSum<>, true>(g, EpiSum<>{st, rows, nullptr, 0}, stream);
         }
         if (eb != hipSuccess) return DVP_ERR_HIP;
         hipLaunchKernelGGL(after_sum_kernel, dim3((rows + kAfterRows - 1) / kAfterRows),
@@ -1338,25 +1400,28 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
     auto backward_block = [&](int r0, int rows, const float *coef, const float *scale) -> dvp_status {
         const int rows_pad = (rows + BM - 1) / BM * BM;
         const uint16_t *hblock = (const uint16_t *)hidden + (int64_t)r0 * p->ld_hidden;
+        // (diag(s) H)^T of the block, zero columns up to the row tile (they pad the K dimension of the dW product)
         hipLaunchKernelGGL(transpose_bf16_kernel, dim3((d + kTrTile - 1) / kTrTile, (rows_pad + kTrTile - 1) / kTrTile),
                            dim3(kTrThreads), 0, stream,
-                           hblock, p->ld_hidden, ht, (int64_t)L.block_pad, rows, d, rows_pad, scale, n_dev, r0);
+                           hblock, p->ld_hidden, hst, (int64_t)L.block_pad, rows, d, rows_pad, scale, n_dev, r0);
         DVP_CHECK_LAUNCH();
-        // dH[r0 : r0 + rows, :] = diag(s) . E [rows, v_pad] . (W^T [d, v_pad])^T + diag(q) . W[y, :]
+        // dH[r0 : r0 + rows, :] = diag(s) . E [rows, v_pad] . W [v, d] + diag(q) . W[y, :]; W is read as it lies, its rows
+        // are the product's k (E's columns from v to v_pad are zero)
         GemmArgs gh;
-        gh.A = E; gh.lda = L.v_pad; gh.B = wt; gh.ldb = L.v_pad;
-        gh.M = rows; gh.N = d; gh.K = L.v_pad; gh.scale = 1.0f;
+        gh.A = E; gh.lda = BM; gh.a_panel = (int64_t)L.block_pad * BM; gh.B = (const uint16_t *)w_train; gh.ldb = p->ld_w;
+        gh.M = rows; gh.N = d; gh.K = L.v_pad; gh.kb_rows = (int)v; gh.b_cols = (int)d; gh.scale = 1.0f;
         if (n_dev) { gh.n_dev = n_dev; gh.n_off = r0; gh.dev_dim = 1; }
         const EpiStore eh{d_hidden + (int64_t)r0 * p->ld_hidden, p->ld_hidden, 0, scale, coef, ids + r0,
                           (const uint16_t *)w_train, p->ld_w};
-        if (launch_gemm<EpiStore, false>(gh, eh, stream) != hipSuccess) return DVP_ERR_HIP;
-        // dW (+)= E^T [v, rows_pad] . ((diag(s) H)^T [d, rows_pad])^T, then the sampled tokens' rows
+        if (launch_gemm<EpiStore, false, false, false, true>(gh, eh, stream) != hipSuccess) return DVP_ERR_HIP;
+        // dW (+)= E^T . diag(s) H, then the sampled tokens' rows: E as it lies (the block's rows are the product's k,
+        // zero rows from `rows` to rows_pad), against the small transposed copy of diag(s) H
         GemmArgs gw;
-        gw.A = Et; gw.lda = L.block_pad; gw.B = ht; gw.ldb = L.block_pad;
+        gw.A = E; gw.lda = BM; gw.a_panel = (int64_t)L.block_pad * BM; gw.B = hst; gw.ldb = L.block_pad;
         gw.M = v; gw.N = d; gw.K = rows_pad; gw.scale = 1.0f;
         if (n_dev) { gw.n_dev = n_dev; gw.n_off = r0; gw.dev_dim = 2; }
         const EpiStore ew{d_w, p->ld_w, r0 > 0 || dw_accumulate, nullptr, nullptr, nullptr, nullptr, 0};
-        if (launch_gemm<EpiStore, false>(gw, ew, stream) != hipSuccess) return DVP_ERR_HIP;
+        if (launch_gemm<EpiStore, false, false, true, false>(gw, ew, stream) != hipSuccess) return DVP_ERR_HIP;
         for (int q0 = 0; q0 < rows; q0 += kOnehotRows) {   // in row order: launches on one stream run in order
             const int qrows = (rows - q0) < kOnehotRows ? (rows - q0) : kOnehotRows;
             hipLaunchKernelGGL(onehot_dw_kernel, dim3(qrows), dim3(kOnehotThreads), 0, stream, ids + r0 + q0,
@@ -1366,14 +1431,6 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
         }
         return DVP_OK;
     };
-    auto transpose_w = [&]() -> dvp_status {
-        hipLaunchKernelGGL(transpose_bf16_kernel, dim3((d + kTrTile - 1) / kTrTile, (L.v_pad + kTrTile - 1) / kTrTile),
-                           dim3(kTrThreads), 0, stream,
-                           (const uint16_t *)w_train, p->ld_w, wt, (int64_t)L.v_pad, v, d, L.v_pad, (const float *)nullptr);
-        DVP_CHECK_LAUNCH();
-        return DVP_OK;
-    };
-
     // a side's forward without E: row block by row block where the logits are stored (one block's worth of
     // room), all rows at once where they are produced twice
     auto forward_all = [&](int side) -> dvp_status {
@@ -1387,7 +1444,6 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
     };
 
     if (phase == LM_BACKWARD_SAVED) {
-        if ((rc = transpose_w()) != DVP_OK) return rc;
         float *coef = (float *)(ws + L.off_coef), *scale = (float *)(ws + L.off_scale);
         for (int r0 = 0; r0 < n; r0 += kRowBlock) {
             const int rows = (n - r0) < kRowBlock ? (n - r0) : kRowBlock;
@@ -1409,7 +1465,6 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
         if ((rc = forward_all(0)) != DVP_OK) return rc;
     } else {
         // training side with gradient, in blocks of kRowBlock token rows
-        if ((rc = transpose_w()) != DVP_OK) return rc;
         for (int r0 = 0; r0 < n; r0 += kRowBlock) {
             const int rows = (n - r0) < kRowBlock ? (n - r0) : kRowBlock;
             if ((rc = forward(0, r0, rows, true, st)) != DVP_OK) return rc;
@@ -1561,14 +1616,14 @@ static dvp_status run_lmhead_lists(const dvp_lmhead_params *p, const void *hidde
             RowStats sub = st;                    // m, tau and the partials by position in the subset
             sub.m = sa.m_sub; sub.tau = sa.tau_sub;
             if (s == 0 && lists)
-                eb = launch_gemm<EpiSum<false, false, true, true>, true>(
-                    gs, EpiSum<false, false, true, true>{sub, n, nullptr, nullptr, nullptr, 0, 0, nullptr, 0, entries, cursor, list_cap,
+                eb = launch_gemm<EpiSum<false, true, true>, true>(
+                    gs, EpiSum<false, true, true>{sub, n, nullptr, 0, entries, cursor, list_cap,
                                                          rowmap, n_sub}, stream);
             else {
-                const EpiSum<false, false, false, true> es{sub, n, nullptr, nullptr, nullptr, 0, 0, nullptr, 0, nullptr, nullptr, 0,
+                const EpiSum<false, false, true> es{sub, n, nullptr, 0, nullptr, nullptr, 0,
                                                            rowmap, n_sub};
-                eb = bytes ? launch_gemm<EpiSum<false, false, false, true>, true, true>(gs, es, stream)
-                           : launch_gemm<EpiSum<false, false, false, true>, true>(gs, es, stream);
+                eb = bytes ? launch_gemm<EpiSum<false, false, true>, true, true>(gs, es, stream)
+                           : launch_gemm<EpiSum<false, false, true>, true>(gs, es, stream);
             }
             if (eb != hipSuccess) return DVP_ERR_HIP;
             hipLaunchKernelGGL(after_sum_kernel, dim3((n + kAfterRows - 1) / kAfterRows), dim3(kAfterRows * kAfterSegs), 0,
@@ -1577,13 +1632,13 @@ static dvp_status run_lmhead_lists(const dvp_lmhead_params *p, const void *hidde
             DVP_CHECK_LAUNCH();
         } else {
             if (s == 0 && lists)
-                eb = launch_gemm<EpiSum<false, false, true>, true>(
-                    g, EpiSum<false, false, true>{st, n, nullptr, nullptr, nullptr, 0, 0, nullptr, 0, entries, cursor, list_cap,
+                eb = launch_gemm<EpiSum<false, true>, true>(
+                    g, EpiSum<false, true>{st, n, nullptr, 0, entries, cursor, list_cap,
                                                   nullptr, nullptr}, stream);
             else if (bytes)
-                eb = launch_gemm<EpiSum<false>, true, true>(g, EpiSum<false>{st, n, nullptr, nullptr, nullptr, 0, 0, nullptr, 0}, stream);
+                eb = launch_gemm<EpiSum<>, true, true>(g, EpiSum<>{st, n, nullptr, 0}, stream);
             else
-                eb = launch_gemm<EpiSum<false>, true>(g, EpiSum<false>{st, n, nullptr, nullptr, nullptr, 0, 0, nullptr, 0}, stream);
+                eb = launch_gemm<EpiSum<>, true>(g, EpiSum<>{st, n, nullptr, 0}, stream);
             if (eb != hipSuccess) return DVP_ERR_HIP;
             hipLaunchKernelGGL(after_sum_kernel, dim3((n + kAfterRows - 1) / kAfterRows), dim3(kAfterRows * kAfterSegs), 0,
                                stream, st, o, ids, grad_out, row_flags, n, v, L.col_tiles, s, 0, (const int *)nullptr,

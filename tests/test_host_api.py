@@ -196,7 +196,9 @@ def test_lmhead_argument_validation_needs_no_gpu():
     assert call(P(), bytes_=16) == 6 and call(P(), workspace=None) == 6
 
     # forward and backward as two calls
-    assert L.dvp_fused_lmhead_saved_bytes(ctypes.byref(P(n=300, v=1000))) >= 2 * 512 * 1024 * 2
+    # the masked exponentials of 300 rows x 1000 tokens as bf16, padded to whole 256 x 256 tiles, and two factors per row
+    saved_bytes = L.dvp_fused_lmhead_saved_bytes(ctypes.byref(P(n=300, v=1000)))
+    assert 512 * 1024 * 2 + 2 * 300 * 4 <= saved_bytes <= 512 * 1024 * 2 + 2 * 300 * 4 + 1024
     assert L.dvp_fused_lmhead_saved_bytes(ctypes.byref(P(d=100))) == 0
 
     def fwd(p, saved=ws, saved_bytes=1 << 40, w_infer=FAKE, side=None):

@@ -106,7 +106,7 @@ struct GemmArgs {
     // A stored in panels (a_panel > 0, elements): the matrix [R, C] is cut into panels of 256 columns, each a
     // contiguous [R, 256] block, element (r, c) at (c / 256) * a_panel + r * 256 + c % 256; lda is 256.  As a K-major
     // operand its columns are k (a K step is a quarter of a panel row), as a [K, lda] operand its rows are k and a
-    // tile of 256 m is one panel, 64 rows of k a contiguous 32 KB.
+    // tile of 256 m is one panel, 64 rows of k a contiguous 32 KB.  (Read by the ATR / BTR builds only.)
     int64_t a_panel = 0;
 };
 
@@ -554,11 +554,12 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)lds;
     // rows of k a [K, ld] operand has in memory (K itself when the caller says nothing)
     const int kb_rows = g.kb_rows > 0 ? g.kb_rows : g.K;
+    constexpr bool kPanels = ATR || BTR;             // only the gradient products take an A stored in panels
     constexpr int kTrCopyRows = 2 * kGemmWaves;      // rows of k between a wavefront's successive copies of a [K, ld] tile
     auto issue_copies = [&](const TilePlace &tp, int kt, int stage) {
         const uint8_t *pa = tp.baseA + (ATR ? (size_t)kt * BK * (size_t)g.lda * 2
-                                            : g.a_panel > 0 ? (size_t)(kt / (BM / BK)) * (size_t)g.a_panel * 2 + (size_t)(kt % (BM / BK)) * kRowBytes
-                                                            : (size_t)kt * kRowBytes);
+                                            : kPanels && g.a_panel > 0 ? (size_t)(kt / (BM / BK)) * (size_t)g.a_panel * 2 + (size_t)(kt % (BM / BK)) * kRowBytes
+                                                                       : (size_t)kt * kRowBytes);
         const uint8_t *pb = tp.baseB + (BTR ? (size_t)kt * BK * (size_t)g.ldb * 2 : (size_t)kt * kRowBytes);
         const uint32_t sa = lds_base + stage * kStageBytes;
 #pragma unroll
@@ -824,6 +825,7 @@ static hipError_t launch_gemm(const GemmArgs &g, const Epi &epi, hipStream_t str
     int grid = gemm_cu_count() / 8 * 8;     // one workgroup per CU; a multiple of the XCD count
     if (grid < 8) grid = 8;
     if (grid > total) grid = total;
+    if (g.a_panel > 0 && !(ATR || BTR)) return hipErrorInvalidValue;   // the other builds do not read a_panel
     hipLaunchKernelGGL((gemm_nt_kernel<Epi, NEEDS_FINISH, F8, ATR, BTR>), dim3((unsigned)grid), dim3(kGemmThreads),
                        kGemmLdsBytes, stream, g, epi, tiles_m, tiles_n);
     return hipGetLastError();

@@ -118,6 +118,48 @@ __device__ __forceinline__ int rows_on_device(const int *n_dev, int n_off, int r
 }
 
 // ---------------------------------------------------------------------------
+// From a row per lane to whole lines per store.  In a swapped 32x32 block (see EpiMax) lane l holds, of token row
+// l % 32, the columns 8 q + 4 (l / 32) .. + 3 in x[q]: a 16-byte store of x[q] puts 32 bytes on each of 32 rows.
+// Afterwards lane l holds in x[q] the columns 16 (l / 32) + 4 (l % 4) .. + 3 of token row (l % 32 & ~3) + q: four
+// neighbouring lanes then store 64 consecutive bytes, and the eight lanes l % 4, l / 32 a row's whole 128-byte line.
+// Two steps: the two halves of the wavefront trade registers (v_permlane32_swap) so that a lane owns 16 consecutive
+// columns of its row, then each group of four lanes transposes its 4 x 4 pieces of 16 bytes (two butterfly stages
+// through the quad permutation of the data-parallel move).  Lane layout checked element by element on the device.
+// ---------------------------------------------------------------------------
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+template <int QUAD_PERM>
+__device__ __forceinline__ float quad_from(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), QUAD_PERM, 0xf, 0xf, true));
+}
+template <int QUAD_PERM>
+__device__ __forceinline__ void trade_pieces(f32x4 &lo, f32x4 &hi, bool upper)
+{
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const float sent = upper ? lo[c] : hi[c];
+        const float got = quad_from<QUAD_PERM>(sent);
+        lo[c] = upper ? got : lo[c];
+        hi[c] = upper ? hi[c] : got;
+    }
+}
+__device__ __forceinline__ void rows_to_lines(f32x4 (&x)[4], int lane)
+{
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x[0][c]), __float_as_uint(x[2][c]), false, false);
+        x[0][c] = __uint_as_float(r[0]); x[2][c] = __uint_as_float(r[1]);
+        r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x[1][c]), __float_as_uint(x[3][c]), false, false);
+        x[1][c] = __uint_as_float(r[0]); x[3][c] = __uint_as_float(r[1]);
+    }
+    const f32x4 t = x[1]; x[1] = x[2]; x[2] = t;     // x[s] now: columns 16 (l / 32) + 4 s .. + 3 of the lane's row
+    constexpr int kXor1 = 0xB1, kXor2 = 0x4E;        // quad permutations [1, 0, 3, 2] and [2, 3, 0, 1]
+    const bool odd = lane & 1, up = lane & 2;
+    trade_pieces<kXor1>(x[0], x[1], odd); trade_pieces<kXor1>(x[2], x[3], odd);
+    trade_pieces<kXor2>(x[0], x[2], up);  trade_pieces<kXor2>(x[1], x[3], up);
+}
+
+// ---------------------------------------------------------------------------
 // epilogues: called once per wavefront with its 64x128 accumulator block.
 // Element (mi, ni, i) of lane l is row r0 + mi*32 + (i/4)*8 + (l/32)*4 + i%4,
 // column c0 + ni*32 + l%32 of the launch's output (kSwapped epilogues: see EpiMax).  `lds` is the workgroup's
@@ -135,9 +177,13 @@ struct EpiMax {
     // vocabulary column c0 + ni*32 + (i/4)*8 + (l/32)*4 + i%4.  A lane owns one token row per mi and
     // four consecutive columns per register quad: the row maximum is 63 in-lane maxima and one exchange
     // with lane l ^ 32 (the column-per-lane layout needs five exchanges for each of 32 rows and 32 atomic
-    // instructions of two lanes each), the sampled token's id is loaded once per lane, and the logits
-    // leave as 16-byte stores.  Measured on the forward product of configs[4] (9.44 ms per block of 8192
-    // rows with the column-per-lane epilogue): 0.57 ms of it were the maxima, 0.85 ms the 4-byte stores.
+    // instructions of two lanes each) and the sampled token's id is loaded once per lane.  Measured on the
+    // forward product of configs[4] (9.44 ms per block of 8192 rows with the column-per-lane epilogue): 0.57 ms
+    // of it were the maxima, 0.85 ms the 4-byte stores.  The logits leave as 16-byte stores after the lanes
+    // have traded pieces so that a store covers whole lines (rows_to_lines): stored straight from the row-per-lane
+    // layout (32 bytes on each of 32 rows per store) they cost 0.9 ms per block, two thirds of it spent issuing
+    // them into the L2; with whole lines the block takes 8.15 ms instead of 8.45.  Whole lines can also leave as
+    // nontemporal stores (0.3 ms per call less; as 32-byte pieces they had cost the call 11 ms).
     static constexpr bool kSwapped = true;
     RowStats st;
     const int64_t *ids;
@@ -155,7 +201,6 @@ struct EpiMax {
             // column N - 1 and are never the sampled one: y < N)
             const int yc = (y >= (int64_t)c0 && y < (int64_t)c0 + NI * 32) ? (int)(y - c0) : -1;
             float v = -INFINITY;
-            float *zrow = Z + (int64_t)row * ldz + c0;
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni) {
 #pragma unroll
@@ -165,9 +210,17 @@ struct EpiMax {
                                 z3 = acc[mi][ni][q * 4 + 3];
                     v = fmaxf(fmaxf(v, fmaxf(z0, z1)), fmaxf(z2, z3));    // (repeated columns repeat a real logit)
                     if (yc >= colb && yc < colb + 4) st.zy[row] = yc == colb ? z0 : (yc == colb + 1 ? z1 : (yc == colb + 2 ? z2 : z3));
-                    if constexpr (STORE_Z) {
-                        if (row_ok) *(f32x4 *)(zrow + colb) = (f32x4){z0, z1, z2, z3};
-                    }
+                }
+                if constexpr (STORE_Z) {
+                    f32x4 x[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) x[q] = (f32x4){acc[mi][ni][q * 4], acc[mi][ni][q * 4 + 1], acc[mi][ni][q * 4 + 2], acc[mi][ni][q * 4 + 3]};
+                    rows_to_lines(x, lane);
+                    const int row0 = r0 + mi * 32 + ((lane % 32) & ~3);
+                    float *zline = Z + (int64_t)row0 * ldz + c0 + ni * 32 + 16 * half + 4 * (lane % 4);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        if (row0 + q < g.M) __builtin_nontemporal_store(x[q], (f32x4 *)(zline + (int64_t)q * ldz));
                 }
             }
             v = fmaxf(v, __shfl_xor(v, 32, kWave));

@@ -57,7 +57,10 @@ constexpr int kWaveStageBytes = kPipeLdsBytes / kGemmWaves;   // 16 KB: a wavefr
 static_assert(kWaveStageBytes == MI * 32 * NI * 32 * 2, "epilogue staging assumes one bf16 block per wavefront");
 constexpr int kCopiesPerWave = BM * (BK / 8) / kWave / kGemmWaves;   // 1 KB wavefront copies per operand tile and wavefront
 static_assert(BM == BN, "the operand tiles share one copy schedule");
-constexpr int kRowBlock = 8192;                 // token rows whose logits and masked exponentials are held at a time
+constexpr int kRowBlock = 8192;                 // token rows whose logits are held at a time
+constexpr int kDwBlocks = 2;                    // row blocks whose masked exponentials are held for one dW product
+constexpr int kHstPad = 64;                     // elements added to the row pitch of (diag(s) H)^T: a tile's 256 rows, a power of
+                                                // two apart otherwise, then start on different 128-byte lines
 
 __device__ __forceinline__ int float_to_ordered(float f)
 {
@@ -1174,6 +1177,7 @@ struct LmLayout {
     size_t off_ps[2], off_pf[2], off_pc[2];
     size_t off_hst, off_e, off_z;
     int block_pad, v_pad, col_tiles;
+    int e_blocks;        // row blocks of E (and of the scaled H^T) the workspace holds: one dW product's worth
 };
 
 static LmLayout lm_layout(int64_t n, int64_t d, int64_t v, bool dense_buffers = true)
@@ -1183,6 +1187,8 @@ static LmLayout lm_layout(int64_t n, int64_t d, int64_t v, bool dense_buffers = 
     L.block_pad = (int)((block + BM - 1) / BM * BM);
     L.v_pad = (int)((v + BN - 1) / BN * BN);
     L.col_tiles = L.v_pad / BN;
+    const int64_t n_blocks = (n + kRowBlock - 1) / kRowBlock;
+    L.e_blocks = (int)(n_blocks < kDwBlocks ? (n_blocks < 1 ? 1 : n_blocks) : kDwBlocks);
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o += align256(bytes); return at; };
     for (int s = 0; s < 2; ++s) {
@@ -1197,8 +1203,8 @@ static LmLayout lm_layout(int64_t n, int64_t d, int64_t v, bool dense_buffers = 
     L.off_hst = L.off_e = L.off_z = 0;
     if (dense_buffers) {
         L.off_z = take((size_t)L.block_pad * L.v_pad * 4);      // fp32 logits of one row block
-        L.off_hst = take((size_t)d * L.block_pad * 2);          // (diag(s) H)^T of one row block
-        L.off_e = take((size_t)L.block_pad * L.v_pad * 2);      // masked exponentials of one row block
+        L.off_hst = take((size_t)d * (L.e_blocks * L.block_pad + kHstPad) * 2);   // (diag(s) H)^T of the blocks of one dW product
+        L.off_e = take((size_t)L.e_blocks * L.block_pad * L.v_pad * 2);      // their masked exponentials
     }
     L.total = o;
     return L;
@@ -1351,13 +1357,25 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
         }
     }
     uint16_t *hst = (uint16_t *)(ws + L.off_hst);
-    uint16_t *E = (uint16_t *)(ws + L.off_e);   // of the current row block
     float *unit_coef = saved ? (float *)((char *)saved + SV.off_ucoef) : nullptr;
     float *unit_scale = saved ? (float *)((char *)saved + SV.off_uscale) : nullptr;
-    auto use_block = [&](int r0) {   // saved phases keep every block's E; the fused call reuses one
-        if (phase == LM_FUSED) return;
-        const size_t b = (size_t)(r0 / kRowBlock) * SV.block_bytes;
-        E = (uint16_t *)((char *)saved + SV.off_e + b);
+    // Where the masked exponentials of the row block at r0 lie.  Up to kDwBlocks consecutive row blocks form a
+    // group with one panelled E (panels of 256 columns over the group's rows, a block's rows following the
+    // previous block's: every block but the call's last is full) and one dW product.  The fused call reuses one
+    // group's room in the workspace; the saved phases keep every group, one after the other.
+    struct EPlace {
+        uint16_t *group;     // E of the group
+        int64_t panel;       // elements per panel
+        int64_t ld_t;        // row pitch of the group's (diag(s) H)^T
+        int first_row;       // of the block within the group
+    };
+    const int n_blocks = (n + kRowBlock - 1) / kRowBlock;
+    auto e_place = [&](int r0) {
+        const int b = r0 / kRowBlock, grp = b / kDwBlocks;
+        const int in_group = (n_blocks - grp * kDwBlocks) < kDwBlocks ? (n_blocks - grp * kDwBlocks) : kDwBlocks;
+        char *base = phase == LM_FUSED ? ws + L.off_e : (char *)saved + SV.off_e + (size_t)grp * kDwBlocks * SV.block_bytes;
+        return EPlace{(uint16_t *)base, (int64_t)in_group * L.block_pad * BM, (int64_t)in_group * L.block_pad + kHstPad,
+                      (b % kDwBlocks) * L.block_pad};
     };
     const int tb = 256;
 #define DVP_CHECK_LAUNCH() do { if (hipGetLastError() != hipSuccess) return DVP_ERR_HIP; } while (0)
@@ -1367,7 +1385,8 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
     auto forward = [&](int s, int r0, int rows, bool write_e, RowStats &st) -> dvp_status {
         st.max_key = (int *)(ws + L.off_i32[s]); st.zy = (float *)(ws + L.off_zy[s]);
         st.m = (float *)(ws + L.off_m[s]); st.tau = (float *)(ws + L.off_tau[s]);
-        st.coef = (float *)(ws + L.off_coef); st.scale = (float *)(ws + L.off_scale);
+        // (the gradient factors are kept for every row of the call: a group's dW product comes after its last block)
+        st.coef = (float *)(ws + L.off_coef) + r0; st.scale = (float *)(ws + L.off_scale) + r0;
         if (phase == LM_FORWARD_SAVE) { st.coef = unit_coef + r0; st.scale = unit_scale + r0; }
         st.part_s = (float *)(ws + L.off_ps[s]); st.part_c = (int *)(ws + L.off_pc[s]);
         st.part_f = outs[s].lse_full ? (float *)(ws + L.off_pf[s]) : nullptr;
@@ -1393,7 +1412,7 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
         }
         hipLaunchKernelGGL(init_stats_kernel, dim3(nb), dim3(tb), 0, stream, st, rows);
         DVP_CHECK_LAUNCH();
-        const int64_t e_panel = (int64_t)L.block_pad * BM;
+        const EPlace ep = e_place(r0);
         if (!stats_only_ws) {
             // One pass of the product: row maxima, and the block's logits kept as fp32; the sums at the
             // threshold (and E) are then read off the stored logits.  Re-reading them costs a few percent
@@ -1408,7 +1427,7 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
             ZRowArgs za;
             za.Z = Z; za.ldz = L.v_pad; za.st = st; za.out = o; za.ids = ids + r0;
             za.grad_out = grad_out ? grad_out + r0 : nullptr; za.row_flags = row_flags ? row_flags + r0 : nullptr;
-            za.E = E; za.e_panel = e_panel; za.bits = bits; za.bits_ld = bits_ld;
+            za.E = ep.group + (int64_t)ep.first_row * BM; za.e_panel = ep.panel; za.bits = bits; za.bits_ld = bits_ld;
             za.vocab = v; za.v_pad = L.v_pad; za.side = s; za.unit_grad = phase == LM_FORWARD_SAVE ? 1 : 0;
             za.n_dev = n_dev; za.n_off = r0; za.rows = rows;
             const dim3 zg((unsigned)rows), zb(kZRowThreads);
@@ -1451,38 +1470,62 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
 
     RowStats st;
     dvp_status rc;
-    // dH and dW of the row block at r0 from its E / E^T and the per-row factors coef (q) and scale (s)
-    auto backward_block = [&](int r0, int rows, const float *coef, const float *scale) -> dvp_status {
+    // dH of the row block at r0 from its E and the per-row factors coef (q) and scale (s), and the block's part of
+    // the second operand of its group's dW product
+    auto backward_dh = [&](int r0, int rows, const float *coef, const float *scale) -> dvp_status {
+        const EPlace ep = e_place(r0);
         const int rows_pad = (rows + BM - 1) / BM * BM;
         const uint16_t *hblock = (const uint16_t *)hidden + (int64_t)r0 * p->ld_hidden;
         // (diag(s) H)^T of the block, zero columns up to the row tile (they pad the K dimension of the dW product)
         hipLaunchKernelGGL(transpose_bf16_kernel, dim3((d + kTrTile - 1) / kTrTile, (rows_pad + kTrTile - 1) / kTrTile),
                            dim3(kTrThreads), 0, stream,
-                           hblock, p->ld_hidden, hst, (int64_t)L.block_pad, rows, d, rows_pad, scale, n_dev, r0);
+                           hblock, p->ld_hidden, hst + ep.first_row, ep.ld_t, rows, d, rows_pad, scale, n_dev, r0);
         DVP_CHECK_LAUNCH();
         // dH[r0 : r0 + rows, :] = diag(s) . E [rows, v_pad] . W [v, d] + diag(q) . W[y, :]; W is read as it lies, its rows
         // are the product's k (E's columns from v to v_pad are zero)
         GemmArgs gh;
-        gh.A = E; gh.lda = BM; gh.a_panel = (int64_t)L.block_pad * BM; gh.B = (const uint16_t *)w_train; gh.ldb = p->ld_w;
+        gh.A = ep.group + (int64_t)ep.first_row * BM; gh.lda = BM; gh.a_panel = ep.panel;
+        gh.B = (const uint16_t *)w_train; gh.ldb = p->ld_w;
         gh.M = rows; gh.N = d; gh.K = L.v_pad; gh.kb_rows = (int)v; gh.b_cols = (int)d; gh.scale = 1.0f;
         if (n_dev) { gh.n_dev = n_dev; gh.n_off = r0; gh.dev_dim = 1; }
         const EpiStore eh{d_hidden + (int64_t)r0 * p->ld_hidden, p->ld_hidden, 0, scale, coef, ids + r0,
                           (const uint16_t *)w_train, p->ld_w};
         if (launch_gemm<EpiStore, false, false, false, true>(gh, eh, stream) != hipSuccess) return DVP_ERR_HIP;
-        // dW (+)= E^T . diag(s) H, then the sampled tokens' rows: E as it lies (the block's rows are the product's k,
-        // zero rows from `rows` to rows_pad), against the small transposed copy of diag(s) H
+        return DVP_OK;
+    };
+    // dW (+)= E^T . diag(s) H over the `rows` token rows of the group that starts at r0, then the sampled tokens' rows:
+    // E as it lies (the group's rows are the product's k, zero rows from the last one to the row tile), against the
+    // small transposed copy of diag(s) H
+    auto backward_dw = [&](int r0, int rows, const float *coef) -> dvp_status {
+        const EPlace ep = e_place(r0);
         GemmArgs gw;
-        gw.A = E; gw.lda = BM; gw.a_panel = (int64_t)L.block_pad * BM; gw.B = hst; gw.ldb = L.block_pad;
-        gw.M = v; gw.N = d; gw.K = rows_pad; gw.scale = 1.0f;
+        gw.A = ep.group; gw.lda = BM; gw.a_panel = ep.panel; gw.B = hst; gw.ldb = ep.ld_t;
+        gw.M = v; gw.N = d; gw.K = (rows + BM - 1) / BM * BM; gw.scale = 1.0f;
         if (n_dev) { gw.n_dev = n_dev; gw.n_off = r0; gw.dev_dim = 2; }
         const EpiStore ew{d_w, p->ld_w, r0 > 0 || dw_accumulate, nullptr, nullptr, nullptr, nullptr, 0};
         if (launch_gemm<EpiStore, false, false, true, false>(gw, ew, stream) != hipSuccess) return DVP_ERR_HIP;
         for (int q0 = 0; q0 < rows; q0 += kOnehotRows) {   // in row order: launches on one stream run in order
             const int qrows = (rows - q0) < kOnehotRows ? (rows - q0) : kOnehotRows;
             hipLaunchKernelGGL(onehot_dw_kernel, dim3(qrows), dim3(kOnehotThreads), 0, stream, ids + r0 + q0,
-                               coef + q0, hblock + (int64_t)q0 * p->ld_hidden, p->ld_hidden, d_w, p->ld_w, qrows, d, n_dev,
-                               r0 + q0);
+                               coef + q0, (const uint16_t *)hidden + (int64_t)(r0 + q0) * p->ld_hidden, p->ld_hidden, d_w,
+                               p->ld_w, qrows, d, n_dev, r0 + q0);
             DVP_CHECK_LAUNCH();
+        }
+        return DVP_OK;
+    };
+    // the training side with gradient: per group of row blocks, `block` for each of its blocks, then the group's dW
+    auto by_groups = [&](auto &&block) -> dvp_status {
+        constexpr int kGroupRows = kDwBlocks * kRowBlock;
+        const float *coef = (const float *)(ws + L.off_coef);
+        for (int g0 = 0; g0 < n; g0 += kGroupRows) {
+            const int g_rows = (n - g0) < kGroupRows ? (n - g0) : kGroupRows;
+            for (int r0 = g0; r0 < g0 + g_rows; r0 += kRowBlock) {
+                const int rows = (g0 + g_rows - r0) < kRowBlock ? (g0 + g_rows - r0) : kRowBlock;
+                const dvp_status rs = block(r0, rows);
+                if (rs != DVP_OK) return rs;
+            }
+            const dvp_status rs = backward_dw(g0, g_rows, coef + g0);
+            if (rs != DVP_OK) return rs;
         }
         return DVP_OK;
     };
@@ -1500,31 +1543,26 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
 
     if (phase == LM_BACKWARD_SAVED) {
         float *coef = (float *)(ws + L.off_coef), *scale = (float *)(ws + L.off_scale);
-        for (int r0 = 0; r0 < n; r0 += kRowBlock) {
-            const int rows = (n - r0) < kRowBlock ? (n - r0) : kRowBlock;
-            use_block(r0);
-            hipLaunchKernelGGL(apply_grad_kernel, dim3((rows + tb - 1) / tb), dim3(tb), 0, stream, coef, scale,
+        return by_groups([&](int r0, int rows) -> dvp_status {
+            hipLaunchKernelGGL(apply_grad_kernel, dim3((rows + tb - 1) / tb), dim3(tb), 0, stream, coef + r0, scale + r0,
                                (const float *)unit_coef + r0, (const float *)unit_scale + r0, grad_out + r0, rows);
             DVP_CHECK_LAUNCH();
-            if ((rc = backward_block(r0, rows, coef, scale)) != DVP_OK) return rc;
-        }
-        return DVP_OK;
+            return backward_dh(r0, rows, coef + r0, scale + r0);
+        });
     }
     if (phase == LM_FORWARD_SAVE) {
         for (int r0 = 0; r0 < n; r0 += kRowBlock) {
             const int rows = (n - r0) < kRowBlock ? (n - r0) : kRowBlock;
-            use_block(r0);
             if ((rc = forward(0, r0, rows, true, st)) != DVP_OK) return rc;
         }
     } else if (!grad_out) {
         if ((rc = forward_all(0)) != DVP_OK) return rc;
     } else {
-        // training side with gradient, in blocks of kRowBlock token rows
-        for (int r0 = 0; r0 < n; r0 += kRowBlock) {
-            const int rows = (n - r0) < kRowBlock ? (n - r0) : kRowBlock;
-            if ((rc = forward(0, r0, rows, true, st)) != DVP_OK) return rc;
-            if ((rc = backward_block(r0, rows, st.coef, st.scale)) != DVP_OK) return rc;
-        }
+        rc = by_groups([&](int r0, int rows) -> dvp_status {
+            const dvp_status rs = forward(0, r0, rows, true, st);
+            return rs != DVP_OK ? rs : backward_dh(r0, rows, st.coef, st.scale);
+        });
+        if (rc != DVP_OK) return rc;
     }
     if (infer_side) {
         if ((rc = forward_all(1)) != DVP_OK) return rc;

@@ -775,7 +775,6 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs
     for (;;) {
         const int t_next = t + (int)gridDim.x;
         const bool has_next = t_next < total;
-        if (has_next) place(t_next, nxt);
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
@@ -783,7 +782,8 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.0f;
 
-        for (int j = 0; j < nk; ++j) {
+        // one K step; `issue_next` starts the copies that may overwrite the stage this step has just finished with
+        auto k_step = [&](int j, auto &&issue_next) {
             const int stage = (sp + j) & 1;
             if constexpr (F8) {
                 fetch(1, stage, 1); multiply(0);
@@ -795,11 +795,17 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs
             // own reads of K step j are home, own copies of step j+1 have landed; past the
             // barrier that holds for every wavefront
             wait_copies_and_barrier();
-            if (j + 2 < nk) issue_copies(cur, j + 2, stage);
-            else if (chain && has_next) issue_copies(nxt, j + 2 - nk, stage);
+            issue_next(stage);
             fetch(0, stage ^ 1, 0);         // step j+1, or step 0 of the next tile; unused (dead buffer) otherwise
             multiply(1);
-        }
+        };
+        int j = 0;
+        for (; j + 2 < nk; ++j) k_step(j, [&](int stage) { issue_copies(cur, j + 2, stage); });
+        // The last two steps copy the first two of the next tile.  Its placement is formed here and not before the
+        // loop: its per-lane offsets would otherwise occupy registers through the whole loop (with them the builds
+        // that take an operand as it lies spilled one and reloaded it inside the loop).
+        if (has_next) place(t_next, nxt);
+        for (; j < nk; ++j) k_step(j, [&](int stage) { if (chain && has_next) issue_copies(nxt, j + 2 - nk, stage); });
 
         if constexpr (F8) {
 #pragma unroll

@@ -1078,7 +1078,15 @@ __global__ __launch_bounds__(kAfterRows * kAfterSegs) void after_sum_kernel(RowS
 // after the block's E^T product has been written to dW.
 constexpr int kOnehotThreads = 256;
 constexpr int kOnehotRows = 4096;       // rows per launch: every workgroup scans its launch's sampled tokens
-__global__ __launch_bounds__(kOnehotThreads) void onehot_dw_kernel(const int64_t *ids, const float *coef, const uint16_t *H,
+// tokens[r] = the sampled token of row r as a 32-bit integer, -1 where the row contributes nothing (coef 0): what
+// every workgroup of onehot_dw_kernel scans, a third of the bytes of the ids and factors themselves
+__global__ void onehot_tokens_kernel(const int64_t *ids, const float *coef, int *tokens, int rows)
+{
+    const int r = blockIdx.x * blockDim.x + threadIdx.x;
+    if (r < rows) tokens[r] = coef[r] != 0.0f ? (int)ids[r] : -1;
+}
+
+__global__ __launch_bounds__(kOnehotThreads) void onehot_dw_kernel(const int *tokens, const float *coef, const uint16_t *H,
                                                                    int64_t ld_h, float *dW, int64_t ld_w, int rows, int d,
                                                                    const int *n_dev = nullptr, int n_off = 0)
 {
@@ -1088,7 +1096,7 @@ __global__ __launch_bounds__(kOnehotThreads) void onehot_dw_kernel(const int64_t
     __shared__ uint16_t match[kOnehotRows];   // rows that sampled this workgroup's token, ascending
     __shared__ int n_match;
     const int i = blockIdx.x, tid = threadIdx.x;
-    for (int r = tid; r < rows; r += kOnehotThreads) tok[r] = coef[r] != 0.0f ? (int)ids[r] : -1;
+    for (int r = tid; r < rows; r += kOnehotThreads) tok[r] = tokens[r];
     __syncthreads();
     const int y = tok[i];
     if (y < 0) return;
@@ -1108,13 +1116,35 @@ __global__ __launch_bounds__(kOnehotThreads) void onehot_dw_kernel(const int64_t
     }
     __syncthreads();
     const int nm = n_match;
+    float *wrow = dW + (int64_t)y * ld_w;
+    // Four columns per thread where the rows of dW allow 16-byte accesses (the rows of H always allow 8-byte ones: the
+    // entry points check its alignment and pitch): a few wide, independent accesses per thread instead of d / 256
+    // narrow ones in a row, each waiting for the one before.  Per element the sums are formed in the same order.
+    if (((((uintptr_t)dW) | (uintptr_t)(ld_w * 4)) & 15u) == 0 && (d & 3) == 0) {
+#pragma unroll 4
+        for (int u = tid; u < d / 4; u += kOnehotThreads) {
+            f32x4 a = {0.0f, 0.0f, 0.0f, 0.0f};
+            for (int q = 0; q < nm; ++q) {
+                const int r = match[q];
+                const float c = coef[r];
+                const uint2 h = *(const uint2 *)(H + (int64_t)r * ld_h + 4 * u);
+                a[0] += c * __uint_as_float(h.x << 16);
+                a[1] += c * __uint_as_float(h.x & 0xffff0000u);
+                a[2] += c * __uint_as_float(h.y << 16);
+                a[3] += c * __uint_as_float(h.y & 0xffff0000u);
+            }
+            f32x4 *p = (f32x4 *)(wrow + 4 * u);
+            *p = *p + a;
+        }
+        return;
+    }
     for (int j = tid; j < d; j += kOnehotThreads) {
         float a = 0.0f;
         for (int q = 0; q < nm; ++q) {
             const int r = match[q];
             a += coef[r] * __uint_as_float((uint32_t)H[(int64_t)r * ld_h + j] << 16);
         }
-        dW[(int64_t)y * ld_w + j] += a;
+        wrow[j] += a;
     }
 }
 
@@ -1181,7 +1211,7 @@ struct LmLayout {
     size_t total;
     size_t off_i32[2], off_zy[2], off_m[2], off_tau[2], off_coef, off_scale;
     size_t off_ps[2], off_pf[2], off_pc[2];
-    size_t off_hst, off_e, off_z;
+    size_t off_hst, off_e, off_z, off_tok;
     int block_pad, v_pad, col_tiles;
     int e_blocks;        // row blocks of E (and of the scaled H^T) the workspace holds: one dW product's worth
 };
@@ -1206,9 +1236,10 @@ static LmLayout lm_layout(int64_t n, int64_t d, int64_t v, bool dense_buffers = 
     }
     L.off_coef = take(n * 4);
     L.off_scale = take(n * 4);
-    L.off_hst = L.off_e = L.off_z = 0;
+    L.off_hst = L.off_e = L.off_z = L.off_tok = 0;
     if (dense_buffers) {
         L.off_z = take((size_t)L.block_pad * L.v_pad * 4);      // fp32 logits of one row block
+        L.off_tok = take(n * 4);                                // sampled tokens as 32-bit integers, for the sampled-token part of dW
         L.off_hst = take((size_t)d * (L.e_blocks * L.block_pad + kHstPad) * 2);   // (diag(s) H)^T of the blocks of one dW product
         L.off_e = take((size_t)L.e_blocks * L.block_pad * L.v_pad * 2);      // their masked exponentials
     }
@@ -1510,9 +1541,12 @@ static dvp_status run_lmhead(const dvp_lmhead_params *p, const void *hidden, con
         if (n_dev) { gw.n_dev = n_dev; gw.n_off = r0; gw.dev_dim = 2; }
         const EpiStore ew{d_w, p->ld_w, r0 > 0 || dw_accumulate, nullptr, nullptr, nullptr, nullptr, 0};
         if (launch_gemm<EpiStore, false, false, true, false>(gw, ew, stream) != hipSuccess) return DVP_ERR_HIP;
+        int *tokens = (int *)(ws + L.off_tok) + r0;
+        hipLaunchKernelGGL(onehot_tokens_kernel, dim3((rows + tb - 1) / tb), dim3(tb), 0, stream, ids + r0, coef, tokens, rows);
+        DVP_CHECK_LAUNCH();
         for (int q0 = 0; q0 < rows; q0 += kOnehotRows) {   // in row order: launches on one stream run in order
             const int qrows = (rows - q0) < kOnehotRows ? (rows - q0) : kOnehotRows;
-            hipLaunchKernelGGL(onehot_dw_kernel, dim3(qrows), dim3(kOnehotThreads), 0, stream, ids + r0 + q0,
+            hipLaunchKernelGGL(onehot_dw_kernel, dim3(qrows), dim3(kOnehotThreads), 0, stream, tokens + q0,
                                coef + q0, (const uint16_t *)hidden + (int64_t)(r0 + q0) * p->ld_hidden, p->ld_hidden, d_w,
                                p->ld_w, qrows, d, n_dev, r0 + q0);
             DVP_CHECK_LAUNCH();

@@ -240,7 +240,11 @@ struct EpiMax {
 // Candidates (token, z) are appended in arrival order; at most cand_cap are kept.
 struct EpiMaxCand {
     static constexpr bool kRowMap = false;
-    static constexpr bool kSwapped = false;
+    // Operands swapped as in EpiMax: a lane owns a token row, so the maximum over the wavefront's 128 columns, the
+    // threshold and the test of the row's 128 logits against it are all in-lane.  Candidates are rare where this
+    // form is used (peaked rows): the lanes that have any are served one after the other, their hit mask and their
+    // logits read through v_readlane, every register named statically.
+    static constexpr bool kSwapped = true;
     RowStats st;
     const int64_t *ids;
     const float *zy_low;     // [n] lower bound of the row maximum, -inf where there is none
@@ -250,51 +254,70 @@ struct EpiMaxCand {
     float log_rho;
     __device__ __forceinline__ void operator()(const GemmArgs &g, f32x16 (&acc)[MI][NI], int r0, int c0, int lane, uint8_t *, int, int) const
     {
+        const int half = lane / 32;
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
+            const int row = r0 + mi * 32 + (lane % 32);
+            const bool row_ok = row < g.M;
+            const int64_t y = row_ok ? ids[row] : -1;
+            const int yc = (y >= (int64_t)c0 && y < (int64_t)c0 + NI * 32) ? (int)(y - c0) : -1;   // see EpiMax
+            float v = -INFINITY;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int row = r0 + mi * 32 + (i / 4) * 8 + (lane / 32) * 4 + (i % 4);
-                const bool row_ok = row < g.M;
-                const int64_t y = row_ok ? ids[row] : -1;
-                float v = -INFINITY;
+            for (int ni = 0; ni < NI; ++ni) {
 #pragma unroll
-                for (int ni = 0; ni < NI; ++ni) {
-                    const int col = c0 + ni * 32 + (lane % 32);
-                    const float z = acc[mi][ni][i];
-                    if (col < g.N) {
-                        v = fmaxf(v, z);
-                        if (row_ok && (int64_t)col == y) st.zy[row] = z;
-                    }
+                for (int q = 0; q < 4; ++q) {
+                    const int colb = ni * 32 + q * 8 + half * 4;
+                    const float z0 = acc[mi][ni][q * 4], z1 = acc[mi][ni][q * 4 + 1], z2 = acc[mi][ni][q * 4 + 2],
+                                z3 = acc[mi][ni][q * 4 + 3];
+                    v = fmaxf(fmaxf(v, fmaxf(z0, z1)), fmaxf(z2, z3));    // (repeated columns repeat a real logit)
+                    if (yc >= colb && yc < colb + 4) st.zy[row] = yc == colb ? z0 : (yc == colb + 1 ? z1 : (yc == colb + 2 ? z2 : z3));
                 }
+            }
+            v = fmaxf(v, __shfl_xor(v, 32, kWave));
+            if (half == 0 && row_ok) atomicMax(st.max_key + row, float_to_ordered(v));
+            // <= the row's final threshold (fp32 addition is monotone)
+            const float thr = row_ok ? fmaxf(v, zy_low[row]) + log_rho : INFINITY;
+            // bit ni * 16 + q * 4 + e of the lane's mask: column c0 + ni * 32 + q * 8 + half * 4 + e is a candidate
+            uint32_t m_lo = 0u, m_hi = 0u;
 #pragma unroll
-                for (int off = 16; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
-                if ((lane % 32) == 0 && row_ok) atomicMax(st.max_key + row, float_to_ordered(v));
-                // <= the row's final threshold (fp32 addition is monotone)
-                const float thr = row_ok ? fmaxf(v, zy_low[row]) + log_rho : INFINITY;
-                bool mine = false;
+            for (int ni = 0; ni < NI; ++ni) {
 #pragma unroll
-                for (int ni = 0; ni < NI; ++ni) mine |= (c0 + ni * 32 + (lane % 32)) < g.N && acc[mi][ni][i] >= thr;
-                if (__builtin_amdgcn_ballot_w64(mine) == 0ull) continue;      // the same for the whole wavefront
-                int *cur = cursor + (row_ok ? row : 0);
-                // one look per lane and row: a full buffer stops the appends (a stale value only costs appends)
-                const bool open = mine && __hip_atomic_load(cur, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) <= cand_cap;
+                for (int i = 0; i < 16; ++i) {
+                    const int col = c0 + ni * 32 + (i / 4) * 8 + half * 4 + (i % 4);
+                    const uint32_t hit = (col < g.N && acc[mi][ni][i] >= thr) ? 1u : 0u;
+                    if (ni * 16 + i < 32) m_lo |= hit << (ni * 16 + i);
+                    else                  m_hi |= hit << (ni * 16 + i - 32);
+                }
+            }
+            static_assert(NI * 16 == 64, "the hit mask of a lane and row is two 32-bit words");
+            bool mine = (m_lo | m_hi) != 0u;
+            if (__builtin_amdgcn_ballot_w64(mine) == 0ull) continue;          // the same for the whole wavefront
+            // one look per lane and row: a full buffer stops the appends (a stale value only costs appends)
+            if (mine && __hip_atomic_load(cursor + row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) > cand_cap) mine = false;
+            unsigned long long todo = __builtin_amdgcn_ballot_w64(mine);
+            while (todo != 0ull) {                                            // wavefront-uniform
+                const int src = __builtin_ctzll(todo);
+                todo &= todo - 1ull;
+                const uint32_t s_lo = (uint32_t)__builtin_amdgcn_readlane((int)m_lo, src);
+                const uint32_t s_hi = (uint32_t)__builtin_amdgcn_readlane((int)m_hi, src);
+                const int s_row = r0 + mi * 32 + (src % 32), s_half = src / 32;
+                int base = 0;
+                if (lane == 0) base = atomicAdd(cursor + s_row, __builtin_popcount(s_lo) + __builtin_popcount(s_hi));
+                base = __builtin_amdgcn_readfirstlane(base);
+                dvp_grad_entry *out = cand + (int64_t)s_row * cand_cap;
+                int pos = base;
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni) {
-                    const int col = c0 + ni * 32 + (lane % 32);
-                    const float z = acc[mi][ni][i];
-                    const bool take = open && col < g.N && z >= thr;
-                    // the 32 lanes of a row reserve their slots with one atomic (lanes 32..63 hold another row)
-                    const uint32_t group = (uint32_t)(__builtin_amdgcn_ballot_w64(take) >> (lane & 32));
-                    if (group == 0u) continue;
-                    const int leader = __builtin_ctz(group) + (lane & 32);
-                    int base = 0;
-                    if (lane == leader) base = atomicAdd(cur, __builtin_popcount(group));
-                    base = __shfl(base, leader, kWave);
-                    const int pos = base + __builtin_popcount(group & ((1u << (lane % 32)) - 1u));
-                    if (take && pos < cand_cap) {
-                        dvp_grad_entry *e = cand + (int64_t)row * cand_cap + pos;
-                        e->index = (uint32_t)col; e->value = z;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const uint32_t word = ni * 16 + i < 32 ? s_lo : s_hi;
+                        if (!((word >> ((ni * 16 + i) & 31)) & 1u)) continue;  // uniform
+                        const float z = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(acc[mi][ni][i]), src));
+                        if (lane == 0 && pos < cand_cap) {
+                            out[pos].index = (uint32_t)(c0 + ni * 32 + (i / 4) * 8 + s_half * 4 + (i % 4));
+                            out[pos].value = z;
+                        }
+                        ++pos;
                     }
                 }
             }
@@ -505,6 +528,16 @@ __device__ __forceinline__ void wait_copies_and_barrier()
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+// copy16_to_lds with the base address forced into scalar registers: it is wavefront-uniform by construction (tile
+// bases and K steps), and saying so keeps it there in builds where the compiler's own analysis loses track of that
+__device__ __forceinline__ void copy16_uniform(const void *gbase, uint32_t voff, uint32_t lds_addr)
+{
+    const uint64_t b = (uint64_t)(uintptr_t)gbase;
+    const uint64_t ub = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(b >> 32)) << 32) |
+                        (uint32_t)__builtin_amdgcn_readfirstlane((int)b);
+    copy16_to_lds((const void *)(uintptr_t)ub, voff, lds_addr);
+}
+
 // scheduling hint for a slice with more LDS reads than matrix instructions: after instruction i, its share of the reads
 template <int NM, int NR, int... I>
 __device__ __forceinline__ void spread_reads(std::integer_sequence<int, I...>)
@@ -620,8 +653,8 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs
         const uint32_t sa = lds_base + stage * kStageBytes;
 #pragma unroll
         for (int i = 0; i < kCopiesPerWave; ++i) {
-            if constexpr (ATR) copy16_to_lds(pa + (size_t)i * kTrCopyRows * (size_t)g.lda * 2, tp.off_a[0], sa + (i * kGemmWaves + wave) * 1024);
-            else               copy16_to_lds(pa, tp.off_a[i], sa + (i * kGemmWaves + wave) * 1024);
+            if constexpr (ATR) copy16_uniform(pa + (size_t)i * kTrCopyRows * (size_t)g.lda * 2, tp.off_a[0], sa + (i * kGemmWaves + wave) * 1024);
+            else               copy16_uniform(pa, tp.off_a[i], sa + (i * kGemmWaves + wave) * 1024);
         }
         // A [K, ld] B operand whose rows of k end inside or before this step: the rows past the end repeat the last one.
         // (`last` is that row relative to the step; when the whole step lies past it the base moves back to it, so that
@@ -635,13 +668,13 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs
             for (int i = 0; i < kCopiesPerWave; ++i) {
                 const int tk = tk0 + i * kTrCopyRows;
                 const int row = tk > lim ? lim : tk;
-                copy16_to_lds(pb2, tp.off_b[0] + (uint32_t)(row - tk0) * (uint32_t)(g.ldb * 2), sa + kTileBytes + (i * kGemmWaves + wave) * 1024);
+                copy16_uniform(pb2, tp.off_b[0] + (uint32_t)(row - tk0) * (uint32_t)(g.ldb * 2), sa + kTileBytes + (i * kGemmWaves + wave) * 1024);
             }
         } else {
 #pragma unroll
             for (int i = 0; i < kCopiesPerWave; ++i) {
-                if constexpr (BTR) copy16_to_lds(pb + (size_t)i * kTrCopyRows * (size_t)g.ldb * 2, tp.off_b[0], sa + kTileBytes + (i * kGemmWaves + wave) * 1024);
-                else               copy16_to_lds(pb, tp.off_b[i], sa + kTileBytes + (i * kGemmWaves + wave) * 1024);
+                if constexpr (BTR) copy16_uniform(pb + (size_t)i * kTrCopyRows * (size_t)g.ldb * 2, tp.off_b[0], sa + kTileBytes + (i * kGemmWaves + wave) * 1024);
+                else               copy16_uniform(pb, tp.off_b[i], sa + kTileBytes + (i * kGemmWaves + wave) * 1024);
             }
         }
     };

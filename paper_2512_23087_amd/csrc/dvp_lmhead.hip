@@ -284,7 +284,7 @@ struct EpiMaxCand {
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int col = c0 + ni * 32 + (i / 4) * 8 + half * 4 + (i % 4);
-                    const uint32_t hit = (col < g.N && acc[mi][ni][i] >= thr) ? 1u : 0u;
+                    const uint32_t hit = (row_ok && col < g.N && acc[mi][ni][i] >= thr) ? 1u : 0u;   // (an infinite logit meets any threshold)
                     if (ni * 16 + i < 32) m_lo |= hit << (ni * 16 + i);
                     else                  m_hi |= hit << (ni * 16 + i - 32);
                 }
@@ -343,7 +343,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)   // hardwar
 template <bool WRITE_BITS = false, bool WRITE_LIST = false, bool ROWMAP = false>
 struct EpiSum {
     static constexpr bool kRowMap = ROWMAP;
-    static constexpr bool kSwapped = false;
+    static constexpr bool kSwapped = true;    // a lane owns a token row: see EpiMax; the row's sums are in-lane
     RowStats st;
     int n_rows;
     uint32_t *bits;          // membership bitmask [n_rows, bits_ld] of the side, or null
@@ -359,30 +359,28 @@ struct EpiSum {
         float *ls = (float *)(lds + kPipeLdsBytes), *lf = ls + 2 * BM;
         int *lc = (int *)(ls + 4 * BM);
         const int tile_row0 = r0 - (r0 % BM);
+        const int half = lane / 32;
+        static_assert(NI * 16 == 64, "the safe mask of a lane and row is two 32-bit words");
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
+            const int row = r0 + mi * 32 + (lane % 32);
+            const bool row_ok = row < g.M;
+            const float m = row_ok ? st.m[row] : 0.0f;
+            const float tau = row_ok ? st.tau[row] : INFINITY;
+            float s = 0.0f, f = 0.0f;
+            int c = 0;
+            // bit ni * 16 + i of the lane's mask: column c0 + ni * 32 + (i / 4) * 8 + half * 4 + i % 4 is safe
+            uint32_t safe_lo = 0u, safe_hi = 0u;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int row = r0 + mi * 32 + (i / 4) * 8 + (lane / 32) * 4 + (i % 4);
-                const bool row_ok = row < g.M;
-                const float m = row_ok ? st.m[row] : 0.0f;
-                const float tau = row_ok ? st.tau[row] : INFINITY;
-                float s = 0.0f, f = 0.0f;
-                int c = 0;
-                [[maybe_unused]] int list_open = -1, list_row = 0;   // WRITE_LIST
+            for (int ni = 0; ni < NI; ++ni) {
 #pragma unroll
-                for (int ni = 0; ni < NI; ++ni) {
-                    const int col = c0 + ni * 32 + (lane % 32);
+                for (int i = 0; i < 16; ++i) {
+                    const int col = c0 + ni * 32 + (i / 4) * 8 + half * 4 + (i % 4);
                     const float z = acc[mi][ni][i];
-                    float kept = 0.0f;
-                    if constexpr (WRITE_BITS) {   // lanes 0..31 hold 32 consecutive columns of one row, lanes 32..63 of the row 4 below
-                        const unsigned long long b = __builtin_amdgcn_ballot_w64(col < g.N && row_ok && z >= tau);
-                        const int64_t w = (c0 + ni * 32) >> 5;
-                        if ((lane % 32) == 0 && row_ok && w < bits_ld) bits[(int64_t)row * bits_ld + w] = (uint32_t)(b >> (lane & 32));
-                    }
                     if (col < g.N && row_ok) {
                         const bool safe = z >= tau;
                         c += safe ? 1 : 0;
+                        float kept = 0.0f;
                         if (want_full) {
                             const float e = __expf(z - m);
                             f += e;
@@ -391,38 +389,77 @@ struct EpiSum {
                             kept = __expf(z - m);
                         }
                         s += kept;
-                        if constexpr (WRITE_LIST) {
-                            if (safe) {
-                                if (list_open < 0) {       // one look per lane and row: a full list stops the appends
-                                    list_row = row;
-                                    if constexpr (ROWMAP) list_row = rowmap[row];
-                                    list_open = __hip_atomic_load(cursor + list_row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) <= list_cap;
+                        if constexpr (WRITE_BITS || WRITE_LIST) {
+                            if (ni * 16 + i < 32) safe_lo |= (safe ? 1u : 0u) << (ni * 16 + i);
+                            else                  safe_hi |= (safe ? 1u : 0u) << (ni * 16 + i - 32);
+                        }
+                    }
+                }
+            }
+            if constexpr (WRITE_BITS) {
+                // a 32-column word of the row: the 16 bits of this lane (4 i / 4 groups of 4 at 8 (i / 4) + 4 half)
+                // and the 16 of the lane that holds the row's other columns
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni) {
+                    const uint32_t mine16 = ((ni * 16 < 32 ? safe_lo : safe_hi) >> ((ni * 16) & 31)) & 0xffffu;
+                    uint32_t word = 0u;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) word |= ((mine16 >> (4 * q)) & 0xfu) << (8 * q + 4 * half);
+                    word |= (uint32_t)__shfl_xor((int)word, 32, kWave);
+                    const int64_t w = (c0 + ni * 32) >> 5;
+                    if (half == 0 && row_ok && w < bits_ld) bits[(int64_t)row * bits_ld + w] = word;
+                }
+            }
+            if constexpr (WRITE_LIST) {
+                // Lanes with safe tokens (few rows reach this pass, and their safe sets are short) are served one
+                // after the other; the lane's mask, maximum and logits are read through v_readlane, so every
+                // accumulator register is named statically.  One look at the cursor per lane and row: a full list
+                // stops the appends.
+                bool mine = (safe_lo | safe_hi) != 0u;
+                int list_row = row;
+                if (__builtin_amdgcn_ballot_w64(mine) != 0ull) {
+                    if (mine) {
+                        if constexpr (ROWMAP) list_row = rowmap[row];
+                        if (__hip_atomic_load(cursor + list_row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) > list_cap) mine = false;
+                    }
+                    unsigned long long todo = __builtin_amdgcn_ballot_w64(mine);
+                    while (todo != 0ull) {                                    // wavefront-uniform
+                        const int src = __builtin_ctzll(todo);
+                        todo &= todo - 1ull;
+                        const uint32_t s_lo = (uint32_t)__builtin_amdgcn_readlane((int)safe_lo, src);
+                        const uint32_t s_hi = (uint32_t)__builtin_amdgcn_readlane((int)safe_hi, src);
+                        const int s_list_row = __builtin_amdgcn_readlane(list_row, src), s_half = src / 32;
+                        const float s_m = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(m), src));
+                        int base = 0;
+                        if (lane == 0) base = atomicAdd(cursor + s_list_row, __builtin_popcount(s_lo) + __builtin_popcount(s_hi));
+                        base = __builtin_amdgcn_readfirstlane(base);
+                        dvp_grad_entry *out = entries + (int64_t)s_list_row * list_cap;
+                        int pos = base;
+#pragma unroll
+                        for (int ni = 0; ni < NI; ++ni) {
+#pragma unroll
+                            for (int i = 0; i < 16; ++i) {
+                                const uint32_t word = ni * 16 + i < 32 ? s_lo : s_hi;
+                                if (!((word >> ((ni * 16 + i) & 31)) & 1u)) continue;   // uniform
+                                const float z = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(acc[mi][ni][i]), src));
+                                if (lane == 0 && pos < list_cap) {
+                                    out[pos].index = (uint32_t)(c0 + ni * 32 + (i / 4) * 8 + s_half * 4 + (i % 4));
+                                    out[pos].value = __expf(z - s_m);
                                 }
-                                const int lrow = list_row;
-                                int *cur = cursor + lrow;
-                                if (list_open) {
-                                    const int pos = atomicAdd(cur, 1);
-                                    if (pos < list_cap) {
-                                        dvp_grad_entry *e = entries + (int64_t)lrow * list_cap + pos;
-                                        e->index = (uint32_t)col; e->value = kept;
-                                    }
-                                }
+                                ++pos;
                             }
                         }
                     }
                 }
-#pragma unroll
-                for (int off = 16; off > 0; off >>= 1) {
-                    s += __shfl_xor(s, off, kWave);
-                    f += __shfl_xor(f, off, kWave);
-                    c += __shfl_xor(c, off, kWave);
-                }
-                if ((lane % 32) == 0) {
-                    const int lr = row - tile_row0;           // 0..BM-1
-                    ls[wn * BM + lr] = s;
-                    lf[wn * BM + lr] = f;
-                    lc[wn * BM + lr] = c;
-                }
+            }
+            s += __shfl_xor(s, 32, kWave);
+            f += __shfl_xor(f, 32, kWave);
+            c += __shfl_xor(c, 32, kWave);
+            if (half == 0) {
+                const int lr = row - tile_row0;           // 0..BM-1
+                ls[wn * BM + lr] = s;
+                lf[wn * BM + lr] = f;
+                lc[wn * BM + lr] = c;
             }
         }
     }

@@ -164,10 +164,11 @@ __device__ __forceinline__ void rows_to_lines(f32x4 (&x)[4], int lane)
 
 // ---------------------------------------------------------------------------
 // epilogues: called once per wavefront with its 64x128 accumulator block.
-// Element (mi, ni, i) of lane l is row r0 + mi*32 + (i/4)*8 + (l/32)*4 + i%4,
-// column c0 + ni*32 + l%32 of the launch's output (kSwapped epilogues: see EpiMax).  `lds` is the workgroup's
-// dynamic LDS: the operand tiles (dead by now) and, behind them, the scratch of
-// pass B's sums.
+// Every product is taken with the operands swapped (the B fragment is the matrix instruction's row operand): element
+// (mi, ni, i) of lane l is row r0 + mi*32 + l%32, column c0 + ni*32 + (i/4)*8 + (l/32)*4 + i%4 of the launch's
+// output, i.e. a lane owns one output row per mi and four consecutive columns per register quad (see EpiMax for
+// what that buys).  `lds` is the workgroup's dynamic LDS: the operand tiles and, behind them, the scratch of pass
+// B's sums.
 // ---------------------------------------------------------------------------
 // STORE_Z: the tile's logits are also stored as fp32, row-major in Z [rows of the launch, ldz]: the
 // statistics at the threshold are then taken from them by a streaming kernel instead of a second
@@ -175,10 +176,8 @@ __device__ __forceinline__ void rows_to_lines(f32x4 (&x)[4], int lane)
 template <bool STORE_Z>
 struct EpiMax {
     static constexpr bool kRowMap = false;
-    // The products of this epilogue are taken with the operands swapped (the B fragment is the matrix
-    // instruction's row operand): element (mi, ni, i) of lane l is then token row r0 + mi*32 + l%32 and
-    // vocabulary column c0 + ni*32 + (i/4)*8 + (l/32)*4 + i%4.  A lane owns one token row per mi and
-    // four consecutive columns per register quad: the row maximum is 63 in-lane maxima and one exchange
+    // A lane owns one token row per mi and four consecutive columns per register quad (in the matrix instruction's
+    // natural order it would own a column of 16 rows): the row maximum is 63 in-lane maxima and one exchange
     // with lane l ^ 32 (the column-per-lane layout needs five exchanges for each of 32 rows and 32 atomic
     // instructions of two lanes each) and the sampled token's id is loaded once per lane.  Measured on the
     // forward product of configs[4] (9.44 ms per block of 8192 rows with the column-per-lane epilogue): 0.57 ms
@@ -187,7 +186,6 @@ struct EpiMax {
     // layout (32 bytes on each of 32 rows per store) they cost 0.9 ms per block, two thirds of it spent issuing
     // them into the L2; with whole lines the block takes 8.15 ms instead of 8.45.  Whole lines can also leave as
     // nontemporal stores (0.3 ms per call less; as 32-byte pieces they had cost the call 11 ms).
-    static constexpr bool kSwapped = true;
     RowStats st;
     const int64_t *ids;
     float *Z;            // [rows padded to BM, ldz]; ldz covers whole column tiles, so every tile element has a place
@@ -240,11 +238,10 @@ struct EpiMax {
 // Candidates (token, z) are appended in arrival order; at most cand_cap are kept.
 struct EpiMaxCand {
     static constexpr bool kRowMap = false;
-    // Operands swapped as in EpiMax: a lane owns a token row, so the maximum over the wavefront's 128 columns, the
-    // threshold and the test of the row's 128 logits against it are all in-lane.  Candidates are rare where this
+    // A lane owns a token row, so the maximum over the wavefront's 128 columns, the threshold and the test of the
+    // row's 128 logits against it are all in-lane.  Candidates are rare where this
     // form is used (peaked rows): the lanes that have any are served one after the other, their hit mask and their
     // logits read through v_readlane, every register named statically.
-    static constexpr bool kSwapped = true;
     RowStats st;
     const int64_t *ids;
     const float *zy_low;     // [n] lower bound of the row maximum, -inf where there is none
@@ -343,7 +340,6 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)   // hardwar
 template <bool WRITE_BITS = false, bool WRITE_LIST = false, bool ROWMAP = false>
 struct EpiSum {
     static constexpr bool kRowMap = ROWMAP;
-    static constexpr bool kSwapped = true;    // a lane owns a token row: see EpiMax; the row's sums are in-lane
     RowStats st;
     int n_rows;
     uint32_t *bits;          // membership bitmask [n_rows, bits_ld] of the side, or null
@@ -480,7 +476,6 @@ struct EpiSum {
 
 struct EpiStore {
     static constexpr bool kRowMap = false;
-    static constexpr bool kSwapped = true;    // a lane owns an output row and four consecutive columns: see EpiMax
     float *C;                // [M, ldc] fp32
     int64_t ldc;
     int accumulate;          // 0: C = v, 1: C += v
@@ -787,9 +782,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs
             for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni)   // formats 0, 0: E4M3 x E4M3; zero scale operands: the unscaled instruction
-                    acc[mi][ni] = Epi::kSwapped
-                        ? __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb8[buf][ni], fa8[buf][mi], acc[mi][ni], 0, 0, 0, 0, 0, 0)
-                        : __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fa8[buf][mi], fb8[buf][ni], acc[mi][ni], 0, 0, 0, 0, 0, 0);
+                    acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb8[buf][ni], fa8[buf][mi], acc[mi][ni], 0, 0, 0, 0, 0, 0);
             // twelve 16-byte LDS reads of the next pair between these eight MFMAs
 #pragma unroll
             for (int i = 0; i < MI * NI / 2; ++i) {
@@ -807,9 +800,8 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_nt_kernel(const GemmArgs
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni)
-                acc[mi][ni] = Epi::kSwapped   // (both operands have the same lane layout: 32 rows x 8 k per half)
-                    ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][ni], fa[buf][mi], acc[mi][ni], 0, 0, 0)
-                    : __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][mi], fb[buf][ni], acc[mi][ni], 0, 0, 0);
+                // B first: the lane then owns an output row (both operands have the same lane layout, 32 rows x 8 k per half)
+                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][ni], fa[buf][mi], acc[mi][ni], 0, 0, 0);
         // scheduling hint: spread the LDS reads of the next slice between this slice's MFMAs
         constexpr int NM = MI * NI, NR = (ATR ? 2 : 1) * MI + (BTR ? 2 : 1) * NI;
         if constexpr (NR == NM) {      // two reads behind each of the first half of the instructions: every fragment is
